@@ -1,0 +1,201 @@
+/*
+ * msrl.h -- C ABI of the fused actor+environment rollout fragment and the
+ * GAE advantage/return pass, for one AMD MI355X (gfx950).
+ *
+ * What the calls compute follows the MAPPO listing of the paper (Listing 1,
+ * section 3): Actor.act is "policy network -> action -> env_step -> reward,
+ * new_state", Trainer.train runs it `duration` times and stores every step
+ * (replay_buffer_insert), Learner.learn evaluates the critic on state and
+ * next_state and calls gae().  Section 6 (distribution policy DP-D, "GPU
+ * only") places that whole loop in one device fragment and section 5.2 fuses
+ * the replicas of a fragment by batching their tensors; here the batch axis is
+ * M = num_envs * num_agents rows.
+ *
+ * Conventions
+ *   - Every function returns MSRL_OK (0) or a negative msrl_status and never
+ *     throws or aborts.  msrl_last_error() returns a thread-local message for
+ *     the last failing call of the calling thread.
+ *   - "DEVICE" pointers are HIP device memory of the device that was current
+ *     when msrl_rollout_init ran; "HOST" pointers are ordinary host memory.
+ *   - The caller owns every tensor it passes in; the library owns msrl_state.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the null stream) and the call returns without waiting; the caller
+ *     synchronises.  msrl_state_get/set synchronise the device themselves.
+ *   - Row index m = env * num_agents + agent.  All trajectory tensors are
+ *     time-major and row-major: element (t, m, j) of a [T, M, J] tensor is at
+ *     offset (t*M + m)*J + j.
+ *   - Two calls that use the same msrl_state must not overlap in time.
+ *
+ * Random numbers: Philox4x32-10 (Salmon et al., SC'11), key = the 64-bit seed
+ * (low word, high word), counter = (env, entity, time, stream<<16 | block):
+ *   stream 0  action noise   entity = agent,          time = env step counter g
+ *   stream 1  reset draws    entity = agent | N+landmark (particle), 0 (lingauss),
+ *                            time = episode index
+ *   stream 2  env noise      entity = 0,               time = env step counter g
+ * A 32-bit word w gives u = (w >> 8) * 2^-24 in [0,1); normals come in pairs by
+ * Box-Muller from (w0, w1): radius sqrt(-2 ln(((w0>>8)+1) * 2^-24)), angle
+ * 2*pi*(w1>>8)*2^-24, first normal = r cos, second = r sin; words (0,1) and
+ * (2,3) of block b give normals 4b..4b+3.
+ */
+#ifndef MSRL_H
+#define MSRL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct msrl_state msrl_state; /* opaque, library-owned */
+
+typedef enum {
+  MSRL_OK = 0,
+  MSRL_EINVAL = -1,       /* bad argument or inconsistent configuration */
+  MSRL_ENOMEM = -2,       /* device or host allocation failed */
+  MSRL_EDEVICE = -3,      /* a HIP runtime call failed */
+  MSRL_EUNSUPPORTED = -4  /* valid configuration with no compiled kernel */
+} msrl_status;
+
+typedef enum { MSRL_ENV_PARTICLE = 0, MSRL_ENV_LINGAUSS = 1 } msrl_env_kind;
+typedef enum { MSRL_F32 = 0, MSRL_BF16 = 1 } msrl_dtype;
+typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
+
+/*
+ * Environment (the `env` entry of the algorithm configuration, section 3).
+ *
+ * MSRL_ENV_PARTICLE: num_agents point masses and num_landmarks landmarks in the
+ *   plane.  Per step, per agent: v <- v*(1-damping) + F(action)*dt, then
+ *   p <- p + v*dt with the new v; F = force * {(0,0),(+1,0),(-1,0),(0,+1),(0,-1)}
+ *   for actions 0..4.  Reward, shared by the env's agents and evaluated after
+ *   the move: -(sum over landmarks of the distance to the nearest agent)
+ *   -(number of unordered agent pairs closer than 2*radius).  Observation of
+ *   agent i, obs_dim = 4 + 2*num_landmarks + 4*(num_agents-1) floats:
+ *   [v, p, landmark_k - p (k ascending), p_j - p (j != i ascending), zeros].
+ *   Reset draws every agent and landmark position uniform in [-1,1)^2, v = 0.
+ *   act_dim is ignored.  The compiled kernels need num_landmarks == num_agents.
+ * MSRL_ENV_LINGAUSS: num_agents = 1, num_landmarks = 0, state = observation of
+ *   obs_dim floats; s' = A s + B a + noise_std * N(0,I); reward
+ *   -(s.s + act_cost * a.a) on the state before the step.  Reset: s ~ N(0,I).
+ *
+ * An episode ends (done = 1, then reset) on every step whose counter g
+ * satisfies (g+1) % episode_len == 0; g counts the env's steps since init.
+ */
+typedef struct {
+  int32_t kind;           /* msrl_env_kind */
+  int32_t num_envs;       /* E >= 1 */
+  int32_t num_agents;     /* N >= 1 */
+  int32_t num_landmarks;  /* L */
+  int32_t obs_dim;        /* D */
+  int32_t act_dim;        /* lingauss: action width; particle: ignored */
+  int32_t episode_len;    /* >= 1 */
+  float dt, damping, force, radius;  /* particle */
+  const float* A;         /* lingauss: HOST [D, D] row-major, copied at init */
+  const float* B;         /* lingauss: HOST [D, act_dim] row-major, copied at init */
+  float noise_std;        /* lingauss */
+  float act_cost;         /* lingauss */
+} msrl_env_cfg;
+
+/*
+ * Policy network in_dim - hidden - hidden - out_dim with tanh, and a value
+ * network in_dim - hidden - hidden - 1 of the same dtype, both shared by all
+ * agents.  out_dim = 5 for MSRL_CATEGORICAL (particle env) and 2*act_dim for
+ * MSRL_DIAG_GAUSSIAN (means, then log standard deviations).
+ * MSRL_BF16: parameters are bfloat16; the layer inputs (observation, h1, h2)
+ * are rounded to bfloat16 (nearest even), products are accumulated in fp32,
+ * bias add and tanh are fp32; logits and values are fp32.
+ *
+ * Parameter buffer: policy then value, each
+ *   W1[in_dim, hidden] b1[hidden] W2[hidden, hidden] b2[hidden] W3[hidden, out] b3[out]
+ * with W row-major [in, out], so that y = x W + b.
+ */
+typedef struct {
+  int32_t in_dim, hidden, out_dim;
+  int32_t dtype;  /* msrl_dtype */
+  int32_t dist;   /* msrl_dist */
+} msrl_policy_cfg;
+
+/*
+ * Trajectory of one call (the replay buffer contents of Listing 1).  All
+ * DEVICE pointers, caller-owned, non-overlapping.
+ */
+typedef struct {
+  float* obs;        /* [T+1, M, D]; obs[T] is the observation after the last step */
+  void* actions;     /* categorical: int32 [T, M]; Gaussian: float [T, M, act_dim] */
+  float* logp;       /* [T, M] log-probability (density) of the action taken */
+  float* rewards;    /* [T, M] */
+  uint8_t* dones;    /* [T, M] 0/1 */
+  float* values;     /* [T+1, M]; values[T] = V(obs[T]) */
+  float* logits;     /* optional (NULL allowed): [T, M, out_dim] policy-net outputs */
+  float* adv;        /* [T, M]; written by msrl_rollout_gae only */
+  float* ret;        /* [T, M]; written by msrl_rollout_gae only */
+} msrl_traj;
+
+/* Number of elements (not bytes) of the parameter buffer; 0 if cfg is invalid. */
+size_t msrl_param_count(const msrl_policy_cfg* cfg);
+
+/* Number of floats of env state per env in msrl_state_get/set:
+ * particle 4*N + 2*L laid out [agent0 (px,py,vx,vy), agent1 ..., landmark0 (x,y), ...];
+ * lingauss D.  0 if cfg is invalid. */
+size_t msrl_env_state_size(const msrl_env_cfg* cfg);
+
+/*
+ * Creates the env batch on the current device: allocates the library-owned
+ * state, copies A and B, sets every step counter to 0 and draws the initial
+ * state of episode 0 (the reset of Trainer.train, Listing 1).  EINVAL for null
+ * pointers, non-positive sizes, obs_dim != in_dim, an obs_dim or out_dim that
+ * does not match the env kind; EUNSUPPORTED if no kernel was compiled for the
+ * (env kind, sizes, hidden, dtype) combination.
+ */
+int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy,
+                      uint64_t seed, msrl_state** out);
+
+/*
+ * T steps of Actor.act for every env (Listing 1; the `duration` loop of
+ * Trainer.train), starting from the state the previous call left: observation,
+ * both networks, action sampling, env step, reward, done, reset; fills
+ * out->obs, actions, logp, rewards, dones, values (and logits if non-NULL) and
+ * advances the state.  params: DEVICE buffer of msrl_param_count elements of
+ * the policy dtype.  out->adv and out->ret are not touched.
+ */
+int msrl_rollout_step(msrl_state* st, const void* params, int32_t T,
+                      msrl_traj* out, void* hip_stream);
+
+/*
+ * Generalised advantage estimation over a stored trajectory (the gae() and
+ * discounted_reward() calls of Learner.learn, Listing 1).  For every column m,
+ * with A_T = 0:
+ *   delta_t = r_t + gamma*(1-d_t)*V_{t+1} - V_t
+ *   A_t     = delta_t + gamma*lambda*(1-d_t)*A_{t+1}
+ *   ret_t   = A_t + V_t
+ * rewards, dones, adv, ret: DEVICE [T, M]; values: DEVICE [T+1, M].
+ * T == 0 or M == 0 is a no-op that returns MSRL_OK.
+ */
+int msrl_gae(const float* rewards, const float* values, const uint8_t* dones,
+             int32_t T, int64_t M, float gamma, float lambda,
+             float* adv, float* ret, void* hip_stream);
+
+/* msrl_rollout_step followed by msrl_gae on its outputs, enqueued on the same
+ * stream: the fused rollout+GAE path.  Needs out->adv and out->ret. */
+int msrl_rollout_gae(msrl_state* st, const void* params, int32_t T,
+                     float gamma, float lambda, msrl_traj* out, void* hip_stream);
+
+/*
+ * Snapshot / restore of the env batch.  env_state: HOST
+ * [num_envs, msrl_env_state_size] floats; step_counters: HOST [num_envs] int64
+ * (only the low 32 bits enter the Philox counter).  Either pointer may be NULL
+ * to skip that part.  Both calls wait for the device.
+ */
+int msrl_state_get(msrl_state* st, float* env_state, int64_t* step_counters);
+int msrl_state_set(msrl_state* st, const float* env_state, const int64_t* step_counters);
+
+/* Frees the state (NULL allowed). */
+void msrl_rollout_destroy(msrl_state* st);
+
+/* Message of the last error on this thread ("" if none). */
+const char* msrl_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MSRL_H */

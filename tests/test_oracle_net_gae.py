@@ -1,0 +1,265 @@
+"""Pins of the oracle's networks, samplers, GAE and rollout loop."""
+import numpy as np
+import pytest
+import torch
+from scipy import stats
+
+from oracle import ref
+from paper_2210_00882_amd import synth
+
+
+# ------------------------------------------------------------------ networks
+def split(params, i, h, o):
+    sizes = [i * h, h, h * h, h, h * o, o]
+    parts = np.split(params, np.cumsum(sizes)[:-1])
+    return parts[0].reshape(i, h), parts[1], parts[2].reshape(h, h), parts[3], parts[4].reshape(h, o), parts[5]
+
+
+def test_mlp_against_numpy_matmul():
+    rng = np.random.default_rng(0)
+    for (i, h, o) in [(18, 64, 5), (7, 12, 3), (17, 32, 12), (4, 8, 1)]:
+        p = rng.standard_normal(ref.net_param_count(i, h, o)) * 0.3
+        x = rng.standard_normal(i)
+        W1, b1, W2, b2, W3, b3 = split(p, i, h, o)
+        want = np.tanh(np.tanh(x @ W1 + b1) @ W2 + b2) @ W3 + b3
+        np.testing.assert_allclose(ref.mlp(i, h, o, p, x), want, rtol=1e-12, atol=1e-13)
+
+
+def test_mlp_zero_weights_give_bias_and_saturation():
+    i, h, o = 6, 8, 5
+    p = np.zeros(ref.net_param_count(i, h, o))
+    p[-o:] = [1, 2, 3, 4, 5]
+    np.testing.assert_array_equal(ref.mlp(i, h, o, p, np.ones(i)), [1, 2, 3, 4, 5])
+    # huge first-layer bias saturates tanh at +1; W2 = identity*10 keeps it there; W3 sums
+    p = np.zeros(ref.net_param_count(i, h, o))
+    W1, b1, W2, b2, W3, b3 = split(p, i, h, o)
+    b1[:] = 50.0
+    W2[:] = np.eye(h) * 10
+    W3[:] = 1.0
+    p = np.concatenate([W1.ravel(), b1, W2.ravel(), b2, W3.ravel(), b3])
+    np.testing.assert_allclose(ref.mlp(i, h, o, p, np.zeros(i)), [h * np.tanh(10.0)] * o, rtol=1e-13)
+
+
+def test_tiny_net_by_hand():
+    # 1-1-1 net: y = w3*tanh(w2*tanh(w1*x+b1)+b2)+b3
+    p = np.array([0.5, 0.1, -2.0, 0.3, 4.0, -1.0])
+    y = ref.mlp(1, 1, 1, p, [0.7])[0]
+    assert y == pytest.approx(4.0 * np.tanh(-2.0 * np.tanh(0.5 * 0.7 + 0.1) + 0.3) - 1.0, rel=1e-14)
+
+
+def test_policy_value_split():
+    pol = ref.Policy(18, 64, 5)
+    rng = np.random.default_rng(2)
+    p = rng.standard_normal(pol.param_count) * 0.2
+    x = rng.standard_normal(18)
+    lg, v = ref.policy_value(pol, p, x)
+    n = ref.net_param_count(18, 64, 5)
+    np.testing.assert_array_equal(lg, ref.mlp(18, 64, 5, p[:n], x))
+    assert v == ref.mlp(18, 64, 1, p[n:], x)[0]
+    assert pol.param_count == synth.CONFIGS[1].param_count == 10_880 + 64 * 4 + 5 + 1
+
+
+def test_bf16_round_against_torch():
+    rng = np.random.default_rng(4)
+    x = np.concatenate([rng.standard_normal(5000), rng.standard_normal(500) * 1e-3, [0.0, 1.0, -1.0, 1.00390625,
+                        1.005859375, 1.001953125, 3.0e38, 1e-40]]).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    got = np.array([ref.bf16_round(float(v)) for v in x], dtype=np.float32)
+    np.testing.assert_array_equal(got, want)
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert ref.bf16_round(1.00390625) == 1.0
+    assert ref.bf16_round(1.01171875) == 1.015625
+
+
+def test_mlp_bf16_rounding_points():
+    rng = np.random.default_rng(5)
+    i, h, o = 12, 16, 5
+    bf = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    p = rng.standard_normal(ref.net_param_count(i, h, o)) * 0.3
+    x = rng.standard_normal(i)
+    W1, b1, W2, b2, W3, b3 = split(p, i, h, o)
+    h1 = np.tanh(bf(x) @ bf(W1) + b1)
+    h2 = np.tanh(bf(h1) @ bf(W2) + b2)
+    want = bf(h2) @ bf(W3) + b3
+    np.testing.assert_allclose(ref.mlp(i, h, o, p, x, bf16=True), want, rtol=1e-12, atol=1e-13)
+    # and it stays within bf16 distance of the unrounded network
+    np.testing.assert_allclose(ref.mlp(i, h, o, p, x, bf16=True), ref.mlp(i, h, o, p, x), atol=2e-2 * 3)
+
+
+# ------------------------------------------------------------------ samplers
+def test_categorical_edges_and_logp():
+    lg = np.array([0.3, -1.2, 2.0, 0.0, -0.5])
+    p = np.exp(lg) / np.exp(lg).sum()
+    a, lp, _ = ref.categorical(lg, 0.0)
+    assert a == 0 and lp == pytest.approx(np.log(p[0]), rel=1e-12)
+    a, lp, _ = ref.categorical(lg, 1 - 2.0 ** -24)
+    assert a == 4 and lp == pytest.approx(np.log(p[4]), rel=1e-12)
+    c = np.cumsum(p)
+    for k in range(5):
+        lo = c[k - 1] if k else 0.0
+        a, lp, mg = ref.categorical(lg, 0.5 * (lo + c[k]))
+        assert a == k and lp == pytest.approx(np.log(p[k]), rel=1e-12)
+        assert mg == pytest.approx(0.5 * (c[k] - lo), abs=1e-6) or mg < 0.5 * (c[k] - lo)
+    total = sum(np.exp(ref.categorical(lg, (lo + 1e-3))[1]) for lo in np.concatenate([[0], c[:-1]]))
+    assert total == pytest.approx(1.0, rel=1e-12)
+    # a zero-probability tail bin is never chosen even for the largest u
+    a, _, _ = ref.categorical([0.0, 0.0, -200.0], 1 - 2.0 ** -24)
+    assert a == 1
+    # shift invariance and large logits
+    a1, lp1, _ = ref.categorical(lg + 1000.0, 0.37)
+    a0, lp0, _ = ref.categorical(lg, 0.37)
+    assert a1 == a0 and lp1 == pytest.approx(lp0, abs=1e-9)
+
+
+def test_categorical_frequencies_million_draws():
+    pol = ref.Policy(18, 64, 5)
+    lg = np.array([0.2, -0.7, 1.1, 0.0, -1.5])
+    p = np.exp(lg) / np.exp(lg).sum()
+    n = 1_000_000
+    counts = ref.categorical_counts(pol, 31337, 12, lg, n)
+    assert counts.sum() == n
+    assert (np.abs(counts / n - p) < 4 * np.sqrt(p * (1 - p) / n)).all()
+    # the draw of (env, agent, g) is word 0 of stream 0, block 0
+    a, lp, _ = ref.sample(pol, 31337, 5, 2, 12, lg)
+    a2, lp2, _ = ref.categorical(lg, ref.uniform(ref.draw(31337, 5, 2, 12, 0, 0)[0]))
+    assert (a, lp) == (a2, lp2)
+
+
+def test_gaussian_density_and_sample():
+    mean = np.array([0.1, -0.2, 0.3, 0.0, 1.0, -1.0])
+    logstd = np.array([-0.5, 0.0, 0.2, -1.0, 0.3, -0.1])
+    eps = np.array([0.5, -1.0, 0.0, 2.0, -0.3, 0.7])
+    a, lp = ref.gaussian(mean, logstd, eps)
+    np.testing.assert_allclose(a, mean + np.exp(logstd) * eps, rtol=1e-15)
+    assert lp == pytest.approx(stats.norm.logpdf(a, loc=mean, scale=np.exp(logstd)).sum(), rel=1e-12)
+    pol = ref.Policy(17, 256, 12, dist=ref.DIAG_GAUSSIAN)
+    a2, lp2, _ = ref.sample(pol, 8, 3, 0, 9, np.concatenate([mean, logstd]))
+    e = ref.normals(8, 3, 0, 9, 0, 6)
+    np.testing.assert_allclose(a2, mean + np.exp(logstd) * e, rtol=1e-15)
+    assert lp2 == pytest.approx(stats.norm.logpdf(a2, loc=mean, scale=np.exp(logstd)).sum(), rel=1e-12)
+
+
+# ------------------------------------------------------------------ GAE
+def gae_bruteforce(r, V, d, gamma, lam):
+    """A_t = sum_{l=0}^{e(t)-t} (gamma*lambda)^l delta_{t+l}, e(t) = first done at or after t (else T-1)."""
+    T = len(r)
+    delta = [r[t] + gamma * (1 - d[t]) * V[t + 1] - V[t] for t in range(T)]
+    adv = []
+    for t in range(T):
+        e = next((k for k in range(t, T) if d[k]), T - 1)
+        adv.append(sum((gamma * lam) ** l * delta[t + l] for l in range(e - t + 1)))
+    return np.array(adv)
+
+
+def test_gae_worked_example():
+    r = np.ones((3, 1))
+    V = np.full((4, 1), 0.5)
+    adv, ret = ref.gae(r, V, np.zeros((3, 1), np.uint8), 0.99, 0.95)
+    np.testing.assert_allclose(adv[:, 0], [2.81091504875, 1.9307975, 0.995], rtol=1e-12)
+    np.testing.assert_allclose(ret, adv + 0.5, rtol=1e-15)
+    d = np.array([[0], [1], [0]], np.uint8)
+    adv, _ = ref.gae(r, V, d, 0.99, 0.95)
+    np.testing.assert_allclose(adv[:, 0], [1.46525, 0.5, 0.995], rtol=1e-12)
+
+
+def test_gae_bruteforce_small():
+    rng = np.random.default_rng(6)
+    for T in range(1, 9):
+        for _ in range(10):
+            M = 3
+            r = rng.standard_normal((T, M))
+            V = rng.standard_normal((T + 1, M))
+            d = (rng.random((T, M)) < 0.3).astype(np.uint8)
+            adv, ret = ref.gae(r, V, d, 0.99, 0.95)
+            for m in range(M):
+                np.testing.assert_allclose(adv[:, m], gae_bruteforce(r[:, m], V[:, m], d[:, m], 0.99, 0.95),
+                                           rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(ret - adv, V[:T], rtol=1e-12, atol=1e-13)
+
+
+def test_gae_special_cases():
+    rng = np.random.default_rng(7)
+    T, M = 12, 4
+    r, V = rng.standard_normal((T, M)), rng.standard_normal((T + 1, M))
+    d0 = np.zeros((T, M), np.uint8)
+    # lambda = 0: one-step TD error
+    adv, _ = ref.gae(r, V, d0, 0.9, 0.0)
+    np.testing.assert_allclose(adv, r + 0.9 * V[1:] - V[:-1], rtol=1e-13, atol=1e-14)
+    # gamma = lambda = 1, no dones: Monte-Carlo return plus bootstrap minus V_t
+    adv, ret = ref.gae(r, V, d0, 1.0, 1.0)
+    np.testing.assert_allclose(adv, np.cumsum(r[::-1], 0)[::-1] + V[T] - V[:T], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(ret, np.cumsum(r[::-1], 0)[::-1] + V[T], rtol=1e-12, atol=1e-13)
+    # a done on the last step removes the bootstrap value
+    d = d0.copy()
+    d[T - 1] = 1
+    adv, _ = ref.gae(r, V, d, 1.0, 1.0)
+    np.testing.assert_allclose(adv, np.cumsum(r[::-1], 0)[::-1] - V[:T], rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ rollout loop
+def oracle_setup(cfg, bias_std=0.1):
+    if cfg.kind == synth.PARTICLE:
+        env = ref.Env(ref.PARTICLE, cfg.num_agents, cfg.num_landmarks, cfg.obs_dim, 1, cfg.episode_len)
+    else:
+        A, B = synth.make_dynamics(cfg)
+        env = ref.Env(ref.LINGAUSS, 1, 0, cfg.obs_dim, cfg.act_dim, cfg.episode_len, A=A, B=B)
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist)
+    return env, pol, synth.make_params(cfg, bias_std=bias_std).astype(np.float64)
+
+
+@pytest.mark.parametrize("idx", [1, 4])
+def test_rollout_is_the_composition_of_its_steps(idx):
+    cfg = synth.CONFIGS[idx].with_(num_envs=3, T=7, episode_len=3 if idx == 1 else 4, hidden=16)
+    env, pol, params = oracle_setup(cfg)
+    seed, env0, T = 1234, 40, cfg.T
+    state, g = ref.init(env, seed, env0, cfg.num_envs)
+    s_chk = state.copy()
+    tr = ref.rollout(env, pol, seed, env0, state, g, params, T)
+    N = env.N
+    for e in range(cfg.num_envs):
+        s = s_chk[e].copy()
+        np.testing.assert_array_equal(s, ref.env_reset(env, seed, env0 + e, 0))
+        for t in range(T + 1):
+            o = ref.env_obs(env, s)
+            np.testing.assert_array_equal(tr["obs"][t, e * N:(e + 1) * N], o)
+            acts = []
+            for i in range(N):
+                lg, v = ref.policy_value(pol, params, o[i])
+                assert tr["values"][t, e * N + i] == v
+                if t == T:
+                    continue
+                a, lp, _ = ref.sample(pol, seed, env0 + e, i, t, lg)
+                np.testing.assert_array_equal(tr["logits"][t, e * N + i], lg)
+                np.testing.assert_array_equal(tr["actions"][t, e * N + i], a)
+                assert tr["logp"][t, e * N + i] == lp
+                acts.append(a)
+            if t == T:
+                continue
+            s, r, d, _ = ref.env_step(env, seed, env0 + e, t, s, acts if idx == 1 else acts[0])
+            assert (tr["rewards"][t, e * N:(e + 1) * N] == r).all()
+            assert (tr["dones"][t, e * N:(e + 1) * N] == d).all()
+            assert d == int((t + 1) % cfg.episode_len == 0)
+        np.testing.assert_array_equal(state[e], s)
+    assert (g == T).all()
+    if idx == 1:
+        assert (tr["rewards"] <= 0).all()
+        assert (tr["obs"][:, :, 14:] == 0).all()
+
+
+def test_rollout_continues_across_calls_and_env_subsets():
+    cfg = synth.CONFIGS[1].with_(num_envs=4, hidden=16, episode_len=5)
+    env, pol, params = oracle_setup(cfg)
+    seed = 9
+    st, g = ref.init(env, seed, 0, 4)
+    whole = ref.rollout(env, pol, seed, 0, st, g, params, 12)
+    st2, g2 = ref.init(env, seed, 0, 4)
+    a = ref.rollout(env, pol, seed, 0, st2, g2, params, 5)
+    b = ref.rollout(env, pol, seed, 0, st2, g2, params, 7)
+    for k in ("actions", "rewards", "dones", "logp"):
+        np.testing.assert_array_equal(whole[k], np.concatenate([a[k], b[k]]))
+    np.testing.assert_array_equal(whole["obs"][5:], b["obs"])
+    # envs 2..3 alone reproduce their slice (streams are keyed by global env id)
+    st3, g3 = ref.init(env, seed, 2, 2)
+    sub = ref.rollout(env, pol, seed, 2, st3, g3, params, 12)
+    np.testing.assert_array_equal(sub["obs"], whole["obs"][:, 6:12])
+    np.testing.assert_array_equal(sub["actions"], whole["actions"][:, 6:12])
