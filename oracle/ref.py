@@ -79,7 +79,8 @@ class Env:
         self.A = None if A is None else _f64(A)
         self.B = None if B is None else _f64(B)
         self.c = EnvCfg(kind, num_agents, num_landmarks, obs_dim, act_dim, episode_len,
-                        dt, damping, force, radius, _p(self.A), _p(self.B), noise_std, act_cost)
+                        float(dt), float(damping), float(force), float(radius), _p(self.A), _p(self.B),
+                        float(noise_std), float(act_cost))
         self.kind, self.N, self.L, self.D, self.K = kind, num_agents, num_landmarks, obs_dim, act_dim
         self.episode_len = episode_len
         self.S = int(lib().ref_env_state_size(C.byref(self.c)))

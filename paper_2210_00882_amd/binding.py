@@ -1,0 +1,223 @@
+"""Thin ctypes binding of libmsrl.so: the functions of include/msrl.h under the
+same names.  Argument marshalling only -- every step of the path runs in the HIP
+kernels.  torch is used for device memory and streams; tensors are passed as raw
+device pointers.  There is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmsrl.so")
+
+MSRL_OK, MSRL_EINVAL, MSRL_ENOMEM, MSRL_EDEVICE, MSRL_EUNSUPPORTED = 0, -1, -2, -3, -4
+MSRL_ENV_PARTICLE, MSRL_ENV_LINGAUSS = 0, 1
+MSRL_F32, MSRL_BF16 = 0, 1
+MSRL_CATEGORICAL, MSRL_DIAG_GAUSSIAN = 0, 1
+
+EXPORTS = (
+    "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",
+    "msrl_rollout_gae", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
+)
+
+
+class msrl_env_cfg(C.Structure):
+    _fields_ = [
+        ("kind", C.c_int32), ("num_envs", C.c_int32), ("num_agents", C.c_int32),
+        ("num_landmarks", C.c_int32), ("obs_dim", C.c_int32), ("act_dim", C.c_int32),
+        ("episode_len", C.c_int32),
+        ("dt", C.c_float), ("damping", C.c_float), ("force", C.c_float), ("radius", C.c_float),
+        ("A", C.c_void_p), ("B", C.c_void_p),
+        ("noise_std", C.c_float), ("act_cost", C.c_float),
+    ]
+
+
+class msrl_policy_cfg(C.Structure):
+    _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("out_dim", C.c_int32),
+                ("dtype", C.c_int32), ("dist", C.c_int32)]
+
+
+class msrl_traj(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("obs", "actions", "logp", "rewards", "dones", "values", "logits", "adv", "ret")]
+
+
+class MsrlError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"msrl error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Loads libmsrl.so (built by `python -m paper_2210_00882_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2210_00882_amd.build`; "
+            "there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_uint64
+    lib.msrl_param_count.restype = C.c_size_t
+    lib.msrl_param_count.argtypes = [C.POINTER(msrl_policy_cfg)]
+    lib.msrl_env_state_size.restype = C.c_size_t
+    lib.msrl_env_state_size.argtypes = [C.POINTER(msrl_env_cfg)]
+    lib.msrl_rollout_init.restype = C.c_int
+    lib.msrl_rollout_init.argtypes = [C.POINTER(msrl_env_cfg), C.POINTER(msrl_policy_cfg), u64, C.POINTER(vp)]
+    lib.msrl_rollout_step.restype = C.c_int
+    lib.msrl_rollout_step.argtypes = [vp, vp, i32, C.POINTER(msrl_traj), vp]
+    lib.msrl_gae.restype = C.c_int
+    lib.msrl_gae.argtypes = [vp, vp, vp, i32, i64, f32, f32, vp, vp, vp]
+    lib.msrl_rollout_gae.restype = C.c_int
+    lib.msrl_rollout_gae.argtypes = [vp, vp, i32, f32, f32, C.POINTER(msrl_traj), vp]
+    lib.msrl_state_get.restype = C.c_int
+    lib.msrl_state_get.argtypes = [vp, vp, vp]
+    lib.msrl_state_set.restype = C.c_int
+    lib.msrl_state_set.argtypes = [vp, vp, vp]
+    lib.msrl_rollout_destroy.restype = None
+    lib.msrl_rollout_destroy.argtypes = [vp]
+    lib.msrl_last_error.restype = C.c_char_p
+    lib.msrl_last_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def msrl_last_error() -> str:
+    return load().msrl_last_error().decode()
+
+
+def _check(rc):
+    if rc != MSRL_OK:
+        raise MsrlError(rc, msrl_last_error())
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or None)."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA/HIP tensors"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def make_env_cfg(cfg, A=None, B=None):
+    """msrl_env_cfg from a synth.Config; A, B float32 host arrays for lingauss.
+    Returns (struct, keepalive)."""
+    keep = []
+    pa = pb = None
+    if A is not None:
+        A = np.ascontiguousarray(A, dtype=np.float32)
+        B = np.ascontiguousarray(B, dtype=np.float32)
+        keep = [A, B]
+        pa, pb = A.ctypes.data, B.ctypes.data
+    e = msrl_env_cfg(cfg.kind, cfg.num_envs, cfg.num_agents, cfg.num_landmarks, cfg.obs_dim, cfg.act_dim,
+                     cfg.episode_len, cfg.dt, cfg.damping, cfg.force, cfg.radius, pa, pb,
+                     cfg.noise_std, cfg.act_cost)
+    return e, keep
+
+
+def make_policy_cfg(cfg):
+    return msrl_policy_cfg(cfg.obs_dim, cfg.hidden, cfg.out_dim, cfg.dtype, cfg.dist)
+
+
+def msrl_param_count(policy_cfg: msrl_policy_cfg) -> int:
+    return int(load().msrl_param_count(C.byref(policy_cfg)))
+
+
+def msrl_env_state_size(env_cfg: msrl_env_cfg) -> int:
+    return int(load().msrl_env_state_size(C.byref(env_cfg)))
+
+
+def msrl_rollout_init(env_cfg: msrl_env_cfg, policy_cfg: msrl_policy_cfg, seed: int) -> C.c_void_p:
+    st = C.c_void_p()
+    _check(load().msrl_rollout_init(C.byref(env_cfg), C.byref(policy_cfg), C.c_uint64(seed), C.byref(st)))
+    return st
+
+
+def msrl_rollout_destroy(state) -> None:
+    load().msrl_rollout_destroy(state)
+
+
+def _traj(out: dict) -> msrl_traj:
+    t = msrl_traj()
+    for name, _ in msrl_traj._fields_:
+        v = out.get(name)
+        setattr(t, name, None if v is None else v.data_ptr())
+    return t
+
+
+def msrl_rollout_step(state, params, T: int, out: dict, stream=None) -> None:
+    """out: dict of preallocated device tensors (see alloc_traj)."""
+    tr = _traj(out)
+    _check(load().msrl_rollout_step(state, _ptr(params), C.c_int32(T), C.byref(tr), _stream(stream)))
+
+
+def msrl_gae(rewards, values, dones, gamma: float, lam: float, adv, ret, stream=None) -> None:
+    T = rewards.shape[0]
+    M = rewards.numel() // T if T else 0
+    _check(load().msrl_gae(_ptr(rewards), _ptr(values), _ptr(dones), C.c_int32(T), C.c_int64(M),
+                           C.c_float(gamma), C.c_float(lam), _ptr(adv), _ptr(ret), _stream(stream)))
+
+
+def msrl_rollout_gae(state, params, T: int, gamma: float, lam: float, out: dict, stream=None) -> None:
+    tr = _traj(out)
+    _check(load().msrl_rollout_gae(state, _ptr(params), C.c_int32(T), C.c_float(gamma), C.c_float(lam),
+                                   C.byref(tr), _stream(stream)))
+
+
+def msrl_state_get(state, num_envs: int, state_size: int):
+    es = np.zeros((num_envs, state_size), dtype=np.float32)
+    g = np.zeros(num_envs, dtype=np.int64)
+    _check(load().msrl_state_get(state, es.ctypes.data_as(C.c_void_p), g.ctypes.data_as(C.c_void_p)))
+    return es, g
+
+
+def msrl_state_set(state, env_state=None, step_counters=None) -> None:
+    es = None if env_state is None else np.ascontiguousarray(env_state, dtype=np.float32)
+    g = None if step_counters is None else np.ascontiguousarray(step_counters, dtype=np.int64)
+    _check(load().msrl_state_set(state,
+                                 None if es is None else es.ctypes.data_as(C.c_void_p),
+                                 None if g is None else g.ctypes.data_as(C.c_void_p)))
+
+
+# ------------------------------------------------------------------ device-memory helpers (plumbing)
+def alloc_traj(cfg, T: int, device="cuda:0", logits: bool = False, gae: bool = True) -> dict:
+    """Caller-owned trajectory tensors of the shapes msrl_traj documents."""
+    import torch
+    M, D = cfg.M, cfg.obs_dim
+    out = {
+        "obs": torch.empty((T + 1, M, D), dtype=torch.float32, device=device),
+        "logp": torch.empty((T, M), dtype=torch.float32, device=device),
+        "rewards": torch.empty((T, M), dtype=torch.float32, device=device),
+        "dones": torch.empty((T, M), dtype=torch.uint8, device=device),
+        "values": torch.empty((T + 1, M), dtype=torch.float32, device=device),
+        "logits": torch.empty((T, M, cfg.out_dim), dtype=torch.float32, device=device) if logits else None,
+        "adv": torch.empty((T, M), dtype=torch.float32, device=device) if gae else None,
+        "ret": torch.empty((T, M), dtype=torch.float32, device=device) if gae else None,
+    }
+    if cfg.dist == MSRL_CATEGORICAL:
+        out["actions"] = torch.empty((T, M), dtype=torch.int32, device=device)
+    else:
+        out["actions"] = torch.empty((T, M, cfg.act_dim), dtype=torch.float32, device=device)
+    return out
+
+
+def upload_params(cfg, params_f32: np.ndarray, device="cuda:0"):
+    """Parameter vector as a device tensor of the policy dtype."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(params_f32, dtype=np.float32))
+    if cfg.dtype == MSRL_BF16:
+        t = t.to(torch.bfloat16)
+    return t.to(device)

@@ -1,0 +1,402 @@
+// C ABI of the library (include/msrl.h): argument checks, state ownership,
+// kernel selection and launches.  All arithmetic of the path runs in the HIP
+// kernels; nothing here computes on the host.
+#include "../../include/msrl.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "dev_common.h"
+#include "packed.h"
+#include "registry.h"
+
+namespace msrl {
+hipError_t launch_pack(const PackJobs& jobs, hipStream_t stream);
+hipError_t launch_gae(const float* rewards, const float* values, const uint8_t* dones, int T,
+                      int64_t M, float gamma, float lambda, float* adv, float* ret,
+                      hipStream_t stream);
+}  // namespace msrl
+
+using namespace msrl;
+
+struct msrl_state {
+  msrl_env_cfg env;
+  msrl_policy_cfg pol;
+  uint64_t seed;
+  int device;
+  int state_size;        // floats per env
+  float* env_state;      // device [E, S]
+  int64_t* g;            // device [E]
+  uint8_t* packed;       // device, two packed networks
+  uint8_t* dyn;          // device, lingauss dynamics tiles
+  float* dyn_src;        // device copy of A then B (row-major), source of dyn
+  NetLayout layout;
+  KernelEntry kernel;
+};
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return fail(e_ == hipErrorOutOfMemory ? MSRL_ENOMEM : MSRL_EDEVICE, "%s failed: %s",  \
+                  #expr, hipGetErrorString(e_));                                            \
+  } while (0)
+
+std::vector<KernelEntry> all_kernels() {
+  return {entry_p1_h64_f32(),  entry_p2_h64_f32(),    entry_p3_h64_f32(), entry_p3_h64_bf16(),
+          entry_p6_h128_f32(), entry_p10_h256_bf16(), entry_l17_6_h256()};
+}
+
+bool valid_policy(const msrl_policy_cfg* p) {
+  return p && p->in_dim >= 1 && p->hidden >= 1 && p->out_dim >= 1 &&
+         (p->dtype == MSRL_F32 || p->dtype == MSRL_BF16) &&
+         (p->dist == MSRL_CATEGORICAL || p->dist == MSRL_DIAG_GAUSSIAN);
+}
+
+bool valid_env_shape(const msrl_env_cfg* e) {
+  if (!e || e->num_envs < 1 || e->num_agents < 1 || e->obs_dim < 1 || e->episode_len < 1) return false;
+  if (e->kind == MSRL_ENV_PARTICLE)
+    return e->num_landmarks >= 0 &&
+           e->obs_dim == 4 + 2 * e->num_landmarks + 4 * (e->num_agents - 1);
+  if (e->kind == MSRL_ENV_LINGAUSS)
+    return e->num_agents == 1 && e->num_landmarks == 0 && e->act_dim >= 1;
+  return false;
+}
+
+size_t net_params(int in, int h, int out) {
+  return (size_t)in * h + h + (size_t)h * h + h + (size_t)h * out + out;
+}
+
+// Initial state of episode 0: one thread per (env, entity).
+__global__ void init_state_kernel(int kind, int E, int N, int L, int D, uint32_t seed_lo,
+                                  uint32_t seed_hi, float* env_state, int64_t* g) {
+  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (kind == MSRL_ENV_PARTICLE) {
+    const int per = N + L, S = 4 * N + 2 * L;
+    if (tid >= (int64_t)E * per) return;
+    const int env = (int)(tid / per), ent = (int)(tid % per);
+    const Words4 w = draw(seed_lo, seed_hi, (uint32_t)env, (uint32_t)ent, 0, 1, 0);
+    const float x = 2.0f * u01(w.w[0]) - 1.0f, y = 2.0f * u01(w.w[1]) - 1.0f;
+    float* es = env_state + (size_t)env * S;
+    if (ent < N) {
+      es[4 * ent] = x;
+      es[4 * ent + 1] = y;
+      es[4 * ent + 2] = 0.0f;
+      es[4 * ent + 3] = 0.0f;
+    } else {
+      es[4 * N + 2 * (ent - N)] = x;
+      es[4 * N + 2 * (ent - N) + 1] = y;
+    }
+    if (ent == 0) g[env] = 0;
+  } else {
+    const int blocks = (D + 3) / 4;
+    if (tid >= (int64_t)E * blocks) return;
+    const int env = (int)(tid / blocks), b = (int)(tid % blocks);
+    float e[4];
+    normals4(seed_lo, seed_hi, (uint32_t)env, 0, 0, 1, (uint32_t)b, e);
+    for (int c = 0; c < 4; ++c)
+      if (4 * b + c < D) env_state[(size_t)env * D + 4 * b + c] = e[c];
+    if (b == 0) g[env] = 0;
+  }
+}
+
+PackJob weight_job(const void* src, void* dst, bool bf16, int n_in, int n_out, int nuc, int kt,
+                   int in_map, int out_map, int gauss_k) {
+  PackJob j;
+  memset(&j, 0, sizeof(j));
+  j.src = src; j.dst = dst; j.src_bf16 = bf16; j.is_bias = 0;
+  j.n_in = n_in; j.n_out = n_out; j.src_out_major = 0;
+  j.nuc = nuc; j.kt = kt; j.in_map = in_map; j.out_map = out_map; j.gauss_k = gauss_k;
+  return j;
+}
+
+PackJob bias_job(const void* src, void* dst, bool bf16, int n_out, int nuc, int out_map, int gauss_k) {
+  PackJob j;
+  memset(&j, 0, sizeof(j));
+  j.src = src; j.dst = dst; j.src_bf16 = bf16; j.is_bias = 1;
+  j.n_out = n_out; j.nuc = nuc; j.out_map = out_map; j.gauss_k = gauss_k;
+  return j;
+}
+
+// Enqueue the re-ordering of the caller's parameter buffer into st->packed.
+int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
+  const msrl_policy_cfg& p = st->pol;
+  const bool bf16 = p.dtype == MSRL_BF16;
+  const size_t esz = bf16 ? 2 : 4;
+  const int in_map1 = st->env.kind == MSRL_ENV_LINGAUSS ? IN_CHAIN : (bf16 ? IN_LINEAR16 : IN_PAIRS);
+  const NetLayout& L = st->layout;
+  PackJobs jobs;
+  jobs.n = 0;
+  const uint8_t* src = (const uint8_t*)params;
+  for (int net = 0; net < 2; ++net) {
+    const int out = net == 0 ? p.out_dim : 1;
+    const int out_map = (net == 0 && p.dist == MSRL_DIAG_GAUSSIAN) ? OUT_GAUSS : OUT_NATURAL;
+    const int gk = p.out_dim / 2;
+    uint8_t* dst = st->packed + (size_t)net * L.bytes;
+    const uint8_t* W1 = src;
+    const uint8_t* b1 = W1 + (size_t)p.in_dim * p.hidden * esz;
+    const uint8_t* W2 = b1 + (size_t)p.hidden * esz;
+    const uint8_t* b2 = W2 + (size_t)p.hidden * p.hidden * esz;
+    const uint8_t* W3 = b2 + (size_t)p.hidden * esz;
+    const uint8_t* b3 = W3 + (size_t)p.hidden * out * esz;
+    jobs.job[jobs.n++] = weight_job(W1, dst + L.w1, bf16, p.in_dim, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
+    jobs.job[jobs.n++] = weight_job(W2, dst + L.w2, bf16, p.hidden, p.hidden, L.nuc, L.kt2, IN_CHAIN, OUT_NATURAL, 0);
+    jobs.job[jobs.n++] = weight_job(W3, dst + L.w3, bf16, p.hidden, out, 1, L.kt2, IN_CHAIN, out_map, gk);
+    jobs.job[jobs.n++] = bias_job(b1, dst + L.b1, bf16, p.hidden, L.nuc, OUT_NATURAL, 0);
+    jobs.job[jobs.n++] = bias_job(b2, dst + L.b2, bf16, p.hidden, L.nuc, OUT_NATURAL, 0);
+    jobs.job[jobs.n++] = bias_job(b3, dst + L.b3, bf16, out, 1, out_map, gk);
+    src = b3 + (size_t)out * esz;
+  }
+  HIP_TRY(launch_pack(jobs, stream));
+  return MSRL_OK;
+}
+
+int check_traj(const msrl_state* st, const msrl_traj* out, bool need_gae) {
+  if (!out) return fail(MSRL_EINVAL, "trajectory struct is NULL");
+  if (!out->obs || !out->actions || !out->logp || !out->rewards || !out->dones || !out->values)
+    return fail(MSRL_EINVAL, "a required trajectory pointer is NULL");
+  if (need_gae && (!out->adv || !out->ret)) return fail(MSRL_EINVAL, "adv / ret pointer is NULL");
+  (void)st;
+  return MSRL_OK;
+}
+
+int enqueue_rollout(msrl_state* st, const void* params, int32_t T, msrl_traj* out, hipStream_t stream) {
+  int rc = pack_params(st, params, stream);
+  if (rc != MSRL_OK) return rc;
+  RolloutArgs a;
+  memset(&a, 0, sizeof(a));
+  a.env_state = st->env_state;
+  a.g = st->g;
+  a.packed = st->packed;
+  a.dyn = st->dyn;
+  a.E = st->env.num_envs;
+  a.T = T;
+  a.ep = st->env.episode_len;
+  a.dt = st->env.dt;
+  a.keep = 1.0f - st->env.damping;
+  a.fdt = st->env.force * st->env.dt;
+  a.coll2 = (2.0f * st->env.radius) * (2.0f * st->env.radius);
+  a.noise_std = st->env.noise_std;
+  a.act_cost = st->env.act_cost;
+  a.seed_lo = (uint32_t)st->seed;
+  a.seed_hi = (uint32_t)(st->seed >> 32);
+  a.obs = out->obs;
+  a.actions = out->actions;
+  a.logp = out->logp;
+  a.rewards = out->rewards;
+  a.dones = out->dones;
+  a.values = out->values;
+  a.logits = out->logits;
+  a.M = (int64_t)st->env.num_envs * st->env.num_agents;
+  const int64_t waves = ((int64_t)a.E + st->kernel.envs_per_wave - 1) / st->kernel.envs_per_wave;
+  const int64_t blocks = (waves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+  void* args[] = {&a};
+  HIP_TRY(hipLaunchKernel(st->kernel.fn, dim3((unsigned)blocks), dim3(64 * WAVES_PER_BLOCK), args, 0, stream));
+  return MSRL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* msrl_last_error(void) { return g_err; }
+
+size_t msrl_param_count(const msrl_policy_cfg* cfg) {
+  if (!valid_policy(cfg)) return 0;
+  return net_params(cfg->in_dim, cfg->hidden, cfg->out_dim) + net_params(cfg->in_dim, cfg->hidden, 1);
+}
+
+size_t msrl_env_state_size(const msrl_env_cfg* cfg) {
+  if (!valid_env_shape(cfg)) return 0;
+  return cfg->kind == MSRL_ENV_PARTICLE ? (size_t)4 * cfg->num_agents + 2 * cfg->num_landmarks
+                                        : (size_t)cfg->obs_dim;
+}
+
+int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, uint64_t seed,
+                      msrl_state** out) {
+  if (!env || !policy || !out) return fail(MSRL_EINVAL, "msrl_rollout_init: NULL argument");
+  *out = nullptr;
+  if (!valid_env_shape(env))
+    return fail(MSRL_EINVAL, "msrl_rollout_init: inconsistent environment configuration "
+                             "(kind %d, envs %d, agents %d, landmarks %d, obs_dim %d, episode_len %d)",
+                env->kind, env->num_envs, env->num_agents, env->num_landmarks, env->obs_dim, env->episode_len);
+  if (!valid_policy(policy)) return fail(MSRL_EINVAL, "msrl_rollout_init: invalid policy configuration");
+  if (policy->in_dim != env->obs_dim)
+    return fail(MSRL_EINVAL, "msrl_rollout_init: policy in_dim %d != obs_dim %d", policy->in_dim, env->obs_dim);
+  if (env->kind == MSRL_ENV_PARTICLE) {
+    if (policy->dist != MSRL_CATEGORICAL || policy->out_dim != 5)
+      return fail(MSRL_EINVAL, "msrl_rollout_init: the particle env needs a categorical policy with out_dim 5");
+  } else {
+    if (policy->dist != MSRL_DIAG_GAUSSIAN || policy->out_dim != 2 * env->act_dim)
+      return fail(MSRL_EINVAL, "msrl_rollout_init: the lingauss env needs a Gaussian policy with out_dim 2*act_dim");
+    if (!env->A || !env->B) return fail(MSRL_EINVAL, "msrl_rollout_init: lingauss needs A and B");
+  }
+  // kernel selection
+  KernelEntry found;
+  bool ok = false;
+  for (const KernelEntry& k : all_kernels()) {
+    const bool bf16 = policy->dtype == MSRL_BF16;
+    if (k.kind != env->kind || k.hidden != policy->hidden || (k.bf16 != 0) != bf16) continue;
+    if (env->kind == MSRL_ENV_PARTICLE) {
+      if (k.n != env->num_agents || env->num_landmarks != env->num_agents) continue;
+    } else {
+      if (k.n != env->obs_dim || k.k != env->act_dim) continue;
+    }
+    found = k;
+    ok = true;
+    break;
+  }
+  if (!ok)
+    return fail(MSRL_EUNSUPPORTED,
+                "msrl_rollout_init: no kernel compiled for kind %d, agents %d, landmarks %d, obs_dim %d, "
+                "act_dim %d, hidden %d, dtype %d",
+                env->kind, env->num_agents, env->num_landmarks, env->obs_dim, env->act_dim, policy->hidden,
+                policy->dtype);
+
+  msrl_state* st = new (std::nothrow) msrl_state;
+  if (!st) return fail(MSRL_ENOMEM, "msrl_rollout_init: host allocation failed");
+  memset(st, 0, sizeof(*st));
+  st->env = *env;
+  st->env.A = nullptr;
+  st->env.B = nullptr;
+  st->pol = *policy;
+  st->seed = seed;
+  st->kernel = found;
+  st->state_size = (int)msrl_env_state_size(env);
+  st->layout = net_layout(policy->in_dim, policy->hidden, policy->dtype == MSRL_BF16);
+
+  int rc = MSRL_OK;
+  auto cleanup = [&](int code) {
+    msrl_rollout_destroy(st);
+    return code;
+  };
+#define INIT_TRY(expr)                                                                         \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess) {                                                                    \
+      rc = fail(e_ == hipErrorOutOfMemory ? MSRL_ENOMEM : MSRL_EDEVICE, "%s failed: %s", #expr, \
+                hipGetErrorString(e_));                                                        \
+      return cleanup(rc);                                                                      \
+    }                                                                                          \
+  } while (0)
+
+  INIT_TRY(hipGetDevice(&st->device));
+  const size_t E = (size_t)env->num_envs;
+  INIT_TRY(hipMalloc((void**)&st->env_state, E * st->state_size * sizeof(float)));
+  INIT_TRY(hipMalloc((void**)&st->g, E * sizeof(int64_t)));
+  INIT_TRY(hipMalloc((void**)&st->packed, 2 * st->layout.bytes));
+  INIT_TRY(hipMemset(st->packed, 0, 2 * st->layout.bytes));
+  if (env->kind == MSRL_ENV_LINGAUSS) {
+    const int D = env->obs_dim, K = env->act_dim;
+    const int ktA = tiles_for_inputs(D, false), ktB = tiles_for_inputs(K, false);
+    INIT_TRY(hipMalloc((void**)&st->dyn_src, ((size_t)D * D + (size_t)D * K) * sizeof(float)));
+    INIT_TRY(hipMalloc((void**)&st->dyn, (size_t)(ktA + ktB) * 1024));
+    INIT_TRY(hipMemcpy(st->dyn_src, env->A, (size_t)D * D * sizeof(float), hipMemcpyHostToDevice));
+    INIT_TRY(hipMemcpy(st->dyn_src + (size_t)D * D, env->B, (size_t)D * K * sizeof(float), hipMemcpyHostToDevice));
+    PackJobs jobs;
+    jobs.n = 2;
+    jobs.job[0] = weight_job(st->dyn_src, st->dyn, false, D, D, 1, ktA, IN_CHAIN, OUT_NATURAL, 0);
+    jobs.job[0].src_out_major = 1;  // A[out, in]
+    jobs.job[1] = weight_job(st->dyn_src + (size_t)D * D, st->dyn + (size_t)ktA * 1024, false, K, D, 1, ktB,
+                             IN_CHAIN, OUT_NATURAL, 0);
+    jobs.job[1].src_out_major = 1;  // B[out, in]
+    INIT_TRY(launch_pack(jobs, nullptr));
+  }
+  {
+    const int64_t items = env->kind == MSRL_ENV_PARTICLE
+                              ? (int64_t)E * (env->num_agents + env->num_landmarks)
+                              : (int64_t)E * ((env->obs_dim + 3) / 4);
+    hipLaunchKernelGGL(init_state_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, nullptr,
+                       env->kind, env->num_envs, env->num_agents, env->num_landmarks, env->obs_dim,
+                       (uint32_t)seed, (uint32_t)(seed >> 32), st->env_state, st->g);
+    INIT_TRY(hipGetLastError());
+    INIT_TRY(hipDeviceSynchronize());
+  }
+#undef INIT_TRY
+  *out = st;
+  return MSRL_OK;
+}
+
+void msrl_rollout_destroy(msrl_state* st) {
+  if (!st) return;
+  if (st->env_state) (void)hipFree(st->env_state);
+  if (st->g) (void)hipFree(st->g);
+  if (st->packed) (void)hipFree(st->packed);
+  if (st->dyn) (void)hipFree(st->dyn);
+  if (st->dyn_src) (void)hipFree(st->dyn_src);
+  delete st;
+}
+
+int msrl_rollout_step(msrl_state* st, const void* params, int32_t T, msrl_traj* out, void* hip_stream) {
+  if (!st || !params) return fail(MSRL_EINVAL, "msrl_rollout_step: NULL argument");
+  if (T <= 0) return fail(MSRL_EINVAL, "msrl_rollout_step: T must be positive (got %d)", T);
+  int rc = check_traj(st, out, false);
+  if (rc != MSRL_OK) return rc;
+  return enqueue_rollout(st, params, T, out, (hipStream_t)hip_stream);
+}
+
+int msrl_gae(const float* rewards, const float* values, const uint8_t* dones, int32_t T, int64_t M,
+             float gamma, float lambda, float* adv, float* ret, void* hip_stream) {
+  if (T < 0 || M < 0) return fail(MSRL_EINVAL, "msrl_gae: negative size (T %d, M %lld)", T, (long long)M);
+  if (T == 0 || M == 0) return MSRL_OK;
+  if (!rewards || !values || !dones || !adv || !ret) return fail(MSRL_EINVAL, "msrl_gae: NULL argument");
+  HIP_TRY(launch_gae(rewards, values, dones, T, M, gamma, lambda, adv, ret, (hipStream_t)hip_stream));
+  return MSRL_OK;
+}
+
+int msrl_rollout_gae(msrl_state* st, const void* params, int32_t T, float gamma, float lambda,
+                     msrl_traj* out, void* hip_stream) {
+  if (!st || !params) return fail(MSRL_EINVAL, "msrl_rollout_gae: NULL argument");
+  if (T <= 0) return fail(MSRL_EINVAL, "msrl_rollout_gae: T must be positive (got %d)", T);
+  int rc = check_traj(st, out, true);
+  if (rc != MSRL_OK) return rc;
+  rc = enqueue_rollout(st, params, T, out, (hipStream_t)hip_stream);
+  if (rc != MSRL_OK) return rc;
+  const int64_t M = (int64_t)st->env.num_envs * st->env.num_agents;
+  HIP_TRY(launch_gae(out->rewards, out->values, out->dones, T, M, gamma, lambda, out->adv, out->ret,
+                     (hipStream_t)hip_stream));
+  return MSRL_OK;
+}
+
+int msrl_state_get(msrl_state* st, float* env_state, int64_t* step_counters) {
+  if (!st) return fail(MSRL_EINVAL, "msrl_state_get: NULL state");
+  HIP_TRY(hipDeviceSynchronize());
+  const size_t E = (size_t)st->env.num_envs;
+  if (env_state)
+    HIP_TRY(hipMemcpy(env_state, st->env_state, E * st->state_size * sizeof(float), hipMemcpyDeviceToHost));
+  if (step_counters) HIP_TRY(hipMemcpy(step_counters, st->g, E * sizeof(int64_t), hipMemcpyDeviceToHost));
+  return MSRL_OK;
+}
+
+int msrl_state_set(msrl_state* st, const float* env_state, const int64_t* step_counters) {
+  if (!st) return fail(MSRL_EINVAL, "msrl_state_set: NULL state");
+  const size_t E = (size_t)st->env.num_envs;
+  if (step_counters)
+    for (size_t e = 0; e < E; ++e)
+      if (step_counters[e] < 0) return fail(MSRL_EINVAL, "msrl_state_set: negative step counter");
+  HIP_TRY(hipDeviceSynchronize());
+  if (env_state)
+    HIP_TRY(hipMemcpy(st->env_state, env_state, E * st->state_size * sizeof(float), hipMemcpyHostToDevice));
+  if (step_counters) HIP_TRY(hipMemcpy(st->g, step_counters, E * sizeof(int64_t), hipMemcpyHostToDevice));
+  HIP_TRY(hipDeviceSynchronize());
+  return MSRL_OK;
+}
+
+}  // extern "C"

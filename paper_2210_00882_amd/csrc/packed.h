@@ -1,0 +1,81 @@
+// Layout of network parameters re-ordered for the MFMA kernels ("packed"
+// parameters), shared by the packing kernel and the rollout kernels.
+//
+// The rollout kernels compute every layer transposed: out^T = W^T * in^T, so the
+// weights are the MFMA "A" operand (32 output units x k input units per
+// instruction), the batch rows are the 32 columns of the "B" operand, and a
+// layer's result lands in the accumulator layout
+//     lane (n = lane % 32, h = lane / 32), register r  <->  row n, unit 8*(r/4) + 4*h + r%4.
+// Because the order of the k index inside a contraction is free, the weights of
+// the next layer are stored so that this accumulator layout can be fed straight
+// back in as the next B operand, with no transpose through LDS ("chained" map).
+//
+// A tile is 1 KiB: 64 lanes x 16 bytes; lane (m = lane % 32, h) holds, for output
+// unit 32*uc + m, the inputs
+//   bf16 : 8 values s = 0..7  = the k slots 8*h + s of one 32x32x16 MFMA
+//   f32  : 4 values j = 0..3  = the k slot h of four consecutive 32x32x2 MFMAs.
+// Input index of (tile kt, h, s or j):
+//   chained bf16 : 32*(kt/2) + 16*(kt%2) + 8*(s/4) + 4*h + s%4
+//   chained f32  : 32*(kt/4) + 8*(kt%4) + 4*h + j
+//   linear  bf16 : 16*kt + 8*h + s                  (particle observation, layer 1)
+//   pairs   f32  : 8*kt + 2*j + h                   (particle observation, layer 1)
+// Inputs or outputs beyond the real sizes hold zeros.
+//
+// One network = [layer-1 tiles (uc major, kt minor)] [layer-2 tiles] [layer-3
+// tiles, one output chunk] [b1 (H floats)] [b2 (H)] [b3 (32, physical order)].
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace msrl {
+
+enum InMap : int { IN_CHAIN = 0, IN_LINEAR16 = 1, IN_PAIRS = 2 };
+// physical output row m of a layer-3 tile -> logical output
+//   OUT_NATURAL : m
+//   OUT_GAUSS   : m < 8 -> mean m;  8 <= m < 16 -> log-std (m - 8)   (act_dim <= 8)
+enum OutMap : int { OUT_NATURAL = 0, OUT_GAUSS = 1 };
+
+struct NetLayout {
+  int kt1, kt2, nuc;           // tiles per output chunk in layer 1 / layers 2,3; chunks of 32 units
+  size_t w1, w2, w3;           // byte offsets of the tile arrays
+  size_t b1, b2, b3;           // byte offsets of the bias arrays
+  size_t bytes;                // size of one packed network
+};
+
+__host__ __device__ inline int tiles_for_inputs(int n_in, bool bf16) {
+  return bf16 ? (n_in + 15) / 16 : (n_in + 7) / 8;
+}
+
+__host__ __device__ inline NetLayout net_layout(int in_dim, int hidden, bool bf16) {
+  NetLayout L;
+  L.kt1 = tiles_for_inputs(in_dim, bf16);
+  L.kt2 = tiles_for_inputs(hidden, bf16);
+  L.nuc = hidden / 32;
+  L.w1 = 0;
+  L.w2 = L.w1 + (size_t)L.nuc * L.kt1 * 1024;
+  L.w3 = L.w2 + (size_t)L.nuc * L.kt2 * 1024;
+  L.b1 = L.w3 + (size_t)L.kt2 * 1024;
+  L.b2 = L.b1 + (size_t)hidden * 4;
+  L.b3 = L.b2 + (size_t)hidden * 4;
+  L.bytes = L.b3 + 32 * 4;
+  return L;
+}
+
+// One matrix (or bias vector) to re-order.
+struct PackJob {
+  const void* src;   // device
+  void* dst;         // device
+  int src_bf16;      // source element type (dst tiles have the same type; biases become f32)
+  int is_bias;       // 1: copy n_out values through the output map into 32*nuc floats
+  int n_in, n_out;   // logical sizes
+  int src_out_major; // 0: src[in * n_out + out] (network weights); 1: src[out * n_in + in]
+  int nuc, kt;       // output chunks, tiles per chunk
+  int in_map, out_map, gauss_k;
+};
+
+struct PackJobs {
+  int n;
+  PackJob job[14];
+};
+
+}  // namespace msrl

@@ -1,0 +1,38 @@
+// Table of the compiled rollout kernels.  Each instantiation lives in its own
+// translation unit (inst_*.hip) so that they compile in parallel.
+#pragma once
+#include "rollout_kernels.h"
+
+namespace msrl {
+
+struct KernelEntry {
+  int kind;           // 0 particle, 1 lingauss
+  int n;              // particle: agents per env; lingauss: state width
+  int k;              // lingauss: action width; particle: 0
+  int hidden;
+  int bf16;
+  const void* fn;     // __global__ void (*)(RolloutArgs)
+  int envs_per_wave;
+};
+
+#define MSRL_PARTICLE_ENTRY(NAME, N, H, BF16)                                              \
+  KernelEntry NAME() {                                                                     \
+    return KernelEntry{0, N, 0, H, BF16 ? 1 : 0,                                           \
+                       (const void*)&particle_rollout_kernel<N, H, BF16>,                  \
+                       (BF16 ? 64 : 32) / N};                                              \
+  }
+
+#define MSRL_LINGAUSS_ENTRY(NAME, D, K, H)                                                 \
+  KernelEntry NAME() {                                                                     \
+    return KernelEntry{1, D, K, H, 0, (const void*)&lingauss_rollout_kernel<D, K, H>, 32}; \
+  }
+
+KernelEntry entry_p1_h64_f32();
+KernelEntry entry_p2_h64_f32();
+KernelEntry entry_p3_h64_f32();
+KernelEntry entry_p3_h64_bf16();
+KernelEntry entry_p6_h128_f32();
+KernelEntry entry_p10_h256_bf16();
+KernelEntry entry_l17_6_h256();
+
+}  // namespace msrl

@@ -1,0 +1,437 @@
+// The fused actor + environment rollout kernels.
+//
+// One launch runs all T steps (Listing 1 of the paper: the `duration` loop of
+// Trainer.train around Actor.act).  Environments are independent, so a wave
+// owns a fixed group of environments for the whole call, keeps their state in
+// registers / LDS, and never synchronises with another wave: per step it builds
+// the observation rows, stores them, runs both networks on MFMA (mlp.h),
+// samples the action with Philox, moves the environment, computes reward and
+// done, resets finished episodes and stores the step's trajectory entries.
+//
+// Row <-> lane mapping: a wave handles 32*NB rows; row 32*q + n lives on lanes n
+// and n + 32 (the two k-halves of the MFMA operands).  Both lanes keep a copy of
+// the row's state and execute the same arithmetic; lane n does the stores.
+#pragma once
+#include "dev_common.h"
+#include "mlp.h"
+#include "packed.h"
+
+namespace msrl {
+
+struct RolloutArgs {
+  float* env_state;       // [E, S] snapshot layout of msrl_state_get
+  int64_t* g;             // [E] step counters
+  const uint8_t* packed;  // policy network, then value network (packed.h)
+  const uint8_t* dyn;     // lingauss: tiles of A, then one tile of B
+  int E, T, ep;
+  float dt, keep, fdt, coll2;  // particle: dt, 1 - damping, force * dt, (2 radius)^2
+  float noise_std, act_cost;   // lingauss
+  uint32_t seed_lo, seed_hi;
+  float* obs;
+  void* actions;
+  float* logp;
+  float* rewards;
+  uint8_t* dones;
+  float* values;
+  float* logits;  // may be null
+  int64_t M;
+};
+
+constexpr int WAVES_PER_BLOCK = 4;
+
+__device__ __forceinline__ void load_bias_to_lds(float* dst, const uint8_t* packed, size_t net_bytes,
+                                                 size_t bias_off, int per_net) {
+  for (int i = threadIdx.x; i < 2 * per_net; i += blockDim.x) {
+    const int net = i / per_net, k = i - net * per_net;
+    dst[i] = *(const float*)(packed + (size_t)net * net_bytes + bias_off + (size_t)k * 4);
+  }
+}
+
+// Categorical draw by inverse CDF in fp32, in index order; logp = z_a - log(sum exp z).
+__device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u, int& action,
+                                                    float& logp) {
+  float mx = l[0];
+#pragma unroll
+  for (int k = 1; k < 5; ++k) mx = fmaxf(mx, l[k]);
+  float z[5], e[5], s = 0.0f;
+#pragma unroll
+  for (int k = 0; k < 5; ++k) {
+    z[k] = l[k] - mx;
+    e[k] = __expf(z[k]);
+    s += e[k];
+  }
+  float c = 0.0f;
+  int a = 4;
+  bool found = false;
+#pragma unroll
+  for (int k = 0; k < 5; ++k) {
+    c += e[k] / s;
+    if (!found && u < c) {
+      a = k;
+      found = true;
+    }
+  }
+  float za = z[0];
+#pragma unroll
+  for (int k = 1; k < 5; ++k) za = (a == k) ? z[k] : za;
+  action = a;
+  logp = za - logf(s);
+}
+
+// ------------------------------------------------------------------ particle env
+template <int N, int H, bool BF16>
+__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void particle_rollout_kernel(RolloutArgs a) {
+  constexpr int NB = BF16 ? 2 : 1;
+  constexpr int ROWS = 32 * NB;
+  constexpr int EPW = ROWS / N;  // envs per wave
+  constexpr int VR = EPW * N;    // rows in use
+  constexpr int L = N;
+  constexpr int D = 6 * N;
+  constexpr int S = 4 * N + 2 * L;
+  constexpr int KT1 = BF16 ? (D + 15) / 16 : (D + 7) / 8;
+  typedef Mlp<H, BF16, NB, KT1> Net;
+  typedef typename Net::Op Op;
+  constexpr int BIAS = 2 * H + 32;
+  static_assert(EPW >= 1, "a wave must hold at least one env");
+
+  __shared__ __attribute__((aligned(16))) float s_bias[2 * BIAS];
+  __shared__ float2 s_tab[WAVES_PER_BLOCK][2 * ROWS];  // [0,ROWS) landmarks, [ROWS,2ROWS) agents
+  __shared__ float s_part[WAVES_PER_BLOCK][2 * ROWS];
+
+  const NetLayout ly = net_layout(D, H, BF16);
+  load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 31, h = lane >> 5;
+  const int64_t env0 = ((int64_t)blockIdx.x * WAVES_PER_BLOCK + wave) * EPW;
+  if (env0 >= a.E) return;  // no block-wide barrier after this point
+  float2* tab = s_tab[wave];
+  float* part = s_part[wave];
+  const uint8_t* net_p = a.packed;
+  const uint8_t* net_v = a.packed + ly.bytes;
+
+  int row[NB], base[NB], ag[NB];
+  uint32_t env[NB];
+  bool valid[NB];
+  float2 p[NB], v[NB];
+  uint32_t g32[NB];
+  int tau[NB];
+  uint32_t episode[NB];
+  int64_t g64[NB];
+#pragma unroll
+  for (int q = 0; q < NB; ++q) {
+    row[q] = 32 * q + n;
+    int le = row[q] / N;
+    ag[q] = row[q] - le * N;
+    valid[q] = row[q] < VR && env0 + le < a.E;
+    if (!valid[q]) {
+      le = 0;
+      ag[q] = 0;
+    }
+    base[q] = le * N;
+    env[q] = (uint32_t)(env0 + le);
+    const float* es = a.env_state + (size_t)env[q] * S;
+    p[q] = make_float2(es[4 * ag[q]], es[4 * ag[q] + 1]);
+    v[q] = make_float2(es[4 * ag[q] + 2], es[4 * ag[q] + 3]);
+    const float2 lm = make_float2(es[4 * N + 2 * ag[q]], es[4 * N + 2 * ag[q] + 1]);
+    g64[q] = a.g[env[q]];
+    g32[q] = (uint32_t)g64[q];
+    tau[q] = (int)(g64[q] % a.ep);
+    episode[q] = (uint32_t)(g64[q] / a.ep);
+    if (h == 0 && valid[q]) {
+      tab[base[q] + ag[q]] = lm;
+      tab[ROWS + base[q] + ag[q]] = p[q];
+    }
+  }
+  wave_lds_sync();
+
+  const int64_t m0 = env0 * N;  // first trajectory row of this wave
+
+  for (int t = 0; t <= a.T; ++t) {
+    // ---------------- observation rows: build, store, convert to MFMA operands
+    Op x[NB][KT1 * Net::PT];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      float* orow = a.obs + ((size_t)t * a.M + m0 + row[q]) * D;
+      auto pair_value = [&](int gp) -> float2 {
+        // pair 0: v, 1: p, [2, 2+L): landmark - p, [2+L, 1+L+N): other agent - p, rest 0
+        const int jj = gp - 2 - L;
+        const int j = jj + (jj >= ag[q] ? 1 : 0);
+        int idx = gp < 2 + L ? base[q] + gp - 2 : ROWS + base[q] + j;
+        idx = min(max(idx, 0), 2 * ROWS - 1);
+        const float2 tv = tab[idx];
+        float2 o = make_float2(tv.x - p[q].x, tv.y - p[q].y);
+        if (gp >= 1 + L + N) o = make_float2(0.0f, 0.0f);
+        if (gp == 1) o = p[q];
+        if (gp == 0) o = v[q];
+        return o;
+      };
+      if constexpr (BF16) {
+#pragma unroll
+        for (int kt = 0; kt < KT1; ++kt) {
+          f32x8 f;
+#pragma unroll
+          for (int pi = 0; pi < 4; ++pi) {
+            const float2 o = pair_value(8 * kt + 4 * h + pi);
+            f[2 * pi] = o.x;
+            f[2 * pi + 1] = o.y;
+          }
+          const int f0 = 16 * kt + 8 * h;
+          if (valid[q]) {
+            if constexpr (D % 4 == 0) {
+              if (f0 + 4 <= D) *(float4*)(orow + f0) = make_float4(f[0], f[1], f[2], f[3]);
+              if (f0 + 8 <= D) *(float4*)(orow + f0 + 4) = make_float4(f[4], f[5], f[6], f[7]);
+            } else {
+#pragma unroll
+              for (int pi = 0; pi < 4; ++pi)
+                if (f0 + 2 * pi + 2 <= D) *(float2*)(orow + f0 + 2 * pi) = make_float2(f[2 * pi], f[2 * pi + 1]);
+            }
+          }
+          x[q][kt] = __builtin_convertvector(f, bf16x8);
+        }
+      } else {
+#pragma unroll
+        for (int mm = 0; mm < KT1 * 4; ++mm) {
+          float2 o = make_float2(0.0f, 0.0f);
+          if (2 * mm < D) {
+            o = pair_value(mm);
+            if (valid[q] && (mm & 1) == h) *(float2*)(orow + 2 * mm) = o;
+          }
+          x[q][mm] = h ? o.y : o.x;
+        }
+      }
+    }
+
+    // ---------------- networks
+    f32x16 out_v[NB];
+    Net::forward(net_v, s_bias + BIAS, x, out_v, lane);
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+      if (h == 0 && valid[q]) a.values[(size_t)t * a.M + m0 + row[q]] = out_v[q][0];
+    if (t == a.T) break;
+
+    f32x16 out_p[NB];
+    Net::forward(net_p, s_bias, x, out_p, lane);
+
+    // ---------------- sampling, physics
+    float rew_term[NB];
+    int action[NB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      float l[5];
+      l[0] = out_p[q][0];
+      l[1] = out_p[q][1];
+      l[2] = out_p[q][2];
+      l[3] = out_p[q][3];
+      l[4] = __shfl_xor(out_p[q][0], 32);  // logit 4 sits in register 0 of the partner lane
+      const Words4 w = draw(a.seed_lo, a.seed_hi, env[q], (uint32_t)ag[q], g32[q], 0, 0);
+      float lp;
+      int act;
+      sample_categorical5(l, u01(w.w[0]), act, lp);
+      act = __shfl(act, n);  // the h = 0 lane of the row decides
+      action[q] = act;
+      const size_t o = (size_t)t * a.M + m0 + row[q];
+      if (h == 0 && valid[q]) {
+        ((int32_t*)a.actions)[o] = act;
+        a.logp[o] = lp;
+        if (a.logits) {
+#pragma unroll
+          for (int k = 0; k < 5; ++k) a.logits[o * 5 + k] = l[k];
+        }
+      }
+      const float fx = (act == 1 ? 1.0f : 0.0f) - (act == 2 ? 1.0f : 0.0f);
+      const float fy = (act == 3 ? 1.0f : 0.0f) - (act == 4 ? 1.0f : 0.0f);
+      v[q].x = v[q].x * a.keep + fx * a.fdt;
+      v[q].y = v[q].y * a.keep + fy * a.fdt;
+      p[q].x += v[q].x * a.dt;
+      p[q].y += v[q].y * a.dt;
+      if (h == 0 && valid[q]) tab[ROWS + base[q] + ag[q]] = p[q];
+    }
+    wave_lds_sync();
+
+    // ---------------- shared reward: lane h = 0 takes landmark ag, lane h = 1 the collisions of agent ag
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      const float2 lm = tab[base[q] + ag[q]];
+      float mn = 3.0e38f, cnt = 0.0f;
+      for (int j = 0; j < N; ++j) {
+        const float2 pj = tab[ROWS + base[q] + j];
+        const float dxl = pj.x - lm.x, dyl = pj.y - lm.y;
+        mn = fminf(mn, dxl * dxl + dyl * dyl);
+        const float dxa = pj.x - p[q].x, dya = pj.y - p[q].y;
+        if (j > ag[q] && dxa * dxa + dya * dya < a.coll2) cnt += 1.0f;
+      }
+      rew_term[q] = h ? -cnt : -sqrtf(mn);
+      if (valid[q]) part[h * ROWS + base[q] + ag[q]] = rew_term[q];
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      float r = 0.0f;
+      for (int j = 0; j < N; ++j) r += part[base[q] + j] + part[ROWS + base[q] + j];
+      const bool done = tau[q] + 1 == a.ep;
+      const size_t o = (size_t)t * a.M + m0 + row[q];
+      if (h == 0 && valid[q]) {
+        a.rewards[o] = r;
+        a.dones[o] = done ? 1 : 0;
+      }
+      g32[q] += 1;
+      tau[q] = done ? 0 : tau[q] + 1;
+      if (done) {
+        episode[q] += 1;
+        const Words4 wa = draw(a.seed_lo, a.seed_hi, env[q], (uint32_t)ag[q], episode[q], 1, 0);
+        p[q] = make_float2(2.0f * u01(wa.w[0]) - 1.0f, 2.0f * u01(wa.w[1]) - 1.0f);
+        v[q] = make_float2(0.0f, 0.0f);
+        const Words4 wl = draw(a.seed_lo, a.seed_hi, env[q], (uint32_t)(N + ag[q]), episode[q], 1, 0);
+        if (h == 0 && valid[q]) {
+          tab[base[q] + ag[q]] = make_float2(2.0f * u01(wl.w[0]) - 1.0f, 2.0f * u01(wl.w[1]) - 1.0f);
+          tab[ROWS + base[q] + ag[q]] = p[q];
+        }
+      }
+    }
+    wave_lds_sync();
+  }
+
+  // ---------------- write the env state back
+#pragma unroll
+  for (int q = 0; q < NB; ++q) {
+    if (h == 0 && valid[q]) {
+      float* es = a.env_state + (size_t)env[q] * S;
+      es[4 * ag[q]] = p[q].x;
+      es[4 * ag[q] + 1] = p[q].y;
+      es[4 * ag[q] + 2] = v[q].x;
+      es[4 * ag[q] + 3] = v[q].y;
+      const float2 lm = tab[base[q] + ag[q]];
+      es[4 * N + 2 * ag[q]] = lm.x;
+      es[4 * N + 2 * ag[q] + 1] = lm.y;
+      if (ag[q] == 0) a.g[env[q]] = g64[q] + a.T;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ linear-Gaussian env
+// State unit u of a row lives in accumulator layout: lane (n, h), register r with
+// u = 8*(r/4) + 4*h + r%4, so s' = A s + B a is one more MFMA chain on the same
+// registers and its result is already the next step's layer-1 operand.
+template <int D, int K, int H>
+__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void lingauss_rollout_kernel(RolloutArgs a) {
+  constexpr int KT1 = (D + 7) / 8;
+  constexpr int NR = 4 * KT1;  // state registers per lane
+  typedef Mlp<H, false, 1, KT1> Net;
+  constexpr int BIAS = 2 * H + 32;
+  static_assert(D <= 32 && K <= 8, "one MFMA chunk of state, one tile of action");
+
+  __shared__ __attribute__((aligned(16))) float s_bias[2 * BIAS];
+  const NetLayout ly = net_layout(D, H, false);
+  load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 31, h = lane >> 5;
+  const int64_t env0 = ((int64_t)blockIdx.x * WAVES_PER_BLOCK + wave) * 32;
+  if (env0 >= a.E) return;
+  const bool valid = env0 + n < a.E;
+  const uint32_t env = (uint32_t)(valid ? env0 + n : env0);
+  const uint8_t* net_p = a.packed;
+  const uint8_t* net_v = a.packed + ly.bytes;
+  const u32x4* dynA = (const u32x4*)a.dyn + lane;
+  const u32x4* dynB = (const u32x4*)a.dyn + KT1 * 64 + lane;
+
+  float s[1][NR];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const int u = 8 * (r >> 2) + 4 * h + (r & 3);
+    s[0][r] = u < D ? a.env_state[(size_t)env * D + u] : 0.0f;
+  }
+  const int64_t g64 = a.g[env];
+  uint32_t g32 = (uint32_t)g64;
+  int tau = (int)(g64 % a.ep);
+  uint32_t episode = (uint32_t)(g64 / a.ep);
+
+  for (int t = 0; t <= a.T; ++t) {
+    const size_t o = (size_t)t * a.M + env;
+    if (valid) {
+#pragma unroll
+      for (int r = 0; r < NR; ++r) {
+        const int u = 8 * (r >> 2) + 4 * h + (r & 3);
+        if (u < D) a.obs[o * D + u] = s[0][r];
+      }
+    }
+    f32x16 out_v[1];
+    Net::forward(net_v, s_bias + BIAS, s, out_v, lane);
+    if (valid && h == 0) a.values[o] = out_v[0][0];
+    if (t == a.T) break;
+
+    f32x16 out_p[1];
+    Net::forward(net_p, s_bias, s, out_p, lane);
+
+    // action dims 4h + c: mean in register c, log-std in register 4 + c
+    float eps[4], act[4], lp = 0.0f, cost = 0.0f;
+    normals4(a.seed_lo, a.seed_hi, env, 0, g32, 0, (uint32_t)h, eps);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int d = 4 * h + c;
+      const float mean = out_p[0][c], logstd = out_p[0][4 + c];
+      act[c] = 0.0f;
+      if (d < K) {
+        act[c] = mean + __expf(logstd) * eps[c];
+        lp += -0.5f * eps[c] * eps[c] - logstd - 0.9189385332046727f;
+        cost += act[c] * act[c];
+        if (valid) {
+          ((float*)a.actions)[o * K + d] = act[c];
+          if (a.logits) {
+            a.logits[o * (2 * K) + d] = mean;
+            a.logits[o * (2 * K) + K + d] = logstd;
+          }
+        }
+      }
+    }
+    lp += __shfl_xor(lp, 32);
+    float ss = 0.0f;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) ss += s[0][r] * s[0][r];
+    float rew = ss + a.act_cost * cost;
+    rew += __shfl_xor(rew, 32);
+    const bool done = tau + 1 == a.ep;
+    if (valid && h == 0) {
+      a.logp[o] = lp;
+      a.rewards[o] = -rew;
+      a.dones[o] = done ? 1 : 0;
+    }
+
+    // s' = A s + B a + noise_std * eps
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+    for (int kt = 0; kt < KT1; ++kt) mma_tile<false>(dynA[kt * 64], &s[0][4 * kt], acc);
+    mma_tile<false>(dynB[0], act, acc);
+#pragma unroll
+    for (int b = 0; b < KT1; ++b) {
+      float e[4];  // reset draw (stream 1, new episode) or step noise (stream 2, step counter)
+      normals4(a.seed_lo, a.seed_hi, env, 0, done ? episode + 1 : g32, done ? 1u : 2u,
+               (uint32_t)(2 * b + h), e);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int u = 8 * b + 4 * h + c;
+        const float nv = done ? e[c] : acc[4 * b + c] + a.noise_std * e[c];
+        s[0][4 * b + c] = u < D ? nv : 0.0f;
+      }
+    }
+    g32 += 1;
+    tau = done ? 0 : tau + 1;
+    if (done) episode += 1;
+  }
+
+  if (valid) {
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      const int u = 8 * (r >> 2) + 4 * h + (r & 3);
+      if (u < D) a.env_state[(size_t)env * D + u] = s[0][r];
+    }
+    if (h == 0) a.g[env] = g64 + a.T;
+  }
+}
+
+}  // namespace msrl

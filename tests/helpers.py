@@ -1,0 +1,199 @@
+"""Shared test plumbing: oracle objects for a synthetic configuration, a GPU
+runner that goes through the C ABI, and the stage-wise (teacher-forced) parity
+check of a GPU trajectory against the CPU oracle.
+
+Tolerances (written out where they are used):
+  fp32 quantities  |gpu - oracle| <= 1e-4 * max(1, |oracle|)
+  bf16 networks    |gpu - oracle| <= 2e-2 * max(1, |oracle|)   (logits, values)
+  integers         bit-exact, except a categorical action whose uniform lies
+                   within 1e-5 of a CDF bin edge, and a reward whose collision
+                   count hinges on a pair distance within 1e-5 of 2*radius.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import ref
+from paper_2210_00882_amd import synth
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+EDGE = 1e-5
+
+
+def close(g, o, tol):
+    g, o = np.asarray(g, dtype=np.float64), np.asarray(o, dtype=np.float64)
+    return np.abs(g - o) <= tol * np.maximum(1.0, np.abs(o))
+
+
+def assert_close(g, o, tol, what):
+    ok = close(g, o, tol)
+    if not np.all(ok):
+        g, o = np.asarray(g, dtype=np.float64), np.asarray(o, dtype=np.float64)
+        bad = np.argwhere(~ok)
+        i = tuple(bad[0])
+        raise AssertionError(f"{what}: {len(bad)} of {ok.size} outside tol {tol}; first at {i}: "
+                             f"gpu {g[i]!r} oracle {o[i]!r}")
+
+
+def oracle_setup(cfg: synth.Config, bias_std=0.1, params=None):
+    """-> (ref.Env, ref.Policy, params float64 as the networks see them, dynamics (A, B) or None)."""
+    dyn = None
+    if cfg.kind == synth.PARTICLE:
+        env = ref.Env(ref.PARTICLE, cfg.num_agents, cfg.num_landmarks, cfg.obs_dim, 1, cfg.episode_len,
+                      dt=np.float32(cfg.dt), damping=np.float32(cfg.damping), force=np.float32(cfg.force),
+                      radius=np.float32(cfg.radius))
+    else:
+        dyn = synth.make_dynamics(cfg)
+        env = ref.Env(ref.LINGAUSS, 1, 0, cfg.obs_dim, cfg.act_dim, cfg.episode_len, A=dyn[0], B=dyn[1],
+                      noise_std=np.float32(cfg.noise_std), act_cost=np.float32(cfg.act_cost))
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist)
+    if params is None:
+        params = synth.make_params(cfg, bias_std=bias_std)
+    return env, pol, np.asarray(params, dtype=np.float64), dyn
+
+
+class GpuRollout:
+    """One env batch on cuda:0 driven through the C ABI binding."""
+
+    def __init__(self, cfg: synth.Config, params_f32, seed, dyn=None):
+        import torch
+        from paper_2210_00882_amd import binding as B
+        self.B, self.cfg, self.torch = B, cfg, torch
+        A, Bm = dyn if dyn is not None else (None, None)
+        self.env_cfg, self._keep = B.make_env_cfg(cfg, A, Bm)
+        self.pol_cfg = B.make_policy_cfg(cfg)
+        self.state = B.msrl_rollout_init(self.env_cfg, self.pol_cfg, seed)
+        self.params = B.upload_params(cfg, params_f32)
+        self.seed = seed
+
+    def close(self):
+        if self.state is not None:
+            self.B.msrl_rollout_destroy(self.state)
+            self.state = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def get_state(self):
+        return self.B.msrl_state_get(self.state, self.cfg.num_envs, self.cfg.env_state_size)
+
+    def set_state(self, env_state=None, g=None):
+        self.B.msrl_state_set(self.state, env_state, g)
+
+    def run(self, T, gae=True, logits=True, out=None):
+        """-> dict of numpy arrays (device tensors copied back after a sync)."""
+        B, cfg = self.B, self.cfg
+        dev = out if out is not None else B.alloc_traj(cfg, T, logits=logits, gae=gae)
+        for v in dev.values():
+            if v is not None:
+                v.fill_(-77 if v.dtype != self.torch.uint8 else 77)
+        if gae:
+            B.msrl_rollout_gae(self.state, self.params, T, cfg.gamma, cfg.lam, dev)
+        else:
+            B.msrl_rollout_step(self.state, self.params, T, dev)
+        self.torch.cuda.synchronize()
+        self.dev = dev
+        return {k: (None if v is None else v.cpu().numpy()) for k, v in dev.items()}
+
+
+def particle_state_from_obs(cfg, rows):
+    """Env state [4N + 2L] from the env's N observation rows."""
+    N, L = cfg.num_agents, cfg.num_landmarks
+    s = np.zeros(4 * N + 2 * L)
+    for i in range(N):
+        s[4 * i:4 * i + 2] = rows[i][2:4]
+        s[4 * i + 2:4 * i + 4] = rows[i][0:2]
+    s[4 * N:] = rows[0][4:4 + 2 * L].astype(np.float64) + np.tile(rows[0][2:4].astype(np.float64), L)
+    return s
+
+
+def check_trajectory(cfg, tr, env, pol, params, seed, env_ids, g0, T, mlp_rows_cap=None, rng=None, row0=None):
+    """Stage-wise check of a GPU trajectory `tr` for the listed env ids.
+
+    g0: step counter of every listed env at t = 0 (int or array over env_ids).
+    row0: first row of each listed env inside `tr` (default env * N; differs when
+    `tr` holds only the sampled envs of a larger run).
+    Each stage is fed what the GPU itself produced for the previous stage, so one
+    flipped action cannot make every later comparison meaningless.
+    Returns counters of the exemptions that were used.
+    """
+    N, D, M = cfg.num_agents, cfg.obs_dim, cfg.M
+    net_tol = TOL_BF16 if cfg.dtype == synth.BF16 else TOL_F32
+    stats = {"rows": 0, "action_edge": 0, "collision_edge": 0, "mlp_rows": 0}
+    g0 = np.broadcast_to(np.asarray(g0, dtype=np.int64), (len(env_ids),))
+    rng = rng or np.random.default_rng(0)
+    for k, e in enumerate(env_ids):
+        r0 = e * N if row0 is None else int(row0[k])
+        rows = slice(r0, r0 + N)
+        for t in range(T + 1):
+            g = int(g0[k]) + t
+            o_gpu = tr["obs"][t, rows]
+            if cfg.kind == synth.PARTICLE:
+                s = particle_state_from_obs(cfg, o_gpu)
+                assert_close(o_gpu, ref.env_obs(env, s), TOL_F32, f"obs rows env {e} t {t}")
+                assert (o_gpu[:, 4 + 2 * cfg.num_landmarks + 2 * (N - 1):] == 0).all()
+            else:
+                s = o_gpu[0].astype(np.float64)
+            # networks on the GPU's own observation rows
+            do_mlp = mlp_rows_cap is None or rng.random() < mlp_rows_cap
+            for i in range(N):
+                m = r0 + i
+                if do_mlp:
+                    lg, v = ref.policy_value(pol, params, o_gpu[i])
+                    assert_close(tr["values"][t, m], v, net_tol, f"value env {e} agent {i} t {t}")
+                    if t < T and tr.get("logits") is not None:
+                        assert_close(tr["logits"][t, m], lg, net_tol, f"logits env {e} agent {i} t {t}")
+                    stats["mlp_rows"] += 1
+            if t == T:
+                break
+            # sampler on the GPU's own logits
+            acts = []
+            for i in range(N):
+                m = r0 + i
+                a_o, lp_o, mg = ref.sample(pol, seed, e, i, g, tr["logits"][t, m])
+                if cfg.dist == synth.CATEGORICAL:
+                    a_g = int(tr["actions"][t, m])
+                    if a_g != a_o:
+                        assert mg < EDGE, f"action env {e} agent {i} t {t}: gpu {a_g} oracle {a_o} margin {mg}"
+                        stats["action_edge"] += 1
+                        _, lp_o = _logp_of(tr["logits"][t, m], a_g)
+                    assert 0 <= a_g < 5
+                    acts.append(a_g)
+                else:
+                    assert_close(tr["actions"][t, m], a_o, TOL_F32, f"action env {e} t {t}")
+                    acts = tr["actions"][t, m].astype(np.float64)
+                assert_close(tr["logp"][t, m], lp_o, TOL_F32, f"logp env {e} agent {i} t {t}")
+                stats["rows"] += 1
+            # env step from the GPU's state with the GPU's actions
+            s1, r, d, mg = ref.env_step(env, seed, e, g, s, acts)
+            assert (tr["dones"][t, rows] == d).all(), f"done env {e} t {t}"
+            r_gpu = tr["rewards"][t, rows]
+            assert (r_gpu == r_gpu[0]).all(), f"reward not shared env {e} t {t}"
+            if not close(r_gpu[0], r, TOL_F32):
+                assert mg < EDGE and abs(abs(r_gpu[0] - r) - 1.0) < 1e-3, \
+                    f"reward env {e} t {t}: gpu {r_gpu[0]} oracle {r} (collision margin {mg})"
+                stats["collision_edge"] += 1
+            assert_close(tr["obs"][t + 1, rows], ref.env_obs(env, s1), TOL_F32, f"next obs env {e} t {t}")
+    return stats
+
+
+def _logp_of(logits, a):
+    lg = np.asarray(logits, dtype=np.float64)
+    z = lg - lg.max()
+    return a, float(z[a] - np.log(np.exp(z).sum()))
+
+
+def check_gae(cfg, tr, cols=None):
+    r, V, d = tr["rewards"], tr["values"], tr["dones"]
+    if cols is not None:
+        r, V, d = r[:, cols], V[:, cols], d[:, cols]
+    adv, ret = ref.gae(np.ascontiguousarray(r), np.ascontiguousarray(V), np.ascontiguousarray(d), cfg.gamma, cfg.lam)
+    ga, gr = tr["adv"], tr["ret"]
+    if cols is not None:
+        ga, gr = ga[:, cols], gr[:, cols]
+    assert_close(ga, adv, TOL_F32, "adv")
+    assert_close(gr, ret, TOL_F32, "ret")
