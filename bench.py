@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused rollout + GAE path on one MI355X.
+
+One "step" = one msrl_rollout_gae call = T environment steps of every env
+(observation, both networks, sampling, env move, reward, reset, trajectory
+stores) followed by the GAE pass.  The default workload is the largest of the
+five synthetic configurations (65536 envs x 10 agents, bf16 networks, T = 200).
+
+Prints ONE JSON line: agent-steps/s of the whole call, the roofline of the
+dominant kernel (the rollout kernel: MFMA-bound) from HIP-event timings taken
+in this run, a second roofline object for the GAE kernel (HBM-bound), and the
+CPU oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+PEAK_HBM_GBS = 8000.0
+
+
+def mlp_flops_per_agent_step(cfg) -> int:
+    """2 * MACs of the un-padded policy and value networks."""
+    d, h = cfg.obs_dim, cfg.hidden
+    return 2 * ((d * h + h * h + h * cfg.out_dim) + (d * h + h * h + h))
+
+
+def rollout_bytes_per_agent_step(cfg) -> int:
+    act = 4 if cfg.dist == 0 else 4 * cfg.act_dim
+    return 4 * cfg.obs_dim + act + 4 + 4 + 1 + 4  # obs, action, logp, reward, done, value
+
+
+GAE_BYTES_PER_AGENT_STEP = 17  # r, V, d read; adv, ret written
+
+
+def read_traffic(name: str):
+    """HBM bytes per launch from the committed counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(cfg, seed, seconds_target=15.0):
+    """The oracle as it stands on the host cores, on the first envs of the same
+    workload over the full T (envs are independent and keyed by global env id)."""
+    from concurrent.futures import ThreadPoolExecutor
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import oracle_setup
+    from oracle import ref
+
+    env, pol, params, _ = oracle_setup(cfg, bias_std=0.0)
+
+    def run(env0, n_env, T):
+        st, g = ref.init(env, seed, env0, n_env)
+        tr = ref.rollout(env, pol, seed, env0, st, g, params, T, want_logits=False)
+        ref.gae(tr["rewards"], tr["values"], tr["dones"], cfg.gamma, cfg.lam)
+        return n_env * cfg.num_agents * T
+
+    # calibrate on one env for a few steps, then size the sample to the target time
+    t0 = time.perf_counter()
+    n = run(0, 1, 4)
+    per_step = (time.perf_counter() - t0) / n
+    n_env = int(max(1, min(cfg.num_envs, seconds_target / (per_step * cfg.num_agents * cfg.T))))
+    t0 = time.perf_counter()
+    n = run(0, n_env, cfg.T)
+    dt1 = time.perf_counter() - t0
+    one = n / dt1
+    threads = min(16, os.cpu_count() or 1)
+    per_thread = max(1, n_env // 2)
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as pool:
+        done = sum(pool.map(lambda k: run(k * per_thread, per_thread, cfg.T), range(threads)))
+    dtn = time.perf_counter() - t0
+    return {
+        "value": one, "unit": "agent-steps/s", "cores": 1, "kind": "oracle",
+        "sample": f"envs 0..{n_env - 1} of {cfg.num_envs}, all T={cfg.T} steps, rollout + GAE ({n} agent-steps, {dt1:.1f} s)",
+        "all_cores": {"value": done / dtn, "cores": threads,
+                      "sample": f"{threads} threads x {per_thread} envs ({done} agent-steps, {dtn:.1f} s)"},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=5, help="synthetic configuration 1..5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    from paper_2210_00882_amd import binding as B, synth
+
+    cfg = synth.CONFIGS[args.config]
+    seed = cfg.env_seed
+    params = synth.make_params(cfg)  # benchmark recipe: weights N(0, 1/fan_in), biases 0
+    dyn = synth.make_dynamics(cfg) if cfg.kind == synth.LINGAUSS else (None, None)
+    env_cfg, keep = B.make_env_cfg(cfg, *dyn)
+    state = B.msrl_rollout_init(env_cfg, B.make_policy_cfg(cfg), seed)
+    dparams = B.upload_params(cfg, params)
+    out = B.alloc_traj(cfg, cfg.T, logits=False, gae=True)
+    T, M = cfg.T, cfg.M
+    agent_steps = T * M
+
+    def step():
+        B.msrl_rollout_gae(state, dparams, T, cfg.gamma, cfg.lam, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # per-kernel durations: the same two launches msrl_rollout_gae enqueues, issued
+    # separately with HIP events between them on the stream they run on
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for k in range(args.steps):
+        ev[k][0].record()
+        B.msrl_rollout_step(state, dparams, T, out)
+        ev[k][1].record()
+        B.msrl_gae(out["rewards"], out["values"], out["dones"], cfg.gamma, cfg.lam, out["adv"], out["ret"])
+        ev[k][2].record()
+    torch.cuda.synchronize()
+    roll_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    gae_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+
+    dt_name = "bf16" if cfg.dtype == synth.BF16 else "f32"
+    flops = mlp_flops_per_agent_step(cfg) * agent_steps
+    achieved = flops / (roll_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": "rollout", "bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dt_name],
+        "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS[dt_name],
+        "traffic": read_traffic(f"rollout_cfg{args.config}_pmc.md"),
+        "ms_per_launch": roll_ms,
+        "hbm_GBps": rollout_bytes_per_agent_step(cfg) * agent_steps / (roll_ms * 1e-3) / 1e9,
+    }
+    gae_achieved = GAE_BYTES_PER_AGENT_STEP * agent_steps / (gae_ms * 1e-3) / 1e9
+    roofline_gae = {
+        "kernel": "gae", "bound": "hbm", "achieved": gae_achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+        "frac": gae_achieved / PEAK_HBM_GBS, "traffic": read_traffic(f"gae_cfg{args.config}_pmc.md"),
+        "ms_per_launch": gae_ms,
+    }
+
+    B.msrl_rollout_destroy(state)
+    del out
+    torch.cuda.empty_cache()
+
+    result = {
+        "metric": "agent-steps/sec of fused rollout+GAE at 1 GPU",
+        "value": agent_steps / (ms_per_step * 1e-3),
+        "unit": "agent-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dt_name, "data": "synthetic",
+        "config": {"workload": cfg.name, "num_envs": cfg.num_envs, "num_agents": cfg.num_agents,
+                   "rows_M": M, "T": T, "obs_dim": cfg.obs_dim, "hidden": cfg.hidden,
+                   "agent_steps_per_step": agent_steps},
+        "roofline": roofline,
+        "roofline_gae": roofline_gae,
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(cfg, seed),
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
