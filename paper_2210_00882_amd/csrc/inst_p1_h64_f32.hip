@@ -1,5 +1,5 @@
 // One rollout-kernel instantiation (see registry.h).
 #include "registry.h"
 namespace msrl {
-MSRL_PARTICLE_ENTRY(entry_p1_h64_f32, 1, 64, false)
+MSRL_PARTICLE_ENTRY(entry_p1_h64_f32, 1, 64, false, 1, 2)
 }  // namespace msrl

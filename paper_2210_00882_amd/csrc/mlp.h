@@ -4,9 +4,11 @@
 //   lane (n = lane % 32, h = lane / 32), register r  <->  row n, unit 32*uc + 8*(r/4) + 4*h + r%4
 // are, after bias + tanh (+ rounding to bf16), exactly the B operand of the next
 // layer's MFMAs: activations never leave the register file.  The weights are
-// the A operand and stream in as 1 KiB tiles in the order written by the
-// packing kernel (packed.h).  Layer 3 is accumulated inside the layer-2 chunk
-// loop, so h2 is consumed as soon as it is produced.
+// the A operand; the workgroup streams them through LDS in stages (the layer-1
+// tiles, then one block per 32-unit chunk of layer 2 with the layer-3 tiles that
+// consume it; see packed.h), and every wave of the workgroup reads the same
+// stage.  Layer 3 is accumulated inside the layer-2 chunk stage, so h2 is
+// consumed as soon as it is produced.
 #pragma once
 #include "dev_common.h"
 #include "packed.h"
@@ -24,9 +26,9 @@ __device__ __forceinline__ f32x16 mma(float a, float b, f32x16 c) {
 
 template <bool BF16> struct Operand;
 template <> struct Operand<true> {
-  typedef bf16x8 T;                 // one B operand: 8 k-slots of one MFMA
-  static constexpr int PER_TILE = 1;  // MFMAs (B operands) per weight tile
-  static constexpr int PER_CHUNK = 2; // B operands made from one 32-unit accumulator
+  typedef bf16x8 T;                    // one B operand: 8 k-slots of one MFMA
+  static constexpr int PER_TILE = 1;   // MFMAs (B operands) per weight tile
+  static constexpr int PER_CHUNK = 2;  // B operands made from one 32-unit accumulator
 };
 template <> struct Operand<false> {
   typedef float T;
@@ -83,65 +85,93 @@ struct Mlp {
   static constexpr int PC = Operand<BF16>::PER_CHUNK;
   static constexpr int NUC = H / 32;
   static constexpr int KT2 = BF16 ? H / 16 : H / 8;
-  static constexpr int TPC = KT2 / NUC;  // layer-3 tiles fed by one 32-unit chunk
+  static constexpr int TPC = KT2 / NUC;            // layer-3 tiles fed by one 32-unit chunk
+  static constexpr int L1_TILES = NUC * KT1;       // stage 0 of a network
+  static constexpr int CHUNK_TILES = KT2 + TPC;    // stages 1..NUC of a network
+  static constexpr int STAGES = 1 + NUC;
+  static constexpr int MAX_STAGE_TILES = L1_TILES > CHUNK_TILES ? L1_TILES : CHUNK_TILES;
 
-  // net: packed network in global memory; lds_bias: b1[H] b2[H] b3[32];
-  // x: layer-1 B operands; out: layer-3 accumulators (32 physical outputs x rows).
-  __device__ static __forceinline__ void forward(const uint8_t* __restrict__ net,
-                                                 const float* lds_bias, const Op (&x)[NB][KT1 * PT],
-                                                 f32x16 (&out)[NB], int lane) {
-    const int h = lane >> 5;
-    const u32x4* w1 = (const u32x4*)net + lane;
-    const u32x4* w2 = (const u32x4*)(net + (size_t)NUC * KT1 * 1024) + lane;
-    const u32x4* w3 = (const u32x4*)(net + (size_t)NUC * KT1 * 1024 + (size_t)NUC * KT2 * 1024) + lane;
-    Op h1[NB][KT2 * PT];
-
+  // tiles: this lane's slot of tile 0 of the stage in LDS (tile t is at tiles[64 t]).
+  __device__ static __forceinline__ void layer1(const u32x4* tiles, const float* lds_b1,
+                                                const Op (&x)[NB][KT1 * PT],
+                                                Op (&h1)[NB][KT2 * PT], int h) {
 #pragma unroll
     for (int uc = 0; uc < NUC; ++uc) {
       f32x16 acc[NB];
-      const f32x16 b = bias_init(lds_bias, uc, h);
+      const f32x16 b = bias_init(lds_b1, uc, h);
 #pragma unroll
       for (int q = 0; q < NB; ++q) acc[q] = b;
 #pragma unroll
       for (int kt = 0; kt < KT1; ++kt) {
-        const u32x4 raw = w1[(uc * KT1 + kt) * 64];
+        const u32x4 raw = tiles[(uc * KT1 + kt) * 64];
 #pragma unroll
         for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
       }
 #pragma unroll
       for (int q = 0; q < NB; ++q) activate<BF16>(acc[q], &h1[q][uc * PC]);
     }
+  }
 
-    {
-      const f32x16 b = bias_init(lds_bias + 2 * H, 0, h);
+  __device__ static __forceinline__ void out_init(const float* lds_b3, f32x16 (&out)[NB], int h) {
+    const f32x16 b = bias_init(lds_b3, 0, h);
 #pragma unroll
-      for (int q = 0; q < NB; ++q) out[q] = b;
+    for (int q = 0; q < NB; ++q) out[q] = b;
+  }
+
+  // one 32-unit chunk of layer 2 and its contribution to layer 3
+  __device__ static __forceinline__ void layer2_chunk(const u32x4* tiles, const float* lds_b2, int uc,
+                                                      const Op (&h1)[NB][KT2 * PT],
+                                                      f32x16 (&out)[NB], int h) {
+    f32x16 acc[NB];
+    const f32x16 b = bias_init(lds_b2, uc, h);
+#pragma unroll
+    for (int q = 0; q < NB; ++q) acc[q] = b;
+#pragma unroll
+    for (int kt = 0; kt < KT2; ++kt) {
+      const u32x4 raw = tiles[kt * 64];
+#pragma unroll
+      for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
     }
-#pragma unroll 1
-    for (int uc = 0; uc < NUC; ++uc) {
-      f32x16 acc[NB];
-      const f32x16 b = bias_init(lds_bias + H, uc, h);
+    Op h2[NB][PC];
 #pragma unroll
-      for (int q = 0; q < NB; ++q) acc[q] = b;
-      const u32x4* w = w2 + (size_t)uc * KT2 * 64;
+    for (int q = 0; q < NB; ++q) activate<BF16>(acc[q], h2[q]);
 #pragma unroll
-      for (int kt = 0; kt < KT2; ++kt) {
-        const u32x4 raw = w[kt * 64];
+    for (int i = 0; i < TPC; ++i) {
+      const u32x4 raw = tiles[(KT2 + i) * 64];
 #pragma unroll
-        for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
-      }
-      Op h2[NB][PC];
-#pragma unroll
-      for (int q = 0; q < NB; ++q) activate<BF16>(acc[q], h2[q]);
-      const u32x4* w3c = w3 + (size_t)uc * TPC * 64;
-#pragma unroll
-      for (int i = 0; i < TPC; ++i) {
-        const u32x4 raw = w3c[i * 64];
-#pragma unroll
-        for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h2[q][i * PT], out[q]);
-      }
+      for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h2[q][i * PT], out[q]);
     }
   }
+};
+
+// Double-buffered weight stream of a workgroup: stage g of the endless sequence
+// (policy stages, value stages, policy stages, ...) lives in buffer g % 2.
+template <class Net, int WAVES>
+struct WeightStream {
+  static constexpr int STAGES_PER_STEP = 2 * Net::STAGES;
+  static constexpr int BUF_SLOTS = Net::MAX_STAGE_TILES * 64;  // u32x4 slots per buffer
+  u32x4* lds;            // 2 * BUF_SLOTS slots
+  const uint8_t* packed;
+  size_t net_bytes, chunks_off, chunk_bytes;
+  int wave, lane;
+
+  // start the copy of stage s (0 .. STAGES_PER_STEP-1) into buffer `parity`
+  __device__ __forceinline__ void issue(int s, int parity) const {
+    const int net = s >= Net::STAGES ? 1 : 0;
+    const int ls = s - net * Net::STAGES;
+    const uint8_t* src = packed + (size_t)net * net_bytes +
+                         (ls == 0 ? 0 : chunks_off + (size_t)(ls - 1) * chunk_bytes);
+    const int n_tiles = ls == 0 ? Net::L1_TILES : Net::CHUNK_TILES;
+    u32x4* dst = lds + parity * BUF_SLOTS;
+    for (int t = wave; t < n_tiles; t += WAVES)
+      __builtin_amdgcn_global_load_lds((const u32x4*)(src + (size_t)t * 1024) + lane, dst + t * 64, 16, 0, 0);
+  }
+  // wait for this wave's copies, then for every wave of the workgroup
+  __device__ __forceinline__ void wait() const {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  }
+  __device__ __forceinline__ const u32x4* tiles(int parity) const { return lds + parity * BUF_SLOTS + lane; }
 };
 
 }  // namespace msrl

@@ -37,6 +37,7 @@ struct msrl_state {
   float* dyn_src;        // device copy of A then B (row-major), source of dyn
   NetLayout layout;
   KernelEntry kernel;
+  int envs_per_block;    // envs owned by one workgroup
 };
 
 namespace {
@@ -124,6 +125,7 @@ PackJob weight_job(const void* src, void* dst, bool bf16, int n_in, int n_out, i
   j.src = src; j.dst = dst; j.src_bf16 = bf16; j.is_bias = 0;
   j.n_in = n_in; j.n_out = n_out; j.src_out_major = 0;
   j.nuc = nuc; j.kt = kt; j.in_map = in_map; j.out_map = out_map; j.gauss_k = gauss_k;
+  j.group = kt; j.chunk_stride = kt; j.slot_base = 0;  // plain (uc major, kt minor) order
   return j;
 }
 
@@ -157,8 +159,15 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     const uint8_t* W3 = b2 + (size_t)p.hidden * esz;
     const uint8_t* b3 = W3 + (size_t)p.hidden * out * esz;
     jobs.job[jobs.n++] = weight_job(W1, dst + L.w1, bf16, p.in_dim, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
-    jobs.job[jobs.n++] = weight_job(W2, dst + L.w2, bf16, p.hidden, p.hidden, L.nuc, L.kt2, IN_CHAIN, OUT_NATURAL, 0);
-    jobs.job[jobs.n++] = weight_job(W3, dst + L.w3, bf16, p.hidden, out, 1, L.kt2, IN_CHAIN, out_map, gk);
+    // chunk blocks: kt2 layer-2 tiles of chunk uc, then the tpc layer-3 tiles fed by chunk uc
+    PackJob j2 = weight_job(W2, dst + L.chunks, bf16, p.hidden, p.hidden, L.nuc, L.kt2, IN_CHAIN, OUT_NATURAL, 0);
+    j2.chunk_stride = L.kt2 + L.tpc;
+    jobs.job[jobs.n++] = j2;
+    PackJob j3 = weight_job(W3, dst + L.chunks, bf16, p.hidden, out, 1, L.kt2, IN_CHAIN, out_map, gk);
+    j3.group = L.tpc;
+    j3.chunk_stride = L.kt2 + L.tpc;
+    j3.slot_base = L.kt2;
+    jobs.job[jobs.n++] = j3;
     jobs.job[jobs.n++] = bias_job(b1, dst + L.b1, bf16, p.hidden, L.nuc, OUT_NATURAL, 0);
     jobs.job[jobs.n++] = bias_job(b2, dst + L.b2, bf16, p.hidden, L.nuc, OUT_NATURAL, 0);
     jobs.job[jobs.n++] = bias_job(b3, dst + L.b3, bf16, out, 1, out_map, gk);
@@ -205,10 +214,10 @@ int enqueue_rollout(msrl_state* st, const void* params, int32_t T, msrl_traj* ou
   a.values = out->values;
   a.logits = out->logits;
   a.M = (int64_t)st->env.num_envs * st->env.num_agents;
-  const int64_t waves = ((int64_t)a.E + st->kernel.envs_per_wave - 1) / st->kernel.envs_per_wave;
-  const int64_t blocks = (waves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+  a.envs_per_block = st->envs_per_block;
+  const int64_t blocks = ((int64_t)a.E + a.envs_per_block - 1) / a.envs_per_block;
   void* args[] = {&a};
-  HIP_TRY(hipLaunchKernel(st->kernel.fn, dim3((unsigned)blocks), dim3(64 * WAVES_PER_BLOCK), args, 0, stream));
+  HIP_TRY(hipLaunchKernel(st->kernel.fn, dim3((unsigned)blocks), dim3(64 * st->kernel.waves), args, 0, stream));
   return MSRL_OK;
 }
 
@@ -279,6 +288,23 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   st->pol = *policy;
   st->seed = seed;
   st->kernel = found;
+  {
+    // Every workgroup runs all T steps, so the launch takes ceil(blocks / resident) rounds.  Shrink the
+    // block to the smallest size that needs no more rounds than the largest one: equal work per
+    // workgroup instead of a short last round.
+    hipDeviceProp_t prop;
+    int dev = 0;
+    int cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cus = prop.multiProcessorCount;
+    const int64_t max_epb = (int64_t)found.envs_per_wave * found.waves;
+    const int64_t blocks_max = (env->num_envs + max_epb - 1) / max_epb;
+    const int64_t rounds = (blocks_max + cus - 1) / cus;
+    int64_t epb = (env->num_envs + rounds * cus - 1) / (rounds * cus);
+    if (epb < 1) epb = 1;
+    if (epb > max_epb) epb = max_epb;
+    st->envs_per_block = (int)epb;
+  }
   st->state_size = (int)msrl_env_state_size(env);
   st->layout = net_layout(policy->in_dim, policy->hidden, policy->dtype == MSRL_BF16);
 

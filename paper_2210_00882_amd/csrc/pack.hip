@@ -48,6 +48,7 @@ __global__ void pack_kernel(PackJobs jobs) {
   if (tid >= n_tiles * 64) return;
   const int tile = tid >> 6, lane = tid & 63;
   const int uc = tile / j.kt, kt = tile % j.kt;
+  const int dst_slot = ((uc + kt / j.group) * j.chunk_stride + j.slot_base + kt % j.group) * 64 + lane;
   const int m = lane & 31, h = lane >> 5;
   const int o = out_index(j.out_map, j.gauss_k, 32 * uc + m, j.n_out);
   const bool bf16 = j.src_bf16 != 0;
@@ -63,9 +64,9 @@ __global__ void pack_kernel(PackJobs jobs) {
     uint32_t w[4];
     for (int p = 0; p < 4; ++p)
       w[p] = (__float_as_uint(v[2 * p]) >> 16) | (__float_as_uint(v[2 * p + 1]) & 0xFFFF0000u);
-    ((uint4*)j.dst)[tid] = make_uint4(w[0], w[1], w[2], w[3]);
+    ((uint4*)j.dst)[dst_slot] = make_uint4(w[0], w[1], w[2], w[3]);
   } else {
-    ((float4*)j.dst)[tid] = make_float4(v[0], v[1], v[2], v[3]);
+    ((float4*)j.dst)[dst_slot] = make_float4(v[0], v[1], v[2], v[3]);
   }
 }
 

@@ -21,8 +21,12 @@
 //   pairs   f32  : 8*kt + 2*j + h                   (particle observation, layer 1)
 // Inputs or outputs beyond the real sizes hold zeros.
 //
-// One network = [layer-1 tiles (uc major, kt minor)] [layer-2 tiles] [layer-3
-// tiles, one output chunk] [b1 (H floats)] [b2 (H)] [b3 (32, physical order)].
+// One network = [layer-1 tiles (uc major, kt minor)], then per 32-unit chunk uc
+// of layer 2 one "chunk block" = [its kt2 layer-2 tiles][the kt2/nuc layer-3
+// tiles that consume that chunk's outputs], then [b1 (H floats)] [b2 (H)]
+// [b3 (32, physical order)].  The rollout kernels stream the weights through LDS
+// in stages: the layer-1 tiles are one stage, every chunk block is one stage, so
+// each stage is one contiguous byte range.
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -36,8 +40,10 @@ enum InMap : int { IN_CHAIN = 0, IN_LINEAR16 = 1, IN_PAIRS = 2 };
 enum OutMap : int { OUT_NATURAL = 0, OUT_GAUSS = 1 };
 
 struct NetLayout {
-  int kt1, kt2, nuc;           // tiles per output chunk in layer 1 / layers 2,3; chunks of 32 units
-  size_t w1, w2, w3;           // byte offsets of the tile arrays
+  int kt1, kt2, nuc, tpc;      // tiles per chunk in layer 1 / layer 2; chunks of 32 units; layer-3 tiles per chunk
+  size_t w1;                   // byte offset of the layer-1 tiles
+  size_t chunks;               // byte offset of chunk block 0
+  size_t chunk_bytes;          // size of one chunk block: (kt2 + tpc) KiB
   size_t b1, b2, b3;           // byte offsets of the bias arrays
   size_t bytes;                // size of one packed network
 };
@@ -51,10 +57,11 @@ __host__ __device__ inline NetLayout net_layout(int in_dim, int hidden, bool bf1
   L.kt1 = tiles_for_inputs(in_dim, bf16);
   L.kt2 = tiles_for_inputs(hidden, bf16);
   L.nuc = hidden / 32;
+  L.tpc = L.kt2 / L.nuc;
   L.w1 = 0;
-  L.w2 = L.w1 + (size_t)L.nuc * L.kt1 * 1024;
-  L.w3 = L.w2 + (size_t)L.nuc * L.kt2 * 1024;
-  L.b1 = L.w3 + (size_t)L.kt2 * 1024;
+  L.chunks = L.w1 + (size_t)L.nuc * L.kt1 * 1024;
+  L.chunk_bytes = (size_t)(L.kt2 + L.tpc) * 1024;
+  L.b1 = L.chunks + (size_t)L.nuc * L.chunk_bytes;
   L.b2 = L.b1 + (size_t)hidden * 4;
   L.b3 = L.b2 + (size_t)hidden * 4;
   L.bytes = L.b3 + 32 * 4;
@@ -70,6 +77,11 @@ struct PackJob {
   int n_in, n_out;   // logical sizes
   int src_out_major; // 0: src[in * n_out + out] (network weights); 1: src[out * n_in + in]
   int nuc, kt;       // output chunks, tiles per chunk
+  // destination tile of (output chunk uc, input tile kt):
+  //   (uc + kt / group) * chunk_stride + slot_base + kt % group
+  // layers 1, 2: group = kt (tiles of a chunk are consecutive); layer 3: group = tiles
+  // per chunk block, so its tiles follow the layer-2 tiles of the chunk they consume.
+  int group, chunk_stride, slot_base;
   int in_map, out_map, gauss_k;
 };
 

@@ -13,18 +13,21 @@ struct KernelEntry {
   int bf16;
   const void* fn;     // __global__ void (*)(RolloutArgs)
   int envs_per_wave;
+  int waves;          // waves per workgroup
 };
 
-#define MSRL_PARTICLE_ENTRY(NAME, N, H, BF16)                                              \
+// NB: 32-row blocks per wave; WAVES: waves per workgroup (they share the LDS weight window)
+#define MSRL_PARTICLE_ENTRY(NAME, N, H, BF16, NB, WAVES)                                   \
   KernelEntry NAME() {                                                                     \
     return KernelEntry{0, N, 0, H, BF16 ? 1 : 0,                                           \
-                       (const void*)&particle_rollout_kernel<N, H, BF16>,                  \
-                       (BF16 ? 64 : 32) / N};                                              \
+                       (const void*)&particle_rollout_kernel<N, H, BF16, NB, WAVES>,       \
+                       32 * NB / N, WAVES};                                                \
   }
 
-#define MSRL_LINGAUSS_ENTRY(NAME, D, K, H)                                                 \
+#define MSRL_LINGAUSS_ENTRY(NAME, D, K, H, WAVES)                                          \
   KernelEntry NAME() {                                                                     \
-    return KernelEntry{1, D, K, H, 0, (const void*)&lingauss_rollout_kernel<D, K, H>, 32}; \
+    return KernelEntry{1, D, K, H, 0, (const void*)&lingauss_rollout_kernel<D, K, H, WAVES>, \
+                       32, WAVES};                                                         \
   }
 
 KernelEntry entry_p1_h64_f32();

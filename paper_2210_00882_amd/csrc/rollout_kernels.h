@@ -2,11 +2,14 @@
 //
 // One launch runs all T steps (Listing 1 of the paper: the `duration` loop of
 // Trainer.train around Actor.act).  Environments are independent, so a wave
-// owns a fixed group of environments for the whole call, keeps their state in
-// registers / LDS, and never synchronises with another wave: per step it builds
-// the observation rows, stores them, runs both networks on MFMA (mlp.h),
-// samples the action with Philox, moves the environment, computes reward and
-// done, resets finished episodes and stores the step's trajectory entries.
+// owns a fixed group of environments for the whole call and keeps their state in
+// registers / LDS: per step it builds the observation rows, stores them, runs
+// both networks on MFMA (mlp.h), samples the action with Philox, moves the
+// environment, computes reward and done, resets finished episodes and stores
+// the step's trajectory entries.  The waves of a workgroup share only the
+// weight stream: the network parameters pass through a double-buffered LDS
+// window, one barrier per stage, and every wave multiplies its own rows with
+// the stage that is resident.
 //
 // Row <-> lane mapping: a wave handles 32*NB rows; row 32*q + n lives on lanes n
 // and n + 32 (the two k-halves of the MFMA operands).  Both lanes keep a copy of
@@ -24,6 +27,7 @@ struct RolloutArgs {
   const uint8_t* packed;  // policy network, then value network (packed.h)
   const uint8_t* dyn;     // lingauss: tiles of A, then one tile of B
   int E, T, ep;
+  int envs_per_block;     // envs owned by one workgroup (<= WAVES * envs per wave)
   float dt, keep, fdt, coll2;  // particle: dt, 1 - damping, force * dt, (2 radius)^2
   float noise_std, act_cost;   // lingauss
   uint32_t seed_lo, seed_hi;
@@ -36,8 +40,6 @@ struct RolloutArgs {
   float* logits;  // may be null
   int64_t M;
 };
-
-constexpr int WAVES_PER_BLOCK = 4;
 
 __device__ __forceinline__ void load_bias_to_lds(float* dst, const uint8_t* packed, size_t net_bytes,
                                                  size_t bias_off, int per_net) {
@@ -79,9 +81,8 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 }
 
 // ------------------------------------------------------------------ particle env
-template <int N, int H, bool BF16>
-__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void particle_rollout_kernel(RolloutArgs a) {
-  constexpr int NB = BF16 ? 2 : 1;
+template <int N, int H, bool BF16, int NB, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArgs a) {
   constexpr int ROWS = 32 * NB;
   constexpr int EPW = ROWS / N;  // envs per wave
   constexpr int VR = EPW * N;    // rows in use
@@ -90,26 +91,36 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void particle_rollout_kernel(
   constexpr int S = 4 * N + 2 * L;
   constexpr int KT1 = BF16 ? (D + 15) / 16 : (D + 7) / 8;
   typedef Mlp<H, BF16, NB, KT1> Net;
+  typedef WeightStream<Net, WAVES> Stream;
   typedef typename Net::Op Op;
   constexpr int BIAS = 2 * H + 32;
   static_assert(EPW >= 1, "a wave must hold at least one env");
 
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[2 * Stream::BUF_SLOTS];
   __shared__ __attribute__((aligned(16))) float s_bias[2 * BIAS];
-  __shared__ float2 s_tab[WAVES_PER_BLOCK][2 * ROWS];  // [0,ROWS) landmarks, [ROWS,2ROWS) agents
-  __shared__ float s_part[WAVES_PER_BLOCK][2 * ROWS];
-
-  const NetLayout ly = net_layout(D, H, BF16);
-  load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
-  __syncthreads();
+  __shared__ float2 s_tab[WAVES][2 * ROWS];  // [0,ROWS) landmarks, [ROWS,2ROWS) agents
+  __shared__ float s_part[WAVES][2 * ROWS];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 31, h = lane >> 5;
-  const int64_t env0 = ((int64_t)blockIdx.x * WAVES_PER_BLOCK + wave) * EPW;
-  if (env0 >= a.E) return;  // no block-wide barrier after this point
+  const NetLayout ly = net_layout(D, H, BF16);
+  Stream ws;
+  ws.lds = s_w;
+  ws.packed = a.packed;
+  ws.net_bytes = ly.bytes;
+  ws.chunks_off = ly.chunks;
+  ws.chunk_bytes = ly.chunk_bytes;
+  ws.wave = wave;
+  ws.lane = lane;
+  ws.issue(0, 0);
+  load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
+
+  // envs of this workgroup: [blk0, blk0 + envs_per_block); of this wave: EPW of them
+  const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
+  const int64_t blk_end = min(blk0 + (int64_t)a.envs_per_block, (int64_t)a.E);
+  const int64_t env0 = blk0 + (int64_t)wave * EPW;
   float2* tab = s_tab[wave];
   float* part = s_part[wave];
-  const uint8_t* net_p = a.packed;
-  const uint8_t* net_v = a.packed + ly.bytes;
 
   int row[NB], base[NB], ag[NB];
   uint32_t env[NB];
@@ -124,13 +135,13 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void particle_rollout_kernel(
     row[q] = 32 * q + n;
     int le = row[q] / N;
     ag[q] = row[q] - le * N;
-    valid[q] = row[q] < VR && env0 + le < a.E;
+    valid[q] = row[q] < VR && env0 + le < blk_end;
     if (!valid[q]) {
       le = 0;
       ag[q] = 0;
     }
     base[q] = le * N;
-    env[q] = (uint32_t)(env0 + le);
+    env[q] = (uint32_t)(valid[q] ? env0 + le : blk0);
     const float* es = a.env_state + (size_t)env[q] * S;
     p[q] = make_float2(es[4 * ag[q]], es[4 * ag[q] + 1]);
     v[q] = make_float2(es[4 * ag[q] + 2], es[4 * ag[q] + 3]);
@@ -147,6 +158,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void particle_rollout_kernel(
   wave_lds_sync();
 
   const int64_t m0 = env0 * N;  // first trajectory row of this wave
+  int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % 2
 
   for (int t = 0; t <= a.T; ++t) {
     // ---------------- observation rows: build, store, convert to MFMA operands
@@ -203,16 +215,34 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void particle_rollout_kernel(
       }
     }
 
-    // ---------------- networks
-    f32x16 out_v[NB];
-    Net::forward(net_v, s_bias + BIAS, x, out_v, lane);
+    // ---------------- networks: policy stages, then value stages, through the LDS window
+    f32x16 out_p[NB], out_v[NB];
+    {
+      Op h1[NB][Net::KT2 * Net::PT];
+#pragma unroll
+      for (int net = 0; net < 2; ++net) {
+        f32x16(&out)[NB] = net == 0 ? out_p : out_v;
+        const float* bias = s_bias + net * BIAS;
+        ws.wait();
+        ws.issue(net * Net::STAGES + 1, (gs + 1) & 1);
+        Net::layer1(ws.tiles(gs & 1), bias, x, h1, h);
+        ++gs;
+        Net::out_init(bias + 2 * H, out, h);
+#pragma unroll 1
+        for (int uc = 0; uc < Net::NUC; ++uc) {
+          ws.wait();
+          const int next = net * Net::STAGES + 2 + uc;  // stage after this one, cyclic over the step
+          const bool last = net == 1 && uc == Net::NUC - 1;
+          if (!(last && t == a.T)) ws.issue(last ? 0 : next, (gs + 1) & 1);
+          Net::layer2_chunk(ws.tiles(gs & 1), bias + H, uc, h1, out, h);
+          ++gs;
+        }
+      }
+    }
 #pragma unroll
     for (int q = 0; q < NB; ++q)
       if (h == 0 && valid[q]) a.values[(size_t)t * a.M + m0 + row[q]] = out_v[q][0];
     if (t == a.T) break;
-
-    f32x16 out_p[NB];
-    Net::forward(net_p, s_bias, x, out_p, lane);
 
     // ---------------- sampling, physics
     float rew_term[NB];
@@ -314,29 +344,43 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void particle_rollout_kernel(
 // State unit u of a row lives in accumulator layout: lane (n, h), register r with
 // u = 8*(r/4) + 4*h + r%4, so s' = A s + B a is one more MFMA chain on the same
 // registers and its result is already the next step's layer-1 operand.
-template <int D, int K, int H>
-__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void lingauss_rollout_kernel(RolloutArgs a) {
+template <int D, int K, int H, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArgs a) {
   constexpr int KT1 = (D + 7) / 8;
   constexpr int NR = 4 * KT1;  // state registers per lane
   typedef Mlp<H, false, 1, KT1> Net;
+  typedef WeightStream<Net, WAVES> Stream;
   constexpr int BIAS = 2 * H + 32;
   static_assert(D <= 32 && K <= 8, "one MFMA chunk of state, one tile of action");
 
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[2 * Stream::BUF_SLOTS];
   __shared__ __attribute__((aligned(16))) float s_bias[2 * BIAS];
-  const NetLayout ly = net_layout(D, H, false);
-  load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
-  __syncthreads();
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 31, h = lane >> 5;
-  const int64_t env0 = ((int64_t)blockIdx.x * WAVES_PER_BLOCK + wave) * 32;
-  if (env0 >= a.E) return;
-  const bool valid = env0 + n < a.E;
-  const uint32_t env = (uint32_t)(valid ? env0 + n : env0);
-  const uint8_t* net_p = a.packed;
-  const uint8_t* net_v = a.packed + ly.bytes;
-  const u32x4* dynA = (const u32x4*)a.dyn + lane;
-  const u32x4* dynB = (const u32x4*)a.dyn + KT1 * 64 + lane;
+  const NetLayout ly = net_layout(D, H, false);
+  Stream ws;
+  ws.lds = s_w;
+  ws.packed = a.packed;
+  ws.net_bytes = ly.bytes;
+  ws.chunks_off = ly.chunks;
+  ws.chunk_bytes = ly.chunk_bytes;
+  ws.wave = wave;
+  ws.lane = lane;
+  ws.issue(0, 0);
+  load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
+
+  const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
+  const int64_t blk_end = min(blk0 + (int64_t)a.envs_per_block, (int64_t)a.E);
+  const int64_t env0 = blk0 + (int64_t)wave * 32;
+  const bool valid = env0 + n < blk_end;
+  const uint32_t env = (uint32_t)(valid ? env0 + n : blk0);
+  // the dynamics tiles are read once per step by every wave: they stay in registers
+  u32x4 dynA[KT1], dynB;
+#pragma unroll
+  for (int kt = 0; kt < KT1; ++kt) dynA[kt] = ((const u32x4*)a.dyn)[kt * 64 + lane];
+  dynB = ((const u32x4*)a.dyn)[KT1 * 64 + lane];
+  int gs = 0;
 
   float s[1][NR];
 #pragma unroll
@@ -358,13 +402,31 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void lingauss_rollout_kernel(
         if (u < D) a.obs[o * D + u] = s[0][r];
       }
     }
-    f32x16 out_v[1];
-    Net::forward(net_v, s_bias + BIAS, s, out_v, lane);
+    f32x16 out_p[1], out_v[1];
+    {
+      float h1[1][Net::KT2 * Net::PT];
+#pragma unroll
+      for (int net = 0; net < 2; ++net) {
+        f32x16(&out)[1] = net == 0 ? out_p : out_v;
+        const float* bias = s_bias + net * BIAS;
+        ws.wait();
+        ws.issue(net * Net::STAGES + 1, (gs + 1) & 1);
+        Net::layer1(ws.tiles(gs & 1), bias, s, h1, h);
+        ++gs;
+        Net::out_init(bias + 2 * H, out, h);
+#pragma unroll 1
+        for (int uc = 0; uc < Net::NUC; ++uc) {
+          ws.wait();
+          const int next = net * Net::STAGES + 2 + uc;
+          const bool last = net == 1 && uc == Net::NUC - 1;
+          if (!(last && t == a.T)) ws.issue(last ? 0 : next, (gs + 1) & 1);
+          Net::layer2_chunk(ws.tiles(gs & 1), bias + H, uc, h1, out, h);
+          ++gs;
+        }
+      }
+    }
     if (valid && h == 0) a.values[o] = out_v[0][0];
     if (t == a.T) break;
-
-    f32x16 out_p[1];
-    Net::forward(net_p, s_bias, s, out_p, lane);
 
     // action dims 4h + c: mean in register c, log-std in register 4 + c
     float eps[4], act[4], lp = 0.0f, cost = 0.0f;
@@ -405,8 +467,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void lingauss_rollout_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
-    for (int kt = 0; kt < KT1; ++kt) mma_tile<false>(dynA[kt * 64], &s[0][4 * kt], acc);
-    mma_tile<false>(dynB[0], act, acc);
+    for (int kt = 0; kt < KT1; ++kt) mma_tile<false>(dynA[kt], &s[0][4 * kt], acc);
+    mma_tile<false>(dynB, act, acc);
 #pragma unroll
     for (int b = 0; b < KT1; ++b) {
       float e[4];  // reset draw (stream 1, new episode) or step noise (stream 2, step counter)
