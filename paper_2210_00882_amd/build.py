@@ -18,7 +18,7 @@ FLAGS = [
     # packed fp32 instructions are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
-]
+] + os.environ.get("MSRL_EXTRA_FLAGS", "").split()
 
 
 def _compile(src: str) -> str:

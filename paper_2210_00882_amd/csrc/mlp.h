@@ -5,10 +5,10 @@
 // are, after bias + tanh (+ rounding to bf16), exactly the B operand of the next
 // layer's MFMAs: activations never leave the register file.  The weights are
 // the A operand; the workgroup streams them through LDS in stages (the layer-1
-// tiles, then one block per 32-unit chunk of layer 2 with the layer-3 tiles that
-// consume it; see packed.h), and every wave of the workgroup reads the same
-// stage.  Layer 3 is accumulated inside the layer-2 chunk stage, so h2 is
-// consumed as soon as it is produced.
+// tiles, then one block per 32-unit chunk of layer 2 together with the layer-3
+// tiles of that chunk and of the one before; see packed.h), and every wave of
+// the workgroup reads the same stage.  Layer 3 is accumulated as the layer-2
+// chunks complete, so h2 is consumed as soon as it is produced.
 #pragma once
 #include "dev_common.h"
 #include "packed.h"
@@ -40,6 +40,10 @@ template <> struct Operand<false> {
 template <bool BF16>
 __device__ __forceinline__ void mma_tile(const u32x4& raw, const typename Operand<BF16>::T* b,
                                          f32x16& acc) {
+#ifdef MSRL_X_NO_MFMA
+  acc[0] += __builtin_bit_cast(f32x4, raw)[0];
+  return;
+#endif
   if constexpr (BF16) {
     acc = mma(__builtin_bit_cast(bf16x8, raw), b[0], acc);
   } else {
@@ -61,54 +65,125 @@ __device__ __forceinline__ f32x16 bias_init(const float* lds_bias, int uc, int h
   return acc;
 }
 
-// tanh of a 32-unit accumulator, stored as the next layer's B operands
+// Program-order pins.  The compiler is free to move pure arithmetic anywhere, and left alone it
+// puts all MFMAs of a block first and all tanh work last, so nothing overlaps inside a wave.  An
+// empty volatile asm on a value fixes the point in program order where the value must exist; the
+// pins keep "MFMAs of tile k, tanh slice k, MFMAs of tile k+1, ..." in the order written below.
+__device__ __forceinline__ void pin(float& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin(f32x16& v) { asm volatile("" : "+v"(v)); }
+
+// tanh of accumulator registers [r0, r1) of a 32-unit chunk into a scratch array.  When pinned,
+// the whole group is computed between two pins, so its independent chains can be interleaved
+// with each other but stay between the neighbouring MFMAs.
+__device__ __forceinline__ void tanh_range(const f32x16& acc, float (&t)[16], int r0, int r1, bool pinned) {
+  float v[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) {
+      v[r] = acc[r];
+      if (pinned) pin(v[r]);
+    }
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) t[r] = fast_tanh(v[r]);
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1 && pinned) pin(t[r]);
+}
+
+// the 16 activated values of a chunk as the next layer's B operands
 template <bool BF16>
-__device__ __forceinline__ void activate(const f32x16& acc, typename Operand<BF16>::T* out) {
+__device__ __forceinline__ void to_operands(const float (&t)[16], typename Operand<BF16>::T* out) {
   if constexpr (BF16) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      f32x8 t;
+      f32x8 v;
 #pragma unroll
-      for (int s = 0; s < 8; ++s) t[s] = fast_tanh(acc[8 * j + s]);
-      out[j] = __builtin_convertvector(t, bf16x8);  // round to nearest even
+      for (int s = 0; s < 8; ++s) v[s] = t[8 * j + s];
+      out[j] = __builtin_convertvector(v, bf16x8);  // round to nearest even
     }
   } else {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) out[r] = fast_tanh(acc[r]);
+    for (int r = 0; r < 16; ++r) out[r] = t[r];
   }
 }
 
+// Software pipeline inside a wave: while the MFMAs of chunk c run, the VALU
+// applies bias-free tanh to the accumulators of chunk c-1 (the bias is the
+// accumulator's initial value), so both pipes are busy from one instruction
+// stream.  In a layer-2 stage the layer-3 MFMAs of chunk c-1 follow.
 template <int H, bool BF16, int NB, int KT1>
 struct Mlp {
+#ifdef MSRL_X_NO_TILE_READ
+#define TILE_AT(p, i) (u32x4{(uint32_t)(i), 1u, 2u, 3u})
+#else
+#define TILE_AT(p, i) ((p)[(i) * 64])
+#endif
   typedef typename Operand<BF16>::T Op;
   static constexpr int PT = Operand<BF16>::PER_TILE;
   static constexpr int PC = Operand<BF16>::PER_CHUNK;
   static constexpr int NUC = H / 32;
   static constexpr int KT2 = BF16 ? H / 16 : H / 8;
-  static constexpr int TPC = KT2 / NUC;            // layer-3 tiles fed by one 32-unit chunk
-  static constexpr int L1_TILES = NUC * KT1;       // stage 0 of a network
-  static constexpr int CHUNK_TILES = KT2 + TPC;    // stages 1..NUC of a network
+  static constexpr int TPC = KT2 / NUC;              // layer-3 tiles fed by one 32-unit chunk
+  static constexpr int L1_TILES = NUC * KT1;         // stage 0 of a network
+  static constexpr int CHUNK_TILES = KT2 + 2 * TPC;  // stages 1..NUC: layer-2 tiles of chunk c,
+                                                     // layer-3 tiles of chunk c-1, of chunk c
   static constexpr int STAGES = 1 + NUC;
   static constexpr int MAX_STAGE_TILES = L1_TILES > CHUNK_TILES ? L1_TILES : CHUNK_TILES;
+  static constexpr int G = 4;  // LDS reads run G tiles ahead of the MFMAs that consume them
+  // tanh of the previous chunk, spread over the NT tiles of the current one
+#ifndef MSRL_GS
+#define MSRL_GS 1
+#endif
+  // tiles per tanh group: after every GS-th tile the tanh of GS tiles' share of values is issued
+  static constexpr int GS = MSRL_GS;
+  template <int NT>
+  __device__ static __forceinline__ void tanh_slice(const f32x16 (&prev)[NB], float (&t)[NB][16], int kt) {
+    constexpr int gs = GS < NT ? GS : NT;
+    if (kt % gs != gs - 1) return;
+    const int k0 = kt - (gs - 1);
+    const int r0 = k0 * 16 / NT, r1 = (kt + 1) * 16 / NT;
+#pragma unroll
+    for (int q = 0; q < NB; ++q) tanh_range(prev[q], t[q], r0, r1, true);
+  }
 
   // tiles: this lane's slot of tile 0 of the stage in LDS (tile t is at tiles[64 t]).
   __device__ static __forceinline__ void layer1(const u32x4* tiles, const float* lds_b1,
                                                 const Op (&x)[NB][KT1 * PT],
                                                 Op (&h1)[NB][KT2 * PT], int h) {
+    u32x4 ring[G];
 #pragma unroll
-    for (int uc = 0; uc < NUC; ++uc) {
+    for (int i = 0; i < G && i < L1_TILES; ++i) ring[i] = TILE_AT(tiles, i);
+    f32x16 prev[NB];
+#pragma unroll
+    for (int uc = 0; uc <= NUC; ++uc) {
       f32x16 acc[NB];
-      const f32x16 b = bias_init(lds_b1, uc, h);
+      float t[NB][16];
+      if (uc < NUC) {
+        const f32x16 b = bias_init(lds_b1, uc, h);
 #pragma unroll
-      for (int q = 0; q < NB; ++q) acc[q] = b;
-#pragma unroll
-      for (int kt = 0; kt < KT1; ++kt) {
-        const u32x4 raw = tiles[(uc * KT1 + kt) * 64];
-#pragma unroll
-        for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
+        for (int q = 0; q < NB; ++q) acc[q] = b;
       }
 #pragma unroll
-      for (int q = 0; q < NB; ++q) activate<BF16>(acc[q], &h1[q][uc * PC]);
+      for (int kt = 0; kt < KT1; ++kt) {
+        if (uc < NUC) {
+          const int idx = uc * KT1 + kt;
+          const u32x4 raw = ring[idx % G];
+          if (idx + G < L1_TILES) ring[idx % G] = TILE_AT(tiles, idx + G);
+#pragma unroll
+          for (int q = 0; q < NB; ++q) {
+            mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
+            if (uc > 0) pin(acc[q]);
+          }
+        }
+        if (uc > 0) tanh_slice<KT1>(prev, t, kt);
+      }
+      if (uc > 0) {
+#pragma unroll
+        for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], &h1[q][(uc - 1) * PC]);
+      }
+#pragma unroll
+      for (int q = 0; q < NB; ++q) prev[q] = acc[q];
     }
   }
 
@@ -118,60 +193,135 @@ struct Mlp {
     for (int q = 0; q < NB; ++q) out[q] = b;
   }
 
-  // one 32-unit chunk of layer 2 and its contribution to layer 3
+  // Stage of chunk uc: acc <- layer-2 pre-activations of chunk uc; if PIPE, `acc` holds
+  // those of chunk uc-1 on entry, which get tanh and feed layer 3 meanwhile.
+  template <bool PIPE>
   __device__ static __forceinline__ void layer2_chunk(const u32x4* tiles, const float* lds_b2, int uc,
                                                       const Op (&h1)[NB][KT2 * PT],
-                                                      f32x16 (&out)[NB], int h) {
-    f32x16 acc[NB];
+                                                      f32x16 (&acc)[NB], f32x16 (&out)[NB], int h) {
+    u32x4 ring[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) ring[i] = TILE_AT(tiles, i);
+    f32x16 prev[NB];
+    float t[NB][16];
     const f32x16 b = bias_init(lds_b2, uc, h);
 #pragma unroll
-    for (int q = 0; q < NB; ++q) acc[q] = b;
+    for (int q = 0; q < NB; ++q) {
+      prev[q] = acc[q];
+      acc[q] = b;
+    }
 #pragma unroll
     for (int kt = 0; kt < KT2; ++kt) {
-      const u32x4 raw = tiles[kt * 64];
+      const u32x4 raw = ring[kt % G];
+      if (kt + G < KT2 + TPC) ring[kt % G] = TILE_AT(tiles, kt + G);
 #pragma unroll
-      for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
+      for (int q = 0; q < NB; ++q) {
+        mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
+        if (PIPE) pin(acc[q]);
+      }
+      if (PIPE) tanh_slice<KT2>(prev, t, kt);
     }
+    if (PIPE) {
+      Op h2[NB][PC];
+#pragma unroll
+      for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], h2[q]);
+#pragma unroll
+      for (int i = 0; i < TPC; ++i) {
+        const u32x4 raw = ring[(KT2 + i) % G];
+#pragma unroll
+        for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h2[q][i * PT], out[q]);
+      }
+    }
+  }
+
+  // after the last chunk stage: its tanh and layer-3 contribution (tiles of the same stage)
+  __device__ static __forceinline__ void layer2_drain(const u32x4* tiles, const f32x16 (&acc)[NB],
+                                                      f32x16 (&out)[NB]) {
+    u32x4 w3[TPC];
+#pragma unroll
+    for (int i = 0; i < TPC; ++i) w3[i] = TILE_AT(tiles, KT2 + TPC + i);
+    float t[NB][16];
     Op h2[NB][PC];
 #pragma unroll
-    for (int q = 0; q < NB; ++q) activate<BF16>(acc[q], h2[q]);
+    for (int q = 0; q < NB; ++q) {
+      tanh_range(acc[q], t[q], 0, 16, false);
+      to_operands<BF16>(t[q], h2[q]);
+    }
 #pragma unroll
     for (int i = 0; i < TPC; ++i) {
-      const u32x4 raw = tiles[(KT2 + i) * 64];
 #pragma unroll
-      for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h2[q][i * PT], out[q]);
+      for (int q = 0; q < NB; ++q) mma_tile<BF16>(w3[i], &h2[q][i * PT], out[q]);
     }
   }
 };
 
-// Double-buffered weight stream of a workgroup: stage g of the endless sequence
-// (policy stages, value stages, policy stages, ...) lives in buffer g % 2.
+// Weight stream of a workgroup: stage g of the endless sequence (policy stages,
+// value stages, policy stages, ...) lives in LDS buffer g % 3 and is copied there
+// two stages ahead by direct global->LDS loads (no registers involved).
+//
+// The copy instruction is issued from inline assembly on purpose: issued through
+// the compiler builtin, every later LDS read of the *resident* stage would be
+// made to wait for the copies still in flight (the compiler cannot tell the
+// buffers apart), which serialises the L2 latency with the compute.  The price
+// is that the wait is written by hand: each wave issues exactly PER_WAVE copies
+// per stage, loads complete in order, so "at most PER_WAVE vector-memory
+// operations outstanding" means the copies of the stage before the newest one
+// have landed.  Vector-memory operations the compiler issues itself only add to
+// the outstanding count, which makes the wait longer, never shorter.
 template <class Net, int WAVES>
 struct WeightStream {
   static constexpr int STAGES_PER_STEP = 2 * Net::STAGES;
-  static constexpr int BUF_SLOTS = Net::MAX_STAGE_TILES * 64;  // u32x4 slots per buffer
-  u32x4* lds;            // 2 * BUF_SLOTS slots
+  static constexpr int PER_WAVE = (Net::MAX_STAGE_TILES + WAVES - 1) / WAVES;  // copies per wave and stage
+  static constexpr int BUF_TILES = PER_WAVE * WAVES;                            // incl. padding tiles
+  static constexpr int BUF_SLOTS = BUF_TILES * 64;                              // u32x4 slots per buffer
+  static constexpr int NBUF = 3;
+  static_assert(PER_WAVE <= 15, "the hand-written wait encodes the count in 4 bits");
+  u32x4* lds;  // NBUF * BUF_SLOTS slots
   const uint8_t* packed;
   size_t net_bytes, chunks_off, chunk_bytes;
   int wave, lane;
 
-  // start the copy of stage s (0 .. STAGES_PER_STEP-1) into buffer `parity`
-  __device__ __forceinline__ void issue(int s, int parity) const {
+  // start copying stage s (0 .. STAGES_PER_STEP-1) into buffer `buf`
+  mutable int x_issued = 0;
+  __device__ __forceinline__ void issue(int s, int buf) const {
+#ifdef MSRL_X_NO_RELOAD
+    if (x_issued >= MSRL_X_NO_RELOAD) return;
+    ++x_issued;
+#endif
     const int net = s >= Net::STAGES ? 1 : 0;
     const int ls = s - net * Net::STAGES;
     const uint8_t* src = packed + (size_t)net * net_bytes +
                          (ls == 0 ? 0 : chunks_off + (size_t)(ls - 1) * chunk_bytes);
     const int n_tiles = ls == 0 ? Net::L1_TILES : Net::CHUNK_TILES;
-    u32x4* dst = lds + parity * BUF_SLOTS;
-    for (int t = wave; t < n_tiles; t += WAVES)
-      __builtin_amdgcn_global_load_lds((const u32x4*)(src + (size_t)t * 1024) + lane, dst + t * 64, 16, 0, 0);
+    typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+    const uint32_t base = (uint32_t)(uintptr_t)(lds_u32x4*)(lds + buf * BUF_SLOTS);
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+      const int t = wave + i * WAVES;
+      // a wave with no tile left repeats tile 0 into its padding tile: every wave issues PER_WAVE copies
+      const uint8_t* g = src + (size_t)(t < n_tiles ? t : 0) * 1024 + (size_t)lane * 16;
+      const uint32_t m0 = __builtin_amdgcn_readfirstlane(base + (uint32_t)t * 1024u);
+      asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory", "m0");
+    }
   }
-  // wait for this wave's copies, then for every wave of the workgroup
-  __device__ __forceinline__ void wait() const {
-    __builtin_amdgcn_s_waitcnt(0);
+  // wait until only the newest stage's copies may be outstanding, then for every wave
+  __device__ __forceinline__ void wait_older() const {
+    // s_waitcnt vmcnt(PER_WAVE): simm16 = vmcnt[3:0] | expcnt(7) << 4 | lgkmcnt(15) << 8
+#ifndef MSRL_X_NO_WAIT
+    __builtin_amdgcn_s_waitcnt(0x0F70 | PER_WAVE);
+#endif
+    sync();
+  }
+  __device__ __forceinline__ void wait_all() const {
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    sync();
+  }
+  __device__ __forceinline__ void sync() const {
+#ifndef MSRL_X_NO_BARRIER
     __syncthreads();
+#endif
   }
-  __device__ __forceinline__ const u32x4* tiles(int parity) const { return lds + parity * BUF_SLOTS + lane; }
+  __device__ __forceinline__ const u32x4* tiles(int buf) const { return lds + buf * BUF_SLOTS + lane; }
 };
 
 }  // namespace msrl

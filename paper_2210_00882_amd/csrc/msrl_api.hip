@@ -159,15 +159,24 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     const uint8_t* W3 = b2 + (size_t)p.hidden * esz;
     const uint8_t* b3 = W3 + (size_t)p.hidden * out * esz;
     jobs.job[jobs.n++] = weight_job(W1, dst + L.w1, bf16, p.in_dim, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
-    // chunk blocks: kt2 layer-2 tiles of chunk uc, then the tpc layer-3 tiles fed by chunk uc
+    // chunk block uc: kt2 layer-2 tiles of chunk uc, the tpc layer-3 tiles fed by chunk uc-1, the
+    // tpc layer-3 tiles fed by chunk uc
+    const int block_tiles = L.kt2 + 2 * L.tpc;
     PackJob j2 = weight_job(W2, dst + L.chunks, bf16, p.hidden, p.hidden, L.nuc, L.kt2, IN_CHAIN, OUT_NATURAL, 0);
-    j2.chunk_stride = L.kt2 + L.tpc;
+    j2.chunk_stride = block_tiles;
     jobs.job[jobs.n++] = j2;
     PackJob j3 = weight_job(W3, dst + L.chunks, bf16, p.hidden, out, 1, L.kt2, IN_CHAIN, out_map, gk);
     j3.group = L.tpc;
-    j3.chunk_stride = L.kt2 + L.tpc;
-    j3.slot_base = L.kt2;
+    j3.chunk_stride = block_tiles;
+    j3.slot_base = L.kt2 + L.tpc;  // own chunk's copy
     jobs.job[jobs.n++] = j3;
+    if (L.nuc > 1) {
+      PackJob j3b = j3;            // copy for the following chunk's stage: tiles of chunks 0 .. nuc-2
+      j3b.dst = dst + L.chunks + L.chunk_bytes;
+      j3b.kt = L.kt2 - L.tpc;
+      j3b.slot_base = L.kt2;
+      jobs.job[jobs.n++] = j3b;
+    }
     jobs.job[jobs.n++] = bias_job(b1, dst + L.b1, bf16, p.hidden, L.nuc, OUT_NATURAL, 0);
     jobs.job[jobs.n++] = bias_job(b2, dst + L.b2, bf16, p.hidden, L.nuc, OUT_NATURAL, 0);
     jobs.job[jobs.n++] = bias_job(b3, dst + L.b3, bf16, out, 1, out_map, gk);

@@ -22,9 +22,12 @@
 // Inputs or outputs beyond the real sizes hold zeros.
 //
 // One network = [layer-1 tiles (uc major, kt minor)], then per 32-unit chunk uc
-// of layer 2 one "chunk block" = [its kt2 layer-2 tiles][the kt2/nuc layer-3
-// tiles that consume that chunk's outputs], then [b1 (H floats)] [b2 (H)]
-// [b3 (32, physical order)].  The rollout kernels stream the weights through LDS
+// of layer 2 one "chunk block" = [its kt2 layer-2 tiles][the tpc = kt2/nuc
+// layer-3 tiles that consume the outputs of chunk uc-1 (zeros for uc = 0)][the
+// tpc layer-3 tiles that consume the outputs of chunk uc], then [b1 (H floats)]
+// [b2 (H)] [b3 (32, physical order)].  (The kernels activate chunk uc-1 while the
+// MFMAs of chunk uc run, so a stage carries the layer-3 tiles of the chunk before
+// it; the copy for chunk uc itself is used by the last stage only.)  The rollout kernels stream the weights through LDS
 // in stages: the layer-1 tiles are one stage, every chunk block is one stage, so
 // each stage is one contiguous byte range.
 #pragma once
@@ -43,7 +46,7 @@ struct NetLayout {
   int kt1, kt2, nuc, tpc;      // tiles per chunk in layer 1 / layer 2; chunks of 32 units; layer-3 tiles per chunk
   size_t w1;                   // byte offset of the layer-1 tiles
   size_t chunks;               // byte offset of chunk block 0
-  size_t chunk_bytes;          // size of one chunk block: (kt2 + tpc) KiB
+  size_t chunk_bytes;          // size of one chunk block: (kt2 + 2 tpc) KiB
   size_t b1, b2, b3;           // byte offsets of the bias arrays
   size_t bytes;                // size of one packed network
 };
@@ -60,7 +63,7 @@ __host__ __device__ inline NetLayout net_layout(int in_dim, int hidden, bool bf1
   L.tpc = L.kt2 / L.nuc;
   L.w1 = 0;
   L.chunks = L.w1 + (size_t)L.nuc * L.kt1 * 1024;
-  L.chunk_bytes = (size_t)(L.kt2 + L.tpc) * 1024;
+  L.chunk_bytes = (size_t)(L.kt2 + 2 * L.tpc) * 1024;
   L.b1 = L.chunks + (size_t)L.nuc * L.chunk_bytes;
   L.b2 = L.b1 + (size_t)hidden * 4;
   L.b3 = L.b2 + (size_t)hidden * 4;
@@ -87,7 +90,7 @@ struct PackJob {
 
 struct PackJobs {
   int n;
-  PackJob job[14];
+  PackJob job[16];
 };
 
 }  // namespace msrl

@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int BIAS = 2 * H + 32;
   static_assert(EPW >= 1, "a wave must hold at least one env");
 
-  __shared__ __attribute__((aligned(16))) u32x4 s_w[2 * Stream::BUF_SLOTS];
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[Stream::NBUF * Stream::BUF_SLOTS];
   __shared__ __attribute__((aligned(16))) float s_bias[2 * BIAS];
   __shared__ float2 s_tab[WAVES][2 * ROWS];  // [0,ROWS) landmarks, [ROWS,2ROWS) agents
   __shared__ float s_part[WAVES][2 * ROWS];
@@ -113,6 +113,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   ws.wave = wave;
   ws.lane = lane;
   ws.issue(0, 0);
+  ws.issue(1, 1);
   load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
 
   // envs of this workgroup: [blk0, blk0 + envs_per_block); of this wave: EPW of them
@@ -190,7 +191,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             f[2 * pi + 1] = o.y;
           }
           const int f0 = 16 * kt + 8 * h;
+#ifdef MSRL_X_NO_OBS_STORE
+          if (false) {
+#else
           if (valid[q]) {
+#endif
             if constexpr (D % 4 == 0) {
               if (f0 + 4 <= D) *(float4*)(orow + f0) = make_float4(f[0], f[1], f[2], f[3]);
               if (f0 + 8 <= D) *(float4*)(orow + f0 + 4) = make_float4(f[4], f[5], f[6], f[7]);
@@ -223,18 +228,23 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       for (int net = 0; net < 2; ++net) {
         f32x16(&out)[NB] = net == 0 ? out_p : out_v;
         const float* bias = s_bias + net * BIAS;
-        ws.wait();
-        ws.issue(net * Net::STAGES + 1, (gs + 1) & 1);
-        Net::layer1(ws.tiles(gs & 1), bias, x, h1, h);
+        ws.wait_older();
+        ws.issue(net * Net::STAGES + 2, (gs + 2) % 3);  // stage g + 2 -> buffer (g + 2) % 3
+        Net::layer1(ws.tiles(gs % 3), bias, x, h1, h);
         ++gs;
         Net::out_init(bias + 2 * H, out, h);
+        f32x16 acc[NB];
 #pragma unroll 1
         for (int uc = 0; uc < Net::NUC; ++uc) {
-          ws.wait();
-          const int next = net * Net::STAGES + 2 + uc;  // stage after this one, cyclic over the step
-          const bool last = net == 1 && uc == Net::NUC - 1;
-          if (!(last && t == a.T)) ws.issue(last ? 0 : next, (gs + 1) & 1);
-          Net::layer2_chunk(ws.tiles(gs & 1), bias + H, uc, h1, out, h);
+          ws.wait_older();
+          int next = net * Net::STAGES + 3 + uc;  // two stages ahead, cyclic over the step
+          if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
+          ws.issue(next, (gs + 2) % 3);
+          if (uc == 0)
+            Net::template layer2_chunk<false>(ws.tiles(gs % 3), bias + H, uc, h1, acc, out, h);
+          else
+            Net::template layer2_chunk<true>(ws.tiles(gs % 3), bias + H, uc, h1, acc, out, h);
+          if (uc == Net::NUC - 1) Net::layer2_drain(ws.tiles(gs % 3), acc, out);
           ++gs;
         }
       }
@@ -243,6 +253,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     for (int q = 0; q < NB; ++q)
       if (h == 0 && valid[q]) a.values[(size_t)t * a.M + m0 + row[q]] = out_v[q][0];
     if (t == a.T) break;
+#ifdef MSRL_X_NO_ENV
+    continue;
+#endif
 
     // ---------------- sampling, physics
     float rew_term[NB];
@@ -323,6 +336,8 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     wave_lds_sync();
   }
 
+  ws.wait_all();  // copies issued ahead for stages that will not run
+
   // ---------------- write the env state back
 #pragma unroll
   for (int q = 0; q < NB; ++q) {
@@ -353,7 +368,7 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   constexpr int BIAS = 2 * H + 32;
   static_assert(D <= 32 && K <= 8, "one MFMA chunk of state, one tile of action");
 
-  __shared__ __attribute__((aligned(16))) u32x4 s_w[2 * Stream::BUF_SLOTS];
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[Stream::NBUF * Stream::BUF_SLOTS];
   __shared__ __attribute__((aligned(16))) float s_bias[2 * BIAS];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -368,6 +383,7 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   ws.wave = wave;
   ws.lane = lane;
   ws.issue(0, 0);
+  ws.issue(1, 1);
   load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
 
   const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
@@ -409,18 +425,23 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
       for (int net = 0; net < 2; ++net) {
         f32x16(&out)[1] = net == 0 ? out_p : out_v;
         const float* bias = s_bias + net * BIAS;
-        ws.wait();
-        ws.issue(net * Net::STAGES + 1, (gs + 1) & 1);
-        Net::layer1(ws.tiles(gs & 1), bias, s, h1, h);
+        ws.wait_older();
+        ws.issue(net * Net::STAGES + 2, (gs + 2) % 3);  // stage g + 2 -> buffer (g + 2) % 3
+        Net::layer1(ws.tiles(gs % 3), bias, s, h1, h);
         ++gs;
         Net::out_init(bias + 2 * H, out, h);
+        f32x16 acc[1];
 #pragma unroll 1
         for (int uc = 0; uc < Net::NUC; ++uc) {
-          ws.wait();
-          const int next = net * Net::STAGES + 2 + uc;
-          const bool last = net == 1 && uc == Net::NUC - 1;
-          if (!(last && t == a.T)) ws.issue(last ? 0 : next, (gs + 1) & 1);
-          Net::layer2_chunk(ws.tiles(gs & 1), bias + H, uc, h1, out, h);
+          ws.wait_older();
+          int next = net * Net::STAGES + 3 + uc;  // two stages ahead, cyclic over the step
+          if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
+          ws.issue(next, (gs + 2) % 3);
+          if (uc == 0)
+            Net::template layer2_chunk<false>(ws.tiles(gs % 3), bias + H, uc, h1, acc, out, h);
+          else
+            Net::template layer2_chunk<true>(ws.tiles(gs % 3), bias + H, uc, h1, acc, out, h);
+          if (uc == Net::NUC - 1) Net::layer2_drain(ws.tiles(gs % 3), acc, out);
           ++gs;
         }
       }
@@ -485,6 +506,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
     tau = done ? 0 : tau + 1;
     if (done) episode += 1;
   }
+
+  ws.wait_all();  // copies issued ahead for stages that will not run
 
   if (valid) {
 #pragma unroll
