@@ -68,9 +68,6 @@ __device__ __forceinline__ void normals4(uint32_t seed_lo, uint32_t seed_hi, uin
 // tanh(x) = 1 - 2 / (1 + e^(2x)) on the hardware exp2 / rcp units; absolute
 // error about 2e-7, saturates cleanly to +-1 for large |x|.
 __device__ __forceinline__ float fast_tanh(float x) {
-#ifdef MSRL_X_NO_TANH
-  return x * 0.5f;
-#endif
   const float e = __builtin_amdgcn_exp2f(x * 2.8853900817779268f);
   return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
 }

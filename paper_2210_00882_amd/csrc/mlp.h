@@ -2,13 +2,14 @@
 //
 // Every layer is computed transposed (units x rows), so a layer's accumulators
 //   lane (n = lane % 32, h = lane / 32), register r  <->  row n, unit 32*uc + 8*(r/4) + 4*h + r%4
-// are, after bias + tanh (+ rounding to bf16), exactly the B operand of the next
+// are, after tanh (+ rounding to bf16), exactly the B operand of the next
 // layer's MFMAs: activations never leave the register file.  The weights are
-// the A operand; the workgroup streams them through LDS in stages (the layer-1
-// tiles, then one block per 32-unit chunk of layer 2 together with the layer-3
-// tiles of that chunk and of the one before; see packed.h), and every wave of
-// the workgroup reads the same stage.  Layer 3 is accumulated as the layer-2
-// chunks complete, so h2 is consumed as soon as it is produced.
+// the A operand and come from LDS: the layer-1 tiles stay resident, the layer-2
+// and layer-3 tiles stream through an LDS window in one stage per 32-unit chunk
+// (packed.h), and every wave of the workgroup reads the same stage.  Biases are
+// one more input of the contraction (the constant 1), so an accumulator starts
+// at zero.  Layer 3 is accumulated as the layer-2 chunks complete, so h2 is
+// consumed as soon as it is produced.
 #pragma once
 #include "dev_common.h"
 #include "packed.h"
@@ -29,21 +30,24 @@ template <> struct Operand<true> {
   typedef bf16x8 T;                    // one B operand: 8 k-slots of one MFMA
   static constexpr int PER_TILE = 1;   // MFMAs (B operands) per weight tile
   static constexpr int PER_CHUNK = 2;  // B operands made from one 32-unit accumulator
+  // B operand of a bias tile: the constant 1 at input slot (h = 0, s = 0)
+  static __device__ __forceinline__ T one(int h) {
+    T v = {0, 0, 0, 0, 0, 0, 0, 0};
+    v[0] = (__bf16)(h == 0 ? 1.0f : 0.0f);
+    return v;
+  }
 };
 template <> struct Operand<false> {
   typedef float T;
   static constexpr int PER_TILE = 4;
   static constexpr int PER_CHUNK = 16;
+  static __device__ __forceinline__ T one(int h) { return h == 0 ? 1.0f : 0.0f; }
 };
 
 // acc += tile * operands, for one weight tile held as raw 16 bytes per lane
 template <bool BF16>
 __device__ __forceinline__ void mma_tile(const u32x4& raw, const typename Operand<BF16>::T* b,
                                          f32x16& acc) {
-#ifdef MSRL_X_NO_MFMA
-  acc[0] += __builtin_bit_cast(f32x4, raw)[0];
-  return;
-#endif
   if constexpr (BF16) {
     acc = mma(__builtin_bit_cast(bf16x8, raw), b[0], acc);
   } else {
@@ -53,12 +57,29 @@ __device__ __forceinline__ void mma_tile(const u32x4& raw, const typename Operan
   }
 }
 
-// bias for the 16 accumulator registers of chunk uc: units 32uc + 8b + 4h + c
-__device__ __forceinline__ f32x16 bias_init(const float* lds_bias, int uc, int h) {
+// acc += bias tile * 1: only input slot (h = 0, first k) of the tile is populated
+template <bool BF16>
+__device__ __forceinline__ void mma_bias_tile(const u32x4& raw, const typename Operand<BF16>::T& one,
+                                              f32x16& acc) {
+  if constexpr (BF16)
+    acc = mma(__builtin_bit_cast(bf16x8, raw), one, acc);
+  else
+    acc = mma(__builtin_bit_cast(f32x4, raw)[0], one, acc);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.0f;
+  return z;
+}
+
+// the 16 accumulator registers of the output chunk from a bias vector in LDS (units 8b + 4h + c)
+__device__ __forceinline__ f32x16 bias_init(const float* lds_bias, int h) {
   f32x16 acc;
 #pragma unroll
   for (int b = 0; b < 4; ++b) {
-    const f32x4 v = *(const f32x4*)(lds_bias + 32 * uc + 8 * b + 4 * h);
+    const f32x4 v = *(const f32x4*)(lds_bias + 8 * b + 4 * h);
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[4 * b + c] = v[c];
   }
@@ -73,8 +94,7 @@ __device__ __forceinline__ void pin(float& v) { asm volatile("" : "+v"(v)); }
 __device__ __forceinline__ void pin(f32x16& v) { asm volatile("" : "+v"(v)); }
 
 // tanh of accumulator registers [r0, r1) of a 32-unit chunk into a scratch array.  When pinned,
-// the whole group is computed between two pins, so its independent chains can be interleaved
-// with each other but stay between the neighbouring MFMAs.
+// the whole group is computed between two pins, so it stays between the neighbouring MFMAs.
 __device__ __forceinline__ void tanh_range(const f32x16& acc, float (&t)[16], int r0, int r1, bool pinned) {
   float v[16];
 #pragma unroll
@@ -108,68 +128,51 @@ __device__ __forceinline__ void to_operands(const float (&t)[16], typename Opera
   }
 }
 
-// Software pipeline inside a wave: while the MFMAs of chunk c run, the VALU
-// applies bias-free tanh to the accumulators of chunk c-1 (the bias is the
-// accumulator's initial value), so both pipes are busy from one instruction
-// stream.  In a layer-2 stage the layer-3 MFMAs of chunk c-1 follow.
+// Software pipeline inside a wave: while the MFMAs of chunk c run, the VALU applies tanh to the
+// accumulators of chunk c-1, so both pipes are busy from one instruction stream.  In a layer-2
+// stage the layer-3 MFMAs of chunk c-1 follow.
 template <int H, bool BF16, int NB, int KT1>
 struct Mlp {
-#ifdef MSRL_X_NO_TILE_READ
-#define TILE_AT(p, i) (u32x4{(uint32_t)(i), 1u, 2u, 3u})
-#else
-#define TILE_AT(p, i) ((p)[(i) * 64])
-#endif
   typedef typename Operand<BF16>::T Op;
   static constexpr int PT = Operand<BF16>::PER_TILE;
   static constexpr int PC = Operand<BF16>::PER_CHUNK;
   static constexpr int NUC = H / 32;
   static constexpr int KT2 = BF16 ? H / 16 : H / 8;
-  static constexpr int TPC = KT2 / NUC;              // layer-3 tiles fed by one 32-unit chunk
-  static constexpr int L1_TILES = NUC * KT1;         // stage 0 of a network
-  static constexpr int CHUNK_TILES = KT2 + 2 * TPC;  // stages 1..NUC: layer-2 tiles of chunk c,
-                                                     // layer-3 tiles of chunk c-1, of chunk c
-  static constexpr int STAGES = 1 + NUC;
-  static constexpr int MAX_STAGE_TILES = L1_TILES > CHUNK_TILES ? L1_TILES : CHUNK_TILES;
+  static constexpr int TPC = KT2 / NUC;                  // layer-3 tiles fed by one 32-unit chunk
+  static constexpr int L1_TILES = NUC * KT1;             // resident
+  static constexpr int CHUNK_TILES = KT2 + 1 + 2 * TPC;  // one stage: layer-2 tiles of chunk c, its bias
+                                                         // tile, layer-3 tiles of chunk c-1, of chunk c
+  static constexpr int L3_PREV = KT2 + 1, L3_OWN = KT2 + 1 + TPC;
   static constexpr int G = 4;  // LDS reads run G tiles ahead of the MFMAs that consume them
+
   // tanh of the previous chunk, spread over the NT tiles of the current one
-#ifndef MSRL_GS
-#define MSRL_GS 1
-#endif
-  // tiles per tanh group: after every GS-th tile the tanh of GS tiles' share of values is issued
-  static constexpr int GS = MSRL_GS;
   template <int NT>
   __device__ static __forceinline__ void tanh_slice(const f32x16 (&prev)[NB], float (&t)[NB][16], int kt) {
-    constexpr int gs = GS < NT ? GS : NT;
-    if (kt % gs != gs - 1) return;
-    const int k0 = kt - (gs - 1);
-    const int r0 = k0 * 16 / NT, r1 = (kt + 1) * 16 / NT;
+    const int r0 = kt * 16 / NT, r1 = (kt + 1) * 16 / NT;
 #pragma unroll
     for (int q = 0; q < NB; ++q) tanh_range(prev[q], t[q], r0, r1, true);
   }
 
-  // tiles: this lane's slot of tile 0 of the stage in LDS (tile t is at tiles[64 t]).
-  __device__ static __forceinline__ void layer1(const u32x4* tiles, const float* lds_b1,
-                                                const Op (&x)[NB][KT1 * PT],
-                                                Op (&h1)[NB][KT2 * PT], int h) {
+  // Layer 1.  tiles: this lane's slot of tile 0 in LDS (tile t is at tiles[64 t]); x holds the
+  // observation with the constant 1 at input index in_dim.
+  __device__ static __forceinline__ void layer1(const u32x4* tiles, const Op (&x)[NB][KT1 * PT],
+                                                Op (&h1)[NB][KT2 * PT]) {
     u32x4 ring[G];
 #pragma unroll
-    for (int i = 0; i < G && i < L1_TILES; ++i) ring[i] = TILE_AT(tiles, i);
+    for (int i = 0; i < G && i < L1_TILES; ++i) ring[i] = tiles[i * 64];
     f32x16 prev[NB];
 #pragma unroll
     for (int uc = 0; uc <= NUC; ++uc) {
       f32x16 acc[NB];
       float t[NB][16];
-      if (uc < NUC) {
-        const f32x16 b = bias_init(lds_b1, uc, h);
 #pragma unroll
-        for (int q = 0; q < NB; ++q) acc[q] = b;
-      }
+      for (int q = 0; q < NB; ++q) acc[q] = zero16();
 #pragma unroll
       for (int kt = 0; kt < KT1; ++kt) {
         if (uc < NUC) {
           const int idx = uc * KT1 + kt;
           const u32x4 raw = ring[idx % G];
-          if (idx + G < L1_TILES) ring[idx % G] = TILE_AT(tiles, idx + G);
+          if (idx + G < L1_TILES) ring[idx % G] = tiles[(idx + G) * 64];
 #pragma unroll
           for (int q = 0; q < NB; ++q) {
             mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
@@ -187,33 +190,25 @@ struct Mlp {
     }
   }
 
-  __device__ static __forceinline__ void out_init(const float* lds_b3, f32x16 (&out)[NB], int h) {
-    const f32x16 b = bias_init(lds_b3, 0, h);
-#pragma unroll
-    for (int q = 0; q < NB; ++q) out[q] = b;
-  }
-
-  // Stage of chunk uc: acc <- layer-2 pre-activations of chunk uc; if PIPE, `acc` holds
-  // those of chunk uc-1 on entry, which get tanh and feed layer 3 meanwhile.
+  // Stage of chunk uc: acc <- layer-2 pre-activations of chunk uc; if PIPE, `acc` holds those of
+  // chunk uc-1 on entry, which get tanh and feed layer 3 meanwhile.
   template <bool PIPE>
-  __device__ static __forceinline__ void layer2_chunk(const u32x4* tiles, const float* lds_b2, int uc,
-                                                      const Op (&h1)[NB][KT2 * PT],
+  __device__ static __forceinline__ void layer2_chunk(const u32x4* tiles, const Op (&h1)[NB][KT2 * PT],
                                                       f32x16 (&acc)[NB], f32x16 (&out)[NB], int h) {
     u32x4 ring[G];
 #pragma unroll
-    for (int i = 0; i < G; ++i) ring[i] = TILE_AT(tiles, i);
+    for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
     f32x16 prev[NB];
     float t[NB][16];
-    const f32x16 b = bias_init(lds_b2, uc, h);
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
       prev[q] = acc[q];
-      acc[q] = b;
+      acc[q] = zero16();
     }
 #pragma unroll
     for (int kt = 0; kt < KT2; ++kt) {
       const u32x4 raw = ring[kt % G];
-      if (kt + G < KT2 + TPC) ring[kt % G] = TILE_AT(tiles, kt + G);
+      if (kt + G < L3_PREV + TPC) ring[kt % G] = tiles[(kt + G) * 64];
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
         mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
@@ -221,13 +216,20 @@ struct Mlp {
       }
       if (PIPE) tanh_slice<KT2>(prev, t, kt);
     }
+    {
+      const Op one = Operand<BF16>::one(h);
+      const u32x4 raw = ring[KT2 % G];
+      if (KT2 + G < L3_PREV + TPC) ring[KT2 % G] = tiles[(KT2 + G) * 64];
+#pragma unroll
+      for (int q = 0; q < NB; ++q) mma_bias_tile<BF16>(raw, one, acc[q]);
+    }
     if (PIPE) {
       Op h2[NB][PC];
 #pragma unroll
       for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], h2[q]);
 #pragma unroll
       for (int i = 0; i < TPC; ++i) {
-        const u32x4 raw = ring[(KT2 + i) % G];
+        const u32x4 raw = ring[(L3_PREV + i) % G];
 #pragma unroll
         for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h2[q][i * PT], out[q]);
       }
@@ -239,7 +241,7 @@ struct Mlp {
                                                       f32x16 (&out)[NB]) {
     u32x4 w3[TPC];
 #pragma unroll
-    for (int i = 0; i < TPC; ++i) w3[i] = TILE_AT(tiles, KT2 + TPC + i);
+    for (int i = 0; i < TPC; ++i) w3[i] = tiles[(L3_OWN + i) * 64];
     float t[NB][16];
     Op h2[NB][PC];
 #pragma unroll
@@ -255,71 +257,57 @@ struct Mlp {
   }
 };
 
-// Weight stream of a workgroup: stage g of the endless sequence (policy stages,
-// value stages, policy stages, ...) lives in LDS buffer g % 3 and is copied there
-// two stages ahead by direct global->LDS loads (no registers involved).
+// Weight stream of a workgroup: stage g of the endless sequence (policy chunk
+// blocks, value chunk blocks, policy chunk blocks, ...) lives in LDS buffer
+// g % NBUF and is copied there NBUF - 1 stages ahead by direct global->LDS loads
+// (no registers involved).
 //
 // The copy instruction is issued from inline assembly on purpose: issued through
 // the compiler builtin, every later LDS read of the *resident* stage would be
 // made to wait for the copies still in flight (the compiler cannot tell the
 // buffers apart), which serialises the L2 latency with the compute.  The price
 // is that the wait is written by hand: each wave issues exactly PER_WAVE copies
-// per stage, loads complete in order, so "at most PER_WAVE vector-memory
-// operations outstanding" means the copies of the stage before the newest one
+// per stage, loads complete in order, so "at most (NBUF - 2) * PER_WAVE vector
+// memory operations outstanding" means the copies of the stage about to be used
 // have landed.  Vector-memory operations the compiler issues itself only add to
 // the outstanding count, which makes the wait longer, never shorter.
-template <class Net, int WAVES>
+template <class Net, int WAVES, int NBUF>
 struct WeightStream {
-  static constexpr int STAGES_PER_STEP = 2 * Net::STAGES;
-  static constexpr int PER_WAVE = (Net::MAX_STAGE_TILES + WAVES - 1) / WAVES;  // copies per wave and stage
-  static constexpr int BUF_TILES = PER_WAVE * WAVES;                            // incl. padding tiles
-  static constexpr int BUF_SLOTS = BUF_TILES * 64;                              // u32x4 slots per buffer
-  static constexpr int NBUF = 3;
-  static_assert(PER_WAVE <= 15, "the hand-written wait encodes the count in 4 bits");
+  static constexpr int STAGES_PER_STEP = 2 * Net::NUC;
+  static constexpr int PER_WAVE = (Net::CHUNK_TILES + WAVES - 1) / WAVES;  // copies per wave and stage
+  static constexpr int BUF_TILES = PER_WAVE * WAVES;                        // incl. padding tiles
+  static constexpr int BUF_SLOTS = BUF_TILES * 64;                          // u32x4 slots per buffer
+  static constexpr int AHEAD = NBUF - 1;
+  static_assert(NBUF >= 2 && (NBUF - 2) * PER_WAVE <= 15, "the hand-written wait encodes the count in 4 bits");
   u32x4* lds;  // NBUF * BUF_SLOTS slots
   const uint8_t* packed;
   size_t net_bytes, chunks_off, chunk_bytes;
   int wave, lane;
 
-  // start copying stage s (0 .. STAGES_PER_STEP-1) into buffer `buf`
-  mutable int x_issued = 0;
+  // start copying stage s (0 .. STAGES_PER_STEP-1: chunk block s % NUC of network s / NUC) into buffer `buf`
   __device__ __forceinline__ void issue(int s, int buf) const {
-#ifdef MSRL_X_NO_RELOAD
-    if (x_issued >= MSRL_X_NO_RELOAD) return;
-    ++x_issued;
-#endif
-    const int net = s >= Net::STAGES ? 1 : 0;
-    const int ls = s - net * Net::STAGES;
-    const uint8_t* src = packed + (size_t)net * net_bytes +
-                         (ls == 0 ? 0 : chunks_off + (size_t)(ls - 1) * chunk_bytes);
-    const int n_tiles = ls == 0 ? Net::L1_TILES : Net::CHUNK_TILES;
+    const int net = s >= Net::NUC ? 1 : 0;
+    const uint8_t* src = packed + (size_t)net * net_bytes + chunks_off + (size_t)(s - net * Net::NUC) * chunk_bytes;
     typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
     const uint32_t base = (uint32_t)(uintptr_t)(lds_u32x4*)(lds + buf * BUF_SLOTS);
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
       const int t = wave + i * WAVES;
       // a wave with no tile left repeats tile 0 into its padding tile: every wave issues PER_WAVE copies
-      const uint8_t* g = src + (size_t)(t < n_tiles ? t : 0) * 1024 + (size_t)lane * 16;
+      const uint8_t* g = src + (size_t)(t < Net::CHUNK_TILES ? t : 0) * 1024 + (size_t)lane * 16;
       const uint32_t m0 = __builtin_amdgcn_readfirstlane(base + (uint32_t)t * 1024u);
       asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory", "m0");
     }
   }
-  // wait until only the newest stage's copies may be outstanding, then for every wave
-  __device__ __forceinline__ void wait_older() const {
-    // s_waitcnt vmcnt(PER_WAVE): simm16 = vmcnt[3:0] | expcnt(7) << 4 | lgkmcnt(15) << 8
-#ifndef MSRL_X_NO_WAIT
-    __builtin_amdgcn_s_waitcnt(0x0F70 | PER_WAVE);
-#endif
-    sync();
+  // wait until the oldest stage in flight has landed, then for every wave of the workgroup
+  __device__ __forceinline__ void wait_oldest() const {
+    // s_waitcnt vmcnt(n): simm16 = vmcnt[3:0] | expcnt(7) << 4 | lgkmcnt(15) << 8
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((NBUF - 2) * PER_WAVE));
+    __syncthreads();
   }
   __device__ __forceinline__ void wait_all() const {
     __builtin_amdgcn_s_waitcnt(0x0F70);
-    sync();
-  }
-  __device__ __forceinline__ void sync() const {
-#ifndef MSRL_X_NO_BARRIER
     __syncthreads();
-#endif
   }
   __device__ __forceinline__ const u32x4* tiles(int buf) const { return lds + buf * BUF_SLOTS + lane; }
 };

@@ -158,27 +158,29 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     const uint8_t* b2 = W2 + (size_t)p.hidden * p.hidden * esz;
     const uint8_t* W3 = b2 + (size_t)p.hidden * esz;
     const uint8_t* b3 = W3 + (size_t)p.hidden * out * esz;
-    jobs.job[jobs.n++] = weight_job(W1, dst + L.w1, bf16, p.in_dim, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
-    // chunk block uc: kt2 layer-2 tiles of chunk uc, the tpc layer-3 tiles fed by chunk uc-1, the
-    // tpc layer-3 tiles fed by chunk uc
-    const int block_tiles = L.kt2 + 2 * L.tpc;
-    PackJob j2 = weight_job(W2, dst + L.chunks, bf16, p.hidden, p.hidden, L.nuc, L.kt2, IN_CHAIN, OUT_NATURAL, 0);
-    j2.chunk_stride = block_tiles;
+    PackJob j1 = weight_job(W1, dst + L.w1, bf16, p.in_dim, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
+    j1.bias = b1;  // the bias is input number in_dim; the kernels feed 1 there
+    j1.bias_index = p.in_dim;
+    jobs.job[jobs.n++] = j1;
+    // chunk block uc: kt2 layer-2 tiles of chunk uc, its bias tile, the tpc layer-3 tiles fed by
+    // chunk uc-1, the tpc layer-3 tiles fed by chunk uc
+    PackJob j2 = weight_job(W2, dst + L.chunks, bf16, p.hidden, p.hidden, L.nuc, L.kt2 + 1, IN_CHAIN, OUT_NATURAL, 0);
+    j2.bias = b2;
+    j2.bias_index = p.hidden;
+    j2.chunk_stride = L.chunk_tiles;
     jobs.job[jobs.n++] = j2;
     PackJob j3 = weight_job(W3, dst + L.chunks, bf16, p.hidden, out, 1, L.kt2, IN_CHAIN, out_map, gk);
     j3.group = L.tpc;
-    j3.chunk_stride = block_tiles;
-    j3.slot_base = L.kt2 + L.tpc;  // own chunk's copy
+    j3.chunk_stride = L.chunk_tiles;
+    j3.slot_base = L.kt2 + 1 + L.tpc;  // own chunk's copy
     jobs.job[jobs.n++] = j3;
     if (L.nuc > 1) {
-      PackJob j3b = j3;            // copy for the following chunk's stage: tiles of chunks 0 .. nuc-2
+      PackJob j3b = j3;               // copy for the following chunk's stage: tiles of chunks 0 .. nuc-2
       j3b.dst = dst + L.chunks + L.chunk_bytes;
       j3b.kt = L.kt2 - L.tpc;
-      j3b.slot_base = L.kt2;
+      j3b.slot_base = L.kt2 + 1;
       jobs.job[jobs.n++] = j3b;
     }
-    jobs.job[jobs.n++] = bias_job(b1, dst + L.b1, bf16, p.hidden, L.nuc, OUT_NATURAL, 0);
-    jobs.job[jobs.n++] = bias_job(b2, dst + L.b2, bf16, p.hidden, L.nuc, OUT_NATURAL, 0);
     jobs.job[jobs.n++] = bias_job(b3, dst + L.b3, bf16, out, 1, out_map, gk);
     src = b3 + (size_t)out * esz;
   }
@@ -340,7 +342,7 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   INIT_TRY(hipMemset(st->packed, 0, 2 * st->layout.bytes));
   if (env->kind == MSRL_ENV_LINGAUSS) {
     const int D = env->obs_dim, K = env->act_dim;
-    const int ktA = tiles_for_inputs(D, false), ktB = tiles_for_inputs(K, false);
+    const int ktA = tiles_for_inputs(D + 1, false), ktB = tiles_for_inputs(K, false);  // as the kernel counts them
     INIT_TRY(hipMalloc((void**)&st->dyn_src, ((size_t)D * D + (size_t)D * K) * sizeof(float)));
     INIT_TRY(hipMalloc((void**)&st->dyn, (size_t)(ktA + ktB) * 1024));
     INIT_TRY(hipMemcpy(st->dyn_src, env->A, (size_t)D * D * sizeof(float), hipMemcpyHostToDevice));

@@ -26,12 +26,12 @@ __device__ __forceinline__ int out_index(int map, int gauss_k, int phys, int n_o
   return phys < n_out ? phys : -1;
 }
 
-__device__ __forceinline__ float load_src(const PackJob& j, int idx) {
-  if (j.src_bf16) {
-    const uint32_t b = (uint32_t)((const uint16_t*)j.src)[idx] << 16;
+__device__ __forceinline__ float load_src(const void* src, int bf16, int idx) {
+  if (bf16) {
+    const uint32_t b = (uint32_t)((const uint16_t*)src)[idx] << 16;
     return __uint_as_float(b);
   }
-  return ((const float*)j.src)[idx];
+  return ((const float*)src)[idx];
 }
 
 // grid: (blocks over work items, job); one thread per (tile, lane) or per bias slot.
@@ -41,7 +41,7 @@ __global__ void pack_kernel(PackJobs jobs) {
   if (j.is_bias) {
     if (tid >= 32 * j.nuc) return;
     const int o = out_index(j.out_map, j.gauss_k, tid, j.n_out);
-    ((float*)j.dst)[tid] = o >= 0 ? load_src(j, o) : 0.0f;
+    ((float*)j.dst)[tid] = o >= 0 ? load_src(j.src, j.src_bf16, o) : 0.0f;
     return;
   }
   const int n_tiles = j.nuc * j.kt;
@@ -57,7 +57,10 @@ __global__ void pack_kernel(PackJobs jobs) {
   for (int e = 0; e < ne; ++e) {
     const int i = in_index(j.in_map, bf16, kt, h, e);
     v[e] = 0.0f;
-    if (o >= 0 && i < j.n_in) v[e] = load_src(j, j.src_out_major ? o * j.n_in + i : i * j.n_out + o);
+    if (o >= 0 && i < j.n_in)
+      v[e] = load_src(j.src, j.src_bf16, j.src_out_major ? o * j.n_in + i : i * j.n_out + o);
+    else if (o >= 0 && j.bias && i == j.bias_index)
+      v[e] = load_src(j.bias, j.src_bf16, o);
   }
   if (bf16) {
     // values are bfloat16-representable already: keep the top 16 bits

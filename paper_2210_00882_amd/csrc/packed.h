@@ -21,15 +21,23 @@
 //   pairs   f32  : 8*kt + 2*j + h                   (particle observation, layer 1)
 // Inputs or outputs beyond the real sizes hold zeros.
 //
-// One network = [layer-1 tiles (uc major, kt minor)], then per 32-unit chunk uc
-// of layer 2 one "chunk block" = [its kt2 layer-2 tiles][the tpc = kt2/nuc
-// layer-3 tiles that consume the outputs of chunk uc-1 (zeros for uc = 0)][the
-// tpc layer-3 tiles that consume the outputs of chunk uc], then [b1 (H floats)]
-// [b2 (H)] [b3 (32, physical order)].  (The kernels activate chunk uc-1 while the
-// MFMAs of chunk uc run, so a stage carries the layer-3 tiles of the chunk before
-// it; the copy for chunk uc itself is used by the last stage only.)  The rollout kernels stream the weights through LDS
-// in stages: the layer-1 tiles are one stage, every chunk block is one stage, so
-// each stage is one contiguous byte range.
+// Biases of layers 1 and 2 ride along as one more input: input index n_in holds
+// the bias, and the kernels feed the constant 1 at that index.  (A bias read
+// from LDS costs as much LDS bandwidth per chunk as four weight tiles; one more
+// MFMA is cheaper.)  For layer 1 the index falls into the padding of the last
+// tile when there is room, for layer 2 it opens one extra tile.
+//
+// One network =
+//   [layer-1 tiles (uc major, kt minor), nuc * kt1 tiles, kt1 = tiles(in_dim + 1)]
+//   [chunk block uc = 0 .. nuc-1], each kt2 + 1 + 2 tpc tiles:
+//       kt2 layer-2 tiles of the 32-unit chunk uc, 1 bias tile of chunk uc,
+//       tpc = kt2/nuc layer-3 tiles that consume the outputs of chunk uc-1
+//       (zeros for uc = 0), tpc layer-3 tiles that consume the outputs of chunk uc
+//   [b3: 32 floats in physical output order]
+// The kernels keep the layer-1 tiles resident in LDS and stream the chunk blocks
+// through an LDS window, one block per stage; they activate chunk uc-1 while the
+// MFMAs of chunk uc run, which is why a block carries the layer-3 tiles of the
+// chunk before it (the copy for chunk uc itself is used after the last block).
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -43,12 +51,13 @@ enum InMap : int { IN_CHAIN = 0, IN_LINEAR16 = 1, IN_PAIRS = 2 };
 enum OutMap : int { OUT_NATURAL = 0, OUT_GAUSS = 1 };
 
 struct NetLayout {
-  int kt1, kt2, nuc, tpc;      // tiles per chunk in layer 1 / layer 2; chunks of 32 units; layer-3 tiles per chunk
-  size_t w1;                   // byte offset of the layer-1 tiles
-  size_t chunks;               // byte offset of chunk block 0
-  size_t chunk_bytes;          // size of one chunk block: (kt2 + 2 tpc) KiB
-  size_t b1, b2, b3;           // byte offsets of the bias arrays
-  size_t bytes;                // size of one packed network
+  int kt1, kt2, nuc, tpc;  // tiles per chunk in layer 1 / layer 2; chunks of 32 units; layer-3 tiles per chunk
+  int chunk_tiles;         // tiles of one chunk block
+  size_t w1;               // byte offset of the layer-1 tiles
+  size_t chunks;           // byte offset of chunk block 0
+  size_t chunk_bytes;      // size of one chunk block
+  size_t b3;               // byte offset of the output bias
+  size_t bytes;            // size of one packed network, a multiple of 1 KiB
 };
 
 __host__ __device__ inline int tiles_for_inputs(int n_in, bool bf16) {
@@ -57,29 +66,30 @@ __host__ __device__ inline int tiles_for_inputs(int n_in, bool bf16) {
 
 __host__ __device__ inline NetLayout net_layout(int in_dim, int hidden, bool bf16) {
   NetLayout L;
-  L.kt1 = tiles_for_inputs(in_dim, bf16);
+  L.kt1 = tiles_for_inputs(in_dim + 1, bf16);
   L.kt2 = tiles_for_inputs(hidden, bf16);
   L.nuc = hidden / 32;
   L.tpc = L.kt2 / L.nuc;
+  L.chunk_tiles = L.kt2 + 1 + 2 * L.tpc;
   L.w1 = 0;
   L.chunks = L.w1 + (size_t)L.nuc * L.kt1 * 1024;
-  L.chunk_bytes = (size_t)(L.kt2 + 2 * L.tpc) * 1024;
-  L.b1 = L.chunks + (size_t)L.nuc * L.chunk_bytes;
-  L.b2 = L.b1 + (size_t)hidden * 4;
-  L.b3 = L.b2 + (size_t)hidden * 4;
-  L.bytes = L.b3 + 32 * 4;
+  L.chunk_bytes = (size_t)L.chunk_tiles * 1024;
+  L.b3 = L.chunks + (size_t)L.nuc * L.chunk_bytes;
+  L.bytes = (L.b3 + 32 * 4 + 1023) / 1024 * 1024;
   return L;
 }
 
 // One matrix (or bias vector) to re-order.
 struct PackJob {
-  const void* src;   // device
-  void* dst;         // device
-  int src_bf16;      // source element type (dst tiles have the same type; biases become f32)
-  int is_bias;       // 1: copy n_out values through the output map into 32*nuc floats
-  int n_in, n_out;   // logical sizes
-  int src_out_major; // 0: src[in * n_out + out] (network weights); 1: src[out * n_in + in]
-  int nuc, kt;       // output chunks, tiles per chunk
+  const void* src;    // device
+  const void* bias;   // device, or null: values served at input index bias_index
+  void* dst;          // device
+  int src_bf16;       // source element type (dst tiles have the same type; bias vectors become f32)
+  int is_bias;        // 1: copy n_out values through the output map into 32*nuc floats
+  int n_in, n_out;    // logical sizes
+  int bias_index;     // input index that reads bias[out] (only if bias != null)
+  int src_out_major;  // 0: src[in * n_out + out] (network weights); 1: src[out * n_in + in]
+  int nuc, kt;        // output chunks, tiles per chunk
   // destination tile of (output chunk uc, input tile kt):
   //   (uc + kt / group) * chunk_stride + slot_base + kt % group
   // layers 1, 2: group = kt (tiles of a chunk are consecutive); layer 3: group = tiles
@@ -90,7 +100,7 @@ struct PackJob {
 
 struct PackJobs {
   int n;
-  PackJob job[16];
+  PackJob job[12];
 };
 
 }  // namespace msrl

@@ -41,11 +41,14 @@ struct RolloutArgs {
   int64_t M;
 };
 
-__device__ __forceinline__ void load_bias_to_lds(float* dst, const uint8_t* packed, size_t net_bytes,
-                                                 size_t bias_off, int per_net) {
-  for (int i = threadIdx.x; i < 2 * per_net; i += blockDim.x) {
-    const int net = i / per_net, k = i - net * per_net;
-    dst[i] = *(const float*)(packed + (size_t)net * net_bytes + bias_off + (size_t)k * 4);
+// Copies the layer-1 tiles and the output biases of both packed networks into LDS (once per kernel).
+__device__ __forceinline__ void load_resident(u32x4* l1, float* b3, const uint8_t* packed,
+                                              const NetLayout& ly, int l1_tiles) {
+  for (int net = 0; net < 2; ++net) {
+    const u32x4* src = (const u32x4*)(packed + (size_t)net * ly.bytes + ly.w1);
+    for (int i = threadIdx.x; i < l1_tiles * 64; i += blockDim.x) l1[net * l1_tiles * 64 + i] = src[i];
+    if (threadIdx.x < 32)
+      b3[net * 32 + threadIdx.x] = *(const float*)(packed + (size_t)net * ly.bytes + ly.b3 + threadIdx.x * 4);
   }
 }
 
@@ -89,15 +92,16 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int L = N;
   constexpr int D = 6 * N;
   constexpr int S = 4 * N + 2 * L;
-  constexpr int KT1 = BF16 ? (D + 15) / 16 : (D + 7) / 8;
+  constexpr int KT1 = BF16 ? (D + 1 + 15) / 16 : (D + 1 + 7) / 8;  // + the constant-1 input that carries the bias
+  constexpr int NBUF = BF16 ? 3 : 2;  // window depth: bf16 stages are short, keep two in flight
   typedef Mlp<H, BF16, NB, KT1> Net;
-  typedef WeightStream<Net, WAVES> Stream;
+  typedef WeightStream<Net, WAVES, NBUF> Stream;
   typedef typename Net::Op Op;
-  constexpr int BIAS = 2 * H + 32;
   static_assert(EPW >= 1, "a wave must hold at least one env");
 
-  __shared__ __attribute__((aligned(16))) u32x4 s_w[Stream::NBUF * Stream::BUF_SLOTS];
-  __shared__ __attribute__((aligned(16))) float s_bias[2 * BIAS];
+  __shared__ __attribute__((aligned(16))) u32x4 s_l1[2][Net::L1_TILES * 64];  // resident layer-1 tiles
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[NBUF * Stream::BUF_SLOTS];  // chunk-block window
+  __shared__ __attribute__((aligned(16))) float s_b3[2][32];
   __shared__ float2 s_tab[WAVES][2 * ROWS];  // [0,ROWS) landmarks, [ROWS,2ROWS) agents
   __shared__ float s_part[WAVES][2 * ROWS];
 
@@ -112,9 +116,10 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   ws.chunk_bytes = ly.chunk_bytes;
   ws.wave = wave;
   ws.lane = lane;
-  ws.issue(0, 0);
-  ws.issue(1, 1);
-  load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
+#pragma unroll
+  for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
+  load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
+  __syncthreads();
 
   // envs of this workgroup: [blk0, blk0 + envs_per_block); of this wave: EPW of them
   const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   wave_lds_sync();
 
   const int64_t m0 = env0 * N;  // first trajectory row of this wave
-  int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % 2
+  int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % NBUF
 
   for (int t = 0; t <= a.T; ++t) {
     // ---------------- observation rows: build, store, convert to MFMA operands
@@ -191,11 +196,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             f[2 * pi + 1] = o.y;
           }
           const int f0 = 16 * kt + 8 * h;
-#ifdef MSRL_X_NO_OBS_STORE
-          if (false) {
-#else
           if (valid[q]) {
-#endif
             if constexpr (D % 4 == 0) {
               if (f0 + 4 <= D) *(float4*)(orow + f0) = make_float4(f[0], f[1], f[2], f[3]);
               if (f0 + 8 <= D) *(float4*)(orow + f0 + 4) = make_float4(f[4], f[5], f[6], f[7]);
@@ -205,6 +206,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
                 if (f0 + 2 * pi + 2 <= D) *(float2*)(orow + f0 + 2 * pi) = make_float2(f[2 * pi], f[2 * pi + 1]);
             }
           }
+          if (D / 16 == kt && (D % 16) / 8 == h) f[D % 8] = 1.0f;  // input D carries the bias
           x[q][kt] = __builtin_convertvector(f, bf16x8);
         }
       } else {
@@ -216,35 +218,37 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             if (valid[q] && (mm & 1) == h) *(float2*)(orow + 2 * mm) = o;
           }
           x[q][mm] = h ? o.y : o.x;
+          if (2 * mm == D) x[q][mm] = h ? 0.0f : 1.0f;  // input D carries the bias
         }
       }
     }
 
-    // ---------------- networks: policy stages, then value stages, through the LDS window
+    // ---------------- networks: policy, then value; chunk blocks come through the LDS window
     f32x16 out_p[NB], out_v[NB];
     {
       Op h1[NB][Net::KT2 * Net::PT];
 #pragma unroll
       for (int net = 0; net < 2; ++net) {
         f32x16(&out)[NB] = net == 0 ? out_p : out_v;
-        const float* bias = s_bias + net * BIAS;
-        ws.wait_older();
-        ws.issue(net * Net::STAGES + 2, (gs + 2) % 3);  // stage g + 2 -> buffer (g + 2) % 3
-        Net::layer1(ws.tiles(gs % 3), bias, x, h1, h);
-        ++gs;
-        Net::out_init(bias + 2 * H, out, h);
+        Net::layer1(&s_l1[net][0] + lane, x, h1);
+        {
+          const f32x16 b = bias_init(s_b3[net], h);
+#pragma unroll
+          for (int q = 0; q < NB; ++q) out[q] = b;
+        }
         f32x16 acc[NB];
 #pragma unroll 1
         for (int uc = 0; uc < Net::NUC; ++uc) {
-          ws.wait_older();
-          int next = net * Net::STAGES + 3 + uc;  // two stages ahead, cyclic over the step
+          ws.wait_oldest();
+          int next = net * Net::NUC + uc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
           if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
-          ws.issue(next, (gs + 2) % 3);
+          ws.issue(next, (gs + Stream::AHEAD) % NBUF);
+          const u32x4* tiles = ws.tiles(gs % NBUF);
           if (uc == 0)
-            Net::template layer2_chunk<false>(ws.tiles(gs % 3), bias + H, uc, h1, acc, out, h);
+            Net::template layer2_chunk<false>(tiles, h1, acc, out, h);
           else
-            Net::template layer2_chunk<true>(ws.tiles(gs % 3), bias + H, uc, h1, acc, out, h);
-          if (uc == Net::NUC - 1) Net::layer2_drain(ws.tiles(gs % 3), acc, out);
+            Net::template layer2_chunk<true>(tiles, h1, acc, out, h);
+          if (uc == Net::NUC - 1) Net::layer2_drain(tiles, acc, out);
           ++gs;
         }
       }
@@ -253,9 +257,6 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     for (int q = 0; q < NB; ++q)
       if (h == 0 && valid[q]) a.values[(size_t)t * a.M + m0 + row[q]] = out_v[q][0];
     if (t == a.T) break;
-#ifdef MSRL_X_NO_ENV
-    continue;
-#endif
 
     // ---------------- sampling, physics
     float rew_term[NB];
@@ -361,15 +362,16 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 // registers and its result is already the next step's layer-1 operand.
 template <int D, int K, int H, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArgs a) {
-  constexpr int KT1 = (D + 7) / 8;
-  constexpr int NR = 4 * KT1;  // state registers per lane
+  constexpr int KT1 = (D + 1 + 7) / 8;  // + the constant-1 input that carries the bias
+  constexpr int NR = 4 * KT1;           // state registers per lane
+  constexpr int NBUF = 2;
   typedef Mlp<H, false, 1, KT1> Net;
-  typedef WeightStream<Net, WAVES> Stream;
-  constexpr int BIAS = 2 * H + 32;
-  static_assert(D <= 32 && K <= 8, "one MFMA chunk of state, one tile of action");
+  typedef WeightStream<Net, WAVES, NBUF> Stream;
+  static_assert(D <= 31 && K <= 8, "one MFMA chunk of state (plus the constant input), one tile of action");
 
-  __shared__ __attribute__((aligned(16))) u32x4 s_w[Stream::NBUF * Stream::BUF_SLOTS];
-  __shared__ __attribute__((aligned(16))) float s_bias[2 * BIAS];
+  __shared__ __attribute__((aligned(16))) u32x4 s_l1[2][Net::L1_TILES * 64];
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[NBUF * Stream::BUF_SLOTS];
+  __shared__ __attribute__((aligned(16))) float s_b3[2][32];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 31, h = lane >> 5;
@@ -382,9 +384,10 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   ws.chunk_bytes = ly.chunk_bytes;
   ws.wave = wave;
   ws.lane = lane;
-  ws.issue(0, 0);
-  ws.issue(1, 1);
-  load_bias_to_lds(s_bias, a.packed, ly.bytes, ly.b1, BIAS);
+#pragma unroll
+  for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
+  load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
+  __syncthreads();
 
   const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
   const int64_t blk_end = min(blk0 + (int64_t)a.envs_per_block, (int64_t)a.E);
@@ -421,27 +424,30 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
     f32x16 out_p[1], out_v[1];
     {
       float h1[1][Net::KT2 * Net::PT];
+      float x[1][NR];  // the state with the constant 1 at input D
+#pragma unroll
+      for (int r = 0; r < NR; ++r) {
+        const int u = 8 * (r >> 2) + 4 * h + (r & 3);
+        x[0][r] = u == D ? 1.0f : s[0][r];
+      }
 #pragma unroll
       for (int net = 0; net < 2; ++net) {
         f32x16(&out)[1] = net == 0 ? out_p : out_v;
-        const float* bias = s_bias + net * BIAS;
-        ws.wait_older();
-        ws.issue(net * Net::STAGES + 2, (gs + 2) % 3);  // stage g + 2 -> buffer (g + 2) % 3
-        Net::layer1(ws.tiles(gs % 3), bias, s, h1, h);
-        ++gs;
-        Net::out_init(bias + 2 * H, out, h);
+        Net::layer1(&s_l1[net][0] + lane, x, h1);
+        out[0] = bias_init(s_b3[net], h);
         f32x16 acc[1];
 #pragma unroll 1
         for (int uc = 0; uc < Net::NUC; ++uc) {
-          ws.wait_older();
-          int next = net * Net::STAGES + 3 + uc;  // two stages ahead, cyclic over the step
+          ws.wait_oldest();
+          int next = net * Net::NUC + uc + Stream::AHEAD;
           if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
-          ws.issue(next, (gs + 2) % 3);
+          ws.issue(next, (gs + Stream::AHEAD) % NBUF);
+          const u32x4* tiles = ws.tiles(gs % NBUF);
           if (uc == 0)
-            Net::template layer2_chunk<false>(ws.tiles(gs % 3), bias + H, uc, h1, acc, out, h);
+            Net::template layer2_chunk<false>(tiles, h1, acc, out, h);
           else
-            Net::template layer2_chunk<true>(ws.tiles(gs % 3), bias + H, uc, h1, acc, out, h);
-          if (uc == Net::NUC - 1) Net::layer2_drain(ws.tiles(gs % 3), acc, out);
+            Net::template layer2_chunk<true>(tiles, h1, acc, out, h);
+          if (uc == Net::NUC - 1) Net::layer2_drain(tiles, acc, out);
           ++gs;
         }
       }
