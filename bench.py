@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5, help="synthetic configuration 1..5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run one plain device copy of this size (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -158,6 +160,15 @@ def main():
         "frac": gae_achieved / PEAK_HBM_GBS, "traffic": read_traffic(f"gae_cfg{args.config}_pmc.md"),
         "ms_per_launch": gae_ms,
     }
+
+    if args.copy_calibration:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # reads and writes copy_calibration MiB each
+        torch.cuda.synchronize()
+        del src, dst
 
     B.msrl_rollout_destroy(state)
     del out
