@@ -195,9 +195,12 @@ struct Mlp {
 
   // Stage of chunk uc: acc <- layer-2 pre-activations of chunk uc; if PIPE, `acc` holds those of
   // chunk uc-1 on entry, which get tanh and feed layer 3 meanwhile.
-  template <bool PIPE>
+  // tick(kt) is called once per layer-2 tile: the caller spreads the copies of a later stage over
+  // the loop, so that they queue behind the MFMAs instead of stalling every wave at the stage start.
+  template <bool PIPE, class Tick>
   __device__ static __forceinline__ void layer2_chunk(const u32x4* tiles, const Op (&h1)[NB][KT2 * PT],
-                                                      f32x16 (&acc)[NB], f32x16 (&out)[NB], int h) {
+                                                      f32x16 (&acc)[NB], f32x16 (&out)[NB], int h,
+                                                      Tick&& tick) {
     u32x4 ring[G];
 #pragma unroll
     for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
@@ -218,6 +221,7 @@ struct Mlp {
         if (PIPE) pin(acc[q]);
       }
       if (PIPE) tanh_slice<KT2>(prev, t, kt);
+      tick(kt);
     }
     {
       const Op one = Operand<BF16>::one(h);
@@ -287,20 +291,22 @@ struct WeightStream {
   size_t net_bytes, chunks_off, chunk_bytes;
   int wave, lane;
 
-  // start copying stage s (0 .. STAGES_PER_STEP-1: chunk block s % NUC of network s / NUC) into buffer `buf`
-  __device__ __forceinline__ void issue(int s, int buf) const {
+  // copy number i (0 .. PER_WAVE-1) of this wave for stage s (0 .. STAGES_PER_STEP-1: chunk block
+  // s % NUC of network s / NUC) into buffer `buf`
+  __device__ __forceinline__ void issue_part(int s, int buf, int i) const {
     const int net = s >= Net::NUC ? 1 : 0;
     const uint8_t* src = packed + (size_t)net * net_bytes + chunks_off + (size_t)(s - net * Net::NUC) * chunk_bytes;
     typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
     const uint32_t base = (uint32_t)(uintptr_t)(lds_u32x4*)(lds + buf * BUF_SLOTS);
+    const int t = wave + i * WAVES;
+    // a wave with no tile left repeats tile 0 into its padding tile: every wave issues PER_WAVE copies
+    const uint8_t* g = src + (size_t)(t < Net::CHUNK_TILES ? t : 0) * 1024 + (size_t)lane * 16;
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(base + (uint32_t)t * 1024u);
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory", "m0");
+  }
+  __device__ __forceinline__ void issue(int s, int buf) const {
 #pragma unroll
-    for (int i = 0; i < PER_WAVE; ++i) {
-      const int t = wave + i * WAVES;
-      // a wave with no tile left repeats tile 0 into its padding tile: every wave issues PER_WAVE copies
-      const uint8_t* g = src + (size_t)(t < Net::CHUNK_TILES ? t : 0) * 1024 + (size_t)lane * 16;
-      const uint32_t m0 = __builtin_amdgcn_readfirstlane(base + (uint32_t)t * 1024u);
-      asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory", "m0");
-    }
+    for (int i = 0; i < PER_WAVE; ++i) issue_part(s, buf, i);
   }
   // wait until the oldest stage in flight has landed, then for every wave of the workgroup
   __device__ __forceinline__ void wait_oldest() const {

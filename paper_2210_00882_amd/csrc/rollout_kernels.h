@@ -242,12 +242,18 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           ws.wait_oldest();
           int next = net * Net::NUC + uc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
           if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
-          ws.issue(next, (gs + Stream::AHEAD) % NBUF);
           const u32x4* tiles = ws.tiles(gs % NBUF);
+          const int nbuf = (gs + Stream::AHEAD) % NBUF;
+          // the copies of the stage AHEAD stages later, spread over this stage's tile loop
+          auto tick = [&](int kt) {
+#pragma unroll
+            for (int i = 0; i < Stream::PER_WAVE; ++i)
+              if (i * Net::KT2 / Stream::PER_WAVE == kt) ws.issue_part(next, nbuf, i);
+          };
           if (uc == 0)
-            Net::template layer2_chunk<false>(tiles, h1, acc, out, h);
+            Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
           else
-            Net::template layer2_chunk<true>(tiles, h1, acc, out, h);
+            Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
           if (uc == Net::NUC - 1) Net::layer2_drain(tiles, acc, out);
           ++gs;
         }
@@ -441,12 +447,17 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
           ws.wait_oldest();
           int next = net * Net::NUC + uc + Stream::AHEAD;
           if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
-          ws.issue(next, (gs + Stream::AHEAD) % NBUF);
           const u32x4* tiles = ws.tiles(gs % NBUF);
+          const int nbuf = (gs + Stream::AHEAD) % NBUF;
+          auto tick = [&](int kt) {
+#pragma unroll
+            for (int i = 0; i < Stream::PER_WAVE; ++i)
+              if (i * Net::KT2 / Stream::PER_WAVE == kt) ws.issue_part(next, nbuf, i);
+          };
           if (uc == 0)
-            Net::template layer2_chunk<false>(tiles, h1, acc, out, h);
+            Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
           else
-            Net::template layer2_chunk<true>(tiles, h1, acc, out, h);
+            Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
           if (uc == Net::NUC - 1) Net::layer2_drain(tiles, acc, out);
           ++gs;
         }
