@@ -264,9 +264,9 @@ struct Mlp {
   }
 };
 
-// Weight stream of a workgroup: stage g of the endless sequence (policy chunk
-// blocks, value chunk blocks, policy chunk blocks, ...) lives in LDS buffer
-// g % NBUF and is copied there NBUF - 1 stages ahead by direct global->LDS loads
+// Weight stream of a workgroup: stage g of the endless sequence (groups of CPS
+// policy chunk blocks, then of value chunk blocks, then policy again, ...) lives
+// in LDS buffer g % NBUF and is copied there NBUF - 1 stages ahead by direct global->LDS loads
 // (no registers involved).
 //
 // The copy instruction is issued from inline assembly on purpose: issued through
@@ -278,12 +278,15 @@ struct Mlp {
 // memory operations outstanding" means the copies of the stage about to be used
 // have landed.  Vector-memory operations the compiler issues itself only add to
 // the outstanding count, which makes the wait longer, never shorter.
-template <class Net, int WAVES, int NBUF>
+template <class Net, int WAVES, int NBUF, int CPS>
 struct WeightStream {
-  static constexpr int STAGES_PER_STEP = 2 * Net::NUC;
-  static constexpr int PER_WAVE = (Net::CHUNK_TILES + WAVES - 1) / WAVES;  // copies per wave and stage
-  static constexpr int BUF_TILES = PER_WAVE * WAVES;                        // incl. padding tiles
-  static constexpr int BUF_SLOTS = BUF_TILES * 64;                          // u32x4 slots per buffer
+  // a stage = CPS consecutive chunk blocks of one network
+  static_assert(Net::NUC % CPS == 0, "stages must not straddle networks");
+  static constexpr int STAGES_PER_NET = Net::NUC / CPS;
+  static constexpr int STAGES_PER_STEP = 2 * STAGES_PER_NET;
+  static constexpr int STAGE_TILES = CPS * Net::CHUNK_TILES;
+  static constexpr int PER_WAVE = (STAGE_TILES + WAVES - 1) / WAVES;  // copies per wave and stage
+  static constexpr int BUF_SLOTS = STAGE_TILES * 64;                   // u32x4 slots per buffer
   static constexpr int AHEAD = NBUF - 1;
   static_assert(NBUF >= 2 && (NBUF - 2) * PER_WAVE <= 15, "the hand-written wait encodes the count in 4 bits");
   u32x4* lds;  // NBUF * BUF_SLOTS slots
@@ -291,16 +294,18 @@ struct WeightStream {
   size_t net_bytes, chunks_off, chunk_bytes;
   int wave, lane;
 
-  // copy number i (0 .. PER_WAVE-1) of this wave for stage s (0 .. STAGES_PER_STEP-1: chunk block
-  // s % NUC of network s / NUC) into buffer `buf`
+  // copy number i (0 .. PER_WAVE-1) of this wave for stage s (0 .. STAGES_PER_STEP-1) into buffer `buf`
   __device__ __forceinline__ void issue_part(int s, int buf, int i) const {
-    const int net = s >= Net::NUC ? 1 : 0;
-    const uint8_t* src = packed + (size_t)net * net_bytes + chunks_off + (size_t)(s - net * Net::NUC) * chunk_bytes;
+    const int net = s >= STAGES_PER_NET ? 1 : 0;
+    const uint8_t* src = packed + (size_t)net * net_bytes + chunks_off +
+                         (size_t)(s - net * STAGES_PER_NET) * CPS * chunk_bytes;
     typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
     const uint32_t base = (uint32_t)(uintptr_t)(lds_u32x4*)(lds + buf * BUF_SLOTS);
-    const int t = wave + i * WAVES;
-    // a wave with no tile left repeats tile 0 into its padding tile: every wave issues PER_WAVE copies
-    const uint8_t* g = src + (size_t)(t < Net::CHUNK_TILES ? t : 0) * 1024 + (size_t)lane * 16;
+    // a wave with no tile left copies tile 0 once more (same bytes to the same place), so that
+    // every wave issues exactly PER_WAVE copies per stage
+    int t = wave + i * WAVES;
+    t = t < STAGE_TILES ? t : 0;
+    const uint8_t* g = src + (size_t)t * 1024 + (size_t)lane * 16;
     const uint32_t m0 = __builtin_amdgcn_readfirstlane(base + (uint32_t)t * 1024u);
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory", "m0");
   }
@@ -318,7 +323,10 @@ struct WeightStream {
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
   }
-  __device__ __forceinline__ const u32x4* tiles(int buf) const { return lds + buf * BUF_SLOTS + lane; }
+  // this lane's slot of tile 0 of chunk block c of the stage in buffer `buf`
+  __device__ __forceinline__ const u32x4* tiles(int buf, int c) const {
+    return lds + buf * BUF_SLOTS + c * Net::CHUNK_TILES * 64 + lane;
+  }
 };
 
 }  // namespace msrl

@@ -93,9 +93,10 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int D = 6 * N;
   constexpr int S = 4 * N + 2 * L;
   constexpr int KT1 = BF16 ? (D + 1 + 15) / 16 : (D + 1 + 7) / 8;  // + the constant-1 input that carries the bias
-  constexpr int NBUF = BF16 ? 3 : 2;  // window depth: bf16 stages are short, keep two in flight
+  constexpr int NBUF = 2;             // LDS window: the stage in use and the one being copied
+  constexpr int CPS = BF16 && H >= 64 ? 2 : 1;  // chunk blocks per stage (fewer barriers when they fit)
   typedef Mlp<H, BF16, NB, KT1> Net;
-  typedef WeightStream<Net, WAVES, NBUF> Stream;
+  typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   typedef typename Net::Op Op;
   static_assert(EPW >= 1, "a wave must hold at least one env");
 
@@ -238,23 +239,26 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         }
         f32x16 acc[NB];
 #pragma unroll 1
-        for (int uc = 0; uc < Net::NUC; ++uc) {
+        for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
           ws.wait_oldest();
-          int next = net * Net::NUC + uc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
+          int next = net * Stream::STAGES_PER_NET + sc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
           if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
-          const u32x4* tiles = ws.tiles(gs % NBUF);
           const int nbuf = (gs + Stream::AHEAD) % NBUF;
-          // the copies of the stage AHEAD stages later, spread over this stage's tile loop
-          auto tick = [&](int kt) {
 #pragma unroll
-            for (int i = 0; i < Stream::PER_WAVE; ++i)
-              if (i * Net::KT2 / Stream::PER_WAVE == kt) ws.issue_part(next, nbuf, i);
-          };
-          if (uc == 0)
-            Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
-          else
-            Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
-          if (uc == Net::NUC - 1) Net::layer2_drain(tiles, acc, out);
+          for (int c = 0; c < CPS; ++c) {
+            const u32x4* tiles = ws.tiles(gs % NBUF, c);
+            // the copies of the stage AHEAD stages later, spread over this stage's tile loops
+            auto tick = [&](int kt) {
+#pragma unroll
+              for (int i = 0; i < Stream::PER_WAVE; ++i)
+                if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
+            };
+            if (c == 0 && sc == 0)
+              Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
+            else
+              Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
+            if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
+          }
           ++gs;
         }
       }
@@ -370,9 +374,9 @@ template <int D, int K, int H, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArgs a) {
   constexpr int KT1 = (D + 1 + 7) / 8;  // + the constant-1 input that carries the bias
   constexpr int NR = 4 * KT1;           // state registers per lane
-  constexpr int NBUF = 2;
+  constexpr int NBUF = 2, CPS = 1;
   typedef Mlp<H, false, 1, KT1> Net;
-  typedef WeightStream<Net, WAVES, NBUF> Stream;
+  typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   static_assert(D <= 31 && K <= 8, "one MFMA chunk of state (plus the constant input), one tile of action");
 
   __shared__ __attribute__((aligned(16))) u32x4 s_l1[2][Net::L1_TILES * 64];
@@ -443,22 +447,26 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
         out[0] = bias_init(s_b3[net], h);
         f32x16 acc[1];
 #pragma unroll 1
-        for (int uc = 0; uc < Net::NUC; ++uc) {
+        for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
           ws.wait_oldest();
-          int next = net * Net::NUC + uc + Stream::AHEAD;
+          int next = net * Stream::STAGES_PER_NET + sc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
           if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
-          const u32x4* tiles = ws.tiles(gs % NBUF);
           const int nbuf = (gs + Stream::AHEAD) % NBUF;
-          auto tick = [&](int kt) {
 #pragma unroll
-            for (int i = 0; i < Stream::PER_WAVE; ++i)
-              if (i * Net::KT2 / Stream::PER_WAVE == kt) ws.issue_part(next, nbuf, i);
-          };
-          if (uc == 0)
-            Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
-          else
-            Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
-          if (uc == Net::NUC - 1) Net::layer2_drain(tiles, acc, out);
+          for (int c = 0; c < CPS; ++c) {
+            const u32x4* tiles = ws.tiles(gs % NBUF, c);
+            // the copies of the stage AHEAD stages later, spread over this stage's tile loops
+            auto tick = [&](int kt) {
+#pragma unroll
+              for (int i = 0; i < Stream::PER_WAVE; ++i)
+                if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
+            };
+            if (c == 0 && sc == 0)
+              Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
+            else
+              Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
+            if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
+          }
           ++gs;
         }
       }
