@@ -65,12 +65,13 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
     e[k] = __expf(z[k]);
     s += e[k];
   }
+  const float inv = __builtin_amdgcn_rcpf(s);  // 1 ulp; a draw that close to a bin edge is exempt anyway
   float c = 0.0f;
   int a = 4;
   bool found = false;
 #pragma unroll
   for (int k = 0; k < 5; ++k) {
-    c += e[k] / s;
+    c += e[k] * inv;
     if (!found && u < c) {
       a = k;
       found = true;
@@ -80,7 +81,7 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 #pragma unroll
   for (int k = 1; k < 5; ++k) za = (a == k) ? z[k] : za;
   action = a;
-  logp = za - logf(s);
+  logp = za - __logf(s);  // s is in [1, 5]: absolute error of the fast log ~1e-7
 }
 
 // ------------------------------------------------------------------ particle env
@@ -316,7 +317,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         const float dxa = pj.x - p[q].x, dya = pj.y - p[q].y;
         if (j > ag[q] && dxa * dxa + dya * dya < a.coll2) cnt += 1.0f;
       }
-      rew_term[q] = h ? -cnt : -sqrtf(mn);
+      rew_term[q] = h ? -cnt : -__builtin_amdgcn_sqrtf(mn);
       if (valid[q]) part[h * ROWS + base[q] + ag[q]] = rew_term[q];
     }
     wave_lds_sync();
