@@ -143,10 +143,7 @@ struct Mlp {
   static constexpr int CHUNK_TILES = KT2 + 1 + 2 * TPC;  // one stage: layer-2 tiles of chunk c, its bias
                                                          // tile, layer-3 tiles of chunk c-1, of chunk c
   static constexpr int L3_PREV = KT2 + 1, L3_OWN = KT2 + 1 + TPC;
-  #ifndef MSRL_G
-#define MSRL_G 4
-#endif
-  static constexpr int G = MSRL_G;  // LDS reads run G tiles ahead of the MFMAs that consume them
+  static constexpr int G = 4;  // LDS reads run G tiles ahead of the MFMAs that consume them
 
   // tanh of the previous chunk, spread over the NT tiles of the current one
   template <int NT>

@@ -1,0 +1,89 @@
+"""Behaviour of the C ABI on the device beyond numerics: determinism, optional
+outputs, call equivalences, argument errors raised before any launch."""
+import numpy as np
+import pytest
+
+from paper_2210_00882_amd import synth
+from helpers import GpuRollout, oracle_setup
+
+pytestmark = pytest.mark.gpu
+
+
+def small_cfg():
+    return synth.CONFIGS[1].with_(num_envs=77, episode_len=6)
+
+
+def test_two_runs_are_bit_identical():
+    cfg = small_cfg()
+    _, _, params, _ = oracle_setup(cfg)
+    runs = []
+    for _ in range(2):
+        with GpuRollout(cfg, params.astype(np.float32), 99) as gpu:
+            runs.append(gpu.run(21))
+    for k in runs[0]:
+        np.testing.assert_array_equal(runs[0][k], runs[1][k])
+
+
+def test_optional_logits_and_step_vs_fused_call():
+    cfg = small_cfg()
+    _, _, params, _ = oracle_setup(cfg)
+    with GpuRollout(cfg, params.astype(np.float32), 5) as gpu:
+        full = gpu.run(15, gae=True, logits=True)
+    with GpuRollout(cfg, params.astype(np.float32), 5) as gpu:
+        bare = gpu.run(15, gae=False, logits=False)
+        # adv / ret are not touched by msrl_rollout_step; logits were not requested
+        assert bare["logits"] is None and bare["adv"] is None
+    for k in ("obs", "actions", "logp", "rewards", "dones", "values"):
+        np.testing.assert_array_equal(full[k], bare[k])
+
+
+def test_one_long_call_equals_two_short_ones():
+    cfg = small_cfg()
+    _, _, params, _ = oracle_setup(cfg)
+    with GpuRollout(cfg, params.astype(np.float32), 5) as gpu:
+        whole = gpu.run(17)
+    with GpuRollout(cfg, params.astype(np.float32), 5) as gpu:
+        a = gpu.run(8)
+        b = gpu.run(9)
+    for k in ("actions", "logp", "rewards", "dones"):
+        np.testing.assert_array_equal(whole[k], np.concatenate([a[k], b[k]]))
+    np.testing.assert_array_equal(whole["obs"][8:], b["obs"])
+    np.testing.assert_array_equal(whole["values"][:8], a["values"][:8])
+
+
+def test_state_snapshot_round_trip():
+    cfg = small_cfg()
+    _, _, params, _ = oracle_setup(cfg)
+    with GpuRollout(cfg, params.astype(np.float32), 5) as gpu:
+        gpu.run(7)
+        es, g = gpu.get_state()
+        ref_run = gpu.run(5)
+        gpu.set_state(es, g)
+        again = gpu.run(5)
+    for k in ref_run:
+        np.testing.assert_array_equal(ref_run[k], again[k])
+
+
+def test_argument_errors():
+    import torch
+    cfg = small_cfg()
+    _, _, params, _ = oracle_setup(cfg)
+    with GpuRollout(cfg, params.astype(np.float32), 5) as gpu:
+        B = gpu.B
+        out = B.alloc_traj(cfg, 4, logits=False, gae=False)
+        with pytest.raises(B.MsrlError) as e:
+            B.msrl_rollout_step(gpu.state, gpu.params, 0, out)
+        assert e.value.code == B.MSRL_EINVAL
+        with pytest.raises(B.MsrlError) as e:           # adv / ret missing for the fused call
+            B.msrl_rollout_gae(gpu.state, gpu.params, 4, 0.99, 0.95, out)
+        assert e.value.code == B.MSRL_EINVAL
+        broken = dict(out)
+        broken["rewards"] = None
+        with pytest.raises(B.MsrlError):
+            B.msrl_rollout_step(gpu.state, gpu.params, 4, broken)
+        with pytest.raises(B.MsrlError):
+            B.msrl_state_set(gpu.state, None, np.full(cfg.num_envs, -1, dtype=np.int64))
+        # the state is still usable after rejected calls
+        B.msrl_rollout_step(gpu.state, gpu.params, 4, out)
+        torch.cuda.synchronize()
+        assert int(out["dones"].max()) <= 1
