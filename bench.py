@@ -98,6 +98,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=5, help="synthetic configuration 1..5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-phases", action="store_true", help="skip the env-only / MLP-only phase timings")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this size (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -161,6 +162,33 @@ def main():
         "ms_per_launch": gae_ms,
     }
 
+    # phase rooflines: the same kernel with the networks skipped (env phase, HBM-bound: every
+    # trajectory store is kept) and with only the networks (MLP phase, MFMA-bound)
+    phases = None
+    if not args.no_phases:
+        phases = {}
+        for name, phase in (("env", B.MSRL_PHASE_ENV), ("mlp", B.MSRL_PHASE_MLP)):
+            try:
+                B.msrl_measure_phase(state, dparams, T, out, phase)
+            except B.MsrlError:
+                continue  # variant not compiled for this configuration
+            e0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+            e1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+            for k in range(args.steps):
+                e0[k].record()
+                B.msrl_measure_phase(state, dparams, T, out, phase)
+                e1[k].record()
+            torch.cuda.synchronize()
+            ms = float(np.mean([a.elapsed_time(b) for a, b in zip(e0, e1)]))
+            if name == "env":
+                gbs = rollout_bytes_per_agent_step(cfg) * agent_steps / (ms * 1e-3) / 1e9
+                phases[name] = {"bound": "hbm", "ms_per_launch": ms, "achieved": gbs, "peak": PEAK_HBM_GBS,
+                                "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+            else:
+                tf = flops / (ms * 1e-3) / 1e12
+                phases[name] = {"bound": "mfma", "ms_per_launch": ms, "achieved": tf, "peak": PEAK_TFLOPS[dt_name],
+                                "unit": "TFLOP/s", "frac": tf / PEAK_TFLOPS[dt_name]}
+
     if args.copy_calibration:
         n = args.copy_calibration * (1 << 20) // 4
         src = torch.ones(n, dtype=torch.float32, device="cuda")
@@ -186,6 +214,7 @@ def main():
                    "agent_steps_per_step": agent_steps},
         "roofline": roofline,
         "roofline_gae": roofline_gae,
+        "phases": phases,
         "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(cfg, seed),
     }
     print(json.dumps(result))

@@ -181,6 +181,21 @@ int msrl_rollout_gae(msrl_state* st, const void* params, int32_t T,
                      float gamma, float lambda, msrl_traj* out, void* hip_stream);
 
 /*
+ * Measurement only (phase rooflines of the rollout kernel; not part of the
+ * method).  Same arguments as msrl_rollout_step.
+ *   MSRL_PHASE_ENV: the rollout with both networks skipped.  Logits and values
+ *     are 0, i.e. exactly what msrl_rollout_step computes for an all-zero
+ *     parameter buffer: every output is defined, the state advances.
+ *   MSRL_PHASE_MLP: T evaluations of both networks on the observation of the
+ *     current state; no env step, no state change.  The contents of `out` are
+ *     unspecified afterwards (only rewards[0, :] is written, with a checksum).
+ * EUNSUPPORTED if the variant was not compiled for the state's configuration.
+ */
+typedef enum { MSRL_PHASE_ENV = 1, MSRL_PHASE_MLP = 2 } msrl_phase;
+int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj* out,
+                       int32_t phase, void* hip_stream);
+
+/*
  * Snapshot / restore of the env batch.  env_state: HOST
  * [num_envs, msrl_env_state_size] floats; step_counters: HOST [num_envs] int64
  * (only the low 32 bits enter the Philox counter).  Either pointer may be NULL

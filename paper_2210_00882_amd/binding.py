@@ -17,10 +17,11 @@ MSRL_OK, MSRL_EINVAL, MSRL_ENOMEM, MSRL_EDEVICE, MSRL_EUNSUPPORTED = 0, -1, -2, 
 MSRL_ENV_PARTICLE, MSRL_ENV_LINGAUSS = 0, 1
 MSRL_F32, MSRL_BF16 = 0, 1
 MSRL_CATEGORICAL, MSRL_DIAG_GAUSSIAN = 0, 1
+MSRL_PHASE_ENV, MSRL_PHASE_MLP = 1, 2
 
 EXPORTS = (
     "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",
-    "msrl_rollout_gae", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
+    "msrl_rollout_gae", "msrl_measure_phase", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
 )
 
 
@@ -77,6 +78,8 @@ def load():
     lib.msrl_gae.argtypes = [vp, vp, vp, i32, i64, f32, f32, vp, vp, vp]
     lib.msrl_rollout_gae.restype = C.c_int
     lib.msrl_rollout_gae.argtypes = [vp, vp, i32, f32, f32, C.POINTER(msrl_traj), vp]
+    lib.msrl_measure_phase.restype = C.c_int
+    lib.msrl_measure_phase.argtypes = [vp, vp, i32, C.POINTER(msrl_traj), i32, vp]
     lib.msrl_state_get.restype = C.c_int
     lib.msrl_state_get.argtypes = [vp, vp, vp]
     lib.msrl_state_set.restype = C.c_int
@@ -175,6 +178,12 @@ def msrl_rollout_gae(state, params, T: int, gamma: float, lam: float, out: dict,
     tr = _traj(out)
     _check(load().msrl_rollout_gae(state, _ptr(params), C.c_int32(T), C.c_float(gamma), C.c_float(lam),
                                    C.byref(tr), _stream(stream)))
+
+
+def msrl_measure_phase(state, params, T: int, out: dict, phase: int, stream=None) -> None:
+    tr = _traj(out)
+    _check(load().msrl_measure_phase(state, _ptr(params), C.c_int32(T), C.byref(tr), C.c_int32(phase),
+                                     _stream(stream)))
 
 
 def msrl_state_get(state, num_envs: int, state_size: int):

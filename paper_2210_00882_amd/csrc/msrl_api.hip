@@ -62,7 +62,8 @@ int fail(int code, const char* fmt, ...) {
 
 std::vector<KernelEntry> all_kernels() {
   return {entry_p1_h64_f32(),  entry_p2_h64_f32(),    entry_p3_h64_f32(), entry_p3_h64_bf16(),
-          entry_p6_h128_f32(), entry_p10_h256_bf16(), entry_l17_6_h256()};
+          entry_p6_h128_f32(), entry_p10_h256_bf16(), entry_l17_6_h256(),
+          entry_p10_h256_bf16_env(), entry_p10_h256_bf16_mlp(), entry_p3_h64_f32_env()};
 }
 
 bool valid_policy(const msrl_policy_cfg* p) {
@@ -197,7 +198,24 @@ int check_traj(const msrl_state* st, const msrl_traj* out, bool need_gae) {
   return MSRL_OK;
 }
 
-int enqueue_rollout(msrl_state* st, const void* params, int32_t T, msrl_traj* out, hipStream_t stream) {
+// the compiled kernel for this state's configuration and the given phase variant, or null
+bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase, KernelEntry* out) {
+  const bool bf16 = pol.dtype == MSRL_BF16;
+  for (const KernelEntry& k : all_kernels()) {
+    if (k.phase != phase || k.kind != env.kind || k.hidden != pol.hidden || (k.bf16 != 0) != bf16) continue;
+    if (env.kind == MSRL_ENV_PARTICLE) {
+      if (k.n != env.num_agents || env.num_landmarks != env.num_agents) continue;
+    } else {
+      if (k.n != env.obs_dim || k.k != env.act_dim) continue;
+    }
+    *out = k;
+    return true;
+  }
+  return false;
+}
+
+int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* params, int32_t T, msrl_traj* out,
+                    hipStream_t stream) {
   int rc = pack_params(st, params, stream);
   if (rc != MSRL_OK) return rc;
   RolloutArgs a;
@@ -228,7 +246,7 @@ int enqueue_rollout(msrl_state* st, const void* params, int32_t T, msrl_traj* ou
   a.envs_per_block = st->envs_per_block;
   const int64_t blocks = ((int64_t)a.E + a.envs_per_block - 1) / a.envs_per_block;
   void* args[] = {&a};
-  HIP_TRY(hipLaunchKernel(st->kernel.fn, dim3((unsigned)blocks), dim3(64 * st->kernel.waves), args, 0, stream));
+  HIP_TRY(hipLaunchKernel(kernel.fn, dim3((unsigned)blocks), dim3(64 * kernel.waves), args, 0, stream));
   return MSRL_OK;
 }
 
@@ -270,19 +288,7 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   }
   // kernel selection
   KernelEntry found;
-  bool ok = false;
-  for (const KernelEntry& k : all_kernels()) {
-    const bool bf16 = policy->dtype == MSRL_BF16;
-    if (k.kind != env->kind || k.hidden != policy->hidden || (k.bf16 != 0) != bf16) continue;
-    if (env->kind == MSRL_ENV_PARTICLE) {
-      if (k.n != env->num_agents || env->num_landmarks != env->num_agents) continue;
-    } else {
-      if (k.n != env->obs_dim || k.k != env->act_dim) continue;
-    }
-    found = k;
-    ok = true;
-    break;
-  }
+  const bool ok = find_kernel(*env, *policy, PHASE_ALL, &found);
   if (!ok)
     return fail(MSRL_EUNSUPPORTED,
                 "msrl_rollout_init: no kernel compiled for kind %d, agents %d, landmarks %d, obs_dim %d, "
@@ -386,7 +392,7 @@ int msrl_rollout_step(msrl_state* st, const void* params, int32_t T, msrl_traj* 
   if (T <= 0) return fail(MSRL_EINVAL, "msrl_rollout_step: T must be positive (got %d)", T);
   int rc = check_traj(st, out, false);
   if (rc != MSRL_OK) return rc;
-  return enqueue_rollout(st, params, T, out, (hipStream_t)hip_stream);
+  return enqueue_rollout(st, st->kernel, params, T, out, (hipStream_t)hip_stream);
 }
 
 int msrl_gae(const float* rewards, const float* values, const uint8_t* dones, int32_t T, int64_t M,
@@ -404,12 +410,26 @@ int msrl_rollout_gae(msrl_state* st, const void* params, int32_t T, float gamma,
   if (T <= 0) return fail(MSRL_EINVAL, "msrl_rollout_gae: T must be positive (got %d)", T);
   int rc = check_traj(st, out, true);
   if (rc != MSRL_OK) return rc;
-  rc = enqueue_rollout(st, params, T, out, (hipStream_t)hip_stream);
+  rc = enqueue_rollout(st, st->kernel, params, T, out, (hipStream_t)hip_stream);
   if (rc != MSRL_OK) return rc;
   const int64_t M = (int64_t)st->env.num_envs * st->env.num_agents;
   HIP_TRY(launch_gae(out->rewards, out->values, out->dones, T, M, gamma, lambda, out->adv, out->ret,
                      (hipStream_t)hip_stream));
   return MSRL_OK;
+}
+
+int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj* out, int32_t phase,
+                       void* hip_stream) {
+  if (!st || !params) return fail(MSRL_EINVAL, "msrl_measure_phase: NULL argument");
+  if (T <= 0) return fail(MSRL_EINVAL, "msrl_measure_phase: T must be positive (got %d)", T);
+  if (phase != MSRL_PHASE_ENV && phase != MSRL_PHASE_MLP)
+    return fail(MSRL_EINVAL, "msrl_measure_phase: unknown phase %d", phase);
+  int rc = check_traj(st, out, false);
+  if (rc != MSRL_OK) return rc;
+  KernelEntry k;
+  if (!find_kernel(st->env, st->pol, phase, &k))
+    return fail(MSRL_EUNSUPPORTED, "msrl_measure_phase: phase %d is not compiled for this configuration", phase);
+  return enqueue_rollout(st, k, params, T, out, (hipStream_t)hip_stream);
 }
 
 int msrl_state_get(msrl_state* st, float* env_state, int64_t* step_counters) {

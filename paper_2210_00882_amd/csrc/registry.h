@@ -14,20 +14,23 @@ struct KernelEntry {
   const void* fn;     // __global__ void (*)(RolloutArgs)
   int envs_per_wave;
   int waves;          // waves per workgroup
+  int phase;          // PHASE_ALL, or a measurement variant
 };
 
 // NB: 32-row blocks per wave; WAVES: waves per workgroup (they share the LDS weight window)
-#define MSRL_PARTICLE_ENTRY(NAME, N, H, BF16, NB, WAVES)                                   \
+#define MSRL_PARTICLE_ENTRY_PHASE(NAME, N, H, BF16, NB, WAVES, PHASE)                       \
   KernelEntry NAME() {                                                                     \
     return KernelEntry{0, N, 0, H, BF16 ? 1 : 0,                                           \
-                       (const void*)&particle_rollout_kernel<N, H, BF16, NB, WAVES>,       \
-                       32 * NB / N, WAVES};                                                \
+                       (const void*)&particle_rollout_kernel<N, H, BF16, NB, WAVES, PHASE>, \
+                       32 * NB / N, WAVES, PHASE};                                         \
   }
+#define MSRL_PARTICLE_ENTRY(NAME, N, H, BF16, NB, WAVES) \
+  MSRL_PARTICLE_ENTRY_PHASE(NAME, N, H, BF16, NB, WAVES, PHASE_ALL)
 
 #define MSRL_LINGAUSS_ENTRY(NAME, D, K, H, WAVES)                                          \
   KernelEntry NAME() {                                                                     \
     return KernelEntry{1, D, K, H, 0, (const void*)&lingauss_rollout_kernel<D, K, H, WAVES>, \
-                       32, WAVES};                                                         \
+                       32, WAVES, PHASE_ALL};                                              \
   }
 
 KernelEntry entry_p1_h64_f32();
@@ -37,5 +40,9 @@ KernelEntry entry_p3_h64_bf16();
 KernelEntry entry_p6_h128_f32();
 KernelEntry entry_p10_h256_bf16();
 KernelEntry entry_l17_6_h256();
+// measurement variants (phase rooflines)
+KernelEntry entry_p10_h256_bf16_env();
+KernelEntry entry_p10_h256_bf16_mlp();
+KernelEntry entry_p3_h64_f32_env();
 
 }  // namespace msrl

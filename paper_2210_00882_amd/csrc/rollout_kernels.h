@@ -84,8 +84,15 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
   logp = za - __logf(s);  // s is in [1, 5]: absolute error of the fast log ~1e-7
 }
 
+// Measurement variants of the same kernel (phase rooflines):
+//   PHASE_ENV  the networks are skipped; logits and values are 0, which is what an all-zero parameter
+//              buffer gives, so every output is still defined and checked against the full kernel;
+//   PHASE_MLP  T evaluations of both networks on the current observation, no env step and no
+//              trajectory stores (a checksum of the outputs goes to rewards[0, :] to keep them live).
+enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2 };
+
 // ------------------------------------------------------------------ particle env
-template <int N, int H, bool BF16, int NB, int WAVES>
+template <int N, int H, bool BF16, int NB, int WAVES, int PHASE = PHASE_ALL>
 __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArgs a) {
   constexpr int ROWS = 32 * NB;
   constexpr int EPW = ROWS / N;  // envs per wave
@@ -118,9 +125,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   ws.chunk_bytes = ly.chunk_bytes;
   ws.wave = wave;
   ws.lane = lane;
+  if constexpr (PHASE != PHASE_ENV) {
 #pragma unroll
-  for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
-  load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
+    for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
+    load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
+  }
   __syncthreads();
 
   // envs of this workgroup: [blk0, blk0 + envs_per_block); of this wave: EPW of them
@@ -167,6 +176,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 
   const int64_t m0 = env0 * N;  // first trajectory row of this wave
   int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % NBUF
+  float checksum[NB] = {};      // PHASE_MLP only
 
   for (int t = 0; t <= a.T; ++t) {
     // ---------------- observation rows: build, store, convert to MFMA operands
@@ -198,7 +208,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             f[2 * pi + 1] = o.y;
           }
           const int f0 = 16 * kt + 8 * h;
-          if (valid[q]) {
+          if (valid[q] && PHASE != PHASE_MLP) {
             if constexpr (D % 4 == 0) {
               if (f0 + 4 <= D) *(float4*)(orow + f0) = make_float4(f[0], f[1], f[2], f[3]);
               if (f0 + 8 <= D) *(float4*)(orow + f0 + 4) = make_float4(f[4], f[5], f[6], f[7]);
@@ -217,7 +227,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           float2 o = make_float2(0.0f, 0.0f);
           if (2 * mm < D) {
             o = pair_value(mm);
-            if (valid[q] && (mm & 1) == h) *(float2*)(orow + 2 * mm) = o;
+            if (valid[q] && (mm & 1) == h && PHASE != PHASE_MLP) *(float2*)(orow + 2 * mm) = o;
           }
           x[q][mm] = h ? o.y : o.x;
           if (2 * mm == D) x[q][mm] = h ? 0.0f : 1.0f;  // input D carries the bias
@@ -227,7 +237,10 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 
     // ---------------- networks: policy, then value; chunk blocks come through the LDS window
     f32x16 out_p[NB], out_v[NB];
-    {
+    if constexpr (PHASE == PHASE_ENV) {
+#pragma unroll
+      for (int q = 0; q < NB; ++q) out_p[q] = out_v[q] = zero16();
+    } else {
       Op h1[NB][Net::KT2 * Net::PT];
 #pragma unroll
       for (int net = 0; net < 2; ++net) {
@@ -263,6 +276,12 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           ++gs;
         }
       }
+    }
+    if constexpr (PHASE == PHASE_MLP) {
+#pragma unroll
+      for (int q = 0; q < NB; ++q)
+        checksum[q] += out_v[q][0] + out_p[q][0] + out_p[q][1] + out_p[q][2] + out_p[q][3];
+      continue;
     }
 #pragma unroll
     for (int q = 0; q < NB; ++q)
@@ -348,7 +367,13 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     wave_lds_sync();
   }
 
-  ws.wait_all();  // copies issued ahead for stages that will not run
+  if constexpr (PHASE != PHASE_ENV) ws.wait_all();  // copies issued ahead for stages that will not run
+  if constexpr (PHASE == PHASE_MLP) {
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+      if (valid[q]) a.rewards[m0 + row[q]] = checksum[q];
+    return;  // the env state did not move
+  }
 
   // ---------------- write the env state back
 #pragma unroll

@@ -87,3 +87,51 @@ def test_argument_errors():
         B.msrl_rollout_step(gpu.state, gpu.params, 4, out)
         torch.cuda.synchronize()
         assert int(out["dones"].max()) <= 1
+
+
+@pytest.mark.parametrize("which", ["f32_small", "bf16_big"])
+def test_env_phase_equals_the_full_kernel_with_zero_parameters(which):
+    # the measurement variant that skips the networks must be the rollout an all-zero parameter
+    # buffer gives: logits 0, values 0, uniform categorical draws
+    import torch
+    if which == "f32_small":
+        cfg = synth.CONFIGS[1].with_(num_envs=53, episode_len=7)
+    else:
+        cfg = synth.CONFIGS[5].with_(num_envs=100, T=12, episode_len=5)
+    T = 12
+    zeros = np.zeros(cfg.param_count, dtype=np.float32)
+    with GpuRollout(cfg, zeros, 21) as gpu:
+        full = gpu.run(T, gae=False, logits=True)
+    with GpuRollout(cfg, zeros, 21) as gpu:
+        B = gpu.B
+        dev = B.alloc_traj(cfg, T, logits=True, gae=False)
+        B.msrl_measure_phase(gpu.state, gpu.params, T, dev, B.MSRL_PHASE_ENV)
+        torch.cuda.synchronize()
+        _, g = gpu.get_state()
+        env_only = {k: (None if v is None else v.cpu().numpy()) for k, v in dev.items()}
+    assert (g == T).all()
+    for k in ("obs", "actions", "logp", "rewards", "dones", "values", "logits"):
+        np.testing.assert_array_equal(full[k], env_only[k])
+    assert (env_only["logits"] == 0).all() and (env_only["values"] == 0).all()
+    np.testing.assert_allclose(env_only["logp"], np.log(0.2), rtol=1e-6)
+
+
+def test_mlp_phase_leaves_the_state_alone():
+    import torch
+    cfg = synth.CONFIGS[5].with_(num_envs=60, T=6)
+    _, _, params, _ = oracle_setup(cfg)
+    with GpuRollout(cfg, params.astype(np.float32), 3) as gpu:
+        B = gpu.B
+        es0, g0 = gpu.get_state()
+        dev = B.alloc_traj(cfg, 6, logits=False, gae=False)
+        B.msrl_measure_phase(gpu.state, gpu.params, 6, dev, B.MSRL_PHASE_MLP)
+        torch.cuda.synchronize()
+        es1, g1 = gpu.get_state()
+        assert bool(torch.isfinite(dev["rewards"][0]).all())
+    np.testing.assert_array_equal(es0, es1)
+    np.testing.assert_array_equal(g0, g1)
+    with GpuRollout(synth.CONFIGS[2].with_(num_envs=8), np.zeros(synth.CONFIGS[2].param_count, np.float32), 1) as gpu:
+        dev = gpu.B.alloc_traj(gpu.cfg, 2, gae=False)
+        with pytest.raises(gpu.B.MsrlError) as e:   # not compiled for this configuration
+            gpu.B.msrl_measure_phase(gpu.state, gpu.params, 2, dev, gpu.B.MSRL_PHASE_MLP)
+        assert e.value.code == gpu.B.MSRL_EUNSUPPORTED
