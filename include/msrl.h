@@ -72,6 +72,9 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   -(number of unordered agent pairs closer than 2*radius).  Observation of
  *   agent i, obs_dim = 4 + 2*num_landmarks + 4*(num_agents-1) floats:
  *   [v, p, landmark_k - p (k ascending), p_j - p (j != i ascending), zeros].
+ *   The 2*(num_agents-1) trailing slots are zero by construction; the kernels
+ *   store them but leave the matching rows of W1 out of the contraction, so a
+ *   non-finite weight in those rows does not reach the outputs.
  *   Reset draws every agent and landmark position uniform in [-1,1)^2, v = 0.
  *   act_dim is ignored.  The compiled kernels need num_landmarks == num_agents.
  * MSRL_ENV_LINGAUSS: num_agents = 1, num_landmarks = 0, state = observation of

@@ -302,9 +302,17 @@ struct WeightStream {
     // every wave issues exactly PER_WAVE copies per stage
     int t = wave + i * WAVES;
     t = t < STAGE_TILES ? t : 0;
-    const uint8_t* g = src + (size_t)t * 1024 + (size_t)lane * 16;
-    const uint32_t m0 = __builtin_amdgcn_readfirstlane(base + (uint32_t)t * 1024u);
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0) : "memory", "m0");
+    // Scalar base address + per-lane byte offset: no vector registers are tied up by addresses.
+    // `wave` must be wave-uniform (the kernels read it with readfirstlane), so both the source
+    // address and the LDS address are scalar values.  The s_nop covers the wait states the
+    // hardware wants between a write of M0 (or of a scalar address register by a vector
+    // instruction) and the memory instruction that reads it, which the compiler cannot insert
+    // inside an asm block.
+    const uint64_t sbase = (uint64_t)(uintptr_t)(src + (size_t)t * 1024);
+    const uint32_t m0 = base + (uint32_t)t * 1024u;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane * 16), "s"(sbase),
+                 "s"(m0)
+                 : "memory", "m0");
   }
   __device__ __forceinline__ void issue(int s, int buf) const {
 #pragma unroll

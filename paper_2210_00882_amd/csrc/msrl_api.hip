@@ -38,6 +38,7 @@ struct msrl_state {
   NetLayout layout;
   KernelEntry kernel;
   int envs_per_block;    // envs owned by one workgroup
+  int in_used;           // leading observation features that can be non-zero (inputs of layer 1)
 };
 
 namespace {
@@ -159,9 +160,10 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     const uint8_t* b2 = W2 + (size_t)p.hidden * p.hidden * esz;
     const uint8_t* W3 = b2 + (size_t)p.hidden * esz;
     const uint8_t* b3 = W3 + (size_t)p.hidden * out * esz;
-    PackJob j1 = weight_job(W1, dst + L.w1, bf16, p.in_dim, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
-    j1.bias = b1;  // the bias is input number in_dim; the kernels feed 1 there
-    j1.bias_index = p.in_dim;
+    // only the inputs that can be non-zero are packed (a prefix of the rows of W1)
+    PackJob j1 = weight_job(W1, dst + L.w1, bf16, st->in_used, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
+    j1.bias = b1;  // the bias is the input after them; the kernels feed 1 there
+    j1.bias_index = st->in_used;
     jobs.job[jobs.n++] = j1;
     // chunk block uc: kt2 layer-2 tiles of chunk uc, its bias tile, the tpc layer-3 tiles fed by
     // chunk uc-1, the tpc layer-3 tiles fed by chunk uc
@@ -314,6 +316,10 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
     int cus = 256;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
       cus = prop.multiProcessorCount;
+    int per_cu = 1;  // workgroups of this kernel that fit one compute unit together
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, found.fn, 64 * found.waves, 0) == hipSuccess &&
+        per_cu > 1)
+      cus *= per_cu;
     const int64_t max_epb = (int64_t)found.envs_per_wave * found.waves;
     const int64_t blocks_max = (env->num_envs + max_epb - 1) / max_epb;
     const int64_t rounds = (blocks_max + cus - 1) / cus;
@@ -323,7 +329,9 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
     st->envs_per_block = (int)epb;
   }
   st->state_size = (int)msrl_env_state_size(env);
-  st->layout = net_layout(policy->in_dim, policy->hidden, policy->dtype == MSRL_BF16);
+  // The particle observation ends in 2 (N - 1) slots that are always zero: layer 1 skips them.
+  st->in_used = env->kind == MSRL_ENV_PARTICLE ? 4 * env->num_agents + 2 : policy->in_dim;
+  st->layout = net_layout(st->in_used, policy->hidden, policy->dtype == MSRL_BF16);
 
   int rc = MSRL_OK;
   auto cleanup = [&](int code) {

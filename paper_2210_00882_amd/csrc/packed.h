@@ -28,7 +28,7 @@
 // tile when there is room, for layer 2 it opens one extra tile.
 //
 // One network =
-//   [layer-1 tiles (uc major, kt minor), nuc * kt1 tiles, kt1 = tiles(in_dim + 1)]
+//   [layer-1 tiles (uc major, kt minor), nuc * kt1 tiles, kt1 = tiles(in_used + 1)]
 //   [chunk block uc = 0 .. nuc-1], each kt2 + 1 + 2 tpc tiles:
 //       kt2 layer-2 tiles of the 32-unit chunk uc, 1 bias tile of chunk uc,
 //       tpc = kt2/nuc layer-3 tiles that consume the outputs of chunk uc-1
@@ -64,9 +64,10 @@ __host__ __device__ inline int tiles_for_inputs(int n_in, bool bf16) {
   return bf16 ? (n_in + 15) / 16 : (n_in + 7) / 8;
 }
 
-__host__ __device__ inline NetLayout net_layout(int in_dim, int hidden, bool bf16) {
+// in_used: number of leading inputs of layer 1 that are packed (the rest are known to be zero)
+__host__ __device__ inline NetLayout net_layout(int in_used, int hidden, bool bf16) {
   NetLayout L;
-  L.kt1 = tiles_for_inputs(in_dim + 1, bf16);
+  L.kt1 = tiles_for_inputs(in_used + 1, bf16);
   L.kt2 = tiles_for_inputs(hidden, bf16);
   L.nuc = hidden / 32;
   L.tpc = L.kt2 / L.nuc;

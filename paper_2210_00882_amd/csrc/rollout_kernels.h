@@ -6,14 +6,22 @@
 // registers / LDS: per step it builds the observation rows, stores them, runs
 // both networks on MFMA (mlp.h), samples the action with Philox, moves the
 // environment, computes reward and done, resets finished episodes and stores
-// the step's trajectory entries.  The waves of a workgroup share only the
-// weight stream: the network parameters pass through a double-buffered LDS
-// window, one barrier per stage, and every wave multiplies its own rows with
-// the stage that is resident.
+// the step's trajectory entries.  The waves of a workgroup share the weight
+// stream (the network parameters pass through a double-buffered LDS window, one
+// barrier per stage, and every wave multiplies its own rows with the stage that
+// is resident) and the way out of the per-row outputs.
 //
 // Row <-> lane mapping: a wave handles 32*NB rows; row 32*q + n lives on lanes n
 // and n + 32 (the two k-halves of the MFMA operands).  Both lanes keep a copy of
-// the row's state and execute the same arithmetic; lane n does the stores.
+// the row's state and execute the same arithmetic.
+//
+// Stores.  A store instruction whose 64 lanes hit 64 different cache lines costs
+// the memory pipeline about as much as 64 stores, and a cache line written in
+// pieces by different waves reaches HBM in pieces.  So nothing is stored in row
+// layout: observation rows pass through a per-wave LDS staging area and leave as
+// consecutive 16-byte pieces of the wave's contiguous block, and the per-row
+// scalars (value, action, logp, reward, done) of all waves are collected in LDS
+// and written by one wave per array, after a barrier of the following step.
 #pragma once
 #include "dev_common.h"
 #include "mlp.h"
@@ -100,23 +108,52 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int L = N;
   constexpr int D = 6 * N;
   constexpr int S = 4 * N + 2 * L;
-  constexpr int KT1 = BF16 ? (D + 1 + 15) / 16 : (D + 1 + 7) / 8;  // + the constant-1 input that carries the bias
+  // Only the first NZ observation features can be non-zero (the remaining 2(N-1) are the zero
+  // padding of the layout), so layer 1 contracts over NZ inputs plus the constant 1 that carries
+  // the bias, which sits at input index NZ.
+  constexpr int NZ = 4 * N + 2;
+  constexpr int KT1 = BF16 ? (NZ + 1 + 15) / 16 : (NZ + 1 + 7) / 8;
   constexpr int NBUF = 2;             // LDS window: the stage in use and the one being copied
   constexpr int CPS = BF16 && H >= 64 ? 2 : 1;  // chunk blocks per stage (fewer barriers when they fit)
   typedef Mlp<H, BF16, NB, KT1> Net;
   typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   typedef typename Net::Op Op;
   static_assert(EPW >= 1, "a wave must hold at least one env");
+  static_assert(NB == 1, "the observation staging below assumes one 32-row block per wave");
 
-  __shared__ __attribute__((aligned(16))) u32x4 s_l1[2][Net::L1_TILES * 64];  // resident layer-1 tiles
-  __shared__ __attribute__((aligned(16))) u32x4 s_w[NBUF * Stream::BUF_SLOTS];  // chunk-block window
+  // Observation rows leave through a per-wave LDS staging area: the lanes write their features
+  // in row layout, then the wave stores the same bytes as consecutive 16-byte (8-byte when D is
+  // not a multiple of 4) pieces, so that one store instruction covers whole cache lines instead
+  // of 64 separate rows.  SE envs (SR rows) are staged per pass.
+  constexpr int SE = EPW * N * D * 4 <= 4608 ? EPW : (3072 / (N * D * 4) >= 1 ? 3072 / (N * D * 4) : 1);
+  constexpr int SR = SE * N;
+  constexpr int PASSES = (EPW + SE - 1) / SE;
+  constexpr int PW = D % 4 == 0 ? 4 : 2;  // floats per piece
+  constexpr int STG = PHASE == PHASE_MLP ? 4 : SR * D;
+
+  // (the env-only measurement variant holds no weights, so that as many of its workgroups fit a CU
+  // as its registers allow)
+  constexpr int L1_SLOTS = PHASE == PHASE_ENV ? 1 : Net::L1_TILES * 64;
+  constexpr int W_SLOTS = PHASE == PHASE_ENV ? 1 : NBUF * Stream::BUF_SLOTS;
+  __shared__ __attribute__((aligned(16))) u32x4 s_l1[2][L1_SLOTS];  // resident layer-1 tiles
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[W_SLOTS];       // chunk-block window
   __shared__ __attribute__((aligned(16))) float s_b3[2][32];
+  __shared__ __attribute__((aligned(16))) float s_stg[WAVES][STG];
   __shared__ float2 s_tab[WAVES][2 * ROWS];  // [0,ROWS) landmarks, [ROWS,2ROWS) agents
-  __shared__ float s_part[WAVES][2 * ROWS];
+  // Per-row outputs of a step (value, action, logp, reward, done) are collected for the whole
+  // workgroup and written one array per wave after the next barrier: WAVES * VR consecutive rows
+  // per store instead of VR, so that all but the edge cache lines are written whole.
+  constexpr int WGR = PHASE == PHASE_MLP ? 1 : WAVES * VR;
+  constexpr int PF = D < (BF16 ? 16 : 8) * KT1 ? D : (BF16 ? 16 : 8) * KT1;  // features every write fills
+  constexpr bool PART_IN_STG = PF >= 32 && SR >= 2 && PHASE != PHASE_MLP && H >= 256;
+  __shared__ float s_part[WAVES][PART_IN_STG ? 1 : 2 * ROWS];
+  __shared__ float s_out[4][WGR];
+  __shared__ __attribute__((aligned(4))) uint8_t s_done[WGR];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: lives in a scalar register
   const int n = lane & 31, h = lane >> 5;
-  const NetLayout ly = net_layout(D, H, BF16);
+  const NetLayout ly = net_layout(NZ, H, BF16);
   Stream ws;
   ws.lds = s_w;
   ws.packed = a.packed;
@@ -130,6 +167,8 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
     load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
   }
+  // features the lanes never write (>= the layer-1 tile range) stay zero for the whole kernel
+  for (int i = threadIdx.x; i < WAVES * STG; i += blockDim.x) (&s_stg[0][0])[i] = 0.0f;
   __syncthreads();
 
   // envs of this workgroup: [blk0, blk0 + envs_per_block); of this wave: EPW of them
@@ -137,7 +176,15 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   const int64_t blk_end = min(blk0 + (int64_t)a.envs_per_block, (int64_t)a.E);
   const int64_t env0 = blk0 + (int64_t)wave * EPW;
   float2* tab = s_tab[wave];
-  float* part = s_part[wave];
+  float* stg = s_stg[wave];
+  // Reward partials (2 x 32 floats, used only between the env move and the end of the step): when the
+  // LDS is full they live in staging positions that the next observation write fills again (the
+  // first 32 features of staging rows 0 and 1), otherwise in an array of their own.
+  float* part0 = PART_IN_STG ? stg : s_part[wave];
+  float* part1 = PART_IN_STG ? stg + D : s_part[wave] + ROWS;
+  // rows of this wave that hold an env (the same for every lane)
+  const int live_rows =
+      __builtin_amdgcn_readfirstlane((int)max((int64_t)0, min((int64_t)EPW, blk_end - env0))) * N;
 
   int row[NB], base[NB], ag[NB];
   uint32_t env[NB];
@@ -175,15 +222,46 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   wave_lds_sync();
 
   const int64_t m0 = env0 * N;  // first trajectory row of this wave
+  const int wrow0 = wave * VR;  // ... and its first row within the workgroup
+  // stores the collected per-row outputs of step ts (only the values if !all); array k goes out
+  // through wave k % WAVES, 64 consecutive rows per store instruction
+  auto flush = [&](int ts, bool all) {
+    const int wg_rows = __builtin_amdgcn_readfirstlane((int)(blk_end - blk0)) * N;
+    const size_t o0 = (size_t)ts * a.M + (size_t)blk0 * N;
+    constexpr int J = (WGR + 63) / 64;
+    for (int arr = wave; arr < (all ? 5 : 1); arr += WAVES) {
+      if (arr < 4) {
+        float vv[J];
+#pragma unroll
+        for (int j = 0; j < J; ++j) vv[j] = s_out[arr][min(lane + 64 * j, WGR - 1)];
+        float* dst = arr == 0 ? a.values : arr == 1 ? (float*)a.actions : arr == 2 ? a.logp : a.rewards;
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+          if (lane + 64 * j < wg_rows) dst[o0 + lane + 64 * j] = vv[j];
+      } else {
+        uint8_t vv[J];
+#pragma unroll
+        for (int j = 0; j < J; ++j) vv[j] = s_done[min(lane + 64 * j, WGR - 1)];
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+          if (lane + 64 * j < wg_rows) a.dones[o0 + lane + 64 * j] = vv[j];
+      }
+    }
+  };
+
   int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % NBUF
   float checksum[NB] = {};      // PHASE_MLP only
 
   for (int t = 0; t <= a.T; ++t) {
-    // ---------------- observation rows: build, store, convert to MFMA operands
+    if constexpr (PHASE == PHASE_ENV) {  // (no stage barriers in this variant)
+      __syncthreads();
+      if (t > 0) flush(t - 1, true);
+      __syncthreads();
+    }
+    // ---------------- observation rows: build, store (through the staging area), convert to MFMA operands
     Op x[NB][KT1 * Net::PT];
-#pragma unroll
-    for (int q = 0; q < NB; ++q) {
-      float* orow = a.obs + ((size_t)t * a.M + m0 + row[q]) * D;
+    {
+      constexpr int q = 0;
       auto pair_value = [&](int gp) -> float2 {
         // pair 0: v, 1: p, [2, 2+L): landmark - p, [2+L, 1+L+N): other agent - p, rest 0
         const int jj = gp - 2 - L;
@@ -197,40 +275,70 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         if (gp == 0) o = v[q];
         return o;
       };
+      // pairs this lane contributes to the stored row: bf16 tiles hold 4 consecutive pairs per lane,
+      // f32 tiles hold pair mm on both half-waves, of which half-wave mm % 2 stores it
+      constexpr int NP = BF16 ? 4 * KT1 : 2 * KT1;
+      float2 pr[NP];
+      if constexpr (BF16) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) pr[i] = pair_value(8 * (i / 4) + 4 * h + i % 4);
+      } else {
+#pragma unroll
+        for (int mm = 0; mm < KT1 * 4; ++mm) {
+          const float2 o = pair_value(mm);
+          if ((mm & 1) == 0) pr[mm / 2] = o;
+          if ((mm & 1) == 1 && h == 1) pr[mm / 2] = o;
+          x[q][mm] = h ? o.y : o.x;
+          if (2 * mm == NZ) x[q][mm] = h ? 0.0f : 1.0f;  // input NZ carries the bias
+        }
+      }
+      // feature index of pr[i]
+      auto feat = [&](int i) { return BF16 ? 16 * (i / 4) + 8 * h + 2 * (i % 4) : 4 * i + 2 * h; };
+      if constexpr (PHASE != PHASE_MLP) {
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+          const int r0 = ps * SR;
+          const int lr = row[q] - r0;
+          if (valid[q] && lr >= 0 && lr < SR) {
+            float* dst = stg + lr * D;
+            if constexpr (BF16 && D % 4 == 0) {
+#pragma unroll
+              for (int i = 0; i < NP; i += 2)
+                if (feat(i) + 4 <= D)
+                  *(float4*)(dst + feat(i)) = make_float4(pr[i].x, pr[i].y, pr[i + 1].x, pr[i + 1].y);
+            } else {
+#pragma unroll
+              for (int i = 0; i < NP; ++i)
+                if (feat(i) + 2 <= D) *(float2*)(dst + feat(i)) = pr[i];
+            }
+          }
+          wave_lds_sync();
+          const int pieces = min(SR, live_rows - r0) * (D / PW);
+          float* gdst = a.obs + ((size_t)t * a.M + m0 + r0) * D;
+#pragma unroll
+          for (int j = 0; j * 64 < SR * (D / PW); ++j) {
+            const int i = j * 64 + lane;
+            if (i < pieces) {
+              if constexpr (PW == 4)
+                *(float4*)(gdst + 4 * i) = *(const float4*)(stg + 4 * i);
+              else
+                *(float2*)(gdst + 2 * i) = *(const float2*)(stg + 2 * i);
+            }
+          }
+          wave_lds_sync();
+        }
+      }
       if constexpr (BF16) {
 #pragma unroll
         for (int kt = 0; kt < KT1; ++kt) {
           f32x8 f;
 #pragma unroll
           for (int pi = 0; pi < 4; ++pi) {
-            const float2 o = pair_value(8 * kt + 4 * h + pi);
-            f[2 * pi] = o.x;
-            f[2 * pi + 1] = o.y;
+            f[2 * pi] = pr[4 * kt + pi].x;
+            f[2 * pi + 1] = pr[4 * kt + pi].y;
           }
-          const int f0 = 16 * kt + 8 * h;
-          if (valid[q] && PHASE != PHASE_MLP) {
-            if constexpr (D % 4 == 0) {
-              if (f0 + 4 <= D) *(float4*)(orow + f0) = make_float4(f[0], f[1], f[2], f[3]);
-              if (f0 + 8 <= D) *(float4*)(orow + f0 + 4) = make_float4(f[4], f[5], f[6], f[7]);
-            } else {
-#pragma unroll
-              for (int pi = 0; pi < 4; ++pi)
-                if (f0 + 2 * pi + 2 <= D) *(float2*)(orow + f0 + 2 * pi) = make_float2(f[2 * pi], f[2 * pi + 1]);
-            }
-          }
-          if (D / 16 == kt && (D % 16) / 8 == h) f[D % 8] = 1.0f;  // input D carries the bias
+          if (NZ / 16 == kt && (NZ % 16) / 8 == h) f[NZ % 8] = 1.0f;  // input NZ carries the bias
           x[q][kt] = __builtin_convertvector(f, bf16x8);
-        }
-      } else {
-#pragma unroll
-        for (int mm = 0; mm < KT1 * 4; ++mm) {
-          float2 o = make_float2(0.0f, 0.0f);
-          if (2 * mm < D) {
-            o = pair_value(mm);
-            if (valid[q] && (mm & 1) == h && PHASE != PHASE_MLP) *(float2*)(orow + 2 * mm) = o;
-          }
-          x[q][mm] = h ? o.y : o.x;
-          if (2 * mm == D) x[q][mm] = h ? 0.0f : 1.0f;  // input D carries the bias
         }
       }
     }
@@ -245,6 +353,12 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 #pragma unroll
       for (int net = 0; net < 2; ++net) {
         f32x16(&out)[NB] = net == 0 ? out_p : out_v;
+        // The first stage of a network landed long ago, so its barrier can come before layer 1.
+        // At the value network's, every wave has left the previous step long since and the store
+        // path is idle (the observation stores went out at the start of the step): the collected
+        // per-row outputs of the previous step go out here.
+        ws.wait_oldest();
+        if (PHASE == PHASE_ALL && net == 1 && t > 0) flush(t - 1, true);
         Net::layer1(&s_l1[net][0] + lane, x, h1);
         {
           const f32x16 b = bias_init(s_b3[net], h);
@@ -254,7 +368,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         f32x16 acc[NB];
 #pragma unroll 1
         for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
-          ws.wait_oldest();
+          if (sc != 0) ws.wait_oldest();
           int next = net * Stream::STAGES_PER_NET + sc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
           if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
           const int nbuf = (gs + Stream::AHEAD) % NBUF;
@@ -285,7 +399,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     }
 #pragma unroll
     for (int q = 0; q < NB; ++q)
-      if (h == 0 && valid[q]) a.values[(size_t)t * a.M + m0 + row[q]] = out_v[q][0];
+      if (h == 0 && valid[q]) s_out[0][wrow0 + row[q]] = out_v[q][0];
     if (t == a.T) break;
 
     // ---------------- sampling, physics
@@ -307,8 +421,8 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       action[q] = act;
       const size_t o = (size_t)t * a.M + m0 + row[q];
       if (h == 0 && valid[q]) {
-        ((int32_t*)a.actions)[o] = act;
-        a.logp[o] = lp;
+        s_out[1][wrow0 + row[q]] = __int_as_float(act);
+        s_out[2][wrow0 + row[q]] = lp;
         if (a.logits) {
 #pragma unroll
           for (int k = 0; k < 5; ++k) a.logits[o * 5 + k] = l[k];
@@ -337,18 +451,17 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         if (j > ag[q] && dxa * dxa + dya * dya < a.coll2) cnt += 1.0f;
       }
       rew_term[q] = h ? -cnt : -__builtin_amdgcn_sqrtf(mn);
-      if (valid[q]) part[h * ROWS + base[q] + ag[q]] = rew_term[q];
+      if (valid[q]) (h ? part1 : part0)[base[q] + ag[q]] = rew_term[q];
     }
     wave_lds_sync();
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
       float r = 0.0f;
-      for (int j = 0; j < N; ++j) r += part[base[q] + j] + part[ROWS + base[q] + j];
+      for (int j = 0; j < N; ++j) r += part0[base[q] + j] + part1[base[q] + j];
       const bool done = tau[q] + 1 == a.ep;
-      const size_t o = (size_t)t * a.M + m0 + row[q];
       if (h == 0 && valid[q]) {
-        a.rewards[o] = r;
-        a.dones[o] = done ? 1 : 0;
+        s_out[3][wrow0 + row[q]] = r;
+        s_done[wrow0 + row[q]] = done ? 1 : 0;
       }
       g32[q] += 1;
       tau[q] = done ? 0 : tau[q] + 1;
@@ -368,6 +481,8 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   }
 
   if constexpr (PHASE != PHASE_ENV) ws.wait_all();  // copies issued ahead for stages that will not run
+  if constexpr (PHASE == PHASE_ENV) __syncthreads();
+  if constexpr (PHASE != PHASE_MLP) flush(a.T, false);  // values[T]; every earlier step went out inside the loop
   if constexpr (PHASE == PHASE_MLP) {
 #pragma unroll
     for (int q = 0; q < NB; ++q)
@@ -409,7 +524,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   __shared__ __attribute__((aligned(16))) u32x4 s_w[NBUF * Stream::BUF_SLOTS];
   __shared__ __attribute__((aligned(16))) float s_b3[2][32];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: lives in a scalar register
   const int n = lane & 31, h = lane >> 5;
   const NetLayout ly = net_layout(D, H, false);
   Stream ws;
