@@ -129,9 +129,8 @@ __device__ __forceinline__ void to_operands(const float (&t)[16], typename Opera
 }
 
 // Software pipeline inside a wave: while the MFMAs of chunk c run, the VALU applies tanh to the
-// accumulators of chunk c-1, so both pipes are busy from one instruction stream.  The pipeline runs
-// on across the layer boundary (the last chunk of layer 1 is activated under the first chunk of
-// layer 2); in a layer-2 stage the layer-3 MFMAs of chunk c-1 follow.
+// accumulators of chunk c-1, so both pipes are busy from one instruction stream.  In a layer-2
+// stage the layer-3 MFMAs of chunk c-1 follow.
 template <int H, bool BF16, int NB, int KT1>
 struct Mlp {
   typedef typename Operand<BF16>::T Op;
@@ -155,30 +154,30 @@ struct Mlp {
   }
 
   // Layer 1.  tiles: this lane's slot of tile 0 in LDS (tile t is at tiles[64 t]); x holds the
-  // observation with the constant 1 at the bias input.  Fills the h1 operands of all unit chunks but
-  // the last, whose pre-activations are returned in `last`: the first layer-2 stage activates them
-  // while its own MFMAs run (they feed the last tiles of its contraction).
+  // observation with the constant 1 at input index in_dim.
   __device__ static __forceinline__ void layer1(const u32x4* tiles, const Op (&x)[NB][KT1 * PT],
-                                                Op (&h1)[NB][KT2 * PT], f32x16 (&last)[NB]) {
+                                                Op (&h1)[NB][KT2 * PT]) {
     u32x4 ring[G];
 #pragma unroll
     for (int i = 0; i < G && i < L1_TILES; ++i) ring[i] = tiles[i * 64];
     f32x16 prev[NB];
 #pragma unroll
-    for (int uc = 0; uc < NUC; ++uc) {
+    for (int uc = 0; uc <= NUC; ++uc) {
       f32x16 acc[NB];
       float t[NB][16];
 #pragma unroll
       for (int q = 0; q < NB; ++q) acc[q] = zero16();
 #pragma unroll
       for (int kt = 0; kt < KT1; ++kt) {
-        const int idx = uc * KT1 + kt;
-        const u32x4 raw = ring[idx % G];
-        if (idx + G < L1_TILES) ring[idx % G] = tiles[(idx + G) * 64];
+        if (uc < NUC) {
+          const int idx = uc * KT1 + kt;
+          const u32x4 raw = ring[idx % G];
+          if (idx + G < L1_TILES) ring[idx % G] = tiles[(idx + G) * 64];
 #pragma unroll
-        for (int q = 0; q < NB; ++q) {
-          mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
-          if (uc > 0) pin(acc[q]);
+          for (int q = 0; q < NB; ++q) {
+            mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
+            if (uc > 0) pin(acc[q]);
+          }
         }
         if (uc > 0) tanh_slice<KT1>(prev, t, kt);
       }
@@ -189,25 +188,16 @@ struct Mlp {
 #pragma unroll
       for (int q = 0; q < NB; ++q) prev[q] = acc[q];
     }
-#pragma unroll
-    for (int q = 0; q < NB; ++q) last[q] = prev[q];
   }
 
-  // Stage of chunk uc: acc <- layer-2 pre-activations of chunk uc, while the VALU activates what
-  // `acc` holds on entry:
-  //   FIRST  the last unit chunk of layer 1 -> the last TAIL operand tiles of h1, finished before
-  //          the contraction reaches them;
-  //   PIPE   chunk uc-1 of layer 2 -> h2, which the layer-3 tiles of this stage consume.
+  // Stage of chunk uc: acc <- layer-2 pre-activations of chunk uc; if PIPE, `acc` holds those of
+  // chunk uc-1 on entry, which get tanh and feed layer 3 meanwhile.
   // tick(kt) is called once per layer-2 tile: the caller spreads the copies of a later stage over
   // the loop, so that they queue behind the MFMAs instead of stalling every wave at the stage start.
-  enum : int { FIRST = 0, PIPE = 1 };
-  static constexpr int TAIL = PC / PT;  // h1 tiles fed by one unit chunk
-  static_assert(KT2 > TAIL, "the hidden layer must span at least two 32-unit chunks");
-  template <int MODE, class Tick>
-  __device__ static __forceinline__ void layer2_chunk(const u32x4* tiles, Op (&h1)[NB][KT2 * PT],
+  template <bool PIPE, class Tick>
+  __device__ static __forceinline__ void layer2_chunk(const u32x4* tiles, const Op (&h1)[NB][KT2 * PT],
                                                       f32x16 (&acc)[NB], f32x16 (&out)[NB], int h,
                                                       Tick&& tick) {
-    constexpr int NT = MODE == FIRST ? KT2 - TAIL : KT2;  // tiles the activation is spread over
     u32x4 ring[G];
 #pragma unroll
     for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
@@ -225,13 +215,9 @@ struct Mlp {
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
         mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
-        if (kt < NT) pin(acc[q]);
+        if (PIPE) pin(acc[q]);
       }
-      if (kt < NT) tanh_slice<NT>(prev, t, kt);
-      if (MODE == FIRST && kt == NT - 1) {
-#pragma unroll
-        for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], &h1[q][(NUC - 1) * PC]);
-      }
+      if (PIPE) tanh_slice<KT2>(prev, t, kt);
       tick(kt);
     }
     {
@@ -241,7 +227,7 @@ struct Mlp {
 #pragma unroll
       for (int q = 0; q < NB; ++q) mma_bias_tile<BF16>(raw, one, acc[q]);
     }
-    if (MODE == PIPE) {
+    if (PIPE) {
       Op h2[NB][PC];
 #pragma unroll
       for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], h2[q]);
@@ -316,16 +302,19 @@ struct WeightStream {
     // every wave issues exactly PER_WAVE copies per stage
     int t = wave + i * WAVES;
     t = t < STAGE_TILES ? t : 0;
-    // Scalar base address + per-lane byte offset: no vector registers are tied up by addresses.
-    // `wave` must be wave-uniform (the kernels read it with readfirstlane), so both the source
-    // address and the LDS address are scalar values.  The s_nop covers the wait states the
-    // hardware wants between a write of M0 (or of a scalar address register by a vector
-    // instruction) and the memory instruction that reads it, which the compiler cannot insert
-    // inside an asm block.
+    // Scalar base address + per-lane byte offset: no vector registers are tied up by addresses
+    // (`wave` must be wave-uniform; the kernels read it with readfirstlane).  The address is copied
+    // by a scalar instruction inside the asm block: that is the one wait state the hardware wants
+    // between the write of M0 and the copy instruction, and it makes the address register
+    // scalar-written whatever produced the operand (a memory instruction may not read a scalar
+    // register a vector instruction wrote less than 5 cycles earlier, and the compiler cannot
+    // see into the block to keep that distance).
     const uint64_t sbase = (uint64_t)(uintptr_t)(src + (size_t)t * 1024);
     const uint32_t m0 = base + (uint32_t)t * 1024u;
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane * 16), "s"(sbase),
-                 "s"(m0)
+    uint64_t tmp;
+    asm volatile("s_mov_b32 m0, %3\n\ts_mov_b64 %0, %2\n\tglobal_load_lds_dwordx4 %1, %0"
+                 : "=&s"(tmp)
+                 : "v"(lane * 16), "s"(sbase), "s"(m0)
                  : "memory", "m0");
   }
   __device__ __forceinline__ void issue(int s, int buf) const {

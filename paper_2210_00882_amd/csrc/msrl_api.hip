@@ -308,18 +308,15 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   st->seed = seed;
   st->kernel = found;
   {
-    // Every workgroup runs all T steps, so the launch takes ceil(blocks / resident) rounds.  Shrink the
+    // Every workgroup runs all T steps, so the launch takes ceil(blocks / CUs) rounds.  Shrink the
     // block to the smallest size that needs no more rounds than the largest one: equal work per
-    // workgroup instead of a short last round.
+    // workgroup instead of a short last round.  (Rounds are counted per CU even where several
+    // workgroups fit one: they would share its SIMDs, and a wave with fewer rows costs the same.)
     hipDeviceProp_t prop;
     int dev = 0;
     int cus = 256;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
       cus = prop.multiProcessorCount;
-    int per_cu = 1;  // workgroups of this kernel that fit one compute unit together
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, found.fn, 64 * found.waves, 0) == hipSuccess &&
-        per_cu > 1)
-      cus *= per_cu;
     const int64_t max_epb = (int64_t)found.envs_per_wave * found.waves;
     const int64_t blocks_max = (env->num_envs + max_epb - 1) / max_epb;
     const int64_t rounds = (blocks_max + cus - 1) / cus;

@@ -359,8 +359,8 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         // per-row outputs of the previous step go out here.
         ws.wait_oldest();
         if (PHASE == PHASE_ALL && net == 1 && t > 0) flush(t - 1, true);
+        Net::layer1(&s_l1[net][0] + lane, x, h1);
         f32x16 acc[NB];
-        Net::layer1(&s_l1[net][0] + lane, x, h1, acc);
         {
           const f32x16 b = bias_init(s_b3[net], h);
 #pragma unroll
@@ -382,9 +382,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
                 if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
             };
             if (c == 0 && sc == 0)
-              Net::template layer2_chunk<Net::FIRST>(tiles, h1, acc, out, h, tick);
+              Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
             else
-              Net::template layer2_chunk<Net::PIPE>(tiles, h1, acc, out, h, tick);
+              Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
             if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
           }
           ++gs;
@@ -585,8 +585,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
 #pragma unroll
       for (int net = 0; net < 2; ++net) {
         f32x16(&out)[1] = net == 0 ? out_p : out_v;
+        Net::layer1(&s_l1[net][0] + lane, x, h1);
         f32x16 acc[1];
-        Net::layer1(&s_l1[net][0] + lane, x, h1, acc);
         out[0] = bias_init(s_b3[net], h);
 #pragma unroll 1
         for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
@@ -604,9 +604,9 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
                 if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
             };
             if (c == 0 && sc == 0)
-              Net::template layer2_chunk<Net::FIRST>(tiles, h1, acc, out, h, tick);
+              Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
             else
-              Net::template layer2_chunk<Net::PIPE>(tiles, h1, acc, out, h, tick);
+              Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
             if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
           }
           ++gs;
