@@ -189,6 +189,27 @@ def main():
                 phases[name] = {"bound": "mfma", "ms_per_launch": ms, "achieved": tf, "peak": PEAK_TFLOPS[dt_name],
                                 "unit": "TFLOP/s", "frac": tf / PEAK_TFLOPS[dt_name]}
 
+        # in-kernel clocks of the fused kernel: where one step of one workgroup spends its cycles
+        stamps = torch.zeros(1024, dtype=torch.float32, device="cuda")
+        try:
+            B.msrl_measure_phase(state, dparams, T, dict(out, logits=stamps), B.MSRL_PHASE_CLOCKS)
+            torch.cuda.synchronize()
+            c = stamps[:256].cpu().numpy().reshape(8, 32)
+            names = {1: "obs_build_store", 2: "policy_layer1", 3: "policy_stage0", 4: "policy_stage1",
+                     5: "policy_stage2", 6: "policy_stage3", 8: "value_layer1", 9: "value_stage0",
+                     10: "value_stage1", 11: "value_stage2", 12: "value_stage3", 14: "outputs",
+                     15: "sample_move", 16: "reward_done_reset"}
+            order = sorted(names)
+            mean = c.mean(0)
+            prev, split = 0.0, {}
+            for i in order:
+                split[names[i]] = float(mean[i] - prev)
+                prev = float(mean[i])
+            phases["clocks"] = {"unit": "shader-clock cycles, mean over the 8 waves of workgroup 0, step T/2",
+                                "step_total": prev, "split": split}
+        except B.MsrlError:
+            pass  # variant not compiled for this configuration
+
     if args.copy_calibration:
         n = args.copy_calibration * (1 << 20) // 4
         src = torch.ones(n, dtype=torch.float32, device="cuda")

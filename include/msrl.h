@@ -192,9 +192,18 @@ int msrl_rollout_gae(msrl_state* st, const void* params, int32_t T,
  *   MSRL_PHASE_MLP: T evaluations of both networks on the observation of the
  *     current state; no env step, no state change.  The contents of `out` are
  *     unspecified afterwards (only rewards[0, :] is written, with a checksum).
+ *   MSRL_PHASE_CLOCKS: the full rollout (every output of msrl_rollout_step is
+ *     written, the state advances), except that out->logits, which must not be
+ *     NULL and needs room for 32 floats per wave of a workgroup (256 floats
+ *     suffice), receives no logits but clock stamps: for each wave w of the
+ *     first workgroup, float 32*w + i is the number of shader-clock cycles from
+ *     the start of step T/2 to the end of phase i of that step, with i = 1
+ *     observation rows built and stored, 2 policy layer 1, 3..6 policy weight
+ *     stages, 8 value layer 1, 9..12 value weight stages, 14 logits and values
+ *     ready, 15 sampling and move, 16 end of step (reward, done, reset).
  * EUNSUPPORTED if the variant was not compiled for the state's configuration.
  */
-typedef enum { MSRL_PHASE_ENV = 1, MSRL_PHASE_MLP = 2 } msrl_phase;
+typedef enum { MSRL_PHASE_ENV = 1, MSRL_PHASE_MLP = 2, MSRL_PHASE_CLOCKS = 3 } msrl_phase;
 int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj* out,
                        int32_t phase, void* hip_stream);
 

@@ -17,7 +17,7 @@ MSRL_OK, MSRL_EINVAL, MSRL_ENOMEM, MSRL_EDEVICE, MSRL_EUNSUPPORTED = 0, -1, -2, 
 MSRL_ENV_PARTICLE, MSRL_ENV_LINGAUSS = 0, 1
 MSRL_F32, MSRL_BF16 = 0, 1
 MSRL_CATEGORICAL, MSRL_DIAG_GAUSSIAN = 0, 1
-MSRL_PHASE_ENV, MSRL_PHASE_MLP = 1, 2
+MSRL_PHASE_ENV, MSRL_PHASE_MLP, MSRL_PHASE_CLOCKS = 1, 2, 3
 
 EXPORTS = (
     "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",

@@ -64,7 +64,8 @@ int fail(int code, const char* fmt, ...) {
 std::vector<KernelEntry> all_kernels() {
   return {entry_p1_h64_f32(),  entry_p2_h64_f32(),    entry_p3_h64_f32(), entry_p3_h64_bf16(),
           entry_p6_h128_f32(), entry_p10_h256_bf16(), entry_l17_6_h256(),
-          entry_p10_h256_bf16_env(), entry_p10_h256_bf16_mlp(), entry_p3_h64_f32_env()};
+          entry_p10_h256_bf16_env(), entry_p10_h256_bf16_mlp(), entry_p10_h256_bf16_clocks(),
+          entry_p3_h64_f32_env()};
 }
 
 bool valid_policy(const msrl_policy_cfg* p) {
@@ -427,10 +428,12 @@ int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj*
                        void* hip_stream) {
   if (!st || !params) return fail(MSRL_EINVAL, "msrl_measure_phase: NULL argument");
   if (T <= 0) return fail(MSRL_EINVAL, "msrl_measure_phase: T must be positive (got %d)", T);
-  if (phase != MSRL_PHASE_ENV && phase != MSRL_PHASE_MLP)
+  if (phase != MSRL_PHASE_ENV && phase != MSRL_PHASE_MLP && phase != MSRL_PHASE_CLOCKS)
     return fail(MSRL_EINVAL, "msrl_measure_phase: unknown phase %d", phase);
   int rc = check_traj(st, out, false);
   if (rc != MSRL_OK) return rc;
+  if (phase == MSRL_PHASE_CLOCKS && !out->logits)
+    return fail(MSRL_EINVAL, "msrl_measure_phase: the clock stamps go to out->logits, which is NULL");
   KernelEntry k;
   if (!find_kernel(st->env, st->pol, phase, &k))
     return fail(MSRL_EUNSUPPORTED, "msrl_measure_phase: phase %d is not compiled for this configuration", phase);

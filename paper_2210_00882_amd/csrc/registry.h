@@ -43,6 +43,7 @@ KernelEntry entry_l17_6_h256();
 // measurement variants (phase rooflines)
 KernelEntry entry_p10_h256_bf16_env();
 KernelEntry entry_p10_h256_bf16_mlp();
+KernelEntry entry_p10_h256_bf16_clocks();
 KernelEntry entry_p3_h64_f32_env();
 
 }  // namespace msrl

@@ -97,7 +97,16 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 //              buffer gives, so every output is still defined and checked against the full kernel;
 //   PHASE_MLP  T evaluations of both networks on the current observation, no env step and no
 //              trajectory stores (a checksum of the outputs goes to rewards[0, :] to keep them live).
-enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2 };
+//   PHASE_CLOCKS  the full kernel; in addition lane 0 of every wave of workgroup 0 reads the shader
+//              clock at the phase boundaries of step T/2 and writes the cycles since the start of
+//              that step to the logits buffer (which then holds no logits): wave w, stamp i at
+//              float 32 w + i, i = CLK_* below.
+enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3 };
+// stamps: start of the step, observation rows built and stored, policy layer 1 done (after the
+// stage barrier that precedes it), policy stage s done (s < 5), same for the value network,
+// logits and values ready, sampling and move done, end of the step
+enum : int { CLK_START = 0, CLK_OBS = 1, CLK_P_L1 = 2, CLK_P_STAGE = 3, CLK_V_L1 = 8, CLK_V_STAGE = 9,
+             CLK_NETS = 14, CLK_SAMPLE = 15, CLK_END = 16, CLK_COUNT = 17 };
 
 // ------------------------------------------------------------------ particle env
 template <int N, int H, bool BF16, int NB, int WAVES, int PHASE = PHASE_ALL>
@@ -119,6 +128,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   typedef typename Net::Op Op;
   static_assert(EPW >= 1, "a wave must hold at least one env");
+  constexpr bool FULL = PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS;
   static_assert(NB == 1, "the observation staging below assumes one 32-row block per wave");
 
   // Observation rows leave through a per-wave LDS staging area: the lanes write their features
@@ -252,7 +262,18 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % NBUF
   float checksum[NB] = {};      // PHASE_MLP only
 
+  long long clk0 = 0;
   for (int t = 0; t <= a.T; ++t) {
+    auto stamp = [&](int i) {
+      if constexpr (PHASE == PHASE_CLOCKS) {
+        if (blockIdx.x == 0 && t == a.T / 2 && lane == 0) {
+          const long long now = clock64();
+          if (i == CLK_START) clk0 = now;
+          a.logits[32 * wave + i] = (float)(now - clk0);
+        }
+      }
+    };
+    stamp(CLK_START);
     if constexpr (PHASE == PHASE_ENV) {  // (no stage barriers in this variant)
       __syncthreads();
       if (t > 0) flush(t - 1, true);
@@ -343,6 +364,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       }
     }
 
+    stamp(CLK_OBS);
     // ---------------- networks: policy, then value; chunk blocks come through the LDS window
     f32x16 out_p[NB], out_v[NB];
     if constexpr (PHASE == PHASE_ENV) {
@@ -358,8 +380,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         // path is idle (the observation stores went out at the start of the step): the collected
         // per-row outputs of the previous step go out here.
         ws.wait_oldest();
-        if (PHASE == PHASE_ALL && net == 1 && t > 0) flush(t - 1, true);
+        if (FULL && net == 1 && t > 0) flush(t - 1, true);
         Net::layer1(&s_l1[net][0] + lane, x, h1);
+        stamp(net == 0 ? CLK_P_L1 : CLK_V_L1);
         f32x16 acc[NB];
         {
           const f32x16 b = bias_init(s_b3[net], h);
@@ -388,9 +411,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
           }
           ++gs;
+          if (sc < 5) stamp((net == 0 ? CLK_P_STAGE : CLK_V_STAGE) + sc);
         }
       }
     }
+    stamp(CLK_NETS);
     if constexpr (PHASE == PHASE_MLP) {
 #pragma unroll
       for (int q = 0; q < NB; ++q)
@@ -423,7 +448,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       if (h == 0 && valid[q]) {
         s_out[1][wrow0 + row[q]] = __int_as_float(act);
         s_out[2][wrow0 + row[q]] = lp;
-        if (a.logits) {
+        if (PHASE != PHASE_CLOCKS && a.logits) {
 #pragma unroll
           for (int k = 0; k < 5; ++k) a.logits[o * 5 + k] = l[k];
         }
@@ -437,6 +462,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       if (h == 0 && valid[q]) tab[ROWS + base[q] + ag[q]] = p[q];
     }
     wave_lds_sync();
+    stamp(CLK_SAMPLE);
 
     // ---------------- shared reward: lane h = 0 takes landmark ag, lane h = 1 the collisions of agent ag
 #pragma unroll
@@ -478,6 +504,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       }
     }
     wave_lds_sync();
+    stamp(CLK_END);
   }
 
   if constexpr (PHASE != PHASE_ENV) ws.wait_all();  // copies issued ahead for stages that will not run

@@ -135,3 +135,30 @@ def test_mlp_phase_leaves_the_state_alone():
         with pytest.raises(gpu.B.MsrlError) as e:   # not compiled for this configuration
             gpu.B.msrl_measure_phase(gpu.state, gpu.params, 2, dev, gpu.B.MSRL_PHASE_MLP)
         assert e.value.code == gpu.B.MSRL_EUNSUPPORTED
+
+
+def test_clock_variant_computes_the_same_rollout():
+    # the variant that also records in-kernel clocks must write every output of the plain kernel,
+    # and monotonically increasing stamps for the waves of the first workgroup
+    import torch
+    cfg = synth.CONFIGS[5].with_(num_envs=100, T=8, episode_len=5)
+    T = 8
+    _, _, params, _ = oracle_setup(cfg)
+    with GpuRollout(cfg, params.astype(np.float32), 9) as gpu:
+        plain = gpu.run(T, gae=False, logits=False)
+    with GpuRollout(cfg, params.astype(np.float32), 9) as gpu:
+        B = gpu.B
+        dev = B.alloc_traj(cfg, T, logits=False, gae=False)
+        with pytest.raises(B.MsrlError) as e:           # the stamps need a buffer
+            B.msrl_measure_phase(gpu.state, gpu.params, T, dev, B.MSRL_PHASE_CLOCKS)
+        assert e.value.code == B.MSRL_EINVAL
+        stamps = torch.zeros(256, dtype=torch.float32, device="cuda")
+        B.msrl_measure_phase(gpu.state, gpu.params, T, dict(dev, logits=stamps), B.MSRL_PHASE_CLOCKS)
+        torch.cuda.synchronize()
+        timed = {k: v.cpu().numpy() for k, v in dev.items() if v is not None}
+        c = stamps.cpu().numpy().reshape(8, 32)
+    for k in ("obs", "actions", "logp", "rewards", "dones", "values"):
+        np.testing.assert_array_equal(plain[k], timed[k])
+    order = [0, 1, 2, 3, 4, 5, 6, 8, 9, 10, 11, 12, 14, 15, 16]
+    assert (np.diff(c[:, order], axis=1) > 0).all()
+    assert (c[:, 16] < 5e6).all()
