@@ -90,8 +90,11 @@ __device__ __forceinline__ f32x16 bias_init(const float* lds_bias, int h) {
 // puts all MFMAs of a block first and all tanh work last, so nothing overlaps inside a wave.  An
 // empty volatile asm on a value fixes the point in program order where the value must exist; the
 // pins keep "MFMAs of tile k, tanh slice k, MFMAs of tile k+1, ..." in the order written below.
+// The MFMAs are held in place through their weight tile, not through the accumulator: where the
+// compiler keeps accumulators in the accumulation registers, a pin on one would cost a round trip
+// through vector registers and a wait for the matrix pipe at every tile.
 __device__ __forceinline__ void pin(float& v) { asm volatile("" : "+v"(v)); }
-__device__ __forceinline__ void pin(f32x16& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin(u32x4& v) { asm volatile("" : "+v"(v)); }
 
 // tanh of accumulator registers [r0, r1) of a 32-unit chunk into a scratch array.  When pinned,
 // the whole group is computed between two pins, so it stays between the neighbouring MFMAs.
@@ -171,13 +174,11 @@ struct Mlp {
       for (int kt = 0; kt < KT1; ++kt) {
         if (uc < NUC) {
           const int idx = uc * KT1 + kt;
-          const u32x4 raw = ring[idx % G];
+          u32x4 raw = ring[idx % G];
           if (idx + G < L1_TILES) ring[idx % G] = tiles[(idx + G) * 64];
+          if (uc > 0) pin(raw);
 #pragma unroll
-          for (int q = 0; q < NB; ++q) {
-            mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
-            if (uc > 0) pin(acc[q]);
-          }
+          for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
         }
         if (uc > 0) tanh_slice<KT1>(prev, t, kt);
       }
@@ -210,13 +211,11 @@ struct Mlp {
     }
 #pragma unroll
     for (int kt = 0; kt < KT2; ++kt) {
-      const u32x4 raw = ring[kt % G];
+      u32x4 raw = ring[kt % G];
       if (kt + G < L3_PREV + TPC) ring[kt % G] = tiles[(kt + G) * 64];
+      if (PIPE) pin(raw);
 #pragma unroll
-      for (int q = 0; q < NB; ++q) {
-        mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
-        if (PIPE) pin(acc[q]);
-      }
+      for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
       if (PIPE) tanh_slice<KT2>(prev, t, kt);
       tick(kt);
     }
