@@ -189,6 +189,38 @@ def main():
                 phases[name] = {"bound": "mfma", "ms_per_launch": ms, "achieved": tf, "peak": PEAK_TFLOPS[dt_name],
                                 "unit": "TFLOP/s", "frac": tf / PEAK_TFLOPS[dt_name]}
 
+        # the step-granular calls (actor fragment, environment fragment) at the same batch size
+        try:
+            obs1 = torch.empty((M, cfg.obs_dim), dtype=torch.float32, device="cuda")
+            B.msrl_observe(state, obs1)
+            a1, lp1, v1 = out["actions"][0], out["logp"][0], out["values"][0]
+            r1, d1 = out["rewards"][0], out["dones"][0]
+            reps = 10
+            for name in ("act", "env_step"):
+                ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                for k in range(reps + 1):
+                    if k == 1:
+                        ev0.record()
+                    if name == "act":
+                        B.msrl_act(state, dparams, obs1, a1, lp1, v1)
+                    else:
+                        B.msrl_env_step(state, a1, r1, d1, obs1)
+                ev1.record()
+                torch.cuda.synchronize()
+                ms = ev0.elapsed_time(ev1) / reps
+                if name == "act":
+                    tf = mlp_flops_per_agent_step(cfg) * M / (ms * 1e-3) / 1e12
+                    phases[name] = {"bound": "mfma", "ms_per_call": ms, "achieved": tf, "peak": PEAK_TFLOPS[dt_name],
+                                    "unit": "TFLOP/s", "frac": tf / PEAK_TFLOPS[dt_name], "rows": M}
+                else:
+                    act_b = 4 if cfg.dist == 0 else 4 * cfg.act_dim
+                    state_b = 8 * (cfg.env_state_size + 2) / cfg.num_agents   # state + counter, read and written
+                    gbs = (4 * cfg.obs_dim + act_b + 5 + state_b) * M / (ms * 1e-3) / 1e9
+                    phases[name] = {"bound": "hbm", "ms_per_call": ms, "achieved": gbs, "peak": PEAK_HBM_GBS,
+                                    "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "rows": M}
+        except B.MsrlError:
+            pass
+
         # in-kernel clocks of the fused kernel: where one step of one workgroup spends its cycles
         stamps = torch.zeros(1024, dtype=torch.float32, device="cuda")
         try:

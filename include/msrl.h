@@ -208,6 +208,34 @@ int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj*
                        int32_t phase, void* hip_stream);
 
 /*
+ * Step-granular calls: the two halves of Actor.act (Listing 1) as calls of their
+ * own, for deployments that keep actor and environment in different fragments
+ * (distribution policies DP-A and DP-B of section 6, Table 2, run the policy
+ * inference as a device fragment and the environment elsewhere; the dedicated
+ * environment fragments of the evaluation do the opposite).  All pointers DEVICE.
+ *
+ *   msrl_observe   obs [M, D] <- observation of the current state.
+ *   msrl_act       both networks and the sampling on the rows of `obs` [M, D]:
+ *                  actions (int32 [M] or float [M, act_dim]), logp [M], values
+ *                  [M], optional logits [M, out_dim].  The noise is the one msrl_rollout_step would
+ *                  draw at the state's step counters; the state is not changed.
+ *                  The rows must be observations of this env kind: for the
+ *                  particle env the 2*(num_agents-1) trailing slots are taken to
+ *                  be zero (they are not multiplied).
+ *   msrl_env_step  applies `actions` (one step of msrl_traj.actions: int32 [M],
+ *                  values outside 0..4 move nothing; or float [M, act_dim]):
+ *                  move, reward, done, reset, step counters + 1; rewards [M],
+ *                  dones [M], next_obs [M, D] = observation of the new state.
+ * T repetitions of { act on the current observation; env_step } produce exactly
+ * the trajectory of one msrl_rollout_step(T) call.
+ */
+int msrl_observe(msrl_state* st, float* obs, void* hip_stream);
+int msrl_act(msrl_state* st, const void* params, const float* obs, void* actions,
+             float* logp, float* values, float* logits, void* hip_stream);
+int msrl_env_step(msrl_state* st, const void* actions, float* rewards, uint8_t* dones,
+                  float* next_obs, void* hip_stream);
+
+/*
  * Snapshot / restore of the env batch.  env_state: HOST
  * [num_envs, msrl_env_state_size] floats; step_counters: HOST [num_envs] int64
  * (only the low 32 bits enter the Philox counter).  Either pointer may be NULL

@@ -21,7 +21,7 @@ MSRL_PHASE_ENV, MSRL_PHASE_MLP, MSRL_PHASE_CLOCKS = 1, 2, 3
 
 EXPORTS = (
     "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",
-    "msrl_rollout_gae", "msrl_measure_phase", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
+    "msrl_rollout_gae", "msrl_measure_phase", "msrl_observe", "msrl_act", "msrl_env_step", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
 )
 
 
@@ -80,6 +80,12 @@ def load():
     lib.msrl_rollout_gae.argtypes = [vp, vp, i32, f32, f32, C.POINTER(msrl_traj), vp]
     lib.msrl_measure_phase.restype = C.c_int
     lib.msrl_measure_phase.argtypes = [vp, vp, i32, C.POINTER(msrl_traj), i32, vp]
+    lib.msrl_observe.restype = C.c_int
+    lib.msrl_observe.argtypes = [vp, vp, vp]
+    lib.msrl_act.restype = C.c_int
+    lib.msrl_act.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.msrl_env_step.restype = C.c_int
+    lib.msrl_env_step.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.msrl_state_get.restype = C.c_int
     lib.msrl_state_get.argtypes = [vp, vp, vp]
     lib.msrl_state_set.restype = C.c_int
@@ -184,6 +190,20 @@ def msrl_measure_phase(state, params, T: int, out: dict, phase: int, stream=None
     tr = _traj(out)
     _check(load().msrl_measure_phase(state, _ptr(params), C.c_int32(T), C.byref(tr), C.c_int32(phase),
                                      _stream(stream)))
+
+
+def msrl_observe(state, obs, stream=None) -> None:
+    _check(load().msrl_observe(state, _ptr(obs), _stream(stream)))
+
+
+def msrl_act(state, params, obs, actions, logp, values, logits=None, stream=None) -> None:
+    _check(load().msrl_act(state, _ptr(params), _ptr(obs), _ptr(actions), _ptr(logp), _ptr(values),
+                           _ptr(logits), _stream(stream)))
+
+
+def msrl_env_step(state, actions, rewards, dones, next_obs, stream=None) -> None:
+    _check(load().msrl_env_step(state, _ptr(actions), _ptr(rewards), _ptr(dones), _ptr(next_obs),
+                                _stream(stream)))
 
 
 def msrl_state_get(state, num_envs: int, state_size: int):

@@ -65,7 +65,14 @@ std::vector<KernelEntry> all_kernels() {
   return {entry_p1_h64_f32(),  entry_p2_h64_f32(),    entry_p3_h64_f32(), entry_p3_h64_bf16(),
           entry_p6_h128_f32(), entry_p10_h256_bf16(), entry_l17_6_h256(),
           entry_p10_h256_bf16_env(), entry_p10_h256_bf16_mlp(), entry_p10_h256_bf16_clocks(),
-          entry_p3_h64_f32_env()};
+          entry_p3_h64_f32_env(),
+          entry_l17_6_h256_act(), entry_l17_6_h256_step(),
+          entry_p1_h64_f32_act(), entry_p1_h64_f32_step(),
+          entry_p2_h64_f32_act(), entry_p2_h64_f32_step(),
+          entry_p3_h64_f32_act(), entry_p3_h64_f32_step(),
+          entry_p3_h64_bf16_act(), entry_p3_h64_bf16_step(),
+          entry_p6_h128_f32_act(), entry_p6_h128_f32_step(),
+          entry_p10_h256_bf16_act(), entry_p10_h256_bf16_step()};
 }
 
 bool valid_policy(const msrl_policy_cfg* p) {
@@ -217,10 +224,14 @@ bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase,
   return false;
 }
 
+// params may be null for the variants that run no network; obs_in / actions_in feed the
+// step-granular variants
 int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* params, int32_t T, msrl_traj* out,
-                    hipStream_t stream) {
-  int rc = pack_params(st, params, stream);
-  if (rc != MSRL_OK) return rc;
+                    hipStream_t stream, const float* obs_in = nullptr, const void* actions_in = nullptr) {
+  if (params) {
+    int rc = pack_params(st, params, stream);
+    if (rc != MSRL_OK) return rc;
+  }
   RolloutArgs a;
   memset(&a, 0, sizeof(a));
   a.env_state = st->env_state;
@@ -246,6 +257,8 @@ int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* param
   a.values = out->values;
   a.logits = out->logits;
   a.M = (int64_t)st->env.num_envs * st->env.num_agents;
+  a.obs_in = obs_in;
+  a.actions_in = actions_in;
   a.envs_per_block = st->envs_per_block;
   const int64_t blocks = ((int64_t)a.E + a.envs_per_block - 1) / a.envs_per_block;
   void* args[] = {&a};
@@ -438,6 +451,48 @@ int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj*
   if (!find_kernel(st->env, st->pol, phase, &k))
     return fail(MSRL_EUNSUPPORTED, "msrl_measure_phase: phase %d is not compiled for this configuration", phase);
   return enqueue_rollout(st, k, params, T, out, (hipStream_t)hip_stream);
+}
+
+int msrl_observe(msrl_state* st, float* obs, void* hip_stream) {
+  if (!st || !obs) return fail(MSRL_EINVAL, "msrl_observe: NULL argument");
+  KernelEntry k;
+  if (!find_kernel(st->env, st->pol, PHASE_STEP, &k))
+    return fail(MSRL_EUNSUPPORTED, "msrl_observe: not compiled for this configuration");
+  msrl_traj out;
+  memset(&out, 0, sizeof(out));
+  out.obs = obs;
+  return enqueue_rollout(st, k, nullptr, 0, &out, (hipStream_t)hip_stream);
+}
+
+int msrl_act(msrl_state* st, const void* params, const float* obs, void* actions, float* logp, float* values,
+             float* logits, void* hip_stream) {
+  if (!st || !params || !obs || !actions || !logp || !values)
+    return fail(MSRL_EINVAL, "msrl_act: NULL argument");
+  KernelEntry k;
+  if (!find_kernel(st->env, st->pol, PHASE_ACT, &k))
+    return fail(MSRL_EUNSUPPORTED, "msrl_act: not compiled for this configuration");
+  msrl_traj out;
+  memset(&out, 0, sizeof(out));
+  out.actions = actions;
+  out.logp = logp;
+  out.values = values;
+  out.logits = logits;
+  return enqueue_rollout(st, k, params, 0, &out, (hipStream_t)hip_stream, obs, nullptr);
+}
+
+int msrl_env_step(msrl_state* st, const void* actions, float* rewards, uint8_t* dones, float* next_obs,
+                  void* hip_stream) {
+  if (!st || !actions || !rewards || !dones || !next_obs)
+    return fail(MSRL_EINVAL, "msrl_env_step: NULL argument");
+  KernelEntry k;
+  if (!find_kernel(st->env, st->pol, PHASE_STEP, &k))
+    return fail(MSRL_EUNSUPPORTED, "msrl_env_step: not compiled for this configuration");
+  msrl_traj out;
+  memset(&out, 0, sizeof(out));
+  out.obs = next_obs;
+  out.rewards = rewards;
+  out.dones = dones;
+  return enqueue_rollout(st, k, nullptr, 1, &out, (hipStream_t)hip_stream, nullptr, actions);
 }
 
 int msrl_state_get(msrl_state* st, float* env_state, int64_t* step_counters) {

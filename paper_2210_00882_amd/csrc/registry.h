@@ -27,11 +27,12 @@ struct KernelEntry {
 #define MSRL_PARTICLE_ENTRY(NAME, N, H, BF16, NB, WAVES) \
   MSRL_PARTICLE_ENTRY_PHASE(NAME, N, H, BF16, NB, WAVES, PHASE_ALL)
 
-#define MSRL_LINGAUSS_ENTRY(NAME, D, K, H, WAVES)                                          \
-  KernelEntry NAME() {                                                                     \
-    return KernelEntry{1, D, K, H, 0, (const void*)&lingauss_rollout_kernel<D, K, H, WAVES>, \
-                       32, WAVES, PHASE_ALL};                                              \
+#define MSRL_LINGAUSS_ENTRY_PHASE(NAME, D, K, H, WAVES, PHASE)                                    \
+  KernelEntry NAME() {                                                                            \
+    return KernelEntry{1, D, K, H, 0, (const void*)&lingauss_rollout_kernel<D, K, H, WAVES, PHASE>, \
+                       32, WAVES, PHASE};                                                         \
   }
+#define MSRL_LINGAUSS_ENTRY(NAME, D, K, H, WAVES) MSRL_LINGAUSS_ENTRY_PHASE(NAME, D, K, H, WAVES, PHASE_ALL)
 
 KernelEntry entry_p1_h64_f32();
 KernelEntry entry_p2_h64_f32();
@@ -45,5 +46,21 @@ KernelEntry entry_p10_h256_bf16_env();
 KernelEntry entry_p10_h256_bf16_mlp();
 KernelEntry entry_p10_h256_bf16_clocks();
 KernelEntry entry_p3_h64_f32_env();
+
+// step-granular variants (actor only, environment only)
+KernelEntry entry_l17_6_h256_act();
+KernelEntry entry_l17_6_h256_step();
+KernelEntry entry_p1_h64_f32_act();
+KernelEntry entry_p1_h64_f32_step();
+KernelEntry entry_p2_h64_f32_act();
+KernelEntry entry_p2_h64_f32_step();
+KernelEntry entry_p3_h64_f32_act();
+KernelEntry entry_p3_h64_f32_step();
+KernelEntry entry_p3_h64_bf16_act();
+KernelEntry entry_p3_h64_bf16_step();
+KernelEntry entry_p6_h128_f32_act();
+KernelEntry entry_p6_h128_f32_step();
+KernelEntry entry_p10_h256_bf16_act();
+KernelEntry entry_p10_h256_bf16_step();
 
 }  // namespace msrl

@@ -47,6 +47,8 @@ struct RolloutArgs {
   float* values;
   float* logits;  // may be null
   int64_t M;
+  const float* obs_in;     // PHASE_ACT: observation rows [M, D] to act on
+  const void* actions_in;  // PHASE_STEP: actions [M] to apply
 };
 
 // Copies the layer-1 tiles and the output biases of both packed networks into LDS (once per kernel).
@@ -101,7 +103,14 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 //              clock at the phase boundaries of step T/2 and writes the cycles since the start of
 //              that step to the logits buffer (which then holds no logits): wave w, stamp i at
 //              float 32 w + i, i = CLK_* below.
-enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3 };
+// The two halves of a step as kernels of their own (step-granular calls of the library):
+//   PHASE_ACT   both networks and the sampling on observation rows given by the caller (obs_in),
+//              with the noise the fused kernel would draw at the state's step counters; writes
+//              actions, logp, values (and logits); the state is not changed;
+//   PHASE_STEP  applies the caller's actions (actions_in) for T = 1: move, reward, done, reset,
+//              counters + 1; writes rewards[0], dones[0] and the observation of the new state to
+//              obs[0].  With T = 0 it only writes the observation of the current state.
+enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHASE_ACT = 4, PHASE_STEP = 5 };
 // stamps: start of the step, observation rows built and stored, policy layer 1 done (after the
 // stage barrier that precedes it), policy stage s done (s < 5), same for the value network,
 // logits and values ready, sampling and move done, end of the step
@@ -129,6 +138,8 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   typedef typename Net::Op Op;
   static_assert(EPW >= 1, "a wave must hold at least one env");
   constexpr bool FULL = PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS;
+  constexpr bool HAS_NETS = PHASE != PHASE_ENV && PHASE != PHASE_STEP;     // the variant runs the networks
+  constexpr bool STORES_OBS = PHASE != PHASE_MLP && PHASE != PHASE_ACT;    // ... stores observation rows
   static_assert(NB == 1, "the observation staging below assumes one 32-row block per wave");
 
   // Observation rows leave through a per-wave LDS staging area: the lanes write their features
@@ -139,12 +150,12 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int SR = SE * N;
   constexpr int PASSES = (EPW + SE - 1) / SE;
   constexpr int PW = D % 4 == 0 ? 4 : 2;  // floats per piece
-  constexpr int STG = PHASE == PHASE_MLP ? 4 : SR * D;
+  constexpr int STG = STORES_OBS ? SR * D : 4;
 
-  // (the env-only measurement variant holds no weights, so that as many of its workgroups fit a CU
-  // as its registers allow)
-  constexpr int L1_SLOTS = PHASE == PHASE_ENV ? 1 : Net::L1_TILES * 64;
-  constexpr int W_SLOTS = PHASE == PHASE_ENV ? 1 : NBUF * Stream::BUF_SLOTS;
+  // (the variants without networks hold no weights, so that as many of their workgroups fit a CU
+  // as their registers allow)
+  constexpr int L1_SLOTS = HAS_NETS ? Net::L1_TILES * 64 : 1;
+  constexpr int W_SLOTS = HAS_NETS ? NBUF * Stream::BUF_SLOTS : 1;
   __shared__ __attribute__((aligned(16))) u32x4 s_l1[2][L1_SLOTS];  // resident layer-1 tiles
   __shared__ __attribute__((aligned(16))) u32x4 s_w[W_SLOTS];       // chunk-block window
   __shared__ __attribute__((aligned(16))) float s_b3[2][32];
@@ -155,7 +166,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   // per store instead of VR, so that all but the edge cache lines are written whole.
   constexpr int WGR = PHASE == PHASE_MLP ? 1 : WAVES * VR;
   constexpr int PF = D < (BF16 ? 16 : 8) * KT1 ? D : (BF16 ? 16 : 8) * KT1;  // features every write fills
-  constexpr bool PART_IN_STG = PF >= 32 && SR >= 2 && PHASE != PHASE_MLP && H >= 256;
+  constexpr bool PART_IN_STG = PF >= 32 && SR >= 2 && STORES_OBS && H >= 256;
   __shared__ float s_part[WAVES][PART_IN_STG ? 1 : 2 * ROWS];
   __shared__ float s_out[4][WGR];
   __shared__ __attribute__((aligned(4))) uint8_t s_done[WGR];
@@ -172,7 +183,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   ws.chunk_bytes = ly.chunk_bytes;
   ws.wave = wave;
   ws.lane = lane;
-  if constexpr (PHASE != PHASE_ENV) {
+  if constexpr (HAS_NETS) {
 #pragma unroll
     for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
     load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
@@ -233,13 +244,15 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 
   const int64_t m0 = env0 * N;  // first trajectory row of this wave
   const int wrow0 = wave * VR;  // ... and its first row within the workgroup
-  // stores the collected per-row outputs of step ts (only the values if !all); array k goes out
-  // through wave k % WAVES, 64 consecutive rows per store instruction
-  auto flush = [&](int ts, bool all) {
+  // stores the collected per-row outputs of step ts; bit k of `arrays` selects array k (value,
+  // action, logp, reward, done), which goes out through wave k % WAVES, 64 consecutive rows per
+  // store instruction
+  auto flush = [&](int ts, int arrays) {
     const int wg_rows = __builtin_amdgcn_readfirstlane((int)(blk_end - blk0)) * N;
     const size_t o0 = (size_t)ts * a.M + (size_t)blk0 * N;
     constexpr int J = (WGR + 63) / 64;
-    for (int arr = wave; arr < (all ? 5 : 1); arr += WAVES) {
+    for (int arr = wave; arr < 5; arr += WAVES) {
+      if (!((arrays >> arr) & 1)) continue;
       if (arr < 4) {
         float vv[J];
 #pragma unroll
@@ -259,6 +272,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     }
   };
 
+
   int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % NBUF
   float checksum[NB] = {};      // PHASE_MLP only
 
@@ -274,9 +288,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       }
     };
     stamp(CLK_START);
-    if constexpr (PHASE == PHASE_ENV) {  // (no stage barriers in this variant)
+    if constexpr (!HAS_NETS) {  // (no stage barriers in these variants)
       __syncthreads();
-      if (t > 0) flush(t - 1, true);
+      if (t > 0) flush(t - 1, PHASE == PHASE_STEP ? 0x18 : 0x1f);
       __syncthreads();
     }
     // ---------------- observation rows: build, store (through the staging area), convert to MFMA operands
@@ -300,13 +314,28 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       // f32 tiles hold pair mm on both half-waves, of which half-wave mm % 2 stores it
       constexpr int NP = BF16 ? 4 * KT1 : 2 * KT1;
       float2 pr[NP];
-      if constexpr (BF16) {
+      // PHASE_ACT takes the pair from the caller's row instead (zero beyond the row and for idle rows)
+      auto pair_in = [&](int gp) -> float2 {
+        if constexpr (PHASE == PHASE_ACT) {
+          if (!valid[q] || 2 * gp + 2 > D) return make_float2(0.0f, 0.0f);
+          return *(const float2*)(a.obs_in + (size_t)(m0 + row[q]) * D + 2 * gp);
+        } else {
+          return pair_value(gp);
+        }
+      };
+      const bool build = PHASE != PHASE_STEP || t == a.T;  // PHASE_STEP needs rows only to store them
+      if (!build) {
 #pragma unroll
-        for (int i = 0; i < NP; ++i) pr[i] = pair_value(8 * (i / 4) + 4 * h + i % 4);
+        for (int i = 0; i < NP; ++i) pr[i] = make_float2(0.0f, 0.0f);
+#pragma unroll
+        for (int i = 0; i < KT1 * Net::PT; ++i) x[q][i] = Op{};
+      } else if constexpr (BF16) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) pr[i] = pair_in(8 * (i / 4) + 4 * h + i % 4);
       } else {
 #pragma unroll
         for (int mm = 0; mm < KT1 * 4; ++mm) {
-          const float2 o = pair_value(mm);
+          const float2 o = pair_in(mm);
           if ((mm & 1) == 0) pr[mm / 2] = o;
           if ((mm & 1) == 1 && h == 1) pr[mm / 2] = o;
           x[q][mm] = h ? o.y : o.x;
@@ -315,7 +344,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       }
       // feature index of pr[i]
       auto feat = [&](int i) { return BF16 ? 16 * (i / 4) + 8 * h + 2 * (i % 4) : 4 * i + 2 * h; };
-      if constexpr (PHASE != PHASE_MLP) {
+      if (STORES_OBS && build) {
 #pragma unroll
         for (int ps = 0; ps < PASSES; ++ps) {
           const int r0 = ps * SR;
@@ -335,7 +364,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           }
           wave_lds_sync();
           const int pieces = min(SR, live_rows - r0) * (D / PW);
-          float* gdst = a.obs + ((size_t)t * a.M + m0 + r0) * D;
+          float* gdst = a.obs + ((size_t)(PHASE == PHASE_STEP ? 0 : t) * a.M + m0 + r0) * D;
 #pragma unroll
           for (int j = 0; j * 64 < SR * (D / PW); ++j) {
             const int i = j * 64 + lane;
@@ -367,7 +396,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     stamp(CLK_OBS);
     // ---------------- networks: policy, then value; chunk blocks come through the LDS window
     f32x16 out_p[NB], out_v[NB];
-    if constexpr (PHASE == PHASE_ENV) {
+    if constexpr (!HAS_NETS) {
 #pragma unroll
       for (int q = 0; q < NB; ++q) out_p[q] = out_v[q] = zero16();
     } else {
@@ -380,7 +409,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         // path is idle (the observation stores went out at the start of the step): the collected
         // per-row outputs of the previous step go out here.
         ws.wait_oldest();
-        if (FULL && net == 1 && t > 0) flush(t - 1, true);
+        if (FULL && net == 1 && t > 0) flush(t - 1, 0x1f);
         Net::layer1(&s_l1[net][0] + lane, x, h1);
         stamp(net == 0 ? CLK_P_L1 : CLK_V_L1);
         f32x16 acc[NB];
@@ -425,7 +454,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 #pragma unroll
     for (int q = 0; q < NB; ++q)
       if (h == 0 && valid[q]) s_out[0][wrow0 + row[q]] = out_v[q][0];
-    if (t == a.T) break;
+    if (PHASE != PHASE_ACT && t == a.T) break;
 
     // ---------------- sampling, physics
     float rew_term[NB];
@@ -443,6 +472,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       int act;
       sample_categorical5(l, u01(w.w[0]), act, lp);
       act = __shfl(act, n);  // the h = 0 lane of the row decides
+      if constexpr (PHASE == PHASE_STEP) act = valid[q] ? ((const int32_t*)a.actions_in)[m0 + row[q]] : 0;
       action[q] = act;
       const size_t o = (size_t)t * a.M + m0 + row[q];
       if (h == 0 && valid[q]) {
@@ -463,6 +493,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     }
     wave_lds_sync();
     stamp(CLK_SAMPLE);
+    if constexpr (PHASE == PHASE_ACT) break;  // one evaluation, no move
 
     // ---------------- shared reward: lane h = 0 takes landmark ag, lane h = 1 the collisions of agent ag
 #pragma unroll
@@ -507,9 +538,14 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     stamp(CLK_END);
   }
 
-  if constexpr (PHASE != PHASE_ENV) ws.wait_all();  // copies issued ahead for stages that will not run
-  if constexpr (PHASE == PHASE_ENV) __syncthreads();
-  if constexpr (PHASE != PHASE_MLP) flush(a.T, false);  // values[T]; every earlier step went out inside the loop
+  if constexpr (HAS_NETS) ws.wait_all();  // copies issued ahead for stages that will not run
+  if constexpr (!HAS_NETS) __syncthreads();
+  if constexpr (PHASE == PHASE_ACT) {
+    flush(0, 0x07);  // values, actions, logp of the one evaluation
+    return;          // the env state did not move
+  }
+  if constexpr (PHASE != PHASE_MLP && PHASE != PHASE_STEP)
+    flush(a.T, 0x01);  // values[T]; every earlier step went out inside the loop
   if constexpr (PHASE == PHASE_MLP) {
 #pragma unroll
     for (int q = 0; q < NB; ++q)
@@ -538,8 +574,12 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 // State unit u of a row lives in accumulator layout: lane (n, h), register r with
 // u = 8*(r/4) + 4*h + r%4, so s' = A s + B a is one more MFMA chain on the same
 // registers and its result is already the next step's layer-1 operand.
-template <int D, int K, int H, int WAVES>
+// PHASE: PHASE_ALL, or one of the step-granular variants PHASE_ACT / PHASE_STEP (see above; here
+// actions_in is float [M, K]).
+template <int D, int K, int H, int WAVES, int PHASE = PHASE_ALL>
 __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArgs a) {
+  static_assert(PHASE == PHASE_ALL || PHASE == PHASE_ACT || PHASE == PHASE_STEP, "no measurement variants here");
+  constexpr bool HAS_NETS = PHASE != PHASE_STEP;
   constexpr int KT1 = (D + 1 + 7) / 8;  // + the constant-1 input that carries the bias
   constexpr int NR = 4 * KT1;           // state registers per lane
   constexpr int NBUF = 2, CPS = 1;
@@ -547,8 +587,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   static_assert(D <= 31 && K <= 8, "one MFMA chunk of state (plus the constant input), one tile of action");
 
-  __shared__ __attribute__((aligned(16))) u32x4 s_l1[2][Net::L1_TILES * 64];
-  __shared__ __attribute__((aligned(16))) u32x4 s_w[NBUF * Stream::BUF_SLOTS];
+  __shared__ __attribute__((aligned(16))) u32x4 s_l1[2][HAS_NETS ? Net::L1_TILES * 64 : 1];
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[HAS_NETS ? NBUF * Stream::BUF_SLOTS : 1];
   __shared__ __attribute__((aligned(16))) float s_b3[2][32];
 
   const int lane = threadIdx.x & 63;
@@ -563,9 +603,11 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   ws.chunk_bytes = ly.chunk_bytes;
   ws.wave = wave;
   ws.lane = lane;
+  if constexpr (HAS_NETS) {
 #pragma unroll
-  for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
-  load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
+    for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
+    load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
+  }
   __syncthreads();
 
   const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
@@ -584,7 +626,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
     const int u = 8 * (r >> 2) + 4 * h + (r & 3);
-    s[0][r] = u < D ? a.env_state[(size_t)env * D + u] : 0.0f;
+    const float* src = PHASE == PHASE_ACT ? a.obs_in : a.env_state;  // PHASE_ACT works on the caller's rows
+    s[0][r] = u < D ? src[(size_t)env * D + u] : 0.0f;
   }
   const int64_t g64 = a.g[env];
   uint32_t g32 = (uint32_t)g64;
@@ -593,15 +636,19 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
 
   for (int t = 0; t <= a.T; ++t) {
     const size_t o = (size_t)t * a.M + env;
-    if (valid) {
+    // PHASE_STEP writes one observation, that of the last state, to row block 0
+    if (valid && PHASE != PHASE_ACT && (PHASE != PHASE_STEP || t == a.T)) {
+      const size_t oo = PHASE == PHASE_STEP ? (size_t)env : o;
 #pragma unroll
       for (int r = 0; r < NR; ++r) {
         const int u = 8 * (r >> 2) + 4 * h + (r & 3);
-        if (u < D) a.obs[o * D + u] = s[0][r];
+        if (u < D) a.obs[oo * D + u] = s[0][r];
       }
     }
     f32x16 out_p[1], out_v[1];
-    {
+    if constexpr (!HAS_NETS) {
+      out_p[0] = out_v[0] = zero16();
+    } else {
       float h1[1][Net::KT2 * Net::PT];
       float x[1][NR];  // the state with the constant 1 at input D
 #pragma unroll
@@ -640,8 +687,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
         }
       }
     }
-    if (valid && h == 0) a.values[o] = out_v[0][0];
-    if (t == a.T) break;
+    if (valid && h == 0 && PHASE != PHASE_STEP) a.values[o] = out_v[0][0];
+    if (PHASE != PHASE_ACT && t == a.T) break;
 
     // action dims 4h + c: mean in register c, log-std in register 4 + c
     float eps[4], act[4], lp = 0.0f, cost = 0.0f;
@@ -653,9 +700,10 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
       act[c] = 0.0f;
       if (d < K) {
         act[c] = mean + __expf(logstd) * eps[c];
+        if constexpr (PHASE == PHASE_STEP) act[c] = valid ? ((const float*)a.actions_in)[(size_t)env * K + d] : 0.0f;
         lp += -0.5f * eps[c] * eps[c] - logstd - 0.9189385332046727f;
         cost += act[c] * act[c];
-        if (valid) {
+        if (valid && PHASE != PHASE_STEP) {
           ((float*)a.actions)[o * K + d] = act[c];
           if (a.logits) {
             a.logits[o * (2 * K) + d] = mean;
@@ -672,10 +720,13 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
     rew += __shfl_xor(rew, 32);
     const bool done = tau + 1 == a.ep;
     if (valid && h == 0) {
-      a.logp[o] = lp;
-      a.rewards[o] = -rew;
-      a.dones[o] = done ? 1 : 0;
+      if (PHASE != PHASE_STEP) a.logp[o] = lp;
+      if (PHASE != PHASE_ACT) {
+        a.rewards[o] = -rew;
+        a.dones[o] = done ? 1 : 0;
+      }
     }
+    if constexpr (PHASE == PHASE_ACT) break;  // one evaluation, no move
 
     // s' = A s + B a + noise_std * eps
     f32x16 acc;
@@ -701,7 +752,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
     if (done) episode += 1;
   }
 
-  ws.wait_all();  // copies issued ahead for stages that will not run
+  if constexpr (HAS_NETS) ws.wait_all();  // copies issued ahead for stages that will not run
+  if constexpr (PHASE == PHASE_ACT) return;  // the env state did not move
 
   if (valid) {
 #pragma unroll
