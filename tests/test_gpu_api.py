@@ -162,3 +162,35 @@ def test_clock_variant_computes_the_same_rollout():
     order = [0, 1, 2, 3, 4, 5, 6, 8, 9, 10, 11, 12, 14, 15, 16]
     assert (np.diff(c[:, order], axis=1) > 0).all()
     assert (c[:, 16] < 5e6).all()
+
+
+def test_fused_call_replays_from_a_hip_graph():
+    # the call enqueues kernels only (no allocation, no memset), so it can be captured once and
+    # replayed: replay k must equal the k-th eager call of a second, identical state
+    import torch
+    cfg = synth.CONFIGS[1].with_(num_envs=40, episode_len=4)
+    T = 6
+    _, _, params, _ = oracle_setup(cfg)
+    with GpuRollout(cfg, params.astype(np.float32), 13) as gpu:
+        eager = [gpu.run(T, gae=True, logits=False) for _ in range(4)]
+    with GpuRollout(cfg, params.astype(np.float32), 13) as gpu:
+        B = gpu.B
+        dev = B.alloc_traj(cfg, T, logits=False, gae=True)
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(stream):
+            B.msrl_rollout_gae(gpu.state, gpu.params, T, cfg.gamma, cfg.lam, dev, stream=stream)   # call 0, eager
+        stream.synchronize()
+        first = {k: v.cpu().numpy() for k, v in dev.items() if v is not None}
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            B.msrl_rollout_gae(gpu.state, gpu.params, T, cfg.gamma, cfg.lam, dev, stream=torch.cuda.current_stream())
+        for k in first:
+            np.testing.assert_array_equal(first[k], eager[0][k], err_msg=k)
+        for rep in range(1, 4):
+            graph.replay()
+            torch.cuda.synchronize()
+            got = {k: v.cpu().numpy() for k, v in dev.items() if v is not None}
+            for k in got:
+                np.testing.assert_array_equal(got[k], eager[rep][k], err_msg=f"{k} replay {rep}")
+            _ = torch.ones(1000, device="cuda").sum().item()   # unrelated eager work between replays
