@@ -495,17 +495,20 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     stamp(CLK_SAMPLE);
     if constexpr (PHASE == PHASE_ACT) break;  // one evaluation, no move
 
-    // ---------------- shared reward: lane h = 0 takes landmark ag, lane h = 1 the collisions of agent ag
+    // ---------------- shared reward: lane h = 0 takes landmark ag (distance of the nearest agent),
+    // lane h = 1 agent ag (collisions with the agents after it): one distance per lane and agent
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
       const float2 lm = tab[base[q] + ag[q]];
+      const float2 ref = h ? p[q] : lm;
       float mn = 3.0e38f, cnt = 0.0f;
+#pragma unroll
       for (int j = 0; j < N; ++j) {
         const float2 pj = tab[ROWS + base[q] + j];
-        const float dxl = pj.x - lm.x, dyl = pj.y - lm.y;
-        mn = fminf(mn, dxl * dxl + dyl * dyl);
-        const float dxa = pj.x - p[q].x, dya = pj.y - p[q].y;
-        if (j > ag[q] && dxa * dxa + dya * dya < a.coll2) cnt += 1.0f;
+        const float dx = pj.x - ref.x, dy = pj.y - ref.y;
+        const float d2 = dx * dx + dy * dy;
+        mn = fminf(mn, d2);
+        cnt += (j > ag[q] && d2 < a.coll2) ? 1.0f : 0.0f;
       }
       rew_term[q] = h ? -cnt : -__builtin_amdgcn_sqrtf(mn);
       if (valid[q]) (h ? part1 : part0)[base[q] + ag[q]] = rew_term[q];
@@ -513,8 +516,12 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     wave_lds_sync();
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
+      // each half-wave sums its own kind of term over the env's agents; the halves are then added
       float r = 0.0f;
-      for (int j = 0; j < N; ++j) r += part0[base[q] + j] + part1[base[q] + j];
+      const float* mine = h ? part1 : part0;
+#pragma unroll
+      for (int j = 0; j < N; ++j) r += mine[base[q] + j];
+      r += __shfl_xor(r, 32);
       const bool done = tau[q] + 1 == a.ep;
       if (h == 0 && valid[q]) {
         s_out[3][wrow0 + row[q]] = r;
