@@ -292,6 +292,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       __syncthreads();
       if (t > 0) flush(t - 1, PHASE == PHASE_STEP ? 0x18 : 0x1f);
       __syncthreads();
+    } else {
+      // The barrier of the policy network's first stage comes first in the step: its copies went out
+      // during the last stage of the step before, and the wait for them also waits for every store
+      // the wave still has in flight, so it must not sit behind the observation stores below.
+      ws.wait_oldest();
     }
     // ---------------- observation rows: build, store (through the staging area), convert to MFMA operands
     Op x[NB][KT1 * Net::PT];
@@ -404,12 +409,14 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 #pragma unroll
       for (int net = 0; net < 2; ++net) {
         f32x16(&out)[NB] = net == 0 ? out_p : out_v;
-        // The first stage of a network landed long ago, so its barrier can come before layer 1.
-        // At the value network's, every wave has left the previous step long since and the store
-        // path is idle (the observation stores went out at the start of the step): the collected
-        // per-row outputs of the previous step go out here.
-        ws.wait_oldest();
-        if (FULL && net == 1 && t > 0) flush(t - 1, 0x1f);
+        // The first stage of the value network landed long ago, so its barrier can come before
+        // layer 1.  Every wave has left the previous step long since and the store path is idle
+        // (the observation stores went out at the start of the step): the collected per-row
+        // outputs of the previous step go out here.
+        if (net == 1) {
+          ws.wait_oldest();
+          if (FULL && t > 0) flush(t - 1, 0x1f);
+        }
         Net::layer1(&s_l1[net][0] + lane, x, h1);
         stamp(net == 0 ? CLK_P_L1 : CLK_V_L1);
         f32x16 acc[NB];
