@@ -2,8 +2,9 @@
 // parallel over the M trajectory columns.  HBM-bound: 9 bytes read and 8 bytes
 // written per (t, column).  Each lane owns VEC adjacent columns, so every load
 // and store of a wave is one contiguous run; the loads of UNROLL time steps are
-// issued before the dependent recurrence consumes them, which keeps enough
-// bytes in flight without any cross-lane communication.
+// issued as one batch, and the batch after it is already in flight while the
+// dependent recurrence consumes this one, which keeps enough bytes in flight
+// without any cross-lane communication.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -43,17 +44,17 @@ __global__ __launch_bounds__(256) void gae_kernel(const float* __restrict__ rewa
   for (int i = 0; i < VEC; ++i) next_adv[i] = 0.0f;
   F v_next = v[(int64_t)T * stride];
 
-  int t = T - 1;
-  for (; t >= UNROLL - 1; t -= UNROLL) {
-    F rr[UNROLL], vv[UNROLL];
-    B dd[UNROLL];
+  // UNROLL time steps per batch; the loads of the next batch are in flight while this one runs
+  auto load = [&](int tt, F (&rr)[UNROLL], F (&vv)[UNROLL], B (&dd)[UNROLL]) {
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-      const int64_t o = (int64_t)(t - u) * stride;
+      const int64_t o = (int64_t)(tt - u) * stride;
       rr[u] = r[o];
       vv[u] = v[o];
       dd[u] = d[o];
     }
+  };
+  auto scan = [&](int tt, const F (&rr)[UNROLL], const F (&vv)[UNROLL], const B (&dd)[UNROLL]) {
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       F oa, oq;
@@ -66,10 +67,28 @@ __global__ __launch_bounds__(256) void gae_kernel(const float* __restrict__ rewa
         comp_ref(oa, i) = next_adv[i];
         comp_ref(oq, i) = next_adv[i] + vt;
       }
-      const int64_t o = (int64_t)(t - u) * stride;
+      const int64_t o = (int64_t)(tt - u) * stride;
       a[o] = oa;
       q[o] = oq;
       v_next = vv[u];
+    }
+  };
+  int t = T - 1;
+  if (t >= UNROLL - 1) {
+    F ra[UNROLL], va[UNROLL], rb[UNROLL], vb[UNROLL];
+    B da[UNROLL], db[UNROLL];
+    load(t, ra, va, da);
+    while (true) {
+      bool more = t - UNROLL >= UNROLL - 1;  // a whole batch is left below this one
+      if (more) load(t - UNROLL, rb, vb, db);
+      scan(t, ra, va, da);
+      t -= UNROLL;
+      if (!more) break;
+      more = t - UNROLL >= UNROLL - 1;
+      if (more) load(t - UNROLL, ra, va, da);
+      scan(t, rb, vb, db);
+      t -= UNROLL;
+      if (!more) break;
     }
   }
   for (; t >= 0; --t) {
