@@ -1,4 +1,4 @@
-"""ctypes front end of the CPU oracle (oracle/msrl_ref.c).
+"""ctypes front end of the CPU oracle (oracle/msrl_ref.c, oracle/msrl_learn_ref.c).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
 cpu_baseline leg of bench.py.  Nothing in the product package imports it, and it
@@ -16,6 +16,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "msrl_ref.c")
+_SRCS = [_SRC, os.path.join(_HERE, "msrl_learn_ref.c")]
 _LIB = os.path.join(_HERE, "libmsrl_ref.so")
 
 PARTICLE, LINGAUSS = 0, 1
@@ -24,9 +25,9 @@ CATEGORICAL, DIAG_GAUSSIAN = 0, 1
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, no fast-math)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC, "-lm"]
+            ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-o", _LIB, *_SRCS, "-lm"]
         )
     return _LIB
 
@@ -301,3 +302,54 @@ def words_many(seed, stream, n):
     out = np.zeros(n, dtype=np.uint32)
     lib().ref_words_many(C.c_uint64(seed), C.c_uint32(stream), C.c_int64(n), _p(out))
     return out
+
+
+# ------------------------------------------------------------------ learner (policy update)
+class PpoCfg(C.Structure):
+    _fields_ = [("clip", C.c_double), ("vf_coef", C.c_double), ("ent_coef", C.c_double),
+                ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("adam_eps", C.c_double)]
+
+
+def ppo_cfg(clip=0.2, vf_coef=0.5, ent_coef=0.01, lr=3e-4, beta1=0.9, beta2=0.999, adam_eps=1e-8):
+    return PpoCfg(clip, vf_coef, ent_coef, lr, beta1, beta2, adam_eps)
+
+
+def _actions(pol: "Policy", actions):
+    if pol.dist == CATEGORICAL:
+        ai = np.ascontiguousarray(actions, dtype=np.int32)
+        return ai, None, ai.ctypes.data_as(C.c_void_p), None
+    af = _f64(actions)
+    return None, af, None, _p(af)
+
+
+def ppo_loss(pol: "Policy", cfg: PpoCfg, params, obs, actions, logp_old, adv, ret, want_grad=True):
+    """-> (loss, grad or None, stats[5]) of the clipped-surrogate objective over the given rows."""
+    params, obs, logp_old, adv, ret = map(_f64, (params, obs, logp_old, adv, ret))
+    R = logp_old.size
+    assert obs.size == R * pol.in_dim and params.size == pol.param_count
+    ai, af, pi, pf = _actions(pol, actions)
+    grad = np.zeros(params.size) if want_grad else None
+    stats = np.zeros(5)
+    f = lib().ref_ppo_loss
+    f.restype = C.c_double
+    loss = f(C.byref(pol.c), C.byref(cfg), _p(params), C.c_int64(R), _p(obs), pi, pf, _p(logp_old), _p(adv),
+             _p(ret), _p(grad) if want_grad else None, _p(stats))
+    return float(loss), grad, stats
+
+
+def adam_step(cfg: PpoCfg, params, m, v, grad, k):
+    """In place on params, m, v (float64 arrays); k = 1-based step counter."""
+    lib().ref_adam_step(C.byref(cfg), _p(params), _p(m), _p(v), _p(_f64(grad)), C.c_size_t(params.size),
+                        C.c_int64(k))
+
+
+def ppo_update(pol: "Policy", cfg: PpoCfg, params, m, v, step, iters, minibatches, obs, actions, logp_old, adv, ret):
+    """-> (mean minibatch loss, new step counter); params, m, v are updated in place."""
+    obs, logp_old, adv, ret = map(_f64, (obs, logp_old, adv, ret))
+    ai, af, pi, pf = _actions(pol, actions)
+    k = C.c_int64(step)
+    f = lib().ref_ppo_update
+    f.restype = C.c_double
+    loss = f(C.byref(pol.c), C.byref(cfg), _p(params), _p(m), _p(v), C.byref(k), C.c_int64(logp_old.size),
+             C.c_int(iters), C.c_int(minibatches), _p(obs), pi, pf, _p(logp_old), _p(adv), _p(ret))
+    return float(loss), int(k.value)

@@ -1,0 +1,182 @@
+"""Pins of the learner oracle (oracle/msrl_learn_ref.c): CPU only.
+
+The update rule is the PPO clipped surrogate the oracle's header states.  It is pinned to things
+other than itself: an automatic-differentiation library evaluating the same objective (loss and
+every gradient; both action distributions; rows in every clip regime; the bf16 straight-through
+rule), central finite differences of the loss, closed forms at all-zero parameters, the exact zero
+of the policy gradient when every row is clipped, and Adam's one- and two-step closed forms.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+
+LN2PI_HALF = 0.91893853320467274178
+
+
+def split_params(p, i, h, o):
+    s, out = 0, []
+    for shape in ((i, h), (h,), (h, h), (h,), (h, o), (o,)):
+        n = int(np.prod(shape))
+        out.append(p[s:s + n].reshape(shape))
+        s += n
+    return out, s
+
+
+def bf16_ste(x):
+    """Round to bfloat16 (nearest even) in the value, identity in the derivative."""
+    r = x.detach().to(torch.float32).to(torch.bfloat16).to(torch.float64)
+    return x + (r - x).detach()
+
+
+def torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret):
+    """The objective written with library tensor ops; gradients come from autograd."""
+    P = torch.tensor(params, dtype=torch.float64, requires_grad=True)
+    rnd = bf16_ste if pol.bf16 else (lambda t: t)
+
+    def net(p, out):
+        (W1, b1, W2, b2, W3, b3), used = split_params(p, pol.in_dim, pol.hidden, out)
+        h = torch.tanh(rnd(torch.tensor(obs, dtype=torch.float64)) @ rnd(W1) + b1)
+        h = torch.tanh(rnd(h) @ rnd(W2) + b2)
+        return rnd(h) @ rnd(W3) + b3, used
+
+    y, used = net(P, pol.out_dim)
+    v, _ = net(P[used:], 1)
+    A = torch.tensor(adv, dtype=torch.float64)
+    if pol.dist == ref.CATEGORICAL:
+        lsm = torch.log_softmax(y, dim=1)
+        logp = lsm.gather(1, torch.tensor(actions, dtype=torch.int64)[:, None])[:, 0]
+        ent = -(lsm.exp() * lsm).sum(1)
+    else:
+        K = pol.out_dim // 2
+        dist = torch.distributions.Normal(y[:, :K], y[:, K:].exp())
+        logp = dist.log_prob(torch.tensor(actions, dtype=torch.float64)).sum(1)
+        ent = dist.entropy().sum(1)
+    rho = (logp - torch.tensor(logp_old, dtype=torch.float64)).exp()
+    surr = torch.minimum(rho * A, rho.clamp(1 - cfg.clip, 1 + cfg.clip) * A)
+    loss = (-surr + cfg.vf_coef * (v[:, 0] - torch.tensor(ret, dtype=torch.float64)) ** 2 - cfg.ent_coef * ent).mean()
+    loss.backward()
+    return float(loss.detach()), P.grad.numpy(), float(ent.mean().detach())
+
+
+def make_case(dist, bf16, seed, R=41, i=6, h=8, K=3):
+    rng = np.random.default_rng(seed)
+    o = 5 if dist == ref.CATEGORICAL else 2 * K
+    pol = ref.Policy(i, h, o, bf16=bf16, dist=dist)
+    params = rng.normal(0, 0.6, pol.param_count)
+    obs = rng.normal(0, 1, (R, i))
+    if dist == ref.CATEGORICAL:
+        actions = rng.integers(0, o, R).astype(np.int32)
+    else:
+        actions = rng.normal(0, 1, (R, K))
+    adv = rng.normal(0, 1, R)
+    ret = rng.normal(0, 1, R)
+    # old log-probabilities that put the ratios below, inside and above the clip range
+    cfg0 = ref.ppo_cfg()
+    _, _, st = ref.ppo_loss(pol, cfg0, params, obs, actions, np.zeros(R), adv, ret, want_grad=False)
+    logp_new = np.zeros(R)
+    for n in range(R):   # logp of each row from a single-row call with logp_old = 0: stats[4] = -logp
+        _, _, s1 = ref.ppo_loss(pol, cfg0, params, obs[n:n + 1], actions[n:n + 1], np.zeros(1), adv[n:n + 1],
+                                ret[n:n + 1], want_grad=False)
+        logp_new[n] = -s1[4]
+    logp_old = logp_new - rng.choice([-0.5, -0.1, 0.0, 0.1, 0.5], R)
+    return pol, params, obs, actions, logp_old, adv, ret
+
+
+@pytest.mark.parametrize("dist", [ref.CATEGORICAL, ref.DIAG_GAUSSIAN])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_loss_and_gradient_against_autograd(dist, bf16):
+    pol, params, obs, actions, logp_old, adv, ret = make_case(dist, bf16, 3 + dist)
+    cfg = ref.ppo_cfg(clip=0.2, vf_coef=0.7, ent_coef=0.03)
+    loss, grad, stats = ref.ppo_loss(pol, cfg, params, obs, actions, logp_old, adv, ret)
+    t_loss, t_grad, t_ent = torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret)
+    assert 0.1 < stats[3] < 0.9            # both branches of the min occur
+    np.testing.assert_allclose(loss, t_loss, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(stats[2], t_ent, rtol=1e-11)
+    np.testing.assert_allclose(grad, t_grad, rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("dist", [ref.CATEGORICAL, ref.DIAG_GAUSSIAN])
+def test_gradient_against_finite_differences(dist):
+    pol, params, obs, actions, logp_old, adv, ret = make_case(dist, False, 11 + dist, R=17)
+    cfg = ref.ppo_cfg(ent_coef=0.02)
+    _, grad, _ = ref.ppo_loss(pol, cfg, params, obs, actions, logp_old, adv, ret)
+    rng = np.random.default_rng(0)
+    for j in rng.choice(params.size, 40, replace=False):
+        e = np.zeros_like(params)
+        e[j] = 1e-6
+        lp, _, _ = ref.ppo_loss(pol, cfg, params + e, obs, actions, logp_old, adv, ret, want_grad=False)
+        lm, _, _ = ref.ppo_loss(pol, cfg, params - e, obs, actions, logp_old, adv, ret, want_grad=False)
+        np.testing.assert_allclose(grad[j], (lp - lm) / 2e-6, rtol=2e-5, atol=1e-8)
+
+
+def test_closed_forms_at_zero_parameters():
+    rng = np.random.default_rng(1)
+    R = 29
+    adv, ret = rng.normal(0, 1, R), rng.normal(0, 1, R)
+    cfg = ref.ppo_cfg(vf_coef=0.5, ent_coef=0.01)
+    # categorical: uniform over 5 actions, ratio 1 when the old policy was uniform too
+    pol = ref.Policy(4, 8, 5)
+    loss, grad, st = ref.ppo_loss(pol, cfg, np.zeros(pol.param_count), rng.normal(0, 1, (R, 4)),
+                                  rng.integers(0, 5, R), np.full(R, -np.log(5.0)), adv, ret)
+    np.testing.assert_allclose(st[:3], [-adv.mean(), (ret ** 2).mean(), np.log(5.0)], rtol=1e-12)
+    np.testing.assert_allclose(loss, -adv.mean() + 0.5 * (ret ** 2).mean() - 0.01 * np.log(5.0), rtol=1e-12)
+    # only the output biases see a gradient when every weight is zero; the value bias gets c_v 2 mean(0 - ret)
+    used = ref.net_param_count(4, 8, 5)
+    np.testing.assert_allclose(grad[-1], 0.5 * 2.0 * (-ret).mean(), rtol=1e-12)
+    assert np.count_nonzero(grad[:used - 5]) == 0
+    # Gaussian: mean 0, unit standard deviation
+    K = 3
+    polg = ref.Policy(4, 8, 2 * K, dist=ref.DIAG_GAUSSIAN)
+    a = rng.normal(0, 1, (R, K))
+    lp_old = -0.5 * (a ** 2).sum(1) - K * LN2PI_HALF
+    loss, _, st = ref.ppo_loss(polg, cfg, np.zeros(polg.param_count), rng.normal(0, 1, (R, 4)), a, lp_old, adv, ret)
+    np.testing.assert_allclose(st[:3], [-adv.mean(), (ret ** 2).mean(), K * (LN2PI_HALF + 0.5)], rtol=1e-12)
+    np.testing.assert_allclose(st[4], 0.0, atol=1e-14)
+
+
+def test_clipped_rows_give_no_policy_gradient():
+    pol, params, obs, actions, _, adv, ret = make_case(ref.CATEGORICAL, False, 5)
+    cfg = ref.ppo_cfg(ent_coef=0.0)
+    # make every ratio exp(0.5) > 1 + clip and every advantage positive: the min is the clipped, flat branch
+    logp_new = np.array([-ref.ppo_loss(pol, cfg, params, obs[n:n + 1], actions[n:n + 1], np.zeros(1), np.ones(1),
+                                       ret[n:n + 1], want_grad=False)[2][4] for n in range(adv.size)])
+    _, grad, st = ref.ppo_loss(pol, cfg, params, obs, actions, logp_new - 0.5, np.abs(adv) + 0.1, ret)
+    used = ref.net_param_count(pol.in_dim, pol.hidden, pol.out_dim)
+    assert st[3] == 1.0
+    assert np.count_nonzero(grad[:used]) == 0 and np.count_nonzero(grad[used:]) > 0
+    # and with negative advantages the same ratios are not clipped
+    _, grad, st = ref.ppo_loss(pol, cfg, params, obs, actions, logp_new - 0.5, -np.abs(adv) - 0.1, ret)
+    assert st[3] == 0.0 and np.count_nonzero(grad[:used]) > 0
+
+
+def test_adam_closed_forms_and_update_loop():
+    cfg = ref.ppo_cfg(lr=1e-2, beta1=0.9, beta2=0.999, adam_eps=1e-8)
+    rng = np.random.default_rng(2)
+    g = rng.normal(0, 1, 50)
+    p0 = rng.normal(0, 1, 50)
+    p, m, v = p0.copy(), np.zeros(50), np.zeros(50)
+    ref.adam_step(cfg, p, m, v, g, 1)
+    step = -1e-2 * g / (np.abs(g) + 1e-8)          # bias-corrected moments after one step: g and g^2
+    np.testing.assert_allclose(p - p0, step, rtol=1e-12)
+    ref.adam_step(cfg, p, m, v, g, 2)              # same gradient again: same corrected moments, same step
+    np.testing.assert_allclose(p - p0, 2 * step, rtol=1e-12)
+    np.testing.assert_allclose(m, (1 - 0.9 ** 2) * g, rtol=1e-12)
+    np.testing.assert_allclose(v, (1 - 0.999 ** 2) * g * g, rtol=1e-12)
+    # the update loop = the same steps taken by hand, minibatch by minibatch, epoch by epoch
+    pol, params, obs, actions, logp_old, adv, ret = make_case(ref.CATEGORICAL, False, 9, R=30)
+    pa, ma, va = params.copy(), np.zeros_like(params), np.zeros_like(params)
+    mean_loss, k = ref.ppo_update(pol, cfg, pa, ma, va, 0, 2, 3, obs, actions, logp_old, adv, ret)
+    pb, mb, vb, kk, losses = params.copy(), np.zeros_like(params), np.zeros_like(params), 0, []
+    for it in range(2):
+        for b in range(3):
+            sl = slice(10 * b, 10 * b + 10)
+            l, gr, _ = ref.ppo_loss(pol, cfg, pb, obs[sl], actions[sl], logp_old[sl], adv[sl], ret[sl])
+            kk += 1
+            ref.adam_step(cfg, pb, mb, vb, gr, kk)
+            losses.append(l)
+    assert k == 6
+    np.testing.assert_allclose(pa, pb, rtol=1e-13)
+    np.testing.assert_allclose(mean_loss, np.mean(losses), rtol=1e-13)
+    assert np.mean(losses[3:]) < np.mean(losses[:3])    # the second pass starts from improved parameters
