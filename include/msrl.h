@@ -236,6 +236,61 @@ int msrl_env_step(msrl_state* st, const void* actions, float* rewards, uint8_t* 
                   float* next_obs, void* hip_stream);
 
 /*
+ * Learner: the policy update that Learner.learn runs after gae() (Listing 1:
+ * mappo_net_train(action, state, adv, r), `iter` times).  The paper names the
+ * algorithm (multi-agent PPO) and nothing else; what is computed is the clipped
+ * surrogate of PPO with a squared-error value loss and an entropy bonus,
+ *   rho = exp(logp_theta(a|s) - logp_old),
+ *   L = mean_rows( -min(rho A, clip(rho, 1-clip, 1+clip) A)
+ *                  + vf_coef (V_theta(s) - ret)^2 - ent_coef H(pi_theta(.|s)) ),
+ * its gradient with respect to all parameters of both networks, and Adam with
+ * bias correction.  Parameters, moments and gradients are float32 in the
+ * parameter layout of msrl_policy_cfg, whatever the policy dtype; for
+ * MSRL_BF16 the networks are evaluated as in the rollout (weights and layer
+ * inputs rounded to bfloat16, fp32 accumulation) and the backward contractions
+ * take bfloat16 operands too; roundings count as the identity in the
+ * derivative.  A row is one (t, m) entry of a stored trajectory: obs [R, D],
+ * actions int32 [R] or float [R, act_dim], logp_old, adv, ret [R].  All
+ * pointers DEVICE except cfg and step_counter (HOST).
+ */
+typedef struct msrl_learner msrl_learner; /* opaque: workspaces for up to max_rows rows per call */
+typedef struct {
+  float clip, vf_coef, ent_coef;
+  float lr, beta1, beta2, adam_eps;
+} msrl_ppo_cfg;
+
+/* Allocates the workspaces.  EINVAL unless hidden is a multiple of 32 and out_dim <= 32. */
+int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_learner** out);
+void msrl_learner_destroy(msrl_learner* learner);
+
+/*
+ * grad [msrl_param_count] <- dL/dparams over the R given rows (1 <= R <=
+ * max_rows); stats (optional, 5 floats) <- sums over the rows of: the policy
+ * term, (V - ret)^2, the entropy, 1 where the clipped branch of the min is
+ * active, logp_old - logp.  The weight gradients are accumulated with float
+ * atomics, so their last bits depend on the order of the additions.
+ */
+int msrl_ppo_grad(msrl_learner* learner, const float* params, int64_t R, const float* obs,
+                  const void* actions, const float* logp_old, const float* adv, const float* ret,
+                  const msrl_ppo_cfg* cfg, float* grad, float* stats, void* hip_stream);
+
+/* One Adam step on n parameters, in place; k >= 1 is the number of this step. */
+int msrl_adam_step(float* params, float* m, float* v, const float* grad, int64_t n, int64_t k,
+                   const msrl_ppo_cfg* cfg, void* hip_stream);
+
+/*
+ * The training loop of Learner.learn: `iters` passes over the R rows, each
+ * split into `minibatches` consecutive blocks of rows (the last one takes the
+ * remainder; no block may exceed max_rows), one msrl_ppo_grad + msrl_adam_step
+ * per block.  *step_counter (HOST): Adam steps taken so far, advanced by
+ * iters * minibatches.
+ */
+int msrl_ppo_update(msrl_learner* learner, float* params, float* m, float* v, int64_t* step_counter,
+                    int64_t R, int32_t iters, int32_t minibatches, const float* obs,
+                    const void* actions, const float* logp_old, const float* adv, const float* ret,
+                    const msrl_ppo_cfg* cfg, void* hip_stream);
+
+/*
  * Snapshot / restore of the env batch.  env_state: HOST
  * [num_envs, msrl_env_state_size] floats; step_counters: HOST [num_envs] int64
  * (only the low 32 bits enter the Philox counter).  Either pointer may be NULL

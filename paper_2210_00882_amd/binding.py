@@ -21,7 +21,8 @@ MSRL_PHASE_ENV, MSRL_PHASE_MLP, MSRL_PHASE_CLOCKS = 1, 2, 3
 
 EXPORTS = (
     "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",
-    "msrl_rollout_gae", "msrl_measure_phase", "msrl_observe", "msrl_act", "msrl_env_step", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
+    "msrl_rollout_gae", "msrl_measure_phase", "msrl_observe", "msrl_act", "msrl_env_step",
+    "msrl_learner_init", "msrl_learner_destroy", "msrl_ppo_grad", "msrl_adam_step", "msrl_ppo_update", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
 )
 
 
@@ -44,6 +45,10 @@ class msrl_policy_cfg(C.Structure):
 class msrl_traj(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
                 ("obs", "actions", "logp", "rewards", "dones", "values", "logits", "adv", "ret")]
+
+
+class msrl_ppo_cfg(C.Structure):
+    _fields_ = [(n, C.c_float) for n in ("clip", "vf_coef", "ent_coef", "lr", "beta1", "beta2", "adam_eps")]
 
 
 class MsrlError(RuntimeError):
@@ -86,6 +91,17 @@ def load():
     lib.msrl_act.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     lib.msrl_env_step.restype = C.c_int
     lib.msrl_env_step.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.msrl_learner_init.restype = C.c_int
+    lib.msrl_learner_init.argtypes = [C.POINTER(msrl_policy_cfg), i64, C.POINTER(vp)]
+    lib.msrl_learner_destroy.restype = None
+    lib.msrl_learner_destroy.argtypes = [vp]
+    lib.msrl_ppo_grad.restype = C.c_int
+    lib.msrl_ppo_grad.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, C.POINTER(msrl_ppo_cfg), vp, vp, vp]
+    lib.msrl_adam_step.restype = C.c_int
+    lib.msrl_adam_step.argtypes = [vp, vp, vp, vp, i64, i64, C.POINTER(msrl_ppo_cfg), vp]
+    lib.msrl_ppo_update.restype = C.c_int
+    lib.msrl_ppo_update.argtypes = [vp, vp, vp, vp, C.POINTER(i64), i64, i32, i32, vp, vp, vp, vp, vp,
+                                    C.POINTER(msrl_ppo_cfg), vp]
     lib.msrl_state_get.restype = C.c_int
     lib.msrl_state_get.argtypes = [vp, vp, vp]
     lib.msrl_state_set.restype = C.c_int
@@ -204,6 +220,44 @@ def msrl_act(state, params, obs, actions, logp, values, logits=None, stream=None
 def msrl_env_step(state, actions, rewards, dones, next_obs, stream=None) -> None:
     _check(load().msrl_env_step(state, _ptr(actions), _ptr(rewards), _ptr(dones), _ptr(next_obs),
                                 _stream(stream)))
+
+
+def make_ppo_cfg(clip=0.2, vf_coef=0.5, ent_coef=0.01, lr=3e-4, beta1=0.9, beta2=0.999, adam_eps=1e-8):
+    return msrl_ppo_cfg(clip, vf_coef, ent_coef, lr, beta1, beta2, adam_eps)
+
+
+def msrl_learner_init(policy_cfg: msrl_policy_cfg, max_rows: int) -> C.c_void_p:
+    L = C.c_void_p()
+    _check(load().msrl_learner_init(C.byref(policy_cfg), C.c_int64(max_rows), C.byref(L)))
+    return L
+
+
+def msrl_learner_destroy(learner) -> None:
+    load().msrl_learner_destroy(learner)
+
+
+def msrl_ppo_grad(learner, params, obs, actions, logp_old, adv, ret, cfg: msrl_ppo_cfg, grad, stats=None,
+                  stream=None) -> None:
+    """All tensors on the device; params / grad float32 [param_count]; rows = logp_old.numel()."""
+    _check(load().msrl_ppo_grad(learner, _ptr(params), C.c_int64(logp_old.numel()), _ptr(obs), _ptr(actions),
+                                _ptr(logp_old), _ptr(adv), _ptr(ret), C.byref(cfg), _ptr(grad), _ptr(stats),
+                                _stream(stream)))
+
+
+def msrl_adam_step(params, m, v, grad, k: int, cfg: msrl_ppo_cfg, stream=None) -> None:
+    _check(load().msrl_adam_step(_ptr(params), _ptr(m), _ptr(v), _ptr(grad), C.c_int64(params.numel()),
+                                 C.c_int64(k), C.byref(cfg), _stream(stream)))
+
+
+def msrl_ppo_update(learner, params, m, v, step: int, iters: int, minibatches: int, obs, actions, logp_old, adv,
+                    ret, cfg: msrl_ppo_cfg, stream=None) -> int:
+    """-> the new step counter; params, m, v (float32, device) are updated in place."""
+    k = C.c_int64(step)
+    _check(load().msrl_ppo_update(learner, _ptr(params), _ptr(m), _ptr(v), C.byref(k),
+                                  C.c_int64(logp_old.numel()), C.c_int32(iters), C.c_int32(minibatches),
+                                  _ptr(obs), _ptr(actions), _ptr(logp_old), _ptr(adv), _ptr(ret), C.byref(cfg),
+                                  _stream(stream)))
+    return int(k.value)
 
 
 def msrl_state_get(state, num_envs: int, state_size: int):

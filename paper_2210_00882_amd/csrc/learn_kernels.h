@@ -1,0 +1,320 @@
+// Kernels of the learner's policy update (PPO clipped surrogate, Listing 1 of
+// the paper: mappo_net_train): forward and backward passes of the policy and
+// value networks over a minibatch of stored rows, as plain dense contractions
+// on MFMA with the activations kept in device memory, plus the per-row loss,
+// the transposes the weight gradients need, and Adam.
+//
+// First version: correctness first.  Every contraction is one launch of the
+// same kernel, C[m][n] = sum_k A[m][k] * B[n][k], whose two operands are both
+// stored with k contiguous, so that each lane fetches its MFMA fragment with
+// one 16-byte load straight from global memory (no LDS tiling yet: the weights
+// of a contraction are re-read from L2 by every wave).  The weight gradients
+// contract over the rows, so they take the transposed copies (unit-major) that
+// transpose_kernel makes.  Every global access is bounds-checked against the
+// extents passed in.
+#pragma once
+#include "dev_common.h"
+
+namespace msrl {
+
+// ---------------------------------------------------------------- fragments
+// One "k tile" is 16 k-values in bf16 mode (one 32x32x16 MFMA) and 8 in fp32
+// mode (four 32x32x2 MFMAs).  Lane (i = lane % 32, h = lane / 32) holds, for
+// operand row i, k-values 8h..8h+7 of the tile (bf16) or 2j+h, j = 0..3 (fp32).
+template <bool BF16> struct Frag;
+template <> struct Frag<true> {
+  typedef bf16x8 T;
+  static constexpr int KT = 16;
+};
+template <> struct Frag<false> {
+  typedef f32x4 T;
+  static constexpr int KT = 8;
+};
+
+__device__ __forceinline__ bf16x8 frag_zero(bf16x8*) {
+  bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+  return z;
+}
+__device__ __forceinline__ f32x4 frag_zero(f32x4*) {
+  f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
+  return z;
+}
+
+// fragment of row `p` (k contiguous, element type S) at k offset k0; the row holds at least
+// k0 + KT elements (extents are padded to whole tiles by the host)
+__device__ __forceinline__ bf16x8 load_frag(const __bf16* p, int k0, int h, bf16x8*) {
+  return *(const bf16x8*)(p + k0 + 8 * h);
+}
+__device__ __forceinline__ bf16x8 load_frag(const float* p, int k0, int h, bf16x8*) {
+  const f32x4 a = *(const f32x4*)(p + k0 + 8 * h), b = *(const f32x4*)(p + k0 + 8 * h + 4);
+  typedef float f32x8 __attribute__((ext_vector_type(8)));
+  const f32x8 v = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_convertvector(v, bf16x8);  // round to nearest even
+}
+__device__ __forceinline__ f32x4 load_frag(const float* p, int k0, int h, f32x4*) {
+  const f32x4 a = *(const f32x4*)(p + k0), b = *(const f32x4*)(p + k0 + 4);
+  f32x4 r;
+  r[0] = h ? a[1] : a[0];
+  r[1] = h ? a[3] : a[2];
+  r[2] = h ? b[1] : b[0];
+  r[3] = h ? b[3] : b[2];
+  return r;
+}
+
+__device__ __forceinline__ void mma_frag(const bf16x8& a, const bf16x8& b, f32x16& c) {
+  c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ void mma_frag(const f32x4& a, const f32x4& b, f32x16& c) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b[j], c, 0, 0, 0);
+}
+
+__device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_elem(__bf16* p, float v) { *p = (__bf16)v; }
+__device__ __forceinline__ float load_elem(const float* p) { return *p; }
+__device__ __forceinline__ float load_elem(const __bf16* p) { return (float)*p; }
+
+// ---------------------------------------------------------------- contraction
+enum : int {
+  EPI_BIAS_TANH = 0,  // C = tanh(acc + bias[n])
+  EPI_BIAS = 1,       // C = acc + bias[n]
+  EPI_DTANH = 2,      // C = acc * (1 - Hm[m][n]^2)
+  EPI_ATOMIC = 3      // C += acc (fp32 atomics; the k range is split over blockIdx.z)
+};
+
+struct GemmArgs {
+  const void* A;  // [M_alloc, lda], k contiguous
+  const void* B;  // [N_alloc, ldb], k contiguous
+  void* C;        // [M, ldc] row-major
+  const float* bias;
+  const void* Hm;  // EPI_DTANH: [M, ldh], same element type as C
+  int64_t M, N;    // extent of C that is written
+  int64_t M_alloc, N_alloc;  // rows of A / B that may be read (rows beyond read as zero)
+  int64_t K;       // contraction length, a multiple of the k tile; both operands hold it
+  int64_t lda, ldb, ldc, ldh;
+  int64_t k_per_slice;  // EPI_ATOMIC: k values per blockIdx.z, a multiple of the k tile
+};
+
+// 4 waves per workgroup; a wave owns 32 rows of C and NT = 4 column tiles of 32.
+template <bool BF16, typename SA, typename SB, typename SC, int EPI>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
+  typedef typename Frag<BF16>::T F;
+  constexpr int KT = Frag<BF16>::KT, NT = 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i = lane & 31, h = lane >> 5;
+  const int64_t m0 = ((int64_t)blockIdx.x * 4 + wave) * 32;
+  const int64_t n0 = (int64_t)blockIdx.y * (32 * NT);
+  if (m0 >= g.M) return;
+  int64_t k_begin = 0, k_end = g.K;
+  if (EPI == EPI_ATOMIC) {
+    k_begin = (int64_t)blockIdx.z * g.k_per_slice;
+    k_end = min(g.K, k_begin + g.k_per_slice);
+    if (k_begin >= k_end) return;
+  }
+  const SA* arow = (const SA*)g.A + (m0 + i) * g.lda;
+  const bool a_ok = m0 + i < g.M_alloc;
+  const SB* brow[NT];
+  bool b_ok[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    brow[j] = (const SB*)g.B + (n0 + 32 * j + i) * g.ldb;
+    b_ok[j] = n0 + 32 * j + i < g.N_alloc;
+  }
+  f32x16 acc[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+  for (int64_t k = k_begin; k < k_end; k += KT) {
+    const F a = a_ok ? load_frag(arow, (int)k, h, (F*)nullptr) : frag_zero((F*)nullptr);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      if (n0 + 32 * j >= g.N) continue;  // uniform: no column of this tile is written
+      const F b = b_ok[j] ? load_frag(brow[j], (int)k, h, (F*)nullptr) : frag_zero((F*)nullptr);
+      mma_frag(a, b, acc[j]);
+    }
+  }
+  // accumulator: lane (n = i, h), register r <-> row 8 (r / 4) + 4 h + r % 4 of the tile
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int64_t n = n0 + 32 * j + i;
+    if (n >= g.N) continue;
+    const float bias = (EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) ? g.bias[n] : 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t m = m0 + 8 * (r / 4) + 4 * h + r % 4;
+      if (m >= g.M) continue;
+      float v = acc[j][r];
+      SC* dst = (SC*)g.C + m * g.ldc + n;
+      if (EPI == EPI_BIAS_TANH) v = tanhf(v + bias);
+      if (EPI == EPI_BIAS) v = v + bias;
+      if (EPI == EPI_DTANH) {
+        const float hv = load_elem((const SC*)g.Hm + m * g.ldh + n);
+        v = v * (1.0f - hv * hv);
+      }
+      if (EPI == EPI_ATOMIC)
+        atomicAdd((float*)g.C + m * g.ldc + n, v);
+      else
+        store_elem(dst, v);
+    }
+  }
+}
+
+// ---------------------------------------------------------------- transposes, conversions
+// dst[c][r] = src[r][c] for r < rows, c < cols; dst rows are ldd long and columns in
+// [rows, rows_pad) are written as zero (the contraction over rows reads whole k tiles).
+template <typename S, typename D>
+__global__ __launch_bounds__(256) void transpose_kernel(const S* src, int64_t rows, int64_t cols, int64_t lds_,
+                                                        D* dst, int64_t ldd, int64_t rows_pad, int64_t cols_out) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  const int64_t r0 = (int64_t)blockIdx.x * 32, c0 = (int64_t)blockIdx.y * 32;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int64_t r = r0 + ty + 8 * s, c = c0 + tx;
+    tile[ty + 8 * s][tx] = (r < rows && c < cols) ? load_elem(src + r * lds_ + c) : 0.0f;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int64_t c = c0 + ty + 8 * s, r = r0 + tx;
+    if (c < cols_out && r < rows_pad) store_elem(dst + c * ldd + r, tile[tx][ty + 8 * s]);
+  }
+}
+
+// dst[r][c] = src[r][c] converted, zero for c in [cols, ldd) and for r in [rows, rows_pad)
+template <typename S, typename D>
+__global__ void convert_pad_kernel(const S* src, int64_t rows, int64_t cols, int64_t lds_, D* dst, int64_t ldd,
+                                   int64_t rows_pad) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= rows_pad * ldd) return;
+  const int64_t r = idx / ldd, c = idx % ldd;
+  store_elem(dst + idx, (r < rows && c < cols) ? load_elem(src + r * lds_ + c) : 0.0f);
+}
+
+__global__ void fill_kernel(float* p, int64_t n, float v) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < n) p[idx] = v;
+}
+
+// out[u] += sum_r src[u][r], r < rows (src unit-major); one wave per unit
+template <typename S>
+__global__ __launch_bounds__(64) void rowsum_kernel(const S* src, int64_t units, int64_t rows, int64_t lds_,
+                                                    float* out) {
+  const int64_t u = blockIdx.x;
+  if (u >= units) return;
+  float s = 0.0f;
+  for (int64_t r = threadIdx.x; r < rows; r += 64) s += load_elem(src + u * lds_ + r);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+  if (threadIdx.x == 0) out[u] += s;
+}
+
+// ---------------------------------------------------------------- per-row loss
+struct LossArgs {
+  const float* y;       // [R, 32] policy outputs (columns >= out_dim unused)
+  const float* v;       // [R, 32] value output in column 0
+  const void* actions;  // int32 [R] or float [R, K]
+  const float* logp_old;
+  const float* adv;
+  const float* ret;
+  void* dy;             // [R_pad, 32] dL/dy of the policy net, compute type; pad rows and columns zero
+  void* dv;             // [R_pad, 32] dL/dv in column 0
+  float* stats;         // [5] += sum of: policy term, value term, entropy, clipped rows, logp_old - logp
+  int64_t R, R_pad;
+  int out_dim, dist;
+  float clip, vf_coef, ent_coef, inv_R;
+};
+
+template <typename SC>
+__global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
+  const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  float s_pi = 0.0f, s_v = 0.0f, s_h = 0.0f, s_c = 0.0f, s_kl = 0.0f;
+  if (n < a.R_pad) {
+    float dy[32];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) dy[k] = 0.0f;
+    float dv = 0.0f;
+    if (n < a.R) {
+      const float* y = a.y + n * 32;
+      const int O = a.out_dim;
+      float logp = 0.0f, ent = 0.0f;
+      float dlp[32];  // d logp / dy
+      float dH[32];   // d entropy / dy
+#pragma unroll
+      for (int k = 0; k < 32; ++k) dlp[k] = dH[k] = 0.0f;
+      if (a.dist == 0) {
+        float mx = y[0];
+        for (int k = 1; k < O; ++k) mx = fmaxf(mx, y[k]);
+        float z = 0.0f;
+        for (int k = 0; k < O; ++k) z += expf(y[k] - mx);
+        const float lse = mx + logf(z);
+        const int act = ((const int32_t*)a.actions)[n];
+        for (int k = 0; k < O; ++k) {
+          const float lp = y[k] - lse;
+          ent -= expf(lp) * lp;
+        }
+        for (int k = 0; k < O; ++k) {
+          const float lp = y[k] - lse, pk = expf(lp);
+          if (k == act) logp = lp;
+          dlp[k] = (k == act ? 1.0f : 0.0f) - pk;
+          dH[k] = -pk * (lp + ent);
+        }
+      } else {
+        const int K = O / 2;
+        for (int d = 0; d < K; ++d) {
+          const float mu = y[d], ls = y[K + d], sg = expf(ls);
+          const float e = (((const float*)a.actions)[n * K + d] - mu) / sg;
+          logp += -0.5f * e * e - ls - 0.9189385332046727f;
+          ent += ls + 1.4189385332046727f;
+          dlp[d] = e / sg;
+          dlp[K + d] = e * e - 1.0f;
+          dH[K + d] = 1.0f;
+        }
+      }
+      const float rho = expf(logp - a.logp_old[n]), A = a.adv[n];
+      const float rc = fminf(fmaxf(rho, 1.0f - a.clip), 1.0f + a.clip);
+      const float un = rho * A, cl = rc * A;
+      const bool clipped = cl < un;
+      const float gl = clipped ? 0.0f : -A * rho;
+      for (int k = 0; k < O; ++k) dy[k] = (gl * dlp[k] - a.ent_coef * dH[k]) * a.inv_R;
+      const float err = a.v[n * 32] - a.ret[n];
+      dv = a.vf_coef * 2.0f * err * a.inv_R;
+      s_pi = -(clipped ? cl : un);
+      s_v = err * err;
+      s_h = ent;
+      s_c = clipped ? 1.0f : 0.0f;
+      s_kl = a.logp_old[n] - logp;
+    }
+    SC* pdy = (SC*)a.dy + n * 32;
+    SC* pdv = (SC*)a.dv + n * 32;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+      store_elem(pdy + k, dy[k]);
+      store_elem(pdv + k, k == 0 ? dv : 0.0f);
+    }
+  }
+  // block sums -> one atomic per statistic and wave
+  float s[5] = {s_pi, s_v, s_h, s_c, s_kl};
+#pragma unroll
+  for (int q = 0; q < 5; ++q) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s[q] += __shfl_xor(s[q], o);
+    if ((threadIdx.x & 63) == 0) atomicAdd(a.stats + q, s[q]);
+  }
+}
+
+// ---------------------------------------------------------------- Adam
+__global__ void adam_kernel(float* p, float* m, float* v, const float* g, int64_t n, float lr, float b1, float b2,
+                            float eps, float c1, float c2) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n) return;
+  const float gi = g[idx];
+  const float mi = b1 * m[idx] + (1.0f - b1) * gi;
+  const float vi = b2 * v[idx] + (1.0f - b2) * gi * gi;
+  m[idx] = mi;
+  v[idx] = vi;
+  p[idx] -= lr * (mi / c1) / (sqrtf(vi / c2) + eps);
+}
+
+}  // namespace msrl

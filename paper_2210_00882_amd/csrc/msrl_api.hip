@@ -13,6 +13,7 @@
 
 #include "dev_common.h"
 #include "packed.h"
+#include "api_common.h"
 #include "registry.h"
 
 namespace msrl {
@@ -42,9 +43,10 @@ struct msrl_state {
 };
 
 namespace {
-
 thread_local char g_err[512] = "";
+}
 
+namespace msrl {
 int fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -52,6 +54,9 @@ int fail(int code, const char* fmt, ...) {
   va_end(ap);
   return code;
 }
+}  // namespace msrl
+
+namespace {
 
 #define HIP_TRY(expr)                                                                       \
   do {                                                                                      \

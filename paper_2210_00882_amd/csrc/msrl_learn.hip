@@ -1,0 +1,319 @@
+// Learner entry points of the C ABI (include/msrl.h): minibatch gradient of the PPO clipped
+// surrogate, Adam, and the update loop of Learner.learn (Listing 1 of the paper).  Host
+// orchestration of the kernels in learn_kernels.h; see that file for the arithmetic.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <new>
+
+#include "../../include/msrl.h"
+#include "api_common.h"
+#include "learn_kernels.h"
+
+using namespace msrl;
+
+namespace {
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// device buffers of one network's pass over a minibatch (element type = compute type)
+struct NetBufs {
+  void *wt1, *wt2, *wt3;  // forward weights, transposed: [H, Dp], [H, H], [32, H]
+  void *wn2, *wn3;        // backward weights, as stored: [H, H], [H, 32]
+  float *b1, *b2, *b3;    // biases (b3 padded to 32)
+  void *h1, *h2;          // [Rp, H]
+  float* y;               // [Rp, 32]
+  void *dy, *dz2, *dz1;   // [Rp, 32], [Rp, H], [Rp, H]
+  void *h1t, *h2t, *dyt, *dz2t, *dz1t;  // unit-major copies: [H | 32, Rp]
+};
+
+}  // namespace
+
+struct msrl_learner {
+  msrl_policy_cfg pol;
+  int64_t max_rows, Rp;  // Rp: max_rows rounded up to 128
+  int Dp;                // in_dim rounded up to 16
+  bool bf16;
+  size_t esz;
+  void* xc;              // [Rp, Dp]
+  void* xt;              // [Dp, Rp]
+  NetBufs net[2];
+  float* grad;           // scratch gradient of msrl_ppo_update
+  float* stats;          // [8]
+  size_t n_params;
+};
+
+namespace {
+
+#define LTRY(expr)                                                                          \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return fail(e_ == hipErrorOutOfMemory ? MSRL_ENOMEM : MSRL_EDEVICE, "%s failed: %s",  \
+                  #expr, hipGetErrorString(e_));                                            \
+  } while (0)
+
+size_t net_count(int in, int H, int out) { return (size_t)in * H + H + (size_t)H * H + H + (size_t)H * out + out; }
+
+template <typename T> int dev_alloc(T** p, size_t bytes) {
+  LTRY(hipMalloc((void**)p, bytes));
+  LTRY(hipMemset(*p, 0, bytes));
+  return MSRL_OK;
+}
+
+dim3 grid1(int64_t n, int block = 256) { return dim3((unsigned)((n + block - 1) / block)); }
+
+// ---- typed launch helpers (C = compute element type)
+template <bool BF16> struct CT;
+template <> struct CT<true> { typedef __bf16 T; };
+template <> struct CT<false> { typedef float T; };
+
+template <bool BF16, typename SC, int EPI>
+hipError_t gemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, const void* B, int64_t N_alloc,
+                int64_t ldb, void* C, int64_t M, int64_t N, int64_t ldc, int64_t K, const float* bias,
+                const void* Hm, int64_t ldh, int slices = 1) {
+  typedef typename CT<BF16>::T E;
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.A = A; g.B = B; g.C = C; g.bias = bias; g.Hm = Hm;
+  g.M = M; g.N = N; g.M_alloc = M_alloc; g.N_alloc = N_alloc; g.K = K;
+  g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ldh = ldh;
+  const int64_t kt = Frag<BF16>::KT;
+  g.k_per_slice = round_up((K + slices - 1) / slices, kt);
+  dim3 grid((unsigned)((M + 127) / 128), (unsigned)((N + 127) / 128), (unsigned)slices);
+  hipLaunchKernelGGL((gemm_kernel<BF16, E, E, SC, EPI>), grid, dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+
+template <typename S, typename D>
+hipError_t transpose(hipStream_t s, const S* src, int64_t rows, int64_t cols, int64_t ld_src, D* dst, int64_t ldd,
+                     int64_t rows_pad, int64_t cols_out) {
+  dim3 grid((unsigned)((rows_pad + 31) / 32), (unsigned)((cols_out + 31) / 32));
+  hipLaunchKernelGGL((transpose_kernel<S, D>), grid, dim3(256), 0, s, src, rows, cols, ld_src, dst, ldd, rows_pad,
+                     cols_out);
+  return hipGetLastError();
+}
+
+template <typename S, typename D>
+hipError_t convert_pad(hipStream_t s, const S* src, int64_t rows, int64_t cols, int64_t ld_src, D* dst, int64_t ldd,
+                       int64_t rows_pad) {
+  hipLaunchKernelGGL((convert_pad_kernel<S, D>), grid1(rows_pad * ldd), dim3(256), 0, s, src, rows, cols, ld_src,
+                     dst, ldd, rows_pad);
+  return hipGetLastError();
+}
+
+// gradient of one minibatch; grad (device, n_params floats) is overwritten; stats[0..4] are sums
+template <bool BF16>
+int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs, const void* actions,
+              const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* c, float* grad,
+              hipStream_t s) {
+  typedef typename CT<BF16>::T E;
+  const int D = L->pol.in_dim, H = L->pol.hidden, Dp = L->Dp;
+  const int64_t Rp = L->Rp;
+  const int64_t Rk = round_up(R, 16);  // rows as a contraction length
+  hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
+  hipLaunchKernelGGL(fill_kernel, grid1(8), dim3(256), 0, s, L->stats, (int64_t)8, 0.0f);
+  // observations in compute type, padded; and unit-major
+  LTRY(convert_pad(s, obs, R, D, D, (E*)L->xc, Dp, Rk));
+  LTRY(transpose(s, (const E*)L->xc, R, Dp, Dp, (E*)L->xt, Rp, Rk, Dp));
+  const float* P = params;
+  for (int n = 0; n < 2; ++n) {
+    NetBufs& b = L->net[n];
+    const int O = n == 0 ? L->pol.out_dim : 1;
+    const float* W1 = P;
+    const float* b1 = W1 + (size_t)D * H;
+    const float* W2 = b1 + H;
+    const float* b2 = W2 + (size_t)H * H;
+    const float* W3 = b2 + H;
+    const float* b3 = W3 + (size_t)H * O;
+    // weights in compute type: transposed for the forward pass, as stored for the backward pass
+    LTRY(transpose(s, W1, D, H, H, (E*)b.wt1, Dp, Dp, H));
+    LTRY(transpose(s, W2, H, H, H, (E*)b.wt2, H, H, H));
+    LTRY(transpose(s, W3, H, O, O, (E*)b.wt3, H, H, 32));
+    LTRY(convert_pad(s, W2, H, H, H, (E*)b.wn2, H, H));
+    LTRY(convert_pad(s, W3, H, O, O, (E*)b.wn3, 32, H));
+    LTRY(convert_pad(s, b3, 1, O, O, b.b3, 32, 1));
+    // forward
+    LTRY((gemm<BF16, E, EPI_BIAS_TANH>(s, L->xc, Rp, Dp, b.wt1, H, Dp, b.h1, R, H, H, Dp, b1, nullptr, 0)));
+    LTRY((gemm<BF16, E, EPI_BIAS_TANH>(s, b.h1, Rp, H, b.wt2, H, H, b.h2, R, H, H, H, b2, nullptr, 0)));
+    LTRY((gemm<BF16, float, EPI_BIAS>(s, b.h2, Rp, H, b.wt3, 32, H, b.y, R, 32, 32, H, b.b3, nullptr, 0)));
+    P = b3 + O;
+  }
+  {
+    LossArgs a;
+    memset(&a, 0, sizeof(a));
+    a.y = L->net[0].y; a.v = L->net[1].y; a.actions = actions; a.logp_old = logp_old; a.adv = adv; a.ret = ret;
+    a.dy = L->net[0].dy; a.dv = L->net[1].dy; a.stats = L->stats; a.R = R; a.R_pad = Rk;
+    a.out_dim = L->pol.out_dim; a.dist = L->pol.dist;
+    a.clip = c->clip; a.vf_coef = c->vf_coef; a.ent_coef = c->ent_coef; a.inv_R = 1.0f / (float)R;
+    hipLaunchKernelGGL((loss_kernel<E>), grid1(Rk), dim3(256), 0, s, a);
+    LTRY(hipGetLastError());
+  }
+  size_t off = 0;
+  for (int n = 0; n < 2; ++n) {
+    NetBufs& b = L->net[n];
+    const int O = n == 0 ? L->pol.out_dim : 1;
+    float* gW1 = grad + off;
+    float* gb1 = gW1 + (size_t)D * H;
+    float* gW2 = gb1 + H;
+    float* gb2 = gW2 + (size_t)H * H;
+    float* gW3 = gb2 + H;
+    float* gb3 = gW3 + (size_t)H * O;
+    // backward through the activations
+    LTRY((gemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, b.dz2, R, H, H, 32, nullptr, b.h2, H)));
+    LTRY((gemm<BF16, E, EPI_DTANH>(s, b.dz2, Rp, H, b.wn2, H, H, b.dz1, R, H, H, H, nullptr, b.h1, H)));
+    // unit-major copies for the contractions over the rows
+    LTRY(transpose(s, (const E*)b.h2, R, H, H, (E*)b.h2t, Rp, Rk, H));
+    LTRY(transpose(s, (const E*)b.h1, R, H, H, (E*)b.h1t, Rp, Rk, H));
+    LTRY(transpose(s, (const E*)b.dy, R, 32, 32, (E*)b.dyt, Rp, Rk, 32));
+    LTRY(transpose(s, (const E*)b.dz2, R, H, H, (E*)b.dz2t, Rp, Rk, H));
+    LTRY(transpose(s, (const E*)b.dz1, R, H, H, (E*)b.dz1t, Rp, Rk, H));
+    // weight gradients: contraction over the rows, split over workgroups, fp32 atomics
+    const int slices = (int)fmax(1.0, fmin(256.0, (double)(Rk / 2048)));
+    LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h2t, H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, nullptr, nullptr, 0, slices)));
+    LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h1t, H, Rp, b.dz2t, H, Rp, gW2, H, H, H, Rk, nullptr, nullptr, 0, slices)));
+    LTRY((gemm<BF16, float, EPI_ATOMIC>(s, L->xt, Dp, Rp, b.dz1t, H, Rp, gW1, D, H, H, Rk, nullptr, nullptr, 0, slices)));
+    hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)O), dim3(64), 0, s, (const E*)b.dyt, (int64_t)O, R, Rp, gb3);
+    hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)H), dim3(64), 0, s, (const E*)b.dz2t, (int64_t)H, R, Rp, gb2);
+    hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)H), dim3(64), 0, s, (const E*)b.dz1t, (int64_t)H, R, Rp, gb1);
+    LTRY(hipGetLastError());
+    off += net_count(D, H, O);
+  }
+  return MSRL_OK;
+}
+
+int check_learner_args(const char* who, msrl_learner* L, const void* params, int64_t R, const void* obs,
+                       const void* actions, const void* logp_old, const void* adv, const void* ret,
+                       const msrl_ppo_cfg* c) {
+  if (!L || !params || !obs || !actions || !logp_old || !adv || !ret || !c)
+    return fail(MSRL_EINVAL, "%s: NULL argument", who);
+  if (R < 1 || R > L->max_rows)
+    return fail(MSRL_EINVAL, "%s: %lld rows, the learner was created for 1..%lld", who, (long long)R,
+                (long long)L->max_rows);
+  if (!(c->clip >= 0.0f)) return fail(MSRL_EINVAL, "%s: clip must be >= 0", who);
+  return MSRL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_learner** out) {
+  if (!policy || !out) return fail(MSRL_EINVAL, "msrl_learner_init: NULL argument");
+  *out = nullptr;
+  if (policy->in_dim < 1 || policy->hidden < 32 || policy->hidden % 32 != 0 || policy->out_dim < 1 ||
+      policy->out_dim > 32 || (policy->dtype != MSRL_F32 && policy->dtype != MSRL_BF16) ||
+      (policy->dist != MSRL_CATEGORICAL && policy->dist != MSRL_DIAG_GAUSSIAN) ||
+      (policy->dist == MSRL_DIAG_GAUSSIAN && policy->out_dim % 2 != 0))
+    return fail(MSRL_EINVAL, "msrl_learner_init: unsupported policy configuration (hidden must be a multiple of "
+                             "32, out_dim at most 32)");
+  if (max_rows < 1) return fail(MSRL_EINVAL, "msrl_learner_init: max_rows must be positive");
+  msrl_learner* L = new (std::nothrow) msrl_learner;
+  if (!L) return fail(MSRL_ENOMEM, "msrl_learner_init: host allocation failed");
+  memset(L, 0, sizeof(*L));
+  L->pol = *policy;
+  L->max_rows = max_rows;
+  L->Rp = round_up(max_rows, 128);
+  L->Dp = (int)round_up(policy->in_dim, 16);
+  L->bf16 = policy->dtype == MSRL_BF16;
+  L->esz = L->bf16 ? 2 : 4;
+  L->n_params = net_count(policy->in_dim, policy->hidden, policy->out_dim) + net_count(policy->in_dim, policy->hidden, 1);
+  const size_t H = (size_t)policy->hidden, Rp = (size_t)L->Rp, Dp = (size_t)L->Dp, e = L->esz;
+  int rc = MSRL_OK;
+  auto A = [&](void** p, size_t bytes) { if (rc == MSRL_OK) rc = dev_alloc((uint8_t**)p, bytes); };
+  A(&L->xc, Rp * Dp * e);
+  A(&L->xt, Dp * Rp * e);
+  for (int n = 0; n < 2; ++n) {
+    NetBufs& b = L->net[n];
+    A(&b.wt1, H * Dp * e); A(&b.wt2, H * H * e); A(&b.wt3, 32 * H * e);
+    A(&b.wn2, H * H * e); A(&b.wn3, H * 32 * e);
+    A((void**)&b.b3, 32 * sizeof(float));
+    A(&b.h1, Rp * H * e); A(&b.h2, Rp * H * e);
+    A((void**)&b.y, Rp * 32 * sizeof(float));
+    A(&b.dy, Rp * 32 * e); A(&b.dz2, Rp * H * e); A(&b.dz1, Rp * H * e);
+    A(&b.h1t, H * Rp * e); A(&b.h2t, H * Rp * e); A(&b.dyt, 32 * Rp * e);
+    A(&b.dz2t, H * Rp * e); A(&b.dz1t, H * Rp * e);
+  }
+  A((void**)&L->grad, L->n_params * sizeof(float));
+  A((void**)&L->stats, 8 * sizeof(float));
+  if (rc != MSRL_OK) {
+    msrl_learner_destroy(L);
+    return rc;
+  }
+  *out = L;
+  return MSRL_OK;
+}
+
+void msrl_learner_destroy(msrl_learner* L) {
+  if (!L) return;
+  void* ptrs[] = {L->xc, L->xt, L->grad, L->stats};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  for (int n = 0; n < 2; ++n) {
+    NetBufs& b = L->net[n];
+    void* q[] = {b.wt1, b.wt2, b.wt3, b.wn2, b.wn3, b.b3, b.h1, b.h2, b.y, b.dy, b.dz2, b.dz1,
+                 b.h1t, b.h2t, b.dyt, b.dz2t, b.dz1t};
+    for (void* p : q)
+      if (p) (void)hipFree(p);
+  }
+  delete L;
+}
+
+int msrl_ppo_grad(msrl_learner* L, const float* params, int64_t R, const float* obs, const void* actions,
+                  const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* cfg,
+                  float* grad, float* stats, void* hip_stream) {
+  int rc = check_learner_args("msrl_ppo_grad", L, params, R, obs, actions, logp_old, adv, ret, cfg);
+  if (rc != MSRL_OK) return rc;
+  if (!grad) return fail(MSRL_EINVAL, "msrl_ppo_grad: grad is NULL");
+  hipStream_t s = (hipStream_t)hip_stream;
+  rc = L->bf16 ? grad_pass<true>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s)
+               : grad_pass<false>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s);
+  if (rc != MSRL_OK) return rc;
+  if (stats) LTRY(hipMemcpyAsync(stats, L->stats, 5 * sizeof(float), hipMemcpyDeviceToDevice, s));
+  return MSRL_OK;
+}
+
+int msrl_adam_step(float* params, float* m, float* v, const float* grad, int64_t n, int64_t k,
+                   const msrl_ppo_cfg* cfg, void* hip_stream) {
+  if (!params || !m || !v || !grad || !cfg) return fail(MSRL_EINVAL, "msrl_adam_step: NULL argument");
+  if (n < 0 || k < 1) return fail(MSRL_EINVAL, "msrl_adam_step: n must be >= 0 and the step counter >= 1");
+  if (n == 0) return MSRL_OK;
+  const float c1 = (float)(1.0 - pow((double)cfg->beta1, (double)k));
+  const float c2 = (float)(1.0 - pow((double)cfg->beta2, (double)k));
+  hipLaunchKernelGGL(adam_kernel, grid1(n), dim3(256), 0, (hipStream_t)hip_stream, params, m, v, grad, n, cfg->lr,
+                     cfg->beta1, cfg->beta2, cfg->adam_eps, c1, c2);
+  LTRY(hipGetLastError());
+  return MSRL_OK;
+}
+
+int msrl_ppo_update(msrl_learner* L, float* params, float* m, float* v, int64_t* step_counter, int64_t R,
+                    int32_t iters, int32_t minibatches, const float* obs, const void* actions,
+                    const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* cfg,
+                    void* hip_stream) {
+  if (!L || !params || !m || !v || !step_counter || !obs || !actions || !logp_old || !adv || !ret || !cfg)
+    return fail(MSRL_EINVAL, "msrl_ppo_update: NULL argument");
+  if (iters < 1 || minibatches < 1 || R < minibatches)
+    return fail(MSRL_EINVAL, "msrl_ppo_update: iters and minibatches must be positive and R >= minibatches");
+  const int64_t block = R / minibatches;
+  const int64_t largest = R - block * (minibatches - 1);
+  if (largest > L->max_rows)
+    return fail(MSRL_EINVAL, "msrl_ppo_update: a minibatch of %lld rows exceeds the learner's %lld",
+                (long long)largest, (long long)L->max_rows);
+  const int D = L->pol.in_dim;
+  const size_t act_stride = L->pol.dist == MSRL_CATEGORICAL ? sizeof(int32_t) : sizeof(float) * (L->pol.out_dim / 2);
+  for (int it = 0; it < iters; ++it)
+    for (int b = 0; b < minibatches; ++b) {
+      const int64_t r0 = (int64_t)b * block, r1 = b == minibatches - 1 ? R : r0 + block;
+      int rc = msrl_ppo_grad(L, params, r1 - r0, obs + (size_t)r0 * D, (const uint8_t*)actions + (size_t)r0 * act_stride,
+                             logp_old + r0, adv + r0, ret + r0, cfg, L->grad, nullptr, hip_stream);
+      if (rc != MSRL_OK) return rc;
+      *step_counter += 1;
+      rc = msrl_adam_step(params, m, v, L->grad, (int64_t)L->n_params, *step_counter, cfg, hip_stream);
+      if (rc != MSRL_OK) return rc;
+    }
+  return MSRL_OK;
+}
+
+}  // extern "C"
