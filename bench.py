@@ -221,6 +221,35 @@ def main():
         except B.MsrlError:
             pass
 
+        # the learner's minibatch gradient (next row of the path) on rows of the trajectory just produced
+        try:
+            rows = int(min(T * M, 512 * 1024))
+            learner = B.msrl_learner_init(B.make_policy_cfg(cfg), rows)
+            master = torch.from_numpy(np.ascontiguousarray(params, dtype=np.float32)).cuda()
+            grad = torch.empty_like(master)
+            flat = lambda t: t.reshape(-1, *t.shape[2:])[:rows]
+            batch = (flat(out["obs"][:T]), flat(out["actions"]), flat(out["logp"]), flat(out["adv"]), flat(out["ret"]))
+            pc = B.make_ppo_cfg()
+            reps = 3
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for k in range(reps + 1):
+                if k == 1:
+                    ev0.record()
+                B.msrl_ppo_grad(learner, master, *batch, pc, grad)
+            ev1.record()
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1) / reps
+            B.msrl_learner_destroy(learner)
+            # forward + backward through the activations + weight gradients; no gradient w.r.t. the observation
+            fl = (3 * mlp_flops_per_agent_step(cfg) - 2 * 2 * cfg.obs_dim * cfg.hidden) * rows
+            tf = fl / (ms * 1e-3) / 1e12
+            phases["learner_grad"] = {"bound": "mfma", "ms_per_call": ms, "rows": rows, "achieved": tf,
+                                      "peak": PEAK_TFLOPS[dt_name], "unit": "TFLOP/s", "frac": tf / PEAK_TFLOPS[dt_name],
+                                      "rows_per_s": rows / (ms * 1e-3)}
+            del master, grad
+        except B.MsrlError:
+            pass
+
         # in-kernel clocks of the fused kernel: where one step of one workgroup spends its cycles
         stamps = torch.zeros(1024, dtype=torch.float32, device="cuda")
         try:

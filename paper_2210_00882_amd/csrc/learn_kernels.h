@@ -197,17 +197,22 @@ __global__ void fill_kernel(float* p, int64_t n, float v) {
   if (idx < n) p[idx] = v;
 }
 
-// out[u] += sum_r src[u][r], r < rows (src unit-major); one wave per unit
+// out[u] += sum_r src[u][r], r < rows (src unit-major).  blockIdx.x = unit, blockIdx.y = slice of
+// `per_slice` rows; one float atomic per workgroup.
 template <typename S>
-__global__ __launch_bounds__(64) void rowsum_kernel(const S* src, int64_t units, int64_t rows, int64_t lds_,
-                                                    float* out) {
+__global__ __launch_bounds__(256) void rowsum_kernel(const S* src, int64_t units, int64_t rows, int64_t lds_,
+                                                     int64_t per_slice, float* out) {
+  __shared__ float part[4];
   const int64_t u = blockIdx.x;
-  if (u >= units) return;
+  const int64_t r_begin = (int64_t)blockIdx.y * per_slice, r_end = min(rows, r_begin + per_slice);
   float s = 0.0f;
-  for (int64_t r = threadIdx.x; r < rows; r += 64) s += load_elem(src + u * lds_ + r);
+  if (u < units)
+    for (int64_t r = r_begin + threadIdx.x; r < r_end; r += 256) s += load_elem(src + u * lds_ + r);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-  if (threadIdx.x == 0) out[u] += s;
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0 && u < units) atomicAdd(out + u, part[0] + part[1] + part[2] + part[3]);
 }
 
 // ---------------------------------------------------------------- per-row loss

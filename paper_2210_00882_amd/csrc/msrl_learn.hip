@@ -175,9 +175,16 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h2t, H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, nullptr, nullptr, 0, slices)));
     LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h1t, H, Rp, b.dz2t, H, Rp, gW2, H, H, H, Rk, nullptr, nullptr, 0, slices)));
     LTRY((gemm<BF16, float, EPI_ATOMIC>(s, L->xt, Dp, Rp, b.dz1t, H, Rp, gW1, D, H, H, Rk, nullptr, nullptr, 0, slices)));
-    hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)O), dim3(64), 0, s, (const E*)b.dyt, (int64_t)O, R, Rp, gb3);
-    hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)H), dim3(64), 0, s, (const E*)b.dz2t, (int64_t)H, R, Rp, gb2);
-    hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)H), dim3(64), 0, s, (const E*)b.dz1t, (int64_t)H, R, Rp, gb1);
+    {
+      const int64_t per_slice = 16384;
+      const unsigned ns = (unsigned)((R + per_slice - 1) / per_slice);
+      hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)O, ns), dim3(256), 0, s, (const E*)b.dyt, (int64_t)O, R, Rp,
+                         per_slice, gb3);
+      hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)H, ns), dim3(256), 0, s, (const E*)b.dz2t, (int64_t)H, R, Rp,
+                         per_slice, gb2);
+      hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)H, ns), dim3(256), 0, s, (const E*)b.dz1t, (int64_t)H, R, Rp,
+                         per_slice, gb1);
+    }
     LTRY(hipGetLastError());
     off += net_count(D, H, O);
   }
