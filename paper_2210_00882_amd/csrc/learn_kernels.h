@@ -74,6 +74,28 @@ __device__ __forceinline__ void store_elem(__bf16* p, float v) { *p = (__bf16)v;
 __device__ __forceinline__ float load_elem(const float* p) { return *p; }
 __device__ __forceinline__ float load_elem(const __bf16* p) { return (float)*p; }
 
+// 8 consecutive elements as 16-byte pieces (the address must be 16-byte aligned: ld and column
+// offsets are multiples of 8 elements)
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  const f32x4 a = *(const f32x4*)p, b = *(const f32x4*)(p + 4);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { v[e] = a[e]; v[4 + e] = b[e]; }
+}
+__device__ __forceinline__ void load8(const __bf16* p, float (&v)[8]) {
+  const bf16x8 a = *(const bf16x8*)p;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+  *(f32x4*)p = f32x4{v[0], v[1], v[2], v[3]};
+  *(f32x4*)(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+}
+__device__ __forceinline__ void store8(__bf16* p, const float (&v)[8]) {
+  typedef float f32x8 __attribute__((ext_vector_type(8)));
+  const f32x8 f = {v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7]};
+  *(bf16x8*)p = __builtin_convertvector(f, bf16x8);
+}
+
 // ---------------------------------------------------------------- contraction
 enum : int {
   EPI_BIAS_TANH = 0,  // C = tanh(acc + bias[n])
@@ -100,6 +122,7 @@ template <bool BF16, typename SA, typename SB, typename SC, int EPI>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   typedef typename Frag<BF16>::T F;
   constexpr int KT = Frag<BF16>::KT, NT = 4;
+  __shared__ float s_c[EPI == EPI_ATOMIC ? 1 : 4][EPI == EPI_ATOMIC ? 1 : 32 * (32 * NT + 4)];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i = lane & 31, h = lane >> 5;
   const int64_t m0 = ((int64_t)blockIdx.x * 4 + wave) * 32;
@@ -125,6 +148,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   for (int j = 0; j < NT; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+#pragma unroll 4
   for (int64_t k = k_begin; k < k_end; k += KT) {
     const F a = a_ok ? load_frag(arow, (int)k, h, (F*)nullptr) : frag_zero((F*)nullptr);
 #pragma unroll
@@ -135,27 +159,65 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     }
   }
   // accumulator: lane (n = i, h), register r <-> row 8 (r / 4) + 4 h + r % 4 of the tile
+  if constexpr (EPI == EPI_ATOMIC) {
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    const int64_t n = n0 + 32 * j + i;
-    if (n >= g.N) continue;
-    const float bias = (EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) ? g.bias[n] : 0.0f;
+    for (int j = 0; j < NT; ++j) {
+      const int64_t n = n0 + 32 * j + i;
+      if (n >= g.N) continue;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int64_t m = m0 + 8 * (r / 4) + 4 * h + r % 4;
-      if (m >= g.M) continue;
-      float v = acc[j][r];
-      SC* dst = (SC*)g.C + m * g.ldc + n;
-      if (EPI == EPI_BIAS_TANH) v = tanhf(v + bias);
-      if (EPI == EPI_BIAS) v = v + bias;
-      if (EPI == EPI_DTANH) {
-        const float hv = load_elem((const SC*)g.Hm + m * g.ldh + n);
-        v = v * (1.0f - hv * hv);
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + 8 * (r / 4) + 4 * h + r % 4;
+        if (m < g.M) atomicAdd((float*)g.C + m * g.ldc + n, acc[j][r]);
       }
-      if (EPI == EPI_ATOMIC)
-        atomicAdd((float*)g.C + m * g.ldc + n, v);
-      else
-        store_elem(dst, v);
+    }
+  } else {
+    // Through the wave's LDS tile into row layout: a lane then owns 8 consecutive columns of a row, so
+    // C (and Hm) move as 16-byte pieces, 16 lanes per 128-column row, instead of one element per lane.
+    float* t = &s_c[wave][0];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t[(8 * (r / 4) + 4 * h + r % 4) * (32 * NT + 4) + 32 * j + i] = acc[j][r];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int c8 = (lane & 15) * 8;  // first of this lane's 8 columns
+    const int64_t n = n0 + c8;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int rl = (lane >> 4) + 4 * it;
+      const int64_t m = m0 + rl;
+      if (m >= g.M || n >= g.N) continue;
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = t[rl * (32 * NT + 4) + c8 + e];
+      if (n + 8 <= g.N) {
+        if (EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += g.bias[n + e];
+        }
+        if (EPI == EPI_BIAS_TANH) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = tanhf(v[e]);
+        }
+        if (EPI == EPI_DTANH) {
+          float hv[8];
+          load8((const SC*)g.Hm + m * g.ldh + n, hv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= 1.0f - hv[e] * hv[e];
+        }
+        store8((SC*)g.C + m * g.ldc + n, v);
+      } else {  // ragged last columns: one element at a time
+        for (int e = 0; e < 8 && n + e < g.N; ++e) {
+          float w = v[e];
+          if (EPI == EPI_BIAS_TANH) w = tanhf(w + g.bias[n + e]);
+          if (EPI == EPI_BIAS) w = w + g.bias[n + e];
+          if (EPI == EPI_DTANH) {
+            const float hv = load_elem((const SC*)g.Hm + m * g.ldh + n + e);
+            w = w * (1.0f - hv * hv);
+          }
+          store_elem((SC*)g.C + m * g.ldc + n + e, w);
+        }
+      }
     }
   }
 }
@@ -231,6 +293,8 @@ struct LossArgs {
   float clip, vf_coef, ent_coef, inv_R;
 };
 
+// One row per lane.  Every loop runs over the 32 padded columns with a predicate, so that the
+// per-row arrays stay in registers.
 template <typename SC>
 __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
   const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -241,8 +305,13 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
     for (int k = 0; k < 32; ++k) dy[k] = 0.0f;
     float dv = 0.0f;
     if (n < a.R) {
-      const float* y = a.y + n * 32;
       const int O = a.out_dim;
+      float y[32];
+#pragma unroll
+      for (int k = 0; k < 32; k += 4) {
+        const f32x4 t = *(const f32x4*)(a.y + n * 32 + k);
+        y[k] = t[0]; y[k + 1] = t[1]; y[k + 2] = t[2]; y[k + 3] = t[3];
+      }
       float logp = 0.0f, ent = 0.0f;
       float dlp[32];  // d logp / dy
       float dH[32];   // d entropy / dy
@@ -250,31 +319,44 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
       for (int k = 0; k < 32; ++k) dlp[k] = dH[k] = 0.0f;
       if (a.dist == 0) {
         float mx = y[0];
-        for (int k = 1; k < O; ++k) mx = fmaxf(mx, y[k]);
+#pragma unroll
+        for (int k = 1; k < 32; ++k) mx = k < O ? fmaxf(mx, y[k]) : mx;
         float z = 0.0f;
-        for (int k = 0; k < O; ++k) z += expf(y[k] - mx);
+#pragma unroll
+        for (int k = 0; k < 32; ++k) z += k < O ? expf(y[k] - mx) : 0.0f;
         const float lse = mx + logf(z);
         const int act = ((const int32_t*)a.actions)[n];
-        for (int k = 0; k < O; ++k) {
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
           const float lp = y[k] - lse;
-          ent -= expf(lp) * lp;
+          ent -= k < O ? expf(lp) * lp : 0.0f;
         }
-        for (int k = 0; k < O; ++k) {
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
           const float lp = y[k] - lse, pk = expf(lp);
           if (k == act) logp = lp;
-          dlp[k] = (k == act ? 1.0f : 0.0f) - pk;
-          dH[k] = -pk * (lp + ent);
+          dlp[k] = k < O ? (k == act ? 1.0f : 0.0f) - pk : 0.0f;
+          dH[k] = k < O ? -pk * (lp + ent) : 0.0f;
         }
       } else {
-        const int K = O / 2;
-        for (int d = 0; d < K; ++d) {
-          const float mu = y[d], ls = y[K + d], sg = expf(ls);
-          const float e = (((const float*)a.actions)[n * K + d] - mu) / sg;
-          logp += -0.5f * e * e - ls - 0.9189385332046727f;
-          ent += ls + 1.4189385332046727f;
-          dlp[d] = e / sg;
-          dlp[K + d] = e * e - 1.0f;
-          dH[K + d] = 1.0f;
+        const int K = O / 2;  // <= 16: mean d in column d, log-std in column K + d
+#pragma unroll
+        for (int d = 0; d < 16; ++d) {
+          if (d < K) {
+            float ls = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 32; ++k) ls = k == K + d ? y[k] : ls;
+            const float mu = y[d], sg = expf(ls);
+            const float e = (((const float*)a.actions)[n * K + d] - mu) / sg;
+            logp += -0.5f * e * e - ls - 0.9189385332046727f;
+            ent += ls + 1.4189385332046727f;
+            dlp[d] = e / sg;
+#pragma unroll
+            for (int k = 0; k < 32; ++k) {
+              dlp[k] = k == K + d ? e * e - 1.0f : dlp[k];
+              dH[k] = k == K + d ? 1.0f : dH[k];
+            }
+          }
         }
       }
       const float rho = expf(logp - a.logp_old[n]), A = a.adv[n];
@@ -282,7 +364,8 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
       const float un = rho * A, cl = rc * A;
       const bool clipped = cl < un;
       const float gl = clipped ? 0.0f : -A * rho;
-      for (int k = 0; k < O; ++k) dy[k] = (gl * dlp[k] - a.ent_coef * dH[k]) * a.inv_R;
+#pragma unroll
+      for (int k = 0; k < 32; ++k) dy[k] = (gl * dlp[k] - a.ent_coef * dH[k]) * a.inv_R;
       const float err = a.v[n * 32] - a.ret[n];
       dv = a.vf_coef * 2.0f * err * a.inv_R;
       s_pi = -(clipped ? cl : un);
@@ -294,9 +377,11 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
     SC* pdy = (SC*)a.dy + n * 32;
     SC* pdv = (SC*)a.dv + n * 32;
 #pragma unroll
-    for (int k = 0; k < 32; ++k) {
-      store_elem(pdy + k, dy[k]);
-      store_elem(pdv + k, k == 0 ? dv : 0.0f);
+    for (int k = 0; k < 32; k += 8) {
+      const float v8[8] = {dy[k], dy[k + 1], dy[k + 2], dy[k + 3], dy[k + 4], dy[k + 5], dy[k + 6], dy[k + 7]};
+      const float w8[8] = {k == 0 ? dv : 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+      store8(pdy + k, v8);
+      store8(pdv + k, w8);
     }
   }
   // block sums -> one atomic per statistic and wave
