@@ -222,6 +222,131 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   }
 }
 
+// ---------------------------------------------------------------- row-parallel contraction
+// C[m][n] = epilogue(sum_k A[m][k] B[n][k]) for many rows m and few columns n (a layer of a
+// network: B holds its weights).  A workgroup of 8 waves keeps the fragments of 32 NT columns of B
+// in LDS for its whole life and walks over 256-row tiles of A: a wave fetches the fragments of its
+// 32 rows straight from global memory and reads B from LDS.  The result passes through the
+// wave's LDS tile, 64 columns at a time: once row-wise (16-byte pieces of C, and of Hm for the
+// tanh derivative), then, if Ct is given, column-wise for the unit-major copy Ct[n][m] that the
+// weight-gradient contraction reads (rows m in [M, M_pad) of it are written as zero).
+// Needs K <= 256 and N a multiple of 8.
+struct RowGemmArgs {
+  GemmArgs g;
+  void* Ct;        // [N, ldt] or null
+  int64_t ldt;
+  int64_t M_pad;   // rows covered (>= M, a multiple of 16); tiles beyond are not visited
+  int64_t tiles;   // 256-row tiles
+};
+
+template <bool BF16, typename SC, int EPI, int NT>
+__global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
+  typedef typename Frag<BF16>::T F;
+  constexpr int KT = Frag<BF16>::KT, KK_MAX = 256 / KT, TW = 64 + 4;
+  static_assert(NT % 2 == 0, "the epilogue works on pairs of 32-column tiles");
+  __shared__ __attribute__((aligned(16))) u32x4 s_b[NT * KK_MAX * 64];
+  __shared__ float s_c[8][32 * TW];
+  const GemmArgs& g = ra.g;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = lane & 31, h = lane >> 5;
+  const int64_t n0 = (int64_t)blockIdx.y * (32 * NT);
+  const int KK = (int)(g.K / KT);
+  for (int idx = threadIdx.x; idx < NT * KK * 64; idx += 512) {
+    const int j = idx / (KK * 64), rem = idx % (KK * 64), kk = rem / 64, l = rem % 64;
+    const int64_t n = n0 + 32 * j + (l & 31);
+    const F f = n < g.N_alloc ? load_frag((const SC*)g.B + n * g.ldb, kk * KT, l >> 5, (F*)nullptr)
+                              : frag_zero((F*)nullptr);
+    s_b[idx] = __builtin_bit_cast(u32x4, f);
+  }
+  __syncthreads();
+  float* t = &s_c[wave][0];
+  for (int64_t tile = blockIdx.x; tile < ra.tiles; tile += gridDim.x) {
+    const int64_t m0 = (tile * 8 + wave) * 32;
+    if (m0 >= ra.M_pad) continue;  // wave-uniform
+    const SC* arow = (const SC*)g.A + (m0 + i) * g.lda;
+    const bool a_ok = m0 + i < g.M_alloc;
+    f32x16 acc[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+#pragma unroll 4
+    for (int kk = 0; kk < KK; ++kk) {
+      const F a = a_ok ? load_frag(arow, kk * KT, h, (F*)nullptr) : frag_zero((F*)nullptr);
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        if (n0 + 32 * j >= g.N) continue;  // uniform
+        mma_frag(a, __builtin_bit_cast(F, s_b[(j * KK + kk) * 64 + lane]), acc[j]);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < NT / 2; ++c) {
+      const int64_t nc = n0 + 64 * c;
+      if (nc >= g.N) continue;  // uniform
+      // accumulator: lane (n = i, h), register r <-> row 8 (r / 4) + 4 h + r % 4
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t[(8 * (r / 4) + 4 * h + r % 4) * TW + 32 * jj + i] = acc[2 * c + jj][r];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      {
+        const int c8 = (lane & 7) * 8;
+        const int64_t n = nc + c8;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int rl = (lane >> 3) + 8 * it;
+          const int64_t m = m0 + rl;
+          float v[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = t[rl * TW + c8 + e];
+          const bool live = m < g.M && n + 8 <= g.N;
+          if (live) {
+            if (EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] += g.bias[n + e];
+            }
+            if (EPI == EPI_BIAS_TANH) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] = tanhf(v[e]);
+            }
+            if (EPI == EPI_DTANH) {
+              float hv[8];
+              load8((const SC*)g.Hm + m * g.ldh + n, hv);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] *= 1.0f - hv[e] * hv[e];
+            }
+            store8((SC*)g.C + m * g.ldc + n, v);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = 0.0f;
+          }
+#pragma unroll
+          for (int e = 0; e < 8; ++e) t[rl * TW + c8 + e] = v[e];  // final values for the column pass
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (ra.Ct) {
+        const int64_t n = nc + lane;  // one column per lane
+        if (n < g.N) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (m0 + 8 * q >= ra.M_pad) continue;
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = t[(8 * q + e) * TW + lane];
+            store8((SC*)ra.Ct + n * ra.ldt + m0 + 8 * q, v);
+          }
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
 // ---------------------------------------------------------------- transposes, conversions
 // dst[c][r] = src[r][c] for r < rows, c < cols; dst rows are ldd long and columns in
 // [rows, rows_pad) are written as zero (the contraction over rows reads whole k tiles).
@@ -287,6 +412,9 @@ struct LossArgs {
   const float* ret;
   void* dy;             // [R_pad, 32] dL/dy of the policy net, compute type; pad rows and columns zero
   void* dv;             // [R_pad, 32] dL/dv in column 0
+  void* dyt;            // [32, ldt] unit-major copies of the two, columns [R, R_pad) zero
+  void* dvt;
+  int64_t ldt;
   float* stats;         // [5] += sum of: policy term, value term, entropy, clipped rows, logp_old - logp
   int64_t R, R_pad;
   int out_dim, dist;
@@ -382,6 +510,11 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
       const float w8[8] = {k == 0 ? dv : 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
       store8(pdy + k, v8);
       store8(pdv + k, w8);
+    }
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {  // consecutive lanes write consecutive rows of a unit
+      store_elem((SC*)a.dyt + k * a.ldt + n, dy[k]);
+      store_elem((SC*)a.dvt + k * a.ldt + n, k == 0 ? dv : 0.0f);
     }
   }
   // block sums -> one atomic per statistic and wave

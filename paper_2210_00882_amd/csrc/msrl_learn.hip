@@ -87,6 +87,26 @@ hipError_t gemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, cons
   return hipGetLastError();
 }
 
+// row-parallel contraction (weights in LDS, optional unit-major copy Ct of the result)
+template <bool BF16, typename SC, int EPI>
+hipError_t rowgemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, const void* B, int64_t N_alloc,
+                   int64_t ldb, void* C, int64_t M, int64_t N, int64_t ldc, int64_t K, const float* bias,
+                   const void* Hm, int64_t ldh, void* Ct, int64_t ldt, int64_t M_pad) {
+  constexpr int NT = BF16 ? 4 : 2;
+  RowGemmArgs ra;
+  memset(&ra, 0, sizeof(ra));
+  GemmArgs& g = ra.g;
+  g.A = A; g.B = B; g.C = C; g.bias = bias; g.Hm = Hm;
+  g.M = M; g.N = N; g.M_alloc = M_alloc; g.N_alloc = N_alloc; g.K = K;
+  g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ldh = ldh;
+  ra.Ct = Ct; ra.ldt = ldt; ra.M_pad = Ct ? M_pad : M;
+  ra.tiles = (ra.M_pad + 255) / 256;
+  if (K > 256 || N % 8 != 0) return hipErrorInvalidValue;  // shapes the learner never produces
+  dim3 grid((unsigned)(ra.tiles < 256 ? ra.tiles : 256), (unsigned)((N + 32 * NT - 1) / (32 * NT)));
+  hipLaunchKernelGGL((rowgemm_kernel<BF16, SC, EPI, NT>), grid, dim3(512), 0, s, ra);
+  return hipGetLastError();
+}
+
 template <typename S, typename D>
 hipError_t transpose(hipStream_t s, const S* src, int64_t rows, int64_t cols, int64_t ld_src, D* dst, int64_t ldd,
                      int64_t rows_pad, int64_t cols_out) {
@@ -136,8 +156,9 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     LTRY(convert_pad(s, W3, H, O, O, (E*)b.wn3, 32, H));
     LTRY(convert_pad(s, b3, 1, O, O, b.b3, 32, 1));
     // forward
-    LTRY((gemm<BF16, E, EPI_BIAS_TANH>(s, L->xc, Rp, Dp, b.wt1, H, Dp, b.h1, R, H, H, Dp, b1, nullptr, 0)));
-    LTRY((gemm<BF16, E, EPI_BIAS_TANH>(s, b.h1, Rp, H, b.wt2, H, H, b.h2, R, H, H, H, b2, nullptr, 0)));
+    // (the activations also leave unit-major, for the weight gradients)
+    LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, L->xc, Rp, Dp, b.wt1, H, Dp, b.h1, R, H, H, Dp, b1, nullptr, 0, b.h1t, Rp, Rk)));
+    LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, b.h1, Rp, H, b.wt2, H, H, b.h2, R, H, H, H, b2, nullptr, 0, b.h2t, Rp, Rk)));
     LTRY((gemm<BF16, float, EPI_BIAS>(s, b.h2, Rp, H, b.wt3, 32, H, b.y, R, 32, 32, H, b.b3, nullptr, 0)));
     P = b3 + O;
   }
@@ -146,6 +167,7 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     memset(&a, 0, sizeof(a));
     a.y = L->net[0].y; a.v = L->net[1].y; a.actions = actions; a.logp_old = logp_old; a.adv = adv; a.ret = ret;
     a.dy = L->net[0].dy; a.dv = L->net[1].dy; a.stats = L->stats; a.R = R; a.R_pad = Rk;
+    a.dyt = L->net[0].dyt; a.dvt = L->net[1].dyt; a.ldt = Rp;
     a.out_dim = L->pol.out_dim; a.dist = L->pol.dist;
     a.clip = c->clip; a.vf_coef = c->vf_coef; a.ent_coef = c->ent_coef; a.inv_R = 1.0f / (float)R;
     hipLaunchKernelGGL((loss_kernel<E>), grid1(Rk), dim3(256), 0, s, a);
@@ -162,14 +184,8 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     float* gW3 = gb2 + H;
     float* gb3 = gW3 + (size_t)H * O;
     // backward through the activations
-    LTRY((gemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, b.dz2, R, H, H, 32, nullptr, b.h2, H)));
-    LTRY((gemm<BF16, E, EPI_DTANH>(s, b.dz2, Rp, H, b.wn2, H, H, b.dz1, R, H, H, H, nullptr, b.h1, H)));
-    // unit-major copies for the contractions over the rows
-    LTRY(transpose(s, (const E*)b.h2, R, H, H, (E*)b.h2t, Rp, Rk, H));
-    LTRY(transpose(s, (const E*)b.h1, R, H, H, (E*)b.h1t, Rp, Rk, H));
-    LTRY(transpose(s, (const E*)b.dy, R, 32, 32, (E*)b.dyt, Rp, Rk, 32));
-    LTRY(transpose(s, (const E*)b.dz2, R, H, H, (E*)b.dz2t, Rp, Rk, H));
-    LTRY(transpose(s, (const E*)b.dz1, R, H, H, (E*)b.dz1t, Rp, Rk, H));
+    LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, b.dz2, R, H, H, 32, nullptr, b.h2, H, b.dz2t, Rp, Rk)));
+    LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dz2, Rp, H, b.wn2, H, H, b.dz1, R, H, H, H, nullptr, b.h1, H, b.dz1t, Rp, Rk)));
     // weight gradients: contraction over the rows, split over workgroups, fp32 atomics
     const int slices = (int)fmax(1.0, fmin(256.0, (double)(Rk / 2048)));
     LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h2t, H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, nullptr, nullptr, 0, slices)));
