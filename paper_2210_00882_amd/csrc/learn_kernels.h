@@ -347,6 +347,82 @@ __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
   }
 }
 
+// ---------------------------------------------------------------- weight-gradient contraction
+// C[m][n] += sum_k A[m][k] B[n][k] with few m, n (<= 256 each: the units of two layers) and a
+// very long k (the rows of the minibatch).  Output-stationary: workgroup z takes the k range
+// [z k_per_slice, (z+1) k_per_slice), wave w of its 8 waves the 32 rows m = 32 w .. 32 w + 31 of C
+// and all columns (up to 128 accumulator registers); the B fragments of a chunk of 4 k tiles are
+// shared through LDS (loaded once per workgroup, by all threads, one chunk ahead in registers), the
+// A fragments are the wave's own and come straight from global memory.  fp32 atomics at the end.
+template <bool BF16, typename S>
+__global__ __launch_bounds__(512) void wgrad_kernel(GemmArgs g) {
+  typedef typename Frag<BF16>::T F;
+  constexpr int KT = Frag<BF16>::KT, KC = 4 * KT, NTW = 8, PER = NTW * 4 * 64 / 512;  // fragments per thread
+  __shared__ __attribute__((aligned(16))) u32x4 s_b[NTW * 4 * 64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = lane & 31, h = lane >> 5;
+  const int64_t k_begin = (int64_t)blockIdx.x * g.k_per_slice, k_end = min(g.K, k_begin + g.k_per_slice);
+  if (k_begin >= k_end) return;  // whole workgroup
+  const int ntiles = (int)((g.N + 31) / 32);  // column tiles in use (<= NTW)
+  const int64_t m0 = 32 * wave;
+  const bool m_live = m0 < g.M;
+  const S* arow = (const S*)g.A + (m0 + i) * g.lda;
+  const bool a_ok = m_live && m0 + i < g.M_alloc;
+  // fragment `f` of this thread in a chunk: slot = f * 512 + tid -> (column tile j, k tile kk, lane l)
+  auto panel_frag = [&](int f, int64_t k0) -> F {
+    const int slot = f * 512 + threadIdx.x;
+    const int j = slot / 256, kk = (slot / 64) % 4, l = slot % 64;
+    const int64_t n = 32 * j + (l & 31), k = k0 + kk * KT;
+    if (j < ntiles && n < g.N_alloc && k < k_end)
+      return load_frag((const S*)g.B + n * g.ldb, (int)k, l >> 5, (F*)nullptr);
+    return frag_zero((F*)nullptr);
+  };
+  f32x16 acc[NTW];
+#pragma unroll
+  for (int j = 0; j < NTW; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+  F next[PER];
+#pragma unroll
+  for (int f = 0; f < PER; ++f) next[f] = panel_frag(f, k_begin);
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += KC) {
+#pragma unroll
+    for (int f = 0; f < PER; ++f) s_b[f * 512 + threadIdx.x] = __builtin_bit_cast(u32x4, next[f]);
+    __syncthreads();
+    if (k0 + KC < k_end) {
+#pragma unroll
+      for (int f = 0; f < PER; ++f) next[f] = panel_frag(f, k0 + KC);
+    }
+    F a[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      a[kk] = (a_ok && k0 + kk * KT < k_end) ? load_frag(arow, (int)(k0 + kk * KT), h, (F*)nullptr)
+                                            : frag_zero((F*)nullptr);
+    if (m_live) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) {
+          if (j >= ntiles) continue;  // uniform
+          mma_frag(a[kk], __builtin_bit_cast(F, s_b[(j * 4 + kk) * 64 + lane]), acc[j]);
+        }
+    }
+    __syncthreads();
+  }
+  if (!m_live) return;
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) {
+    const int64_t n = 32 * j + i;
+    if (j >= ntiles || n >= g.N) continue;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t m = m0 + 8 * (r / 4) + 4 * h + r % 4;
+      if (m < g.M) atomicAdd((float*)g.C + m * g.ldc + n, acc[j][r]);
+    }
+  }
+}
+
 // ---------------------------------------------------------------- transposes, conversions
 // dst[c][r] = src[r][c] for r < rows, c < cols; dst rows are ldd long and columns in
 // [rows, rows_pad) are written as zero (the contraction over rows reads whole k tiles).
@@ -403,6 +479,7 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const S* src, int64_t units
 }
 
 // ---------------------------------------------------------------- per-row loss
+constexpr int STAT_BINS = 64;
 struct LossArgs {
   const float* y;       // [R, 32] policy outputs (columns >= out_dim unused)
   const float* v;       // [R, 32] value output in column 0
@@ -415,7 +492,8 @@ struct LossArgs {
   void* dyt;            // [32, ldt] unit-major copies of the two, columns [R, R_pad) zero
   void* dvt;
   int64_t ldt;
-  float* stats;         // [5] += sum of: policy term, value term, entropy, clipped rows, logp_old - logp
+  float* stats;         // [8 + 5 * STAT_BINS]: bins at 8 + q * STAT_BINS += sum of statistic q: policy term,
+                        // value term, entropy, clipped rows, logp_old - logp
   int64_t R, R_pad;
   int out_dim, dist;
   float clip, vf_coef, ent_coef, inv_R;
@@ -517,13 +595,29 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
       store_elem((SC*)a.dvt + k * a.ldt + n, k == 0 ? dv : 0.0f);
     }
   }
-  // block sums -> one atomic per statistic and wave
+  // sums of the workgroup -> one atomic per statistic, spread over STAT_BINS bins per statistic
+  // (thousands of atomics on one address would serialise); stats_reduce_kernel adds the bins up
+  __shared__ float part[4][5];
   float s[5] = {s_pi, s_v, s_h, s_c, s_kl};
 #pragma unroll
   for (int q = 0; q < 5; ++q) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) s[q] += __shfl_xor(s[q], o);
-    if ((threadIdx.x & 63) == 0) atomicAdd(a.stats + q, s[q]);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6][q] = s[q];
+  }
+  __syncthreads();
+  if (threadIdx.x < 5)
+    atomicAdd(a.stats + 8 + threadIdx.x * STAT_BINS + blockIdx.x % STAT_BINS,
+              part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x]);
+}
+
+// stats[q] = sum of the bins of statistic q (one wave)
+__global__ __launch_bounds__(64) void stats_reduce_kernel(float* stats) {
+  for (int q = 0; q < 5; ++q) {
+    float s = stats[8 + q * STAT_BINS + threadIdx.x];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (threadIdx.x == 0) stats[q] = s;
   }
 }
 

@@ -41,7 +41,7 @@ struct msrl_learner {
   void* xt;              // [Dp, Rp]
   NetBufs net[2];
   float* grad;           // scratch gradient of msrl_ppo_update
-  float* stats;          // [8]
+  float* stats;          // [8 + 5 * STAT_BINS]: results, then the bins the loss kernel adds into
   size_t n_params;
 };
 
@@ -107,6 +107,24 @@ hipError_t rowgemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, c
   return hipGetLastError();
 }
 
+// weight-gradient contraction: C[M <= 256, N <= 256] += A B^T over K = rows, split into `slices`
+template <bool BF16>
+hipError_t wgrad(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, const void* B, int64_t N_alloc,
+                 int64_t ldb, float* C, int64_t M, int64_t N, int64_t ldc, int64_t K, int slices) {
+  typedef typename CT<BF16>::T E;
+  if (M > 256 || N > 256) return hipErrorInvalidValue;
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.A = A; g.B = B; g.C = C;
+  g.M = M; g.N = N; g.M_alloc = M_alloc; g.N_alloc = N_alloc; g.K = K;
+  g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  const int64_t kc = 4 * Frag<BF16>::KT;
+  g.k_per_slice = round_up((K + slices - 1) / slices, kc);
+  const int64_t used = (K + g.k_per_slice - 1) / g.k_per_slice;
+  hipLaunchKernelGGL((wgrad_kernel<BF16, E>), dim3((unsigned)used), dim3(512), 0, s, g);
+  return hipGetLastError();
+}
+
 template <typename S, typename D>
 hipError_t transpose(hipStream_t s, const S* src, int64_t rows, int64_t cols, int64_t ld_src, D* dst, int64_t ldd,
                      int64_t rows_pad, int64_t cols_out) {
@@ -134,7 +152,7 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
   const int64_t Rp = L->Rp;
   const int64_t Rk = round_up(R, 16);  // rows as a contraction length
   hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
-  hipLaunchKernelGGL(fill_kernel, grid1(8), dim3(256), 0, s, L->stats, (int64_t)8, 0.0f);
+  hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
   // observations in compute type, padded; and unit-major
   LTRY(convert_pad(s, obs, R, D, D, (E*)L->xc, Dp, Rk));
   LTRY(transpose(s, (const E*)L->xc, R, Dp, Dp, (E*)L->xt, Rp, Rk, Dp));
@@ -171,6 +189,7 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     a.out_dim = L->pol.out_dim; a.dist = L->pol.dist;
     a.clip = c->clip; a.vf_coef = c->vf_coef; a.ent_coef = c->ent_coef; a.inv_R = 1.0f / (float)R;
     hipLaunchKernelGGL((loss_kernel<E>), grid1(Rk), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
     LTRY(hipGetLastError());
   }
   size_t off = 0;
@@ -187,10 +206,16 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, b.dz2, R, H, H, 32, nullptr, b.h2, H, b.dz2t, Rp, Rk)));
     LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dz2, Rp, H, b.wn2, H, H, b.dz1, R, H, H, H, nullptr, b.h1, H, b.dz1t, Rp, Rk)));
     // weight gradients: contraction over the rows, split over workgroups, fp32 atomics
-    const int slices = (int)fmax(1.0, fmin(256.0, (double)(Rk / 2048)));
-    LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h2t, H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, nullptr, nullptr, 0, slices)));
-    LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h1t, H, Rp, b.dz2t, H, Rp, gW2, H, H, H, Rk, nullptr, nullptr, 0, slices)));
-    LTRY((gemm<BF16, float, EPI_ATOMIC>(s, L->xt, Dp, Rp, b.dz1t, H, Rp, gW1, D, H, H, Rk, nullptr, nullptr, 0, slices)));
+    const int slices = (int)fmax(1.0, fmin(512.0, (double)(Rk / 1024)));
+    if (H <= 256) {
+      LTRY((wgrad<BF16>(s, b.h2t, H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, slices)));
+      LTRY((wgrad<BF16>(s, b.h1t, H, Rp, b.dz2t, H, Rp, gW2, H, H, H, Rk, slices)));
+      LTRY((wgrad<BF16>(s, L->xt, Dp, Rp, b.dz1t, H, Rp, gW1, D, H, H, Rk, slices)));
+    } else {
+      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h2t, H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, nullptr, nullptr, 0, slices)));
+      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h1t, H, Rp, b.dz2t, H, Rp, gW2, H, H, H, Rk, nullptr, nullptr, 0, slices)));
+      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, L->xt, Dp, Rp, b.dz1t, H, Rp, gW1, D, H, H, Rk, nullptr, nullptr, 0, slices)));
+    }
     {
       const int64_t per_slice = 16384;
       const unsigned ns = (unsigned)((R + per_slice - 1) / per_slice);
@@ -260,7 +285,7 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
     A(&b.dz2t, H * Rp * e); A(&b.dz1t, H * Rp * e);
   }
   A((void**)&L->grad, L->n_params * sizeof(float));
-  A((void**)&L->stats, 8 * sizeof(float));
+  A((void**)&L->stats, (8 + 5 * STAT_BINS) * sizeof(float));
   if (rc != MSRL_OK) {
     msrl_learner_destroy(L);
     return rc;
