@@ -4,14 +4,13 @@
 // on MFMA with the activations kept in device memory, plus the per-row loss,
 // the transposes the weight gradients need, and Adam.
 //
-// First version: correctness first.  Every contraction is one launch of the
-// same kernel, C[m][n] = sum_k A[m][k] * B[n][k], whose two operands are both
-// stored with k contiguous, so that each lane fetches its MFMA fragment with
-// one 16-byte load straight from global memory (no LDS tiling yet: the weights
-// of a contraction are re-read from L2 by every wave).  The weight gradients
-// contract over the rows, so they take the transposed copies (unit-major) that
-// transpose_kernel makes.  Every global access is bounds-checked against the
-// extents passed in.
+// Every contraction has the form C[m][n] = sum_k A[m][k] * B[n][k] with both operands stored
+// k-contiguous, so that a lane fetches its MFMA fragment with one 16-byte load.  Three kernels:
+// rowgemm_kernel for the layers (many rows, few columns; weights resident in LDS; writes the
+// result row-major and, for the weight gradients, unit-major, and sums the columns for the bias
+// gradient), wgrad_kernel for the weight gradients (few outputs, the rows as contraction index;
+// output-stationary with LDS panels), gemm_kernel as the general fallback.  Every global access
+// is bounds-checked against the extents passed in.
 #pragma once
 #include "dev_common.h"
 
@@ -229,14 +228,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 // 32 rows straight from global memory and reads B from LDS.  The result passes through the
 // wave's LDS tile, 64 columns at a time: once row-wise (16-byte pieces of C, and of Hm for the
 // tanh derivative), then, if Ct is given, column-wise for the unit-major copy Ct[n][m] that the
-// weight-gradient contraction reads (rows m in [M, M_pad) of it are written as zero).
-// Needs K <= 256 and N a multiple of 8.
+// weight-gradient contraction reads (rows m in [M, M_pad) of it are written as zero); the column
+// pass can also add up the columns (the bias gradient).  C itself may be null when only the
+// unit-major copy is wanted.  Needs K <= 256 and N a multiple of 8.
 struct RowGemmArgs {
   GemmArgs g;
   void* Ct;        // [N, ldt] or null
   int64_t ldt;
   int64_t M_pad;   // rows covered (>= M, a multiple of 16); tiles beyond are not visited
   int64_t tiles;   // 256-row tiles
+  float* colsum;   // with Ct: colsum[n] += sum_m C[m][n] (the bias gradient of the layer), or null
 };
 
 template <bool BF16, typename SC, int EPI, int NT>
@@ -261,6 +262,9 @@ __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
   }
   __syncthreads();
   float* t = &s_c[wave][0];
+  float csum[NT / 2];  // column sums of this lane's column of each 64-column chunk
+#pragma unroll
+  for (int c = 0; c < NT / 2; ++c) csum[c] = 0.0f;
   for (int64_t tile = blockIdx.x; tile < ra.tiles; tile += gridDim.x) {
     const int64_t m0 = (tile * 8 + wave) * 32;
     if (m0 >= ra.M_pad) continue;  // wave-uniform
@@ -317,7 +321,7 @@ __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
 #pragma unroll
               for (int e = 0; e < 8; ++e) v[e] *= 1.0f - hv[e] * hv[e];
             }
-            store8((SC*)g.C + m * g.ldc + n, v);
+            if (g.C) store8((SC*)g.C + m * g.ldc + n, v);
           } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = 0.0f;
@@ -338,11 +342,20 @@ __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = t[(8 * q + e) * TW + lane];
             store8((SC*)ra.Ct + n * ra.ldt + m0 + 8 * q, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) csum[c] += v[e];
           }
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
+    }
+  }
+  if (ra.Ct && ra.colsum) {
+#pragma unroll
+    for (int c = 0; c < NT / 2; ++c) {
+      const int64_t n = n0 + 64 * c + lane;
+      if (n < g.N) atomicAdd(ra.colsum + n, csum[c]);
     }
   }
 }

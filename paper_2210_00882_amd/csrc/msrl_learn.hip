@@ -25,7 +25,7 @@ struct NetBufs {
   float *b1, *b2, *b3;    // biases (b3 padded to 32)
   void *h1, *h2;          // [Rp, H]
   float* y;               // [Rp, 32]
-  void *dy, *dz2, *dz1;   // [Rp, 32], [Rp, H], [Rp, H]
+  void *dy, *dz2;         // [Rp, 32], [Rp, H]
   void *h1t, *h2t, *dyt, *dz2t, *dz1t;  // unit-major copies: [H | 32, Rp]
 };
 
@@ -91,7 +91,7 @@ hipError_t gemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, cons
 template <bool BF16, typename SC, int EPI>
 hipError_t rowgemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, const void* B, int64_t N_alloc,
                    int64_t ldb, void* C, int64_t M, int64_t N, int64_t ldc, int64_t K, const float* bias,
-                   const void* Hm, int64_t ldh, void* Ct, int64_t ldt, int64_t M_pad) {
+                   const void* Hm, int64_t ldh, void* Ct, int64_t ldt, int64_t M_pad, float* colsum = nullptr) {
   constexpr int NT = BF16 ? 4 : 2;
   RowGemmArgs ra;
   memset(&ra, 0, sizeof(ra));
@@ -99,7 +99,7 @@ hipError_t rowgemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, c
   g.A = A; g.B = B; g.C = C; g.bias = bias; g.Hm = Hm;
   g.M = M; g.N = N; g.M_alloc = M_alloc; g.N_alloc = N_alloc; g.K = K;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ldh = ldh;
-  ra.Ct = Ct; ra.ldt = ldt; ra.M_pad = Ct ? M_pad : M;
+  ra.Ct = Ct; ra.ldt = ldt; ra.M_pad = Ct ? M_pad : M; ra.colsum = colsum;
   ra.tiles = (ra.M_pad + 255) / 256;
   if (K > 256 || N % 8 != 0) return hipErrorInvalidValue;  // shapes the learner never produces
   dim3 grid((unsigned)(ra.tiles < 256 ? ra.tiles : 256), (unsigned)((N + 32 * NT - 1) / (32 * NT)));
@@ -203,8 +203,10 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     float* gW3 = gb2 + H;
     float* gb3 = gW3 + (size_t)H * O;
     // backward through the activations
-    LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, b.dz2, R, H, H, 32, nullptr, b.h2, H, b.dz2t, Rp, Rk)));
-    LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dz2, Rp, H, b.wn2, H, H, b.dz1, R, H, H, H, nullptr, b.h1, H, b.dz1t, Rp, Rk)));
+    // (dZ2 and dZ1 leave unit-major too, and their column sums are the bias gradients; dZ1 is not
+    // needed row-major)
+    LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, b.dz2, R, H, H, 32, nullptr, b.h2, H, b.dz2t, Rp, Rk, gb2)));
+    LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dz2, Rp, H, b.wn2, H, H, nullptr, R, H, H, H, nullptr, b.h1, H, b.dz1t, Rp, Rk, gb1)));
     // weight gradients: contraction over the rows, split over workgroups, fp32 atomics
     const int slices = (int)fmax(1.0, fmin(512.0, (double)(Rk / 1024)));
     if (H <= 256) {
@@ -221,10 +223,6 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
       const unsigned ns = (unsigned)((R + per_slice - 1) / per_slice);
       hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)O, ns), dim3(256), 0, s, (const E*)b.dyt, (int64_t)O, R, Rp,
                          per_slice, gb3);
-      hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)H, ns), dim3(256), 0, s, (const E*)b.dz2t, (int64_t)H, R, Rp,
-                         per_slice, gb2);
-      hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)H, ns), dim3(256), 0, s, (const E*)b.dz1t, (int64_t)H, R, Rp,
-                         per_slice, gb1);
     }
     LTRY(hipGetLastError());
     off += net_count(D, H, O);
@@ -280,7 +278,7 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
     A((void**)&b.b3, 32 * sizeof(float));
     A(&b.h1, Rp * H * e); A(&b.h2, Rp * H * e);
     A((void**)&b.y, Rp * 32 * sizeof(float));
-    A(&b.dy, Rp * 32 * e); A(&b.dz2, Rp * H * e); A(&b.dz1, Rp * H * e);
+    A(&b.dy, Rp * 32 * e); A(&b.dz2, Rp * H * e);
     A(&b.h1t, H * Rp * e); A(&b.h2t, H * Rp * e); A(&b.dyt, 32 * Rp * e);
     A(&b.dz2t, H * Rp * e); A(&b.dz1t, H * Rp * e);
   }
@@ -301,7 +299,7 @@ void msrl_learner_destroy(msrl_learner* L) {
     if (p) (void)hipFree(p);
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
-    void* q[] = {b.wt1, b.wt2, b.wt3, b.wn2, b.wn3, b.b3, b.h1, b.h2, b.y, b.dy, b.dz2, b.dz1,
+    void* q[] = {b.wt1, b.wt2, b.wt3, b.wn2, b.wn3, b.b3, b.h1, b.h2, b.y, b.dy, b.dz2,
                  b.h1t, b.h2t, b.dyt, b.dz2t, b.dz1t};
     for (void* p : q)
       if (p) (void)hipFree(p);

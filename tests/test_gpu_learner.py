@@ -147,3 +147,31 @@ def test_adam_step_and_update_loop():
         assert e.value.code == B.MSRL_EINVAL
     finally:
         B.msrl_learner_destroy(L)
+
+
+@pytest.mark.parametrize("R", [1, 17, 256])
+def test_gradient_for_tiny_and_exactly_full_workspaces(R):
+    import torch
+    from paper_2210_00882_amd import binding as B
+    cfg = synth.CONFIGS[1]
+    params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
+    pol, obs, actions, logp_old, adv, ret = make_batch(cfg, R, 21 + R, params)
+    _, g_ref, st_ref = ref.ppo_loss(pol, ref.ppo_cfg(), params, obs, actions, logp_old, adv, ret)
+    L = B.msrl_learner_init(B.make_policy_cfg(cfg), R)      # workspace of exactly R rows
+    try:
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        grad = torch.empty(params.size, dtype=torch.float32, device="cuda")
+        stats = torch.zeros(5, dtype=torch.float32, device="cuda")
+        B.msrl_ppo_grad(L, dev(params.astype(np.float32)), dev(obs), dev(actions), dev(logp_old), dev(adv), dev(ret),
+                        B.make_ppo_cfg(), grad, stats)
+        torch.cuda.synchronize()
+        with pytest.raises(B.MsrlError) as e:     # one row more than the workspace holds
+            B.msrl_ppo_grad(L, dev(params.astype(np.float32)), dev(np.zeros((R + 1, cfg.obs_dim), np.float32)),
+                            dev(np.zeros(R + 1, np.int32)), dev(np.zeros(R + 1, np.float32)),
+                            dev(np.zeros(R + 1, np.float32)), dev(np.zeros(R + 1, np.float32)), B.make_ppo_cfg(), grad)
+        assert e.value.code == B.MSRL_EINVAL
+    finally:
+        B.msrl_learner_destroy(L)
+    g = grad.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(stats.cpu().numpy()[[0, 1, 2]] / R, st_ref[[0, 1, 2]], rtol=1e-4, atol=1e-4)
+    assert np.abs(g - g_ref).max() <= 1e-4 * np.abs(g_ref).max()
