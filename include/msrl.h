@@ -278,6 +278,10 @@ int msrl_ppo_grad(msrl_learner* learner, const float* params, int64_t R, const f
 int msrl_adam_step(float* params, float* m, float* v, const float* grad, int64_t n, int64_t k,
                    const msrl_ppo_cfg* cfg, void* hip_stream);
 
+/* out [n] (policy dtype: float or bfloat16, nearest even) <- master [n] (float): the parameter
+ * buffer msrl_rollout_step takes, from the learner's float32 master copy. */
+int msrl_params_cast(const float* master, void* out, int64_t n, int32_t dtype, void* hip_stream);
+
 /*
  * The training loop of Learner.learn: `iters` passes over the R rows, each
  * split into `minibatches` consecutive blocks of rows (the last one takes the

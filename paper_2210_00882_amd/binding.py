@@ -22,7 +22,7 @@ MSRL_PHASE_ENV, MSRL_PHASE_MLP, MSRL_PHASE_CLOCKS = 1, 2, 3
 EXPORTS = (
     "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",
     "msrl_rollout_gae", "msrl_measure_phase", "msrl_observe", "msrl_act", "msrl_env_step",
-    "msrl_learner_init", "msrl_learner_destroy", "msrl_ppo_grad", "msrl_adam_step", "msrl_ppo_update", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
+    "msrl_learner_init", "msrl_learner_destroy", "msrl_ppo_grad", "msrl_adam_step", "msrl_ppo_update", "msrl_params_cast", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
 )
 
 
@@ -99,6 +99,8 @@ def load():
     lib.msrl_ppo_grad.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, C.POINTER(msrl_ppo_cfg), vp, vp, vp]
     lib.msrl_adam_step.restype = C.c_int
     lib.msrl_adam_step.argtypes = [vp, vp, vp, vp, i64, i64, C.POINTER(msrl_ppo_cfg), vp]
+    lib.msrl_params_cast.restype = C.c_int
+    lib.msrl_params_cast.argtypes = [vp, vp, i64, i32, vp]
     lib.msrl_ppo_update.restype = C.c_int
     lib.msrl_ppo_update.argtypes = [vp, vp, vp, vp, C.POINTER(i64), i64, i32, i32, vp, vp, vp, vp, vp,
                                     C.POINTER(msrl_ppo_cfg), vp]
@@ -247,6 +249,11 @@ def msrl_ppo_grad(learner, params, obs, actions, logp_old, adv, ret, cfg: msrl_p
 def msrl_adam_step(params, m, v, grad, k: int, cfg: msrl_ppo_cfg, stream=None) -> None:
     _check(load().msrl_adam_step(_ptr(params), _ptr(m), _ptr(v), _ptr(grad), C.c_int64(params.numel()),
                                  C.c_int64(k), C.byref(cfg), _stream(stream)))
+
+
+def msrl_params_cast(master, out, dtype: int, stream=None) -> None:
+    _check(load().msrl_params_cast(_ptr(master), _ptr(out), C.c_int64(master.numel()), C.c_int32(dtype),
+                                   _stream(stream)))
 
 
 def msrl_ppo_update(learner, params, m, v, step: int, iters: int, minibatches: int, obs, actions, logp_old, adv,

@@ -334,6 +334,18 @@ int msrl_adam_step(float* params, float* m, float* v, const float* grad, int64_t
   return MSRL_OK;
 }
 
+int msrl_params_cast(const float* master, void* out, int64_t n, int32_t dtype, void* hip_stream) {
+  if (!master || !out) return fail(MSRL_EINVAL, "msrl_params_cast: NULL argument");
+  if (n < 0 || (dtype != MSRL_F32 && dtype != MSRL_BF16)) return fail(MSRL_EINVAL, "msrl_params_cast: bad size or dtype");
+  if (n == 0) return MSRL_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (dtype == MSRL_BF16)
+    LTRY(convert_pad(s, master, 1, n, n, (__bf16*)out, n, 1));
+  else
+    LTRY(convert_pad(s, master, 1, n, n, (float*)out, n, 1));
+  return MSRL_OK;
+}
+
 int msrl_ppo_update(msrl_learner* L, float* params, float* m, float* v, int64_t* step_counter, int64_t R,
                     int32_t iters, int32_t minibatches, const float* obs, const void* actions,
                     const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* cfg,
