@@ -1,0 +1,463 @@
+// Learner's gradient pass with the activations kept on chip (bf16 networks, categorical policy).
+//
+// ppo_rows_kernel runs forward pass, per-row loss and backward pass through the activations for a
+// tile of 32 rows per wave, in the transposed "chained" form of the rollout kernels (mlp.h): a
+// layer's accumulators (units x rows) are the next layer's B operand, so h1, h2, dL/dz2 and dL/dz1
+// never leave the register file.  What the weight gradients need -- the layer inputs and the
+// pre-activation gradients with the rows as contraction index -- is written once, as bf16, in a
+// tiled unit-major layout:
+//     tensor[tile][unit][32 rows],   tile = row / 32,
+// i.e. the 16 KiB a wave produces per tensor and tile are contiguous, and a lane of the weight
+// gradient kernel (wgrad_tiled_kernel) fetches the 8 rows of its MFMA fragment with one 16-byte
+// load.  Weights reach the row kernel as MFMA A-operand tiles (packed.h) through the LDS window of
+// WeightStream: per 32-row tile the forward chunk blocks (W2 by output chunk, W3), then the
+// backward chunk blocks (W2 by input chunk); the layer-1 tiles and the tiles of W3 for the backward
+// pass stay resident.
+//
+// Per-row loss (Listing 1 of the paper, mappo_net_train; the definition is that of the clipped
+// surrogate objective stated with msrl_ppo_grad in the interface header).
+#pragma once
+#include "mlp.h"
+
+namespace msrl {
+
+// ---------------------------------------------------------------- row kernel
+struct RowsArgs {
+  const uint8_t* packed;  // this network: forward image (NetLayout), then backward image of the same size:
+                          // W3 tiles for dL/dz2 in the layer-1 area, W2 tiles by input chunk in the chunk blocks
+  const float* b3;        // output bias [out_dim] (fp32 master)
+  const float* obs;       // [R, D]
+  const void* actions;    // int32 [R]
+  const float* logp_old;
+  const float* adv;
+  const float* ret;
+  int64_t R, n_tiles;     // n_tiles = ceil(R / 32)
+  int D, out_dim;
+  int obs_vec4;           // rows of obs may be read as 16-byte pieces (D % 4 == 0, base aligned)
+  float clip, vf_coef, ent_coef, inv_R;
+  // tiled unit-major outputs (bf16): xt has 16 KT1 units, h1t .. dz1t have H, dyt has 16
+  __bf16 *xt, *h1t, *h2t, *dz2t, *dz1t, *dyt;
+  float* stats;  // bins as in LossArgs
+};
+
+__device__ __forceinline__ uint32_t quad_swap1(uint32_t x) {  // value of lane ^ 1
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false);
+}
+
+// Stores values held one row per lane and two consecutive units per 32-bit register into a tile
+// [unit][32 rows]: neighbouring lanes trade halves, so that a lane holds two consecutive rows of one
+// unit and the wave writes 64-byte runs.  `unit` is the unit of the low half of this lane's register.
+__device__ __forceinline__ void store_pair_t(__bf16* tile, int unit, uint32_t x, int n) {
+  const uint32_t p = quad_swap1(x);
+  const uint32_t v = __builtin_amdgcn_perm(p, x, (n & 1) ? 0x03020706u : 0x05040100u);
+  *(uint32_t*)(tile + (size_t)(unit + (n & 1)) * 32 + (n & ~1)) = v;
+}
+
+// one 32-unit chunk in operand form (NOPS = 2) or its first 16 units (NOPS = 1)
+template <int NOPS>
+__device__ __forceinline__ void store_chunk_t(__bf16* tile, int unit0, const bf16x8 (&op)[2], int n, int h) {
+#pragma unroll
+  for (int j = 0; j < NOPS; ++j) {
+    const u32x4 w = __builtin_bit_cast(u32x4, op[j]);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const int r = 8 * j + 2 * d;  // accumulator register of the low half
+      store_pair_t(tile, unit0 + 8 * (r / 4) + 4 * h + r % 4, w[d], n);
+    }
+  }
+}
+
+// acc * (1 - a^2) for accumulator registers [r0, r1), a = the stored (rounded) activation
+__device__ __forceinline__ void dtanh_range(const f32x16& acc, const bf16x8 (&hp)[2], float (&t)[16], int r0,
+                                            int r1, bool pinned) {
+  float v[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) {
+      v[r] = acc[r];
+      if (pinned) pin(v[r]);
+    }
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) {
+      const float a = (float)hp[r / 8][r % 8];
+      t[r] = v[r] * (1.0f - a * a);
+    }
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1 && pinned) pin(t[r]);
+}
+
+// One chunk block of the forward pass: acc <- layer-2 pre-activations of the block's 32 units (bias
+// included); if PIPE, `acc` holds those of the chunk before on entry: they get tanh, feed layer 3
+// (out) and are returned as operands in hprev.  tick(kt) runs once per layer-2 tile.
+template <class Net, bool PIPE, class Tick>
+__device__ __forceinline__ void fwd_chunk(const u32x4* tiles, const bf16x8 (&h1)[1][Net::KT2], f32x16& acc,
+                                          f32x16& out, int h, bf16x8 (&hprev)[2], Tick&& tick) {
+  constexpr int KT2 = Net::KT2, TPC = Net::TPC, G = Net::G, LAST = Net::L3_PREV + TPC;
+  u32x4 ring[G];
+#pragma unroll
+  for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
+  const f32x16 prev = acc;
+  float t[16];
+  acc = zero16();
+#pragma unroll
+  for (int kt = 0; kt < KT2; ++kt) {
+    u32x4 raw = ring[kt % G];
+    if (kt + G < LAST) ring[kt % G] = tiles[(kt + G) * 64];
+    if (PIPE) pin(raw);
+    acc = mma(__builtin_bit_cast(bf16x8, raw), h1[0][kt], acc);
+    if (PIPE) tanh_range(prev, t, kt * 16 / KT2, (kt + 1) * 16 / KT2, true);
+    tick(kt);
+  }
+  {
+    bf16x8 one = {0, 0, 0, 0, 0, 0, 0, 0};  // the two parts of the bias sit at k slots 0 and 1 of h = 0
+    one[0] = (__bf16)(h == 0 ? 1.0f : 0.0f);
+    one[1] = one[0];
+    const u32x4 raw = ring[KT2 % G];
+    if (KT2 + G < LAST) ring[KT2 % G] = tiles[(KT2 + G) * 64];
+    acc = mma(__builtin_bit_cast(bf16x8, raw), one, acc);
+  }
+  if (PIPE) {
+    to_operands<true>(t, hprev);
+#pragma unroll
+    for (int i = 0; i < TPC; ++i)
+      out = mma(__builtin_bit_cast(bf16x8, ring[(Net::L3_PREV + i) % G]), hprev[i], out);
+  }
+}
+
+// One chunk block of the backward pass: acc <- W2 dz2 for the block's 32 layer-1 units; if PIPE, the
+// result of the chunk before (in `acc` on entry) is multiplied by 1 - h1^2 (hp: that chunk's
+// activations) and returned as operands in dprev.
+template <class Net, bool PIPE, class Tick>
+__device__ __forceinline__ void bwd_chunk(const u32x4* tiles, const bf16x8 (&dz2)[Net::KT2], f32x16& acc,
+                                          const bf16x8 (&hp)[2], bf16x8 (&dprev)[2], Tick&& tick) {
+  constexpr int KT2 = Net::KT2, G = Net::G;
+  u32x4 ring[G];
+#pragma unroll
+  for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
+  const f32x16 prev = acc;
+  float t[16];
+  acc = zero16();
+#pragma unroll
+  for (int kt = 0; kt < KT2; ++kt) {
+    u32x4 raw = ring[kt % G];
+    if (kt + G < KT2) ring[kt % G] = tiles[(kt + G) * 64];
+    if (PIPE) pin(raw);
+    acc = mma(__builtin_bit_cast(bf16x8, raw), dz2[kt], acc);
+    if (PIPE) dtanh_range(prev, hp, t, kt * 16 / KT2, (kt + 1) * 16 / KT2, true);
+    tick(kt);
+  }
+  if (PIPE) to_operands<true>(t, dprev);
+}
+
+#ifndef MSRL_ROWS_WAVES
+#define MSRL_ROWS_WAVES 4
+#endif
+constexpr int ROWS_WAVES = MSRL_ROWS_WAVES;  // waves per workgroup of the row kernel = row tiles per group
+constexpr int ROWS_STAT_BINS = 64;  // bins per statistic in RowsArgs::stats (after 8 result slots)
+
+template <int H, int KT1, int NET, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
+  constexpr int NBUF = 2;
+  typedef Mlp<H, true, 1, KT1> Net;
+  constexpr int NUC = Net::NUC, KT2 = Net::KT2, TPC = Net::TPC, G = Net::G;
+  constexpr int CPS = NUC % 2 == 0 ? 2 : 1;
+  typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
+  constexpr int SPN = Stream::STAGES_PER_NET;
+  typedef bf16x8 Op;
+  static_assert(KT2 >= G && TPC <= 2, "ring prefetch depth; layer-3 tiles per chunk");
+
+  __shared__ __attribute__((aligned(16))) u32x4 s_l1[Net::L1_TILES * 64];
+  __shared__ __attribute__((aligned(16))) u32x4 s_w3t[NUC * 64];
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[NBUF * Stream::BUF_SLOTS];
+  __shared__ __attribute__((aligned(16))) float s_b3[32];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 31, h = lane >> 5;
+  const int O = NET == 0 ? a.out_dim : 1;
+  const NetLayout ly = net_layout(16 * KT1 - 1, H, true);
+  Stream ws;
+  ws.lds = s_w;
+  ws.packed = a.packed;
+  ws.net_bytes = ly.bytes;  // "network 1" of the stream = the backward image
+  ws.chunks_off = ly.chunks;
+  ws.chunk_bytes = ly.chunk_bytes;
+  ws.wave = wave;
+  ws.lane = lane;
+  ws.issue(0, 0);
+  {
+    const u32x4* src = (const u32x4*)(a.packed + ly.w1);
+    for (int i = threadIdx.x; i < Net::L1_TILES * 64; i += blockDim.x) s_l1[i] = src[i];
+    const u32x4* src3 = (const u32x4*)(a.packed + ly.bytes + ly.w1);
+    for (int i = threadIdx.x; i < NUC * 64; i += blockDim.x) s_w3t[i] = src3[i];
+    if (threadIdx.x < 32) s_b3[threadIdx.x] = (int)threadIdx.x < O ? a.b3[threadIdx.x] : 0.0f;
+  }
+  __syncthreads();
+
+  float st[5] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f};  // per-lane sums: policy term, value term, entropy, clipped, kl
+  int gs = 0;  // stages consumed so far: stage gs sits in buffer gs % NBUF
+  const int64_t groups = (a.n_tiles + WAVES - 1) / WAVES;
+  // copies of stage `next` into buffer `nbuf`, spread over the tile loops of the current stage
+  auto spread = [&](int next, int nbuf, int c, int kt) {
+#pragma unroll
+    for (int i = 0; i < Stream::PER_WAVE; ++i)
+      if (i * (CPS * KT2) / Stream::PER_WAVE == c * KT2 + kt) ws.issue_part(next, nbuf, i);
+  };
+#pragma unroll 1
+  for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const int64_t tile = grp * WAVES + wave;
+    const bool live = tile < a.n_tiles;  // uniform over the wave
+    const int64_t row = tile * 32 + n;
+    const bool valid = live && row < a.R;
+    ws.wait_oldest();  // forward stage 0 is in; every wave has left the previous tile
+
+    // ---------------- observation row -> layer-1 operands (inputs D and D + 1 carry the two bias parts)
+    Op x[1][KT1];
+#pragma unroll
+    for (int kt = 0; kt < KT1; ++kt) {
+      f32x8 f;
+      const int i0 = 16 * kt + 8 * h;
+      if (valid && a.obs_vec4 && i0 + 8 <= a.D) {
+        const f32x4 u = *(const f32x4*)(a.obs + row * a.D + i0), w = *(const f32x4*)(a.obs + row * a.D + i0 + 4);
+        f = f32x8{u[0], u[1], u[2], u[3], w[0], w[1], w[2], w[3]};
+      } else {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) f[s] = (valid && i0 + s < a.D) ? a.obs[row * a.D + i0 + s] : 0.0f;
+      }
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+        if (i0 + s == a.D || i0 + s == a.D + 1) f[s] = 1.0f;
+      x[0][kt] = __builtin_convertvector(f, bf16x8);
+    }
+    if (NET == 0 && live) {
+      __bf16* xt = a.xt + (size_t)tile * (16 * KT1) * 32;
+#pragma unroll
+      for (int kt = 0; kt < KT1; ++kt) {
+        const u32x4 w = __builtin_bit_cast(u32x4, x[0][kt]);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) store_pair_t(xt, 16 * kt + 8 * h + 2 * d, w[d], n);
+      }
+    }
+
+    // ---------------- forward
+    Op h1[1][KT2];
+    Net::layer1(s_l1 + lane, x, h1);
+    if (live) {
+      __bf16* t1 = a.h1t + (size_t)tile * H * 32;
+#pragma unroll
+      for (int c = 0; c < NUC; ++c) {
+        const Op pr[2] = {h1[0][2 * c], h1[0][2 * c + 1]};
+        store_chunk_t<2>(t1, 32 * c, pr, n, h);
+      }
+    }
+    Op h2[KT2];  // layer-2 activations, later overwritten chunk by chunk with dL/dz2
+    f32x16 out = bias_init(s_b3, h);
+    __bf16* t2 = a.h2t + (size_t)tile * H * 32;
+    {
+      f32x16 acc = zero16();
+#pragma unroll 1
+      for (int sc = 0; sc < SPN; ++sc) {
+        if (sc != 0) ws.wait_oldest();
+        const int next = sc + 1;  // the first backward stage follows the last forward stage
+        const int nbuf = (gs + 1) % NBUF;
+        Op hn[CPS][2];
+#pragma unroll
+        for (int c = 0; c < CPS; ++c) {
+          const u32x4* tiles = ws.tiles(gs % NBUF, c);
+          auto tick = [&](int kt) { spread(next, nbuf, c, kt); };
+          if (c == 0 && sc == 0) {  // the first chunk of a tile has no chunk before it
+            fwd_chunk<Net, false>(tiles, h1, acc, out, h, hn[c], tick);
+            hn[c][0] = hn[c][1] = Op{0, 0, 0, 0, 0, 0, 0, 0};
+          } else {
+            fwd_chunk<Net, true>(tiles, h1, acc, out, h, hn[c], tick);
+            if (live) store_chunk_t<2>(t2, 32 * (sc * CPS + c - 1), hn[c], n, h);
+          }
+        }
+        // file the finished chunks (register indices are compile-time constants inside each branch)
+#pragma unroll
+        for (int k = 0; k < SPN; ++k)
+          if (sc == k) {
+#pragma unroll
+            for (int c = 0; c < CPS; ++c) {
+              const int idx = k * CPS + c - 1;
+              if (idx >= 0) {
+                h2[2 * idx] = hn[c][0];
+                h2[2 * idx + 1] = hn[c][1];
+              }
+            }
+          }
+        ++gs;
+      }
+      // last chunk: its tanh and layer-3 contribution (tiles of the last stage, still resident)
+      {
+        const u32x4* tiles = ws.tiles((gs - 1) % NBUF, CPS - 1);
+        float t[16];
+        Op hl[2];
+        tanh_range(acc, t, 0, 16, false);
+        to_operands<true>(t, hl);
+#pragma unroll
+        for (int i = 0; i < TPC; ++i)
+          out = mma(__builtin_bit_cast(bf16x8, tiles[(Net::L3_OWN + i) * 64]), hl[i], out);
+        h2[2 * (NUC - 1)] = hl[0];
+        h2[2 * (NUC - 1) + 1] = hl[1];
+        if (live) store_chunk_t<2>(t2, 32 * (NUC - 1), hl, n, h);
+      }
+    }
+
+    // ---------------- per-row loss and dL/dy in accumulator layout (register r <-> output 8 (r/4) + 4 h + r % 4)
+    float dyr[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dyr[r] = 0.0f;
+    if constexpr (NET == 0) {
+      float l[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        const int r = 4 * (k >> 3) + (k & 3);
+        const float own = out[r], oth = __shfl_xor(own, 32);
+        l[k] = (((k >> 2) & 1) == h) ? own : oth;
+      }
+      float mx = l[0];
+#pragma unroll
+      for (int k = 1; k < 16; ++k) mx = k < O ? fmaxf(mx, l[k]) : mx;
+      float z = 0.0f;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) z += k < O ? expf(l[k] - mx) : 0.0f;
+      const float lse = mx + logf(z);
+      const int act = valid ? ((const int32_t*)a.actions)[row] : 0;
+      float ent = 0.0f, logp = 0.0f;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        const float lp = l[k] - lse;
+        ent -= k < O ? expf(lp) * lp : 0.0f;
+        if (k == act) logp = lp;
+      }
+      const float lpo = valid ? a.logp_old[row] : 0.0f, A = valid ? a.adv[row] : 0.0f;
+      const float rho = expf(logp - lpo);
+      const float rc = fminf(fmaxf(rho, 1.0f - a.clip), 1.0f + a.clip);
+      const float un = rho * A, cl = rc * A;
+      const bool clipped = cl < un;
+      const float gl = clipped ? 0.0f : -A * rho;
+      // each lane differentiates with respect to its own eight outputs
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int k = 8 * (r / 4) + 4 * h + r % 4;
+        const float lp = out[r] - lse, pk = expf(lp);
+        const float dlp = (k == act ? 1.0f : 0.0f) - pk, dH = -pk * (lp + ent);
+        dyr[r] = (valid && k < O) ? (gl * dlp - a.ent_coef * dH) * a.inv_R : 0.0f;
+      }
+      if (valid && h == 0) {
+        st[0] += -(clipped ? cl : un);
+        st[2] += ent;
+        st[3] += clipped ? 1.0f : 0.0f;
+        st[4] += lpo - logp;
+      }
+    } else {
+      const float v = __shfl(out[0], n);  // output 0 sits in register 0 of the h = 0 lane
+      const float err = v - (valid ? a.ret[row] : 0.0f);
+      if (valid && h == 0) {
+        dyr[0] = a.vf_coef * 2.0f * err * a.inv_R;
+        st[1] += err * err;
+      }
+    }
+    Op dyo[2];
+    to_operands<true>(dyr, dyo);
+    if (live) store_chunk_t<1>(a.dyt + (size_t)tile * 16 * 32, 0, dyo, n, h);
+
+    // ---------------- dL/dz2 = (W3 dy) * (1 - h2^2), chunk by chunk, in place of h2
+    {
+      __bf16* tz2 = a.dz2t + (size_t)tile * H * 32;
+#pragma unroll
+      for (int c = 0; c < NUC; ++c) {
+        const f32x16 g = mma(__builtin_bit_cast(bf16x8, s_w3t[c * 64 + lane]), dyo[0], zero16());
+        const Op hp[2] = {h2[2 * c], h2[2 * c + 1]};
+        float t[16];
+        dtanh_range(g, hp, t, 0, 16, false);
+        Op dz[2];
+        to_operands<true>(t, dz);
+        h2[2 * c] = dz[0];
+        h2[2 * c + 1] = dz[1];
+        if (live) store_chunk_t<2>(tz2, 32 * c, dz, n, h);
+      }
+    }
+
+    // ---------------- dL/dz1 = (W2 dz2) * (1 - h1^2): chunk blocks of the backward image
+    {
+      __bf16* tz1 = a.dz1t + (size_t)tile * H * 32;
+      f32x16 acc = zero16();
+#pragma unroll 1
+      for (int sc = 0; sc < SPN; ++sc) {
+        ws.wait_oldest();
+        int next = SPN + sc + 1;  // the next tile's first forward stage follows the last backward stage
+        if (next >= 2 * SPN) next -= 2 * SPN;
+        const int nbuf = (gs + 1) % NBUF;
+        // layer-1 activations of the chunks whose epilogue runs in this stage
+        Op hp[CPS][2];
+#pragma unroll
+        for (int c = 0; c < CPS; ++c) hp[c][0] = hp[c][1] = Op{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < SPN; ++k)
+          if (sc == k) {
+#pragma unroll
+            for (int c = 0; c < CPS; ++c) {
+              const int idx = k * CPS + c - 1;
+              if (idx >= 0) {
+                hp[c][0] = h1[0][2 * idx];
+                hp[c][1] = h1[0][2 * idx + 1];
+              }
+            }
+          }
+#pragma unroll
+        for (int c = 0; c < CPS; ++c) {
+          const u32x4* tiles = ws.tiles(gs % NBUF, c);
+          auto tick = [&](int kt) { spread(next, nbuf, c, kt); };
+          Op dz[2];
+          if (c == 0 && sc == 0) {
+            bwd_chunk<Net, false>(tiles, h2, acc, hp[c], dz, tick);
+          } else {
+            bwd_chunk<Net, true>(tiles, h2, acc, hp[c], dz, tick);
+            if (live) store_chunk_t<2>(tz1, 32 * (sc * CPS + c - 1), dz, n, h);
+          }
+        }
+        ++gs;
+      }
+      {
+        const Op hp[2] = {h1[0][2 * (NUC - 1)], h1[0][2 * (NUC - 1) + 1]};
+        float t[16];
+        dtanh_range(acc, hp, t, 0, 16, false);
+        Op dz[2];
+        to_operands<true>(t, dz);
+        if (live) store_chunk_t<2>(tz1, 32 * (NUC - 1), dz, n, h);
+      }
+    }
+  }
+  ws.wait_all();  // the copy issued ahead for a tile that does not exist
+
+  // sums of the wave -> one atomic per statistic and wave, spread over the bins
+#pragma unroll
+  for (int q = 0; q < 5; ++q) {
+    if ((NET == 0) == (q == 1)) continue;  // the value term belongs to the value network's launch
+    float s = st[q];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) atomicAdd(a.stats + 8 + q * ROWS_STAT_BINS + (blockIdx.x * WAVES + wave) % ROWS_STAT_BINS, s);
+  }
+}
+
+// launchers of the instantiated row kernels (one translation unit per hidden size)
+hipError_t launch_ppo_rows_h64(int kt1, int net, const RowsArgs& a, unsigned grid, hipStream_t s);
+hipError_t launch_ppo_rows_h128(int kt1, int net, const RowsArgs& a, unsigned grid, hipStream_t s);
+hipError_t launch_ppo_rows_h256(int kt1, int net, const RowsArgs& a, unsigned grid, hipStream_t s);
+
+#define MSRL_ROWS_LAUNCHER(HID)                                                                             \
+  hipError_t launch_ppo_rows_h##HID(int kt1, int net, const RowsArgs& a, unsigned grid, hipStream_t s) {    \
+    if (kt1 == 2 && net == 0) hipLaunchKernelGGL((ppo_rows_kernel<HID, 2, 0, ROWS_WAVES>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, a);      \
+    else if (kt1 == 2) hipLaunchKernelGGL((ppo_rows_kernel<HID, 2, 1, ROWS_WAVES>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, a);    \
+    else if (kt1 == 4 && net == 0) hipLaunchKernelGGL((ppo_rows_kernel<HID, 4, 0, ROWS_WAVES>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, a); \
+    else if (kt1 == 4) hipLaunchKernelGGL((ppo_rows_kernel<HID, 4, 1, ROWS_WAVES>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, a);    \
+    else return hipErrorInvalidValue;                                                                       \
+    return hipGetLastError();                                                                               \
+  }
+
+}  // namespace msrl

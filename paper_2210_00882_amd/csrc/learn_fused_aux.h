@@ -1,0 +1,160 @@
+// Kernels around the learner's row kernel (learn_fused.h): packing of the fp32 master weights into
+// bf16 MFMA tiles, and the weight gradients from the tiled unit-major tensors the row kernel writes.
+// Included by one translation unit only (the kernels here are not templates).
+#pragma once
+#include "learn_fused.h"
+
+namespace msrl {
+
+// ---------------------------------------------------------------- packing (fp32 master -> bf16 tiles)
+struct LearnPackJob {
+  const float* src;
+  const float* bias;  // or null: split into a bf16 high and low part at input indices bias_index, +1
+  u32x4* dst;
+  int n_in, n_out;
+  int64_t s_in, s_out;  // element (in, out) is src[in * s_in + out * s_out]
+  int bias_index;
+  int nuc, kt;  // output chunks of 32, tiles per chunk
+  int group, chunk_stride, slot_base;  // destination tile as in PackJob (packed.h)
+  int linear;   // input map: 1 = 16 kt + 8 h + s (observation), 0 = chained
+};
+struct LearnPackJobs {
+  int n;
+  LearnPackJob job[12];
+};
+
+__device__ __forceinline__ uint32_t bf16_bits(float v) {
+  const __bf16 b = (__bf16)v;  // round to nearest even
+  return (uint32_t)__builtin_bit_cast(uint16_t, b);
+}
+
+__global__ void learn_pack_kernel(LearnPackJobs jobs) {
+  const LearnPackJob& j = jobs.job[blockIdx.y];
+  const int tid = blockIdx.x * blockDim.x + threadIdx.x;
+  if (tid >= j.nuc * j.kt * 64) return;
+  const int tile = tid >> 6, lane = tid & 63;
+  const int uc = tile / j.kt, kt = tile % j.kt;
+  const int dst_slot = ((uc + kt / j.group) * j.chunk_stride + j.slot_base + kt % j.group) * 64 + lane;
+  const int m = lane & 31, h = lane >> 5;
+  const int o = 32 * uc + m;
+  float v[8];
+  for (int e = 0; e < 8; ++e) {
+    const int i = j.linear ? 16 * kt + 8 * h + e : 32 * (kt >> 1) + 16 * (kt & 1) + 8 * (e >> 2) + 4 * h + (e & 3);
+    v[e] = 0.0f;
+    if (o < j.n_out) {
+      if (i < j.n_in) {
+        v[e] = j.src[(int64_t)i * j.s_in + (int64_t)o * j.s_out];
+      } else if (j.bias && (i == j.bias_index || i == j.bias_index + 1)) {
+        const float b = j.bias[o];
+        const float hi = (float)(__bf16)b;
+        v[e] = i == j.bias_index ? hi : b - hi;
+      }
+    }
+  }
+  u32x4 w;
+  for (int p = 0; p < 4; ++p) w[p] = bf16_bits(v[2 * p]) | (bf16_bits(v[2 * p + 1]) << 16);
+  j.dst[dst_slot] = w;
+}
+
+// ---------------------------------------------------------------- weight gradients from the tiled layout
+struct WgradTArgs {
+  const __bf16* A;  // [tiles][UA][32]: left operand, its units are the rows of C
+  const __bf16* B;  // [tiles][UB][32]: right operand, its units are the columns of C
+  int UA, UB;
+  int M, N;         // units that take part (M <= min(UA, 256), N <= min(UB, 256))
+  int m_out;        // rows m < m_out of C are written
+  int64_t n_tiles;
+  int tiles_per_slice;  // row tiles per workgroup, even
+  float* C;         // [m_out, ldc] += A^T-contraction (fp32 atomics)
+  int64_t ldc;
+  float* bias;      // [N] += sums of B over the rows, or null
+};
+
+// Output-stationary like wgrad_kernel (learn_kernels.h): workgroup z takes the row tiles
+// [z tiles_per_slice, (z+1) tiles_per_slice), wave w the units 32 w .. 32 w + 31 of A and all columns;
+// the B fragments of two row tiles (four k tiles) are shared through LDS, loaded one step ahead.
+// The bias gradient is one more contraction with a left operand of ones: wave w adds it up for
+// column tile w.
+__global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTArgs g) {
+  constexpr int NTW = 8, PER = NTW * 4 * 64 / 512;
+  __shared__ __attribute__((aligned(16))) u32x4 s_b[NTW * 4 * 64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = lane & 31, h = lane >> 5;
+  const int64_t t_begin = (int64_t)blockIdx.x * g.tiles_per_slice;
+  const int64_t t_end = min(g.n_tiles, t_begin + g.tiles_per_slice);
+  if (t_begin >= t_end) return;  // whole workgroup
+  const int ntiles = (g.N + 31) / 32;
+  const int m0 = 32 * wave;
+  const bool m_live = m0 < g.M;
+  const bool a_ok = m0 + i < g.M;
+  const bool b_live = g.bias != nullptr && wave < ntiles;
+  const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  auto panel_frag = [&](int f, int64_t T0) -> bf16x8 {
+    const int slot = f * 512 + threadIdx.x;
+    const int j = slot / 256, kk = (slot / 64) % 4, l = slot % 64;
+    const int nn = 32 * j + (l & 31);
+    const int64_t T = T0 + kk / 2;
+    if (j < ntiles && nn < g.N && T < t_end)
+      return *(const bf16x8*)(g.B + ((size_t)T * g.UB + nn) * 32 + (kk % 2) * 16 + (l >> 5) * 8);
+    return zero;
+  };
+  f32x16 acc[NTW], accb = zero16();
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) acc[j] = zero16();
+  bf16x8 ones;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) ones[s] = (__bf16)1.0f;
+  bf16x8 next[PER];
+#pragma unroll
+  for (int f = 0; f < PER; ++f) next[f] = panel_frag(f, t_begin);
+  for (int64_t T0 = t_begin; T0 < t_end; T0 += 2) {
+#pragma unroll
+    for (int f = 0; f < PER; ++f) s_b[f * 512 + threadIdx.x] = __builtin_bit_cast(u32x4, next[f]);
+    __syncthreads();
+    if (T0 + 2 < t_end) {
+#pragma unroll
+      for (int f = 0; f < PER; ++f) next[f] = panel_frag(f, T0 + 2);
+    }
+    bf16x8 av[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int64_t T = T0 + kk / 2;
+      av[kk] = (a_ok && T < t_end)
+                   ? *(const bf16x8*)(g.A + ((size_t)T * g.UA + m0 + i) * 32 + (kk % 2) * 16 + h * 8)
+                   : zero;
+    }
+    if (m_live) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) {
+          if (j >= ntiles) continue;  // uniform
+          acc[j] = mma(av[kk], __builtin_bit_cast(bf16x8, s_b[(j * 4 + kk) * 64 + lane]), acc[j]);
+        }
+    }
+    if (b_live) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        accb = mma(ones, __builtin_bit_cast(bf16x8, s_b[(wave * 4 + kk) * 64 + lane]), accb);
+    }
+    __syncthreads();
+  }
+  if (b_live && h == 0) {
+    const int nn = 32 * wave + i;  // every row of the ones-contraction is the column sum: take row 0
+    if (nn < g.N) atomicAdd(g.bias + nn, accb[0]);
+  }
+  if (!m_live) return;
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) {
+    const int nn = 32 * j + i;
+    if (j >= ntiles || nn >= g.N) continue;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + 8 * (r / 4) + 4 * h + r % 4;
+      if (m < g.m_out && m < g.M) atomicAdd(g.C + (int64_t)m * g.ldc + nn, acc[j][r]);
+    }
+  }
+}
+
+}  // namespace msrl

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -11,6 +12,7 @@
 #include "../../include/msrl.h"
 #include "api_common.h"
 #include "learn_kernels.h"
+#include "learn_fused_aux.h"
 
 using namespace msrl;
 
@@ -43,6 +45,12 @@ struct msrl_learner {
   float* grad;           // scratch gradient of msrl_ppo_update
   float* stats;          // [8 + 5 * STAT_BINS]: results, then the bins the loss kernel adds into
   size_t n_params;
+  // on-chip gradient pass (learn_fused.h): bf16 networks with a categorical policy of at most 16 actions
+  bool fused;
+  int kt1;               // layer-1 tiles of the row kernel: inputs, plus the two bias parts, in tiles of 16
+  NetLayout fly;         // layout of one image of the packed weights
+  uint8_t* fpacked;      // per network: forward image, backward image
+  int cus;               // compute units of the device
 };
 
 namespace {
@@ -230,6 +238,112 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
   return MSRL_OK;
 }
 
+static_assert(ROWS_STAT_BINS == STAT_BINS, "the row kernel and the loss kernel share the bins");
+
+// The same gradient with the activations kept on chip: weights packed into MFMA tiles, one row
+// kernel launch per network (forward, loss, backward through the activations; writes the tiled
+// unit-major operands), then the weight and bias gradients from those.
+int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs, const void* actions,
+                    const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* c, float* grad,
+                    hipStream_t s) {
+  const int D = L->pol.in_dim, H = L->pol.hidden, kt1 = L->kt1;
+  const NetLayout& ly = L->fly;
+  hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
+  hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
+  const float* b3p[2];
+  {
+    LearnPackJobs jobs;
+    memset(&jobs, 0, sizeof(jobs));
+    const float* P = params;
+    int max_items = 0;
+    for (int n = 0; n < 2; ++n) {
+      const int O = n == 0 ? L->pol.out_dim : 1;
+      const float* W1 = P;
+      const float* b1 = W1 + (size_t)D * H;
+      const float* W2 = b1 + H;
+      const float* b2 = W2 + (size_t)H * H;
+      const float* W3 = b2 + H;
+      b3p[n] = W3 + (size_t)H * O;
+      uint8_t* fwd = L->fpacked + (size_t)n * 2 * ly.bytes;
+      uint8_t* bwd = fwd + ly.bytes;
+      auto job = [&](const float* src, const float* bias, uint8_t* dst, int n_in, int n_out, int64_t s_in,
+                     int64_t s_out, int bias_index, int nuc, int kt, int group, int stride, int slot, int linear) {
+        LearnPackJob& j = jobs.job[jobs.n++];
+        j.src = src; j.bias = bias; j.dst = (u32x4*)dst; j.n_in = n_in; j.n_out = n_out; j.s_in = s_in; j.s_out = s_out;
+        j.bias_index = bias_index; j.nuc = nuc; j.kt = kt; j.group = group; j.chunk_stride = stride; j.slot_base = slot;
+        j.linear = linear;
+        if (nuc * kt * 64 > max_items) max_items = nuc * kt * 64;
+      };
+      // forward image: layer 1 (bias parts at inputs D, D + 1), chunk blocks of layer 2 (+ bias tile), layer 3
+      // next to the chunk it consumes and once more in the block after it
+      job(W1, b1, fwd + ly.w1, D, H, H, 1, D, ly.nuc, ly.kt1, ly.kt1, ly.kt1, 0, 1);
+      job(W2, b2, fwd + ly.chunks, H, H, H, 1, H, ly.nuc, ly.kt2 + 1, ly.kt2 + 1, ly.chunk_tiles, 0, 0);
+      job(W3, nullptr, fwd + ly.chunks, H, O, O, 1, 0, 1, ly.kt2, ly.tpc, ly.chunk_tiles, ly.kt2 + 1 + ly.tpc, 0);
+      if (ly.nuc > 1)
+        job(W3, nullptr, fwd + ly.chunks + ly.chunk_bytes, H, O, O, 1, 0, 1, ly.kt2 - ly.tpc, ly.tpc, ly.chunk_tiles,
+            ly.kt2 + 1, 0);
+      // backward image: W3 with the layer-2 units as tile rows (in the layer-1 area), W2 with the layer-1
+      // units as tile rows (chunk blocks)
+      job(W3, nullptr, bwd + ly.w1, O, H, 1, O, 0, ly.nuc, 1, 1, 1, 0, 0);
+      job(W2, nullptr, bwd + ly.chunks, H, H, 1, H, 0, ly.nuc, ly.kt2, ly.kt2, ly.chunk_tiles, 0, 0);
+      P = b3p[n] + O;
+    }
+    hipLaunchKernelGGL(learn_pack_kernel, dim3((unsigned)((max_items + 255) / 256), (unsigned)jobs.n), dim3(256), 0, s,
+                       jobs);
+    LTRY(hipGetLastError());
+  }
+  const int64_t n_tiles = (R + 31) / 32;
+  const int64_t groups = (n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
+  const unsigned grid = (unsigned)(groups < L->cus ? groups : L->cus);
+  for (int n = 0; n < 2; ++n) {
+    NetBufs& b = L->net[n];
+    RowsArgs a;
+    memset(&a, 0, sizeof(a));
+    a.packed = L->fpacked + (size_t)n * 2 * ly.bytes;
+    a.b3 = b3p[n];
+    a.obs = obs; a.actions = actions; a.logp_old = logp_old; a.adv = adv; a.ret = ret;
+    a.R = R; a.n_tiles = n_tiles; a.D = D; a.out_dim = L->pol.out_dim;
+    a.obs_vec4 = (D % 4 == 0 && ((uintptr_t)obs & 15) == 0) ? 1 : 0;
+    a.clip = c->clip; a.vf_coef = c->vf_coef; a.ent_coef = c->ent_coef; a.inv_R = 1.0f / (float)R;
+    a.xt = (__bf16*)L->xt; a.h1t = (__bf16*)b.h1t; a.h2t = (__bf16*)b.h2t; a.dz2t = (__bf16*)b.dz2t;
+    a.dz1t = (__bf16*)b.dz1t; a.dyt = (__bf16*)b.dyt;
+    a.stats = L->stats;
+    hipError_t e = H == 64 ? launch_ppo_rows_h64(kt1, n, a, grid, s)
+                 : H == 128 ? launch_ppo_rows_h128(kt1, n, a, grid, s)
+                            : launch_ppo_rows_h256(kt1, n, a, grid, s);
+    LTRY(e);
+  }
+  hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
+  LTRY(hipGetLastError());
+  size_t off = 0;
+  int tps = (int)((n_tiles + 511) / 512);
+  tps = (tps + 1) / 2 * 2;
+  const unsigned slices = (unsigned)((n_tiles + tps - 1) / tps);
+  for (int n = 0; n < 2; ++n) {
+    NetBufs& b = L->net[n];
+    const int O = n == 0 ? L->pol.out_dim : 1;
+    float* gW1 = grad + off;
+    float* gb1 = gW1 + (size_t)D * H;
+    float* gW2 = gb1 + H;
+    float* gb2 = gW2 + (size_t)H * H;
+    float* gW3 = gb2 + H;
+    float* gb3 = gW3 + (size_t)H * O;
+    auto wg = [&](const void* A, int UA, int M, const void* B, int UB, int N, float* C, int64_t ldc, float* bias) {
+      WgradTArgs g;
+      memset(&g, 0, sizeof(g));
+      g.A = (const __bf16*)A; g.B = (const __bf16*)B; g.UA = UA; g.UB = UB; g.M = M; g.N = N; g.m_out = M;
+      g.n_tiles = n_tiles; g.tiles_per_slice = tps; g.C = C; g.ldc = ldc; g.bias = bias;
+      hipLaunchKernelGGL(wgrad_tiled_kernel, dim3(slices), dim3(512), 0, s, g);
+    };
+    wg(b.h2t, H, H, b.dyt, 16, O, gW3, O, gb3);
+    wg(b.h1t, H, H, b.dz2t, H, H, gW2, H, gb2);
+    wg(L->xt, 16 * kt1, D, b.dz1t, H, H, gW1, H, gb1);
+    LTRY(hipGetLastError());
+    off += net_count(D, H, O);
+  }
+  return MSRL_OK;
+}
+
 int check_learner_args(const char* who, msrl_learner* L, const void* params, int64_t R, const void* obs,
                        const void* actions, const void* logp_old, const void* adv, const void* ret,
                        const msrl_ppo_cfg* c) {
@@ -267,10 +381,23 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
   L->esz = L->bf16 ? 2 : 4;
   L->n_params = net_count(policy->in_dim, policy->hidden, policy->out_dim) + net_count(policy->in_dim, policy->hidden, 1);
   const size_t H = (size_t)policy->hidden, Rp = (size_t)L->Rp, Dp = (size_t)L->Dp, e = L->esz;
+  L->kt1 = policy->in_dim + 2 <= 32 ? 2 : 4;
+  L->fused = L->bf16 && policy->dist == MSRL_CATEGORICAL && policy->out_dim <= 16 && policy->in_dim + 2 <= 64 &&
+             (policy->hidden == 64 || policy->hidden == 128 || policy->hidden == 256) && !getenv("MSRL_LEARNER_UNFUSED");
+  L->fly = net_layout(16 * L->kt1 - 1, policy->hidden, true);
   int rc = MSRL_OK;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+      delete L;
+      return fail(MSRL_EDEVICE, "msrl_learner_init: cannot query the device");
+    }
+    L->cus = cus;
+  }
   auto A = [&](void** p, size_t bytes) { if (rc == MSRL_OK) rc = dev_alloc((uint8_t**)p, bytes); };
   A(&L->xc, Rp * Dp * e);
-  A(&L->xt, Dp * Rp * e);
+  A(&L->xt, (L->fused && (size_t)(16 * L->kt1) > Dp ? (size_t)(16 * L->kt1) : Dp) * Rp * e);
+  if (L->fused) A((void**)&L->fpacked, 4 * L->fly.bytes);
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
     A(&b.wt1, H * Dp * e); A(&b.wt2, H * H * e); A(&b.wt3, 32 * H * e);
@@ -294,7 +421,7 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
 
 void msrl_learner_destroy(msrl_learner* L) {
   if (!L) return;
-  void* ptrs[] = {L->xc, L->xt, L->grad, L->stats};
+  void* ptrs[] = {L->xc, L->xt, L->grad, L->stats, L->fpacked};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (int n = 0; n < 2; ++n) {
@@ -314,8 +441,9 @@ int msrl_ppo_grad(msrl_learner* L, const float* params, int64_t R, const float* 
   if (rc != MSRL_OK) return rc;
   if (!grad) return fail(MSRL_EINVAL, "msrl_ppo_grad: grad is NULL");
   hipStream_t s = (hipStream_t)hip_stream;
-  rc = L->bf16 ? grad_pass<true>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s)
-               : grad_pass<false>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s);
+  rc = L->fused ? fused_grad_pass(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s)
+     : L->bf16  ? grad_pass<true>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s)
+                : grad_pass<false>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s);
   if (rc != MSRL_OK) return rc;
   if (stats) LTRY(hipMemcpyAsync(stats, L->stats, 5 * sizeof(float), hipMemcpyDeviceToDevice, s));
   return MSRL_OK;

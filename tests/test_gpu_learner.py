@@ -48,14 +48,21 @@ CASES = {
     "cfg4_gauss_f32": (synth.CONFIGS[4], 200),
     "p3_bf16": (synth.particle("p3b", 8, 3, 64, 4, 4, synth.BF16, 12), 300),
     "cfg5_bf16": (synth.CONFIGS[5], 259),
+    "cfg5_bf16_many_tiles": (synth.CONFIGS[5], 32 * 4 * 5 + 17),
+    "p6_bf16_h128": (synth.particle("p6b", 8, 6, 128, 4, 4, synth.BF16, 12), 150),
+    # the same bf16 networks through the kernels that keep the activations in device memory
+    "p3_bf16_unfused": (synth.particle("p3b", 8, 3, 64, 4, 4, synth.BF16, 12), 300),
+    "cfg5_bf16_unfused": (synth.CONFIGS[5], 259),
 }
 
 
 @pytest.mark.parametrize("which", list(CASES))
-def test_gradient_and_statistics_match_the_oracle(which):
+def test_gradient_and_statistics_match_the_oracle(which, monkeypatch):
     import torch
     from paper_2210_00882_amd import binding as B
     cfg, R = CASES[which]
+    if which.endswith("_unfused"):
+        monkeypatch.setenv("MSRL_LEARNER_UNFUSED", "1")   # read by msrl_learner_init
     params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
     pol, obs, actions, logp_old, adv, ret = make_batch(cfg, R, 7, params)
     hp = dict(clip=0.2, vf_coef=0.7, ent_coef=0.03)
