@@ -44,28 +44,63 @@ __device__ __forceinline__ uint32_t quad_swap1(uint32_t x) {  // value of lane ^
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false);
 }
 
-// Stores values held one row per lane and two consecutive units per 32-bit register into a tile
-// [unit][32 rows]: neighbouring lanes trade halves, so that a lane holds two consecutive rows of one
-// unit and the wave writes 64-byte runs.  `unit` is the unit of the low half of this lane's register.
-__device__ __forceinline__ void store_pair_t(__bf16* tile, int unit, uint32_t x, int n) {
-  const uint32_t p = quad_swap1(x);
-  const uint32_t v = __builtin_amdgcn_perm(p, x, (n & 1) ? 0x03020706u : 0x05040100u);
-  *(uint32_t*)(tile + (size_t)(unit + (n & 1)) * 32 + (n & ~1)) = v;
-}
-
-// one 32-unit chunk in operand form (NOPS = 2) or its first 16 units (NOPS = 1)
-template <int NOPS>
-__device__ __forceinline__ void store_chunk_t(__bf16* tile, int unit0, const bf16x8 (&op)[2], int n, int h) {
-#pragma unroll
-  for (int j = 0; j < NOPS; ++j) {
-    const u32x4 w = __builtin_bit_cast(u32x4, op[j]);
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      const int r = 8 * j + 2 * d;  // accumulator register of the low half
-      store_pair_t(tile, unit0 + 8 * (r / 4) + 4 * h + r % 4, w[d], n);
-    }
+// Results leave the wave through a 2 KiB staging area in LDS (one per wave), so that the global
+// stores are whole 1 KiB runs of 16 bytes per lane: the memory pipeline takes about as long for a
+// 64-lane store of 4 bytes per lane as for one of 16, and a tile has 20480 values per tensor row.
+// Values are held one row per lane and two consecutive units per 32-bit register; neighbouring
+// lanes trade halves, so that a lane holds two consecutive rows of one unit, and write the staging
+// area in [unit][32 rows] order (32-bit LDS writes, conflict-free).
+struct Stager {
+  uint32_t* stg;     // this wave's staging area: 512 words
+  uint32_t sel;      // byte selector of the exchange
+  int w_chain;       // word offset of this lane for chunk values: (4 h + n % 2) * 16 + n / 2
+  int w_lin;         // ... for observation values (linear input map): (8 h + n % 2) * 16 + n / 2
+  int lane;
+  __device__ __forceinline__ Stager(uint32_t* s, int lane_, int n, int h)
+      : stg(s), sel((n & 1) ? 0x03020706u : 0x05040100u), w_chain((4 * h + (n & 1)) * 16 + (n >> 1)),
+        w_lin((8 * h + (n & 1)) * 16 + (n >> 1)), lane(lane_) {}
+  __device__ __forceinline__ uint32_t trade(uint32_t x) const {
+    return __builtin_amdgcn_perm(quad_swap1(x), x, sel);
   }
-}
+  // KB KiB of staged values -> dst (16-byte aligned), as 16 bytes per lane and instruction
+  template <int KB>
+  __device__ __forceinline__ void flush(__bf16* dst) const {
+    wave_lds_sync();
+    u32x4 v[KB];
+#pragma unroll
+    for (int k = 0; k < KB; ++k) v[k] = ((const u32x4*)stg)[64 * k + lane];
+#pragma unroll
+    for (int k = 0; k < KB; ++k) ((u32x4*)dst)[64 * k + lane] = v[k];
+    wave_lds_sync();
+  }
+  // one 32-unit chunk in operand form -> tile[unit0 .. unit0 + 31][32 rows] (2 KiB, contiguous)
+  __device__ __forceinline__ void chunk(__bf16* tile, int unit0, const bf16x8 (&op)[2]) const {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const u32x4 w = __builtin_bit_cast(u32x4, op[j]);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const int r = 8 * j + 2 * d;  // accumulator register of the low half
+        stg[(8 * (r / 4) + r % 4) * 16 + w_chain] = trade(w[d]);
+      }
+    }
+    flush<2>(tile + (size_t)unit0 * 32);
+  }
+  // the first 16 units of a chunk (operand 0) -> tile[0 .. 15][32 rows] (1 KiB)
+  __device__ __forceinline__ void half_chunk(__bf16* tile, const bf16x8& op) const {
+    const u32x4 w = __builtin_bit_cast(u32x4, op);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) stg[(8 * (d / 2) + 2 * (d % 2)) * 16 + w_chain] = trade(w[d]);
+    flush<1>(tile);
+  }
+  // 16 observation inputs (one layer-1 operand) -> tile[unit0 .. unit0 + 15][32 rows] (1 KiB)
+  __device__ __forceinline__ void inputs16(__bf16* tile, int unit0, const bf16x8& op) const {
+    const u32x4 w = __builtin_bit_cast(u32x4, op);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) stg[(2 * d) * 16 + w_lin] = trade(w[d]);
+    flush<1>(tile + (size_t)unit0 * 32);
+  }
+};
 
 // acc * (1 - a^2) for accumulator registers [r0, r1), a = the stored (rounded) activation
 __device__ __forceinline__ void dtanh_range(const f32x16& acc, const bf16x8 (&hp)[2], float (&t)[16], int r0,
@@ -172,10 +207,12 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
   __shared__ __attribute__((aligned(16))) u32x4 s_w3t[NUC * 64];
   __shared__ __attribute__((aligned(16))) u32x4 s_w[NBUF * Stream::BUF_SLOTS];
   __shared__ __attribute__((aligned(16))) float s_b3[32];
+  __shared__ __attribute__((aligned(16))) uint32_t s_stg[WAVES][512];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 31, h = lane >> 5;
+  const Stager sg(s_stg[wave], lane, n, h);
   const int O = NET == 0 ? a.out_dim : 1;
   const NetLayout ly = net_layout(16 * KT1 - 1, H, true);
   Stream ws;
@@ -234,11 +271,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     if (NET == 0 && live) {
       __bf16* xt = a.xt + (size_t)tile * (16 * KT1) * 32;
 #pragma unroll
-      for (int kt = 0; kt < KT1; ++kt) {
-        const u32x4 w = __builtin_bit_cast(u32x4, x[0][kt]);
-#pragma unroll
-        for (int d = 0; d < 4; ++d) store_pair_t(xt, 16 * kt + 8 * h + 2 * d, w[d], n);
-      }
+      for (int kt = 0; kt < KT1; ++kt) sg.inputs16(xt, 16 * kt, x[0][kt]);
     }
 
     // ---------------- forward
@@ -249,7 +282,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
 #pragma unroll
       for (int c = 0; c < NUC; ++c) {
         const Op pr[2] = {h1[0][2 * c], h1[0][2 * c + 1]};
-        store_chunk_t<2>(t1, 32 * c, pr, n, h);
+        sg.chunk(t1, 32 * c, pr);
       }
     }
     Op h2[KT2];  // layer-2 activations, later overwritten chunk by chunk with dL/dz2
@@ -272,7 +305,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
             hn[c][0] = hn[c][1] = Op{0, 0, 0, 0, 0, 0, 0, 0};
           } else {
             fwd_chunk<Net, true>(tiles, h1, acc, out, h, hn[c], tick);
-            if (live) store_chunk_t<2>(t2, 32 * (sc * CPS + c - 1), hn[c], n, h);
+            if (live) sg.chunk(t2, 32 * (sc * CPS + c - 1), hn[c]);
           }
         }
         // file the finished chunks (register indices are compile-time constants inside each branch)
@@ -302,7 +335,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
           out = mma(__builtin_bit_cast(bf16x8, tiles[(Net::L3_OWN + i) * 64]), hl[i], out);
         h2[2 * (NUC - 1)] = hl[0];
         h2[2 * (NUC - 1) + 1] = hl[1];
-        if (live) store_chunk_t<2>(t2, 32 * (NUC - 1), hl, n, h);
+        if (live) sg.chunk(t2, 32 * (NUC - 1), hl);
       }
     }
 
@@ -363,7 +396,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     }
     Op dyo[2];
     to_operands<true>(dyr, dyo);
-    if (live) store_chunk_t<1>(a.dyt + (size_t)tile * 16 * 32, 0, dyo, n, h);
+    if (live) sg.half_chunk(a.dyt + (size_t)tile * 16 * 32, dyo[0]);
 
     // ---------------- dL/dz2 = (W3 dy) * (1 - h2^2), chunk by chunk, in place of h2
     {
@@ -378,7 +411,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
         to_operands<true>(t, dz);
         h2[2 * c] = dz[0];
         h2[2 * c + 1] = dz[1];
-        if (live) store_chunk_t<2>(tz2, 32 * c, dz, n, h);
+        if (live) sg.chunk(tz2, 32 * c, dz);
       }
     }
 
@@ -417,7 +450,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
             bwd_chunk<Net, false>(tiles, h2, acc, hp[c], dz, tick);
           } else {
             bwd_chunk<Net, true>(tiles, h2, acc, hp[c], dz, tick);
-            if (live) store_chunk_t<2>(tz1, 32 * (sc * CPS + c - 1), dz, n, h);
+            if (live) sg.chunk(tz1, 32 * (sc * CPS + c - 1), dz);
           }
         }
         ++gs;
@@ -428,7 +461,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
         dtanh_range(acc, hp, t, 0, 16, false);
         Op dz[2];
         to_operands<true>(t, dz);
-        if (live) store_chunk_t<2>(tz1, 32 * (NUC - 1), dz, n, h);
+        if (live) sg.chunk(tz1, 32 * (NUC - 1), dz);
       }
     }
   }

@@ -105,24 +105,29 @@ __global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTArgs g) {
   bf16x8 ones;
 #pragma unroll
   for (int s = 0; s < 8; ++s) ones[s] = (__bf16)1.0f;
-  bf16x8 next[PER];
+  auto a_frag = [&](int kk, int64_t T0) -> bf16x8 {
+    const int64_t T = T0 + kk / 2;
+    if (a_ok && T < t_end) return *(const bf16x8*)(g.A + ((size_t)T * g.UA + m0 + i) * 32 + (kk % 2) * 16 + h * 8);
+    return zero;
+  };
+  // both operands of a step are fetched one step ahead, into registers
+  bf16x8 next[PER], next_a[4];
 #pragma unroll
   for (int f = 0; f < PER; ++f) next[f] = panel_frag(f, t_begin);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) next_a[kk] = a_frag(kk, t_begin);
   for (int64_t T0 = t_begin; T0 < t_end; T0 += 2) {
 #pragma unroll
     for (int f = 0; f < PER; ++f) s_b[f * 512 + threadIdx.x] = __builtin_bit_cast(u32x4, next[f]);
+    bf16x8 av[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) av[kk] = next_a[kk];
     __syncthreads();
     if (T0 + 2 < t_end) {
 #pragma unroll
       for (int f = 0; f < PER; ++f) next[f] = panel_frag(f, T0 + 2);
-    }
-    bf16x8 av[4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int64_t T = T0 + kk / 2;
-      av[kk] = (a_ok && T < t_end)
-                   ? *(const bf16x8*)(g.A + ((size_t)T * g.UA + m0 + i) * 32 + (kk % 2) * 16 + h * 8)
-                   : zero;
+      for (int kk = 0; kk < 4; ++kk) next_a[kk] = a_frag(kk, T0 + 2);
     }
     if (m_live) {
 #pragma unroll

@@ -316,7 +316,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
   hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
   LTRY(hipGetLastError());
   size_t off = 0;
-  int tps = (int)((n_tiles + 511) / 512);
+  int tps = (int)((n_tiles + L->cus - 1) / L->cus);  // one workgroup per compute unit
   tps = (tps + 1) / 2 * 2;
   const unsigned slices = (unsigned)((n_tiles + tps - 1) / tps);
   for (int n = 0; n < 2; ++n) {
