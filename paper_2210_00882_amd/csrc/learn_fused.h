@@ -65,12 +65,19 @@ struct Stager {
   // KB KiB of staged values -> dst (16-byte aligned), as 16 bytes per lane and instruction
   template <int KB>
   __device__ __forceinline__ void flush(__bf16* dst) const {
+#ifdef MSRL_DBG_NOSTAGE
+    return;
+#endif
     wave_lds_sync();
     u32x4 v[KB];
 #pragma unroll
     for (int k = 0; k < KB; ++k) v[k] = ((const u32x4*)stg)[64 * k + lane];
 #pragma unroll
-    for (int k = 0; k < KB; ++k) ((u32x4*)dst)[64 * k + lane] = v[k];
+    for (int k = 0; k < KB; ++k)
+#ifdef MSRL_DBG_NOSTORE
+      if (v[k][0] == 0x12345678u)
+#endif
+      ((u32x4*)dst)[64 * k + lane] = v[k];
     wave_lds_sync();
   }
   // one 32-unit chunk in operand form -> tile[unit0 .. unit0 + 31][32 rows] (2 KiB, contiguous)
@@ -92,6 +99,30 @@ struct Stager {
 #pragma unroll
     for (int d = 0; d < 4; ++d) stg[(8 * (d / 2) + 2 * (d % 2)) * 16 + w_chain] = trade(w[d]);
     flush<1>(tile);
+  }
+  // The way back, for a chunk the wave wrote earlier: 2 KiB of a tile into registers as they lie in
+  // memory (fetch; issued early), then through the staging area into operand form (unstage).
+  __device__ __forceinline__ void fetch(const __bf16* tile, int unit0, u32x4 (&raw)[2]) const {
+    const u32x4* src = (const u32x4*)(tile + (size_t)unit0 * 32);
+    raw[0] = src[lane];
+    raw[1] = src[64 + lane];
+  }
+  __device__ __forceinline__ void unstage(const u32x4 (&raw)[2], bf16x8 (&op)[2]) const {
+    wave_lds_sync();
+    ((u32x4*)stg)[lane] = raw[0];
+    ((u32x4*)stg)[64 + lane] = raw[1];
+    wave_lds_sync();
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      u32x4 w;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const int r = 8 * j + 2 * d;
+        w[d] = trade(stg[(8 * (r / 4) + r % 4) * 16 + w_chain]);  // the 2 x 2 exchange is its own inverse
+      }
+      op[j] = __builtin_bit_cast(bf16x8, w);
+    }
+    wave_lds_sync();
   }
   // 16 observation inputs (one layer-1 operand) -> tile[unit0 .. unit0 + 15][32 rows] (1 KiB)
   __device__ __forceinline__ void inputs16(__bf16* tile, int unit0, const bf16x8& op) const {
@@ -123,13 +154,21 @@ __device__ __forceinline__ void dtanh_range(const f32x16& acc, const bf16x8 (&hp
     if (r >= r0 && r < r1 && pinned) pin(t[r]);
 }
 
+// The activation work of the chunk before is spread over the MFMAs of the current one in groups of
+// ROWS_EPI_GROUP tiles' worth: a group holds that many independent dependency chains, which is what
+// hides the latency of the transcendental unit when a SIMD runs a single wave.
+#ifndef MSRL_ROWS_EPI_GROUP
+#define MSRL_ROWS_EPI_GROUP 4
+#endif
+constexpr int ROWS_EPI_GROUP = MSRL_ROWS_EPI_GROUP;
+
 // One chunk block of the forward pass: acc <- layer-2 pre-activations of the block's 32 units (bias
 // included); if PIPE, `acc` holds those of the chunk before on entry: they get tanh, feed layer 3
 // (out) and are returned as operands in hprev.  tick(kt) runs once per layer-2 tile.
 template <class Net, bool PIPE, class Tick>
 __device__ __forceinline__ void fwd_chunk(const u32x4* tiles, const bf16x8 (&h1)[1][Net::KT2], f32x16& acc,
                                           f32x16& out, int h, bf16x8 (&hprev)[2], Tick&& tick) {
-  constexpr int KT2 = Net::KT2, TPC = Net::TPC, G = Net::G, LAST = Net::L3_PREV + TPC;
+  constexpr int KT2 = Net::KT2, TPC = Net::TPC, G = Net::G, LAST = Net::L3_PREV + TPC, GR = ROWS_EPI_GROUP;
   u32x4 ring[G];
 #pragma unroll
   for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
@@ -142,7 +181,7 @@ __device__ __forceinline__ void fwd_chunk(const u32x4* tiles, const bf16x8 (&h1)
     if (kt + G < LAST) ring[kt % G] = tiles[(kt + G) * 64];
     if (PIPE) pin(raw);
     acc = mma(__builtin_bit_cast(bf16x8, raw), h1[0][kt], acc);
-    if (PIPE) tanh_range(prev, t, kt * 16 / KT2, (kt + 1) * 16 / KT2, true);
+    if (PIPE && kt % GR == GR - 1) tanh_range(prev, t, (kt + 1 - GR) * 16 / KT2, (kt + 1) * 16 / KT2, true);
     tick(kt);
   }
   {
@@ -167,7 +206,7 @@ __device__ __forceinline__ void fwd_chunk(const u32x4* tiles, const bf16x8 (&h1)
 template <class Net, bool PIPE, class Tick>
 __device__ __forceinline__ void bwd_chunk(const u32x4* tiles, const bf16x8 (&dz2)[Net::KT2], f32x16& acc,
                                           const bf16x8 (&hp)[2], bf16x8 (&dprev)[2], Tick&& tick) {
-  constexpr int KT2 = Net::KT2, G = Net::G;
+  constexpr int KT2 = Net::KT2, G = Net::G, GR = ROWS_EPI_GROUP;
   u32x4 ring[G];
 #pragma unroll
   for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
@@ -180,14 +219,14 @@ __device__ __forceinline__ void bwd_chunk(const u32x4* tiles, const bf16x8 (&dz2
     if (kt + G < KT2) ring[kt % G] = tiles[(kt + G) * 64];
     if (PIPE) pin(raw);
     acc = mma(__builtin_bit_cast(bf16x8, raw), dz2[kt], acc);
-    if (PIPE) dtanh_range(prev, hp, t, kt * 16 / KT2, (kt + 1) * 16 / KT2, true);
+    if (PIPE && kt % GR == GR - 1) dtanh_range(prev, hp, t, (kt + 1 - GR) * 16 / KT2, (kt + 1) * 16 / KT2, true);
     tick(kt);
   }
   if (PIPE) to_operands<true>(t, dprev);
 }
 
 #ifndef MSRL_ROWS_WAVES
-#define MSRL_ROWS_WAVES 4
+#define MSRL_ROWS_WAVES 8
 #endif
 constexpr int ROWS_WAVES = MSRL_ROWS_WAVES;  // waves per workgroup of the row kernel = row tiles per group
 constexpr int ROWS_STAT_BINS = 64;  // bins per statistic in RowsArgs::stats (after 8 result slots)
@@ -249,6 +288,18 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     const int64_t row = tile * 32 + n;
     const bool valid = live && row < a.R;
     ws.wait_oldest();  // forward stage 0 is in; every wave has left the previous tile
+    // per-row inputs of the loss, fetched early
+    int act = 0;
+    float lpo = 0.0f, adv = 0.0f, ret = 0.0f;
+    if (valid) {
+      if constexpr (NET == 0) {
+        act = ((const int32_t*)a.actions)[row];
+        lpo = a.logp_old[row];
+        adv = a.adv[row];
+      } else {
+        ret = a.ret[row];
+      }
+    }
 
     // ---------------- observation row -> layer-1 operands (inputs D and D + 1 carry the two bias parts)
     Op x[1][KT1];
@@ -274,53 +325,41 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
       for (int kt = 0; kt < KT1; ++kt) sg.inputs16(xt, 16 * kt, x[0][kt]);
     }
 
-    // ---------------- forward
-    Op h1[1][KT2];
-    Net::layer1(s_l1 + lane, x, h1);
-    if (live) {
-      __bf16* t1 = a.h1t + (size_t)tile * H * 32;
-#pragma unroll
-      for (int c = 0; c < NUC; ++c) {
-        const Op pr[2] = {h1[0][2 * c], h1[0][2 * c + 1]};
-        sg.chunk(t1, 32 * c, pr);
-      }
-    }
-    Op h2[KT2];  // layer-2 activations, later overwritten chunk by chunk with dL/dz2
-    f32x16 out = bias_init(s_b3, h);
+    // ---------------- forward.  The activations go to their tiles as they are produced and are
+    // read back from there (by the wave that wrote them) where the backward pass needs them:
+    // holding both layers in registers to the end of the tile would leave room for one wave per
+    // SIMD only.
+    __bf16* t1 = a.h1t + (size_t)tile * H * 32;
     __bf16* t2 = a.h2t + (size_t)tile * H * 32;
+    f32x16 out = bias_init(s_b3, h);
     {
+      Op h1[1][KT2];
+      Net::layer1(s_l1 + lane, x, h1);
+      if (live) {
+#pragma unroll
+        for (int c = 0; c < NUC; ++c) {
+          const Op pr[2] = {h1[0][2 * c], h1[0][2 * c + 1]};
+          sg.chunk(t1, 32 * c, pr);
+        }
+      }
       f32x16 acc = zero16();
 #pragma unroll 1
       for (int sc = 0; sc < SPN; ++sc) {
         if (sc != 0) ws.wait_oldest();
         const int next = sc + 1;  // the first backward stage follows the last forward stage
         const int nbuf = (gs + 1) % NBUF;
-        Op hn[CPS][2];
 #pragma unroll
         for (int c = 0; c < CPS; ++c) {
           const u32x4* tiles = ws.tiles(gs % NBUF, c);
           auto tick = [&](int kt) { spread(next, nbuf, c, kt); };
+          Op hn[2];
           if (c == 0 && sc == 0) {  // the first chunk of a tile has no chunk before it
-            fwd_chunk<Net, false>(tiles, h1, acc, out, h, hn[c], tick);
-            hn[c][0] = hn[c][1] = Op{0, 0, 0, 0, 0, 0, 0, 0};
+            fwd_chunk<Net, false>(tiles, h1, acc, out, h, hn, tick);
           } else {
-            fwd_chunk<Net, true>(tiles, h1, acc, out, h, hn[c], tick);
-            if (live) sg.chunk(t2, 32 * (sc * CPS + c - 1), hn[c]);
+            fwd_chunk<Net, true>(tiles, h1, acc, out, h, hn, tick);
+            if (live) sg.chunk(t2, 32 * (sc * CPS + c - 1), hn);
           }
         }
-        // file the finished chunks (register indices are compile-time constants inside each branch)
-#pragma unroll
-        for (int k = 0; k < SPN; ++k)
-          if (sc == k) {
-#pragma unroll
-            for (int c = 0; c < CPS; ++c) {
-              const int idx = k * CPS + c - 1;
-              if (idx >= 0) {
-                h2[2 * idx] = hn[c][0];
-                h2[2 * idx + 1] = hn[c][1];
-              }
-            }
-          }
         ++gs;
       }
       // last chunk: its tanh and layer-3 contribution (tiles of the last stage, still resident)
@@ -333,8 +372,6 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
 #pragma unroll
         for (int i = 0; i < TPC; ++i)
           out = mma(__builtin_bit_cast(bf16x8, tiles[(Net::L3_OWN + i) * 64]), hl[i], out);
-        h2[2 * (NUC - 1)] = hl[0];
-        h2[2 * (NUC - 1) + 1] = hl[1];
         if (live) sg.chunk(t2, 32 * (NUC - 1), hl);
       }
     }
@@ -356,27 +393,25 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
       for (int k = 1; k < 16; ++k) mx = k < O ? fmaxf(mx, l[k]) : mx;
       float z = 0.0f;
 #pragma unroll
-      for (int k = 0; k < 16; ++k) z += k < O ? expf(l[k] - mx) : 0.0f;
-      const float lse = mx + logf(z);
-      const int act = valid ? ((const int32_t*)a.actions)[row] : 0;
+      for (int k = 0; k < 16; ++k) z += k < O ? __expf(l[k] - mx) : 0.0f;
+      const float lse = mx + __logf(z);
       float ent = 0.0f, logp = 0.0f;
 #pragma unroll
       for (int k = 0; k < 16; ++k) {
         const float lp = l[k] - lse;
-        ent -= k < O ? expf(lp) * lp : 0.0f;
+        ent -= k < O ? __expf(lp) * lp : 0.0f;
         if (k == act) logp = lp;
       }
-      const float lpo = valid ? a.logp_old[row] : 0.0f, A = valid ? a.adv[row] : 0.0f;
-      const float rho = expf(logp - lpo);
+      const float rho = __expf(logp - lpo);
       const float rc = fminf(fmaxf(rho, 1.0f - a.clip), 1.0f + a.clip);
-      const float un = rho * A, cl = rc * A;
+      const float un = rho * adv, cl = rc * adv;
       const bool clipped = cl < un;
-      const float gl = clipped ? 0.0f : -A * rho;
+      const float gl = clipped ? 0.0f : -adv * rho;
       // each lane differentiates with respect to its own eight outputs
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
         const int k = 8 * (r / 4) + 4 * h + r % 4;
-        const float lp = out[r] - lse, pk = expf(lp);
+        const float lp = out[r] - lse, pk = __expf(lp);
         const float dlp = (k == act ? 1.0f : 0.0f) - pk, dH = -pk * (lp + ent);
         dyr[r] = (valid && k < O) ? (gl * dlp - a.ent_coef * dH) * a.inv_R : 0.0f;
       }
@@ -388,7 +423,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
       }
     } else {
       const float v = __shfl(out[0], n);  // output 0 sits in register 0 of the h = 0 lane
-      const float err = v - (valid ? a.ret[row] : 0.0f);
+      const float err = v - ret;
       if (valid && h == 0) {
         dyr[0] = a.vf_coef * 2.0f * err * a.inv_R;
         st[1] += err * err;
@@ -398,19 +433,24 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     to_operands<true>(dyr, dyo);
     if (live) sg.half_chunk(a.dyt + (size_t)tile * 16 * 32, dyo[0]);
 
-    // ---------------- dL/dz2 = (W3 dy) * (1 - h2^2), chunk by chunk, in place of h2
+    // ---------------- dL/dz2 = (W3 dy) * (1 - h2^2), chunk by chunk
+    Op dz2[KT2];
     {
       __bf16* tz2 = a.dz2t + (size_t)tile * H * 32;
+      u32x4 raw[2] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
+      if (live) sg.fetch(t2, 0, raw);
 #pragma unroll
       for (int c = 0; c < NUC; ++c) {
+        Op hp[2];
+        sg.unstage(raw, hp);
+        if (live && c + 1 < NUC) sg.fetch(t2, 32 * (c + 1), raw);
         const f32x16 g = mma(__builtin_bit_cast(bf16x8, s_w3t[c * 64 + lane]), dyo[0], zero16());
-        const Op hp[2] = {h2[2 * c], h2[2 * c + 1]};
         float t[16];
         dtanh_range(g, hp, t, 0, 16, false);
         Op dz[2];
         to_operands<true>(t, dz);
-        h2[2 * c] = dz[0];
-        h2[2 * c + 1] = dz[1];
+        dz2[2 * c] = dz[0];
+        dz2[2 * c + 1] = dz[1];
         if (live) sg.chunk(tz2, 32 * c, dz);
       }
     }
@@ -419,44 +459,34 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     {
       __bf16* tz1 = a.dz1t + (size_t)tile * H * 32;
       f32x16 acc = zero16();
+      Op hp[2] = {Op{0, 0, 0, 0, 0, 0, 0, 0}, Op{0, 0, 0, 0, 0, 0, 0, 0}};  // layer-1 activations of the chunk before
 #pragma unroll 1
       for (int sc = 0; sc < SPN; ++sc) {
         ws.wait_oldest();
         int next = SPN + sc + 1;  // the next tile's first forward stage follows the last backward stage
         if (next >= 2 * SPN) next -= 2 * SPN;
         const int nbuf = (gs + 1) % NBUF;
-        // layer-1 activations of the chunks whose epilogue runs in this stage
-        Op hp[CPS][2];
-#pragma unroll
-        for (int c = 0; c < CPS; ++c) hp[c][0] = hp[c][1] = Op{0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int k = 0; k < SPN; ++k)
-          if (sc == k) {
-#pragma unroll
-            for (int c = 0; c < CPS; ++c) {
-              const int idx = k * CPS + c - 1;
-              if (idx >= 0) {
-                hp[c][0] = h1[0][2 * idx];
-                hp[c][1] = h1[0][2 * idx + 1];
-              }
-            }
-          }
 #pragma unroll
         for (int c = 0; c < CPS; ++c) {
           const u32x4* tiles = ws.tiles(gs % NBUF, c);
           auto tick = [&](int kt) { spread(next, nbuf, c, kt); };
+          const int chunk = sc * CPS + c;
+          // activations of this chunk, for the epilogue that runs during the next one: fetched now,
+          // turned into operand form after the tile loop
+          u32x4 raw[2] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
+          if (live) sg.fetch(t1, 32 * chunk, raw);
           Op dz[2];
           if (c == 0 && sc == 0) {
-            bwd_chunk<Net, false>(tiles, h2, acc, hp[c], dz, tick);
+            bwd_chunk<Net, false>(tiles, dz2, acc, hp, dz, tick);
           } else {
-            bwd_chunk<Net, true>(tiles, h2, acc, hp[c], dz, tick);
-            if (live) sg.chunk(tz1, 32 * (sc * CPS + c - 1), dz);
+            bwd_chunk<Net, true>(tiles, dz2, acc, hp, dz, tick);
+            if (live) sg.chunk(tz1, 32 * (chunk - 1), dz);
           }
+          sg.unstage(raw, hp);
         }
         ++gs;
       }
       {
-        const Op hp[2] = {h1[0][2 * (NUC - 1)], h1[0][2 * (NUC - 1) + 1]};
         float t[16];
         dtanh_range(acc, hp, t, 0, 16, false);
         Op dz[2];
