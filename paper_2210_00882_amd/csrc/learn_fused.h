@@ -6,10 +6,10 @@
 // never leave the register file.  What the weight gradients need -- the layer inputs and the
 // pre-activation gradients with the rows as contraction index -- is written once, as bf16, in a
 // tiled unit-major layout:
-//     tensor[tile][unit][32 rows],   tile = row / 32,
+//     tensor[tile][g][unit][8 rows],   tile = row / 32, g = (row % 32) / 8,
 // i.e. the 16 KiB a wave produces per tensor and tile are contiguous, and a lane of the weight
 // gradient kernel (wgrad_tiled_kernel) fetches the 8 rows of its MFMA fragment with one 16-byte
-// load.  Weights reach the row kernel as MFMA A-operand tiles (packed.h) through the LDS window of
+// load, the lanes of a wave reading consecutive pieces.  Weights reach the row kernel as MFMA A-operand tiles (packed.h) through the LDS window of
 // WeightStream: per 32-row tile the forward chunk blocks (W2 by output chunk, W3), then the
 // backward chunk blocks (W2 by input chunk); the layer-1 tiles and the tiles of W3 for the backward
 // pass stay resident.
@@ -44,73 +44,92 @@ __device__ __forceinline__ uint32_t quad_swap1(uint32_t x) {  // value of lane ^
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, false);
 }
 
-// Results leave the wave through a 2 KiB staging area in LDS (one per wave), so that the global
-// stores are whole 1 KiB runs of 16 bytes per lane: the memory pipeline takes about as long for a
-// 64-lane store of 4 bytes per lane as for one of 16, and a tile has 20480 values per tensor row.
-// Values are held one row per lane and two consecutive units per 32-bit register; neighbouring
-// lanes trade halves, so that a lane holds two consecutive rows of one unit, and write the staging
-// area in [unit][32 rows] order (32-bit LDS writes, conflict-free).
+// Tiled unit-major layout of the tensors the weight gradients read (bf16):
+//     tensor[tile = row / 32][g = (row % 32) / 8][unit][row % 8]
+// The 8 rows of one unit and group are the 16 bytes a lane of the weight-gradient kernel feeds to
+// an MFMA, and the lanes of that kernel (one unit each) read consecutive 16-byte pieces.
+//
+// Results leave the wave through a staging area in LDS (one per wave), so that the global stores
+// are runs of 16 bytes per lane (512 bytes per group for a chunk of 32 units): the memory pipeline
+// takes about as long for a 64-lane store of 4 bytes per lane as for one of 16.  Values are held
+// one row per lane and two consecutive units per 32-bit register; neighbouring lanes trade halves,
+// so that a lane holds two consecutive rows of one unit, and write the staging area in the order
+// [g][unit][4 row pairs] (32-bit LDS writes; the groups are 8 words apart modulo the banks).
 struct Stager {
-  uint32_t* stg;     // this wave's staging area: 512 words
+  static constexpr int GS = 136;  // words per group in the staging area (32 units x 4, + 8)
+  static constexpr int WORDS = 4 * GS;
+  uint32_t* stg;     // this wave's staging area
   uint32_t sel;      // byte selector of the exchange
-  int w_chain;       // word offset of this lane for chunk values: (4 h + n % 2) * 16 + n / 2
-  int w_lin;         // ... for observation values (linear input map): (8 h + n % 2) * 16 + n / 2
+  int w_chain;       // word offset of this lane for chunk values
+  int w_lin;         // ... for observation values (linear input map)
   int lane;
   __device__ __forceinline__ Stager(uint32_t* s, int lane_, int n, int h)
-      : stg(s), sel((n & 1) ? 0x03020706u : 0x05040100u), w_chain((4 * h + (n & 1)) * 16 + (n >> 1)),
-        w_lin((8 * h + (n & 1)) * 16 + (n >> 1)), lane(lane_) {}
+      : stg(s), sel((n & 1) ? 0x03020706u : 0x05040100u),
+        w_chain((n >> 3) * GS + (4 * h + (n & 1)) * 4 + ((n >> 1) & 3)),
+        w_lin((n >> 3) * GS + (8 * h + (n & 1)) * 4 + ((n >> 1) & 3)), lane(lane_) {}
   __device__ __forceinline__ uint32_t trade(uint32_t x) const {
     return __builtin_amdgcn_perm(quad_swap1(x), x, sel);
   }
-  // KB KiB of staged values -> dst (16-byte aligned), as 16 bytes per lane and instruction
-  template <int KB>
-  __device__ __forceinline__ void flush(__bf16* dst) const {
-#ifdef MSRL_DBG_NOSTAGE
-    return;
-#endif
+  // staged values of NU units (32: two pieces per lane, 16: one) -> units unit0 .. of a tile with U units
+  template <int NU>
+  __device__ __forceinline__ void flush(__bf16* tile, int U, int unit0) const {
+    constexpr int K = NU / 16;
     wave_lds_sync();
-    u32x4 v[KB];
+    u32x4 v[K];
+    int at[K];
 #pragma unroll
-    for (int k = 0; k < KB; ++k) v[k] = ((const u32x4*)stg)[64 * k + lane];
+    for (int k = 0; k < K; ++k) {
+      const int idx = 64 * k + lane, g = idx / NU, u = idx % NU;
+      v[k] = *(const u32x4*)(stg + g * GS + u * 4);
+      at[k] = g * U + unit0 + u;
+    }
 #pragma unroll
-    for (int k = 0; k < KB; ++k)
-#ifdef MSRL_DBG_NOSTORE
-      if (v[k][0] == 0x12345678u)
-#endif
-      ((u32x4*)dst)[64 * k + lane] = v[k];
+    for (int k = 0; k < K; ++k) ((u32x4*)tile)[at[k]] = v[k];
     wave_lds_sync();
   }
-  // one 32-unit chunk in operand form -> tile[unit0 .. unit0 + 31][32 rows] (2 KiB, contiguous)
-  __device__ __forceinline__ void chunk(__bf16* tile, int unit0, const bf16x8 (&op)[2]) const {
+  // one 32-unit chunk in operand form -> units unit0 .. unit0 + 31 of a tile
+  __device__ __forceinline__ void chunk(__bf16* tile, int U, int unit0, const bf16x8 (&op)[2]) const {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const u32x4 w = __builtin_bit_cast(u32x4, op[j]);
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         const int r = 8 * j + 2 * d;  // accumulator register of the low half
-        stg[(8 * (r / 4) + r % 4) * 16 + w_chain] = trade(w[d]);
+        stg[(8 * (r / 4) + r % 4) * 4 + w_chain] = trade(w[d]);
       }
     }
-    flush<2>(tile + (size_t)unit0 * 32);
+    flush<32>(tile, U, unit0);
   }
-  // the first 16 units of a chunk (operand 0) -> tile[0 .. 15][32 rows] (1 KiB)
+  // the first 16 units of a chunk (operand 0) -> units 0 .. 15 of a tile with 16 units
   __device__ __forceinline__ void half_chunk(__bf16* tile, const bf16x8& op) const {
     const u32x4 w = __builtin_bit_cast(u32x4, op);
 #pragma unroll
-    for (int d = 0; d < 4; ++d) stg[(8 * (d / 2) + 2 * (d % 2)) * 16 + w_chain] = trade(w[d]);
-    flush<1>(tile);
+    for (int d = 0; d < 4; ++d) stg[(8 * (d / 2) + 2 * (d % 2)) * 4 + w_chain] = trade(w[d]);
+    flush<16>(tile, 16, 0);
   }
-  // The way back, for a chunk the wave wrote earlier: 2 KiB of a tile into registers as they lie in
+  // 16 observation inputs (one layer-1 operand) -> units unit0 .. unit0 + 15 of a tile
+  __device__ __forceinline__ void inputs16(__bf16* tile, int U, int unit0, const bf16x8& op) const {
+    const u32x4 w = __builtin_bit_cast(u32x4, op);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) stg[(2 * d) * 4 + w_lin] = trade(w[d]);
+    flush<16>(tile, U, unit0);
+  }
+  // The way back, for a chunk the wave wrote earlier: its 2 KiB into registers as they lie in
   // memory (fetch; issued early), then through the staging area into operand form (unstage).
-  __device__ __forceinline__ void fetch(const __bf16* tile, int unit0, u32x4 (&raw)[2]) const {
-    const u32x4* src = (const u32x4*)(tile + (size_t)unit0 * 32);
-    raw[0] = src[lane];
-    raw[1] = src[64 + lane];
+  __device__ __forceinline__ void fetch(const __bf16* tile, int U, int unit0, u32x4 (&raw)[2]) const {
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int idx = 64 * k + lane, g = idx / 32, u = idx % 32;
+      raw[k] = ((const u32x4*)tile)[g * U + unit0 + u];
+    }
   }
   __device__ __forceinline__ void unstage(const u32x4 (&raw)[2], bf16x8 (&op)[2]) const {
     wave_lds_sync();
-    ((u32x4*)stg)[lane] = raw[0];
-    ((u32x4*)stg)[64 + lane] = raw[1];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int idx = 64 * k + lane, g = idx / 32, u = idx % 32;
+      *(u32x4*)(stg + g * GS + u * 4) = raw[k];
+    }
     wave_lds_sync();
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -118,18 +137,11 @@ struct Stager {
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         const int r = 8 * j + 2 * d;
-        w[d] = trade(stg[(8 * (r / 4) + r % 4) * 16 + w_chain]);  // the 2 x 2 exchange is its own inverse
+        w[d] = trade(stg[(8 * (r / 4) + r % 4) * 4 + w_chain]);  // the 2 x 2 exchange is its own inverse
       }
       op[j] = __builtin_bit_cast(bf16x8, w);
     }
     wave_lds_sync();
-  }
-  // 16 observation inputs (one layer-1 operand) -> tile[unit0 .. unit0 + 15][32 rows] (1 KiB)
-  __device__ __forceinline__ void inputs16(__bf16* tile, int unit0, const bf16x8& op) const {
-    const u32x4 w = __builtin_bit_cast(u32x4, op);
-#pragma unroll
-    for (int d = 0; d < 4; ++d) stg[(2 * d) * 16 + w_lin] = trade(w[d]);
-    flush<1>(tile + (size_t)unit0 * 32);
   }
 };
 
@@ -246,7 +258,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
   __shared__ __attribute__((aligned(16))) u32x4 s_w3t[NUC * 64];
   __shared__ __attribute__((aligned(16))) u32x4 s_w[NBUF * Stream::BUF_SLOTS];
   __shared__ __attribute__((aligned(16))) float s_b3[32];
-  __shared__ __attribute__((aligned(16))) uint32_t s_stg[WAVES][512];
+  __shared__ __attribute__((aligned(16))) uint32_t s_stg[WAVES][Stager::WORDS];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -322,7 +334,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     if (NET == 0 && live) {
       __bf16* xt = a.xt + (size_t)tile * (16 * KT1) * 32;
 #pragma unroll
-      for (int kt = 0; kt < KT1; ++kt) sg.inputs16(xt, 16 * kt, x[0][kt]);
+      for (int kt = 0; kt < KT1; ++kt) sg.inputs16(xt, 16 * KT1, 16 * kt, x[0][kt]);
     }
 
     // ---------------- forward.  The activations go to their tiles as they are produced and are
@@ -339,7 +351,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
 #pragma unroll
         for (int c = 0; c < NUC; ++c) {
           const Op pr[2] = {h1[0][2 * c], h1[0][2 * c + 1]};
-          sg.chunk(t1, 32 * c, pr);
+          sg.chunk(t1, H, 32 * c, pr);
         }
       }
       f32x16 acc = zero16();
@@ -357,7 +369,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
             fwd_chunk<Net, false>(tiles, h1, acc, out, h, hn, tick);
           } else {
             fwd_chunk<Net, true>(tiles, h1, acc, out, h, hn, tick);
-            if (live) sg.chunk(t2, 32 * (sc * CPS + c - 1), hn);
+            if (live) sg.chunk(t2, H, 32 * (sc * CPS + c - 1), hn);
           }
         }
         ++gs;
@@ -372,7 +384,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
 #pragma unroll
         for (int i = 0; i < TPC; ++i)
           out = mma(__builtin_bit_cast(bf16x8, tiles[(Net::L3_OWN + i) * 64]), hl[i], out);
-        if (live) sg.chunk(t2, 32 * (NUC - 1), hl);
+        if (live) sg.chunk(t2, H, 32 * (NUC - 1), hl);
       }
     }
 
@@ -438,12 +450,12 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     {
       __bf16* tz2 = a.dz2t + (size_t)tile * H * 32;
       u32x4 raw[2] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
-      if (live) sg.fetch(t2, 0, raw);
+      if (live) sg.fetch(t2, H, 0, raw);
 #pragma unroll
       for (int c = 0; c < NUC; ++c) {
         Op hp[2];
         sg.unstage(raw, hp);
-        if (live && c + 1 < NUC) sg.fetch(t2, 32 * (c + 1), raw);
+        if (live && c + 1 < NUC) sg.fetch(t2, H, 32 * (c + 1), raw);
         const f32x16 g = mma(__builtin_bit_cast(bf16x8, s_w3t[c * 64 + lane]), dyo[0], zero16());
         float t[16];
         dtanh_range(g, hp, t, 0, 16, false);
@@ -451,7 +463,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
         to_operands<true>(t, dz);
         dz2[2 * c] = dz[0];
         dz2[2 * c + 1] = dz[1];
-        if (live) sg.chunk(tz2, 32 * c, dz);
+        if (live) sg.chunk(tz2, H, 32 * c, dz);
       }
     }
 
@@ -474,13 +486,13 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
           // activations of this chunk, for the epilogue that runs during the next one: fetched now,
           // turned into operand form after the tile loop
           u32x4 raw[2] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
-          if (live) sg.fetch(t1, 32 * chunk, raw);
+          if (live) sg.fetch(t1, H, 32 * chunk, raw);
           Op dz[2];
           if (c == 0 && sc == 0) {
             bwd_chunk<Net, false>(tiles, dz2, acc, hp, dz, tick);
           } else {
             bwd_chunk<Net, true>(tiles, dz2, acc, hp, dz, tick);
-            if (live) sg.chunk(tz1, 32 * (chunk - 1), dz);
+            if (live) sg.chunk(tz1, H, 32 * (chunk - 1), dz);
           }
           sg.unstage(raw, hp);
         }
@@ -491,7 +503,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
         dtanh_range(acc, hp, t, 0, 16, false);
         Op dz[2];
         to_operands<true>(t, dz);
-        if (live) sg.chunk(tz1, 32 * (NUC - 1), dz);
+        if (live) sg.chunk(tz1, H, 32 * (NUC - 1), dz);
       }
     }
   }

@@ -58,8 +58,8 @@ __global__ void learn_pack_kernel(LearnPackJobs jobs) {
 
 // ---------------------------------------------------------------- weight gradients from the tiled layout
 struct WgradTArgs {
-  const __bf16* A;  // [tiles][UA][32]: left operand, its units are the rows of C
-  const __bf16* B;  // [tiles][UB][32]: right operand, its units are the columns of C
+  const __bf16* A;  // [tiles][4][UA][8]: left operand, its units are the rows of C
+  const __bf16* B;  // [tiles][4][UB][8]: right operand, its units are the columns of C
   int UA, UB;
   int M, N;         // units that take part (M <= min(UA, 256), N <= min(UB, 256))
   int m_out;        // rows m < m_out of C are written
@@ -71,20 +71,25 @@ struct WgradTArgs {
 };
 
 // Output-stationary like wgrad_kernel (learn_kernels.h): workgroup z takes the row tiles
-// [z tiles_per_slice, (z+1) tiles_per_slice), wave w the units 32 w .. 32 w + 31 of A and all columns;
-// the B fragments of two row tiles (four k tiles) are shared through LDS, loaded one step ahead.
+// [z tiles_per_slice, (z+1) tiles_per_slice), wave w the units 32 w .. 32 w + 31 of A and all NTW
+// column tiles of 32; the B fragments of a step (two row tiles = four k tiles) are shared through
+// LDS.  Both operands are fetched DEPTH steps ahead into registers: the kernel does little
+// arithmetic per byte, so what it needs is enough loads in flight per compute unit to cover the
+// memory latency (NTW = 1, the output layer, has the registers for a deeper queue).
 // The bias gradient is one more contraction with a left operand of ones: wave w adds it up for
 // column tile w.
+template <int NTW, int DEPTH>
 __global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTArgs g) {
-  constexpr int NTW = 8, PER = NTW * 4 * 64 / 512;
-  __shared__ __attribute__((aligned(16))) u32x4 s_b[NTW * 4 * 64];
+  constexpr int FR = NTW * 4 * 64;                 // B fragments per step
+  constexpr int PER = (FR + 511) / 512;            // ... per thread
+  __shared__ __attribute__((aligned(16))) u32x4 s_b[FR];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int i = lane & 31, h = lane >> 5;
   const int64_t t_begin = (int64_t)blockIdx.x * g.tiles_per_slice;
   const int64_t t_end = min(g.n_tiles, t_begin + g.tiles_per_slice);
   if (t_begin >= t_end) return;  // whole workgroup
-  const int ntiles = (g.N + 31) / 32;
+  const int ntiles = min(NTW, (g.N + 31) / 32);
   const int m0 = 32 * wave;
   const bool m_live = m0 < g.M;
   const bool a_ok = m0 + i < g.M;
@@ -95,8 +100,13 @@ __global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTArgs g) {
     const int j = slot / 256, kk = (slot / 64) % 4, l = slot % 64;
     const int nn = 32 * j + (l & 31);
     const int64_t T = T0 + kk / 2;
-    if (j < ntiles && nn < g.N && T < t_end)
-      return *(const bf16x8*)(g.B + ((size_t)T * g.UB + nn) * 32 + (kk % 2) * 16 + (l >> 5) * 8);
+    if (slot < FR && j < ntiles && nn < g.N && T < t_end)
+      return ((const bf16x8*)g.B)[((size_t)T * 4 + 2 * (kk % 2) + (l >> 5)) * g.UB + nn];
+    return zero;
+  };
+  auto a_frag = [&](int kk, int64_t T0) -> bf16x8 {
+    const int64_t T = T0 + kk / 2;
+    if (a_ok && T < t_end) return ((const bf16x8*)g.A)[((size_t)T * 4 + 2 * (kk % 2) + h) * g.UA + m0 + i];
     return zero;
   };
   f32x16 acc[NTW], accb = zero16();
@@ -105,45 +115,46 @@ __global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTArgs g) {
   bf16x8 ones;
 #pragma unroll
   for (int s = 0; s < 8; ++s) ones[s] = (__bf16)1.0f;
-  auto a_frag = [&](int kk, int64_t T0) -> bf16x8 {
-    const int64_t T = T0 + kk / 2;
-    if (a_ok && T < t_end) return *(const bf16x8*)(g.A + ((size_t)T * g.UA + m0 + i) * 32 + (kk % 2) * 16 + h * 8);
-    return zero;
-  };
-  // both operands of a step are fetched one step ahead, into registers
-  bf16x8 next[PER], next_a[4];
+  // queue of DEPTH steps; slot d holds step (begin + 2 d) + 2 DEPTH k for k = 0, 1, ...
+  bf16x8 qb[DEPTH][PER], qa[DEPTH][4];
 #pragma unroll
-  for (int f = 0; f < PER; ++f) next[f] = panel_frag(f, t_begin);
+  for (int d = 0; d < DEPTH; ++d) {
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) next_a[kk] = a_frag(kk, t_begin);
-  for (int64_t T0 = t_begin; T0 < t_end; T0 += 2) {
+    for (int f = 0; f < PER; ++f) qb[d][f] = panel_frag(f, t_begin + 2 * d);
 #pragma unroll
-    for (int f = 0; f < PER; ++f) s_b[f * 512 + threadIdx.x] = __builtin_bit_cast(u32x4, next[f]);
-    bf16x8 av[4];
+    for (int kk = 0; kk < 4; ++kk) qa[d][kk] = a_frag(kk, t_begin + 2 * d);
+  }
+  for (int64_t T0 = t_begin; T0 < t_end; T0 += 2 * DEPTH) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) av[kk] = next_a[kk];
-    __syncthreads();
-    if (T0 + 2 < t_end) {
+    for (int d = 0; d < DEPTH; ++d) {
+      const int64_t Td = T0 + 2 * d;
+      if (Td >= t_end) break;  // uniform
 #pragma unroll
-      for (int f = 0; f < PER; ++f) next[f] = panel_frag(f, T0 + 2);
+      for (int f = 0; f < PER; ++f)
+        if (f * 512 + (int)threadIdx.x < FR) s_b[f * 512 + threadIdx.x] = __builtin_bit_cast(u32x4, qb[d][f]);
+      __syncthreads();
+      // refill the slot (fragments beyond the slice read as zero): the B part now, the A part once
+      // the MFMAs below have been issued (they read the registers at issue)
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) next_a[kk] = a_frag(kk, T0 + 2);
+      for (int f = 0; f < PER; ++f) qb[d][f] = panel_frag(f, Td + 2 * DEPTH);
+      if (m_live) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+          for (int j = 0; j < NTW; ++j) {
+            if (j >= ntiles) continue;  // uniform
+            acc[j] = mma(qa[d][kk], __builtin_bit_cast(bf16x8, s_b[(j * 4 + kk) * 64 + lane]), acc[j]);
+          }
+      }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) qa[d][kk] = a_frag(kk, Td + 2 * DEPTH);
+      if (b_live) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          accb = mma(ones, __builtin_bit_cast(bf16x8, s_b[(wave * 4 + kk) * 64 + lane]), accb);
+      }
+      __syncthreads();
     }
-    if (m_live) {
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-        for (int j = 0; j < NTW; ++j) {
-          if (j >= ntiles) continue;  // uniform
-          acc[j] = mma(av[kk], __builtin_bit_cast(bf16x8, s_b[(j * 4 + kk) * 64 + lane]), acc[j]);
-        }
-    }
-    if (b_live) {
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-        accb = mma(ones, __builtin_bit_cast(bf16x8, s_b[(wave * 4 + kk) * 64 + lane]), accb);
-    }
-    __syncthreads();
   }
   if (b_live && h == 0) {
     const int nn = 32 * wave + i;  // every row of the ones-contraction is the column sum: take row 0

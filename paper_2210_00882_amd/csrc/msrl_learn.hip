@@ -333,7 +333,10 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
       memset(&g, 0, sizeof(g));
       g.A = (const __bf16*)A; g.B = (const __bf16*)B; g.UA = UA; g.UB = UB; g.M = M; g.N = N; g.m_out = M;
       g.n_tiles = n_tiles; g.tiles_per_slice = tps; g.C = C; g.ldc = ldc; g.bias = bias;
-      hipLaunchKernelGGL(wgrad_tiled_kernel, dim3(slices), dim3(512), 0, s, g);
+      if (N <= 32)
+        hipLaunchKernelGGL((wgrad_tiled_kernel<1, 4>), dim3(slices), dim3(512), 0, s, g);
+      else
+        hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices), dim3(512), 0, s, g);
     };
     wg(b.h2t, H, H, b.dyt, 16, O, gW3, O, gb3);
     wg(b.h1t, H, H, b.dz2t, H, H, gW2, H, gb2);
