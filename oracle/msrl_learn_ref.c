@@ -46,6 +46,7 @@ typedef struct {
   int32_t in_dim, hidden, out_dim;
   int32_t bf16;
   int32_t dist;
+  int32_t hidden_layers; /* the learner is defined for two hidden layers only (0 or 2) */
 } ref_policy_cfg;
 
 typedef struct {

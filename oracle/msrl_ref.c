@@ -49,6 +49,7 @@ typedef struct {
   int32_t in_dim, hidden, out_dim;
   int32_t bf16; /* 0: exact arithmetic on the given values; 1: bf16 rounding points */
   int32_t dist;
+  int32_t hidden_layers; /* tanh layers of `hidden` units in front of the output layer; 0 means 2 */
 } ref_policy_cfg;
 
 /* ---------------------------------------------------------------- Philox */
@@ -141,36 +142,51 @@ static void dense(const double* W, const double* b, int in, int out, const doubl
   }
 }
 
-/* in - H - H - out network with tanh hidden layers; params = W1 b1 W2 b2 W3 b3.
- * bf16 = 1 rounds every layer input and every weight to bfloat16; sums, bias
- * add and tanh are not rounded. */
-void ref_mlp(int in, int H, int out, const double* params, const double* x, double* y,
-             int bf16) {
-  const double* W1 = params;
-  const double* b1 = W1 + (size_t)in * H;
-  const double* W2 = b1 + H;
-  const double* b2 = W2 + (size_t)H * H;
-  const double* W3 = b2 + H;
-  const double* b3 = W3 + (size_t)H * out;
-  double* h1 = (double*)malloc(sizeof(double) * (size_t)H);
-  double* h2 = (double*)malloc(sizeof(double) * (size_t)H);
-  dense(W1, b1, in, H, x, h1, 1, bf16);
-  dense(W2, b2, H, H, h1, h2, 1, bf16);
-  dense(W3, b3, H, out, h2, y, 0, bf16);
-  free(h1);
-  free(h2);
+/* in - H - ... - H - out network with L >= 1 tanh hidden layers of H units (the paper's
+ * evaluation uses a deeper policy than its listings: section 6, "seven-layer DNN"; the depth is a
+ * parameter here); params = W1 b1, then W b per further hidden layer, then the output layer's
+ * W b, every W stored [inputs, outputs].  bf16 = 1 rounds every layer input and every weight to
+ * bfloat16; sums, bias add and tanh are not rounded. */
+void ref_mlp_l(int in, int H, int out, int L, const double* params, const double* x, double* y,
+               int bf16) {
+  double* ha = (double*)malloc(sizeof(double) * (size_t)H);
+  double* hb = (double*)malloc(sizeof(double) * (size_t)H);
+  const double* P = params;
+  dense(P, P + (size_t)in * H, in, H, x, ha, 1, bf16);
+  P += (size_t)in * H + H;
+  for (int l = 1; l < L; ++l) {
+    dense(P, P + (size_t)H * H, H, H, ha, hb, 1, bf16);
+    P += (size_t)H * H + H;
+    double* t = ha;
+    ha = hb;
+    hb = t;
+  }
+  dense(P, P + (size_t)H * out, H, out, ha, y, 0, bf16);
+  free(ha);
+  free(hb);
 }
 
-size_t ref_net_param_count(int in, int H, int out) {
-  return (size_t)in * H + H + (size_t)H * H + H + (size_t)H * out + out;
+/* the two-hidden-layer network of the benchmark configurations: W1 b1 W2 b2 W3 b3 */
+void ref_mlp(int in, int H, int out, const double* params, const double* x, double* y,
+             int bf16) {
+  ref_mlp_l(in, H, out, 2, params, x, y, bf16);
 }
+
+size_t ref_net_param_count_l(int in, int H, int out, int L) {
+  return (size_t)in * H + H + (size_t)(L - 1) * ((size_t)H * H + H) + (size_t)H * out + out;
+}
+
+size_t ref_net_param_count(int in, int H, int out) { return ref_net_param_count_l(in, H, out, 2); }
+
+static int layers_of(const ref_policy_cfg* p) { return p->hidden_layers > 0 ? p->hidden_layers : 2; }
 
 /* Policy outputs and value of one observation row; params = policy net, value net. */
 void ref_policy_value(const ref_policy_cfg* p, const double* params, const double* x,
                       double* logits, double* value) {
-  ref_mlp(p->in_dim, p->hidden, p->out_dim, params, x, logits, p->bf16);
-  ref_mlp(p->in_dim, p->hidden, 1,
-          params + ref_net_param_count(p->in_dim, p->hidden, p->out_dim), x, value, p->bf16);
+  const int L = layers_of(p);
+  ref_mlp_l(p->in_dim, p->hidden, p->out_dim, L, params, x, logits, p->bf16);
+  ref_mlp_l(p->in_dim, p->hidden, 1, L,
+            params + ref_net_param_count_l(p->in_dim, p->hidden, p->out_dim, L), x, value, p->bf16);
 }
 
 /* ---------------------------------------------------------------- sampling */

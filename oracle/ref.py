@@ -44,7 +44,7 @@ class EnvCfg(C.Structure):
 
 class PolicyCfg(C.Structure):
     _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("out_dim", C.c_int32),
-                ("bf16", C.c_int32), ("dist", C.c_int32)]
+                ("bf16", C.c_int32), ("dist", C.c_int32), ("hidden_layers", C.c_int32)]
 
 
 _lib = None
@@ -59,6 +59,7 @@ def lib():
         _lib.ref_bf16_round.restype = C.c_double
         _lib.ref_bf16_round.argtypes = [C.c_double]
         _lib.ref_net_param_count.restype = C.c_size_t
+        _lib.ref_net_param_count_l.restype = C.c_size_t
         _lib.ref_env_state_size.restype = C.c_int
     return _lib
 
@@ -88,18 +89,19 @@ class Env:
 
 
 class Policy:
-    def __init__(self, in_dim, hidden, out_dim, bf16=False, dist=CATEGORICAL):
-        self.c = PolicyCfg(in_dim, hidden, out_dim, int(bf16), dist)
+    def __init__(self, in_dim, hidden, out_dim, bf16=False, dist=CATEGORICAL, hidden_layers=2):
+        self.c = PolicyCfg(in_dim, hidden, out_dim, int(bf16), dist, hidden_layers)
         self.in_dim, self.hidden, self.out_dim, self.bf16, self.dist = in_dim, hidden, out_dim, bool(bf16), dist
+        self.hidden_layers = hidden_layers
 
     @property
     def param_count(self):
-        return net_param_count(self.in_dim, self.hidden, self.out_dim) + \
-            net_param_count(self.in_dim, self.hidden, 1)
+        return net_param_count(self.in_dim, self.hidden, self.out_dim, self.hidden_layers) + \
+            net_param_count(self.in_dim, self.hidden, 1, self.hidden_layers)
 
 
-def net_param_count(i, h, o):
-    return int(lib().ref_net_param_count(C.c_int(i), C.c_int(h), C.c_int(o)))
+def net_param_count(i, h, o, layers=2):
+    return int(lib().ref_net_param_count_l(C.c_int(i), C.c_int(h), C.c_int(o), C.c_int(layers)))
 
 
 # ------------------------------------------------------------------ random numbers
@@ -140,11 +142,12 @@ def bf16_round(x):
 
 
 # ------------------------------------------------------------------ networks / sampling
-def mlp(i, h, o, params, x, bf16=False):
+def mlp(i, h, o, params, x, bf16=False, layers=2):
     params, x = _f64(params), _f64(x)
-    assert params.size == net_param_count(i, h, o) and x.size == i
+    assert params.size == net_param_count(i, h, o, layers) and x.size == i
     y = np.zeros(o, dtype=np.float64)
-    lib().ref_mlp(C.c_int(i), C.c_int(h), C.c_int(o), _p(params), _p(x), _p(y), C.c_int(int(bf16)))
+    lib().ref_mlp_l(C.c_int(i), C.c_int(h), C.c_int(o), C.c_int(layers), _p(params), _p(x), _p(y),
+                    C.c_int(int(bf16)))
     return y
 
 

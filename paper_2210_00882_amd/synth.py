@@ -45,6 +45,7 @@ class Config:
     lam: float = 0.95
     env_seed: int = 0
     param_seed: int = 0
+    hidden_layers: int = 2   # tanh layers of `hidden` units in front of the output layer
     extra: dict = field(default_factory=dict)
 
     @property
@@ -59,8 +60,8 @@ class Config:
 
     @property
     def param_count(self) -> int:
-        return net_param_count(self.obs_dim, self.hidden, self.out_dim) + \
-            net_param_count(self.obs_dim, self.hidden, 1)
+        return net_param_count(self.obs_dim, self.hidden, self.out_dim, self.hidden_layers) + \
+            net_param_count(self.obs_dim, self.hidden, 1, self.hidden_layers)
 
     def with_(self, **kw) -> "Config":
         d = dict(self.__dict__)
@@ -68,8 +69,8 @@ class Config:
         return Config(**d)
 
 
-def net_param_count(i: int, h: int, o: int) -> int:
-    return i * h + h + h * h + h + h * o + o
+def net_param_count(i: int, h: int, o: int, layers: int = 2) -> int:
+    return i * h + h + (layers - 1) * (h * h + h) + h * o + o
 
 
 def particle(name, E, N, H, T, ep, dtype=F32, idx=0) -> Config:
@@ -95,13 +96,14 @@ CONFIGS = {
 
 def make_params(cfg: Config, bias_std: float = 0.0, seed: int | None = None) -> np.ndarray:
     """Flat float32 parameter vector, policy net then value net, each
-    W1 b1 W2 b2 W3 b3 with W[in, out]; weights ~ N(0, 1/fan_in), biases ~
+    W1 b1 W2 b2 W3 b3 (one more W b per hidden layer beyond two) with W[in, out]; weights ~ N(0, 1/fan_in), biases ~
     N(0, bias_std^2) (0 in the benchmark recipe).  For BF16 configurations every
     value is rounded to a bfloat16-representable float32."""
     rng = np.random.default_rng(cfg.param_seed if seed is None else seed)
     parts = []
     for out in (cfg.out_dim, 1):
-        for fan_in, fan_out in ((cfg.obs_dim, cfg.hidden), (cfg.hidden, cfg.hidden), (cfg.hidden, out)):
+        dims = [cfg.obs_dim] + [cfg.hidden] * cfg.hidden_layers + [out]
+        for fan_in, fan_out in zip(dims[:-1], dims[1:]):
             parts.append((rng.standard_normal((fan_in, fan_out)) / np.sqrt(fan_in)).ravel())
             parts.append(rng.standard_normal(fan_out) * bias_std)
     p = np.concatenate(parts).astype(np.float32)

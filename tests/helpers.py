@@ -47,7 +47,8 @@ def oracle_setup(cfg: synth.Config, bias_std=0.1, params=None):
         dyn = synth.make_dynamics(cfg)
         env = ref.Env(ref.LINGAUSS, 1, 0, cfg.obs_dim, cfg.act_dim, cfg.episode_len, A=dyn[0], B=dyn[1],
                       noise_std=np.float32(cfg.noise_std), act_cost=np.float32(cfg.act_cost))
-    pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist)
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist,
+                     hidden_layers=cfg.hidden_layers)
     if params is None:
         params = synth.make_params(cfg, bias_std=bias_std)
     return env, pol, np.asarray(params, dtype=np.float64), dyn

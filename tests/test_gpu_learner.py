@@ -26,7 +26,8 @@ def tensors_of(vec, i, h, o):
 def make_batch(cfg, R, seed, params):
     """Rows with the shapes of a stored trajectory; ratios spread around the clip range."""
     rng = np.random.default_rng(seed)
-    pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist)
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist,
+                     hidden_layers=cfg.hidden_layers)
     obs = rng.uniform(-1, 1, (R, cfg.obs_dim)).astype(np.float32)
     if cfg.kind == synth.PARTICLE:
         obs[:, 4 * cfg.num_agents + 2:] = 0.0      # the zero slots of the particle observation

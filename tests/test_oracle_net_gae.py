@@ -86,6 +86,72 @@ def test_mlp_bf16_rounding_points():
     np.testing.assert_allclose(ref.mlp(i, h, o, p, x, bf16=True), ref.mlp(i, h, o, p, x), atol=2e-2 * 3)
 
 
+def split_deep(params, i, h, o, layers):
+    """[(W, b)] of the layers of a net with `layers` hidden layers, in parameter order."""
+    dims = [i] + [h] * layers + [o]
+    out, at = [], 0
+    for a, b in zip(dims[:-1], dims[1:]):
+        out.append((params[at:at + a * b].reshape(a, b), params[at + a * b:at + a * b + b]))
+        at += a * b + b
+    assert at == params.size
+    return out
+
+
+@pytest.mark.parametrize("layers", [1, 2, 3, 6])
+def test_deep_mlp_against_numpy_and_torch(layers):
+    # the same chain written with matmuls (numpy, float64) and with torch.nn.Linear modules
+    rng = np.random.default_rng(10 + layers)
+    bf = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    for (i, h, o) in [(18, 64, 5), (7, 12, 3)]:
+        n = ref.net_param_count(i, h, o, layers)
+        assert n == i * h + h + (layers - 1) * (h * h + h) + h * o + o
+        p = rng.standard_normal(n) * 0.3
+        x = rng.standard_normal(i)
+        wb = split_deep(p, i, h, o, layers)
+        a, ab = x, x
+        for W, b in wb[:-1]:
+            a = np.tanh(a @ W + b)
+            ab = np.tanh(bf(ab) @ bf(W) + b)
+        want, want_bf = a @ wb[-1][0] + wb[-1][1], bf(ab) @ bf(wb[-1][0]) + wb[-1][1]
+        np.testing.assert_allclose(ref.mlp(i, h, o, p, x, layers=layers), want, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(ref.mlp(i, h, o, p, x, bf16=True, layers=layers), want_bf, rtol=1e-12, atol=1e-13)
+        mods = []
+        for W, b in wb:
+            lin = torch.nn.Linear(W.shape[0], W.shape[1]).double()
+            with torch.no_grad():
+                lin.weight.copy_(torch.from_numpy(W.T.copy()))
+                lin.bias.copy_(torch.from_numpy(b.copy()))
+            mods += [lin, torch.nn.Tanh()]
+        net = torch.nn.Sequential(*mods[:-1])
+        with torch.no_grad():
+            np.testing.assert_allclose(ref.mlp(i, h, o, p, x, layers=layers), net(torch.from_numpy(x)).numpy(),
+                                       rtol=1e-12, atol=1e-13)
+
+
+def test_deep_policy_value_split_and_depth_two_is_the_default():
+    rng = np.random.default_rng(21)
+    pol = ref.Policy(18, 32, 5, hidden_layers=4)
+    p = rng.standard_normal(pol.param_count) * 0.2
+    x = rng.standard_normal(18)
+    lg, v = ref.policy_value(pol, p, x)
+    n = ref.net_param_count(18, 32, 5, 4)
+    np.testing.assert_array_equal(lg, ref.mlp(18, 32, 5, p[:n], x, layers=4))
+    assert v == ref.mlp(18, 32, 1, p[n:], x, layers=4)[0]
+    # an identity-like extra layer cannot be told from the shallower net: W = I / eps scaled so that
+    # tanh is linear is not exact, so instead check the count and the default
+    assert ref.Policy(18, 64, 5).param_count == ref.Policy(18, 64, 5, hidden_layers=2).param_count
+    p2 = rng.standard_normal(ref.net_param_count(6, 8, 3)) * 0.3
+    np.testing.assert_array_equal(ref.mlp(6, 8, 3, p2, np.ones(6)), ref.mlp(6, 8, 3, p2, np.ones(6), layers=2))
+
+
+def test_deep_mlp_by_hand():
+    # 1-1-1-1-1 net (three hidden layers)
+    p = np.array([0.5, 0.1, -2.0, 0.3, 1.5, -0.2, 4.0, -1.0])
+    y = ref.mlp(1, 1, 1, p, [0.7], layers=3)[0]
+    want = 4.0 * np.tanh(1.5 * np.tanh(-2.0 * np.tanh(0.5 * 0.7 + 0.1) + 0.3) - 0.2) - 1.0
+    assert y == pytest.approx(want, rel=1e-14)
+
+
 # ------------------------------------------------------------------ samplers
 def test_categorical_edges_and_logp():
     lg = np.array([0.3, -1.2, 2.0, 0.0, -0.5])
@@ -203,7 +269,8 @@ def oracle_setup(cfg, bias_std=0.1):
     else:
         A, B = synth.make_dynamics(cfg)
         env = ref.Env(ref.LINGAUSS, 1, 0, cfg.obs_dim, cfg.act_dim, cfg.episode_len, A=A, B=B)
-    pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist)
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist,
+                     hidden_layers=cfg.hidden_layers)
     return env, pol, synth.make_params(cfg, bias_std=bias_std).astype(np.float64)
 
 
