@@ -111,11 +111,20 @@ typedef struct {
  * Parameter buffer: policy then value, each
  *   W1[in_dim, hidden] b1[hidden] W2[hidden, hidden] b2[hidden] W3[hidden, out] b3[out]
  * with W row-major [in, out], so that y = x W + b.
+ *
+ * hidden_layers (0 means 2; 2..8): number of tanh layers of `hidden` units in
+ * front of the output layer (the evaluation of the paper, section 6, uses a
+ * seven-layer network).  Each layer beyond two adds one W[hidden, hidden]
+ * b[hidden] pair in front of W3.  More than two layers are supported by
+ * msrl_rollout_step / msrl_rollout_gae (and msrl_observe / msrl_env_step, which
+ * run no network) on the particle env; msrl_act, msrl_measure_phase and the
+ * learner return MSRL_EUNSUPPORTED for them.
  */
 typedef struct {
   int32_t in_dim, hidden, out_dim;
   int32_t dtype;  /* msrl_dtype */
   int32_t dist;   /* msrl_dist */
+  int32_t hidden_layers;
 } msrl_policy_cfg;
 
 /*

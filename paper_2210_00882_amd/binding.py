@@ -39,7 +39,7 @@ class msrl_env_cfg(C.Structure):
 
 class msrl_policy_cfg(C.Structure):
     _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("out_dim", C.c_int32),
-                ("dtype", C.c_int32), ("dist", C.c_int32)]
+                ("dtype", C.c_int32), ("dist", C.c_int32), ("hidden_layers", C.c_int32)]
 
 
 class msrl_traj(C.Structure):
@@ -156,7 +156,7 @@ def make_env_cfg(cfg, A=None, B=None):
 
 
 def make_policy_cfg(cfg):
-    return msrl_policy_cfg(cfg.obs_dim, cfg.hidden, cfg.out_dim, cfg.dtype, cfg.dist)
+    return msrl_policy_cfg(cfg.obs_dim, cfg.hidden, cfg.out_dim, cfg.dtype, cfg.dist, cfg.hidden_layers)
 
 
 def msrl_param_count(policy_cfg: msrl_policy_cfg) -> int:

@@ -239,6 +239,54 @@ struct Mlp {
     }
   }
 
+  // A chunk block of a hidden layer that is not the last one: acc <- pre-activations of chunk uc
+  // (bias included); if PIPE, `acc` holds those of chunk uc-1 on entry, which get tanh meanwhile and
+  // are returned as operands of the following layer in hprev.
+  template <bool PIPE, class Tick>
+  __device__ static __forceinline__ void hidden_chunk(const u32x4* tiles, const Op (&hin)[NB][KT2 * PT],
+                                                      f32x16 (&acc)[NB], Op (&hprev)[NB][PC], int h,
+                                                      Tick&& tick) {
+    u32x4 ring[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
+    f32x16 prev[NB];
+    float t[NB][16];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      prev[q] = acc[q];
+      acc[q] = zero16();
+    }
+#pragma unroll
+    for (int kt = 0; kt < KT2; ++kt) {
+      u32x4 raw = ring[kt % G];
+      if (kt + G < KT2 + 1) ring[kt % G] = tiles[(kt + G) * 64];
+      if (PIPE) pin(raw);
+#pragma unroll
+      for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &hin[q][kt * PT], acc[q]);
+      if (PIPE) tanh_slice<KT2>(prev, t, kt);
+      tick(kt);
+    }
+    {
+      const Op one = Operand<BF16>::one(h);
+      const u32x4 raw = ring[KT2 % G];
+#pragma unroll
+      for (int q = 0; q < NB; ++q) mma_bias_tile<BF16>(raw, one, acc[q]);
+    }
+    if (PIPE) {
+#pragma unroll
+      for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], hprev[q]);
+    }
+  }
+  // the last chunk of such a layer
+  __device__ static __forceinline__ void hidden_drain(const f32x16 (&acc)[NB], Op (&hlast)[NB][PC]) {
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      float t[16];
+      tanh_range(acc[q], t, 0, 16, false);
+      to_operands<BF16>(t, hlast[q]);
+    }
+  }
+
   // after the last chunk stage: its tanh and layer-3 contribution (tiles of the same stage)
   __device__ static __forceinline__ void layer2_drain(const u32x4* tiles, const f32x16 (&acc)[NB],
                                                       f32x16 (&out)[NB]) {
@@ -289,12 +337,13 @@ struct WeightStream {
   const uint8_t* packed;
   size_t net_bytes, chunks_off, chunk_bytes;
   int wave, lane;
+  int stages_per_net = STAGES_PER_NET;  // more with more than two hidden layers (set by the kernel)
 
-  // copy number i (0 .. PER_WAVE-1) of this wave for stage s (0 .. STAGES_PER_STEP-1) into buffer `buf`
+  // copy number i (0 .. PER_WAVE-1) of this wave for stage s (0 .. 2 stages_per_net - 1) into buffer `buf`
   __device__ __forceinline__ void issue_part(int s, int buf, int i) const {
-    const int net = s >= STAGES_PER_NET ? 1 : 0;
+    const int net = s >= stages_per_net ? 1 : 0;
     const uint8_t* src = packed + (size_t)net * net_bytes + chunks_off +
-                         (size_t)(s - net * STAGES_PER_NET) * CPS * chunk_bytes;
+                         (size_t)(s - net * stages_per_net) * CPS * chunk_bytes;
     typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
     const uint32_t base = (uint32_t)(uintptr_t)(lds_u32x4*)(lds + buf * BUF_SLOTS);
     // a wave with no tile left copies tile 0 once more (same bytes to the same place), so that

@@ -77,14 +77,18 @@ std::vector<KernelEntry> all_kernels() {
           entry_p3_h64_f32_act(), entry_p3_h64_f32_step(),
           entry_p3_h64_bf16_act(), entry_p3_h64_bf16_step(),
           entry_p6_h128_f32_act(), entry_p6_h128_f32_step(),
-          entry_p10_h256_bf16_act(), entry_p10_h256_bf16_step()};
+          entry_p10_h256_bf16_act(), entry_p10_h256_bf16_step(),
+          entry_p3_h64_f32_deep(), entry_p3_h64_bf16_deep(), entry_p10_h256_bf16_deep()};
 }
 
 bool valid_policy(const msrl_policy_cfg* p) {
   return p && p->in_dim >= 1 && p->hidden >= 1 && p->out_dim >= 1 &&
          (p->dtype == MSRL_F32 || p->dtype == MSRL_BF16) &&
-         (p->dist == MSRL_CATEGORICAL || p->dist == MSRL_DIAG_GAUSSIAN);
+         (p->dist == MSRL_CATEGORICAL || p->dist == MSRL_DIAG_GAUSSIAN) &&
+         (p->hidden_layers == 0 || (p->hidden_layers >= 2 && p->hidden_layers <= 8));
 }
+
+int layers_of(const msrl_policy_cfg& p) { return p.hidden_layers == 0 ? 2 : p.hidden_layers; }
 
 bool valid_env_shape(const msrl_env_cfg* e) {
   if (!e || e->num_envs < 1 || e->num_agents < 1 || e->obs_dim < 1 || e->episode_len < 1) return false;
@@ -96,8 +100,8 @@ bool valid_env_shape(const msrl_env_cfg* e) {
   return false;
 }
 
-size_t net_params(int in, int h, int out) {
-  return (size_t)in * h + h + (size_t)h * h + h + (size_t)h * out + out;
+size_t net_params(int in, int h, int out, int layers) {
+  return (size_t)in * h + h + (size_t)(layers - 1) * ((size_t)h * h + h) + (size_t)h * out + out;
 }
 
 // Initial state of episode 0: one thread per (env, entity).
@@ -167,32 +171,46 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     const int out_map = (net == 0 && p.dist == MSRL_DIAG_GAUSSIAN) ? OUT_GAUSS : OUT_NATURAL;
     const int gk = p.out_dim / 2;
     uint8_t* dst = st->packed + (size_t)net * L.bytes;
+    const int layers = layers_of(p);
+    const size_t hh = (size_t)p.hidden * p.hidden * esz, hb = (size_t)p.hidden * esz;
     const uint8_t* W1 = src;
     const uint8_t* b1 = W1 + (size_t)p.in_dim * p.hidden * esz;
-    const uint8_t* W2 = b1 + (size_t)p.hidden * esz;
-    const uint8_t* b2 = W2 + (size_t)p.hidden * p.hidden * esz;
-    const uint8_t* W3 = b2 + (size_t)p.hidden * esz;
+    const uint8_t* Wmid = b1 + hb;                                  // hidden layers 2 .. layers-1: W b each
+    const uint8_t* W2 = Wmid + (size_t)(layers - 2) * (hh + hb);   // the last hidden layer
+    const uint8_t* b2 = W2 + hh;
+    const uint8_t* W3 = b2 + hb;
     const uint8_t* b3 = W3 + (size_t)p.hidden * out * esz;
     // only the inputs that can be non-zero are packed (a prefix of the rows of W1)
     PackJob j1 = weight_job(W1, dst + L.w1, bf16, st->in_used, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
     j1.bias = b1;  // the bias is the input after them; the kernels feed 1 there
     j1.bias_index = st->in_used;
     jobs.job[jobs.n++] = j1;
-    // chunk block uc: kt2 layer-2 tiles of chunk uc, its bias tile, the tpc layer-3 tiles fed by
-    // chunk uc-1, the tpc layer-3 tiles fed by chunk uc
-    PackJob j2 = weight_job(W2, dst + L.chunks, bf16, p.hidden, p.hidden, L.nuc, L.kt2 + 1, IN_CHAIN, OUT_NATURAL, 0);
+    // chunk blocks of the hidden layers before the last one: kt2 tiles of the chunk and its bias tile
+    for (int l = 0; l < layers - 2; ++l) {
+      const uint8_t* Wl = Wmid + (size_t)l * (hh + hb);
+      PackJob jm = weight_job(Wl, dst + L.chunks + (size_t)l * L.nuc * L.chunk_bytes, bf16, p.hidden, p.hidden, L.nuc,
+                              L.kt2 + 1, IN_CHAIN, OUT_NATURAL, 0);
+      jm.bias = Wl + hh;
+      jm.bias_index = p.hidden;
+      jm.chunk_stride = L.chunk_tiles;
+      jobs.job[jobs.n++] = jm;
+    }
+    // chunk block uc of the last hidden layer: kt2 tiles of chunk uc, its bias tile, the tpc layer-3
+    // tiles fed by chunk uc-1, the tpc layer-3 tiles fed by chunk uc
+    uint8_t* last = dst + L.chunks + (size_t)(layers - 2) * L.nuc * L.chunk_bytes;
+    PackJob j2 = weight_job(W2, last, bf16, p.hidden, p.hidden, L.nuc, L.kt2 + 1, IN_CHAIN, OUT_NATURAL, 0);
     j2.bias = b2;
     j2.bias_index = p.hidden;
     j2.chunk_stride = L.chunk_tiles;
     jobs.job[jobs.n++] = j2;
-    PackJob j3 = weight_job(W3, dst + L.chunks, bf16, p.hidden, out, 1, L.kt2, IN_CHAIN, out_map, gk);
+    PackJob j3 = weight_job(W3, last, bf16, p.hidden, out, 1, L.kt2, IN_CHAIN, out_map, gk);
     j3.group = L.tpc;
     j3.chunk_stride = L.chunk_tiles;
     j3.slot_base = L.kt2 + 1 + L.tpc;  // own chunk's copy
     jobs.job[jobs.n++] = j3;
     if (L.nuc > 1) {
       PackJob j3b = j3;               // copy for the following chunk's stage: tiles of chunks 0 .. nuc-2
-      j3b.dst = dst + L.chunks + L.chunk_bytes;
+      j3b.dst = last + L.chunk_bytes;
       j3b.kt = L.kt2 - L.tpc;
       j3b.slot_base = L.kt2 + 1;
       jobs.job[jobs.n++] = j3b;
@@ -216,6 +234,12 @@ int check_traj(const msrl_state* st, const msrl_traj* out, bool need_gae) {
 // the compiled kernel for this state's configuration and the given phase variant, or null
 bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase, KernelEntry* out) {
   const bool bf16 = pol.dtype == MSRL_BF16;
+  // networks with more than two hidden layers have a full-rollout kernel of their own and no
+  // measurement or actor-only variants; the environment-only variant runs no network
+  if (layers_of(pol) > 2) {
+    if (phase == PHASE_ALL) phase = PHASE_DEEP;
+    else if (phase != PHASE_STEP) return false;
+  }
   for (const KernelEntry& k : all_kernels()) {
     if (k.phase != phase || k.kind != env.kind || k.hidden != pol.hidden || (k.bf16 != 0) != bf16) continue;
     if (env.kind == MSRL_ENV_PARTICLE) {
@@ -265,6 +289,7 @@ int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* param
   a.obs_in = obs_in;
   a.actions_in = actions_in;
   a.envs_per_block = st->envs_per_block;
+  a.layers = layers_of(st->pol);
   const int64_t blocks = ((int64_t)a.E + a.envs_per_block - 1) / a.envs_per_block;
   void* args[] = {&a};
   HIP_TRY(hipLaunchKernel(kernel.fn, dim3((unsigned)blocks), dim3(64 * kernel.waves), args, 0, stream));
@@ -279,7 +304,8 @@ const char* msrl_last_error(void) { return g_err; }
 
 size_t msrl_param_count(const msrl_policy_cfg* cfg) {
   if (!valid_policy(cfg)) return 0;
-  return net_params(cfg->in_dim, cfg->hidden, cfg->out_dim) + net_params(cfg->in_dim, cfg->hidden, 1);
+  const int L = layers_of(*cfg);
+  return net_params(cfg->in_dim, cfg->hidden, cfg->out_dim, L) + net_params(cfg->in_dim, cfg->hidden, 1, L);
 }
 
 size_t msrl_env_state_size(const msrl_env_cfg* cfg) {
@@ -347,7 +373,7 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   st->state_size = (int)msrl_env_state_size(env);
   // The particle observation ends in 2 (N - 1) slots that are always zero: layer 1 skips them.
   st->in_used = env->kind == MSRL_ENV_PARTICLE ? 4 * env->num_agents + 2 : policy->in_dim;
-  st->layout = net_layout(st->in_used, policy->hidden, policy->dtype == MSRL_BF16);
+  st->layout = net_layout(st->in_used, policy->hidden, policy->dtype == MSRL_BF16, layers_of(*policy));
 
   int rc = MSRL_OK;
   auto cleanup = [&](int code) {

@@ -372,6 +372,8 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
       (policy->dist == MSRL_DIAG_GAUSSIAN && policy->out_dim % 2 != 0))
     return fail(MSRL_EINVAL, "msrl_learner_init: unsupported policy configuration (hidden must be a multiple of "
                              "32, out_dim at most 32)");
+  if (policy->hidden_layers != 0 && policy->hidden_layers != 2)
+    return fail(MSRL_EUNSUPPORTED, "msrl_learner_init: the learner is built for two hidden layers");
   if (max_rows < 1) return fail(MSRL_EINVAL, "msrl_learner_init: max_rows must be positive");
   msrl_learner* L = new (std::nothrow) msrl_learner;
   if (!L) return fail(MSRL_ENOMEM, "msrl_learner_init: host allocation failed");

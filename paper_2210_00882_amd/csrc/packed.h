@@ -27,13 +27,15 @@
 // MFMA is cheaper.)  For layer 1 the index falls into the padding of the last
 // tile when there is room, for layer 2 it opens one extra tile.
 //
-// One network =
+// One network (two hidden layers) =
 //   [layer-1 tiles (uc major, kt minor), nuc * kt1 tiles, kt1 = tiles(in_used + 1)]
 //   [chunk block uc = 0 .. nuc-1], each kt2 + 1 + 2 tpc tiles:
 //       kt2 layer-2 tiles of the 32-unit chunk uc, 1 bias tile of chunk uc,
 //       tpc = kt2/nuc layer-3 tiles that consume the outputs of chunk uc-1
 //       (zeros for uc = 0), tpc layer-3 tiles that consume the outputs of chunk uc
 //   [b3: 32 floats in physical output order]
+// With more than two hidden layers, every further hidden layer contributes nuc chunk blocks of the
+// same size in front of those of the last hidden layer (layer order), with the layer-3 slots unused.
 // The kernels keep the layer-1 tiles resident in LDS and stream the chunk blocks
 // through an LDS window, one block per stage; they activate chunk uc-1 while the
 // MFMAs of chunk uc run, which is why a block carries the layer-3 tiles of the
@@ -53,6 +55,7 @@ enum OutMap : int { OUT_NATURAL = 0, OUT_GAUSS = 1 };
 struct NetLayout {
   int kt1, kt2, nuc, tpc;  // tiles per chunk in layer 1 / layer 2; chunks of 32 units; layer-3 tiles per chunk
   int chunk_tiles;         // tiles of one chunk block
+  int layers;              // hidden layers (>= 2); chunk blocks: (layers - 1) * nuc
   size_t w1;               // byte offset of the layer-1 tiles
   size_t chunks;           // byte offset of chunk block 0
   size_t chunk_bytes;      // size of one chunk block
@@ -65,17 +68,18 @@ __host__ __device__ inline int tiles_for_inputs(int n_in, bool bf16) {
 }
 
 // in_used: number of leading inputs of layer 1 that are packed (the rest are known to be zero)
-__host__ __device__ inline NetLayout net_layout(int in_used, int hidden, bool bf16) {
+__host__ __device__ inline NetLayout net_layout(int in_used, int hidden, bool bf16, int layers = 2) {
   NetLayout L;
   L.kt1 = tiles_for_inputs(in_used + 1, bf16);
   L.kt2 = tiles_for_inputs(hidden, bf16);
   L.nuc = hidden / 32;
   L.tpc = L.kt2 / L.nuc;
   L.chunk_tiles = L.kt2 + 1 + 2 * L.tpc;
+  L.layers = layers;
   L.w1 = 0;
   L.chunks = L.w1 + (size_t)L.nuc * L.kt1 * 1024;
   L.chunk_bytes = (size_t)L.chunk_tiles * 1024;
-  L.b3 = L.chunks + (size_t)L.nuc * L.chunk_bytes;
+  L.b3 = L.chunks + (size_t)(layers - 1) * L.nuc * L.chunk_bytes;
   L.bytes = (L.b3 + 32 * 4 + 1023) / 1024 * 1024;
   return L;
 }
@@ -101,7 +105,7 @@ struct PackJob {
 
 struct PackJobs {
   int n;
-  PackJob job[12];
+  PackJob job[24];
 };
 
 }  // namespace msrl

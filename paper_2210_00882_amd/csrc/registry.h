@@ -63,4 +63,9 @@ KernelEntry entry_p6_h128_f32_step();
 KernelEntry entry_p10_h256_bf16_act();
 KernelEntry entry_p10_h256_bf16_step();
 
+// more than two hidden layers
+KernelEntry entry_p3_h64_f32_deep();
+KernelEntry entry_p3_h64_bf16_deep();
+KernelEntry entry_p10_h256_bf16_deep();
+
 }  // namespace msrl

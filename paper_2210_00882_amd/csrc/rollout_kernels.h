@@ -49,6 +49,7 @@ struct RolloutArgs {
   int64_t M;
   const float* obs_in;     // PHASE_ACT: observation rows [M, D] to act on
   const void* actions_in;  // PHASE_STEP: actions [M] to apply
+  int layers;              // hidden layers of both networks (>= 2; kernels other than PHASE_DEEP take 2)
 };
 
 // Copies the layer-1 tiles and the output biases of both packed networks into LDS (once per kernel).
@@ -110,7 +111,11 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 //   PHASE_STEP  applies the caller's actions (actions_in) for T = 1: move, reward, done, reset,
 //              counters + 1; writes rewards[0], dones[0] and the observation of the new state to
 //              obs[0].  With T = 0 it only writes the observation of the current state.
-enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHASE_ACT = 4, PHASE_STEP = 5 };
+//   PHASE_DEEP  the full kernel for networks with more than two hidden layers (RolloutArgs::layers):
+//              the further hidden layers run between layer 1 and the last hidden layer, their chunk
+//              blocks coming through the same LDS window.
+enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHASE_ACT = 4, PHASE_STEP = 5,
+             PHASE_DEEP = 6 };
 // stamps: start of the step, observation rows built and stored, policy layer 1 done (after the
 // stage barrier that precedes it), policy stage s done (s < 5), same for the value network,
 // logits and values ready, sampling and move done, end of the step
@@ -137,7 +142,8 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   typedef typename Net::Op Op;
   static_assert(EPW >= 1, "a wave must hold at least one env");
-  constexpr bool FULL = PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS;
+  constexpr bool DEEP = PHASE == PHASE_DEEP;
+  constexpr bool FULL = PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS || DEEP;
   constexpr bool HAS_NETS = PHASE != PHASE_ENV && PHASE != PHASE_STEP;     // the variant runs the networks
   constexpr bool STORES_OBS = PHASE != PHASE_MLP && PHASE != PHASE_ACT;    // ... stores observation rows
   static_assert(NB == 1, "the observation staging below assumes one 32-row block per wave");
@@ -174,7 +180,8 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: lives in a scalar register
   const int n = lane & 31, h = lane >> 5;
-  const NetLayout ly = net_layout(NZ, H, BF16);
+  const int layers = DEEP ? a.layers : 2;
+  const NetLayout ly = net_layout(NZ, H, BF16, layers);
   Stream ws;
   ws.lds = s_w;
   ws.packed = a.packed;
@@ -183,6 +190,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   ws.chunk_bytes = ly.chunk_bytes;
   ws.wave = wave;
   ws.lane = lane;
+  if constexpr (DEEP) ws.stages_per_net = (layers - 1) * Stream::STAGES_PER_NET;
   if constexpr (HAS_NETS) {
 #pragma unroll
     for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
@@ -406,48 +414,150 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       for (int q = 0; q < NB; ++q) out_p[q] = out_v[q] = zero16();
     } else {
       Op h1[NB][Net::KT2 * Net::PT];
-#pragma unroll
-      for (int net = 0; net < 2; ++net) {
-        f32x16(&out)[NB] = net == 0 ? out_p : out_v;
-        // The first stage of the value network landed long ago, so its barrier can come before
-        // layer 1.  Every wave has left the previous step long since and the store path is idle
-        // (the observation stores went out at the start of the step): the collected per-row
-        // outputs of the previous step go out here.
-        if (net == 1) {
-          ws.wait_oldest();
-          if (FULL && t > 0) flush(t - 1, 0x1f);
-        }
-        Net::layer1(&s_l1[net][0] + lane, x, h1);
-        stamp(net == 0 ? CLK_P_L1 : CLK_V_L1);
-        f32x16 acc[NB];
-        {
-          const f32x16 b = bias_init(s_b3[net], h);
-#pragma unroll
-          for (int q = 0; q < NB; ++q) out[q] = b;
-        }
+      if constexpr (DEEP) {
+        const int spn = ws.stages_per_net;
 #pragma unroll 1
-        for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
-          if (sc != 0) ws.wait_oldest();
-          int next = net * Stream::STAGES_PER_NET + sc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
-          if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
-          const int nbuf = (gs + Stream::AHEAD) % NBUF;
-#pragma unroll
-          for (int c = 0; c < CPS; ++c) {
-            const u32x4* tiles = ws.tiles(gs % NBUF, c);
-            // the copies of the stage AHEAD stages later, spread over this stage's tile loops
-            auto tick = [&](int kt) {
-#pragma unroll
-              for (int i = 0; i < Stream::PER_WAVE; ++i)
-                if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
-            };
-            if (c == 0 && sc == 0)
-              Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
-            else
-              Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
-            if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
+        for (int net = 0; net < 2; ++net) {
+          f32x16(&out)[NB] = net == 0 ? out_p : out_v;
+          if (net == 1) {
+            ws.wait_oldest();
+            if (t > 0) flush(t - 1, 0x1f);
           }
-          ++gs;
-          if (sc < 5) stamp((net == 0 ? CLK_P_STAGE : CLK_V_STAGE) + sc);
+          Net::layer1(&s_l1[net][0] + lane, x, h1);
+          int sn = 0;  // stage within the network
+          auto prefetch_target = [&](int& next, int& nbuf) {
+            next = net * spn + sn + Stream::AHEAD;
+            if (next >= 2 * spn) next -= 2 * spn;
+            nbuf = (gs + Stream::AHEAD) % NBUF;
+          };
+          f32x16 acc[NB];
+          // hidden layers 2 .. layers-1: h1 <- tanh(W h1 + b), one 32-unit chunk per block
+#pragma unroll 1
+          for (int layer = 2; layer < layers; ++layer) {
+            Op hb[NB][Net::KT2 * Net::PT];
+#pragma unroll 1
+            for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
+              if (sn != 0) ws.wait_oldest();
+              int next, nbuf;
+              prefetch_target(next, nbuf);
+              Op hn[CPS][NB][Net::PC];
+#pragma unroll
+              for (int c = 0; c < CPS; ++c) {
+                const u32x4* tiles = ws.tiles(gs % NBUF, c);
+                auto tick = [&](int kt) {
+#pragma unroll
+                  for (int i = 0; i < Stream::PER_WAVE; ++i)
+                    if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
+                };
+                if (c == 0 && sc == 0)
+                  Net::template hidden_chunk<false>(tiles, h1, acc, hn[c], h, tick);
+                else
+                  Net::template hidden_chunk<true>(tiles, h1, acc, hn[c], h, tick);
+              }
+              // file the finished chunks (register indices are compile-time constants inside each branch)
+#pragma unroll
+              for (int k = 0; k < Stream::STAGES_PER_NET; ++k)
+                if (sc == k) {
+#pragma unroll
+                  for (int c = 0; c < CPS; ++c) {
+                    const int idx = k * CPS + c - 1;
+                    if (idx >= 0) {
+#pragma unroll
+                      for (int q = 0; q < NB; ++q)
+#pragma unroll
+                        for (int j = 0; j < Net::PC; ++j) hb[q][idx * Net::PC + j] = hn[c][q][j];
+                    }
+                  }
+                }
+              ++gs;
+              ++sn;
+            }
+            {
+              Op hl[NB][Net::PC];
+              Net::hidden_drain(acc, hl);
+#pragma unroll
+              for (int q = 0; q < NB; ++q)
+#pragma unroll
+                for (int j = 0; j < Net::PC; ++j) hb[q][(Net::NUC - 1) * Net::PC + j] = hl[q][j];
+            }
+#pragma unroll
+            for (int q = 0; q < NB; ++q)
+#pragma unroll
+              for (int j = 0; j < Net::KT2 * Net::PT; ++j) h1[q][j] = hb[q][j];
+          }
+          // last hidden layer and output layer
+          {
+            const f32x16 b = bias_init(s_b3[net], h);
+#pragma unroll
+            for (int q = 0; q < NB; ++q) out[q] = b;
+          }
+#pragma unroll 1
+          for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
+            if (sn != 0) ws.wait_oldest();
+            int next, nbuf;
+            prefetch_target(next, nbuf);
+#pragma unroll
+            for (int c = 0; c < CPS; ++c) {
+              const u32x4* tiles = ws.tiles(gs % NBUF, c);
+              auto tick = [&](int kt) {
+#pragma unroll
+                for (int i = 0; i < Stream::PER_WAVE; ++i)
+                  if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
+              };
+              if (c == 0 && sc == 0)
+                Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
+              else
+                Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
+              if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
+            }
+            ++gs;
+            ++sn;
+          }
+        }
+      } else {
+  #pragma unroll
+        for (int net = 0; net < 2; ++net) {
+          f32x16(&out)[NB] = net == 0 ? out_p : out_v;
+          // The first stage of the value network landed long ago, so its barrier can come before
+          // layer 1.  Every wave has left the previous step long since and the store path is idle
+          // (the observation stores went out at the start of the step): the collected per-row
+          // outputs of the previous step go out here.
+          if (net == 1) {
+            ws.wait_oldest();
+            if (FULL && t > 0) flush(t - 1, 0x1f);
+          }
+          Net::layer1(&s_l1[net][0] + lane, x, h1);
+          stamp(net == 0 ? CLK_P_L1 : CLK_V_L1);
+          f32x16 acc[NB];
+          {
+            const f32x16 b = bias_init(s_b3[net], h);
+  #pragma unroll
+            for (int q = 0; q < NB; ++q) out[q] = b;
+          }
+  #pragma unroll 1
+          for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
+            if (sc != 0) ws.wait_oldest();
+            int next = net * Stream::STAGES_PER_NET + sc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
+            if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
+            const int nbuf = (gs + Stream::AHEAD) % NBUF;
+  #pragma unroll
+            for (int c = 0; c < CPS; ++c) {
+              const u32x4* tiles = ws.tiles(gs % NBUF, c);
+              // the copies of the stage AHEAD stages later, spread over this stage's tile loops
+              auto tick = [&](int kt) {
+  #pragma unroll
+                for (int i = 0; i < Stream::PER_WAVE; ++i)
+                  if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
+              };
+              if (c == 0 && sc == 0)
+                Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
+              else
+                Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
+              if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
+            }
+            ++gs;
+            if (sc < 5) stamp((net == 0 ? CLK_P_STAGE : CLK_V_STAGE) + sc);
+          }
         }
       }
     }

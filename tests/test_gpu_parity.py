@@ -111,6 +111,53 @@ def test_particle_bf16_small():
     run_and_check(cfg, 20)
 
 
+@pytest.mark.parametrize("layers", [3, 4, 7])
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_particle_deeper_networks(layers, dtype):
+    # more than two hidden layers (the depth of the paper's evaluation networks is 7): every env and step
+    cfg = synth.particle("p3deep", 45, 3, 64, 14, 6, dtype=dtype, idx=30 + layers).with_(hidden_layers=layers)
+    tr, stats = run_and_check(cfg, 14, calls=2)
+    assert stats["rows"] == 2 * 14 * cfg.M
+
+
+def test_cfg5_networks_with_six_hidden_layers_sampled():
+    # the benchmark's env batch (reduced to 4099 envs: several workgroups and a ragged tail) with
+    # 256-unit bf16 networks of six hidden layers
+    cfg = synth.CONFIGS[5].with_(num_envs=4099, T=12, hidden_layers=6)
+    rng = np.random.default_rng(6)
+    ids = [0, 1, cfg.num_envs - 1] + sorted(rng.choice(cfg.num_envs, 5, replace=False).tolist())
+    tr, _ = run_and_check(cfg, cfg.T, env_ids=ids)
+    assert (tr["obs"][:, :, 42:] == 0).all()
+
+
+def test_deeper_networks_error_paths():
+    from paper_2210_00882_amd import binding as B
+    import torch
+    cfg = synth.particle("p3deep", 8, 3, 64, 4, 4, idx=40).with_(hidden_layers=3)
+    assert B.msrl_param_count(B.make_policy_cfg(cfg)) == cfg.param_count
+    assert B.msrl_param_count(B.make_policy_cfg(cfg.with_(hidden_layers=9))) == 0
+    assert B.msrl_param_count(B.make_policy_cfg(cfg.with_(hidden_layers=1))) == 0
+    with pytest.raises(B.MsrlError):
+        B.msrl_learner_init(B.make_policy_cfg(cfg), 64)
+    env_cfg, keep = B.make_env_cfg(cfg, None, None)
+    st = B.msrl_rollout_init(env_cfg, B.make_policy_cfg(cfg), 1)
+    try:
+        params = B.upload_params(cfg, synth.make_params(cfg))
+        obs = torch.zeros((cfg.M, cfg.obs_dim), device="cuda")
+        B.msrl_observe(st, obs)                      # no network involved: allowed
+        a = torch.zeros(cfg.M, dtype=torch.int32, device="cuda")
+        lp = torch.zeros(cfg.M, device="cuda")
+        with pytest.raises(B.MsrlError):
+            B.msrl_act(st, params, obs, a, lp, lp.clone())
+    finally:
+        B.msrl_rollout_destroy(st)
+    # a lingauss env has no kernel for more than two layers
+    c4 = synth.CONFIGS[4].with_(num_envs=4, hidden_layers=3)
+    e4, keep4 = B.make_env_cfg(c4, *synth.make_dynamics(c4))
+    with pytest.raises(B.MsrlError):
+        B.msrl_rollout_init(e4, B.make_policy_cfg(c4), 1)
+
+
 def test_cfg2_sampled():
     cfg = synth.CONFIGS[2]
     rng = np.random.default_rng(2)
