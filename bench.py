@@ -31,8 +31,8 @@ PEAK_HBM_GBS = 8000.0
 
 def mlp_flops_per_agent_step(cfg) -> int:
     """2 * MACs of the un-padded policy and value networks."""
-    d, h = cfg.obs_dim, cfg.hidden
-    return 2 * ((d * h + h * h + h * cfg.out_dim) + (d * h + h * h + h))
+    d, h, hh = cfg.obs_dim, cfg.hidden, (cfg.hidden_layers - 1) * cfg.hidden * cfg.hidden
+    return 2 * ((d * h + hh + h * cfg.out_dim) + (d * h + hh + h))
 
 
 def rollout_bytes_per_agent_step(cfg) -> int:
@@ -247,6 +247,30 @@ def main():
                                       "peak": PEAK_TFLOPS[dt_name], "unit": "TFLOP/s", "frac": tf / PEAK_TFLOPS[dt_name],
                                       "rows_per_s": rows / (ms * 1e-3)}
             del master, grad
+        except B.MsrlError:
+            pass
+
+        # the same rollout with the network depth of the paper's evaluation (seven layers = six hidden
+        # layers and the output layer), if a kernel for it is compiled
+        try:
+            deep = cfg.with_(hidden_layers=6)
+            dstate = B.msrl_rollout_init(env_cfg, B.make_policy_cfg(deep), seed)
+            dp = B.upload_params(deep, synth.make_params(deep))
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for k in range(3):
+                if k == 1:
+                    ev0.record()
+                B.msrl_rollout_step(dstate, dp, T, out)
+            ev1.record()
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1) / 2
+            B.msrl_rollout_destroy(dstate)
+            tf = mlp_flops_per_agent_step(deep) * agent_steps / (ms * 1e-3) / 1e12
+            phases["rollout_6_hidden_layers"] = {"bound": "mfma", "ms_per_launch": ms, "achieved": tf,
+                                                 "peak": PEAK_TFLOPS[dt_name], "unit": "TFLOP/s",
+                                                 "frac": tf / PEAK_TFLOPS[dt_name],
+                                                 "agent_steps_per_s": agent_steps / (ms * 1e-3)}
+            del dp
         except B.MsrlError:
             pass
 
