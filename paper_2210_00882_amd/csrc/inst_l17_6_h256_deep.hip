@@ -1,0 +1,5 @@
+// Rollout kernel for networks with more than two hidden layers (see registry.h).
+#include "registry.h"
+namespace msrl {
+MSRL_LINGAUSS_ENTRY_PHASE(entry_l17_6_h256_deep, 17, 6, 256, 4, PHASE_DEEP)
+}  // namespace msrl

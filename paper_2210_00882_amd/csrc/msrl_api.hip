@@ -78,7 +78,8 @@ std::vector<KernelEntry> all_kernels() {
           entry_p3_h64_bf16_act(), entry_p3_h64_bf16_step(),
           entry_p6_h128_f32_act(), entry_p6_h128_f32_step(),
           entry_p10_h256_bf16_act(), entry_p10_h256_bf16_step(),
-          entry_p3_h64_f32_deep(), entry_p3_h64_bf16_deep(), entry_p10_h256_bf16_deep()};
+          entry_p3_h64_f32_deep(), entry_p3_h64_bf16_deep(), entry_p10_h256_bf16_deep(),
+          entry_l17_6_h256_deep()};
 }
 
 bool valid_policy(const msrl_policy_cfg* p) {

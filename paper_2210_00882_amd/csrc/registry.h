@@ -67,5 +67,6 @@ KernelEntry entry_p10_h256_bf16_step();
 KernelEntry entry_p3_h64_f32_deep();
 KernelEntry entry_p3_h64_bf16_deep();
 KernelEntry entry_p10_h256_bf16_deep();
+KernelEntry entry_l17_6_h256_deep();
 
 }  // namespace msrl

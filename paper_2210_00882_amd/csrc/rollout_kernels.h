@@ -702,8 +702,10 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 // actions_in is float [M, K]).
 template <int D, int K, int H, int WAVES, int PHASE = PHASE_ALL>
 __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArgs a) {
-  static_assert(PHASE == PHASE_ALL || PHASE == PHASE_ACT || PHASE == PHASE_STEP, "no measurement variants here");
+  static_assert(PHASE == PHASE_ALL || PHASE == PHASE_ACT || PHASE == PHASE_STEP || PHASE == PHASE_DEEP,
+                "no measurement variants here");
   constexpr bool HAS_NETS = PHASE != PHASE_STEP;
+  constexpr bool DEEP = PHASE == PHASE_DEEP;
   constexpr int KT1 = (D + 1 + 7) / 8;  // + the constant-1 input that carries the bias
   constexpr int NR = 4 * KT1;           // state registers per lane
   constexpr int NBUF = 2, CPS = 1;
@@ -718,7 +720,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: lives in a scalar register
   const int n = lane & 31, h = lane >> 5;
-  const NetLayout ly = net_layout(D, H, false);
+  const int layers = DEEP ? a.layers : 2;
+  const NetLayout ly = net_layout(D, H, false, layers);
   Stream ws;
   ws.lds = s_w;
   ws.packed = a.packed;
@@ -727,6 +730,7 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   ws.chunk_bytes = ly.chunk_bytes;
   ws.wave = wave;
   ws.lane = lane;
+  if constexpr (DEEP) ws.stages_per_net = (layers - 1) * Stream::STAGES_PER_NET;
   if constexpr (HAS_NETS) {
 #pragma unroll
     for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
@@ -785,12 +789,56 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
         f32x16(&out)[1] = net == 0 ? out_p : out_v;
         Net::layer1(&s_l1[net][0] + lane, x, h1);
         f32x16 acc[1];
+        const int spn = ws.stages_per_net;
+        int sn = 0;  // stage within the network
+        if constexpr (DEEP) {
+          // hidden layers 2 .. layers-1 (see the particle kernel): h1 <- tanh(W h1 + b)
+#pragma unroll 1
+          for (int layer = 2; layer < layers; ++layer) {
+            float hb[1][Net::KT2 * Net::PT];
+#pragma unroll 1
+            for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
+              ws.wait_oldest();
+              int next = net * spn + sn + Stream::AHEAD;
+              if (next >= 2 * spn) next -= 2 * spn;
+              const int nbuf = (gs + Stream::AHEAD) % NBUF;
+              float hn[1][Net::PC];
+              const u32x4* tiles = ws.tiles(gs % NBUF, 0);
+              auto tick = [&](int kt) {
+#pragma unroll
+                for (int i = 0; i < Stream::PER_WAVE; ++i)
+                  if (i * Net::KT2 / Stream::PER_WAVE == kt) ws.issue_part(next, nbuf, i);
+              };
+              if (sc == 0)
+                Net::template hidden_chunk<false>(tiles, h1, acc, hn, h, tick);
+              else
+                Net::template hidden_chunk<true>(tiles, h1, acc, hn, h, tick);
+#pragma unroll
+              for (int k = 1; k < Stream::STAGES_PER_NET; ++k)
+                if (sc == k) {
+#pragma unroll
+                  for (int j = 0; j < Net::PC; ++j) hb[0][(k - 1) * Net::PC + j] = hn[0][j];
+                }
+              ++gs;
+              ++sn;
+            }
+            {
+              float hl[1][Net::PC];
+              Net::hidden_drain(acc, hl);
+#pragma unroll
+              for (int j = 0; j < Net::PC; ++j) hb[0][(Net::NUC - 1) * Net::PC + j] = hl[0][j];
+            }
+#pragma unroll
+            for (int j = 0; j < Net::KT2 * Net::PT; ++j) h1[0][j] = hb[0][j];
+          }
+        }
         out[0] = bias_init(s_b3[net], h);
 #pragma unroll 1
         for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
           ws.wait_oldest();
-          int next = net * Stream::STAGES_PER_NET + sc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
-          if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
+          int next = net * spn + sn + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
+          if (next >= 2 * spn) next -= 2 * spn;
+          ++sn;
           const int nbuf = (gs + Stream::AHEAD) % NBUF;
 #pragma unroll
           for (int c = 0; c < CPS; ++c) {

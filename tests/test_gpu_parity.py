@@ -151,11 +151,12 @@ def test_deeper_networks_error_paths():
             B.msrl_act(st, params, obs, a, lp, lp.clone())
     finally:
         B.msrl_rollout_destroy(st)
-    # a lingauss env has no kernel for more than two layers
-    c4 = synth.CONFIGS[4].with_(num_envs=4, hidden_layers=3)
-    e4, keep4 = B.make_env_cfg(c4, *synth.make_dynamics(c4))
-    with pytest.raises(B.MsrlError):
-        B.msrl_rollout_init(e4, B.make_policy_cfg(c4), 1)
+
+
+@pytest.mark.parametrize("layers", [3, 5])
+def test_lingauss_deeper_networks(layers):
+    cfg = synth.CONFIGS[4].with_(num_envs=70, T=12, episode_len=5, hidden_layers=layers)
+    run_and_check(cfg, 12, calls=2)
 
 
 def test_cfg2_sampled():
