@@ -18,7 +18,7 @@
  *   L      = mean_n(Lpi_n + c_v Lv_n - c_e H_n),   H_n = entropy of pi_theta(.|s_n)
  *
  * with the policy and value networks of msrl_ref.c (same parameter layout, same
- * bf16 rounding points in the forward pass).  In bf16 mode the derivative
+ * bf16 rounding points in the forward pass, any number of hidden layers).  In bf16 mode the derivative
  * treats every rounding as the identity (straight-through): dL/dW uses the
  * rounded layer input, dL/d(input) uses the rounded weight, nothing else is
  * rounded in the backward pass.  At rho exactly on a clip edge, or where both
@@ -46,7 +46,7 @@ typedef struct {
   int32_t in_dim, hidden, out_dim;
   int32_t bf16;
   int32_t dist;
-  int32_t hidden_layers; /* the learner is defined for two hidden layers only (0 or 2) */
+  int32_t hidden_layers; /* tanh layers in front of the output layer; 0 means 2 */
 } ref_policy_cfg;
 
 typedef struct {
@@ -56,69 +56,87 @@ typedef struct {
 
 double ref_bf16_round(double x); /* msrl_ref.c */
 size_t ref_net_param_count(int in, int H, int out);
+size_t ref_net_param_count_l(int in, int H, int out, int L);
 
 static double rnd(double x, int bf16) { return bf16 ? ref_bf16_round(x) : x; }
 
-/* Forward pass of one in-H-H-out network on one row, keeping what the backward pass needs:
- * xin (rounded input), a1, a2 (tanh outputs, unrounded), y. */
-static void net_forward(int in, int H, int out, const double* P, const double* x, int bf16,
-                        double* xin, double* a1, double* a2, double* y) {
-  const double* W1 = P;
-  const double* b1 = W1 + (size_t)in * H;
-  const double* W2 = b1 + H;
-  const double* b2 = W2 + (size_t)H * H;
-  const double* W3 = b2 + H;
-  const double* b3 = W3 + (size_t)H * out;
+/* Forward pass of one network with L tanh hidden layers of H units on one row (parameter layout
+ * and rounding points of ref_mlp_l), keeping what the backward pass needs: xin (rounded input),
+ * act[l] (tanh output of hidden layer l = 0 .. L-1, unrounded), y. */
+static void net_forward(int in, int H, int out, int L, const double* P, const double* x, int bf16,
+                        double* xin, double* act, double* y) {
   for (int i = 0; i < in; ++i) xin[i] = rnd(x[i], bf16);
+  const double* W = P;
+  const double* b = W + (size_t)in * H;
   for (int o = 0; o < H; ++o) {
     double s = 0.0;
-    for (int i = 0; i < in; ++i) s += xin[i] * rnd(W1[(size_t)i * H + o], bf16);
-    a1[o] = tanh(s + b1[o]);
+    for (int i = 0; i < in; ++i) s += xin[i] * rnd(W[(size_t)i * H + o], bf16);
+    act[o] = tanh(s + b[o]);
   }
-  for (int o = 0; o < H; ++o) {
-    double s = 0.0;
-    for (int i = 0; i < H; ++i) s += rnd(a1[i], bf16) * rnd(W2[(size_t)i * H + o], bf16);
-    a2[o] = tanh(s + b2[o]);
+  W = b + H;
+  for (int l = 1; l < L; ++l) {
+    b = W + (size_t)H * H;
+    const double* ain = act + (size_t)(l - 1) * H;
+    double* aout = act + (size_t)l * H;
+    for (int o = 0; o < H; ++o) {
+      double s = 0.0;
+      for (int i = 0; i < H; ++i) s += rnd(ain[i], bf16) * rnd(W[(size_t)i * H + o], bf16);
+      aout[o] = tanh(s + b[o]);
+    }
+    W = b + H;
   }
+  b = W + (size_t)H * out;
+  const double* alast = act + (size_t)(L - 1) * H;
   for (int o = 0; o < out; ++o) {
     double s = 0.0;
-    for (int i = 0; i < H; ++i) s += rnd(a2[i], bf16) * rnd(W3[(size_t)i * out + o], bf16);
-    y[o] = s + b3[o];
+    for (int i = 0; i < H; ++i) s += rnd(alast[i], bf16) * rnd(W[(size_t)i * out + o], bf16);
+    y[o] = s + b[o];
   }
 }
 
-/* Backward pass of one row: G += dL/dP given dy = dL/dy (straight-through across roundings). */
-static void net_backward(int in, int H, int out, const double* P, int bf16, const double* xin,
-                         const double* a1, const double* a2, const double* dy, double* G,
-                         double* d1, double* d2) {
-  const size_t oW1 = 0, ob1 = (size_t)in * H, oW2 = ob1 + H, ob2 = oW2 + (size_t)H * H,
-               oW3 = ob2 + H, ob3 = oW3 + (size_t)H * out;
-  /* layer 3 */
-  for (int o = 0; o < out; ++o) G[ob3 + o] += dy[o];
-  for (int i = 0; i < H; ++i) {
-    double da = 0.0;
-    const double in3 = rnd(a2[i], bf16);
-    for (int o = 0; o < out; ++o) {
-      G[oW3 + (size_t)i * out + o] += in3 * dy[o];
-      da += rnd(P[oW3 + (size_t)i * out + o], bf16) * dy[o];
+/* Backward pass of one row: G += dL/dP given dy = dL/dy (straight-through across roundings).
+ * delta: scratch [L, H] (dL/d pre-activation of every hidden layer). */
+static void net_backward(int in, int H, int out, int L, const double* P, int bf16, const double* xin,
+                         const double* act, const double* dy, double* G, double* delta) {
+  /* offsets of the layers' W inside the flat vector */
+  const size_t first = (size_t)in * H + H, mid = (size_t)H * H + H;
+  const size_t oWout = first + (size_t)(L - 1) * mid;
+  /* output layer */
+  {
+    const double* alast = act + (size_t)(L - 1) * H;
+    double* dl = delta + (size_t)(L - 1) * H;
+    for (int o = 0; o < out; ++o) G[oWout + (size_t)H * out + o] += dy[o];
+    for (int i = 0; i < H; ++i) {
+      double da = 0.0;
+      const double a_in = rnd(alast[i], bf16);
+      for (int o = 0; o < out; ++o) {
+        G[oWout + (size_t)i * out + o] += a_in * dy[o];
+        da += rnd(P[oWout + (size_t)i * out + o], bf16) * dy[o];
+      }
+      dl[i] = da * (1.0 - alast[i] * alast[i]);
     }
-    d2[i] = da * (1.0 - a2[i] * a2[i]); /* dL/dz2 */
   }
-  /* layer 2 */
-  for (int o = 0; o < H; ++o) G[ob2 + o] += d2[o];
-  for (int i = 0; i < H; ++i) {
-    double da = 0.0;
-    const double in2 = rnd(a1[i], bf16);
-    for (int o = 0; o < H; ++o) {
-      G[oW2 + (size_t)i * H + o] += in2 * d2[o];
-      da += rnd(P[oW2 + (size_t)i * H + o], bf16) * d2[o];
+  /* hidden layers L-1 .. 1 (inputs: the hidden layer before) */
+  for (int l = L - 1; l >= 1; --l) {
+    const size_t oW = first + (size_t)(l - 1) * mid, ob = oW + (size_t)H * H;
+    const double* ain = act + (size_t)(l - 1) * H;
+    const double* dl = delta + (size_t)l * H;
+    double* dprev = delta + (size_t)(l - 1) * H;
+    for (int o = 0; o < H; ++o) G[ob + o] += dl[o];
+    for (int i = 0; i < H; ++i) {
+      double da = 0.0;
+      const double a_in = rnd(ain[i], bf16);
+      for (int o = 0; o < H; ++o) {
+        G[oW + (size_t)i * H + o] += a_in * dl[o];
+        da += rnd(P[oW + (size_t)i * H + o], bf16) * dl[o];
+      }
+      dprev[i] = da * (1.0 - ain[i] * ain[i]);
     }
-    d1[i] = da * (1.0 - a1[i] * a1[i]); /* dL/dz1 */
   }
   /* layer 1 */
-  for (int o = 0; o < H; ++o) G[ob1 + o] += d1[o];
+  for (int o = 0; o < H; ++o) G[(size_t)in * H + o] += delta[o];
   for (int i = 0; i < in; ++i)
-    for (int o = 0; o < H; ++o) G[oW1 + (size_t)i * H + o] += xin[i] * d1[o];
+    for (int o = 0; o < H; ++o) G[(size_t)i * H + o] += xin[i] * delta[o];
 }
 
 /*
@@ -134,14 +152,13 @@ double ref_ppo_loss(const ref_policy_cfg* p, const ref_ppo_cfg* c, const double*
                     const double* logp_old, const double* adv, const double* ret, double* grad,
                     double* stats) {
   const int in = p->in_dim, H = p->hidden, O = p->out_dim, bf = p->bf16;
-  const size_t np_pi = ref_net_param_count(in, H, O), np_v = ref_net_param_count(in, H, 1);
+  const int L = p->hidden_layers > 0 ? p->hidden_layers : 2;
+  const size_t np_pi = ref_net_param_count_l(in, H, O, L), np_v = ref_net_param_count_l(in, H, 1, L);
   const double* Ppi = params;
   const double* Pv = params + np_pi;
   double* xin = (double*)malloc(sizeof(double) * (size_t)in);
-  double* a1 = (double*)malloc(sizeof(double) * (size_t)H);
-  double* a2 = (double*)malloc(sizeof(double) * (size_t)H);
-  double* d1 = (double*)malloc(sizeof(double) * (size_t)H);
-  double* d2 = (double*)malloc(sizeof(double) * (size_t)H);
+  double* act = (double*)malloc(sizeof(double) * (size_t)H * L);
+  double* delta = (double*)malloc(sizeof(double) * (size_t)H * L);
   double* y = (double*)malloc(sizeof(double) * (size_t)O);
   double* dy = (double*)malloc(sizeof(double) * (size_t)O);
   if (grad) memset(grad, 0, sizeof(double) * (np_pi + np_v));
@@ -150,7 +167,7 @@ double ref_ppo_loss(const ref_policy_cfg* p, const ref_ppo_cfg* c, const double*
   for (int64_t n = 0; n < R; ++n) {
     const double* x = obs + (size_t)n * in;
     /* ---- policy */
-    net_forward(in, H, O, Ppi, x, bf, xin, a1, a2, y);
+    net_forward(in, H, O, L, Ppi, x, bf, xin, act, y);
     double logp, ent;
     if (p->dist == REF_CATEGORICAL) {
       double mx = y[0], z = 0.0;
@@ -215,19 +232,19 @@ double ref_ppo_loss(const ref_policy_cfg* p, const ref_ppo_cfg* c, const double*
           dy[K + d] = (gl * dy[K + d] - c->ent_coef * 1.0) * invR;
         }
       }
-      net_backward(in, H, O, Ppi, bf, xin, a1, a2, dy, grad, d1, d2);
+      net_backward(in, H, O, L, Ppi, bf, xin, act, dy, grad, delta);
     }
     /* ---- value */
     double v;
-    net_forward(in, H, 1, Pv, x, bf, xin, a1, a2, &v);
+    net_forward(in, H, 1, L, Pv, x, bf, xin, act, &v);
     const double err = v - ret[n];
     s_v += err * err;
     if (grad) {
       const double dv = c->vf_coef * 2.0 * err * invR;
-      net_backward(in, H, 1, Pv, bf, xin, a1, a2, &dv, grad + np_pi, d1, d2);
+      net_backward(in, H, 1, L, Pv, bf, xin, act, &dv, grad + np_pi, delta);
     }
   }
-  free(xin); free(a1); free(a2); free(d1); free(d2); free(y); free(dy);
+  free(xin); free(act); free(delta); free(y); free(dy);
   if (stats) {
     stats[0] = s_pi * invR;
     stats[1] = s_v * invR;
@@ -259,8 +276,9 @@ double ref_ppo_update(const ref_policy_cfg* p, const ref_ppo_cfg* c, double* par
                       double* v, int64_t* step_counter, int64_t R, int iters, int minibatches,
                       const double* obs, const int32_t* actions_i, const double* actions_f,
                       const double* logp_old, const double* adv, const double* ret) {
-  const size_t np = ref_net_param_count(p->in_dim, p->hidden, p->out_dim) +
-                    ref_net_param_count(p->in_dim, p->hidden, 1);
+  const int L = p->hidden_layers > 0 ? p->hidden_layers : 2;
+  const size_t np = ref_net_param_count_l(p->in_dim, p->hidden, p->out_dim, L) +
+                    ref_net_param_count_l(p->in_dim, p->hidden, 1, L);
   double* g = (double*)malloc(sizeof(double) * np);
   const int K = p->out_dim / 2;
   const int64_t block = R / minibatches;

@@ -15,9 +15,10 @@ from oracle import ref
 LN2PI_HALF = 0.91893853320467274178
 
 
-def split_params(p, i, h, o):
+def split_params(p, i, h, o, layers=2):
     s, out = 0, []
-    for shape in ((i, h), (h,), (h, h), (h,), (h, o), (o,)):
+    shapes = [(i, h), (h,)] + [(h, h), (h,)] * (layers - 1) + [(h, o), (o,)]
+    for shape in shapes:
         n = int(np.prod(shape))
         out.append(p[s:s + n].reshape(shape))
         s += n
@@ -36,10 +37,11 @@ def torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret):
     rnd = bf16_ste if pol.bf16 else (lambda t: t)
 
     def net(p, out):
-        (W1, b1, W2, b2, W3, b3), used = split_params(p, pol.in_dim, pol.hidden, out)
-        h = torch.tanh(rnd(torch.tensor(obs, dtype=torch.float64)) @ rnd(W1) + b1)
-        h = torch.tanh(rnd(h) @ rnd(W2) + b2)
-        return rnd(h) @ rnd(W3) + b3, used
+        parts, used = split_params(p, pol.in_dim, pol.hidden, out, pol.hidden_layers)
+        h = torch.tensor(obs, dtype=torch.float64)
+        for l in range(pol.hidden_layers):
+            h = torch.tanh(rnd(h) @ rnd(parts[2 * l]) + parts[2 * l + 1])
+        return rnd(h) @ rnd(parts[-2]) + parts[-1], used
 
     y, used = net(P, pol.out_dim)
     v, _ = net(P[used:], 1)
@@ -60,10 +62,10 @@ def torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret):
     return float(loss.detach()), P.grad.numpy(), float(ent.mean().detach())
 
 
-def make_case(dist, bf16, seed, R=41, i=6, h=8, K=3):
+def make_case(dist, bf16, seed, R=41, i=6, h=8, K=3, layers=2):
     rng = np.random.default_rng(seed)
     o = 5 if dist == ref.CATEGORICAL else 2 * K
-    pol = ref.Policy(i, h, o, bf16=bf16, dist=dist)
+    pol = ref.Policy(i, h, o, bf16=bf16, dist=dist, hidden_layers=layers)
     params = rng.normal(0, 0.6, pol.param_count)
     obs = rng.normal(0, 1, (R, i))
     if dist == ref.CATEGORICAL:
@@ -95,6 +97,32 @@ def test_loss_and_gradient_against_autograd(dist, bf16):
     np.testing.assert_allclose(loss, t_loss, rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(stats[2], t_ent, rtol=1e-11)
     np.testing.assert_allclose(grad, t_grad, rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("layers", [1, 3, 5])
+@pytest.mark.parametrize("dist,bf16", [(ref.CATEGORICAL, False), (ref.CATEGORICAL, True), (ref.DIAG_GAUSSIAN, False)])
+def test_deeper_networks_against_autograd(layers, dist, bf16):
+    pol, params, obs, actions, logp_old, adv, ret = make_case(dist, bf16, 40 + layers + dist, R=23, layers=layers)
+    cfg = ref.ppo_cfg(clip=0.2, vf_coef=0.7, ent_coef=0.03)
+    loss, grad, stats = ref.ppo_loss(pol, cfg, params, obs, actions, logp_old, adv, ret)
+    t_loss, t_grad, t_ent = torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret)
+    np.testing.assert_allclose(loss, t_loss, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(stats[2], t_ent, rtol=1e-11)
+    np.testing.assert_allclose(grad, t_grad, rtol=1e-9, atol=1e-12)
+    assert np.abs(grad).min() >= 0 and np.count_nonzero(grad) > 0.9 * grad.size
+
+
+def test_deeper_network_against_finite_differences():
+    pol, params, obs, actions, logp_old, adv, ret = make_case(ref.CATEGORICAL, False, 77, R=13, layers=4)
+    cfg = ref.ppo_cfg(ent_coef=0.02)
+    _, grad, _ = ref.ppo_loss(pol, cfg, params, obs, actions, logp_old, adv, ret)
+    rng = np.random.default_rng(0)
+    for j in rng.choice(params.size, 40, replace=False):
+        e = np.zeros_like(params)
+        e[j] = 1e-6
+        lp, _, _ = ref.ppo_loss(pol, cfg, params + e, obs, actions, logp_old, adv, ret, want_grad=False)
+        lm, _, _ = ref.ppo_loss(pol, cfg, params - e, obs, actions, logp_old, adv, ret, want_grad=False)
+        np.testing.assert_allclose(grad[j], (lp - lm) / 2e-6, rtol=2e-5, atol=1e-8)
 
 
 @pytest.mark.parametrize("dist", [ref.CATEGORICAL, ref.DIAG_GAUSSIAN])
