@@ -116,9 +116,9 @@ typedef struct {
  * front of the output layer (the evaluation of the paper, section 6, uses a
  * seven-layer network).  Each layer beyond two adds one W[hidden, hidden]
  * b[hidden] pair in front of W3.  More than two layers are supported by
- * msrl_rollout_step / msrl_rollout_gae (and msrl_observe / msrl_env_step, which
- * run no network) on the particle env; msrl_act, msrl_measure_phase and the
- * learner return MSRL_EUNSUPPORTED for them.
+ * msrl_rollout_step / msrl_rollout_gae, by msrl_observe / msrl_env_step (which
+ * run no network) and by the learner; msrl_act and msrl_measure_phase return
+ * MSRL_EUNSUPPORTED for them.
  */
 typedef struct {
   int32_t in_dim, hidden, out_dim;

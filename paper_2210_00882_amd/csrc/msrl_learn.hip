@@ -20,21 +20,27 @@ namespace {
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
-// device buffers of one network's pass over a minibatch (element type = compute type)
+// device buffers of one network's pass over a minibatch (element type = compute type); index l is
+// the hidden layer, 0 .. layers-1
+constexpr int MAX_LAYERS = 8;
 struct NetBufs {
-  void *wt1, *wt2, *wt3;  // forward weights, transposed: [H, Dp], [H, H], [32, H]
-  void *wn2, *wn3;        // backward weights, as stored: [H, H], [H, 32]
-  float *b1, *b2, *b3;    // biases (b3 padded to 32)
-  void *h1, *h2;          // [Rp, H]
+  void* wt[MAX_LAYERS];   // forward weights, transposed: [H, Dp] for l = 0, [H, H] above
+  void* wn[MAX_LAYERS];   // backward weights, as stored: [H, H] for l >= 1 (inputs x outputs)
+  void *wt3, *wn3;        // output layer: [32, H] and [H, 32]
+  float* b3;              // output bias padded to 32
+  void* h[MAX_LAYERS];    // activations [Rp, H]
+  void* ht[MAX_LAYERS];   // ... unit-major [H, Rp] (in the on-chip path: the tiled layout)
+  void* dz[MAX_LAYERS];   // dL/d pre-activation [Rp, H] (l >= 1; layer 0 is only needed unit-major)
+  void* dzt[MAX_LAYERS];  // ... unit-major
   float* y;               // [Rp, 32]
-  void *dy, *dz2;         // [Rp, 32], [Rp, H]
-  void *h1t, *h2t, *dyt, *dz2t, *dz1t;  // unit-major copies: [H | 32, Rp]
+  void *dy, *dyt;         // [Rp, 32] and unit-major [32, Rp]
 };
 
 }  // namespace
 
 struct msrl_learner {
   msrl_policy_cfg pol;
+  int layers;            // hidden layers of both networks
   int64_t max_rows, Rp;  // Rp: max_rows rounded up to 128
   int Dp;                // in_dim rounded up to 16
   bool bf16;
@@ -63,7 +69,9 @@ namespace {
                   #expr, hipGetErrorString(e_));                                            \
   } while (0)
 
-size_t net_count(int in, int H, int out) { return (size_t)in * H + H + (size_t)H * H + H + (size_t)H * out + out; }
+size_t net_count(int in, int H, int out, int layers = 2) {
+  return (size_t)in * H + H + (size_t)(layers - 1) * ((size_t)H * H + H) + (size_t)H * out + out;
+}
 
 template <typename T> int dev_alloc(T** p, size_t bytes) {
   LTRY(hipMalloc((void**)p, bytes));
@@ -164,28 +172,31 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
   // observations in compute type, padded; and unit-major
   LTRY(convert_pad(s, obs, R, D, D, (E*)L->xc, Dp, Rk));
   LTRY(transpose(s, (const E*)L->xc, R, Dp, Dp, (E*)L->xt, Rp, Rk, Dp));
+  const int NL = L->layers;
+  const size_t first = (size_t)D * H + H, mid = (size_t)H * H + H;
   const float* P = params;
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
     const int O = n == 0 ? L->pol.out_dim : 1;
-    const float* W1 = P;
-    const float* b1 = W1 + (size_t)D * H;
-    const float* W2 = b1 + H;
-    const float* b2 = W2 + (size_t)H * H;
-    const float* W3 = b2 + H;
+    const float* W3 = P + first + (size_t)(NL - 1) * mid;
     const float* b3 = W3 + (size_t)H * O;
     // weights in compute type: transposed for the forward pass, as stored for the backward pass
-    LTRY(transpose(s, W1, D, H, H, (E*)b.wt1, Dp, Dp, H));
-    LTRY(transpose(s, W2, H, H, H, (E*)b.wt2, H, H, H));
+    LTRY(transpose(s, P, D, H, H, (E*)b.wt[0], Dp, Dp, H));
+    for (int l = 1; l < NL; ++l) {
+      const float* Wl = P + first + (size_t)(l - 1) * mid;
+      LTRY(transpose(s, Wl, H, H, H, (E*)b.wt[l], H, H, H));
+      LTRY(convert_pad(s, Wl, H, H, H, (E*)b.wn[l], H, H));
+    }
     LTRY(transpose(s, W3, H, O, O, (E*)b.wt3, H, H, 32));
-    LTRY(convert_pad(s, W2, H, H, H, (E*)b.wn2, H, H));
     LTRY(convert_pad(s, W3, H, O, O, (E*)b.wn3, 32, H));
     LTRY(convert_pad(s, b3, 1, O, O, b.b3, 32, 1));
-    // forward
-    // (the activations also leave unit-major, for the weight gradients)
-    LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, L->xc, Rp, Dp, b.wt1, H, Dp, b.h1, R, H, H, Dp, b1, nullptr, 0, b.h1t, Rp, Rk)));
-    LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, b.h1, Rp, H, b.wt2, H, H, b.h2, R, H, H, H, b2, nullptr, 0, b.h2t, Rp, Rk)));
-    LTRY((gemm<BF16, float, EPI_BIAS>(s, b.h2, Rp, H, b.wt3, 32, H, b.y, R, 32, 32, H, b.b3, nullptr, 0)));
+    // forward (the activations also leave unit-major, for the weight gradients)
+    LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, L->xc, Rp, Dp, b.wt[0], H, Dp, b.h[0], R, H, H, Dp, P + (size_t)D * H, nullptr, 0, b.ht[0], Rp, Rk)));
+    for (int l = 1; l < NL; ++l) {
+      const float* bl = P + first + (size_t)(l - 1) * mid + (size_t)H * H;
+      LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, b.h[l - 1], Rp, H, b.wt[l], H, H, b.h[l], R, H, H, H, bl, nullptr, 0, b.ht[l], Rp, Rk)));
+    }
+    LTRY((gemm<BF16, float, EPI_BIAS>(s, b.h[NL - 1], Rp, H, b.wt3, 32, H, b.y, R, 32, 32, H, b.b3, nullptr, 0)));
     P = b3 + O;
   }
   {
@@ -204,27 +215,30 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
     const int O = n == 0 ? L->pol.out_dim : 1;
-    float* gW1 = grad + off;
-    float* gb1 = gW1 + (size_t)D * H;
-    float* gW2 = gb1 + H;
-    float* gb2 = gW2 + (size_t)H * H;
-    float* gW3 = gb2 + H;
+    float* G = grad + off;
+    float* gW3 = G + first + (size_t)(NL - 1) * mid;
     float* gb3 = gW3 + (size_t)H * O;
-    // backward through the activations
-    // (dZ2 and dZ1 leave unit-major too, and their column sums are the bias gradients; dZ1 is not
-    // needed row-major)
-    LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, b.dz2, R, H, H, 32, nullptr, b.h2, H, b.dz2t, Rp, Rk, gb2)));
-    LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dz2, Rp, H, b.wn2, H, H, nullptr, R, H, H, H, nullptr, b.h1, H, b.dz1t, Rp, Rk, gb1)));
+    auto gW = [&](int l) { return l == 0 ? G : G + first + (size_t)(l - 1) * mid; };          // weights of hidden layer l
+    auto gb = [&](int l) { return l == 0 ? G + (size_t)D * H : gW(l) + (size_t)H * H; };       // ... its bias
+    // backward through the activations: dZ of every hidden layer leaves unit-major, its column sums
+    // are the bias gradient; the first layer's is not needed row-major
+    LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, NL > 1 ? b.dz[NL - 1] : nullptr, R, H, H, 32, nullptr,
+                                      b.h[NL - 1], H, b.dzt[NL - 1], Rp, Rk, gb(NL - 1))));
+    for (int l = NL - 2; l >= 0; --l)
+      LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dz[l + 1], Rp, H, b.wn[l + 1], H, H, l > 0 ? b.dz[l] : nullptr, R, H, H, H,
+                                        nullptr, b.h[l], H, b.dzt[l], Rp, Rk, gb(l))));
     // weight gradients: contraction over the rows, split over workgroups, fp32 atomics
     const int slices = (int)fmax(1.0, fmin(512.0, (double)(Rk / 1024)));
     if (H <= 256) {
-      LTRY((wgrad<BF16>(s, b.h2t, H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, slices)));
-      LTRY((wgrad<BF16>(s, b.h1t, H, Rp, b.dz2t, H, Rp, gW2, H, H, H, Rk, slices)));
-      LTRY((wgrad<BF16>(s, L->xt, Dp, Rp, b.dz1t, H, Rp, gW1, D, H, H, Rk, slices)));
+      LTRY((wgrad<BF16>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, slices)));
+      for (int l = NL - 1; l >= 1; --l)
+        LTRY((wgrad<BF16>(s, b.ht[l - 1], H, Rp, b.dzt[l], H, Rp, gW(l), H, H, H, Rk, slices)));
+      LTRY((wgrad<BF16>(s, L->xt, Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, slices)));
     } else {
-      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h2t, H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, nullptr, nullptr, 0, slices)));
-      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.h1t, H, Rp, b.dz2t, H, Rp, gW2, H, H, H, Rk, nullptr, nullptr, 0, slices)));
-      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, L->xt, Dp, Rp, b.dz1t, H, Rp, gW1, D, H, H, Rk, nullptr, nullptr, 0, slices)));
+      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, nullptr, nullptr, 0, slices)));
+      for (int l = NL - 1; l >= 1; --l)
+        LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.ht[l - 1], H, Rp, b.dzt[l], H, Rp, gW(l), H, H, H, Rk, nullptr, nullptr, 0, slices)));
+      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, L->xt, Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, nullptr, nullptr, 0, slices)));
     }
     {
       const int64_t per_slice = 16384;
@@ -233,7 +247,7 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
                          per_slice, gb3);
     }
     LTRY(hipGetLastError());
-    off += net_count(D, H, O);
+    off += net_count(D, H, O, NL);
   }
   return MSRL_OK;
 }
@@ -305,8 +319,8 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
     a.R = R; a.n_tiles = n_tiles; a.D = D; a.out_dim = L->pol.out_dim;
     a.obs_vec4 = (D % 4 == 0 && ((uintptr_t)obs & 15) == 0) ? 1 : 0;
     a.clip = c->clip; a.vf_coef = c->vf_coef; a.ent_coef = c->ent_coef; a.inv_R = 1.0f / (float)R;
-    a.xt = (__bf16*)L->xt; a.h1t = (__bf16*)b.h1t; a.h2t = (__bf16*)b.h2t; a.dz2t = (__bf16*)b.dz2t;
-    a.dz1t = (__bf16*)b.dz1t; a.dyt = (__bf16*)b.dyt;
+    a.xt = (__bf16*)L->xt; a.h1t = (__bf16*)b.ht[0]; a.h2t = (__bf16*)b.ht[1]; a.dz2t = (__bf16*)b.dzt[1];
+    a.dz1t = (__bf16*)b.dzt[0]; a.dyt = (__bf16*)b.dyt;
     a.stats = L->stats;
     hipError_t e = H == 64 ? launch_ppo_rows_h64(kt1, n, a, grid, s)
                  : H == 128 ? launch_ppo_rows_h128(kt1, n, a, grid, s)
@@ -338,9 +352,9 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
       else
         hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices), dim3(512), 0, s, g);
     };
-    wg(b.h2t, H, H, b.dyt, 16, O, gW3, O, gb3);
-    wg(b.h1t, H, H, b.dz2t, H, H, gW2, H, gb2);
-    wg(L->xt, 16 * kt1, D, b.dz1t, H, H, gW1, H, gb1);
+    wg(b.ht[1], H, H, b.dyt, 16, O, gW3, O, gb3);
+    wg(b.ht[0], H, H, b.dzt[1], H, H, gW2, H, gb2);
+    wg(L->xt, 16 * kt1, D, b.dzt[0], H, H, gW1, H, gb1);
     LTRY(hipGetLastError());
     off += net_count(D, H, O);
   }
@@ -372,8 +386,8 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
       (policy->dist == MSRL_DIAG_GAUSSIAN && policy->out_dim % 2 != 0))
     return fail(MSRL_EINVAL, "msrl_learner_init: unsupported policy configuration (hidden must be a multiple of "
                              "32, out_dim at most 32)");
-  if (policy->hidden_layers != 0 && policy->hidden_layers != 2)
-    return fail(MSRL_EUNSUPPORTED, "msrl_learner_init: the learner is built for two hidden layers");
+  if (policy->hidden_layers != 0 && (policy->hidden_layers < 2 || policy->hidden_layers > MAX_LAYERS))
+    return fail(MSRL_EINVAL, "msrl_learner_init: hidden_layers must be 0 (two) or 2..8");
   if (max_rows < 1) return fail(MSRL_EINVAL, "msrl_learner_init: max_rows must be positive");
   msrl_learner* L = new (std::nothrow) msrl_learner;
   if (!L) return fail(MSRL_ENOMEM, "msrl_learner_init: host allocation failed");
@@ -384,11 +398,14 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
   L->Dp = (int)round_up(policy->in_dim, 16);
   L->bf16 = policy->dtype == MSRL_BF16;
   L->esz = L->bf16 ? 2 : 4;
-  L->n_params = net_count(policy->in_dim, policy->hidden, policy->out_dim) + net_count(policy->in_dim, policy->hidden, 1);
+  L->layers = policy->hidden_layers == 0 ? 2 : policy->hidden_layers;
+  L->n_params = net_count(policy->in_dim, policy->hidden, policy->out_dim, L->layers) +
+                net_count(policy->in_dim, policy->hidden, 1, L->layers);
   const size_t H = (size_t)policy->hidden, Rp = (size_t)L->Rp, Dp = (size_t)L->Dp, e = L->esz;
   L->kt1 = policy->in_dim + 2 <= 32 ? 2 : 4;
   L->fused = L->bf16 && policy->dist == MSRL_CATEGORICAL && policy->out_dim <= 16 && policy->in_dim + 2 <= 64 &&
-             (policy->hidden == 64 || policy->hidden == 128 || policy->hidden == 256) && !getenv("MSRL_LEARNER_UNFUSED");
+             (policy->hidden == 64 || policy->hidden == 128 || policy->hidden == 256) && L->layers == 2 &&
+             !getenv("MSRL_LEARNER_UNFUSED");
   L->fly = net_layout(16 * L->kt1 - 1, policy->hidden, true);
   int rc = MSRL_OK;
   {
@@ -405,14 +422,20 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
   if (L->fused) A((void**)&L->fpacked, 4 * L->fly.bytes);
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
-    A(&b.wt1, H * Dp * e); A(&b.wt2, H * H * e); A(&b.wt3, 32 * H * e);
-    A(&b.wn2, H * H * e); A(&b.wn3, H * 32 * e);
+    for (int l = 0; l < L->layers; ++l) {
+      A(&b.wt[l], H * (l == 0 ? Dp : H) * e);
+      if (l >= 1) A(&b.wn[l], H * H * e);
+      A(&b.h[l], Rp * H * e);
+      A(&b.ht[l], H * Rp * e);
+      if (l >= 1) A(&b.dz[l], Rp * H * e);
+      A(&b.dzt[l], H * Rp * e);
+    }
+    A(&b.wt3, 32 * H * e);
+    A(&b.wn3, H * 32 * e);
     A((void**)&b.b3, 32 * sizeof(float));
-    A(&b.h1, Rp * H * e); A(&b.h2, Rp * H * e);
     A((void**)&b.y, Rp * 32 * sizeof(float));
-    A(&b.dy, Rp * 32 * e); A(&b.dz2, Rp * H * e);
-    A(&b.h1t, H * Rp * e); A(&b.h2t, H * Rp * e); A(&b.dyt, 32 * Rp * e);
-    A(&b.dz2t, H * Rp * e); A(&b.dz1t, H * Rp * e);
+    A(&b.dy, Rp * 32 * e);
+    A(&b.dyt, 32 * Rp * e);
   }
   A((void**)&L->grad, L->n_params * sizeof(float));
   A((void**)&L->stats, (8 + 5 * STAT_BINS) * sizeof(float));
@@ -431,10 +454,14 @@ void msrl_learner_destroy(msrl_learner* L) {
     if (p) (void)hipFree(p);
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
-    void* q[] = {b.wt1, b.wt2, b.wt3, b.wn2, b.wn3, b.b3, b.h1, b.h2, b.y, b.dy, b.dz2,
-                 b.h1t, b.h2t, b.dyt, b.dz2t, b.dz1t};
+    void* q[] = {b.wt3, b.wn3, b.b3, b.y, b.dy, b.dyt};
     for (void* p : q)
       if (p) (void)hipFree(p);
+    for (int l = 0; l < MAX_LAYERS; ++l) {
+      void* r[] = {b.wt[l], b.wn[l], b.h[l], b.ht[l], b.dz[l], b.dzt[l]};
+      for (void* p : r)
+        if (p) (void)hipFree(p);
+    }
   }
   delete L;
 }

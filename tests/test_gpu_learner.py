@@ -14,10 +14,14 @@ from paper_2210_00882_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def tensors_of(vec, i, h, o):
-    """(name, slice) of the six tensors of one network inside the flat vector, and its length."""
+def tensors_of(vec, i, h, o, layers=2):
+    """(name, slice) of the tensors of one network inside the flat vector, and its length."""
     out, s = [], 0
-    for name, n in (("W1", i * h), ("b1", h), ("W2", h * h), ("b2", h), ("W3", h * o), ("b3", o)):
+    names = [("W1", i * h), ("b1", h)]
+    for l in range(2, layers + 1):
+        names += [(f"W{l}", h * h), (f"b{l}", h)]
+    names += [("Wout", h * o), ("bout", o)]
+    for name, n in names:
         out.append((name, slice(s, s + n)))
         s += n
     return out, s
@@ -49,6 +53,11 @@ CASES = {
     "cfg4_gauss_f32": (synth.CONFIGS[4], 200),
     "p3_bf16": (synth.particle("p3b", 8, 3, 64, 4, 4, synth.BF16, 12), 300),
     "cfg5_bf16": (synth.CONFIGS[5], 259),
+    # more than two hidden layers (the kernels that keep the activations in device memory)
+    "cfg1_f32_4_layers": (synth.CONFIGS[1].with_(hidden_layers=4), 333),
+    "cfg4_gauss_f32_3_layers": (synth.CONFIGS[4].with_(hidden_layers=3), 200),
+    "p3_bf16_5_layers": (synth.particle("p3b", 8, 3, 64, 4, 4, synth.BF16, 12).with_(hidden_layers=5), 300),
+    "cfg5_bf16_7_layers": (synth.CONFIGS[5].with_(hidden_layers=7), 131),
     "cfg5_bf16_many_tiles": (synth.CONFIGS[5], 32 * 4 * 5 + 17),
     "p6_bf16_h128": (synth.particle("p6b", 8, 6, 128, 4, 4, synth.BF16, 12), 150),
     # the same bf16 networks through the kernels that keep the activations in device memory
@@ -86,7 +95,7 @@ def test_gradient_and_statistics_match_the_oracle(which, monkeypatch):
     assert 0.1 < st_ref[3] < 0.9
     off = 0
     for o in (cfg.out_dim, 1):
-        names, n = tensors_of(g_ref, cfg.obs_dim, cfg.hidden, o)
+        names, n = tensors_of(g_ref, cfg.obs_dim, cfg.hidden, o, cfg.hidden_layers)
         for name, sl in names:
             a, b = g[off:off + n][sl], g_ref[off:off + n][sl]
             scale = np.abs(b).max()
@@ -185,13 +194,14 @@ def test_gradient_for_tiny_and_exactly_full_workspaces(R):
     assert np.abs(g - g_ref).max() <= 1e-4 * np.abs(g_ref).max()
 
 
-def test_training_loop_improves_the_linear_gaussian_task():
+@pytest.mark.parametrize("layers", [2, 4])
+def test_training_loop_improves_the_linear_gaussian_task(layers):
     # Trainer.train of Listing 1 end to end on the device: rollout + GAE, then the learner's update,
     # repeated.  The reward -(|s|^2 + 0.01 |a|^2) punishes the large actions of the initial policy;
     # eighty iterations must at least halve the cost per step (typically it falls 10x or more; the
     # order of the float atomics in the gradients makes single runs differ).
     from paper_2210_00882_amd import train
-    cfg = synth.CONFIGS[4].with_(num_envs=2048, T=64, episode_len=64)
+    cfg = synth.CONFIGS[4].with_(num_envs=2048, T=64, episode_len=64, hidden_layers=layers)
     params = synth.make_params(cfg, bias_std=0.0, seed=5)
     _, hist = train.ppo_train(cfg, params, 80, 123, lr=1e-3, gamma=0.95, lam=0.95, dyn=synth.make_dynamics(cfg))
     first, last = np.mean(hist[:5]), np.mean(hist[-5:])

@@ -138,7 +138,7 @@ def test_deeper_networks_error_paths():
     assert B.msrl_param_count(B.make_policy_cfg(cfg.with_(hidden_layers=9))) == 0
     assert B.msrl_param_count(B.make_policy_cfg(cfg.with_(hidden_layers=1))) == 0
     with pytest.raises(B.MsrlError):
-        B.msrl_learner_init(B.make_policy_cfg(cfg), 64)
+        B.msrl_learner_init(B.make_policy_cfg(cfg.with_(hidden_layers=9)), 64)
     env_cfg, keep = B.make_env_cfg(cfg, None, None)
     st = B.msrl_rollout_init(env_cfg, B.make_policy_cfg(cfg), 1)
     try:
