@@ -166,21 +166,13 @@ __device__ __forceinline__ void dtanh_range(const f32x16& acc, const bf16x8 (&hp
     if (r >= r0 && r < r1 && pinned) pin(t[r]);
 }
 
-// The activation work of the chunk before is spread over the MFMAs of the current one in groups of
-// ROWS_EPI_GROUP tiles' worth: a group holds that many independent dependency chains, which is what
-// hides the latency of the transcendental unit when a SIMD runs a single wave.
-#ifndef MSRL_ROWS_EPI_GROUP
-#define MSRL_ROWS_EPI_GROUP 4
-#endif
-constexpr int ROWS_EPI_GROUP = MSRL_ROWS_EPI_GROUP;
-
 // One chunk block of the forward pass: acc <- layer-2 pre-activations of the block's 32 units (bias
 // included); if PIPE, `acc` holds those of the chunk before on entry: they get tanh, feed layer 3
 // (out) and are returned as operands in hprev.  tick(kt) runs once per layer-2 tile.
 template <class Net, bool PIPE, class Tick>
 __device__ __forceinline__ void fwd_chunk(const u32x4* tiles, const bf16x8 (&h1)[1][Net::KT2], f32x16& acc,
                                           f32x16& out, int h, bf16x8 (&hprev)[2], Tick&& tick) {
-  constexpr int KT2 = Net::KT2, TPC = Net::TPC, G = Net::G, LAST = Net::L3_PREV + TPC, GR = ROWS_EPI_GROUP;
+  constexpr int KT2 = Net::KT2, TPC = Net::TPC, G = Net::G, LAST = Net::L3_PREV + TPC;
   u32x4 ring[G];
 #pragma unroll
   for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
@@ -193,7 +185,7 @@ __device__ __forceinline__ void fwd_chunk(const u32x4* tiles, const bf16x8 (&h1)
     if (kt + G < LAST) ring[kt % G] = tiles[(kt + G) * 64];
     if (PIPE) pin(raw);
     acc = mma(__builtin_bit_cast(bf16x8, raw), h1[0][kt], acc);
-    if (PIPE && kt % GR == GR - 1) tanh_range(prev, t, (kt + 1 - GR) * 16 / KT2, (kt + 1) * 16 / KT2, true);
+    if (PIPE) tanh_range(prev, t, kt * 16 / KT2, (kt + 1) * 16 / KT2, true);
     tick(kt);
   }
   {
@@ -218,7 +210,7 @@ __device__ __forceinline__ void fwd_chunk(const u32x4* tiles, const bf16x8 (&h1)
 template <class Net, bool PIPE, class Tick>
 __device__ __forceinline__ void bwd_chunk(const u32x4* tiles, const bf16x8 (&dz2)[Net::KT2], f32x16& acc,
                                           const bf16x8 (&hp)[2], bf16x8 (&dprev)[2], Tick&& tick) {
-  constexpr int KT2 = Net::KT2, G = Net::G, GR = ROWS_EPI_GROUP;
+  constexpr int KT2 = Net::KT2, G = Net::G;
   u32x4 ring[G];
 #pragma unroll
   for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
@@ -231,16 +223,13 @@ __device__ __forceinline__ void bwd_chunk(const u32x4* tiles, const bf16x8 (&dz2
     if (kt + G < KT2) ring[kt % G] = tiles[(kt + G) * 64];
     if (PIPE) pin(raw);
     acc = mma(__builtin_bit_cast(bf16x8, raw), dz2[kt], acc);
-    if (PIPE && kt % GR == GR - 1) dtanh_range(prev, hp, t, (kt + 1 - GR) * 16 / KT2, (kt + 1) * 16 / KT2, true);
+    if (PIPE) dtanh_range(prev, hp, t, kt * 16 / KT2, (kt + 1) * 16 / KT2, true);
     tick(kt);
   }
   if (PIPE) to_operands<true>(t, dprev);
 }
 
-#ifndef MSRL_ROWS_WAVES
-#define MSRL_ROWS_WAVES 8
-#endif
-constexpr int ROWS_WAVES = MSRL_ROWS_WAVES;  // waves per workgroup of the row kernel = row tiles per group
+constexpr int ROWS_WAVES = 8;  // waves per workgroup of the row kernel = row tiles per group
 constexpr int ROWS_STAT_BINS = 64;  // bins per statistic in RowsArgs::stats (after 8 result slots)
 
 template <int H, int KT1, int NET, int WAVES>
