@@ -326,15 +326,15 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
       for (int kt = 0; kt < KT1; ++kt) sg.inputs16(xt, 16 * KT1, 16 * kt, x[0][kt]);
     }
 
-    // ---------------- forward.  The activations go to their tiles as they are produced and are
-    // read back from there (by the wave that wrote them) where the backward pass needs them:
-    // holding both layers in registers to the end of the tile would leave room for one wave per
-    // SIMD only.
+    // ---------------- forward.  The activations go to their tiles as they are produced.  Layer 1's
+    // stay in registers for the backward pass; layer 2's are read back from their tile (by the wave
+    // that wrote them) where dL/dz2 needs them: holding both layers to the end of the tile would
+    // leave room for one wave per SIMD only.
     __bf16* t1 = a.h1t + (size_t)tile * H * 32;
     __bf16* t2 = a.h2t + (size_t)tile * H * 32;
     f32x16 out = bias_init(s_b3, h);
+    Op h1[1][KT2];  // layer-1 activations: kept for the backward pass
     {
-      Op h1[1][KT2];
       Net::layer1(s_l1 + lane, x, h1);
       if (live) {
 #pragma unroll
@@ -472,10 +472,6 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
           const u32x4* tiles = ws.tiles(gs % NBUF, c);
           auto tick = [&](int kt) { spread(next, nbuf, c, kt); };
           const int chunk = sc * CPS + c;
-          // activations of this chunk, for the epilogue that runs during the next one: fetched now,
-          // turned into operand form after the tile loop
-          u32x4 raw[2] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
-          if (live) sg.fetch(t1, H, 32 * chunk, raw);
           Op dz[2];
           if (c == 0 && sc == 0) {
             bwd_chunk<Net, false>(tiles, dz2, acc, hp, dz, tick);
@@ -483,7 +479,14 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
             bwd_chunk<Net, true>(tiles, dz2, acc, hp, dz, tick);
             if (live) sg.chunk(tz1, H, 32 * (chunk - 1), dz);
           }
-          sg.unstage(raw, hp);
+          // activations of this chunk, for the epilogue that runs during the next one (register indices
+          // are compile-time constants inside each branch)
+#pragma unroll
+          for (int k = 0; k < SPN; ++k)
+            if (sc == k) {
+              hp[0] = h1[0][2 * (k * CPS + c)];
+              hp[1] = h1[0][2 * (k * CPS + c) + 1];
+            }
         }
         ++gs;
       }
