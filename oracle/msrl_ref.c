@@ -32,6 +32,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#define REF_ENV_TAG 2
 #define REF_ENV_PARTICLE 0
 #define REF_ENV_LINGAUSS 1
 #define REF_CATEGORICAL 0
@@ -43,6 +44,12 @@ typedef struct {
   const double* A; /* [D, D] row-major */
   const double* B; /* [D, act_dim] row-major */
   double noise_std, act_cost;
+  /* pursuit ("tag") variant of the particle env: the first num_chasers agents chase the others */
+  int32_t num_chasers, pad_;
+  double accel_c, accel_r;   /* force of an action, chasers / runners */
+  double vmax_c, vmax_r;     /* speed limit */
+  double radius_c, radius_r; /* body radius */
+  double contact_force, contact_margin;
 } ref_env_cfg;
 
 typedef struct {
@@ -332,6 +339,123 @@ void ref_particle_move(const ref_env_cfg* c, double* s, const int32_t* actions, 
   if (coll_margin) *coll_margin = mg;
 }
 
+/* ---------------------------------------------------------------- pursuit ("tag") env
+ *
+ * The workload of the paper's GPU-only experiment (section 7.4, Fig. 10) is a pursuit task of the
+ * multi-agent particle family: heterogeneous agents (chasers and runners) with a policy per role,
+ * rewards per role, and bodies that push each other apart.  The paper gives no formulas; this is a
+ * synthetic stand-in defined here:
+ *   state        as the particle env: agents (px, py, vx, vy), then landmarks (x, y); reset alike
+ *   observation  of agent i: v_i, p_i, landmark_k - p_i (all k), p_j - p_i (all j != i, index
+ *                order), v_j (all j != i): D = 4 + 2L + 4(N-1)
+ *   move         F_i = accel(role_i) * direction(action_i) + sum_{j != i} contact(i, j),
+ *                contact(i, j) = contact_force * pen(d_ij) * (p_i - p_j) / d_ij,
+ *                pen(d) = m * softplus((r_i + r_j - d) / m), m = contact_margin (a smooth
+ *                max(0, overlap)); v <- v (1 - damping) + F dt; |v| limited to vmax(role);
+ *                p <- p + v dt.  All forces use the positions before the move.
+ *   reward       on the new positions, "contact" = d_ij < r_i + r_j between a chaser and a runner:
+ *                every chaser +10 per contact of any chaser; runner j -10 per chaser in contact
+ *                with it, - 10 * sum over the two axes of max(0, |p| - 1) (leaving the arena).
+ */
+static int tag_is_chaser(const ref_env_cfg* c, int i) { return i < c->num_chasers; }
+
+void ref_tag_obs(const ref_env_cfg* c, const double* s, double* obs /* [N, D] */) {
+  const int N = c->num_agents, L = c->num_landmarks, D = c->obs_dim;
+  const double* lm = s + 4 * N;
+  for (int i = 0; i < N; ++i) {
+    double* o = obs + (size_t)i * D;
+    const double px = s[4 * i], py = s[4 * i + 1];
+    int f = 0;
+    o[f++] = s[4 * i + 2];
+    o[f++] = s[4 * i + 3];
+    o[f++] = px;
+    o[f++] = py;
+    for (int k = 0; k < L; ++k) {
+      o[f++] = lm[2 * k] - px;
+      o[f++] = lm[2 * k + 1] - py;
+    }
+    for (int j = 0; j < N; ++j) {
+      if (j == i) continue;
+      o[f++] = s[4 * j] - px;
+      o[f++] = s[4 * j + 1] - py;
+    }
+    for (int j = 0; j < N; ++j) {
+      if (j == i) continue;
+      o[f++] = s[4 * j + 2];
+      o[f++] = s[4 * j + 3];
+    }
+    while (f < D) o[f++] = 0.0;
+  }
+}
+
+static double softplus(double x) { return (x > 0.0 ? x : 0.0) + log1p(exp(-fabs(x))); }
+
+/* Move of every agent, then the per-agent rewards on the new positions.
+ * margin: smallest |distance - (r_i + r_j)| over the chaser-runner pairs after the move. */
+void ref_tag_move(const ref_env_cfg* c, double* s, const int32_t* actions, double* rewards /* [N] */,
+                  double* margin) {
+  static const double FX[5] = {0.0, 1.0, -1.0, 0.0, 0.0};
+  static const double FY[5] = {0.0, 0.0, 0.0, 1.0, -1.0};
+  const int N = c->num_agents;
+  double fx[64], fy[64];
+  for (int i = 0; i < N; ++i) {
+    const int ci = tag_is_chaser(c, i);
+    const double acc = ci ? c->accel_c : c->accel_r, ri = ci ? c->radius_c : c->radius_r;
+    fx[i] = acc * FX[actions[i]];
+    fy[i] = acc * FY[actions[i]];
+    for (int j = 0; j < N; ++j) {
+      if (j == i) continue;
+      const double rj = tag_is_chaser(c, j) ? c->radius_c : c->radius_r;
+      const double dx = s[4 * i] - s[4 * j], dy = s[4 * i + 1] - s[4 * j + 1];
+      const double d = sqrt(dx * dx + dy * dy);
+      const double pen = c->contact_margin * softplus((ri + rj - d) / c->contact_margin);
+      if (d > 0.0) {
+        fx[i] += c->contact_force * pen * dx / d;
+        fy[i] += c->contact_force * pen * dy / d;
+      }
+    }
+  }
+  for (int i = 0; i < N; ++i) {
+    double* a = s + 4 * i;
+    const double vmax = tag_is_chaser(c, i) ? c->vmax_c : c->vmax_r;
+    a[2] = a[2] * (1.0 - c->damping) + fx[i] * c->dt;
+    a[3] = a[3] * (1.0 - c->damping) + fy[i] * c->dt;
+    const double sp = sqrt(a[2] * a[2] + a[3] * a[3]);
+    if (sp > vmax) {
+      a[2] *= vmax / sp;
+      a[3] *= vmax / sp;
+    }
+    a[0] += a[2] * c->dt;
+    a[1] += a[3] * c->dt;
+  }
+  double mg = 1e30;
+  int total = 0;
+  int per_runner[64];
+  for (int j = 0; j < N; ++j) per_runner[j] = 0;
+  for (int i = 0; i < N; ++i) {
+    if (!tag_is_chaser(c, i)) continue;
+    for (int j = 0; j < N; ++j) {
+      if (tag_is_chaser(c, j)) continue;
+      const double dx = s[4 * i] - s[4 * j], dy = s[4 * i + 1] - s[4 * j + 1];
+      const double d = sqrt(dx * dx + dy * dy), dmin = c->radius_c + c->radius_r;
+      if (d < dmin) {
+        total += 1;
+        per_runner[j] += 1;
+      }
+      if (fabs(d - dmin) < mg) mg = fabs(d - dmin);
+    }
+  }
+  for (int i = 0; i < N; ++i) {
+    if (tag_is_chaser(c, i)) {
+      rewards[i] = 10.0 * total;
+    } else {
+      const double ox = fabs(s[4 * i]) - 1.0, oy = fabs(s[4 * i + 1]) - 1.0;
+      rewards[i] = -10.0 * per_runner[i] - 10.0 * ((ox > 0.0 ? ox : 0.0) + (oy > 0.0 ? oy : 0.0));
+    }
+  }
+  if (margin) *margin = mg;
+}
+
 /* ---------------------------------------------------------------- linear-Gaussian env */
 
 /* reward on (s, a) before the move; then s <- A s + B a + noise_std * eps. */
@@ -356,12 +480,12 @@ void ref_lingauss_move(const ref_env_cfg* c, double* s, const double* a, const d
 /* ---------------------------------------------------------------- env interface */
 
 int ref_env_state_size(const ref_env_cfg* c) {
-  return c->kind == REF_ENV_PARTICLE ? 4 * c->num_agents + 2 * c->num_landmarks : c->obs_dim;
+  return c->kind != REF_ENV_LINGAUSS ? 4 * c->num_agents + 2 * c->num_landmarks : c->obs_dim;
 }
 
 void ref_env_reset(const ref_env_cfg* c, uint64_t seed, uint32_t env, uint32_t episode,
                    double* s) {
-  if (c->kind == REF_ENV_PARTICLE)
+  if (c->kind != REF_ENV_LINGAUSS)
     ref_particle_reset(seed, env, episode, c->num_agents, c->num_landmarks, s);
   else
     ref_normals(seed, env, 0, episode, 1, c->obs_dim, s);
@@ -370,6 +494,8 @@ void ref_env_reset(const ref_env_cfg* c, uint64_t seed, uint32_t env, uint32_t e
 void ref_env_obs(const ref_env_cfg* c, const double* s, double* obs /* [N, D] */) {
   if (c->kind == REF_ENV_PARTICLE)
     ref_particle_obs(c->num_agents, c->num_landmarks, c->obs_dim, s, obs);
+  else if (c->kind == REF_ENV_TAG)
+    ref_tag_obs(c, s, obs);
   else
     memcpy(obs, s, sizeof(double) * (size_t)c->obs_dim);
 }
@@ -387,6 +513,14 @@ void ref_env_step(const ref_env_cfg* c, uint64_t seed, uint32_t env, int64_t g, 
     ref_lingauss_move(c, s, actions_f, eps, reward);
     if (margin) *margin = 1e30;
   }
+  *done = (uint8_t)(((g + 1) % c->episode_len) == 0);
+  if (*done) ref_env_reset(c, seed, env, (uint32_t)((g + 1) / c->episode_len), s);
+}
+
+/* The pursuit env's step: rewards per agent [N]; done and reset as above. */
+void ref_env_step_tag(const ref_env_cfg* c, uint64_t seed, uint32_t env, int64_t g, double* s,
+                      const int32_t* actions, double* rewards, uint8_t* done, double* margin) {
+  ref_tag_move(c, s, actions, rewards, margin);
   *done = (uint8_t)(((g + 1) % c->episode_len) == 0);
   if (*done) ref_env_reset(c, seed, env, (uint32_t)((g + 1) / c->episode_len), s);
 }
@@ -426,7 +560,14 @@ void ref_rollout(const ref_env_cfg* c, const ref_policy_cfg* p, uint64_t seed, i
       for (int i = 0; i < N; ++i) {
         size_t m = (size_t)e * N + i;
         double v;
-        ref_policy_value(p, params, o + (size_t)i * D, lg, &v);
+        /* pursuit env: one parameter set (policy net, value net) per role, chasers first */
+        const double* prm = params;
+        if (c->kind == REF_ENV_TAG && i >= c->num_chasers) {
+          const int Lh = p->hidden_layers > 0 ? p->hidden_layers : 2;
+          prm += ref_net_param_count_l(p->in_dim, p->hidden, p->out_dim, Lh) +
+                 ref_net_param_count_l(p->in_dim, p->hidden, 1, Lh);
+        }
+        ref_policy_value(p, prm, o + (size_t)i * D, lg, &v);
         values[(size_t)t * M + m] = v;
         if (t == T) continue;
         double lp, mg;
@@ -440,12 +581,15 @@ void ref_rollout(const ref_env_cfg* c, const ref_policy_cfg* p, uint64_t seed, i
           memcpy(actions_f + ((size_t)t * M + m) * K, af, sizeof(double) * (size_t)K);
       }
       if (t == T) continue;
-      double r;
+      double r, rr[64];
       uint8_t d;
-      ref_env_step(c, seed, (uint32_t)(env0 + e), g[e], s, ai, af, &r, &d, NULL);
+      if (c->kind == REF_ENV_TAG)
+        ref_env_step_tag(c, seed, (uint32_t)(env0 + e), g[e], s, ai, rr, &d, NULL);
+      else
+        ref_env_step(c, seed, (uint32_t)(env0 + e), g[e], s, ai, af, &r, &d, NULL);
       g[e] += 1;
       for (int i = 0; i < N; ++i) {
-        rewards[(size_t)t * M + (size_t)e * N + i] = r;
+        rewards[(size_t)t * M + (size_t)e * N + i] = c->kind == REF_ENV_TAG ? rr[i] : r;
         dones[(size_t)t * M + (size_t)e * N + i] = d;
       }
     }

@@ -19,7 +19,7 @@ _SRC = os.path.join(_HERE, "msrl_ref.c")
 _SRCS = [_SRC, os.path.join(_HERE, "msrl_learn_ref.c")]
 _LIB = os.path.join(_HERE, "libmsrl_ref.so")
 
-PARTICLE, LINGAUSS = 0, 1
+PARTICLE, LINGAUSS, TAG = 0, 1, 2
 CATEGORICAL, DIAG_GAUSSIAN = 0, 1
 
 
@@ -39,6 +39,10 @@ class EnvCfg(C.Structure):
         ("dt", C.c_double), ("damping", C.c_double), ("force", C.c_double), ("radius", C.c_double),
         ("A", C.c_void_p), ("B", C.c_void_p),
         ("noise_std", C.c_double), ("act_cost", C.c_double),
+        ("num_chasers", C.c_int32), ("pad_", C.c_int32),
+        ("accel_c", C.c_double), ("accel_r", C.c_double), ("vmax_c", C.c_double), ("vmax_r", C.c_double),
+        ("radius_c", C.c_double), ("radius_r", C.c_double),
+        ("contact_force", C.c_double), ("contact_margin", C.c_double),
     ]
 
 
@@ -77,12 +81,16 @@ class Env:
 
     def __init__(self, kind, num_agents, num_landmarks, obs_dim, act_dim, episode_len,
                  dt=0.1, damping=0.25, force=1.0, radius=0.15, A=None, B=None,
-                 noise_std=0.01, act_cost=0.01):
+                 noise_std=0.01, act_cost=0.01, num_chasers=0, accel_c=3.0, accel_r=4.0, vmax_c=1.0, vmax_r=1.3,
+                 radius_c=0.075, radius_r=0.05, contact_force=100.0, contact_margin=1e-3):
         self.A = None if A is None else _f64(A)
         self.B = None if B is None else _f64(B)
         self.c = EnvCfg(kind, num_agents, num_landmarks, obs_dim, act_dim, episode_len,
                         float(dt), float(damping), float(force), float(radius), _p(self.A), _p(self.B),
-                        float(noise_std), float(act_cost))
+                        float(noise_std), float(act_cost), num_chasers, 0, float(accel_c), float(accel_r),
+                        float(vmax_c), float(vmax_r), float(radius_c), float(radius_r), float(contact_force),
+                        float(contact_margin))
+        self.num_chasers = num_chasers
         self.kind, self.N, self.L, self.D, self.K = kind, num_agents, num_landmarks, obs_dim, act_dim
         self.episode_len = episode_len
         self.S = int(lib().ref_env_state_size(C.byref(self.c)))
@@ -220,11 +228,28 @@ def lingauss_move(env: Env, s, a, eps):
     return s, float(r.value)
 
 
+def tag_move(env: Env, s, actions):
+    """-> (new state, rewards [N], contact margin); no done/reset handling."""
+    s = _f64(s).copy()
+    a = np.ascontiguousarray(actions, dtype=np.int32)
+    assert s.size == env.S and a.size == env.N
+    r, mg = np.zeros(env.N), C.c_double()
+    lib().ref_tag_move(C.byref(env.c), _p(s), _p(a), _p(r), C.byref(mg))
+    return s, r, float(mg.value)
+
+
 def env_step(env: Env, seed, env_id, g, s, actions):
-    """One env_step incl. done and reset -> (new state, reward, done, margin)."""
+    """One env_step incl. done and reset -> (new state, reward (per agent for the pursuit env), done, margin)."""
     s = _f64(s).copy()
     assert s.size == env.S
     r, d, mg = C.c_double(), C.c_uint8(), C.c_double()
+    if env.kind == TAG:
+        a = np.ascontiguousarray(actions, dtype=np.int32)
+        assert a.size == env.N
+        rr = np.zeros(env.N)
+        lib().ref_env_step_tag(C.byref(env.c), C.c_uint64(seed), C.c_uint32(env_id), C.c_int64(int(g)),
+                               _p(s), _p(a), _p(rr), C.byref(d), C.byref(mg))
+        return s, rr, int(d.value), float(mg.value)
     if env.kind == PARTICLE:
         a = np.ascontiguousarray(actions, dtype=np.int32)
         assert a.size == env.N
@@ -251,7 +276,7 @@ def rollout(env: Env, pol: Policy, seed, env0, state, g, params, T, want_logits=
     E = state.shape[0]
     assert state.shape == (E, env.S) and g.shape == (E,)
     params = _f64(params)
-    assert params.size == pol.param_count
+    assert params.size == pol.param_count * (2 if env.kind == TAG else 1)   # one parameter set per role
     M = E * env.N
     out = {
         "obs": np.zeros((T + 1, M, env.D)),
