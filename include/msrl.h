@@ -57,7 +57,7 @@ typedef enum {
   MSRL_EUNSUPPORTED = -4  /* valid configuration with no compiled kernel */
 } msrl_status;
 
-typedef enum { MSRL_ENV_PARTICLE = 0, MSRL_ENV_LINGAUSS = 1 } msrl_env_kind;
+typedef enum { MSRL_ENV_PARTICLE = 0, MSRL_ENV_LINGAUSS = 1, MSRL_ENV_TAG = 2 } msrl_env_kind;
 typedef enum { MSRL_F32 = 0, MSRL_BF16 = 1 } msrl_dtype;
 typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
 
@@ -80,6 +80,20 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  * MSRL_ENV_LINGAUSS: num_agents = 1, num_landmarks = 0, state = observation of
  *   obs_dim floats; s' = A s + B a + noise_std * N(0,I); reward
  *   -(s.s + act_cost * a.a) on the state before the step.  Reset: s ~ N(0,I).
+ * MSRL_ENV_TAG: pursuit variant of the particle env (a stand-in for the task of
+ *   the GPU-only experiment, section 7.4): the first num_chasers agents chase
+ *   the others ("runners"), with one parameter set per role (see
+ *   msrl_policy_cfg.roles).  State and reset as MSRL_ENV_PARTICLE.  Observation
+ *   of agent i, obs_dim = 4 + 2*num_landmarks + 4*(num_agents-1):
+ *   [v, p, landmark_k - p, p_j - p (j != i ascending), v_j (j != i ascending)].
+ *   Per step, with the positions before the move: F_i = accel(role) *
+ *   direction(action) + sum_{j != i} contact_force * pen(d_ij) * (p_i - p_j) /
+ *   d_ij, pen(d) = m * log(1 + exp((r_i + r_j - d) / m)), m = contact_margin;
+ *   v <- v*(1-damping) + F*dt, |v| limited to vmax(role), p <- p + v*dt.
+ *   Rewards on the new positions ("contact": d < radius_c + radius_r between a
+ *   chaser and a runner): every chaser +10 per contact of any chaser; a runner
+ *   -10 per chaser in contact with it, -10 * (max(0,|px|-1) + max(0,|py|-1)).
+ *   Supported by msrl_rollout_step / msrl_rollout_gae (and the snapshot calls).
  *
  * An episode ends (done = 1, then reset) on every step whose counter g
  * satisfies (g+1) % episode_len == 0; g counts the env's steps since init.
@@ -97,6 +111,12 @@ typedef struct {
   const float* B;         /* lingauss: HOST [D, act_dim] row-major, copied at init */
   float noise_std;        /* lingauss */
   float act_cost;         /* lingauss */
+  /* tag */
+  int32_t num_chasers;    /* 1 .. num_agents-1 */
+  float accel_c, accel_r;    /* force of an action: chasers, runners */
+  float vmax_c, vmax_r;      /* speed limits */
+  float radius_c, radius_r;  /* body radii */
+  float contact_force, contact_margin;
 } msrl_env_cfg;
 
 /*
@@ -119,12 +139,17 @@ typedef struct {
  * msrl_rollout_step / msrl_rollout_gae, by msrl_observe / msrl_env_step (which
  * run no network) and by the learner; msrl_act and msrl_measure_phase return
  * MSRL_EUNSUPPORTED for them.
+ *
+ * roles (0 means 1; 2 for MSRL_ENV_TAG): number of parameter sets.  The
+ * parameter buffer holds them one after the other (policy then value each);
+ * role 0 are the chasers.
  */
 typedef struct {
   int32_t in_dim, hidden, out_dim;
   int32_t dtype;  /* msrl_dtype */
   int32_t dist;   /* msrl_dist */
   int32_t hidden_layers;
+  int32_t roles;
 } msrl_policy_cfg;
 
 /*

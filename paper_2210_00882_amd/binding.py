@@ -34,12 +34,15 @@ class msrl_env_cfg(C.Structure):
         ("dt", C.c_float), ("damping", C.c_float), ("force", C.c_float), ("radius", C.c_float),
         ("A", C.c_void_p), ("B", C.c_void_p),
         ("noise_std", C.c_float), ("act_cost", C.c_float),
+        ("num_chasers", C.c_int32), ("accel_c", C.c_float), ("accel_r", C.c_float),
+        ("vmax_c", C.c_float), ("vmax_r", C.c_float), ("radius_c", C.c_float), ("radius_r", C.c_float),
+        ("contact_force", C.c_float), ("contact_margin", C.c_float),
     ]
 
 
 class msrl_policy_cfg(C.Structure):
     _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("out_dim", C.c_int32),
-                ("dtype", C.c_int32), ("dist", C.c_int32), ("hidden_layers", C.c_int32)]
+                ("dtype", C.c_int32), ("dist", C.c_int32), ("hidden_layers", C.c_int32), ("roles", C.c_int32)]
 
 
 class msrl_traj(C.Structure):
@@ -151,12 +154,13 @@ def make_env_cfg(cfg, A=None, B=None):
         pa, pb = A.ctypes.data, B.ctypes.data
     e = msrl_env_cfg(cfg.kind, cfg.num_envs, cfg.num_agents, cfg.num_landmarks, cfg.obs_dim, cfg.act_dim,
                      cfg.episode_len, cfg.dt, cfg.damping, cfg.force, cfg.radius, pa, pb,
-                     cfg.noise_std, cfg.act_cost)
+                     cfg.noise_std, cfg.act_cost, cfg.num_chasers, cfg.accel_c, cfg.accel_r, cfg.vmax_c, cfg.vmax_r,
+                     cfg.radius_c, cfg.radius_r, cfg.contact_force, cfg.contact_margin)
     return e, keep
 
 
 def make_policy_cfg(cfg):
-    return msrl_policy_cfg(cfg.obs_dim, cfg.hidden, cfg.out_dim, cfg.dtype, cfg.dist, cfg.hidden_layers)
+    return msrl_policy_cfg(cfg.obs_dim, cfg.hidden, cfg.out_dim, cfg.dtype, cfg.dist, cfg.hidden_layers, cfg.roles)
 
 
 def msrl_param_count(policy_cfg: msrl_policy_cfg) -> int:

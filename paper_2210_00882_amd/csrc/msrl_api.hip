@@ -15,6 +15,7 @@
 #include "packed.h"
 #include "api_common.h"
 #include "registry.h"
+#include "tag_kernels.h"
 
 namespace msrl {
 hipError_t launch_pack(const PackJobs& jobs, hipStream_t stream);
@@ -86,8 +87,11 @@ bool valid_policy(const msrl_policy_cfg* p) {
   return p && p->in_dim >= 1 && p->hidden >= 1 && p->out_dim >= 1 &&
          (p->dtype == MSRL_F32 || p->dtype == MSRL_BF16) &&
          (p->dist == MSRL_CATEGORICAL || p->dist == MSRL_DIAG_GAUSSIAN) &&
-         (p->hidden_layers == 0 || (p->hidden_layers >= 2 && p->hidden_layers <= 8));
+         (p->hidden_layers == 0 || (p->hidden_layers >= 2 && p->hidden_layers <= 8)) &&
+         (p->roles >= 0 && p->roles <= 2);
 }
+
+int roles_of(const msrl_policy_cfg& p) { return p.roles == 0 ? 1 : p.roles; }
 
 int layers_of(const msrl_policy_cfg& p) { return p.hidden_layers == 0 ? 2 : p.hidden_layers; }
 
@@ -98,6 +102,9 @@ bool valid_env_shape(const msrl_env_cfg* e) {
            e->obs_dim == 4 + 2 * e->num_landmarks + 4 * (e->num_agents - 1);
   if (e->kind == MSRL_ENV_LINGAUSS)
     return e->num_agents == 1 && e->num_landmarks == 0 && e->act_dim >= 1;
+  if (e->kind == MSRL_ENV_TAG)
+    return e->num_landmarks >= 0 && e->num_chasers >= 1 && e->num_chasers < e->num_agents &&
+           e->obs_dim == 4 + 2 * e->num_landmarks + 4 * (e->num_agents - 1) && e->contact_margin > 0.0f;
   return false;
 }
 
@@ -167,9 +174,9 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
   PackJobs jobs;
   jobs.n = 0;
   const uint8_t* src = (const uint8_t*)params;
-  for (int net = 0; net < 2; ++net) {
-    const int out = net == 0 ? p.out_dim : 1;
-    const int out_map = (net == 0 && p.dist == MSRL_DIAG_GAUSSIAN) ? OUT_GAUSS : OUT_NATURAL;
+  for (int net = 0; net < 2 * roles_of(p); ++net) {  // per role: policy, value
+    const int out = net % 2 == 0 ? p.out_dim : 1;
+    const int out_map = (net % 2 == 0 && p.dist == MSRL_DIAG_GAUSSIAN) ? OUT_GAUSS : OUT_NATURAL;
     const int gk = p.out_dim / 2;
     uint8_t* dst = st->packed + (size_t)net * L.bytes;
     const int layers = layers_of(p);
@@ -297,6 +304,40 @@ int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* param
   return MSRL_OK;
 }
 
+// the pursuit env has a kernel family of its own (tag_kernels.h)
+int enqueue_tag(msrl_state* st, const void* params, int32_t T, msrl_traj* out, hipStream_t stream) {
+  int rc = pack_params(st, params, stream);
+  if (rc != MSRL_OK) return rc;
+  const msrl_env_cfg& e = st->env;
+  TagArgs a;
+  memset(&a, 0, sizeof(a));
+  a.env_state = st->env_state;
+  a.g = st->g;
+  a.packed = st->packed;
+  a.E = e.num_envs;
+  a.T = T;
+  a.ep = e.episode_len;
+  a.dt = e.dt;
+  a.keep = 1.0f - e.damping;
+  a.accel[0] = e.accel_c; a.accel[1] = e.accel_r;
+  a.vmax[0] = e.vmax_c; a.vmax[1] = e.vmax_r;
+  a.rad[0] = e.radius_c; a.rad[1] = e.radius_r;
+  a.cforce = e.contact_force;
+  a.cmargin = e.contact_margin;
+  a.seed_lo = (uint32_t)st->seed;
+  a.seed_hi = (uint32_t)(st->seed >> 32);
+  a.obs = out->obs;
+  a.actions = (int32_t*)out->actions;
+  a.logp = out->logp;
+  a.rewards = out->rewards;
+  a.dones = out->dones;
+  a.values = out->values;
+  a.logits = out->logits;
+  a.M = (int64_t)e.num_envs * e.num_agents;
+  HIP_TRY(launch_tag_rollout(e.num_chasers, e.num_agents - e.num_chasers, e.num_landmarks, st->pol.hidden, a, stream));
+  return MSRL_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -306,12 +347,13 @@ const char* msrl_last_error(void) { return g_err; }
 size_t msrl_param_count(const msrl_policy_cfg* cfg) {
   if (!valid_policy(cfg)) return 0;
   const int L = layers_of(*cfg);
-  return net_params(cfg->in_dim, cfg->hidden, cfg->out_dim, L) + net_params(cfg->in_dim, cfg->hidden, 1, L);
+  return (size_t)roles_of(*cfg) *
+         (net_params(cfg->in_dim, cfg->hidden, cfg->out_dim, L) + net_params(cfg->in_dim, cfg->hidden, 1, L));
 }
 
 size_t msrl_env_state_size(const msrl_env_cfg* cfg) {
   if (!valid_env_shape(cfg)) return 0;
-  return cfg->kind == MSRL_ENV_PARTICLE ? (size_t)4 * cfg->num_agents + 2 * cfg->num_landmarks
+  return cfg->kind != MSRL_ENV_LINGAUSS ? (size_t)4 * cfg->num_agents + 2 * cfg->num_landmarks
                                         : (size_t)cfg->obs_dim;
 }
 
@@ -326,9 +368,11 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   if (!valid_policy(policy)) return fail(MSRL_EINVAL, "msrl_rollout_init: invalid policy configuration");
   if (policy->in_dim != env->obs_dim)
     return fail(MSRL_EINVAL, "msrl_rollout_init: policy in_dim %d != obs_dim %d", policy->in_dim, env->obs_dim);
-  if (env->kind == MSRL_ENV_PARTICLE) {
+  if (roles_of(*policy) != (env->kind == MSRL_ENV_TAG ? 2 : 1))
+    return fail(MSRL_EINVAL, "msrl_rollout_init: the pursuit env takes two parameter sets (roles = 2), the others one");
+  if (env->kind == MSRL_ENV_PARTICLE || env->kind == MSRL_ENV_TAG) {
     if (policy->dist != MSRL_CATEGORICAL || policy->out_dim != 5)
-      return fail(MSRL_EINVAL, "msrl_rollout_init: the particle env needs a categorical policy with out_dim 5");
+      return fail(MSRL_EINVAL, "msrl_rollout_init: the particle envs need a categorical policy with out_dim 5");
   } else {
     if (policy->dist != MSRL_DIAG_GAUSSIAN || policy->out_dim != 2 * env->act_dim)
       return fail(MSRL_EINVAL, "msrl_rollout_init: the lingauss env needs a Gaussian policy with out_dim 2*act_dim");
@@ -336,7 +380,14 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   }
   // kernel selection
   KernelEntry found;
-  const bool ok = find_kernel(*env, *policy, PHASE_ALL, &found);
+  memset(&found, 0, sizeof(found));
+  found.envs_per_wave = 32;
+  found.waves = 1;
+  const bool ok = env->kind == MSRL_ENV_TAG
+                      ? policy->dtype == MSRL_BF16 && layers_of(*policy) == 2 &&
+                            tag_rollout_compiled(env->num_chasers, env->num_agents - env->num_chasers,
+                                                 env->num_landmarks, policy->hidden)
+                      : find_kernel(*env, *policy, PHASE_ALL, &found);
   if (!ok)
     return fail(MSRL_EUNSUPPORTED,
                 "msrl_rollout_init: no kernel compiled for kind %d, agents %d, landmarks %d, obs_dim %d, "
@@ -374,6 +425,7 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   st->state_size = (int)msrl_env_state_size(env);
   // The particle observation ends in 2 (N - 1) slots that are always zero: layer 1 skips them.
   st->in_used = env->kind == MSRL_ENV_PARTICLE ? 4 * env->num_agents + 2 : policy->in_dim;
+  const int n_nets = 2 * roles_of(*policy);
   st->layout = net_layout(st->in_used, policy->hidden, policy->dtype == MSRL_BF16, layers_of(*policy));
 
   int rc = MSRL_OK;
@@ -395,8 +447,8 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   const size_t E = (size_t)env->num_envs;
   INIT_TRY(hipMalloc((void**)&st->env_state, E * st->state_size * sizeof(float)));
   INIT_TRY(hipMalloc((void**)&st->g, E * sizeof(int64_t)));
-  INIT_TRY(hipMalloc((void**)&st->packed, 2 * st->layout.bytes));
-  INIT_TRY(hipMemset(st->packed, 0, 2 * st->layout.bytes));
+  INIT_TRY(hipMalloc((void**)&st->packed, n_nets * st->layout.bytes));
+  INIT_TRY(hipMemset(st->packed, 0, n_nets * st->layout.bytes));
   if (env->kind == MSRL_ENV_LINGAUSS) {
     const int D = env->obs_dim, K = env->act_dim;
     const int ktA = tiles_for_inputs(D + 1, false), ktB = tiles_for_inputs(K, false);  // as the kernel counts them
@@ -414,11 +466,12 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
     INIT_TRY(launch_pack(jobs, nullptr));
   }
   {
-    const int64_t items = env->kind == MSRL_ENV_PARTICLE
+    const int64_t items = env->kind != MSRL_ENV_LINGAUSS
                               ? (int64_t)E * (env->num_agents + env->num_landmarks)
                               : (int64_t)E * ((env->obs_dim + 3) / 4);
+    // (the pursuit env starts an episode like the particle env)
     hipLaunchKernelGGL(init_state_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, nullptr,
-                       env->kind, env->num_envs, env->num_agents, env->num_landmarks, env->obs_dim,
+                       env->kind == MSRL_ENV_TAG ? (int)MSRL_ENV_PARTICLE : env->kind, env->num_envs, env->num_agents, env->num_landmarks, env->obs_dim,
                        (uint32_t)seed, (uint32_t)(seed >> 32), st->env_state, st->g);
     INIT_TRY(hipGetLastError());
     INIT_TRY(hipDeviceSynchronize());
@@ -443,6 +496,7 @@ int msrl_rollout_step(msrl_state* st, const void* params, int32_t T, msrl_traj* 
   if (T <= 0) return fail(MSRL_EINVAL, "msrl_rollout_step: T must be positive (got %d)", T);
   int rc = check_traj(st, out, false);
   if (rc != MSRL_OK) return rc;
+  if (st->env.kind == MSRL_ENV_TAG) return enqueue_tag(st, params, T, out, (hipStream_t)hip_stream);
   return enqueue_rollout(st, st->kernel, params, T, out, (hipStream_t)hip_stream);
 }
 
@@ -461,7 +515,8 @@ int msrl_rollout_gae(msrl_state* st, const void* params, int32_t T, float gamma,
   if (T <= 0) return fail(MSRL_EINVAL, "msrl_rollout_gae: T must be positive (got %d)", T);
   int rc = check_traj(st, out, true);
   if (rc != MSRL_OK) return rc;
-  rc = enqueue_rollout(st, st->kernel, params, T, out, (hipStream_t)hip_stream);
+  rc = st->env.kind == MSRL_ENV_TAG ? enqueue_tag(st, params, T, out, (hipStream_t)hip_stream)
+                                    : enqueue_rollout(st, st->kernel, params, T, out, (hipStream_t)hip_stream);
   if (rc != MSRL_OK) return rc;
   const int64_t M = (int64_t)st->env.num_envs * st->env.num_agents;
   HIP_TRY(launch_gae(out->rewards, out->values, out->dones, T, M, gamma, lambda, out->adv, out->ret,

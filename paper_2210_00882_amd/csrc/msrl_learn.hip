@@ -388,6 +388,8 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
                              "32, out_dim at most 32)");
   if (policy->hidden_layers != 0 && (policy->hidden_layers < 2 || policy->hidden_layers > MAX_LAYERS))
     return fail(MSRL_EINVAL, "msrl_learner_init: hidden_layers must be 0 (two) or 2..8");
+  if (policy->roles > 1)
+    return fail(MSRL_EINVAL, "msrl_learner_init: a learner holds one parameter set; create one per role");
   if (max_rows < 1) return fail(MSRL_EINVAL, "msrl_learner_init: max_rows must be positive");
   msrl_learner* L = new (std::nothrow) msrl_learner;
   if (!L) return fail(MSRL_ENOMEM, "msrl_learner_init: host allocation failed");

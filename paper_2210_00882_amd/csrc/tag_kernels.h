@@ -1,0 +1,256 @@
+// Fused actor + environment rollout for the pursuit ("tag") env: heterogeneous agents with one
+// parameter set per role (interface header, MSRL_ENV_TAG; the task of the paper's GPU-only
+// experiment, section 7.4, as a synthetic stand-in).
+//
+// Layout: a workgroup owns 32 envs and has one wave per agent slot; lane n of every wave is env n,
+// so the 32 rows of a wave's MFMA tile all have the same role and use the same weights.  The
+// networks are small (bf16, 64 units), so the four of them (chasers' and runners' policy and
+// value) stay resident in LDS for the whole kernel: no weight streaming, and the only barriers are
+// those of the env step, where the agents of an env (one per wave) exchange positions through LDS.
+// The MLP itself is the chained MFMA form of mlp.h, reading its tiles from the resident images.
+#pragma once
+#include "rollout_kernels.h"
+
+namespace msrl {
+
+struct TagArgs {
+  float* env_state;       // [E, 4N + 2L]
+  int64_t* g;             // [E]
+  const uint8_t* packed;  // four packed networks (packed.h): role 0 policy, value, role 1 policy, value
+  int E, T, ep;
+  float dt, keep;
+  float accel[2], vmax[2], rad[2];  // per role: 0 chasers, 1 runners
+  float cforce, cmargin;
+  uint32_t seed_lo, seed_hi;
+  float* obs;
+  int32_t* actions;
+  float* logp;
+  float* rewards;
+  uint8_t* dones;
+  float* values;
+  float* logits;  // may be null
+  int64_t M;
+};
+
+template <int NC, int NR, int L, int H>
+__global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) {
+  constexpr int N = NC + NR;
+  constexpr int D = 4 + 2 * L + 4 * (N - 1);
+  constexpr int S = 4 * N + 2 * L;
+  constexpr int KT1 = (D + 1 + 15) / 16;  // + the constant-1 input that carries the bias
+  typedef Mlp<H, true, 1, KT1> Net;
+  typedef typename Net::Op Op;
+  constexpr int NET_TILES = Net::L1_TILES + Net::NUC * Net::CHUNK_TILES;
+  static_assert(L <= N && N <= 16, "a landmark is handled by the wave of the agent with its index");
+
+  __shared__ __attribute__((aligned(16))) u32x4 s_net[4][NET_TILES * 64];
+  __shared__ __attribute__((aligned(16))) float s_b3[4][32];
+  __shared__ float2 s_p[32][N], s_v[32][N], s_lm[32][L > 0 ? L : 1];
+  __shared__ float s_cnt[32][N];
+
+  const int lane = threadIdx.x & 63;
+  const int j = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // agent slot of this wave
+  const int n = lane & 31, h = lane >> 5;
+  const int role = j < NC ? 0 : 1;
+  const NetLayout ly = net_layout(D, H, true);
+  for (int net = 0; net < 4; ++net) {
+    const u32x4* src = (const u32x4*)(a.packed + (size_t)net * ly.bytes + ly.w1);
+    for (int i = threadIdx.x; i < NET_TILES * 64; i += blockDim.x) s_net[net][i] = src[i];
+    if (threadIdx.x < 32)
+      s_b3[net][threadIdx.x] = *(const float*)(a.packed + (size_t)net * ly.bytes + ly.b3 + threadIdx.x * 4);
+  }
+
+  const int64_t env64 = (int64_t)blockIdx.x * 32 + n;
+  const bool valid = env64 < a.E;
+  const uint32_t env = (uint32_t)(valid ? env64 : a.E - 1);
+  const float* es = a.env_state + (size_t)env * S;
+  float2 p = make_float2(es[4 * j], es[4 * j + 1]);
+  float2 v = make_float2(es[4 * j + 2], es[4 * j + 3]);
+  const int64_t g64 = a.g[env];
+  uint32_t g32 = (uint32_t)g64;
+  int tau = (int)(g64 % a.ep);
+  uint32_t episode = (uint32_t)(g64 / a.ep);
+  if (h == 0) {
+    s_p[n][j] = p;
+    s_v[n][j] = v;
+    if (j < L) s_lm[n][j] = make_float2(es[4 * N + 2 * j], es[4 * N + 2 * j + 1]);
+  }
+  const float my_rad = a.rad[role];
+
+  for (int t = 0; t <= a.T; ++t) {
+    __syncthreads();  // the positions of this step are in LDS
+    // ---------------- observation row of (env n, agent j)
+    auto feature = [&](int idx) -> float {
+      if (idx >= D) return idx == D ? 1.0f : 0.0f;  // input D carries the bias
+      if (idx < 4) return idx == 0 ? v.x : idx == 1 ? v.y : idx == 2 ? p.x : p.y;
+      int q = (idx - 4) >> 1;  // pair index behind the own state
+      const int c = idx & 1;
+      if (q < L) {
+        const float2 lm = s_lm[n][min(q, L > 0 ? L - 1 : 0)];
+        return c ? lm.y - p.y : lm.x - p.x;
+      }
+      q -= L;
+      const bool vel = q >= N - 1;
+      if (vel) q -= N - 1;
+      const int o = q + (q >= j ? 1 : 0);  // the q-th other agent
+      const float2 w = vel ? s_v[n][o] : s_p[n][o];
+      return vel ? (c ? w.y : w.x) : (c ? w.y - p.y : w.x - p.x);
+    };
+    Op x[1][KT1];
+#pragma unroll
+    for (int kt = 0; kt < KT1; ++kt) {
+      f32x8 f;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) f[s] = feature(16 * kt + 8 * h + s);
+      if (valid) {
+        float* dst = a.obs + ((size_t)t * a.M + (size_t)env * N + j) * D + 16 * kt + 8 * h;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+          if (16 * kt + 8 * h + s < D) dst[s] = f[s];
+      }
+      x[0][kt] = __builtin_convertvector(f, bf16x8);
+    }
+
+    // ---------------- networks of this wave's role, from the resident images
+    f32x16 out_p[1], out_v[1];
+#pragma unroll
+    for (int net = 0; net < 2; ++net) {
+      f32x16(&out)[1] = net == 0 ? out_p : out_v;
+      const u32x4* base = &s_net[2 * role + net][0] + lane;
+      Op h1[1][Net::KT2];
+      Net::layer1(base, x, h1);
+      out[0] = bias_init(s_b3[2 * role + net], h);
+      f32x16 acc[1];
+      auto nothing = [](int) {};
+#pragma unroll
+      for (int c = 0; c < Net::NUC; ++c) {
+        const u32x4* tiles = base + (Net::L1_TILES + c * Net::CHUNK_TILES) * 64;
+        if (c == 0)
+          Net::template layer2_chunk<false>(tiles, h1, acc, out, h, nothing);
+        else
+          Net::template layer2_chunk<true>(tiles, h1, acc, out, h, nothing);
+        if (c == Net::NUC - 1) Net::layer2_drain(tiles, acc, out);
+      }
+    }
+    const size_t o = (size_t)t * a.M + (size_t)env * N + j;
+    if (valid && h == 0) a.values[o] = out_v[0][0];
+    if (t == a.T) break;
+
+    // ---------------- sampling
+    float l[5];
+    l[0] = out_p[0][0];
+    l[1] = out_p[0][1];
+    l[2] = out_p[0][2];
+    l[3] = out_p[0][3];
+    l[4] = __shfl_xor(out_p[0][0], 32);  // logit 4 sits in register 0 of the partner lane
+    const Words4 w = draw(a.seed_lo, a.seed_hi, env, (uint32_t)j, g32, 0, 0);
+    float lp;
+    int act;
+    sample_categorical5(l, u01(w.w[0]), act, lp);
+    act = __shfl(act, n);  // the h = 0 lane of the row decides
+    if (valid && h == 0) {
+      a.actions[o] = act;
+      a.logp[o] = lp;
+      if (a.logits) {
+#pragma unroll
+        for (int k = 0; k < 5; ++k) a.logits[o * 5 + k] = l[k];
+      }
+    }
+
+    // ---------------- move: action force and contact forces, from the positions before the move
+    float fx = a.accel[role] * ((act == 1 ? 1.0f : 0.0f) - (act == 2 ? 1.0f : 0.0f));
+    float fy = a.accel[role] * ((act == 3 ? 1.0f : 0.0f) - (act == 4 ? 1.0f : 0.0f));
+#pragma unroll
+    for (int q = 0; q < N; ++q) {
+      if (q == j) continue;  // uniform
+      const float2 po = s_p[n][q];
+      const float dx = p.x - po.x, dy = p.y - po.y;
+      const float d = sqrtf(dx * dx + dy * dy);
+      const float z = (my_rad + a.rad[q < NC ? 0 : 1] - d) / a.cmargin;
+      const float pen = a.cmargin * (fmaxf(z, 0.0f) + log1pf(expf(-fabsf(z))));
+      if (d > 0.0f) {
+        fx += a.cforce * pen * dx / d;
+        fy += a.cforce * pen * dy / d;
+      }
+    }
+    v.x = v.x * a.keep + fx * a.dt;
+    v.y = v.y * a.keep + fy * a.dt;
+    const float sp = sqrtf(v.x * v.x + v.y * v.y);
+    if (sp > a.vmax[role]) {
+      v.x *= a.vmax[role] / sp;
+      v.y *= a.vmax[role] / sp;
+    }
+    p.x += v.x * a.dt;
+    p.y += v.y * a.dt;
+    __syncthreads();  // every wave has read the old positions
+    if (h == 0) {
+      s_p[n][j] = p;
+      s_v[n][j] = v;
+    }
+    __syncthreads();
+
+    // ---------------- rewards on the new positions: contacts between chasers and runners
+    float cnt = 0.0f;
+    const float dmin = a.rad[0] + a.rad[1];
+#pragma unroll
+    for (int q = 0; q < N; ++q) {
+      if ((q < NC) == (j < NC)) continue;  // uniform: only the other role
+      const float2 po = s_p[n][q];
+      const float dx = p.x - po.x, dy = p.y - po.y;
+      cnt += sqrtf(dx * dx + dy * dy) < dmin ? 1.0f : 0.0f;
+    }
+    if (h == 0) s_cnt[n][j] = cnt;
+    __syncthreads();
+    float rew;
+    if (role == 0) {
+      float total = 0.0f;
+#pragma unroll
+      for (int q = 0; q < NC; ++q) total += s_cnt[n][q];
+      rew = 10.0f * total;
+    } else {
+      rew = -10.0f * cnt - 10.0f * (fmaxf(fabsf(p.x) - 1.0f, 0.0f) + fmaxf(fabsf(p.y) - 1.0f, 0.0f));
+    }
+    const bool done = tau + 1 == a.ep;
+    if (valid && h == 0) {
+      a.rewards[o] = rew;
+      a.dones[o] = done ? 1 : 0;
+    }
+    g32 += 1;
+    tau = done ? 0 : tau + 1;
+    if (done) {  // uniform over the workgroup only if all envs share the phase: handled per lane
+      episode += 1;
+      const Words4 wa = draw(a.seed_lo, a.seed_hi, env, (uint32_t)j, episode, 1, 0);
+      p = make_float2(2.0f * u01(wa.w[0]) - 1.0f, 2.0f * u01(wa.w[1]) - 1.0f);
+      v = make_float2(0.0f, 0.0f);
+      if (h == 0) {
+        s_p[n][j] = p;
+        s_v[n][j] = v;
+        if (j < L) {
+          const Words4 wl = draw(a.seed_lo, a.seed_hi, env, (uint32_t)(N + j), episode, 1, 0);
+          s_lm[n][j] = make_float2(2.0f * u01(wl.w[0]) - 1.0f, 2.0f * u01(wl.w[1]) - 1.0f);
+        }
+      }
+    }
+  }
+
+  // ---------------- write the env state back
+  if (valid && h == 0) {
+    float* eo = a.env_state + (size_t)env * S;
+    eo[4 * j] = p.x;
+    eo[4 * j + 1] = p.y;
+    eo[4 * j + 2] = v.x;
+    eo[4 * j + 3] = v.y;
+    if (j < L) {
+      const float2 lm = s_lm[n][j];
+      eo[4 * N + 2 * j] = lm.x;
+      eo[4 * N + 2 * j + 1] = lm.y;
+    }
+    if (j == 0) a.g[env] = g64 + a.T;
+  }
+}
+
+// launcher of the compiled instances; returns hipErrorInvalidValue when no instance matches
+hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, const TagArgs& a, hipStream_t stream);
+bool tag_rollout_compiled(int nc, int nr, int landmarks, int hidden);
+
+}  // namespace msrl

@@ -15,7 +15,7 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-PARTICLE, LINGAUSS = 0, 1
+PARTICLE, LINGAUSS, TAG = 0, 1, 2
 F32, BF16 = 0, 1
 CATEGORICAL, DIAG_GAUSSIAN = 0, 1
 
@@ -46,6 +46,16 @@ class Config:
     env_seed: int = 0
     param_seed: int = 0
     hidden_layers: int = 2   # tanh layers of `hidden` units in front of the output layer
+    # pursuit ("tag") env: the first num_chasers agents chase the others; one parameter set per role
+    num_chasers: int = 0
+    accel_c: float = 3.0
+    accel_r: float = 4.0
+    vmax_c: float = 1.0
+    vmax_r: float = 1.3
+    radius_c: float = 0.075
+    radius_r: float = 0.05
+    contact_force: float = 100.0
+    contact_margin: float = 1e-3
     extra: dict = field(default_factory=dict)
 
     @property
@@ -53,15 +63,19 @@ class Config:
         return self.num_envs * self.num_agents
 
     @property
+    def roles(self) -> int:
+        return 2 if self.kind == TAG else 1
+
+    @property
     def env_state_size(self) -> int:
-        if self.kind == PARTICLE:
+        if self.kind != LINGAUSS:
             return 4 * self.num_agents + 2 * self.num_landmarks
         return self.obs_dim
 
     @property
     def param_count(self) -> int:
-        return net_param_count(self.obs_dim, self.hidden, self.out_dim, self.hidden_layers) + \
-            net_param_count(self.obs_dim, self.hidden, 1, self.hidden_layers)
+        return self.roles * (net_param_count(self.obs_dim, self.hidden, self.out_dim, self.hidden_layers) +
+                             net_param_count(self.obs_dim, self.hidden, 1, self.hidden_layers))
 
     def with_(self, **kw) -> "Config":
         d = dict(self.__dict__)
@@ -77,6 +91,14 @@ def particle(name, E, N, H, T, ep, dtype=F32, idx=0) -> Config:
     return Config(name=name, kind=PARTICLE, num_envs=E, num_agents=N, num_landmarks=N,
                   obs_dim=6 * N, act_dim=1, hidden=H, out_dim=5, dtype=dtype, dist=CATEGORICAL,
                   T=T, episode_len=ep, env_seed=0x5EED0000 + idx, param_seed=1000 + idx)
+
+
+def tag(name, E, NC, NR, L, H, T, ep, dtype=BF16, idx=0) -> Config:
+    """Pursuit env: NC chasers, NR runners, L landmarks; observation 4 + 2L + 4(N-1) wide."""
+    N = NC + NR
+    return Config(name=name, kind=TAG, num_envs=E, num_agents=N, num_landmarks=L,
+                  obs_dim=4 + 2 * L + 4 * (N - 1), act_dim=1, hidden=H, out_dim=5, dtype=dtype, dist=CATEGORICAL,
+                  T=T, episode_len=ep, env_seed=0x5EED0000 + idx, param_seed=1000 + idx, num_chasers=NC)
 
 
 def lingauss(name, E, S, K, H, T, ep, idx=0) -> Config:
@@ -101,7 +123,7 @@ def make_params(cfg: Config, bias_std: float = 0.0, seed: int | None = None) -> 
     value is rounded to a bfloat16-representable float32."""
     rng = np.random.default_rng(cfg.param_seed if seed is None else seed)
     parts = []
-    for out in (cfg.out_dim, 1):
+    for out in (cfg.out_dim, 1) * cfg.roles:
         dims = [cfg.obs_dim] + [cfg.hidden] * cfg.hidden_layers + [out]
         for fan_in, fan_out in zip(dims[:-1], dims[1:]):
             parts.append((rng.standard_normal((fan_in, fan_out)) / np.sqrt(fan_in)).ravel())

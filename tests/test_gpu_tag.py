@@ -1,0 +1,140 @@
+"""GPU parity of the pursuit ("tag") env rollout against the CPU oracle, through the C ABI.
+
+Stage-wise like the other parity tests: every stage of a step is checked on what the GPU itself
+produced for the stage before (observation rows -> networks of the agent's role -> sampler -> move,
+contact forces, per-role rewards, done / reset -> next observation rows).  Tolerances as in
+helpers.py; a reward may differ by one contact (10) where a chaser-runner distance lies within 1e-5
+of the contact distance.
+"""
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2210_00882_amd import synth
+from helpers import EDGE, GpuRollout, TOL_BF16, TOL_F32, assert_close, check_gae, close, _logp_of
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0x7A6C0FFEE
+
+
+def tag_env(cfg):
+    return ref.Env(ref.TAG, cfg.num_agents, cfg.num_landmarks, cfg.obs_dim, 1, cfg.episode_len,
+                   dt=np.float32(cfg.dt), damping=np.float32(cfg.damping), num_chasers=cfg.num_chasers,
+                   accel_c=np.float32(cfg.accel_c), accel_r=np.float32(cfg.accel_r), vmax_c=np.float32(cfg.vmax_c),
+                   vmax_r=np.float32(cfg.vmax_r), radius_c=np.float32(cfg.radius_c), radius_r=np.float32(cfg.radius_r),
+                   contact_force=np.float32(cfg.contact_force), contact_margin=np.float32(cfg.contact_margin))
+
+
+def state_from_obs(cfg, rows):
+    N, L = cfg.num_agents, cfg.num_landmarks
+    s = np.zeros(4 * N + 2 * L)
+    for i in range(N):
+        s[4 * i:4 * i + 2] = rows[i][2:4]
+        s[4 * i + 2:4 * i + 4] = rows[i][0:2]
+    s[4 * N:] = rows[0][4:4 + 2 * L].astype(np.float64) + np.tile(rows[0][2:4].astype(np.float64), L)
+    return s
+
+
+def check(cfg, tr, env, pol, params, env_ids, g0, T):
+    N = cfg.num_agents
+    n_role = pol.param_count
+    stats = {"rows": 0, "action_edge": 0, "contact_edge": 0, "contacts": 0}
+    for k, e in enumerate(env_ids):
+        rows = slice(e * N, (e + 1) * N)
+        for t in range(T + 1):
+            g = int(g0[k]) + t
+            o_gpu = tr["obs"][t, rows]
+            s = state_from_obs(cfg, o_gpu)
+            assert_close(o_gpu, ref.env_obs(env, s), TOL_F32, f"obs rows env {e} t {t}")
+            for i in range(N):
+                m = e * N + i
+                prm = params[:n_role] if i < cfg.num_chasers else params[n_role:]
+                lg, v = ref.policy_value(pol, prm, o_gpu[i])
+                assert_close(tr["values"][t, m], v, TOL_BF16, f"value env {e} agent {i} t {t}")
+                if t < T:
+                    assert_close(tr["logits"][t, m], lg, TOL_BF16, f"logits env {e} agent {i} t {t}")
+            if t == T:
+                break
+            acts = []
+            for i in range(N):
+                m = e * N + i
+                a_o, lp_o, mg = ref.sample(pol, SEED, e, i, g, tr["logits"][t, m])
+                a_g = int(tr["actions"][t, m])
+                if a_g != a_o:
+                    assert mg < EDGE, f"action env {e} agent {i} t {t}: gpu {a_g} oracle {a_o} margin {mg}"
+                    stats["action_edge"] += 1
+                    _, lp_o = _logp_of(tr["logits"][t, m], a_g)
+                assert_close(tr["logp"][t, m], lp_o, TOL_F32, f"logp env {e} agent {i} t {t}")
+                acts.append(a_g)
+                stats["rows"] += 1
+            s1, r, d, mg = ref.env_step(env, SEED, e, g, s, acts)
+            assert (tr["dones"][t, rows] == d).all(), f"done env {e} t {t}"
+            r_gpu = tr["rewards"][t, rows]
+            if not np.all(close(r_gpu, r, TOL_F32)):
+                assert mg < EDGE, f"rewards env {e} t {t}: gpu {r_gpu} oracle {r} (contact margin {mg})"
+                stats["contact_edge"] += 1
+            stats["contacts"] += int(r[0] > 0)
+            assert_close(tr["obs"][t + 1, rows], ref.env_obs(env, s1), TOL_F32, f"next obs env {e} t {t}")
+    return stats
+
+
+@pytest.mark.parametrize("nc,nr,L", [(3, 1, 2), (2, 2, 1)])
+def test_tag_rollout_every_env_and_step(nc, nr, L):
+    # big bodies, so that contact forces and contact rewards occur in most steps
+    cfg = synth.tag("tag", 70, nc, nr, L, 64, 20, 7, idx=50 + nc).with_(radius_c=0.3, radius_r=0.25)
+    env = tag_env(cfg)
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
+    params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
+    assert params.size == 2 * pol.param_count
+    with GpuRollout(cfg, params.astype(np.float32), SEED) as gpu:
+        es0, g0 = gpu.get_state()
+        np.testing.assert_array_equal(es0[3], ref.env_reset(env, SEED, 3, 0).astype(np.float32))
+        shift = (np.arange(cfg.num_envs) * 3 + 1).astype(np.int64)     # a different episode phase per env
+        gpu.set_state(None, shift)
+        ids = list(range(cfg.num_envs))
+        total = {}
+        g = shift.copy()
+        for call in range(2):
+            tr = gpu.run(cfg.T)
+            st = check(cfg, tr, env, pol, params, ids, g, cfg.T)
+            check_gae(cfg, tr)
+            g = g + cfg.T
+            es, gg = gpu.get_state()
+            np.testing.assert_array_equal(gg, g)
+            for e in ids[:6]:
+                assert_close(tr["obs"][cfg.T, e * cfg.num_agents:(e + 1) * cfg.num_agents],
+                             ref.env_obs(env, es[e].astype(np.float64)), 1e-6, "state writeback")
+            for k, v in st.items():
+                total[k] = total.get(k, 0) + v
+    assert total["rows"] == 2 * cfg.T * cfg.M
+    assert total["contacts"] > 100          # the contact path was exercised
+    # chasers share their reward, runners do not see it
+    r = tr["rewards"].reshape(cfg.T, cfg.num_envs, cfg.num_agents)
+    assert (r[:, :, :nc] == r[:, :, :1]).all() and (r[:, :, :nc] >= 0).all() and (r[:, :, nc:] <= 0).all()
+
+
+def test_tag_default_bodies_and_errors():
+    from paper_2210_00882_amd import binding as B
+    cfg = synth.tag("tag", 33, 3, 1, 2, 64, 9, 4, idx=60)
+    env = tag_env(cfg)
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
+    params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
+    with GpuRollout(cfg, params.astype(np.float32), SEED) as gpu:
+        tr = gpu.run(cfg.T)
+        check(cfg, tr, env, pol, params, list(range(cfg.num_envs)), np.zeros(cfg.num_envs, dtype=np.int64), cfg.T)
+        import torch
+        obs = torch.zeros((cfg.M, cfg.obs_dim), device="cuda")
+        with pytest.raises(B.MsrlError):        # the step-granular calls have no pursuit variant
+            B.msrl_observe(gpu.state, obs)
+    assert B.msrl_param_count(B.make_policy_cfg(cfg)) == cfg.param_count == 2 * pol.param_count
+    env_cfg, keep = B.make_env_cfg(cfg, None, None)
+    one_role = B.make_policy_cfg(cfg)
+    one_role.roles = 1
+    with pytest.raises(B.MsrlError):
+        B.msrl_rollout_init(env_cfg, one_role, 1)
+    with pytest.raises(B.MsrlError):            # no instance for five agents
+        c5 = synth.tag("tag5", 8, 4, 1, 2, 64, 4, 4)
+        B.msrl_rollout_init(B.make_env_cfg(c5, None, None)[0], B.make_policy_cfg(c5), 1)
+    with pytest.raises(B.MsrlError):            # a learner holds one parameter set
+        B.msrl_learner_init(B.make_policy_cfg(cfg), 64)
