@@ -274,6 +274,34 @@ def main():
         except B.MsrlError:
             pass
 
+        # the pursuit ("tag") env at the scale of the paper's GPU-only experiment (Fig. 10: up to
+        # 100,000 agents on one GPU): 25,000 envs x (3 chasers + 1 runner), 64-unit bf16 networks per role
+        try:
+            tcfg = synth.tag("tag_100k_agents", 25000, 3, 1, 2, 64, 100, 25)
+            tenv, tkeep = B.make_env_cfg(tcfg, None, None)
+            tstate = B.msrl_rollout_init(tenv, B.make_policy_cfg(tcfg), seed)
+            tparams = B.upload_params(tcfg, synth.make_params(tcfg))
+            tout = B.alloc_traj(tcfg, tcfg.T, logits=False, gae=True)
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 5
+            for k in range(reps + 1):
+                if k == 1:
+                    ev0.record()
+                B.msrl_rollout_gae(tstate, tparams, tcfg.T, tcfg.gamma, tcfg.lam, tout)
+            ev1.record()
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1) / reps
+            B.msrl_rollout_destroy(tstate)
+            steps_t = tcfg.T * tcfg.M
+            gbs = (rollout_bytes_per_agent_step(tcfg) + GAE_BYTES_PER_AGENT_STEP) * steps_t / (ms * 1e-3) / 1e9
+            tf = mlp_flops_per_agent_step(tcfg) * steps_t / (ms * 1e-3) / 1e12
+            phases["tag_100k_agents"] = {"bound": "hbm", "ms_per_call": ms, "achieved": gbs, "peak": PEAK_HBM_GBS,
+                                         "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "T": tcfg.T,
+                                         "agent_steps_per_s": steps_t / (ms * 1e-3), "mfma_TFLOPs": tf}
+            del tout, tparams
+        except B.MsrlError:
+            pass
+
         # in-kernel clocks of the fused kernel: where one step of one workgroup spends its cycles
         stamps = torch.zeros(1024, dtype=torch.float32, device="cuda")
         try:

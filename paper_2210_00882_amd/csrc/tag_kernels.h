@@ -40,7 +40,12 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
   constexpr int KT1 = (D + 1 + 15) / 16;  // + the constant-1 input that carries the bias
   typedef Mlp<H, true, 1, KT1> Net;
   typedef typename Net::Op Op;
-  constexpr int NET_TILES = Net::L1_TILES + Net::NUC * Net::CHUNK_TILES;
+  // Resident image of a network: its layer-1 tiles, then per 32-unit chunk the layer-2 tiles, the
+  // bias tile and the layer-3 tiles the chunk feeds (the second copy of the layer-3 tiles that the
+  // streaming kernels keep in the following block is left out: 72 KiB for the four networks, so
+  // that two workgroups fit a compute unit).
+  constexpr int BLOCK = Net::KT2 + 1 + Net::TPC;
+  constexpr int NET_TILES = Net::L1_TILES + Net::NUC * BLOCK;
   static_assert(L <= N && N <= 16, "a landmark is handled by the wave of the agent with its index");
 
   __shared__ __attribute__((aligned(16))) u32x4 s_net[4][NET_TILES * 64];
@@ -55,7 +60,16 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
   const NetLayout ly = net_layout(D, H, true);
   for (int net = 0; net < 4; ++net) {
     const u32x4* src = (const u32x4*)(a.packed + (size_t)net * ly.bytes + ly.w1);
-    for (int i = threadIdx.x; i < NET_TILES * 64; i += blockDim.x) s_net[net][i] = src[i];
+    for (int i = threadIdx.x; i < NET_TILES * 64; i += blockDim.x) {
+      const int tile = i >> 6;
+      int from = tile;  // layer-1 tiles keep their place
+      if (tile >= Net::L1_TILES) {
+        const int c = (tile - Net::L1_TILES) / BLOCK, r = (tile - Net::L1_TILES) % BLOCK;
+        // layer-2 and bias tiles, then the chunk's own layer-3 tiles (behind the copy for the chunk before)
+        from = Net::L1_TILES + c * Net::CHUNK_TILES + (r <= Net::KT2 ? r : r + Net::TPC);
+      }
+      s_net[net][i] = src[from * 64 + (i & 63)];
+    }
     if (threadIdx.x < 32)
       s_b3[net][threadIdx.x] = *(const float*)(a.packed + (size_t)net * ly.bytes + ly.b3 + threadIdx.x * 4);
   }
@@ -104,9 +118,18 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
       for (int s = 0; s < 8; ++s) f[s] = feature(16 * kt + 8 * h + s);
       if (valid) {
         float* dst = a.obs + ((size_t)t * a.M + (size_t)env * N + j) * D + 16 * kt + 8 * h;
+        const int i0 = 16 * kt + 8 * h;
+        // rows are D floats apart: 16-byte pieces when D % 4 == 0, 8-byte pieces otherwise (D is even)
+        constexpr int PW = D % 4 == 0 ? 4 : 2;
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
-          if (16 * kt + 8 * h + s < D) dst[s] = f[s];
+        for (int q = 0; q < 8 / PW; ++q) {
+          if (i0 + PW * q + PW <= D) {
+            if constexpr (PW == 4)
+              *(f32x4*)(dst + 4 * q) = f32x4{f[4 * q], f[4 * q + 1], f[4 * q + 2], f[4 * q + 3]};
+            else
+              *(f32x2*)(dst + 2 * q) = f32x2{f[2 * q], f[2 * q + 1]};
+          }
+        }
       }
       x[0][kt] = __builtin_convertvector(f, bf16x8);
     }
@@ -120,16 +143,33 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
       Op h1[1][Net::KT2];
       Net::layer1(base, x, h1);
       out[0] = bias_init(s_b3[2 * role + net], h);
-      f32x16 acc[1];
-      auto nothing = [](int) {};
+      // layer 2 chunk by chunk; the tanh of chunk c-1 and its layer-3 MFMAs run among those of chunk c
+      f32x16 acc = zero16(), prev = zero16();
 #pragma unroll
-      for (int c = 0; c < Net::NUC; ++c) {
-        const u32x4* tiles = base + (Net::L1_TILES + c * Net::CHUNK_TILES) * 64;
-        if (c == 0)
-          Net::template layer2_chunk<false>(tiles, h1, acc, out, h, nothing);
-        else
-          Net::template layer2_chunk<true>(tiles, h1, acc, out, h, nothing);
-        if (c == Net::NUC - 1) Net::layer2_drain(tiles, acc, out);
+      for (int c = 0; c <= Net::NUC; ++c) {
+        const u32x4* blk = base + (Net::L1_TILES + c * BLOCK) * 64;
+        float tt[16];
+        if (c < Net::NUC) {
+          acc = zero16();
+#pragma unroll
+          for (int kt = 0; kt < Net::KT2; ++kt) {
+            u32x4 raw = blk[kt * 64];
+            if (c > 0) pin(raw);
+            acc = mma(__builtin_bit_cast(bf16x8, raw), h1[0][kt], acc);
+            if (c > 0) tanh_range(prev, tt, kt * 16 / Net::KT2, (kt + 1) * 16 / Net::KT2, true);
+          }
+          acc = mma(__builtin_bit_cast(bf16x8, blk[Net::KT2 * 64]), Operand<true>::one(h), acc);
+        } else {
+          tanh_range(prev, tt, 0, 16, false);
+        }
+        if (c > 0) {
+          Op h2[2];
+          to_operands<true>(tt, h2);
+          const u32x4* l3 = base + (Net::L1_TILES + (c - 1) * BLOCK + Net::KT2 + 1) * 64;
+#pragma unroll
+          for (int i = 0; i < Net::TPC; ++i) out[0] = mma(__builtin_bit_cast(bf16x8, l3[i * 64]), h2[i], out[0]);
+        }
+        prev = acc;
       }
     }
     const size_t o = (size_t)t * a.M + (size_t)env * N + j;
