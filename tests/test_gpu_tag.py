@@ -138,3 +138,63 @@ def test_tag_default_bodies_and_errors():
         B.msrl_rollout_init(B.make_env_cfg(c5, None, None)[0], B.make_policy_cfg(c5), 1)
     with pytest.raises(B.MsrlError):            # a learner holds one parameter set
         B.msrl_learner_init(B.make_policy_cfg(cfg), 64)
+
+
+def test_learner_gradient_per_role_on_a_tag_trajectory():
+    # the learner holds one parameter set: one learner per role, fed that role's rows of the trajectory
+    import torch
+    from paper_2210_00882_amd import binding as B
+    cfg = synth.tag("tag", 40, 3, 1, 2, 64, 8, 8, idx=61).with_(radius_c=0.3, radius_r=0.25)
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
+    params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
+    n_role = pol.param_count
+    with GpuRollout(cfg, params.astype(np.float32), SEED) as gpu:
+        tr = gpu.run(cfg.T, logits=False)
+    N, T = cfg.num_agents, cfg.T
+    agent = np.tile(np.arange(cfg.M) % N, T)                       # agent slot of every flattened row
+    flat = {k: tr[k][:T].reshape(T * cfg.M, *tr[k].shape[2:]) for k in ("obs", "actions", "logp", "adv", "ret")}
+    one = B.make_policy_cfg(cfg)
+    one.roles = 1
+    for role, sel in ((0, agent < cfg.num_chasers), (1, agent >= cfg.num_chasers)):
+        rows = {k: np.ascontiguousarray(v[sel]) for k, v in flat.items()}
+        R = int(sel.sum())
+        prm = params[role * n_role:(role + 1) * n_role]
+        hp = dict(clip=0.2, vf_coef=0.5, ent_coef=0.01)
+        # old log-probabilities shifted so that both branches of the clipped objective occur
+        lp_old = (rows["logp"] - np.random.default_rng(role).choice([-0.4, 0.0, 0.4], R)).astype(np.float32)
+        _, g_ref, st_ref = ref.ppo_loss(pol, ref.ppo_cfg(**hp), prm, rows["obs"], rows["actions"], lp_old,
+                                        rows["adv"], rows["ret"])
+        L = B.msrl_learner_init(one, R)
+        try:
+            dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+            grad = torch.empty(n_role, dtype=torch.float32, device="cuda")
+            B.msrl_ppo_grad(L, dev(prm.astype(np.float32)), dev(rows["obs"]), dev(rows["actions"]), dev(lp_old),
+                            dev(rows["adv"]), dev(rows["ret"]), B.make_ppo_cfg(**hp), grad)
+            torch.cuda.synchronize()
+        finally:
+            B.msrl_learner_destroy(L)
+        g = grad.cpu().numpy().astype(np.float64)
+        assert 0.05 < st_ref[3] < 0.95
+        off = 0
+        for o in (5, 1):
+            n = cfg.obs_dim * 64 + 64 + 64 * 64 + 64 + 64 * o + o
+            a, b = g[off:off + n], g_ref[off:off + n]
+            assert np.abs(a - b).max() <= 2e-2 * np.abs(b).max(), f"role {role} net out={o}"
+            off += n
+
+
+def test_training_loop_with_a_learner_per_role():
+    # Trainer.train of Listing 1 on the pursuit env: rollout + GAE, then one update per role on that
+    # role's rows.  Checked here: it runs, stays finite and moves both parameter sets; and the
+    # chasers, whose reward is the number of contacts, come to touch the runners more often.
+    from paper_2210_00882_amd import train
+    cfg = synth.tag("tag", 1024, 3, 1, 2, 64, 32, 32, idx=62).with_(radius_c=0.15, radius_r=0.1)
+    params = synth.make_params(cfg, bias_std=0.0, seed=9)
+    final, hist = train.ppo_train(cfg, params, 40, 321, lr=1e-3, gamma=0.95, lam=0.95)
+    hist = np.asarray(hist)
+    assert np.isfinite(final).all() and np.isfinite(hist).all()
+    n = params.size // 2
+    assert np.abs(final[:n] - params[:n]).max() > 1e-3 and np.abs(final[n:] - params[n:]).max() > 1e-3
+    assert (hist[:, 0] >= 0).all() and (hist[:, 1] <= 0).all()
+    first, last = hist[:5, 0].mean(), hist[-5:, 0].mean()
+    assert last > 2.0 * first, (first, last)     # measured: 0.34 -> 2.2 contacts x 10 per step
