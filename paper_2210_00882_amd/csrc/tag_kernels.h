@@ -6,9 +6,12 @@
 // so the 32 rows of a wave's MFMA tile all have the same role and use the same weights.  The
 // networks are small (bf16, 64 units), so the four of them (chasers' and runners' policy and
 // value) stay resident in LDS for the whole kernel: no weight streaming, and the only barriers are
-// those of the env step, where the agents of an env (one per wave) exchange positions through LDS.
+// those of the env step (two per step), where the agents of an env (one per wave) exchange
+// positions through LDS.
 // The MLP itself is the chained MFMA form of mlp.h, reading its tiles from the resident images.
 #pragma once
+#include <type_traits>
+
 #include "rollout_kernels.h"
 
 namespace msrl {
@@ -50,7 +53,11 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
 
   __shared__ __attribute__((aligned(16))) u32x4 s_net[4][NET_TILES * 64];
   __shared__ __attribute__((aligned(16))) float s_b3[4][32];
-  __shared__ float2 s_p[32][N], s_v[32][N], s_lm[32][L > 0 ? L : 1];
+  // State tables of the workgroup's envs, double-buffered over the steps: step t reads buffer t % 2
+  // and writes the state of step t + 1 (moved, or reset after a done) into the other one, so that
+  // two barriers per step suffice (new state visible; contact counts visible).  s_pm holds the
+  // positions after the move, which the rewards are computed on.
+  __shared__ float2 s_p[2][32][N], s_v[2][32][N], s_lm[2][32][L > 0 ? L : 1], s_pm[32][N];
   __shared__ float s_cnt[32][N];
 
   const int lane = threadIdx.x & 63;
@@ -84,40 +91,67 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
   uint32_t g32 = (uint32_t)g64;
   int tau = (int)(g64 % a.ep);
   uint32_t episode = (uint32_t)(g64 / a.ep);
+  float2 lm_own = make_float2(0.0f, 0.0f);  // landmark j, kept by wave j < L
+  if (j < L) lm_own = make_float2(es[4 * N + 2 * j], es[4 * N + 2 * j + 1]);
   if (h == 0) {
-    s_p[n][j] = p;
-    s_v[n][j] = v;
-    if (j < L) s_lm[n][j] = make_float2(es[4 * N + 2 * j], es[4 * N + 2 * j + 1]);
+    s_p[0][n][j] = p;
+    s_v[0][n][j] = v;
+    if (j < L) s_lm[0][n][j] = lm_own;
   }
   const float my_rad = a.rad[role];
+  const float inv_margin = 1.0f / a.cmargin;
+  __syncthreads();
 
   for (int t = 0; t <= a.T; ++t) {
-    __syncthreads();  // the positions of this step are in LDS
+    const int cur = t & 1, nxt = cur ^ 1;
     // ---------------- observation row of (env n, agent j)
-    auto feature = [&](int idx) -> float {
-      if (idx >= D) return idx == D ? 1.0f : 0.0f;  // input D carries the bias
-      if (idx < 4) return idx == 0 ? v.x : idx == 1 ? v.y : idx == 2 ? p.x : p.y;
-      int q = (idx - 4) >> 1;  // pair index behind the own state
-      const int c = idx & 1;
-      if (q < L) {
-        const float2 lm = s_lm[n][min(q, L > 0 ? L - 1 : 0)];
-        return c ? lm.y - p.y : lm.x - p.x;
+    // Feature IDX of the row; the index is a compile-time constant, so that each feature is one LDS
+    // read and a subtraction (a lane needs the features 16 kt + 8 h + s: both halves are evaluated
+    // and the lane keeps its own).
+    auto feature = [&](auto IDX) -> float {
+      constexpr int idx = decltype(IDX)::value;
+      if constexpr (idx > D) {
+        return 0.0f;
+      } else if constexpr (idx == D) {
+        return 1.0f;  // input D carries the bias
+      } else if constexpr (idx < 4) {
+        return idx == 0 ? v.x : idx == 1 ? v.y : idx == 2 ? p.x : p.y;
+      } else if constexpr ((idx - 4) / 2 < L) {
+        const float2 lm = s_lm[cur][n][(idx - 4) / 2];
+        return idx % 2 ? lm.y - p.y : lm.x - p.x;
+      } else {
+        constexpr int q0 = (idx - 4) / 2 - L;
+        constexpr bool vel = q0 >= N - 1;
+        constexpr int q = vel ? q0 - (N - 1) : q0;
+        const int o = q + (q >= j ? 1 : 0);  // the q-th other agent (j is wave-uniform)
+        const float2 w = vel ? s_v[cur][n][o] : s_p[cur][n][o];
+        return vel ? (idx % 2 ? w.y : w.x) : (idx % 2 ? w.y - p.y : w.x - p.x);
       }
-      q -= L;
-      const bool vel = q >= N - 1;
-      if (vel) q -= N - 1;
-      const int o = q + (q >= j ? 1 : 0);  // the q-th other agent
-      const float2 w = vel ? s_v[n][o] : s_p[n][o];
-      return vel ? (c ? w.y : w.x) : (c ? w.y - p.y : w.x - p.x);
     };
     Op x[1][KT1];
+    float* const orow = a.obs + ((size_t)t * a.M + (size_t)env * N + j) * D;
 #pragma unroll
     for (int kt = 0; kt < KT1; ++kt) {
       f32x8 f;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) f[s] = feature(16 * kt + 8 * h + s);
+      auto fill = [&](auto KT, auto S8) {
+        constexpr int k = decltype(KT)::value, s = decltype(S8)::value;
+        const float lo = feature(std::integral_constant<int, 16 * k + s>{});
+        const float hi = feature(std::integral_constant<int, 16 * k + 8 + s>{});
+        f[s] = h ? hi : lo;
+      };
+      auto fill_all = [&](auto KT) {
+        fill(KT, std::integral_constant<int, 0>{}); fill(KT, std::integral_constant<int, 1>{});
+        fill(KT, std::integral_constant<int, 2>{}); fill(KT, std::integral_constant<int, 3>{});
+        fill(KT, std::integral_constant<int, 4>{}); fill(KT, std::integral_constant<int, 5>{});
+        fill(KT, std::integral_constant<int, 6>{}); fill(KT, std::integral_constant<int, 7>{});
+      };
+      static_assert(KT1 <= 4, "layer-1 tiles of the observation");
+      if (kt == 0) fill_all(std::integral_constant<int, 0>{});
+      if (kt == 1) fill_all(std::integral_constant<int, 1>{});
+      if (kt == 2) fill_all(std::integral_constant<int, 2>{});
+      if (kt == 3) fill_all(std::integral_constant<int, 3>{});
       if (valid) {
-        float* dst = a.obs + ((size_t)t * a.M + (size_t)env * N + j) * D + 16 * kt + 8 * h;
+        float* dst = orow + 16 * kt + 8 * h;
         const int i0 = 16 * kt + 8 * h;
         // rows are D floats apart: 16-byte pieces when D % 4 == 0, 8-byte pieces otherwise (D is even)
         constexpr int PW = D % 4 == 0 ? 4 : 2;
@@ -203,44 +237,63 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
 #pragma unroll
     for (int q = 0; q < N; ++q) {
       if (q == j) continue;  // uniform
-      const float2 po = s_p[n][q];
+      const float2 po = s_p[cur][n][q];
       const float dx = p.x - po.x, dy = p.y - po.y;
-      const float d = sqrtf(dx * dx + dy * dy);
-      const float z = (my_rad + a.rad[q < NC ? 0 : 1] - d) / a.cmargin;
-      const float pen = a.cmargin * (fmaxf(z, 0.0f) + log1pf(expf(-fabsf(z))));
+      const float d = __builtin_amdgcn_sqrtf(dx * dx + dy * dy);
+      const float z = (my_rad + a.rad[q < NC ? 0 : 1] - d) * inv_margin;
+      // smooth max(0, overlap): max(z, 0) + log(1 + exp(-|z|)), on the exp2 / log2 units
+      const float pen = a.cmargin * (fmaxf(z, 0.0f) + __logf(1.0f + __expf(-fabsf(z))));
       if (d > 0.0f) {
-        fx += a.cforce * pen * dx / d;
-        fy += a.cforce * pen * dy / d;
+        const float k = a.cforce * pen * __builtin_amdgcn_rcpf(d);
+        fx += k * dx;
+        fy += k * dy;
       }
     }
     v.x = v.x * a.keep + fx * a.dt;
     v.y = v.y * a.keep + fy * a.dt;
-    const float sp = sqrtf(v.x * v.x + v.y * v.y);
+    const float sp = __builtin_amdgcn_sqrtf(v.x * v.x + v.y * v.y);
     if (sp > a.vmax[role]) {
-      v.x *= a.vmax[role] / sp;
-      v.y *= a.vmax[role] / sp;
+      const float k = a.vmax[role] * __builtin_amdgcn_rcpf(sp);
+      v.x *= k;
+      v.y *= k;
     }
     p.x += v.x * a.dt;
     p.y += v.y * a.dt;
-    __syncthreads();  // every wave has read the old positions
-    if (h == 0) {
-      s_p[n][j] = p;
-      s_v[n][j] = v;
+    const float2 moved = p;
+    // the state of the next step: the moved one, or the first of the next episode after a done
+    const bool done = tau + 1 == a.ep;
+    g32 += 1;
+    tau = done ? 0 : tau + 1;
+    if (done) {
+      episode += 1;
+      const Words4 wa = draw(a.seed_lo, a.seed_hi, env, (uint32_t)j, episode, 1, 0);
+      p = make_float2(2.0f * u01(wa.w[0]) - 1.0f, 2.0f * u01(wa.w[1]) - 1.0f);
+      v = make_float2(0.0f, 0.0f);
+      if (j < L) {
+        const Words4 wl = draw(a.seed_lo, a.seed_hi, env, (uint32_t)(N + j), episode, 1, 0);
+        lm_own = make_float2(2.0f * u01(wl.w[0]) - 1.0f, 2.0f * u01(wl.w[1]) - 1.0f);
+      }
     }
-    __syncthreads();
+    if (h == 0) {
+      s_pm[n][j] = moved;
+      s_p[nxt][n][j] = p;
+      s_v[nxt][n][j] = v;
+      if (j < L) s_lm[nxt][n][j] = lm_own;
+    }
+    __syncthreads();  // moved positions and the next state are visible
 
-    // ---------------- rewards on the new positions: contacts between chasers and runners
+    // ---------------- rewards on the moved positions: contacts between chasers and runners
     float cnt = 0.0f;
     const float dmin = a.rad[0] + a.rad[1];
 #pragma unroll
     for (int q = 0; q < N; ++q) {
       if ((q < NC) == (j < NC)) continue;  // uniform: only the other role
-      const float2 po = s_p[n][q];
-      const float dx = p.x - po.x, dy = p.y - po.y;
-      cnt += sqrtf(dx * dx + dy * dy) < dmin ? 1.0f : 0.0f;
+      const float2 po = s_pm[n][q];
+      const float dx = moved.x - po.x, dy = moved.y - po.y;
+      cnt += dx * dx + dy * dy < dmin * dmin ? 1.0f : 0.0f;
     }
     if (h == 0) s_cnt[n][j] = cnt;
-    __syncthreads();
+    __syncthreads();  // contact counts are visible
     float rew;
     if (role == 0) {
       float total = 0.0f;
@@ -248,28 +301,11 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
       for (int q = 0; q < NC; ++q) total += s_cnt[n][q];
       rew = 10.0f * total;
     } else {
-      rew = -10.0f * cnt - 10.0f * (fmaxf(fabsf(p.x) - 1.0f, 0.0f) + fmaxf(fabsf(p.y) - 1.0f, 0.0f));
+      rew = -10.0f * cnt - 10.0f * (fmaxf(fabsf(moved.x) - 1.0f, 0.0f) + fmaxf(fabsf(moved.y) - 1.0f, 0.0f));
     }
-    const bool done = tau + 1 == a.ep;
     if (valid && h == 0) {
       a.rewards[o] = rew;
       a.dones[o] = done ? 1 : 0;
-    }
-    g32 += 1;
-    tau = done ? 0 : tau + 1;
-    if (done) {  // uniform over the workgroup only if all envs share the phase: handled per lane
-      episode += 1;
-      const Words4 wa = draw(a.seed_lo, a.seed_hi, env, (uint32_t)j, episode, 1, 0);
-      p = make_float2(2.0f * u01(wa.w[0]) - 1.0f, 2.0f * u01(wa.w[1]) - 1.0f);
-      v = make_float2(0.0f, 0.0f);
-      if (h == 0) {
-        s_p[n][j] = p;
-        s_v[n][j] = v;
-        if (j < L) {
-          const Words4 wl = draw(a.seed_lo, a.seed_hi, env, (uint32_t)(N + j), episode, 1, 0);
-          s_lm[n][j] = make_float2(2.0f * u01(wl.w[0]) - 1.0f, 2.0f * u01(wl.w[1]) - 1.0f);
-        }
-      }
     }
   }
 
@@ -281,9 +317,8 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
     eo[4 * j + 2] = v.x;
     eo[4 * j + 3] = v.y;
     if (j < L) {
-      const float2 lm = s_lm[n][j];
-      eo[4 * N + 2 * j] = lm.x;
-      eo[4 * N + 2 * j + 1] = lm.y;
+      eo[4 * N + 2 * j] = lm_own.x;
+      eo[4 * N + 2 * j + 1] = lm_own.y;
     }
     if (j == 0) a.g[env] = g64 + a.T;
   }
