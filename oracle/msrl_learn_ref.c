@@ -47,6 +47,7 @@ typedef struct {
   int32_t bf16;
   int32_t dist;
   int32_t hidden_layers; /* tanh layers in front of the output layer; 0 means 2 */
+  int32_t value_in_dim;  /* must be 0 or in_dim here: the learner trains both nets on the same rows */
 } ref_policy_cfg;
 
 typedef struct {

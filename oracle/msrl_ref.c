@@ -57,6 +57,8 @@ typedef struct {
   int32_t bf16; /* 0: exact arithmetic on the given values; 1: bf16 rounding points */
   int32_t dist;
   int32_t hidden_layers; /* tanh layers of `hidden` units in front of the output layer; 0 means 2 */
+  int32_t value_in_dim;  /* input width of the value net; 0 means in_dim.  N * in_dim: a centralised
+                            critic on the joint observation of the env's N agents */
 } ref_policy_cfg;
 
 /* ---------------------------------------------------------------- Philox */
@@ -194,6 +196,16 @@ void ref_policy_value(const ref_policy_cfg* p, const double* params, const doubl
   ref_mlp_l(p->in_dim, p->hidden, p->out_dim, L, params, x, logits, p->bf16);
   ref_mlp_l(p->in_dim, p->hidden, 1, L,
             params + ref_net_param_count_l(p->in_dim, p->hidden, p->out_dim, L), x, value, p->bf16);
+}
+
+/* Centralised critic (multi-agent PPO, section 2.1: the critic takes joint information of all agents): the
+ * value network takes the joint observation of an env, the N rows of its agents one after the
+ * other, and gives one value for the env.  params as above, the value net value_in_dim wide. */
+void ref_central_value(const ref_policy_cfg* p, const double* params, const double* joint,
+                       double* value) {
+  const int L = layers_of(p);
+  ref_mlp_l(p->value_in_dim, p->hidden, 1, L,
+            params + ref_net_param_count_l(p->in_dim, p->hidden, p->out_dim, L), joint, value, p->bf16);
 }
 
 /* ---------------------------------------------------------------- sampling */
@@ -567,7 +579,14 @@ void ref_rollout(const ref_env_cfg* c, const ref_policy_cfg* p, uint64_t seed, i
           prm += ref_net_param_count_l(p->in_dim, p->hidden, p->out_dim, Lh) +
                  ref_net_param_count_l(p->in_dim, p->hidden, 1, Lh);
         }
-        ref_policy_value(p, prm, o + (size_t)i * D, lg, &v);
+        if (p->value_in_dim > 0 && p->value_in_dim != p->in_dim) {
+          /* centralised critic: policy on the agent's row, value on the env's joint observation */
+          const int Lh = p->hidden_layers > 0 ? p->hidden_layers : 2;
+          ref_mlp_l(p->in_dim, p->hidden, p->out_dim, Lh, prm, o + (size_t)i * D, lg, p->bf16);
+          ref_central_value(p, prm, o, &v);
+        } else {
+          ref_policy_value(p, prm, o + (size_t)i * D, lg, &v);
+        }
         values[(size_t)t * M + m] = v;
         if (t == T) continue;
         double lp, mg;

@@ -48,7 +48,8 @@ class EnvCfg(C.Structure):
 
 class PolicyCfg(C.Structure):
     _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("out_dim", C.c_int32),
-                ("bf16", C.c_int32), ("dist", C.c_int32), ("hidden_layers", C.c_int32)]
+                ("bf16", C.c_int32), ("dist", C.c_int32), ("hidden_layers", C.c_int32),
+                ("value_in_dim", C.c_int32)]
 
 
 _lib = None
@@ -97,15 +98,19 @@ class Env:
 
 
 class Policy:
-    def __init__(self, in_dim, hidden, out_dim, bf16=False, dist=CATEGORICAL, hidden_layers=2):
-        self.c = PolicyCfg(in_dim, hidden, out_dim, int(bf16), dist, hidden_layers)
+    def __init__(self, in_dim, hidden, out_dim, bf16=False, dist=CATEGORICAL, hidden_layers=2, value_in_dim=0):
+        self.c = PolicyCfg(in_dim, hidden, out_dim, int(bf16), dist, hidden_layers, value_in_dim)
         self.in_dim, self.hidden, self.out_dim, self.bf16, self.dist = in_dim, hidden, out_dim, bool(bf16), dist
         self.hidden_layers = hidden_layers
+        self.value_in_dim = value_in_dim or in_dim     # wider than in_dim: centralised critic on the joint observation
+
+    @property
+    def policy_param_count(self):
+        return net_param_count(self.in_dim, self.hidden, self.out_dim, self.hidden_layers)
 
     @property
     def param_count(self):
-        return net_param_count(self.in_dim, self.hidden, self.out_dim, self.hidden_layers) + \
-            net_param_count(self.in_dim, self.hidden, 1, self.hidden_layers)
+        return self.policy_param_count + net_param_count(self.value_in_dim, self.hidden, 1, self.hidden_layers)
 
 
 def net_param_count(i, h, o, layers=2):
@@ -166,6 +171,15 @@ def policy_value(pol: Policy, params, x):
     v = C.c_double()
     lib().ref_policy_value(C.byref(pol.c), _p(params), _p(x), _p(lg), C.byref(v))
     return lg, float(v.value)
+
+
+def central_value(pol: Policy, params, joint):
+    """Value of an env from the joint observation of its agents (centralised critic)."""
+    params, joint = _f64(params), _f64(joint).ravel()
+    assert params.size == pol.param_count and joint.size == pol.value_in_dim
+    v = C.c_double()
+    lib().ref_central_value(C.byref(pol.c), _p(params), _p(joint), C.byref(v))
+    return float(v.value)
 
 
 def categorical(logits, u):

@@ -152,6 +152,39 @@ def test_deep_mlp_by_hand():
     assert y == pytest.approx(want, rel=1e-14)
 
 
+def test_centralised_critic_takes_the_joint_observation():
+    # value net on the N rows of an env, one after the other; the policy stays on the agent's own row
+    rng = np.random.default_rng(31)
+    N, L, H = 3, 3, 16
+    D = 6 * N
+    env = ref.Env(ref.PARTICLE, N, L, D, 1, 5)
+    pol = ref.Policy(D, H, 5, value_in_dim=N * D)
+    n_pi = ref.net_param_count(D, H, 5)
+    assert pol.param_count == n_pi + ref.net_param_count(N * D, H, 1) and pol.policy_param_count == n_pi
+    params = rng.standard_normal(pol.param_count) * 0.3
+    joint = rng.standard_normal(N * D)
+    assert ref.central_value(pol, params, joint) == ref.mlp(N * D, H, 1, params[n_pi:], joint)[0]
+    state, g = ref.init(env, 11, 0, 4)
+    tr = ref.rollout(env, pol, 11, 0, state, g, params, 3)
+    for e in range(4):
+        rows = slice(e * N, (e + 1) * N)
+        for t in range(4):
+            v = ref.mlp(N * D, H, 1, params[n_pi:], tr["obs"][t, rows].ravel())[0]
+            np.testing.assert_array_equal(tr["values"][t, rows], [v] * N)       # one value per env
+            if t < 3:
+                for i in range(N):
+                    np.testing.assert_array_equal(tr["logits"][t, e * N + i],
+                                                  ref.mlp(D, H, 5, params[:n_pi], tr["obs"][t, e * N + i]))
+    # a critic that only looks at the first agent's row is that agent's own value net
+    own = ref.Policy(D, H, 5)
+    p_own = rng.standard_normal(own.param_count) * 0.3
+    W1 = p_own[n_pi:n_pi + D * H].reshape(D, H)
+    wide = np.concatenate([W1, np.zeros(((N - 1) * D, H))]).ravel()
+    p_c = np.concatenate([p_own[:n_pi], wide, p_own[n_pi + D * H:]])
+    x = rng.standard_normal((N, D))
+    assert ref.central_value(pol, p_c, x) == ref.policy_value(own, p_own, x[0])[1]
+
+
 # ------------------------------------------------------------------ samplers
 def test_categorical_edges_and_logp():
     lg = np.array([0.3, -1.2, 2.0, 0.0, -0.5])
