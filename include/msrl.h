@@ -143,6 +143,14 @@ typedef struct {
  * roles (0 means 1; 2 for MSRL_ENV_TAG): number of parameter sets.  The
  * parameter buffer holds them one after the other (policy then value each);
  * role 0 are the chasers.
+ *
+ * value_in_dim (0 means in_dim): input width of the value network.  The only
+ * other value accepted is num_agents * in_dim: a centralised critic (multi-
+ * agent PPO, section 2.1 of the paper) that takes the joint observation of an
+ * env, the rows of its agents one after the other, and gives one value per env;
+ * values[t, m] then holds that value on every row of the env.  W1 of the value
+ * network is [value_in_dim, hidden].  Supported by msrl_rollout_step /
+ * msrl_rollout_gae on the particle env with bfloat16 networks.
  */
 typedef struct {
   int32_t in_dim, hidden, out_dim;
@@ -150,6 +158,7 @@ typedef struct {
   int32_t dist;   /* msrl_dist */
   int32_t hidden_layers;
   int32_t roles;
+  int32_t value_in_dim;
 } msrl_policy_cfg;
 
 /*

@@ -42,7 +42,8 @@ class msrl_env_cfg(C.Structure):
 
 class msrl_policy_cfg(C.Structure):
     _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("out_dim", C.c_int32),
-                ("dtype", C.c_int32), ("dist", C.c_int32), ("hidden_layers", C.c_int32), ("roles", C.c_int32)]
+                ("dtype", C.c_int32), ("dist", C.c_int32), ("hidden_layers", C.c_int32), ("roles", C.c_int32),
+                ("value_in_dim", C.c_int32)]
 
 
 class msrl_traj(C.Structure):
@@ -160,7 +161,8 @@ def make_env_cfg(cfg, A=None, B=None):
 
 
 def make_policy_cfg(cfg):
-    return msrl_policy_cfg(cfg.obs_dim, cfg.hidden, cfg.out_dim, cfg.dtype, cfg.dist, cfg.hidden_layers, cfg.roles)
+    return msrl_policy_cfg(cfg.obs_dim, cfg.hidden, cfg.out_dim, cfg.dtype, cfg.dist, cfg.hidden_layers, cfg.roles,
+                           cfg.value_in_dim if cfg.central_critic else 0)
 
 
 def msrl_param_count(policy_cfg: msrl_policy_cfg) -> int:

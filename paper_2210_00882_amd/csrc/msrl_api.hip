@@ -38,6 +38,8 @@ struct msrl_state {
   uint8_t* dyn;          // device, lingauss dynamics tiles
   float* dyn_src;        // device copy of A then B (row-major), source of dyn
   NetLayout layout;
+  NetLayout critic_layout;  // centralised critic: its image follows the policy network's in `packed`
+  bool central;
   KernelEntry kernel;
   int envs_per_block;    // envs owned by one workgroup
   int in_used;           // leading observation features that can be non-zero (inputs of layer 1)
@@ -80,7 +82,8 @@ std::vector<KernelEntry> all_kernels() {
           entry_p6_h128_f32_act(), entry_p6_h128_f32_step(),
           entry_p10_h256_bf16_act(), entry_p10_h256_bf16_step(),
           entry_p3_h64_f32_deep(), entry_p3_h64_bf16_deep(), entry_p10_h256_bf16_deep(),
-          entry_l17_6_h256_deep()};
+          entry_l17_6_h256_deep(),
+          entry_p3_h64_bf16_central(), entry_p10_h256_bf16_central()};
 }
 
 bool valid_policy(const msrl_policy_cfg* p) {
@@ -88,8 +91,12 @@ bool valid_policy(const msrl_policy_cfg* p) {
          (p->dtype == MSRL_F32 || p->dtype == MSRL_BF16) &&
          (p->dist == MSRL_CATEGORICAL || p->dist == MSRL_DIAG_GAUSSIAN) &&
          (p->hidden_layers == 0 || (p->hidden_layers >= 2 && p->hidden_layers <= 8)) &&
-         (p->roles >= 0 && p->roles <= 2);
+         (p->roles >= 0 && p->roles <= 2) && p->value_in_dim >= 0;
 }
+
+// input width of the value network; wider than the policy's: a centralised critic on the joint observation
+int value_in_of(const msrl_policy_cfg& p) { return p.value_in_dim > 0 ? p.value_in_dim : p.in_dim; }
+bool central_of(const msrl_policy_cfg& p) { return value_in_of(p) != p.in_dim; }
 
 int roles_of(const msrl_policy_cfg& p) { return p.roles == 0 ? 1 : p.roles; }
 
@@ -170,7 +177,6 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
   const bool bf16 = p.dtype == MSRL_BF16;
   const size_t esz = bf16 ? 2 : 4;
   const int in_map1 = st->env.kind == MSRL_ENV_LINGAUSS ? IN_CHAIN : (bf16 ? IN_LINEAR16 : IN_PAIRS);
-  const NetLayout& L = st->layout;
   PackJobs jobs;
   jobs.n = 0;
   const uint8_t* src = (const uint8_t*)params;
@@ -178,20 +184,29 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     const int out = net % 2 == 0 ? p.out_dim : 1;
     const int out_map = (net % 2 == 0 && p.dist == MSRL_DIAG_GAUSSIAN) ? OUT_GAUSS : OUT_NATURAL;
     const int gk = p.out_dim / 2;
-    uint8_t* dst = st->packed + (size_t)net * L.bytes;
+    // a centralised critic has a layout of its own (more layer-1 tiles) behind the policy network
+    const bool joint = st->central && net == 1;
+    const NetLayout& L = joint ? st->critic_layout : st->layout;
+    const int in_rows = net % 2 == 1 ? value_in_of(p) : p.in_dim;
+    const int in_used = joint ? st->env.num_agents * st->in_used : st->in_used;
+    uint8_t* dst = st->packed + (size_t)net * st->layout.bytes;
     const int layers = layers_of(p);
     const size_t hh = (size_t)p.hidden * p.hidden * esz, hb = (size_t)p.hidden * esz;
     const uint8_t* W1 = src;
-    const uint8_t* b1 = W1 + (size_t)p.in_dim * p.hidden * esz;
+    const uint8_t* b1 = W1 + (size_t)in_rows * p.hidden * esz;
     const uint8_t* Wmid = b1 + hb;                                  // hidden layers 2 .. layers-1: W b each
     const uint8_t* W2 = Wmid + (size_t)(layers - 2) * (hh + hb);   // the last hidden layer
     const uint8_t* b2 = W2 + hh;
     const uint8_t* W3 = b2 + hb;
     const uint8_t* b3 = W3 + (size_t)p.hidden * out * esz;
     // only the inputs that can be non-zero are packed (a prefix of the rows of W1)
-    PackJob j1 = weight_job(W1, dst + L.w1, bf16, st->in_used, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
+    PackJob j1 = weight_job(W1, dst + L.w1, bf16, in_used, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
     j1.bias = b1;  // the bias is the input after them; the kernels feed 1 there
-    j1.bias_index = st->in_used;
+    j1.bias_index = in_used;
+    if (joint) {  // the non-zero prefix of every agent's row, one after the other
+      j1.in_block = st->in_used;
+      j1.in_block_stride = p.in_dim;
+    }
     jobs.job[jobs.n++] = j1;
     // chunk blocks of the hidden layers before the last one: kt2 tiles of the chunk and its bias tile
     for (int l = 0; l < layers - 2; ++l) {
@@ -248,6 +263,12 @@ bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase,
     if (phase == PHASE_ALL) phase = PHASE_DEEP;
     else if (phase != PHASE_STEP) return false;
   }
+  // likewise a centralised critic
+  if (central_of(pol)) {
+    if (layers_of(pol) > 2) return false;
+    if (phase == PHASE_ALL) phase = PHASE_CENTRAL;
+    else if (phase != PHASE_STEP) return false;
+  }
   for (const KernelEntry& k : all_kernels()) {
     if (k.phase != phase || k.kind != env.kind || k.hidden != pol.hidden || (k.bf16 != 0) != bf16) continue;
     if (env.kind == MSRL_ENV_PARTICLE) {
@@ -298,6 +319,7 @@ int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* param
   a.actions_in = actions_in;
   a.envs_per_block = st->envs_per_block;
   a.layers = layers_of(st->pol);
+  a.critic = st->central ? st->packed + st->layout.bytes : nullptr;
   const int64_t blocks = ((int64_t)a.E + a.envs_per_block - 1) / a.envs_per_block;
   void* args[] = {&a};
   HIP_TRY(hipLaunchKernel(kernel.fn, dim3((unsigned)blocks), dim3(64 * kernel.waves), args, 0, stream));
@@ -348,7 +370,7 @@ size_t msrl_param_count(const msrl_policy_cfg* cfg) {
   if (!valid_policy(cfg)) return 0;
   const int L = layers_of(*cfg);
   return (size_t)roles_of(*cfg) *
-         (net_params(cfg->in_dim, cfg->hidden, cfg->out_dim, L) + net_params(cfg->in_dim, cfg->hidden, 1, L));
+         (net_params(cfg->in_dim, cfg->hidden, cfg->out_dim, L) + net_params(value_in_of(*cfg), cfg->hidden, 1, L));
 }
 
 size_t msrl_env_state_size(const msrl_env_cfg* cfg) {
@@ -378,6 +400,12 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
       return fail(MSRL_EINVAL, "msrl_rollout_init: the lingauss env needs a Gaussian policy with out_dim 2*act_dim");
     if (!env->A || !env->B) return fail(MSRL_EINVAL, "msrl_rollout_init: lingauss needs A and B");
   }
+  if (central_of(*policy) &&
+      (env->kind != MSRL_ENV_PARTICLE || policy->value_in_dim != env->num_agents * policy->in_dim ||
+       policy->dtype != MSRL_BF16 || layers_of(*policy) != 2))
+    return fail(MSRL_EINVAL, "msrl_rollout_init: value_in_dim %d: a centralised critic takes num_agents * in_dim = %d "
+                             "inputs (particle env, bfloat16 networks, two hidden layers)",
+                policy->value_in_dim, env->num_agents * policy->in_dim);
   // kernel selection
   KernelEntry found;
   memset(&found, 0, sizeof(found));
@@ -427,6 +455,9 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   st->in_used = env->kind == MSRL_ENV_PARTICLE ? 4 * env->num_agents + 2 : policy->in_dim;
   const int n_nets = 2 * roles_of(*policy);
   st->layout = net_layout(st->in_used, policy->hidden, policy->dtype == MSRL_BF16, layers_of(*policy));
+  st->central = central_of(*policy);
+  st->critic_layout = net_layout(env->num_agents * st->in_used, policy->hidden, true);
+  const size_t packed_bytes = st->central ? st->layout.bytes + st->critic_layout.bytes : n_nets * st->layout.bytes;
 
   int rc = MSRL_OK;
   auto cleanup = [&](int code) {
@@ -447,8 +478,8 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   const size_t E = (size_t)env->num_envs;
   INIT_TRY(hipMalloc((void**)&st->env_state, E * st->state_size * sizeof(float)));
   INIT_TRY(hipMalloc((void**)&st->g, E * sizeof(int64_t)));
-  INIT_TRY(hipMalloc((void**)&st->packed, n_nets * st->layout.bytes));
-  INIT_TRY(hipMemset(st->packed, 0, n_nets * st->layout.bytes));
+  INIT_TRY(hipMalloc((void**)&st->packed, packed_bytes));
+  INIT_TRY(hipMemset(st->packed, 0, packed_bytes));
   if (env->kind == MSRL_ENV_LINGAUSS) {
     const int D = env->obs_dim, K = env->act_dim;
     const int ktA = tiles_for_inputs(D + 1, false), ktB = tiles_for_inputs(K, false);  // as the kernel counts them

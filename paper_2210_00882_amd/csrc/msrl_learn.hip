@@ -390,6 +390,9 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
     return fail(MSRL_EINVAL, "msrl_learner_init: hidden_layers must be 0 (two) or 2..8");
   if (policy->roles > 1)
     return fail(MSRL_EINVAL, "msrl_learner_init: a learner holds one parameter set; create one per role");
+  if (policy->value_in_dim != 0 && policy->value_in_dim != policy->in_dim)
+    return fail(MSRL_EUNSUPPORTED, "msrl_learner_init: a value network on the joint observation (value_in_dim %d != "
+                                   "in_dim %d) is not supported by the learner", policy->value_in_dim, policy->in_dim);
   if (max_rows < 1) return fail(MSRL_EINVAL, "msrl_learner_init: max_rows must be positive");
   msrl_learner* L = new (std::nothrow) msrl_learner;
   if (!L) return fail(MSRL_ENOMEM, "msrl_learner_init: host allocation failed");

@@ -101,6 +101,9 @@ struct PackJob {
   // per chunk block, so its tiles follow the layer-2 tiles of the chunk they consume.
   int group, chunk_stride, slot_base;
   int in_map, out_map, gauss_k;
+  // packed input i reads source input (i / in_block) * in_block_stride + i % in_block (in_block = 0: i itself):
+  // the joint observation of a centralised critic without the zero slots of every agent's row
+  int in_block, in_block_stride;
 };
 
 struct PackJobs {

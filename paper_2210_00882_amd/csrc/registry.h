@@ -69,4 +69,8 @@ KernelEntry entry_p3_h64_bf16_deep();
 KernelEntry entry_p10_h256_bf16_deep();
 KernelEntry entry_l17_6_h256_deep();
 
+// centralised critic (value network on the joint observation of an env)
+KernelEntry entry_p3_h64_bf16_central();
+KernelEntry entry_p10_h256_bf16_central();
+
 }  // namespace msrl

@@ -50,6 +50,7 @@ struct RolloutArgs {
   const float* obs_in;     // PHASE_ACT: observation rows [M, D] to act on
   const void* actions_in;  // PHASE_STEP: actions [M] to apply
   int layers;              // hidden layers of both networks (>= 2; kernels other than PHASE_DEEP take 2)
+  const uint8_t* critic;   // PHASE_CENTRAL: packed value network on the joint observation (NetLayout of N * NZ inputs)
 };
 
 // Copies the layer-1 tiles and the output biases of both packed networks into LDS (once per kernel).
@@ -115,7 +116,12 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 //              the further hidden layers run between layer 1 and the last hidden layer, their chunk
 //              blocks coming through the same LDS window.
 enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHASE_ACT = 4, PHASE_STEP = 5,
-             PHASE_DEEP = 6 };
+             PHASE_DEEP = 6, PHASE_CENTRAL = 7 };
+//   PHASE_CENTRAL  the full kernel with a centralised critic (bf16 networks): the policy network as
+//              usual; the value network takes the joint observation of an env (RolloutArgs::critic
+//              holds its tiles) and is evaluated once per env by the workgroup as a whole: the
+//              joint observations of its envs are the columns of one MFMA tile, and wave w computes
+//              the 32-unit chunk w of each layer, the layers meeting in LDS.
 // stamps: start of the step, observation rows built and stored, policy layer 1 done (after the
 // stage barrier that precedes it), policy stage s done (s < 5), same for the value network,
 // logits and values ready, sampling and move done, end of the step
@@ -137,13 +143,19 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int NZ = 4 * N + 2;
   constexpr int KT1 = BF16 ? (NZ + 1 + 15) / 16 : (NZ + 1 + 7) / 8;
   constexpr int NBUF = 2;             // LDS window: the stage in use and the one being copied
-  constexpr int CPS = BF16 && H >= 64 ? 2 : 1;  // chunk blocks per stage (fewer barriers when they fit)
+  constexpr bool CENTRAL = PHASE == PHASE_CENTRAL;
+  // chunk blocks per stage (fewer barriers when they fit; the centralised critic needs the LDS)
+  constexpr int CPS = BF16 && H >= 64 && !CENTRAL ? 2 : 1;
   typedef Mlp<H, BF16, NB, KT1> Net;
   typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   typedef typename Net::Op Op;
   static_assert(EPW >= 1, "a wave must hold at least one env");
   constexpr bool DEEP = PHASE == PHASE_DEEP;
-  constexpr bool FULL = PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS || DEEP;
+  constexpr bool FULL = PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS || DEEP || CENTRAL;
+  static_assert(!CENTRAL || (BF16 && WAVES == Net::NUC), "centralised critic: bf16, one wave per 32-unit chunk");
+  constexpr int KT1C = (N * NZ + 1 + 15) / 16;  // tiles of the joint observation (+ the constant 1)
+  constexpr int JCOLS = WAVES * EPW;            // envs of a workgroup = columns of the critic's tile
+  static_assert(!CENTRAL || JCOLS <= 32, "the envs of a workgroup are the columns of one tile");
   constexpr bool HAS_NETS = PHASE != PHASE_ENV && PHASE != PHASE_STEP;     // the variant runs the networks
   constexpr bool STORES_OBS = PHASE != PHASE_MLP && PHASE != PHASE_ACT;    // ... stores observation rows
   static_assert(NB == 1, "the observation staging below assumes one 32-row block per wave");
@@ -162,7 +174,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   // as their registers allow)
   constexpr int L1_SLOTS = HAS_NETS ? Net::L1_TILES * 64 : 1;
   constexpr int W_SLOTS = HAS_NETS ? NBUF * Stream::BUF_SLOTS : 1;
-  __shared__ __attribute__((aligned(16))) u32x4 s_l1[2][L1_SLOTS];  // resident layer-1 tiles
+  __shared__ __attribute__((aligned(16))) u32x4 s_l1[CENTRAL ? 1 : 2][L1_SLOTS];  // resident layer-1 tiles
+  // centralised critic: joint observations as B-operand tiles, the layer outputs as tiles, partial values
+  __shared__ __attribute__((aligned(16))) u32x4 s_j[CENTRAL ? KT1C * 64 : 1];
+  __shared__ __attribute__((aligned(16))) u32x4 s_hc[CENTRAL ? Net::KT2 * 64 : 1];
+  __shared__ float s_vpart[CENTRAL ? WAVES : 1][32];
   __shared__ __attribute__((aligned(16))) u32x4 s_w[W_SLOTS];       // chunk-block window
   __shared__ __attribute__((aligned(16))) float s_b3[2][32];
   __shared__ __attribute__((aligned(16))) float s_stg[WAVES][STG];
@@ -191,14 +207,32 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   ws.wave = wave;
   ws.lane = lane;
   if constexpr (DEEP) ws.stages_per_net = (layers - 1) * Stream::STAGES_PER_NET;
+  const NetLayout lyc = net_layout(N * NZ, H, true);  // the critic's image (PHASE_CENTRAL)
   if constexpr (HAS_NETS) {
 #pragma unroll
     for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
-    load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
+    if constexpr (CENTRAL) {
+      const u32x4* src = (const u32x4*)(a.packed + ly.w1);
+      for (int i = threadIdx.x; i < Net::L1_TILES * 64; i += blockDim.x) s_l1[0][i] = src[i];
+      if (threadIdx.x < 32) {
+        s_b3[0][threadIdx.x] = *(const float*)(a.packed + ly.b3 + threadIdx.x * 4);
+        s_b3[1][threadIdx.x] = *(const float*)(a.critic + lyc.b3 + threadIdx.x * 4);
+      }
+      // joint observations: zero, except the constant 1 at input N * NZ (bias) of every column
+      for (int i = threadIdx.x; i < KT1C * 64 * 4; i += blockDim.x) ((uint32_t*)s_j)[i] = 0u;
+    } else {
+      load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
+    }
   }
   // features the lanes never write (>= the layer-1 tile range) stay zero for the whole kernel
   for (int i = threadIdx.x; i < WAVES * STG; i += blockDim.x) (&s_stg[0][0])[i] = 0.0f;
   __syncthreads();
+  if constexpr (CENTRAL) {
+    constexpr int kb = N * NZ;  // input index of the constant 1
+    if (threadIdx.x < 32)
+      ((uint16_t*)s_j)[(((kb / 16) * 64 + ((kb % 16) / 8) * 32 + (int)threadIdx.x) * 8) + kb % 8] = 0x3F80;  // bf16 1.0
+    __syncthreads();
+  }
 
   // envs of this workgroup: [blk0, blk0 + envs_per_block); of this wave: EPW of them
   const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
@@ -391,6 +425,21 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           wave_lds_sync();
         }
       }
+      if constexpr (CENTRAL) {
+        // this row's features as inputs N Z * agent + f of column (env) `col` of the joint observation
+        const int col = wave * EPW + base[q] / N;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+          const int f = feat(i);
+          if (valid[q] && f < NZ) {
+            const int k = NZ * ag[q] + f;
+            const f32x2 two = {pr[i].x, pr[i].y};
+            const bf16x2 b = __builtin_convertvector(two, bf16x2);
+            ((uint32_t*)s_j)[((k >> 4) * 64 + ((k & 15) >> 3) * 32 + col) * 4 + ((k & 7) >> 1)] =
+                __builtin_bit_cast(uint32_t, b);
+          }
+        }
+      }
       if constexpr (BF16) {
 #pragma unroll
         for (int kt = 0; kt < KT1; ++kt) {
@@ -414,20 +463,21 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       for (int q = 0; q < NB; ++q) out_p[q] = out_v[q] = zero16();
     } else {
       Op h1[NB][Net::KT2 * Net::PT];
-      if constexpr (DEEP) {
+      if constexpr (DEEP || CENTRAL) {
         const int spn = ws.stages_per_net;
+        constexpr int NETS = CENTRAL ? 1 : 2;  // networks that come through the window
 #pragma unroll 1
-        for (int net = 0; net < 2; ++net) {
+        for (int net = 0; net < NETS; ++net) {
           f32x16(&out)[NB] = net == 0 ? out_p : out_v;
           if (net == 1) {
             ws.wait_oldest();
             if (t > 0) flush(t - 1, 0x1f);
           }
-          Net::layer1(&s_l1[net][0] + lane, x, h1);
+          Net::layer1(&s_l1[CENTRAL ? 0 : net][0] + lane, x, h1);
           int sn = 0;  // stage within the network
           auto prefetch_target = [&](int& next, int& nbuf) {
             next = net * spn + sn + Stream::AHEAD;
-            if (next >= 2 * spn) next -= 2 * spn;
+            if (next >= NETS * spn) next -= NETS * spn;
             nbuf = (gs + Stream::AHEAD) % NBUF;
           };
           f32x16 acc[NB];
@@ -512,6 +562,72 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             }
             ++gs;
             ++sn;
+          }
+        }
+        if constexpr (CENTRAL) {
+          // ---------------- centralised critic: the joint observations of the workgroup's envs are the
+          // columns of one tile; this wave computes the 32-unit chunk `wave` of each hidden layer.  Its
+          // weight tiles are nobody else's, so they come straight from global memory (L2), a few ahead.
+          const u32x4* cw = (const u32x4*)a.critic + lane;  // this lane's slot of tile 0
+          constexpr int G = KT1C < 4 ? KT1C : 4;  // tile loads in flight
+          static_assert(Net::KT2 + 1 >= G, "prefetch depth");
+          f32x16 acc = zero16();
+          {
+            const u32x4* t1 = cw + (size_t)wave * KT1C * 64;
+            u32x4 ring[G];
+#pragma unroll
+            for (int i = 0; i < G; ++i) ring[i] = t1[i * 64];
+#pragma unroll
+            for (int kt = 0; kt < KT1C; ++kt) {
+              const u32x4 raw = ring[kt % G];
+              if (kt + G < KT1C) ring[kt % G] = t1[(kt + G) * 64];
+              acc = mma(__builtin_bit_cast(bf16x8, raw), __builtin_bit_cast(bf16x8, s_j[kt * 64 + lane]), acc);
+            }
+          }
+          {
+            float tt[16];
+            Op hc[2];
+            tanh_range(acc, tt, 0, 16, false);
+            to_operands<true>(tt, hc);
+            s_hc[(2 * wave) * 64 + lane] = __builtin_bit_cast(u32x4, hc[0]);
+            s_hc[(2 * wave + 1) * 64 + lane] = __builtin_bit_cast(u32x4, hc[1]);
+          }
+          __syncthreads();  // layer 1 of the critic is complete
+          if (t > 0) flush(t - 1, 0x1f);
+          const u32x4* t2 = cw + (lyc.chunks / 1024 + (size_t)wave * Net::CHUNK_TILES) * 64;
+          acc = zero16();
+          {
+            u32x4 ring[G];
+#pragma unroll
+            for (int i = 0; i < G; ++i) ring[i] = t2[i * 64];
+#pragma unroll
+            for (int kt = 0; kt <= Net::KT2; ++kt) {
+              const u32x4 raw = ring[kt % G];
+              if (kt + G <= Net::KT2) ring[kt % G] = t2[(kt + G) * 64];
+              const Op b = kt < Net::KT2 ? __builtin_bit_cast(bf16x8, s_hc[kt * 64 + lane]) : Operand<true>::one(h);
+              acc = mma(__builtin_bit_cast(bf16x8, raw), b, acc);
+            }
+          }
+          {
+            float tt[16];
+            Op h2c[2];
+            tanh_range(acc, tt, 0, 16, false);
+            to_operands<true>(tt, h2c);
+            f32x16 ov = zero16();  // this chunk's share of the output layer
+#pragma unroll
+            for (int i = 0; i < Net::TPC; ++i)
+              ov = mma(__builtin_bit_cast(bf16x8, t2[(Net::L3_OWN + i) * 64]), h2c[i], ov);
+            if (h == 0) s_vpart[wave][n] = ov[0];  // output 0 of column n
+          }
+          __syncthreads();
+#pragma unroll
+          for (int q = 0; q < NB; ++q) {
+            const int col = wave * EPW + base[q] / N;
+            float vsum = s_b3[1][0];
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) vsum += s_vpart[w][col];
+            out_v[q] = zero16();
+            out_v[q][0] = vsum;
           }
         }
       } else {

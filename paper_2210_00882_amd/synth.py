@@ -46,6 +46,7 @@ class Config:
     env_seed: int = 0
     param_seed: int = 0
     hidden_layers: int = 2   # tanh layers of `hidden` units in front of the output layer
+    central_critic: bool = False   # value net on the joint observation of the env's agents (one value per env)
     # pursuit ("tag") env: the first num_chasers agents chase the others; one parameter set per role
     num_chasers: int = 0
     accel_c: float = 3.0
@@ -75,7 +76,11 @@ class Config:
     @property
     def param_count(self) -> int:
         return self.roles * (net_param_count(self.obs_dim, self.hidden, self.out_dim, self.hidden_layers) +
-                             net_param_count(self.obs_dim, self.hidden, 1, self.hidden_layers))
+                             net_param_count(self.value_in_dim, self.hidden, 1, self.hidden_layers))
+
+    @property
+    def value_in_dim(self) -> int:
+        return self.num_agents * self.obs_dim if self.central_critic else self.obs_dim
 
     def with_(self, **kw) -> "Config":
         d = dict(self.__dict__)
@@ -123,8 +128,8 @@ def make_params(cfg: Config, bias_std: float = 0.0, seed: int | None = None) -> 
     value is rounded to a bfloat16-representable float32."""
     rng = np.random.default_rng(cfg.param_seed if seed is None else seed)
     parts = []
-    for out in (cfg.out_dim, 1) * cfg.roles:
-        dims = [cfg.obs_dim] + [cfg.hidden] * cfg.hidden_layers + [out]
+    for k, out in enumerate((cfg.out_dim, 1) * cfg.roles):   # per role: policy net, value net
+        dims = [cfg.value_in_dim if k % 2 else cfg.obs_dim] + [cfg.hidden] * cfg.hidden_layers + [out]
         for fan_in, fan_out in zip(dims[:-1], dims[1:]):
             parts.append((rng.standard_normal((fan_in, fan_out)) / np.sqrt(fan_in)).ravel())
             parts.append(rng.standard_normal(fan_out) * bias_std)

@@ -48,7 +48,8 @@ def oracle_setup(cfg: synth.Config, bias_std=0.1, params=None):
         env = ref.Env(ref.LINGAUSS, 1, 0, cfg.obs_dim, cfg.act_dim, cfg.episode_len, A=dyn[0], B=dyn[1],
                       noise_std=np.float32(cfg.noise_std), act_cost=np.float32(cfg.act_cost))
     pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist,
-                     hidden_layers=cfg.hidden_layers)
+                     hidden_layers=cfg.hidden_layers,
+                     value_in_dim=cfg.value_in_dim if cfg.central_critic else 0)
     if params is None:
         params = synth.make_params(cfg, bias_std=bias_std)
     return env, pol, np.asarray(params, dtype=np.float64), dyn
@@ -141,10 +142,18 @@ def check_trajectory(cfg, tr, env, pol, params, seed, env_ids, g0, T, mlp_rows_c
                 s = o_gpu[0].astype(np.float64)
             # networks on the GPU's own observation rows
             do_mlp = mlp_rows_cap is None or rng.random() < mlp_rows_cap
+            central = getattr(cfg, "central_critic", False)
+            if central and do_mlp:  # one value per env, from the joint observation, on every row of the env
+                v_env = ref.central_value(pol, params, o_gpu)
             for i in range(N):
                 m = r0 + i
                 if do_mlp:
-                    lg, v = ref.policy_value(pol, params, o_gpu[i])
+                    if central:
+                        lg = ref.mlp(pol.in_dim, pol.hidden, pol.out_dim, params[:pol.policy_param_count], o_gpu[i],
+                                     bf16=cfg.dtype == synth.BF16)
+                        v = v_env
+                    else:
+                        lg, v = ref.policy_value(pol, params, o_gpu[i])
                     assert_close(tr["values"][t, m], v, net_tol, f"value env {e} agent {i} t {t}")
                     if t < T and tr.get("logits") is not None:
                         assert_close(tr["logits"][t, m], lg, net_tol, f"logits env {e} agent {i} t {t}")
