@@ -32,6 +32,8 @@ PEAK_HBM_GBS = 8000.0
 def mlp_flops_per_agent_step(cfg) -> int:
     """2 * MACs of the un-padded policy and value networks."""
     d, h, hh = cfg.obs_dim, cfg.hidden, (cfg.hidden_layers - 1) * cfg.hidden * cfg.hidden
+    if getattr(cfg, "central_critic", False):  # the value network runs once per env, on N * d inputs
+        return 2 * (d * h + hh + h * cfg.out_dim) + 2 * (cfg.value_in_dim * h + hh + h) // cfg.num_agents
     return 2 * ((d * h + hh + h * cfg.out_dim) + (d * h + hh + h))
 
 
@@ -271,6 +273,30 @@ def main():
                                                  "frac": tf / PEAK_TFLOPS[dt_name],
                                                  "agent_steps_per_s": agent_steps / (ms * 1e-3)}
             del dp
+        except B.MsrlError:
+            pass
+
+        # the same rollout with a centralised critic (multi-agent PPO, section 2.1 of the paper): the value
+        # network takes the joint observation of an env and runs once per env
+        try:
+            cen = cfg.with_(central_critic=True)
+            cstate = B.msrl_rollout_init(env_cfg, B.make_policy_cfg(cen), seed)
+            cp = B.upload_params(cen, synth.make_params(cen))
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for k in range(4):
+                if k == 1:
+                    ev0.record()
+                B.msrl_rollout_step(cstate, cp, T, out)
+            ev1.record()
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1) / 3
+            B.msrl_rollout_destroy(cstate)
+            tf = mlp_flops_per_agent_step(cen) * agent_steps / (ms * 1e-3) / 1e12
+            phases["rollout_central_critic"] = {"bound": "mfma", "ms_per_launch": ms, "achieved": tf,
+                                                "peak": PEAK_TFLOPS[dt_name], "unit": "TFLOP/s",
+                                                "frac": tf / PEAK_TFLOPS[dt_name],
+                                                "agent_steps_per_s": agent_steps / (ms * 1e-3)}
+            del cp
         except B.MsrlError:
             pass
 

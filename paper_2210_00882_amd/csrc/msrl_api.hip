@@ -188,7 +188,9 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     const bool joint = st->central && net == 1;
     const NetLayout& L = joint ? st->critic_layout : st->layout;
     const int in_rows = net % 2 == 1 ? value_in_of(p) : p.in_dim;
-    const int in_used = joint ? st->env.num_agents * st->in_used : st->in_used;
+    // joint observation: per agent a block of whole layer-1 tiles, the row's non-zero prefix at its start
+    const int block = tiles_for_inputs(st->in_used + 1, bf16) * (bf16 ? 16 : 8);
+    const int in_used = joint ? st->env.num_agents * block : st->in_used;
     uint8_t* dst = st->packed + (size_t)net * st->layout.bytes;
     const int layers = layers_of(p);
     const size_t hh = (size_t)p.hidden * p.hidden * esz, hb = (size_t)p.hidden * esz;
@@ -202,9 +204,10 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     // only the inputs that can be non-zero are packed (a prefix of the rows of W1)
     PackJob j1 = weight_job(W1, dst + L.w1, bf16, in_used, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
     j1.bias = b1;  // the bias is the input after them; the kernels feed 1 there
-    j1.bias_index = in_used;
-    if (joint) {  // the non-zero prefix of every agent's row, one after the other
-      j1.in_block = st->in_used;
+    j1.bias_index = joint ? st->in_used : in_used;  // (joint: in the padding of the first agent's block)
+    if (joint) {
+      j1.in_block = block;
+      j1.in_block_used = st->in_used;
       j1.in_block_stride = p.in_dim;
     }
     jobs.job[jobs.n++] = j1;
@@ -456,7 +459,8 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
   const int n_nets = 2 * roles_of(*policy);
   st->layout = net_layout(st->in_used, policy->hidden, policy->dtype == MSRL_BF16, layers_of(*policy));
   st->central = central_of(*policy);
-  st->critic_layout = net_layout(env->num_agents * st->in_used, policy->hidden, true);
+  // (joint observation: num_agents blocks of whole layer-1 tiles, see pack_params)
+  st->critic_layout = net_layout(env->num_agents * tiles_for_inputs(st->in_used + 1, true) * 16 - 1, policy->hidden, true);
   const size_t packed_bytes = st->central ? st->layout.bytes + st->critic_layout.bytes : n_nets * st->layout.bytes;
 
   int rc = MSRL_OK;

@@ -57,10 +57,14 @@ __global__ void pack_kernel(PackJobs jobs) {
   for (int e = 0; e < ne; ++e) {
     const int i = in_index(j.in_map, bf16, kt, h, e);
     v[e] = 0.0f;
-    if (o >= 0 && i < j.n_in) {
-      const int li = j.in_block > 0 ? (i / j.in_block) * j.in_block_stride + i % j.in_block : i;
-      v[e] = load_src(j.src, j.src_bf16, j.src_out_major ? o * j.n_in + li : li * j.n_out + o);
+    bool weight = i < j.n_in;
+    int li = i;
+    if (j.in_block > 0) {
+      weight = weight && i % j.in_block < j.in_block_used;
+      li = (i / j.in_block) * j.in_block_stride + i % j.in_block;
     }
+    if (o >= 0 && weight)
+      v[e] = load_src(j.src, j.src_bf16, j.src_out_major ? o * j.n_in + li : li * j.n_out + o);
     else if (o >= 0 && j.bias && i == j.bias_index)
       v[e] = load_src(j.bias, j.src_bf16, o);
   }

@@ -101,9 +101,11 @@ struct PackJob {
   // per chunk block, so its tiles follow the layer-2 tiles of the chunk they consume.
   int group, chunk_stride, slot_base;
   int in_map, out_map, gauss_k;
-  // packed input i reads source input (i / in_block) * in_block_stride + i % in_block (in_block = 0: i itself):
-  // the joint observation of a centralised critic without the zero slots of every agent's row
-  int in_block, in_block_stride;
+  // in_block > 0: the packed inputs come in blocks of in_block; input i reads source input
+  // (i / in_block) * in_block_stride + i % in_block if i % in_block < in_block_used and is zero otherwise
+  // (the joint observation of a centralised critic: per agent, the non-zero prefix of its row padded to
+  // whole tiles; the bias sits in the padding of the first block, at bias_index)
+  int in_block, in_block_used, in_block_stride;
 };
 
 struct PackJobs {

@@ -153,7 +153,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr bool DEEP = PHASE == PHASE_DEEP;
   constexpr bool FULL = PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS || DEEP || CENTRAL;
   static_assert(!CENTRAL || (BF16 && WAVES == Net::NUC), "centralised critic: bf16, one wave per 32-unit chunk");
-  constexpr int KT1C = (N * NZ + 1 + 15) / 16;  // tiles of the joint observation (+ the constant 1)
+  // The joint observation is laid out as one block of KT1 tiles per agent, the agent's row exactly as the
+  // policy's layer 1 takes it (its constant 1 at input NZ included: agent 0's carries the critic's bias).
+  constexpr int KT1C = N * KT1;
   constexpr int JCOLS = WAVES * EPW;            // envs of a workgroup = columns of the critic's tile
   static_assert(!CENTRAL || JCOLS <= 32, "the envs of a workgroup are the columns of one tile");
   constexpr bool HAS_NETS = PHASE != PHASE_ENV && PHASE != PHASE_STEP;     // the variant runs the networks
@@ -178,6 +180,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   // centralised critic: joint observations as B-operand tiles, the layer outputs as tiles, partial values
   __shared__ __attribute__((aligned(16))) u32x4 s_j[CENTRAL ? KT1C * 64 : 1];
   __shared__ __attribute__((aligned(16))) u32x4 s_hc[CENTRAL ? Net::KT2 * 64 : 1];
+  __shared__ __attribute__((aligned(16))) u32x4 s_w3c[CENTRAL ? WAVES * Net::TPC * 64 : 1];  // its output-layer tiles
   __shared__ float s_vpart[CENTRAL ? WAVES : 1][32];
   __shared__ __attribute__((aligned(16))) u32x4 s_w[W_SLOTS];       // chunk-block window
   __shared__ __attribute__((aligned(16))) float s_b3[2][32];
@@ -193,7 +196,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   __shared__ float s_out[4][WGR];
   __shared__ __attribute__((aligned(4))) uint8_t s_done[WGR];
 
-  const int lane = threadIdx.x & 63;
+  int lane = threadIdx.x & 63;  // (not const: the centralised-critic variant hides it from the optimiser once per step)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: lives in a scalar register
   const int n = lane & 31, h = lane >> 5;
   const int layers = DEEP ? a.layers : 2;
@@ -207,7 +210,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   ws.wave = wave;
   ws.lane = lane;
   if constexpr (DEEP) ws.stages_per_net = (layers - 1) * Stream::STAGES_PER_NET;
-  const NetLayout lyc = net_layout(N * NZ, H, true);  // the critic's image (PHASE_CENTRAL)
+  const NetLayout lyc = net_layout(KT1C * 16 - 1, H, true);  // the critic's image (PHASE_CENTRAL): KT1C layer-1 tiles
   if constexpr (HAS_NETS) {
 #pragma unroll
     for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
@@ -218,7 +221,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         s_b3[0][threadIdx.x] = *(const float*)(a.packed + ly.b3 + threadIdx.x * 4);
         s_b3[1][threadIdx.x] = *(const float*)(a.critic + lyc.b3 + threadIdx.x * 4);
       }
-      // joint observations: zero, except the constant 1 at input N * NZ (bias) of every column
+#pragma unroll
+      for (int i = 0; i < Net::TPC; ++i)  // every wave keeps the output-layer tiles of its own chunk
+        s_w3c[(wave * Net::TPC + i) * 64 + lane] =
+            ((const u32x4*)(a.critic + lyc.chunks + ((size_t)wave * Net::CHUNK_TILES + Net::L3_OWN + i) * 1024))[lane];
+      // joint observations: columns without an env stay zero
       for (int i = threadIdx.x; i < KT1C * 64 * 4; i += blockDim.x) ((uint32_t*)s_j)[i] = 0u;
     } else {
       load_resident(&s_l1[0][0], &s_b3[0][0], a.packed, ly, Net::L1_TILES);
@@ -227,13 +234,6 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   // features the lanes never write (>= the layer-1 tile range) stay zero for the whole kernel
   for (int i = threadIdx.x; i < WAVES * STG; i += blockDim.x) (&s_stg[0][0])[i] = 0.0f;
   __syncthreads();
-  if constexpr (CENTRAL) {
-    constexpr int kb = N * NZ;  // input index of the constant 1
-    if (threadIdx.x < 32)
-      ((uint16_t*)s_j)[(((kb / 16) * 64 + ((kb % 16) / 8) * 32 + (int)threadIdx.x) * 8) + kb % 8] = 0x3F80;  // bf16 1.0
-    __syncthreads();
-  }
-
   // envs of this workgroup: [blk0, blk0 + envs_per_block); of this wave: EPW of them
   const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
   const int64_t blk_end = min(blk0 + (int64_t)a.envs_per_block, (int64_t)a.E);
@@ -316,6 +316,97 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 
 
   int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % NBUF
+
+  // Centralised critic (PHASE_CENTRAL).  The joint observations of the workgroup's envs are the
+  // columns of one tile, and this wave computes the 32-unit chunk `wave` of each hidden layer.  Those
+  // weight tiles are nobody else's, so they come straight from global memory (L2) into registers, one
+  // policy stage ahead of the MFMAs that use them: every stage barrier already waits for all loads of
+  // the wave, and the stage in between covers their latency.  The value is no input of the env step,
+  // so nothing waits for it, and the critic rides on the policy's stages with one accumulator and
+  // RING tile registers:
+  //   step t,   stages S2 .. SPN-1  layer 1 on the joint observation of step t (the barrier of stage 1
+  //                                 is the first one behind its writes);
+  //   end of the policy stages      tanh, outputs to LDS (s_hc);
+  //   step t+1, stages 0 .. S2-1    layer 2;
+  //   step t+1, stage S2            tanh, output layer (tiles resident in LDS): the chunk's share of
+  //                                 the value to s_vpart;
+  //   step t+2, top                 every wave adds the shares of its envs; the values go out with the
+  //                                 other per-row outputs at the barrier of stage 1.
+  // The last step's layers 2 and 3 run behind the loop.
+  constexpr int SPN = Stream::STAGES_PER_NET;
+  static_assert(!CENTRAL || SPN >= 2, "the critic rides on the policy stages");
+  constexpr int L2T = Net::KT2 + 1;  // layer-2 tiles of a chunk, the bias tile included
+  constexpr int S2_ = (SPN * L2T + (L2T + KT1C) / 2) / (L2T + KT1C);  // stages in proportion to the tiles
+  constexpr int S2 = S2_ < 1 ? 1 : (S2_ > SPN - 1 ? SPN - 1 : S2_);
+  constexpr int S1 = SPN - S2;
+  constexpr int RING = !CENTRAL ? 1 : ((L2T + S2 - 1) / S2 > (KT1C + S1 - 1) / S1 ? (L2T + S2 - 1) / S2 : (KT1C + S1 - 1) / S1);
+  // uniform base addresses (scalar registers) of the chunk's layer-1 tiles and of its chunk block; the
+  // lanes add 16 lane.  A fetch of RING tiles may reach past the tiles of its layer: it stays inside
+  // the image (chunk blocks follow the layer-1 tiles, a block is longer than its layer-2 tiles), and
+  // the surplus is not used.
+  static_assert(!CENTRAL || (S2 * RING <= Net::CHUNK_TILES && S1 * RING - KT1C <= Net::CHUNK_TILES), "fetch range");
+  const uint8_t* t1 = a.critic + (size_t)wave * KT1C * 1024;
+  const uint8_t* t2 = a.critic + lyc.chunks + (size_t)wave * Net::CHUNK_TILES * 1024;
+  const uint32_t lane16 = (uint32_t)lane * 16u;
+  // Fetch of tiles [0, CNT) behind a base address into dst[0 .. CNT).  Left alone, the compiler
+  // computes 64-bit vector addresses and keeps them in registers.  So the lane offset and the scalar
+  // address of every group of four tiles (the reach of the immediate offset) are made opaque at every
+  // fetch: a load then takes a scalar base, one 32-bit lane offset and an immediate.
+  auto fetch_tiles = [&](const uint8_t* base, auto cnt, u32x4* dst) {
+    typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
+    constexpr int CNT = decltype(cnt)::value;
+    uint32_t off = lane16;
+    asm volatile("" : "+v"(off));
+#pragma unroll
+    for (int g = 0; g < (CNT + 3) / 4; ++g) {
+      uint64_t gb = (uint64_t)(uintptr_t)base + (uint64_t)(4 * g) * 1024;
+      // (uniform: make it scalar; the builtin returns a signed int, which must not sign-extend into the high half)
+      gb = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)gb) |
+           (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(gb >> 32)) << 32;
+      asm volatile("" : "+s"(gb));
+#pragma unroll
+      for (int i = 4 * g; i < 4 * g + 4 && i < CNT; ++i) dst[i] = *(global_u32x4*)(gb + (uint64_t)(i - 4 * g) * 1024 + off);
+    }
+  };
+  f32x16 cacc = zero16();
+  u32x4 cring[RING];
+  // layer-2 tile kt of the chunk times the layer-1 outputs in s_hc (the bias tile times the constant 1)
+  auto critic_l2_tile = [&](const u32x4& w, int kt, f32x16& c) {
+    const bf16x8 b = kt < Net::KT2 ? __builtin_bit_cast(bf16x8, s_hc[kt * 64 + lane]) : Operand<true>::one(h);
+    c = mma(__builtin_bit_cast(bf16x8, w), b, c);
+  };
+  // tanh of the chunk's layer-2 sums and the output layer: the chunk's share of the value of column lane % 32
+  auto critic_l3 = [&](const f32x16& c) {
+    float tt[16];
+    bf16x8 h2c[2];
+    tanh_range(c, tt, 0, 16, false);
+    to_operands<true>(tt, h2c);
+    f32x16 ov = zero16();
+#pragma unroll
+    for (int i = 0; i < Net::TPC; ++i)
+      ov = mma(__builtin_bit_cast(bf16x8, s_w3c[(wave * Net::TPC + i) * 64 + lane]), h2c[i], ov);
+    if (h == 0) s_vpart[wave][n] = ov[0];  // output 0: register 0 of the h = 0 lanes
+  };
+  // tanh of the chunk's layer-1 sums; outputs (as the next layer's operand tiles) to s_hc
+  auto critic_l1_publish = [&](const f32x16& c) {
+    float tt[16];
+    bf16x8 hc[2];
+    tanh_range(c, tt, 0, 16, false);
+    to_operands<true>(tt, hc);
+    s_hc[(2 * wave) * 64 + lane] = __builtin_bit_cast(u32x4, hc[0]);
+    s_hc[(2 * wave + 1) * 64 + lane] = __builtin_bit_cast(u32x4, hc[1]);
+  };
+  // value of the rows' envs from the shares in s_vpart
+  auto collect_values = [&]() {
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      const int col = wave * EPW + base[q] / N;
+      float vsum = s_b3[1][0];
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) vsum += s_vpart[w][col];
+      if (h == 0 && valid[q]) s_out[0][wrow0 + row[q]] = vsum;
+    }
+  };
   float checksum[NB] = {};      // PHASE_MLP only
 
   long long clk0 = 0;
@@ -330,6 +421,14 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       }
     };
     stamp(CLK_START);
+    if constexpr (CENTRAL) {
+      // The compiler moves every address and constant that does not change over the steps in front of
+      // the loop; with the critic's registers on top they no longer fit and would be reloaded from
+      // scratch memory step by step.  Hiding the lane's indices from it once per step keeps that
+      // arithmetic (a few dozen integer operations) inside the step.  (n, h and the wave's
+      // scalars stay where they are.)
+      asm volatile("" : "+v"(ag[0]), "+v"(base[0]), "+v"(row[0]), "+v"(env[0]), "+v"(lane));
+    }
     if constexpr (!HAS_NETS) {  // (no stage barriers in these variants)
       __syncthreads();
       if (t > 0) flush(t - 1, PHASE == PHASE_STEP ? 0x18 : 0x1f);
@@ -339,6 +438,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       // during the last stage of the step before, and the wait for them also waits for every store
       // the wave still has in flight, so it must not sit behind the observation stores below.
       ws.wait_oldest();
+      if constexpr (CENTRAL) {
+        if (t > 1) collect_values();  // of step t - 2
+      }
     }
     // ---------------- observation rows: build, store (through the staging area), convert to MFMA operands
     Op x[NB][KT1 * Net::PT];
@@ -425,21 +527,6 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           wave_lds_sync();
         }
       }
-      if constexpr (CENTRAL) {
-        // this row's features as inputs N Z * agent + f of column (env) `col` of the joint observation
-        const int col = wave * EPW + base[q] / N;
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-          const int f = feat(i);
-          if (valid[q] && f < NZ) {
-            const int k = NZ * ag[q] + f;
-            const f32x2 two = {pr[i].x, pr[i].y};
-            const bf16x2 b = __builtin_convertvector(two, bf16x2);
-            ((uint32_t*)s_j)[((k >> 4) * 64 + ((k & 15) >> 3) * 32 + col) * 4 + ((k & 7) >> 1)] =
-                __builtin_bit_cast(uint32_t, b);
-          }
-        }
-      }
       if constexpr (BF16) {
 #pragma unroll
         for (int kt = 0; kt < KT1; ++kt) {
@@ -452,6 +539,14 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           if (NZ / 16 == kt && (NZ % 16) / 8 == h) f[NZ % 8] = 1.0f;  // input NZ carries the bias
           x[q][kt] = __builtin_convertvector(f, bf16x8);
         }
+        if constexpr (CENTRAL) {
+          // the same operands are the agent's block of column (env) `col` of the joint observation
+          if (valid[q]) {
+            u32x4* dst = s_j + (ag[q] * KT1) * 64 + h * 32 + wave * EPW + base[q] / N;
+#pragma unroll
+            for (int kt = 0; kt < KT1; ++kt) dst[kt * 64] = __builtin_bit_cast(u32x4, x[q][kt]);
+          }
+        }
       }
     }
 
@@ -463,21 +558,20 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       for (int q = 0; q < NB; ++q) out_p[q] = out_v[q] = zero16();
     } else {
       Op h1[NB][Net::KT2 * Net::PT];
-      if constexpr (DEEP || CENTRAL) {
+      if constexpr (DEEP) {
         const int spn = ws.stages_per_net;
-        constexpr int NETS = CENTRAL ? 1 : 2;  // networks that come through the window
 #pragma unroll 1
-        for (int net = 0; net < NETS; ++net) {
+        for (int net = 0; net < 2; ++net) {
           f32x16(&out)[NB] = net == 0 ? out_p : out_v;
           if (net == 1) {
             ws.wait_oldest();
             if (t > 0) flush(t - 1, 0x1f);
           }
-          Net::layer1(&s_l1[CENTRAL ? 0 : net][0] + lane, x, h1);
+          Net::layer1(&s_l1[net][0] + lane, x, h1);
           int sn = 0;  // stage within the network
           auto prefetch_target = [&](int& next, int& nbuf) {
             next = net * spn + sn + Stream::AHEAD;
-            if (next >= NETS * spn) next -= NETS * spn;
+            if (next >= 2 * spn) next -= 2 * spn;
             nbuf = (gs + Stream::AHEAD) % NBUF;
           };
           f32x16 acc[NB];
@@ -564,72 +658,69 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             ++sn;
           }
         }
-        if constexpr (CENTRAL) {
-          // ---------------- centralised critic: the joint observations of the workgroup's envs are the
-          // columns of one tile; this wave computes the 32-unit chunk `wave` of each hidden layer.  Its
-          // weight tiles are nobody else's, so they come straight from global memory (L2), a few ahead.
-          const u32x4* cw = (const u32x4*)a.critic + lane;  // this lane's slot of tile 0
-          constexpr int G = KT1C < 4 ? KT1C : 4;  // tile loads in flight
-          static_assert(Net::KT2 + 1 >= G, "prefetch depth");
-          f32x16 acc = zero16();
-          {
-            const u32x4* t1 = cw + (size_t)wave * KT1C * 64;
-            u32x4 ring[G];
+      } else if constexpr (CENTRAL) {
+        // ---------------- policy network through the window, the critic riding on its stages
+        Net::layer1(&s_l1[0][0] + lane, x, h1);
+        f32x16 acc[NB];
+        {
+          const f32x16 b = bias_init(s_b3[0], h);
 #pragma unroll
-            for (int i = 0; i < G; ++i) ring[i] = t1[i * 64];
-#pragma unroll
-            for (int kt = 0; kt < KT1C; ++kt) {
-              const u32x4 raw = ring[kt % G];
-              if (kt + G < KT1C) ring[kt % G] = t1[(kt + G) * 64];
-              acc = mma(__builtin_bit_cast(bf16x8, raw), __builtin_bit_cast(bf16x8, s_j[kt * 64 + lane]), acc);
-            }
-          }
-          {
-            float tt[16];
-            Op hc[2];
-            tanh_range(acc, tt, 0, 16, false);
-            to_operands<true>(tt, hc);
-            s_hc[(2 * wave) * 64 + lane] = __builtin_bit_cast(u32x4, hc[0]);
-            s_hc[(2 * wave + 1) * 64 + lane] = __builtin_bit_cast(u32x4, hc[1]);
-          }
-          __syncthreads();  // layer 1 of the critic is complete
-          if (t > 0) flush(t - 1, 0x1f);
-          const u32x4* t2 = cw + (lyc.chunks / 1024 + (size_t)wave * Net::CHUNK_TILES) * 64;
-          acc = zero16();
-          {
-            u32x4 ring[G];
-#pragma unroll
-            for (int i = 0; i < G; ++i) ring[i] = t2[i * 64];
-#pragma unroll
-            for (int kt = 0; kt <= Net::KT2; ++kt) {
-              const u32x4 raw = ring[kt % G];
-              if (kt + G <= Net::KT2) ring[kt % G] = t2[(kt + G) * 64];
-              const Op b = kt < Net::KT2 ? __builtin_bit_cast(bf16x8, s_hc[kt * 64 + lane]) : Operand<true>::one(h);
-              acc = mma(__builtin_bit_cast(bf16x8, raw), b, acc);
-            }
-          }
-          {
-            float tt[16];
-            Op h2c[2];
-            tanh_range(acc, tt, 0, 16, false);
-            to_operands<true>(tt, h2c);
-            f32x16 ov = zero16();  // this chunk's share of the output layer
-#pragma unroll
-            for (int i = 0; i < Net::TPC; ++i)
-              ov = mma(__builtin_bit_cast(bf16x8, t2[(Net::L3_OWN + i) * 64]), h2c[i], ov);
-            if (h == 0) s_vpart[wave][n] = ov[0];  // output 0 of column n
-          }
-          __syncthreads();
-#pragma unroll
-          for (int q = 0; q < NB; ++q) {
-            const int col = wave * EPW + base[q] / N;
-            float vsum = s_b3[1][0];
-#pragma unroll
-            for (int w = 0; w < WAVES; ++w) vsum += s_vpart[w][col];
-            out_v[q] = zero16();
-            out_v[q][0] = vsum;
-          }
+          for (int q = 0; q < NB; ++q) out_p[q] = b;
         }
+#pragma unroll 1
+        for (int sc = 0; sc < SPN; ++sc) {
+          if (sc != 0) {
+            ws.wait_oldest();
+            if (sc == 1 && t > 0) {
+              flush(t - 1, 0x1e);
+              if (t > 1) flush(t - 2, 0x01);
+            }
+          }
+          // critic: the tiles fetched during the stage before
+          if (sc < S2) {
+            if (t > 0) {
+#pragma unroll
+              for (int i = 0; i < RING; ++i)
+                if (sc * RING + i < L2T) critic_l2_tile(cring[i], sc * RING + i, cacc);
+            }
+          } else {
+            if (sc == S2) {
+              if (t > 0) critic_l3(cacc);  // of the step before
+              cacc = zero16();
+            }
+#pragma unroll
+            for (int i = 0; i < RING; ++i) {
+              const int kt = (sc - S2) * RING + i;
+              if (kt < KT1C)
+                cacc = mma(__builtin_bit_cast(bf16x8, cring[i]), __builtin_bit_cast(bf16x8, s_j[kt * 64 + lane]), cacc);
+            }
+          }
+          {
+            // ... and the fetch for the next stage (in the last stage, for stage 0 of the next step)
+            const uint8_t* nb = sc + 1 < S2 ? t2 + (size_t)(sc + 1) * RING * 1024
+                                : sc + 1 < SPN ? t1 + (size_t)(sc + 1 - S2) * RING * 1024 : t2;
+            fetch_tiles(nb, std::integral_constant<int, RING>{}, cring);
+          }
+          int next = sc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
+          if (next >= SPN) next -= SPN;
+          const int nbuf = (gs + Stream::AHEAD) % NBUF;
+          const u32x4* tiles = ws.tiles(gs % NBUF, 0);
+          auto tick = [&](int kt) {
+#pragma unroll
+            for (int i = 0; i < Stream::PER_WAVE; ++i)
+              if (i * Net::KT2 / Stream::PER_WAVE == kt) ws.issue_part(next, nbuf, i);
+          };
+          if (sc == 0)
+            Net::template layer2_chunk<false>(tiles, h1, acc, out_p, h, tick);
+          else
+            Net::template layer2_chunk<true>(tiles, h1, acc, out_p, h, tick);
+          if (sc == SPN - 1) Net::layer2_drain(tiles, acc, out_p);
+          ++gs;
+        }
+        critic_l1_publish(cacc);
+        cacc = zero16();  // layer 2 starts from zero in stage 0 of the next step
+#pragma unroll
+        for (int q = 0; q < NB; ++q) out_v[q] = zero16();
       } else {
   #pragma unroll
         for (int net = 0; net < 2; ++net) {
@@ -684,9 +775,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         checksum[q] += out_v[q][0] + out_p[q][0] + out_p[q][1] + out_p[q][2] + out_p[q][3];
       continue;
     }
+    if constexpr (!CENTRAL) {
 #pragma unroll
-    for (int q = 0; q < NB; ++q)
-      if (h == 0 && valid[q]) s_out[0][wrow0 + row[q]] = out_v[q][0];
+      for (int q = 0; q < NB; ++q)
+        if (h == 0 && valid[q]) s_out[0][wrow0 + row[q]] = out_v[q][0];
+    }
     if (PHASE != PHASE_ACT && t == a.T) break;
 
     // ---------------- sampling, physics
@@ -783,6 +876,22 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   if constexpr (PHASE == PHASE_ACT) {
     flush(0, 0x07);  // values, actions, logp of the one evaluation
     return;          // the env state did not move
+  }
+  if constexpr (CENTRAL) {
+    // values of the last two steps: the shares of step T-1 are in s_vpart; layers 2 and 3 of step T
+    // have no policy stages left to ride on and run here
+    u32x4 wl[L2T];
+    fetch_tiles(t2, std::integral_constant<int, L2T>{}, wl);
+    if (a.T > 0) collect_values();
+    cacc = zero16();
+#pragma unroll
+    for (int kt = 0; kt < L2T; ++kt) critic_l2_tile(wl[kt], kt, cacc);
+    __syncthreads();  // s_out[0] holds the values of step T-1, and nobody reads s_vpart any more
+    if (a.T > 0) flush(a.T - 1, 0x01);
+    critic_l3(cacc);
+    __syncthreads();
+    collect_values();
+    __syncthreads();
   }
   if constexpr (PHASE != PHASE_MLP && PHASE != PHASE_STEP)
     flush(a.T, 0x01);  // values[T]; every earlier step went out inside the loop
