@@ -421,9 +421,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       }
     };
     stamp(CLK_START);
-    if constexpr (CENTRAL) {
+    if constexpr (CENTRAL || DEEP) {
       // The compiler moves every address and constant that does not change over the steps in front of
-      // the loop; with the critic's registers on top they no longer fit and would be reloaded from
+      // the loop; with the registers of these variants on top they no longer fit and would be reloaded from
       // scratch memory step by step.  Hiding the lane's indices from it once per step keeps that
       // arithmetic (a few dozen integer operations) inside the step.  (n, h and the wave's
       // scalars stay where they are.)
