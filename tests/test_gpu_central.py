@@ -28,6 +28,15 @@ def test_p3_central_critic_every_env_and_step(E, T, ep):
     _values_shared_per_env(cfg, tr)
 
 
+@pytest.mark.parametrize("T", [1, 2, 3])
+def test_central_critic_shortest_rollouts(T):
+    # the value leaves the kernel two steps behind the step it belongs to: the shortest rollouts are all tail
+    cfg = synth.particle("p3central", 23, 3, 64, T, 2, dtype=synth.BF16, idx=53).with_(central_critic=True)
+    tr, stats = run_and_check(cfg, T, calls=3)
+    assert stats["mlp_rows"] == 3 * (T + 1) * cfg.M
+    _values_shared_per_env(cfg, tr)
+
+
 def test_central_value_depends_on_every_agents_row():
     # with the critic's layer 1 zero except on the rows of one agent, the value must still change when
     # that agent is the last of the env: a critic that only saw the row's own observation would not
