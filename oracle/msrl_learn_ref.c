@@ -18,7 +18,18 @@
  *   L      = mean_n(Lpi_n + c_v Lv_n - c_e H_n),   H_n = entropy of pi_theta(.|s_n)
  *
  * with the policy and value networks of msrl_ref.c (same parameter layout, same
- * bf16 rounding points in the forward pass, any number of hidden layers).  In bf16 mode the derivative
+ * bf16 rounding points in the forward pass, any number of hidden layers).
+ *
+ * Centralised critic (multi-agent PPO, section 2.1 of the paper; value_in_dim =
+ * G * in_dim): the rows come in groups of G consecutive rows, the agents of one
+ * env at one step; the value network takes the group's rows one after the other
+ * as one input and has one target per group, the return of the group's first row
+ * (with a shared reward and a shared value every row of the group has the same).
+ * The value term is then the mean over the R / G groups:
+ *
+ *   L = mean_n(Lpi_n - c_e H_n) + c_v mean_g (V_theta(s_gG .. s_gG+G-1) - ret_gG)^2
+ *
+ * In bf16 mode the derivative
  * treats every rounding as the identity (straight-through): dL/dW uses the
  * rounded layer input, dL/d(input) uses the rounded weight, nothing else is
  * rounded in the backward pass.  At rho exactly on a clip edge, or where both
@@ -47,7 +58,7 @@ typedef struct {
   int32_t bf16;
   int32_t dist;
   int32_t hidden_layers; /* tanh layers in front of the output layer; 0 means 2 */
-  int32_t value_in_dim;  /* must be 0 or in_dim here: the learner trains both nets on the same rows */
+  int32_t value_in_dim;  /* 0 or in_dim: value net on the row; G * in_dim: centralised critic on groups of G rows */
 } ref_policy_cfg;
 
 typedef struct {
@@ -154,10 +165,12 @@ double ref_ppo_loss(const ref_policy_cfg* p, const ref_ppo_cfg* c, const double*
                     double* stats) {
   const int in = p->in_dim, H = p->hidden, O = p->out_dim, bf = p->bf16;
   const int L = p->hidden_layers > 0 ? p->hidden_layers : 2;
-  const size_t np_pi = ref_net_param_count_l(in, H, O, L), np_v = ref_net_param_count_l(in, H, 1, L);
+  const int in_v = p->value_in_dim > 0 ? p->value_in_dim : in; /* input width of the value net */
+  const int G = in_v / in;                                     /* rows per value-net input */
+  const size_t np_pi = ref_net_param_count_l(in, H, O, L), np_v = ref_net_param_count_l(in_v, H, 1, L);
   const double* Ppi = params;
   const double* Pv = params + np_pi;
-  double* xin = (double*)malloc(sizeof(double) * (size_t)in);
+  double* xin = (double*)malloc(sizeof(double) * (size_t)in_v);
   double* act = (double*)malloc(sizeof(double) * (size_t)H * L);
   double* delta = (double*)malloc(sizeof(double) * (size_t)H * L);
   double* y = (double*)malloc(sizeof(double) * (size_t)O);
@@ -235,25 +248,29 @@ double ref_ppo_loss(const ref_policy_cfg* p, const ref_ppo_cfg* c, const double*
       }
       net_backward(in, H, O, L, Ppi, bf, xin, act, dy, grad, delta);
     }
-    /* ---- value */
+  }
+  /* ---- value: one evaluation per group of G rows (G = 1: per row) */
+  const int64_t Rg = R / G;
+  const double invRg = Rg > 0 ? 1.0 / (double)Rg : 0.0;
+  for (int64_t g = 0; g < Rg; ++g) {
     double v;
-    net_forward(in, H, 1, L, Pv, x, bf, xin, act, &v);
-    const double err = v - ret[n];
+    net_forward(in_v, H, 1, L, Pv, obs + (size_t)g * in_v, bf, xin, act, &v);
+    const double err = v - ret[g * G];
     s_v += err * err;
     if (grad) {
-      const double dv = c->vf_coef * 2.0 * err * invR;
-      net_backward(in, H, 1, L, Pv, bf, xin, act, &dv, grad + np_pi, delta);
+      const double dv = c->vf_coef * 2.0 * err * invRg;
+      net_backward(in_v, H, 1, L, Pv, bf, xin, act, &dv, grad + np_pi, delta);
     }
   }
   free(xin); free(act); free(delta); free(y); free(dy);
   if (stats) {
     stats[0] = s_pi * invR;
-    stats[1] = s_v * invR;
+    stats[1] = s_v * invRg;
     stats[2] = s_h * invR;
     stats[3] = s_clip * invR;
     stats[4] = s_kl * invR;
   }
-  return (s_pi + c->vf_coef * s_v - c->ent_coef * s_h) * invR;
+  return (s_pi - c->ent_coef * s_h) * invR + c->vf_coef * s_v * invRg;
 }
 
 /* One Adam step on n parameters; k is the 1-based step counter of this step. */
@@ -269,7 +286,8 @@ void ref_adam_step(const ref_ppo_cfg* c, double* params, double* m, double* v, c
 
 /*
  * Learner.learn's training loop: `iters` passes over the R rows, each split into `minibatches`
- * consecutive blocks of rows (the last takes the remainder), one Adam step per block.
+ * consecutive blocks of rows (the last takes the remainder; with a centralised critic the blocks
+ * hold whole groups), one Adam step per block.
  * step_counter: Adam steps taken before this call (0 for fresh moments); returns the mean of the
  * minibatch losses (the listing's loss / iter, per minibatch).
  */
@@ -279,10 +297,11 @@ double ref_ppo_update(const ref_policy_cfg* p, const ref_ppo_cfg* c, double* par
                       const double* logp_old, const double* adv, const double* ret) {
   const int L = p->hidden_layers > 0 ? p->hidden_layers : 2;
   const size_t np = ref_net_param_count_l(p->in_dim, p->hidden, p->out_dim, L) +
-                    ref_net_param_count_l(p->in_dim, p->hidden, 1, L);
+                    ref_net_param_count_l(p->value_in_dim > 0 ? p->value_in_dim : p->in_dim, p->hidden, 1, L);
   double* g = (double*)malloc(sizeof(double) * np);
   const int K = p->out_dim / 2;
-  const int64_t block = R / minibatches;
+  const int G = p->value_in_dim > p->in_dim ? p->value_in_dim / p->in_dim : 1;
+  const int64_t block = R / minibatches / G * G; /* whole groups of rows (centralised critic) */
   double total = 0.0;
   for (int it = 0; it < iters; ++it)
     for (int b = 0; b < minibatches; ++b) {

@@ -36,15 +36,17 @@ def torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret):
     P = torch.tensor(params, dtype=torch.float64, requires_grad=True)
     rnd = bf16_ste if pol.bf16 else (lambda t: t)
 
-    def net(p, out):
-        parts, used = split_params(p, pol.in_dim, pol.hidden, out, pol.hidden_layers)
-        h = torch.tensor(obs, dtype=torch.float64)
+    def net(p, out, x, width):
+        parts, used = split_params(p, width, pol.hidden, out, pol.hidden_layers)
+        h = torch.tensor(x, dtype=torch.float64)
         for l in range(pol.hidden_layers):
             h = torch.tanh(rnd(h) @ rnd(parts[2 * l]) + parts[2 * l + 1])
         return rnd(h) @ rnd(parts[-2]) + parts[-1], used
 
-    y, used = net(P, pol.out_dim)
-    v, _ = net(P[used:], 1)
+    obs = np.asarray(obs, dtype=np.float64)
+    y, used = net(P, pol.out_dim, obs, pol.in_dim)
+    G = pol.value_in_dim // pol.in_dim       # > 1: centralised critic on groups of G consecutive rows
+    v, _ = net(P[used:], 1, obs.reshape(-1, pol.value_in_dim), pol.value_in_dim)
     A = torch.tensor(adv, dtype=torch.float64)
     if pol.dist == ref.CATEGORICAL:
         lsm = torch.log_softmax(y, dim=1)
@@ -57,15 +59,16 @@ def torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret):
         ent = dist.entropy().sum(1)
     rho = (logp - torch.tensor(logp_old, dtype=torch.float64)).exp()
     surr = torch.minimum(rho * A, rho.clamp(1 - cfg.clip, 1 + cfg.clip) * A)
-    loss = (-surr + cfg.vf_coef * (v[:, 0] - torch.tensor(ret, dtype=torch.float64)) ** 2 - cfg.ent_coef * ent).mean()
+    target = torch.tensor(np.asarray(ret, dtype=np.float64)[::G].copy(), dtype=torch.float64)
+    loss = (-surr - cfg.ent_coef * ent).mean() + cfg.vf_coef * ((v[:, 0] - target) ** 2).mean()
     loss.backward()
     return float(loss.detach()), P.grad.numpy(), float(ent.mean().detach())
 
 
-def make_case(dist, bf16, seed, R=41, i=6, h=8, K=3, layers=2):
+def make_case(dist, bf16, seed, R=41, i=6, h=8, K=3, layers=2, group=1):
     rng = np.random.default_rng(seed)
     o = 5 if dist == ref.CATEGORICAL else 2 * K
-    pol = ref.Policy(i, h, o, bf16=bf16, dist=dist, hidden_layers=layers)
+    pol = ref.Policy(i, h, o, bf16=bf16, dist=dist, hidden_layers=layers, value_in_dim=group * i if group > 1 else 0)
     params = rng.normal(0, 0.6, pol.param_count)
     obs = rng.normal(0, 1, (R, i))
     if dist == ref.CATEGORICAL:
@@ -78,8 +81,11 @@ def make_case(dist, bf16, seed, R=41, i=6, h=8, K=3, layers=2):
     cfg0 = ref.ppo_cfg()
     _, _, st = ref.ppo_loss(pol, cfg0, params, obs, actions, np.zeros(R), adv, ret, want_grad=False)
     logp_new = np.zeros(R)
+    # (a single row is no whole group: the probe uses the policy network with a per-row value net of zeros)
+    own = ref.Policy(i, h, o, bf16=bf16, dist=dist, hidden_layers=layers)
+    p_own = np.concatenate([params[:pol.policy_param_count], np.zeros(own.param_count - own.policy_param_count)])
     for n in range(R):   # logp of each row from a single-row call with logp_old = 0: stats[4] = -logp
-        _, _, s1 = ref.ppo_loss(pol, cfg0, params, obs[n:n + 1], actions[n:n + 1], np.zeros(1), adv[n:n + 1],
+        _, _, s1 = ref.ppo_loss(own, cfg0, p_own, obs[n:n + 1], actions[n:n + 1], np.zeros(1), adv[n:n + 1],
                                 ret[n:n + 1], want_grad=False)
         logp_new[n] = -s1[4]
     logp_old = logp_new - rng.choice([-0.5, -0.1, 0.0, 0.1, 0.5], R)
@@ -97,6 +103,49 @@ def test_loss_and_gradient_against_autograd(dist, bf16):
     np.testing.assert_allclose(loss, t_loss, rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(stats[2], t_ent, rtol=1e-11)
     np.testing.assert_allclose(grad, t_grad, rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("dist,bf16,group", [(ref.CATEGORICAL, False, 3), (ref.CATEGORICAL, True, 4),
+                                             (ref.DIAG_GAUSSIAN, False, 2)])
+def test_centralised_critic_against_autograd(dist, bf16, group):
+    # the value network on groups of `group` consecutive rows (the agents of an env), one target per group
+    pol, params, obs, actions, logp_old, adv, ret = make_case(dist, bf16, 30 + group, R=12 * group, group=group)
+    assert pol.value_in_dim == group * pol.in_dim
+    cfg = ref.ppo_cfg(clip=0.2, vf_coef=0.7, ent_coef=0.03)
+    loss, grad, stats = ref.ppo_loss(pol, cfg, params, obs, actions, logp_old, adv, ret)
+    t_loss, t_grad, t_ent = torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret)
+    np.testing.assert_allclose(loss, t_loss, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(grad, t_grad, rtol=1e-9, atol=1e-12)
+    assert np.abs(grad[pol.policy_param_count:]).min() >= 0 and np.abs(grad[pol.policy_param_count:]).max() > 1e-4
+    # targets other than the group's first row are not used
+    ret2 = ret.copy()
+    ret2[np.arange(ret.size) % group != 0] += 5.0
+    loss2, grad2, _ = ref.ppo_loss(pol, cfg, params, obs, actions, logp_old, adv, ret2)
+    assert loss2 == loss and (grad2 == grad).all()
+
+
+def test_centralised_critic_reduces_to_the_per_row_value_net():
+    # width in_dim (a group of one row) is the per-row learner; and a critic that looks at the group's first
+    # row only has the value loss and value-net gradient of the per-row learner on those rows
+    group = 3
+    pol, params, obs, actions, logp_old, adv, ret = make_case(ref.CATEGORICAL, False, 41, R=30, group=group)
+    cfg = ref.ppo_cfg(vf_coef=0.9)
+    i, h = pol.in_dim, pol.hidden
+    own = ref.Policy(i, h, pol.out_dim)
+    same = ref.Policy(i, h, pol.out_dim, value_in_dim=i)
+    n_pi = pol.policy_param_count
+    p_own = np.concatenate([params[:n_pi], params[n_pi:n_pi + i * h], params[n_pi + group * i * h:]])
+    a = ref.ppo_loss(own, cfg, p_own, obs, actions, logp_old, adv, ret)
+    b = ref.ppo_loss(same, cfg, p_own, obs, actions, logp_old, adv, ret)
+    assert a[0] == b[0] and (a[1] == b[1]).all()
+    pc = params.copy()
+    pc[n_pi + i * h:n_pi + group * i * h] = 0          # W1 rows of the other agents
+    _, g_c, st_c = ref.ppo_loss(pol, cfg, pc, obs, actions, logp_old, adv, ret)
+    first = slice(0, None, group)
+    _, g_o, st_o = ref.ppo_loss(own, cfg, p_own, obs[first], actions[first], logp_old[first], adv[first], ret[first])
+    np.testing.assert_allclose(st_c[1], st_o[1], rtol=1e-13)
+    np.testing.assert_allclose(g_c[n_pi:n_pi + i * h], g_o[n_pi:n_pi + i * h], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(g_c[n_pi + group * i * h:], g_o[n_pi + i * h:], rtol=1e-12, atol=1e-15)
 
 
 @pytest.mark.parametrize("layers", [1, 3, 5])
