@@ -150,7 +150,9 @@ typedef struct {
  * env, the rows of its agents one after the other, and gives one value per env;
  * values[t, m] then holds that value on every row of the env.  W1 of the value
  * network is [value_in_dim, hidden].  Supported by msrl_rollout_step /
- * msrl_rollout_gae on the particle env with bfloat16 networks.
+ * msrl_rollout_gae on the particle env with bfloat16 networks, and by the
+ * learner (any multiple G of in_dim: the value network then reads groups of G
+ * consecutive rows, see msrl_ppo_grad).
  */
 typedef struct {
   int32_t in_dim, hidden, out_dim;
@@ -295,6 +297,15 @@ int msrl_env_step(msrl_state* st, const void* actions, float* rewards, uint8_t* 
  * derivative.  A row is one (t, m) entry of a stored trajectory: obs [R, D],
  * actions int32 [R] or float [R, act_dim], logp_old, adv, ret [R].  All
  * pointers DEVICE except cfg and step_counter (HOST).
+ *
+ * Centralised critic (value_in_dim = G * in_dim, G > 1; multi-agent PPO,
+ * section 2.1 of the paper): the rows come in groups of G consecutive rows, the
+ * agents of one env at one step (the row order of a stored trajectory); the
+ * value network reads a group's rows as one input and has one target per group,
+ * ret of the group's first row, and the value term is the mean over the groups:
+ *   L = mean_rows( policy term - ent_coef H ) + vf_coef mean_groups (V_theta(group) - ret)^2.
+ * R must then be a multiple of G (EINVAL otherwise), and msrl_ppo_update cuts
+ * its blocks at group boundaries.
  */
 typedef struct msrl_learner msrl_learner; /* opaque: workspaces for up to max_rows rows per call */
 typedef struct {
@@ -309,8 +320,9 @@ void msrl_learner_destroy(msrl_learner* learner);
 /*
  * grad [msrl_param_count] <- dL/dparams over the R given rows (1 <= R <=
  * max_rows); stats (optional, 5 floats) <- sums over the rows of: the policy
- * term, (V - ret)^2, the entropy, 1 where the clipped branch of the min is
- * active, logp_old - logp.  The weight gradients are accumulated with float
+ * term, (V - ret)^2 (with a centralised critic: the sum over the R / G groups),
+ * the entropy, 1 where the clipped branch of the min is active, logp_old - logp.
+ * The weight gradients are accumulated with float
  * atomics, so their last bits depend on the order of the additions.
  */
 int msrl_ppo_grad(msrl_learner* learner, const float* params, int64_t R, const float* obs,

@@ -510,6 +510,11 @@ struct LossArgs {
   int64_t R, R_pad;
   int out_dim, dist;
   float clip, vf_coef, ent_coef, inv_R;
+  // value network on groups of G consecutive rows (centralised critic; G = 1: on the row itself): v and dv
+  // have Rv = R / G rows, the target of group g is ret[g G], the value term is a mean over the groups
+  int G;
+  int64_t Rv, Rv_pad;
+  float inv_Rv;
 };
 
 // One row per lane.  Every loop runs over the 32 padded columns with a predicate, so that the
@@ -585,13 +590,15 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
       const float gl = clipped ? 0.0f : -A * rho;
 #pragma unroll
       for (int k = 0; k < 32; ++k) dy[k] = (gl * dlp[k] - a.ent_coef * dH[k]) * a.inv_R;
-      const float err = a.v[n * 32] - a.ret[n];
-      dv = a.vf_coef * 2.0f * err * a.inv_R;
       s_pi = -(clipped ? cl : un);
-      s_v = err * err;
       s_h = ent;
       s_c = clipped ? 1.0f : 0.0f;
       s_kl = a.logp_old[n] - logp;
+    }
+    if (n < a.Rv) {  // thread n also takes group n of the value network
+      const float err = a.v[n * 32] - a.ret[n * a.G];
+      dv = a.vf_coef * 2.0f * err * a.inv_Rv;
+      s_v = err * err;
     }
     SC* pdy = (SC*)a.dy + n * 32;
     SC* pdv = (SC*)a.dv + n * 32;
@@ -600,12 +607,12 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
       const float v8[8] = {dy[k], dy[k + 1], dy[k + 2], dy[k + 3], dy[k + 4], dy[k + 5], dy[k + 6], dy[k + 7]};
       const float w8[8] = {k == 0 ? dv : 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
       store8(pdy + k, v8);
-      store8(pdv + k, w8);
+      if (n < a.Rv_pad) store8(pdv + k, w8);
     }
 #pragma unroll
     for (int k = 0; k < 32; ++k) {  // consecutive lanes write consecutive rows of a unit
       store_elem((SC*)a.dyt + k * a.ldt + n, dy[k]);
-      store_elem((SC*)a.dvt + k * a.ldt + n, k == 0 ? dv : 0.0f);
+      if (n < a.Rv_pad) store_elem((SC*)a.dvt + k * a.ldt + n, k == 0 ? dv : 0.0f);
     }
   }
   // sums of the workgroup -> one atomic per statistic, spread over STAT_BINS bins per statistic

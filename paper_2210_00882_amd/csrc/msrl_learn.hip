@@ -47,6 +47,11 @@ struct msrl_learner {
   size_t esz;
   void* xc;              // [Rp, Dp]
   void* xt;              // [Dp, Rp]
+  // centralised critic: the value network reads groups of G consecutive rows as one input of G * in_dim
+  int G;                 // rows per input of the value network (1: the row itself)
+  int Dvp;               // G * in_dim rounded up to 16
+  void* xcv;             // [Rp / G (+ padding), Dvp]
+  void* xtv;             // [Dvp, Rp]
   NetBufs net[2];
   float* grad;           // scratch gradient of msrl_ppo_update
   float* stats;          // [8 + 5 * STAT_BINS]: results, then the bins the loss kernel adds into
@@ -164,20 +169,32 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
               const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* c, float* grad,
               hipStream_t s) {
   typedef typename CT<BF16>::T E;
-  const int D = L->pol.in_dim, H = L->pol.hidden, Dp = L->Dp;
+  const int H = L->pol.hidden;
   const int64_t Rp = L->Rp;
-  const int64_t Rk = round_up(R, 16);  // rows as a contraction length
+  // per network: input width, its padded width, rows and rows as a contraction length, inputs in
+  // compute type row-major and unit-major.  A centralised critic (G > 1) reads G consecutive
+  // observation rows as one input: the same memory, seen as [R / G, G * in_dim].
+  const int G = L->G;
+  const int Dn[2] = {L->pol.in_dim, G * L->pol.in_dim}, Dpn[2] = {L->Dp, G > 1 ? L->Dvp : L->Dp};
+  const int64_t Rn[2] = {R, R / G}, Rkn[2] = {round_up(R, 16), round_up(R / G, 16)};
+  void* xcn[2] = {L->xc, G > 1 ? L->xcv : L->xc};
+  void* xtn[2] = {L->xt, G > 1 ? L->xtv : L->xt};
   hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
   hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
   // observations in compute type, padded; and unit-major
-  LTRY(convert_pad(s, obs, R, D, D, (E*)L->xc, Dp, Rk));
-  LTRY(transpose(s, (const E*)L->xc, R, Dp, Dp, (E*)L->xt, Rp, Rk, Dp));
+  for (int n = 0; n < (G > 1 ? 2 : 1); ++n) {
+    LTRY(convert_pad(s, obs, Rn[n], Dn[n], Dn[n], (E*)xcn[n], Dpn[n], Rkn[n]));
+    LTRY(transpose(s, (const E*)xcn[n], Rn[n], Dpn[n], Dpn[n], (E*)xtn[n], Rp, Rkn[n], Dpn[n]));
+  }
   const int NL = L->layers;
-  const size_t first = (size_t)D * H + H, mid = (size_t)H * H + H;
+  const size_t mid = (size_t)H * H + H;
   const float* P = params;
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
     const int O = n == 0 ? L->pol.out_dim : 1;
+    const int D = Dn[n], Dp = Dpn[n];
+    const int64_t R = Rn[n], Rk = Rkn[n];
+    const size_t first = (size_t)D * H + H;
     const float* W3 = P + first + (size_t)(NL - 1) * mid;
     const float* b3 = W3 + (size_t)H * O;
     // weights in compute type: transposed for the forward pass, as stored for the backward pass
@@ -191,7 +208,13 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     LTRY(convert_pad(s, W3, H, O, O, (E*)b.wn3, 32, H));
     LTRY(convert_pad(s, b3, 1, O, O, b.b3, 32, 1));
     // forward (the activations also leave unit-major, for the weight gradients)
-    LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, L->xc, Rp, Dp, b.wt[0], H, Dp, b.h[0], R, H, H, Dp, P + (size_t)D * H, nullptr, 0, b.ht[0], Rp, Rk)));
+    if (Dp <= 256) {
+      LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, xcn[n], Rp, Dp, b.wt[0], H, Dp, b.h[0], R, H, H, Dp, P + (size_t)D * H, nullptr, 0, b.ht[0], Rp, Rk)));
+    } else {
+      // wider than the row kernel's weight panel (the joint observation): the general kernel, then the unit-major copy
+      LTRY((gemm<BF16, E, EPI_BIAS_TANH>(s, xcn[n], Rk, Dp, b.wt[0], H, Dp, b.h[0], R, H, H, Dp, P + (size_t)D * H, nullptr, 0)));
+      LTRY(transpose(s, (const E*)b.h[0], R, H, H, (E*)b.ht[0], Rp, Rk, H));
+    }
     for (int l = 1; l < NL; ++l) {
       const float* bl = P + first + (size_t)(l - 1) * mid + (size_t)H * H;
       LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, b.h[l - 1], Rp, H, b.wt[l], H, H, b.h[l], R, H, H, H, bl, nullptr, 0, b.ht[l], Rp, Rk)));
@@ -203,11 +226,12 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     LossArgs a;
     memset(&a, 0, sizeof(a));
     a.y = L->net[0].y; a.v = L->net[1].y; a.actions = actions; a.logp_old = logp_old; a.adv = adv; a.ret = ret;
-    a.dy = L->net[0].dy; a.dv = L->net[1].dy; a.stats = L->stats; a.R = R; a.R_pad = Rk;
+    a.dy = L->net[0].dy; a.dv = L->net[1].dy; a.stats = L->stats; a.R = R; a.R_pad = Rkn[0];
     a.dyt = L->net[0].dyt; a.dvt = L->net[1].dyt; a.ldt = Rp;
     a.out_dim = L->pol.out_dim; a.dist = L->pol.dist;
     a.clip = c->clip; a.vf_coef = c->vf_coef; a.ent_coef = c->ent_coef; a.inv_R = 1.0f / (float)R;
-    hipLaunchKernelGGL((loss_kernel<E>), grid1(Rk), dim3(256), 0, s, a);
+    a.G = G; a.Rv = Rn[1]; a.Rv_pad = Rkn[1]; a.inv_Rv = 1.0f / (float)Rn[1];
+    hipLaunchKernelGGL((loss_kernel<E>), grid1(Rkn[0]), dim3(256), 0, s, a);
     hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
     LTRY(hipGetLastError());
   }
@@ -215,11 +239,14 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
     const int O = n == 0 ? L->pol.out_dim : 1;
-    float* G = grad + off;
-    float* gW3 = G + first + (size_t)(NL - 1) * mid;
+    const int D = Dn[n], Dp = Dpn[n];
+    const int64_t R = Rn[n], Rk = Rkn[n];
+    const size_t first = (size_t)D * H + H;
+    float* Gr = grad + off;
+    float* gW3 = Gr + first + (size_t)(NL - 1) * mid;
     float* gb3 = gW3 + (size_t)H * O;
-    auto gW = [&](int l) { return l == 0 ? G : G + first + (size_t)(l - 1) * mid; };          // weights of hidden layer l
-    auto gb = [&](int l) { return l == 0 ? G + (size_t)D * H : gW(l) + (size_t)H * H; };       // ... its bias
+    auto gW = [&](int l) { return l == 0 ? Gr : Gr + first + (size_t)(l - 1) * mid; };        // weights of hidden layer l
+    auto gb = [&](int l) { return l == 0 ? Gr + (size_t)D * H : gW(l) + (size_t)H * H; };     // ... its bias
     // backward through the activations: dZ of every hidden layer leaves unit-major, its column sums
     // are the bias gradient; the first layer's is not needed row-major
     LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, NL > 1 ? b.dz[NL - 1] : nullptr, R, H, H, 32, nullptr,
@@ -233,12 +260,15 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
       LTRY((wgrad<BF16>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, slices)));
       for (int l = NL - 1; l >= 1; --l)
         LTRY((wgrad<BF16>(s, b.ht[l - 1], H, Rp, b.dzt[l], H, Rp, gW(l), H, H, H, Rk, slices)));
-      LTRY((wgrad<BF16>(s, L->xt, Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, slices)));
+      if (D <= 256)
+        LTRY((wgrad<BF16>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, slices)));
+      else  // more input units than the kernel's panel holds (the joint observation)
+        LTRY((gemm<BF16, float, EPI_ATOMIC>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, nullptr, nullptr, 0, slices)));
     } else {
       LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, nullptr, nullptr, 0, slices)));
       for (int l = NL - 1; l >= 1; --l)
         LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.ht[l - 1], H, Rp, b.dzt[l], H, Rp, gW(l), H, H, H, Rk, nullptr, nullptr, 0, slices)));
-      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, L->xt, Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, nullptr, nullptr, 0, slices)));
+      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, nullptr, nullptr, 0, slices)));
     }
     {
       const int64_t per_slice = 16384;
@@ -370,6 +400,9 @@ int check_learner_args(const char* who, msrl_learner* L, const void* params, int
     return fail(MSRL_EINVAL, "%s: %lld rows, the learner was created for 1..%lld", who, (long long)R,
                 (long long)L->max_rows);
   if (!(c->clip >= 0.0f)) return fail(MSRL_EINVAL, "%s: clip must be >= 0", who);
+  if (R % L->G != 0)
+    return fail(MSRL_EINVAL, "%s: %lld rows are no whole groups of %d (the agents of an env, centralised critic)", who,
+                (long long)R, L->G);
   return MSRL_OK;
 }
 
@@ -390,9 +423,9 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
     return fail(MSRL_EINVAL, "msrl_learner_init: hidden_layers must be 0 (two) or 2..8");
   if (policy->roles > 1)
     return fail(MSRL_EINVAL, "msrl_learner_init: a learner holds one parameter set; create one per role");
-  if (policy->value_in_dim != 0 && policy->value_in_dim != policy->in_dim)
-    return fail(MSRL_EUNSUPPORTED, "msrl_learner_init: a value network on the joint observation (value_in_dim %d != "
-                                   "in_dim %d) is not supported by the learner", policy->value_in_dim, policy->in_dim);
+  if (policy->value_in_dim < 0 || (policy->value_in_dim != 0 && policy->value_in_dim % policy->in_dim != 0))
+    return fail(MSRL_EINVAL, "msrl_learner_init: value_in_dim %d is no multiple of in_dim %d", policy->value_in_dim,
+                policy->in_dim);
   if (max_rows < 1) return fail(MSRL_EINVAL, "msrl_learner_init: max_rows must be positive");
   msrl_learner* L = new (std::nothrow) msrl_learner;
   if (!L) return fail(MSRL_ENOMEM, "msrl_learner_init: host allocation failed");
@@ -404,13 +437,15 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
   L->bf16 = policy->dtype == MSRL_BF16;
   L->esz = L->bf16 ? 2 : 4;
   L->layers = policy->hidden_layers == 0 ? 2 : policy->hidden_layers;
+  L->G = policy->value_in_dim > policy->in_dim ? policy->value_in_dim / policy->in_dim : 1;
+  L->Dvp = (int)round_up((int64_t)L->G * policy->in_dim, 16);
   L->n_params = net_count(policy->in_dim, policy->hidden, policy->out_dim, L->layers) +
-                net_count(policy->in_dim, policy->hidden, 1, L->layers);
+                net_count(L->G * policy->in_dim, policy->hidden, 1, L->layers);
   const size_t H = (size_t)policy->hidden, Rp = (size_t)L->Rp, Dp = (size_t)L->Dp, e = L->esz;
   L->kt1 = policy->in_dim + 2 <= 32 ? 2 : 4;
   L->fused = L->bf16 && policy->dist == MSRL_CATEGORICAL && policy->out_dim <= 16 && policy->in_dim + 2 <= 64 &&
              (policy->hidden == 64 || policy->hidden == 128 || policy->hidden == 256) && L->layers == 2 &&
-             !getenv("MSRL_LEARNER_UNFUSED");
+             L->G == 1 && !getenv("MSRL_LEARNER_UNFUSED");
   L->fly = net_layout(16 * L->kt1 - 1, policy->hidden, true);
   int rc = MSRL_OK;
   {
@@ -425,10 +460,14 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
   A(&L->xc, Rp * Dp * e);
   A(&L->xt, (L->fused && (size_t)(16 * L->kt1) > Dp ? (size_t)(16 * L->kt1) : Dp) * Rp * e);
   if (L->fused) A((void**)&L->fpacked, 4 * L->fly.bytes);
+  if (L->G > 1) {
+    A(&L->xcv, (Rp / L->G + 128) * (size_t)L->Dvp * e);
+    A(&L->xtv, (size_t)L->Dvp * Rp * e);
+  }
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
     for (int l = 0; l < L->layers; ++l) {
-      A(&b.wt[l], H * (l == 0 ? Dp : H) * e);
+      A(&b.wt[l], H * (l == 0 ? (n == 1 && L->G > 1 ? (size_t)L->Dvp : Dp) : H) * e);
       if (l >= 1) A(&b.wn[l], H * H * e);
       A(&b.h[l], Rp * H * e);
       A(&b.ht[l], H * Rp * e);
@@ -454,7 +493,7 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
 
 void msrl_learner_destroy(msrl_learner* L) {
   if (!L) return;
-  void* ptrs[] = {L->xc, L->xt, L->grad, L->stats, L->fpacked};
+  void* ptrs[] = {L->xc, L->xt, L->xcv, L->xtv, L->grad, L->stats, L->fpacked};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (int n = 0; n < 2; ++n) {
@@ -519,7 +558,10 @@ int msrl_ppo_update(msrl_learner* L, float* params, float* m, float* v, int64_t*
     return fail(MSRL_EINVAL, "msrl_ppo_update: NULL argument");
   if (iters < 1 || minibatches < 1 || R < minibatches)
     return fail(MSRL_EINVAL, "msrl_ppo_update: iters and minibatches must be positive and R >= minibatches");
-  const int64_t block = R / minibatches;
+  if (R % L->G != 0 || R / L->G < minibatches)
+    return fail(MSRL_EINVAL, "msrl_ppo_update: %lld rows are no whole groups of %d, or fewer groups than minibatches",
+                (long long)R, L->G);
+  const int64_t block = R / minibatches / L->G * L->G;  // whole groups (the agents of an env) per block
   const int64_t largest = R - block * (minibatches - 1);
   if (largest > L->max_rows)
     return fail(MSRL_EINVAL, "msrl_ppo_update: a minibatch of %lld rows exceeds the learner's %lld",

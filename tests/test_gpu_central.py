@@ -82,8 +82,10 @@ def test_central_critic_error_paths():
     pc_bad.value_in_dim = 2 * cfg.obs_dim
     with pytest.raises(B.MsrlError):
         B.msrl_rollout_init(env_cfg, pc_bad, 1)
+    pc_odd = B.make_policy_cfg(cfg)
+    pc_odd.value_in_dim = 2 * cfg.obs_dim + 1          # the learner takes whole rows per group only
     with pytest.raises(B.MsrlError):
-        B.msrl_learner_init(pc, 64)
+        B.msrl_learner_init(pc_odd, 64)
     st = B.msrl_rollout_init(env_cfg, pc, 1)
     try:
         params = B.upload_params(cfg, synth.make_params(cfg))

@@ -30,8 +30,13 @@ def tensors_of(vec, i, h, o, layers=2):
 def make_batch(cfg, R, seed, params):
     """Rows with the shapes of a stored trajectory; ratios spread around the clip range."""
     rng = np.random.default_rng(seed)
+    central = getattr(cfg, "central_critic", False)
     pol = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist,
+                     hidden_layers=cfg.hidden_layers, value_in_dim=cfg.value_in_dim if central else 0)
+    # single-row calls (the log-probabilities below): the policy network with a per-row value net of zeros
+    own = ref.Policy(cfg.obs_dim, cfg.hidden, cfg.out_dim, bf16=cfg.dtype == synth.BF16, dist=cfg.dist,
                      hidden_layers=cfg.hidden_layers)
+    p_own = np.concatenate([params[:pol.policy_param_count], np.zeros(own.param_count - own.policy_param_count)])
     obs = rng.uniform(-1, 1, (R, cfg.obs_dim)).astype(np.float32)
     if cfg.kind == synth.PARTICLE:
         obs[:, 4 * cfg.num_agents + 2:] = 0.0      # the zero slots of the particle observation
@@ -41,7 +46,7 @@ def make_batch(cfg, R, seed, params):
     adv = rng.normal(0, 1, R).astype(np.float32)
     ret = rng.normal(0, 1, R).astype(np.float32)
     pc = ref.ppo_cfg()
-    logp_new = np.array([-ref.ppo_loss(pol, pc, params, obs[n:n + 1], actions[n:n + 1], np.zeros(1), adv[n:n + 1],
+    logp_new = np.array([-ref.ppo_loss(own, pc, p_own, obs[n:n + 1], actions[n:n + 1], np.zeros(1), adv[n:n + 1],
                                        ret[n:n + 1], want_grad=False)[2][4] for n in range(R)])
     logp_old = (logp_new - rng.choice([-0.5, -0.1, 0.0, 0.1, 0.5], R)).astype(np.float32)
     return pol, obs, actions, logp_old, adv, ret
@@ -63,6 +68,13 @@ CASES = {
     # the same bf16 networks through the kernels that keep the activations in device memory
     "p3_bf16_unfused": (synth.particle("p3b", 8, 3, 64, 4, 4, synth.BF16, 12), 300),
     "cfg5_bf16_unfused": (synth.CONFIGS[5], 259),
+    # centralised critic: the value network on groups of num_agents consecutive rows (54 inputs: the row
+    # kernel's weight panel; 600 inputs: the general kernels for layer 1 and its weight gradient)
+    "p3_f32_central": (synth.particle("p3c", 8, 3, 64, 4, 4, synth.F32, 13).with_(central_critic=True), 3 * 111),
+    "p3_bf16_central": (synth.particle("p3c", 8, 3, 64, 4, 4, synth.BF16, 13).with_(central_critic=True), 3 * 100),
+    "cfg5_f32_central": (synth.CONFIGS[5].with_(dtype=synth.F32, central_critic=True), 10 * 17),
+    "cfg5_bf16_central": (synth.CONFIGS[5].with_(central_critic=True), 10 * 26),
+    "cfg5_bf16_central_4_layers": (synth.CONFIGS[5].with_(central_critic=True, hidden_layers=4), 10 * 60),
 }
 
 
@@ -87,6 +99,12 @@ def test_gradient_and_statistics_match_the_oracle(which, monkeypatch):
             B.msrl_ppo_grad(L, d[0], d[1], d[2], d[3], d[4], d[5], B.make_ppo_cfg(**hp), grad, stats)
         torch.cuda.synchronize()
         g, st = grad.cpu().numpy().astype(np.float64), stats.cpu().numpy().astype(np.float64) / R
+        if cfg.central_critic:
+            st[1] *= cfg.num_agents       # the value term is a sum over the R / num_agents groups
+            with pytest.raises(B.MsrlError) as e:     # rows that are no whole groups
+                B.msrl_ppo_grad(L, d[0], d[1][:R - 1], d[2][:R - 1], d[3][:R - 1], d[4][:R - 1], d[5][:R - 1],
+                                B.make_ppo_cfg(**hp), grad, stats)
+            assert e.value.code == B.MSRL_EINVAL
     finally:
         B.msrl_learner_destroy(L)
     tol = 2e-2 if cfg.dtype == synth.BF16 else 1e-4
@@ -94,8 +112,8 @@ def test_gradient_and_statistics_match_the_oracle(which, monkeypatch):
     assert abs(st[3] - st_ref[3]) <= 2.0 / R      # a ratio within rounding of a clip edge may switch branch
     assert 0.1 < st_ref[3] < 0.9
     off = 0
-    for o in (cfg.out_dim, 1):
-        names, n = tensors_of(g_ref, cfg.obs_dim, cfg.hidden, o, cfg.hidden_layers)
+    for o, width in ((cfg.out_dim, cfg.obs_dim), (1, pol.value_in_dim)):
+        names, n = tensors_of(g_ref, width, cfg.hidden, o, cfg.hidden_layers)
         for name, sl in names:
             a, b = g[off:off + n][sl], g_ref[off:off + n][sl]
             scale = np.abs(b).max()
