@@ -32,7 +32,8 @@ def ppo_train(cfg: synth.Config, params_f32: np.ndarray, iterations: int, seed: 
     else:
         row_sets = [torch.nonzero(agent < cfg.num_chasers).flatten(), torch.nonzero(agent >= cfg.num_chasers).flatten()]
     counts = [T * M if r is None else int(r.numel()) for r in row_sets]
-    learners = [B.msrl_learner_init(one_role, -(-c // minibatches) + minibatches) for c in counts]
+    # (the last block takes the remainder; with a centralised critic the blocks hold whole groups of N rows)
+    learners = [B.msrl_learner_init(one_role, -(-c // minibatches) + minibatches * N) for c in counts]
     try:
         master = torch.from_numpy(np.ascontiguousarray(params_f32, dtype=np.float32)).cuda()
         assert master.numel() == roles * n_role
