@@ -232,8 +232,7 @@ def test_categorical_frequencies_on_gpu():
     assert (tr["values"] == 0).all()
 
 
-def test_cfg5_sampled_full_size():
-    cfg = synth.CONFIGS[5]
+def _cfg5_sampled_full_size(cfg):
     rng = np.random.default_rng(5)
     ids = [0, cfg.num_envs - 1] + sorted(rng.choice(cfg.num_envs, 4, replace=False).tolist())
     env, pol, params, _ = oracle_setup(cfg)
@@ -267,3 +266,12 @@ def test_cfg5_sampled_full_size():
                              row0=[k * N for k in range(len(ids))])
     check_gae(cfg, sub)
     assert stats["rows"] == len(ids) * N * cfg.T
+
+
+def test_cfg5_sampled_full_size():
+    _cfg5_sampled_full_size(synth.CONFIGS[5])
+
+
+def test_cfg5_centralised_critic_sampled_full_size():
+    # the launch that bench.py times as phases.rollout_central_critic
+    _cfg5_sampled_full_size(synth.CONFIGS[5].with_(central_critic=True))
