@@ -1,10 +1,12 @@
 """Pins of the oracle's random-number layer (Philox words, uniforms, normals).
 
 The Philox round is checked against the same round written with Python's
-unbounded integers, the streams against uniformity / independence statistics.
-Bit-for-bit equality with the published Philox4x32-10 is NOT pinned (no
-known-answer vectors offline): parity unpinned for canonicity only.
+unbounded integers and against the published known-answer vectors of
+Philox4x32-10 (tests/golden/philox4x32_10_kat.txt), the streams against
+uniformity / independence statistics.
 """
+import os
+
 import numpy as np
 from scipy import stats
 
@@ -34,6 +36,18 @@ def test_philox_matches_bigint_rounds():
     # extreme operands exercise the 32x32 -> 64 multiply's high word
     assert ref.philox([MASK] * 4, [MASK] * 2) == philox_bigint([MASK] * 4, [MASK] * 2)
     assert ref.philox([0] * 4, [0] * 2) == philox_bigint([0] * 4, [0] * 2)
+
+
+def test_philox_known_answer_vectors():
+    # the generator's published test vectors: a wrong multiplier, Weyl constant, round count or word order fails
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        assert ref.philox(w[0:4], w[4:6]) == w[6:10]
+        assert philox_bigint(w[0:4], w[4:6]) == w[6:10]
+        assert philox_bigint(w[0:4], w[4:6], rounds=9) != w[6:10]
 
 
 def test_draw_counter_layout():
