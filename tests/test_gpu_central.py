@@ -149,3 +149,45 @@ def test_training_loop_with_a_centralised_critic_runs():
     n_pi = cfg.param_count - (cfg.value_in_dim * cfg.hidden + cfg.hidden + cfg.hidden * cfg.hidden + cfg.hidden +
                               cfg.hidden + 1)
     assert np.abs(new[:n_pi] - params[:n_pi]).max() > 0 and np.abs(new[n_pi:] - params[n_pi:]).max() > 0
+
+
+def test_update_loop_cuts_its_blocks_at_group_boundaries():
+    # 37 groups of 3 rows in 4 minibatches: blocks of 27, 27, 27 and 30 rows (the oracle's rule); the loop equals
+    # msrl_ppo_grad + msrl_adam_step on those blocks, and lands where the oracle's loop lands
+    import torch
+    from oracle import ref
+    from paper_2210_00882_amd import binding as B
+    from test_gpu_learner import make_batch
+    cfg = synth.particle("p3c", 8, 3, 64, 4, 4, synth.F32, 13).with_(central_critic=True)
+    G, R, mb, iters = 3, 3 * 37, 4, 2
+    params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
+    pol, obs, actions, logp_old, adv, ret = make_batch(cfg, R, 17, params)
+    c = B.make_ppo_cfg(lr=1e-3)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    d = [dev(x) for x in (obs, actions, logp_old, adv, ret)]
+    L = B.msrl_learner_init(B.make_policy_cfg(cfg), 30)
+    try:
+        pa = dev(params.astype(np.float32)); ma = torch.zeros_like(pa); va = torch.zeros_like(pa)
+        k = B.msrl_ppo_update(L, pa, ma, va, 0, iters, mb, *d, c)
+        assert k == iters * mb
+        pb = dev(params.astype(np.float32)); mbuf = torch.zeros_like(pb); vb = torch.zeros_like(pb)
+        gr, kk, blk = torch.empty_like(pb), 0, R // mb // G * G
+        assert blk == 27
+        for it in range(iters):
+            for b in range(mb):
+                sl = slice(blk * b, R if b == mb - 1 else blk * b + blk)
+                B.msrl_ppo_grad(L, pb, d[0][sl], d[1][sl], d[2][sl], d[3][sl], d[4][sl], c, gr)
+                kk += 1
+                B.msrl_adam_step(pb, mbuf, vb, gr, kk, c)
+        torch.cuda.synchronize()
+        diff = np.abs(pa.cpu().numpy() - pb.cpu().numpy())
+        assert diff.max() <= 2 * 1e-3 * kk + 1e-6 and (diff > 1e-4).mean() < 0.01
+        po, mo, vo = params.copy(), np.zeros_like(params), np.zeros_like(params)
+        ref.ppo_update(pol, ref.ppo_cfg(lr=1e-3), po, mo, vo, 0, iters, mb, obs, actions, logp_old, adv, ret)
+        loss = lambda p: ref.ppo_loss(pol, ref.ppo_cfg(), p, obs, actions, logp_old, adv, ret, want_grad=False)[0]
+        l0, l_ref, l_gpu = loss(params), loss(po), loss(pa.cpu().numpy().astype(np.float64))
+        assert l_ref < l0 and abs(l_gpu - l_ref) <= 0.02 * abs(l0 - l_ref) + 1e-6
+        with pytest.raises(B.MsrlError):     # rows that are no whole groups
+            B.msrl_ppo_update(L, pa, ma, va, k, 1, 4, d[0][:R - 1], d[1][:R - 1], d[2][:R - 1], d[3][:R - 1], d[4][:R - 1], c)
+    finally:
+        B.msrl_learner_destroy(L)
