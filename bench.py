@@ -328,6 +328,56 @@ def main():
         except B.MsrlError:
             pass
 
+        # one training iteration of Listing 1 at that scale: a 25-step episode of 100,000 agents (rollout + GAE),
+        # then the learner's update of both roles on the 2.5 M rows it produced (one pass, four minibatches per
+        # role; the rows of a role are gathered with torch.index_select) -- the kind of figure the paper's
+        # "time per episode" (Fig. 10b) is, on a different task definition
+        try:
+            ecfg = synth.tag("tag_100k_agents_episode", 25000, 3, 1, 2, 64, 25, 25)
+            eenv, ekeep = B.make_env_cfg(ecfg, None, None)
+            estate = B.msrl_rollout_init(eenv, B.make_policy_cfg(ecfg), seed)
+            one_role = B.make_policy_cfg(ecfg)
+            one_role.roles = 1
+            n_role = B.msrl_param_count(one_role)
+            master = torch.from_numpy(synth.make_params(ecfg).astype(np.float32)).cuda()
+            m1, v1 = torch.zeros_like(master), torch.zeros_like(master)
+            acting = torch.empty(master.numel(), dtype=torch.bfloat16, device="cuda")
+            eout = B.alloc_traj(ecfg, ecfg.T, logits=False, gae=True)
+            agent = torch.arange(ecfg.T * ecfg.M, device="cuda") % ecfg.num_agents
+            sets = [torch.nonzero(agent < ecfg.num_chasers).flatten(), torch.nonzero(agent >= ecfg.num_chasers).flatten()]
+            mbs = 4
+            learners = [B.msrl_learner_init(one_role, -(-int(r.numel()) // mbs) + mbs) for r in sets]
+            pc = B.make_ppo_cfg(lr=3e-4)
+            flat = lambda t: t.reshape(-1, *t.shape[2:])
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            reps, t_roll, ksteps = 3, 0.0, [0, 0]
+            for k in range(reps + 1):
+                evs[0].record()
+                B.msrl_params_cast(master, acting, B.MSRL_BF16)
+                B.msrl_rollout_gae(estate, acting, ecfg.T, ecfg.gamma, ecfg.lam, eout)
+                evs[1].record()
+                batch = [flat(eout["obs"][:ecfg.T]), flat(eout["actions"]), flat(eout["logp"]), flat(eout["adv"]),
+                         flat(eout["ret"])]
+                for r in range(2):
+                    sel = [t.index_select(0, sets[r]) for t in batch]
+                    sl = slice(r * n_role, (r + 1) * n_role)
+                    ksteps[r] = B.msrl_ppo_update(learners[r], master[sl], m1[sl], v1[sl], ksteps[r], 1, mbs, *sel, pc)
+                evs[2].record()
+                torch.cuda.synchronize()
+                if k > 0:
+                    t_roll += evs[0].elapsed_time(evs[1])
+                    ms_it = (ms_it if k > 1 else 0.0) + evs[0].elapsed_time(evs[2])
+            for Lr in learners:
+                B.msrl_learner_destroy(Lr)
+            B.msrl_rollout_destroy(estate)
+            phases["tag_100k_agents_train_iteration"] = {
+                "ms_per_iteration": ms_it / reps, "rollout_gae_ms": t_roll / reps, "update_ms": (ms_it - t_roll) / reps,
+                "rows": ecfg.T * ecfg.M, "episode_steps": ecfg.T, "update": "1 pass, 4 minibatches per role",
+                "agent_steps_per_s": ecfg.T * ecfg.M / (ms_it / reps * 1e-3)}
+            del eout, master, m1, v1, acting
+        except B.MsrlError:
+            pass
+
         # in-kernel clocks of the fused kernel: where one step of one workgroup spends its cycles
         stamps = torch.zeros(1024, dtype=torch.float32, device="cuda")
         try:
