@@ -43,6 +43,7 @@ struct msrl_state {
   KernelEntry kernel;
   int envs_per_block;    // envs owned by one workgroup
   int in_used;           // leading observation features that can be non-zero (inputs of layer 1)
+  int tag_tiles;         // pursuit env: 32-env tiles per workgroup (1 or 4)
 };
 
 namespace {
@@ -359,7 +360,8 @@ int enqueue_tag(msrl_state* st, const void* params, int32_t T, msrl_traj* out, h
   a.values = out->values;
   a.logits = out->logits;
   a.M = (int64_t)e.num_envs * e.num_agents;
-  HIP_TRY(launch_tag_rollout(e.num_chasers, e.num_agents - e.num_chasers, e.num_landmarks, st->pol.hidden, a, stream));
+  HIP_TRY(launch_tag_rollout(e.num_chasers, e.num_agents - e.num_chasers, e.num_landmarks, st->pol.hidden, st->tag_tiles, a,
+                             stream));
   return MSRL_OK;
 }
 
@@ -452,6 +454,18 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
     if (epb < 1) epb = 1;
     if (epb > max_epb) epb = max_epb;
     st->envs_per_block = (int)epb;
+  }
+  {
+    // Pursuit env: four tiles per workgroup (16 waves behind one copy of the weights in LDS) once that
+    // still gives most compute units a workgroup, one tile (more, smaller workgroups) below.  The
+    // environment variable MSRL_TAG_TILES (1 or 4) overrides the choice.
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+      cus = 256;
+    st->tag_tiles = (int64_t)(env->num_envs / 128) * 8 >= (int64_t)cus * 5 ? 4 : 1;
+    const char* force = getenv("MSRL_TAG_TILES");
+    if (force && (force[0] == '1' || force[0] == '4') && force[1] == 0) st->tag_tiles = force[0] - '0';
   }
   st->state_size = (int)msrl_env_state_size(env);
   // The particle observation ends in 2 (N - 1) slots that are always zero: layer 1 skips them.

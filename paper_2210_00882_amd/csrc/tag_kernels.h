@@ -2,8 +2,11 @@
 // parameter set per role (interface header, MSRL_ENV_TAG; the task of the paper's GPU-only
 // experiment, section 7.4, as a synthetic stand-in).
 //
-// Layout: a workgroup owns 32 envs and has one wave per agent slot; lane n of every wave is env n,
-// so the 32 rows of a wave's MFMA tile all have the same role and use the same weights.  The
+// Layout: a workgroup owns TILES tiles of 32 envs and has one wave per tile and agent slot; lane n of
+// a wave is env n of its tile, so the 32 rows of a wave's MFMA tile all have the same role and use
+// the same weights.  (TILES = 4 puts 16 waves on a compute unit behind one copy of the weights: the
+// kernel is bound by vector-ALU issue, and four waves per SIMD hide more of its latencies than the
+// two that the LDS leaves room for with one tile per workgroup.)  The
 // networks are small (bf16, 64 units), so the four of them (chasers' and runners' policy and
 // value) stay resident in LDS for the whole kernel: no weight streaming, and the only barriers are
 // those of the env step (two per step), where the agents of an env (one per wave) exchange
@@ -35,9 +38,10 @@ struct TagArgs {
   int64_t M;
 };
 
-template <int NC, int NR, int L, int H>
-__global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) {
+template <int NC, int NR, int L, int H, int TILES = 1>
+__global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(TagArgs a) {
   constexpr int N = NC + NR;
+  static_assert(64 * N * TILES <= 1024, "one wave per tile and agent slot");
   constexpr int D = 4 + 2 * L + 4 * (N - 1);
   constexpr int S = 4 * N + 2 * L;
   constexpr int KT1 = (D + 1 + 15) / 16;  // + the constant-1 input that carries the bias
@@ -57,12 +61,20 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
   // and writes the state of step t + 1 (moved, or reset after a done) into the other one, so that
   // two barriers per step suffice (new state visible; contact counts visible).  s_pm holds the
   // positions after the move, which the rewards are computed on.
-  __shared__ float2 s_p[2][32][N], s_v[2][32][N], s_lm[2][32][L > 0 ? L : 1], s_pm[32][N];
-  __shared__ float s_cnt[32][N];
+  __shared__ float2 t_p[TILES][2][32][N], t_v[TILES][2][32][N], t_lm[TILES][2][32][L > 0 ? L : 1], t_pm[TILES][32][N];
+  __shared__ float t_cnt[TILES][32][N];
 
   const int lane = threadIdx.x & 63;
-  const int j = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // agent slot of this wave
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int tile = wave / N;      // env tile of this wave
+  const int j = wave - tile * N;  // ... and its agent slot
   const int n = lane & 31, h = lane >> 5;
+  // the tables of this wave's tile
+  float2(&s_p)[2][32][N] = t_p[tile];
+  float2(&s_v)[2][32][N] = t_v[tile];
+  float2(&s_lm)[2][32][L > 0 ? L : 1] = t_lm[tile];
+  float2(&s_pm)[32][N] = t_pm[tile];
+  float(&s_cnt)[32][N] = t_cnt[tile];
   const int role = j < NC ? 0 : 1;
   const NetLayout ly = net_layout(D, H, true);
   for (int net = 0; net < 4; ++net) {
@@ -81,7 +93,7 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
       s_b3[net][threadIdx.x] = *(const float*)(a.packed + (size_t)net * ly.bytes + ly.b3 + threadIdx.x * 4);
   }
 
-  const int64_t env64 = (int64_t)blockIdx.x * 32 + n;
+  const int64_t env64 = ((int64_t)blockIdx.x * TILES + tile) * 32 + n;
   const bool valid = env64 < a.E;
   const uint32_t env = (uint32_t)(valid ? env64 : a.E - 1);
   const float* es = a.env_state + (size_t)env * S;
@@ -324,8 +336,9 @@ __global__ __launch_bounds__(64 * (NC + NR)) void tag_rollout_kernel(TagArgs a) 
   }
 }
 
-// launcher of the compiled instances; returns hipErrorInvalidValue when no instance matches
-hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, const TagArgs& a, hipStream_t stream);
+// launcher of the compiled instances; returns hipErrorInvalidValue when no instance matches.
+// tiles: env tiles per workgroup, 1 or 4.
+hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, int tiles, const TagArgs& a, hipStream_t stream);
 bool tag_rollout_compiled(int nc, int nr, int landmarks, int hidden);
 
 }  // namespace msrl

@@ -79,10 +79,14 @@ def check(cfg, tr, env, pol, params, env_ids, g0, T):
     return stats
 
 
+@pytest.mark.parametrize("tiles,E", [(1, 70), (4, 70), (4, 300)])
 @pytest.mark.parametrize("nc,nr,L", [(3, 1, 2), (2, 2, 1)])
-def test_tag_rollout_every_env_and_step(nc, nr, L):
+def test_tag_rollout_every_env_and_step(nc, nr, L, tiles, E, monkeypatch):
+    # both workgroup shapes (one or four 32-env tiles, MSRL_TAG_TILES is read by msrl_rollout_init): E = 70 is
+    # one ragged workgroup of four tiles with an empty tile, E = 300 three workgroups with a ragged last tile
+    monkeypatch.setenv("MSRL_TAG_TILES", str(tiles))
     # big bodies, so that contact forces and contact rewards occur in most steps
-    cfg = synth.tag("tag", 70, nc, nr, L, 64, 20, 7, idx=50 + nc).with_(radius_c=0.3, radius_r=0.25)
+    cfg = synth.tag("tag", E, nc, nr, L, 64, 20 if E < 100 else 8, 7, idx=50 + nc).with_(radius_c=0.3, radius_r=0.25)
     env = tag_env(cfg)
     pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
     params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
@@ -112,6 +116,26 @@ def test_tag_rollout_every_env_and_step(nc, nr, L):
     # chasers share their reward, runners do not see it
     r = tr["rewards"].reshape(cfg.T, cfg.num_envs, cfg.num_agents)
     assert (r[:, :, :nc] == r[:, :, :1]).all() and (r[:, :, :nc] >= 0).all() and (r[:, :, nc:] <= 0).all()
+
+
+def test_tag_at_the_benchmarks_size_sampled():
+    # 25,000 envs (100,000 agents): the launch bench.py times, which takes four tiles per workgroup by itself
+    cfg = synth.tag("tag_100k_agents", 25000, 3, 1, 2, 64, 12, 5, idx=58)
+    env = tag_env(cfg)
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
+    params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
+    rng = np.random.default_rng(2)
+    ids = [0, 31, 32, 127, 128, cfg.num_envs - 1] + sorted(rng.choice(cfg.num_envs, 6, replace=False).tolist())
+    with GpuRollout(cfg, params.astype(np.float32), SEED) as gpu:
+        tr = gpu.run(cfg.T)
+        _, g = gpu.get_state()
+    assert (g == cfg.T).all()
+    st = check(cfg, tr, env, pol, params, ids, np.zeros(len(ids), dtype=np.int64), cfg.T)
+    assert st["rows"] == len(ids) * cfg.num_agents * cfg.T
+    check_gae(cfg, tr)
+    r = tr["rewards"].reshape(cfg.T, cfg.num_envs, cfg.num_agents)
+    assert (r[:, :, :3] == r[:, :, :1]).all() and (r[:, :, :3] >= 0).all() and (r[:, :, 3:] <= 0).all()
+    assert np.isfinite(tr["values"]).all() and ((tr["actions"] >= 0) & (tr["actions"] < 5)).all()
 
 
 def test_tag_default_bodies_and_errors():
