@@ -94,6 +94,9 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   chaser and a runner): every chaser +10 per contact of any chaser; a runner
  *   -10 per chaser in contact with it, -10 * (max(0,|px|-1) + max(0,|py|-1)).
  *   Supported by msrl_rollout_step / msrl_rollout_gae (and the snapshot calls).
+ *   The kernel has two workgroup shapes with identical results (one or four
+ *   tiles of 32 envs); msrl_rollout_init picks by num_envs, the environment
+ *   variable MSRL_TAG_TILES=1|4, read there, overrides the choice.
  *
  * An episode ends (done = 1, then reset) on every step whose counter g
  * satisfies (g+1) % episode_len == 0; g counts the env's steps since init.
@@ -313,7 +316,11 @@ typedef struct {
   float lr, beta1, beta2, adam_eps;
 } msrl_ppo_cfg;
 
-/* Allocates the workspaces.  EINVAL unless hidden is a multiple of 32 and out_dim <= 32. */
+/* Allocates the workspaces.  EINVAL unless hidden is a multiple of 32 and out_dim <= 32.
+ * bfloat16 networks with two hidden layers of 64, 128 or 256 units, a categorical policy of at most
+ * 16 actions, at most 62 inputs and no centralised critic take the path that keeps the activations on
+ * chip; everything else, and every learner created while the environment variable
+ * MSRL_LEARNER_UNFUSED is set, the path through device memory.  Both compute the same gradient. */
 int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_learner** out);
 void msrl_learner_destroy(msrl_learner* learner);
 
