@@ -115,13 +115,13 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 //   PHASE_DEEP  the full kernel for networks with more than two hidden layers (RolloutArgs::layers):
 //              the further hidden layers run between layer 1 and the last hidden layer, their chunk
 //              blocks coming through the same LDS window.
-enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHASE_ACT = 4, PHASE_STEP = 5,
-             PHASE_DEEP = 6, PHASE_CENTRAL = 7 };
 //   PHASE_CENTRAL  the full kernel with a centralised critic (bf16 networks): the policy network as
 //              usual; the value network takes the joint observation of an env (RolloutArgs::critic
 //              holds its tiles) and is evaluated once per env by the workgroup as a whole: the
 //              joint observations of its envs are the columns of one MFMA tile, and wave w computes
 //              the 32-unit chunk w of each layer, the layers meeting in LDS.
+enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHASE_ACT = 4, PHASE_STEP = 5,
+             PHASE_DEEP = 6, PHASE_CENTRAL = 7 };
 // stamps: start of the step, observation rows built and stored, policy layer 1 done (after the
 // stage barrier that precedes it), policy stage s done (s < 5), same for the value network,
 // logits and values ready, sampling and move done, end of the step
