@@ -78,8 +78,17 @@ struct WgradTArgs {
 // memory latency (NTW = 1, the output layer, has the registers for a deeper queue).
 // The bias gradient is one more contraction with a left operand of ones: wave w adds it up for
 // column tile w.
+// Several such contractions in one launch (blockIdx.y picks the job): the launches of one gradient
+// pass are short and end in float atomics, so their tails and their memory latencies overlap when
+// the workgroups of all of them are resident together.
+struct WgradTJobs {
+  int n;
+  WgradTArgs job[4];
+};
+
 template <int NTW, int DEPTH>
-__global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTArgs g) {
+__global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTJobs jobs) {
+  const WgradTArgs& g = jobs.job[blockIdx.y];
   constexpr int FR = NTW * 4 * 64;                 // B fragments per step
   constexpr int PER = (FR + 511) / 512;            // ... per thread
   __shared__ __attribute__((aligned(16))) u32x4 s_b[FR];

@@ -360,9 +360,13 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
   hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
   LTRY(hipGetLastError());
   size_t off = 0;
-  int tps = (int)((n_tiles + L->cus - 1) / L->cus);  // one workgroup per compute unit
+  int tps = (int)((n_tiles + L->cus - 1) / L->cus);  // one workgroup per compute unit and contraction
   tps = (tps + 1) / 2 * 2;
   const unsigned slices = (unsigned)((n_tiles + tps - 1) / tps);
+  // the contractions of both networks in two launches: the four with a hidden layer's width of columns,
+  // and the two of the output layers
+  WgradTJobs wide, narrow;
+  wide.n = narrow.n = 0;
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
     const int O = n == 0 ? L->pol.out_dim : 1;
@@ -373,21 +377,19 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
     float* gW3 = gb2 + H;
     float* gb3 = gW3 + (size_t)H * O;
     auto wg = [&](const void* A, int UA, int M, const void* B, int UB, int N, float* C, int64_t ldc, float* bias) {
-      WgradTArgs g;
+      WgradTArgs& g = N <= 32 ? narrow.job[narrow.n++] : wide.job[wide.n++];
       memset(&g, 0, sizeof(g));
       g.A = (const __bf16*)A; g.B = (const __bf16*)B; g.UA = UA; g.UB = UB; g.M = M; g.N = N; g.m_out = M;
       g.n_tiles = n_tiles; g.tiles_per_slice = tps; g.C = C; g.ldc = ldc; g.bias = bias;
-      if (N <= 32)
-        hipLaunchKernelGGL((wgrad_tiled_kernel<1, 4>), dim3(slices), dim3(512), 0, s, g);
-      else
-        hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices), dim3(512), 0, s, g);
     };
     wg(b.ht[1], H, H, b.dyt, 16, O, gW3, O, gb3);
     wg(b.ht[0], H, H, b.dzt[1], H, H, gW2, H, gb2);
     wg(L->xt, 16 * kt1, D, b.dzt[0], H, H, gW1, H, gb1);
-    LTRY(hipGetLastError());
     off += net_count(D, H, O);
   }
+  hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices, (unsigned)wide.n), dim3(512), 0, s, wide);
+  hipLaunchKernelGGL((wgrad_tiled_kernel<1, 4>), dim3(slices, (unsigned)narrow.n), dim3(512), 0, s, narrow);
+  LTRY(hipGetLastError());
   return MSRL_OK;
 }
 
