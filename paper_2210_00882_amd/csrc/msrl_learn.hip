@@ -362,6 +362,9 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
   size_t off = 0;
   int tps = (int)((n_tiles + L->cus - 1) / L->cus);  // one workgroup per compute unit and contraction
   tps = (tps + 1) / 2 * 2;
+  // (64-unit networks: every slice ends in float atomics on the same few thousand addresses; half as many,
+  // twice as long slices are faster, a quarter as many no longer keep the chip busy)
+  if (H <= 64) tps *= 2;
   const unsigned slices = (unsigned)((n_tiles + tps - 1) / tps);
   // the contractions of both networks in two launches: the four with a hidden layer's width of columns,
   // and the two of the output layers
