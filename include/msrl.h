@@ -318,8 +318,8 @@ typedef struct {
 
 /* Allocates the workspaces.  EINVAL unless hidden is a multiple of 32 and out_dim <= 32.
  * bfloat16 networks with two hidden layers of 64, 128 or 256 units, a categorical policy of at most
- * 16 actions, at most 62 inputs and no centralised critic take the path that keeps the activations on
- * chip; everything else, and every learner created while the environment variable
+ * 16 actions and at most 62 inputs take the path that keeps the activations on chip (with a
+ * centralised critic: the policy network only); everything else, and every learner created while the environment variable
  * MSRL_LEARNER_UNFUSED is set, the path through device memory.  Both compute the same gradient. */
 int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_learner** out);
 void msrl_learner_destroy(msrl_learner* learner);

@@ -515,6 +515,7 @@ struct LossArgs {
   int G;
   int64_t Rv, Rv_pad;
   float inv_Rv;
+  int policy, value;  // which of the two parts this launch computes (the other one's buffers are not touched)
 };
 
 // One row per lane.  Every loop runs over the 32 padded columns with a predicate, so that the
@@ -528,7 +529,7 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
 #pragma unroll
     for (int k = 0; k < 32; ++k) dy[k] = 0.0f;
     float dv = 0.0f;
-    if (n < a.R) {
+    if (n < a.R && a.policy) {
       const int O = a.out_dim;
       float y[32];
 #pragma unroll
@@ -595,7 +596,7 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
       s_c = clipped ? 1.0f : 0.0f;
       s_kl = a.logp_old[n] - logp;
     }
-    if (n < a.Rv) {  // thread n also takes group n of the value network
+    if (n < a.Rv && a.value) {  // thread n also takes group n of the value network
       const float err = a.v[n * 32] - a.ret[n * a.G];
       dv = a.vf_coef * 2.0f * err * a.inv_Rv;
       s_v = err * err;
@@ -606,13 +607,13 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
     for (int k = 0; k < 32; k += 8) {
       const float v8[8] = {dy[k], dy[k + 1], dy[k + 2], dy[k + 3], dy[k + 4], dy[k + 5], dy[k + 6], dy[k + 7]};
       const float w8[8] = {k == 0 ? dv : 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-      store8(pdy + k, v8);
-      if (n < a.Rv_pad) store8(pdv + k, w8);
+      if (a.policy) store8(pdy + k, v8);
+      if (n < a.Rv_pad && a.value) store8(pdv + k, w8);
     }
 #pragma unroll
     for (int k = 0; k < 32; ++k) {  // consecutive lanes write consecutive rows of a unit
-      store_elem((SC*)a.dyt + k * a.ldt + n, dy[k]);
-      if (n < a.Rv_pad) store_elem((SC*)a.dvt + k * a.ldt + n, k == 0 ? dv : 0.0f);
+      if (a.policy) store_elem((SC*)a.dyt + k * a.ldt + n, dy[k]);
+      if (n < a.Rv_pad && a.value) store_elem((SC*)a.dvt + k * a.ldt + n, k == 0 ? dv : 0.0f);
     }
   }
   // sums of the workgroup -> one atomic per statistic, spread over STAT_BINS bins per statistic

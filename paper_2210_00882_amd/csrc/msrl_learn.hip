@@ -57,7 +57,8 @@ struct msrl_learner {
   float* stats;          // [8 + 5 * STAT_BINS]: results, then the bins the loss kernel adds into
   size_t n_params;
   // on-chip gradient pass (learn_fused.h): bf16 networks with a categorical policy of at most 16 actions
-  bool fused;
+  bool fused;            // ... for both networks
+  bool fused_policy;     // ... for the policy network only (centralised critic: its value network takes path (2))
   int kt1;               // layer-1 tiles of the row kernel: inputs, plus the two bias parts, in tiles of 16
   NetLayout fly;         // layout of one image of the packed weights
   uint8_t* fpacked;      // per network: forward image, backward image
@@ -167,7 +168,10 @@ hipError_t convert_pad(hipStream_t s, const S* src, int64_t rows, int64_t cols, 
 template <bool BF16>
 int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs, const void* actions,
               const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* c, float* grad,
-              hipStream_t s) {
+              hipStream_t s, int nets = 3, bool finish = true) {
+  // nets: bit n set = network n (0 policy, 1 value) is handled here; with bit 0 clear, grad and the
+  // statistics bins have been cleared by the caller and the on-chip pass adds the policy network's part.
+  // finish: add the statistics bins up at the end (not while another pass still adds to them)
   typedef typename CT<BF16>::T E;
   const int H = L->pol.hidden;
   const int64_t Rp = L->Rp;
@@ -179,10 +183,13 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
   const int64_t Rn[2] = {R, R / G}, Rkn[2] = {round_up(R, 16), round_up(R / G, 16)};
   void* xcn[2] = {L->xc, G > 1 ? L->xcv : L->xc};
   void* xtn[2] = {L->xt, G > 1 ? L->xtv : L->xt};
-  hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
-  hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
+  if (nets & 1) {
+    hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
+    hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
+  }
   // observations in compute type, padded; and unit-major
   for (int n = 0; n < (G > 1 ? 2 : 1); ++n) {
+    if (!((nets >> n) & 1) && G > 1) continue;
     LTRY(convert_pad(s, obs, Rn[n], Dn[n], Dn[n], (E*)xcn[n], Dpn[n], Rkn[n]));
     LTRY(transpose(s, (const E*)xcn[n], Rn[n], Dpn[n], Dpn[n], (E*)xtn[n], Rp, Rkn[n], Dpn[n]));
   }
@@ -197,6 +204,10 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     const size_t first = (size_t)D * H + H;
     const float* W3 = P + first + (size_t)(NL - 1) * mid;
     const float* b3 = W3 + (size_t)H * O;
+    if (!((nets >> n) & 1)) {
+      P = b3 + O;
+      continue;
+    }
     // weights in compute type: transposed for the forward pass, as stored for the backward pass
     LTRY(transpose(s, P, D, H, H, (E*)b.wt[0], Dp, Dp, H));
     for (int l = 1; l < NL; ++l) {
@@ -231,8 +242,9 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     a.out_dim = L->pol.out_dim; a.dist = L->pol.dist;
     a.clip = c->clip; a.vf_coef = c->vf_coef; a.ent_coef = c->ent_coef; a.inv_R = 1.0f / (float)R;
     a.G = G; a.Rv = Rn[1]; a.Rv_pad = Rkn[1]; a.inv_Rv = 1.0f / (float)Rn[1];
+    a.policy = nets & 1; a.value = (nets >> 1) & 1;
     hipLaunchKernelGGL((loss_kernel<E>), grid1(Rkn[0]), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
+    if (finish) hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
     LTRY(hipGetLastError());
   }
   size_t off = 0;
@@ -242,6 +254,10 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     const int D = Dn[n], Dp = Dpn[n];
     const int64_t R = Rn[n], Rk = Rkn[n];
     const size_t first = (size_t)D * H + H;
+    if (!((nets >> n) & 1)) {
+      off += net_count(D, H, O, NL);
+      continue;
+    }
     float* Gr = grad + off;
     float* gW3 = Gr + first + (size_t)(NL - 1) * mid;
     float* gb3 = gW3 + (size_t)H * O;
@@ -289,11 +305,16 @@ static_assert(ROWS_STAT_BINS == STAT_BINS, "the row kernel and the loss kernel s
 // unit-major operands), then the weight and bias gradients from those.
 int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs, const void* actions,
                     const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* c, float* grad,
-                    hipStream_t s) {
+                    hipStream_t s, int nets = 3, bool clear = true, bool finish = true) {
+  // nets: bit n set = network n is handled here (1: the policy network only; the value network's pass
+  // through device memory adds to the same grad and statistics bins).  clear / finish: zero grad and the
+  // bins first / add the bins up at the end (the caller does both around two concurrent passes)
   const int D = L->pol.in_dim, H = L->pol.hidden, kt1 = L->kt1;
   const NetLayout& ly = L->fly;
-  hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
-  hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
+  if (clear) {
+    hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
+    hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
+  }
   const float* b3p[2];
   {
     LearnPackJobs jobs;
@@ -301,6 +322,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
     const float* P = params;
     int max_items = 0;
     for (int n = 0; n < 2; ++n) {
+      if (!((nets >> n) & 1)) continue;  // (only ever the value network, the last one: P needs no advance)
       const int O = n == 0 ? L->pol.out_dim : 1;
       const float* W1 = P;
       const float* b1 = W1 + (size_t)D * H;
@@ -340,6 +362,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
   const int64_t groups = (n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
   const unsigned grid = (unsigned)(groups < L->cus ? groups : L->cus);
   for (int n = 0; n < 2; ++n) {
+    if (!((nets >> n) & 1)) continue;
     NetBufs& b = L->net[n];
     RowsArgs a;
     memset(&a, 0, sizeof(a));
@@ -357,7 +380,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
                             : launch_ppo_rows_h256(kt1, n, a, grid, s);
     LTRY(e);
   }
-  hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
+  if (finish) hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
   LTRY(hipGetLastError());
   size_t off = 0;
   // Slices of row tiles: two compute units' share each, i.e. half as many workgroups per contraction as
@@ -373,6 +396,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
   WgradTJobs wide, narrow;
   wide.n = narrow.n = 0;
   for (int n = 0; n < 2; ++n) {
+    if (!((nets >> n) & 1)) continue;  // (the value network, behind the policy network's gradient)
     NetBufs& b = L->net[n];
     const int O = n == 0 ? L->pol.out_dim : 1;
     float* gW1 = grad + off;
@@ -392,8 +416,8 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
     wg(L->xt, 16 * kt1, D, b.dzt[0], H, H, gW1, H, gb1);
     off += net_count(D, H, O);
   }
-  hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices, (unsigned)wide.n), dim3(512), 0, s, wide);
-  hipLaunchKernelGGL((wgrad_tiled_kernel<1, 4>), dim3(slices, (unsigned)narrow.n), dim3(512), 0, s, narrow);
+  if (wide.n) hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices, (unsigned)wide.n), dim3(512), 0, s, wide);
+  if (narrow.n) hipLaunchKernelGGL((wgrad_tiled_kernel<1, 4>), dim3(slices, (unsigned)narrow.n), dim3(512), 0, s, narrow);
   LTRY(hipGetLastError());
   return MSRL_OK;
 }
@@ -450,9 +474,10 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
                 net_count(L->G * policy->in_dim, policy->hidden, 1, L->layers);
   const size_t H = (size_t)policy->hidden, Rp = (size_t)L->Rp, Dp = (size_t)L->Dp, e = L->esz;
   L->kt1 = policy->in_dim + 2 <= 32 ? 2 : 4;
-  L->fused = L->bf16 && policy->dist == MSRL_CATEGORICAL && policy->out_dim <= 16 && policy->in_dim + 2 <= 64 &&
-             (policy->hidden == 64 || policy->hidden == 128 || policy->hidden == 256) && L->layers == 2 &&
-             L->G == 1 && !getenv("MSRL_LEARNER_UNFUSED");
+  L->fused_policy = L->bf16 && policy->dist == MSRL_CATEGORICAL && policy->out_dim <= 16 && policy->in_dim + 2 <= 64 &&
+                    (policy->hidden == 64 || policy->hidden == 128 || policy->hidden == 256) && L->layers == 2 &&
+                    !getenv("MSRL_LEARNER_UNFUSED");
+  L->fused = L->fused_policy && L->G == 1;
   L->fly = net_layout(16 * L->kt1 - 1, policy->hidden, true);
   int rc = MSRL_OK;
   {
@@ -465,8 +490,8 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
   }
   auto A = [&](void** p, size_t bytes) { if (rc == MSRL_OK) rc = dev_alloc((uint8_t**)p, bytes); };
   A(&L->xc, Rp * Dp * e);
-  A(&L->xt, (L->fused && (size_t)(16 * L->kt1) > Dp ? (size_t)(16 * L->kt1) : Dp) * Rp * e);
-  if (L->fused) A((void**)&L->fpacked, 4 * L->fly.bytes);
+  A(&L->xt, (L->fused_policy && (size_t)(16 * L->kt1) > Dp ? (size_t)(16 * L->kt1) : Dp) * Rp * e);
+  if (L->fused_policy) A((void**)&L->fpacked, 4 * L->fly.bytes);
   if (L->G > 1) {
     A(&L->xcv, (Rp / L->G + 128) * (size_t)L->Dvp * e);
     A(&L->xtv, (size_t)L->Dvp * Rp * e);
@@ -524,9 +549,19 @@ int msrl_ppo_grad(msrl_learner* L, const float* params, int64_t R, const float* 
   if (rc != MSRL_OK) return rc;
   if (!grad) return fail(MSRL_EINVAL, "msrl_ppo_grad: grad is NULL");
   hipStream_t s = (hipStream_t)hip_stream;
-  rc = L->fused ? fused_grad_pass(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s)
-     : L->bf16  ? grad_pass<true>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s)
-                : grad_pass<false>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s);
+  if (L->fused) {
+    rc = fused_grad_pass(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s);
+  } else if (L->fused_policy) {
+    // Centralised critic: the policy network on chip, then the value network (one row per group, a wide
+    // first layer) through device memory; it adds its part of grad and of the statistics.  (Running the
+    // second pass on a stream of its own beside the first was measured: no gain, the row kernel's
+    // workgroups leave no LDS for the value network's kernels to start beside them.)
+    rc = fused_grad_pass(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s, 1, true, false);
+    if (rc == MSRL_OK) rc = grad_pass<true>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s, 2, true);
+  } else {
+    rc = L->bf16 ? grad_pass<true>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s)
+                 : grad_pass<false>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s);
+  }
   if (rc != MSRL_OK) return rc;
   if (stats) LTRY(hipMemcpyAsync(stats, L->stats, 5 * sizeof(float), hipMemcpyDeviceToDevice, s));
   return MSRL_OK;

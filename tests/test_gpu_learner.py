@@ -75,6 +75,11 @@ CASES = {
     "cfg5_f32_central": (synth.CONFIGS[5].with_(dtype=synth.F32, central_critic=True), 10 * 17),
     "cfg5_bf16_central": (synth.CONFIGS[5].with_(central_critic=True), 10 * 26),
     "cfg5_bf16_central_4_layers": (synth.CONFIGS[5].with_(central_critic=True, hidden_layers=4), 10 * 60),
+    # (bf16, two hidden layers: the policy network takes the on-chip path, the critic the one through device
+    # memory; the same with both networks through device memory)
+    "p3_bf16_central_unfused": (synth.particle("p3c", 8, 3, 64, 4, 4, synth.BF16, 13).with_(central_critic=True), 3 * 100),
+    "cfg5_bf16_central_unfused": (synth.CONFIGS[5].with_(central_critic=True), 10 * 26),
+    "cfg5_bf16_central_many_tiles": (synth.CONFIGS[5].with_(central_critic=True), 10 * 67),
 }
 
 
