@@ -252,37 +252,6 @@ def main():
         except B.MsrlError:
             pass
 
-        # the same gradient with a centralised critic (value network on the joint observation of an env's
-        # agents: a tenth of the rows, ten times the input width), on the same rows
-        try:
-            cen = cfg.with_(central_critic=True)
-            rows = int(min(T * M, 512 * 1024)) // cen.num_agents * cen.num_agents
-            learner = B.msrl_learner_init(B.make_policy_cfg(cen), rows)
-            master = torch.from_numpy(np.ascontiguousarray(synth.make_params(cen), dtype=np.float32)).cuda()
-            grad = torch.empty_like(master)
-            flat = lambda t: t.reshape(-1, *t.shape[2:])[:rows]
-            batch = (flat(out["obs"][:T]), flat(out["actions"]), flat(out["logp"]), flat(out["adv"]), flat(out["ret"]))
-            pc = B.make_ppo_cfg()
-            reps = 3
-            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            for k in range(reps + 1):
-                if k == 1:
-                    ev0.record()
-                B.msrl_ppo_grad(learner, master, *batch, pc, grad)
-            ev1.record()
-            torch.cuda.synchronize()
-            ms = ev0.elapsed_time(ev1) / reps
-            B.msrl_learner_destroy(learner)
-            fl = (3 * mlp_flops_per_agent_step(cen) - 2 * cen.obs_dim * cen.hidden
-                  - 2 * cen.value_in_dim * cen.hidden // cen.num_agents) * rows
-            tf = fl / (ms * 1e-3) / 1e12
-            phases["learner_grad_central_critic"] = {"bound": "mfma", "ms_per_call": ms, "rows": rows, "achieved": tf,
-                                                     "peak": PEAK_TFLOPS[dt_name], "unit": "TFLOP/s",
-                                                     "frac": tf / PEAK_TFLOPS[dt_name], "rows_per_s": rows / (ms * 1e-3)}
-            del master, grad
-        except B.MsrlError:
-            pass
-
         # the same rollout with the network depth of the paper's evaluation (seven layers = six hidden
         # layers and the output layer), if a kernel for it is compiled
         try:
@@ -328,6 +297,37 @@ def main():
                                                 "frac": tf / PEAK_TFLOPS[dt_name],
                                                 "agent_steps_per_s": agent_steps / (ms * 1e-3)}
             del cp
+        except B.MsrlError:
+            pass
+
+        # the same gradient with a centralised critic (value network on the joint observation of an env's
+        # agents: a tenth of the rows, ten times the input width), on the same rows
+        try:
+            cen = cfg.with_(central_critic=True)
+            rows = int(min(T * M, 512 * 1024)) // cen.num_agents * cen.num_agents
+            learner = B.msrl_learner_init(B.make_policy_cfg(cen), rows)
+            master = torch.from_numpy(np.ascontiguousarray(synth.make_params(cen), dtype=np.float32)).cuda()
+            grad = torch.empty_like(master)
+            flat = lambda t: t.reshape(-1, *t.shape[2:])[:rows]
+            batch = (flat(out["obs"][:T]), flat(out["actions"]), flat(out["logp"]), flat(out["adv"]), flat(out["ret"]))
+            pc = B.make_ppo_cfg()
+            reps = 3
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for k in range(reps + 1):
+                if k == 1:
+                    ev0.record()
+                B.msrl_ppo_grad(learner, master, *batch, pc, grad)
+            ev1.record()
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1) / reps
+            B.msrl_learner_destroy(learner)
+            fl = (3 * mlp_flops_per_agent_step(cen) - 2 * cen.obs_dim * cen.hidden
+                  - 2 * cen.value_in_dim * cen.hidden // cen.num_agents) * rows
+            tf = fl / (ms * 1e-3) / 1e12
+            phases["learner_grad_central_critic"] = {"bound": "mfma", "ms_per_call": ms, "rows": rows, "achieved": tf,
+                                                     "peak": PEAK_TFLOPS[dt_name], "unit": "TFLOP/s",
+                                                     "frac": tf / PEAK_TFLOPS[dt_name], "rows_per_s": rows / (ms * 1e-3)}
+            del master, grad
         except B.MsrlError:
             pass
 
