@@ -234,7 +234,8 @@ def test_categorical_frequencies_on_gpu():
 
 def _cfg5_sampled_full_size(cfg):
     rng = np.random.default_rng(5)
-    ids = [0, cfg.num_envs - 1] + sorted(rng.choice(cfg.num_envs, 4, replace=False).tolist())
+    # first, last and 30 random envs (the neighbours of workgroup boundaries among them by chance: 24 envs per workgroup)
+    ids = [0, cfg.num_envs - 1] + sorted(rng.choice(np.arange(1, cfg.num_envs - 1), 30, replace=False).tolist())
     env, pol, params, _ = oracle_setup(cfg)
     import torch
     with GpuRollout(cfg, params.astype(np.float32), SEED) as gpu:
