@@ -576,7 +576,7 @@ void ref_rollout(const ref_env_cfg* c, const ref_policy_cfg* p, uint64_t seed, i
         if (c->kind == REF_ENV_TAG && i >= c->num_chasers) {
           const int Lh = p->hidden_layers > 0 ? p->hidden_layers : 2;
           prm += ref_net_param_count_l(p->in_dim, p->hidden, p->out_dim, Lh) +
-                 ref_net_param_count_l(p->in_dim, p->hidden, 1, Lh);
+                 ref_net_param_count_l(p->value_in_dim > 0 ? p->value_in_dim : p->in_dim, p->hidden, 1, Lh);
         }
         if (p->value_in_dim > 0 && p->value_in_dim != p->in_dim) {
           /* centralised critic: policy on the agent's row, value on the env's joint observation */
