@@ -1,6 +1,7 @@
 /*
- * msrl_learn_ref.c -- CPU oracle of the learner's policy update (next hot-path
- * row after rollout + GAE; no HIP path is checked against it yet).
+ * msrl_learn_ref.c -- CPU oracle of the learner's policy update (the next hot-path
+ * row after rollout + GAE); the HIP entry points msrl_ppo_grad / msrl_adam_step /
+ * msrl_ppo_update are checked against it.
  *
  * TEST INFRASTRUCTURE ONLY, like msrl_ref.c: plain scalar loops in double
  * precision, no code shared with the HIP sources.
@@ -29,11 +30,21 @@
  *
  *   L = mean_n(Lpi_n - c_e H_n) + c_v mean_g (V_theta(s_gG .. s_gG+G-1) - ret_gG)^2
  *
- * In bf16 mode the derivative
- * treats every rounding as the identity (straight-through): dL/dW uses the
- * rounded layer input, dL/d(input) uses the rounded weight, nothing else is
- * rounded in the backward pass.  At rho exactly on a clip edge, or where both
- * branches of the min are equal, the unclipped branch gives the derivative.
+ * In bf16 mode the derivative treats every rounding of the forward pass as the
+ * identity (straight-through): dL/dW uses the rounded layer input, dL/d(input)
+ * uses the rounded weight.  The paper fixes no precision for the update; the
+ * reading taken for bf16 networks is that the backward contractions take bf16
+ * operands just as the forward ones do.  So, in bf16 mode only:
+ *   - dL/dy is rounded to bf16 where the loss produces it;
+ *   - tanh' is 1 - a^2 with a the ROUNDED activation (the value the forward pass
+ *     handed to the next layer);
+ *   - every dL/d(pre-activation) = (sum_o W[i,o] d_o) (1 - a_i^2) is rounded to
+ *     bf16 where it is produced; the sum itself is not rounded (it is an
+ *     accumulator, fp32 in a kernel, double here);
+ *   - weight gradients are sums over the rows of (rounded input) x (rounded d),
+ *     bias gradients sums of the rounded d; the sums are not rounded.
+ * At rho exactly on a clip edge, or where both branches of the min are equal, the
+ * unclipped branch gives the derivative.
  *
  * Adam (Kingma & Ba, 2015) with bias correction, step counter k >= 1:
  *   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
@@ -41,7 +52,9 @@
  *
  * Pins (tests/test_oracle_learner.py): loss and every gradient against an
  * automatic-differentiation library on the same formulas (both distributions,
- * all clip regimes, bf16 straight-through), central finite differences of the
+ * all clip regimes; bf16: straight-through forward roundings, the backward
+ * roundings as gradient hooks of that library, and the distance to the gradient
+ * without backward roundings), central finite differences of the
  * loss, closed forms for all-zero parameters, exact zero policy gradient when
  * every row is clipped, Adam against its one- and two-step closed forms.
  */
@@ -106,10 +119,14 @@ static void net_forward(int in, int H, int out, int L, const double* P, const do
   }
 }
 
-/* Backward pass of one row: G += dL/dP given dy = dL/dy (straight-through across roundings).
+/* Backward pass of one row: G += dL/dP given dy_in = dL/dy (straight-through across the roundings of
+ * the forward pass; in bf16 mode dy and every dL/d(pre-activation) are rounded to bf16 and tanh' uses
+ * the rounded activation, see the header).
  * delta: scratch [L, H] (dL/d pre-activation of every hidden layer). */
 static void net_backward(int in, int H, int out, int L, const double* P, int bf16, const double* xin,
-                         const double* act, const double* dy, double* G, double* delta) {
+                         const double* act, const double* dy_in, double* G, double* delta) {
+  double* dy = (double*)malloc(sizeof(double) * (size_t)out);
+  for (int o = 0; o < out; ++o) dy[o] = rnd(dy_in[o], bf16);
   /* offsets of the layers' W inside the flat vector */
   const size_t first = (size_t)in * H + H, mid = (size_t)H * H + H;
   const size_t oWout = first + (size_t)(L - 1) * mid;
@@ -125,7 +142,7 @@ static void net_backward(int in, int H, int out, int L, const double* P, int bf1
         G[oWout + (size_t)i * out + o] += a_in * dy[o];
         da += rnd(P[oWout + (size_t)i * out + o], bf16) * dy[o];
       }
-      dl[i] = da * (1.0 - alast[i] * alast[i]);
+      dl[i] = rnd(da * (1.0 - a_in * a_in), bf16);
     }
   }
   /* hidden layers L-1 .. 1 (inputs: the hidden layer before) */
@@ -142,13 +159,14 @@ static void net_backward(int in, int H, int out, int L, const double* P, int bf1
         G[oW + (size_t)i * H + o] += a_in * dl[o];
         da += rnd(P[oW + (size_t)i * H + o], bf16) * dl[o];
       }
-      dprev[i] = da * (1.0 - ain[i] * ain[i]);
+      dprev[i] = rnd(da * (1.0 - a_in * a_in), bf16);
     }
   }
   /* layer 1 */
   for (int o = 0; o < H; ++o) G[(size_t)in * H + o] += delta[o];
   for (int i = 0; i < in; ++i)
     for (int o = 0; o < H; ++o) G[(size_t)i * H + o] += xin[i] * delta[o];
+  free(dy);
 }
 
 /*

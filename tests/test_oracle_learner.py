@@ -31,17 +31,54 @@ def bf16_ste(x):
     return x + (r - x).detach()
 
 
-def torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret):
-    """The objective written with library tensor ops; gradients come from autograd."""
+def to_bf16(t):
+    return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+
+class RoundGradient(torch.autograd.Function):
+    """Identity; the gradient that flows back through it is rounded to bfloat16."""
+
+    @staticmethod
+    def forward(ctx, x):
+        return x.clone()
+
+    @staticmethod
+    def backward(ctx, g):
+        return to_bf16(g)
+
+
+class TanhRoundedBackward(torch.autograd.Function):
+    """tanh whose derivative is taken at the bfloat16-rounded output, the result rounded to bfloat16."""
+
+    @staticmethod
+    def forward(ctx, z):
+        a = torch.tanh(z)
+        ctx.save_for_backward(to_bf16(a))
+        return a
+
+    @staticmethod
+    def backward(ctx, g):
+        (ar,) = ctx.saved_tensors
+        return to_bf16(g * (1.0 - ar * ar))
+
+
+def torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret, backward_rounding=True):
+    """The objective written with library tensor ops; gradients come from autograd.  In bf16 mode the
+    roundings of the forward pass are straight-through; with backward_rounding the gradient is also
+    rounded to bfloat16 at the network output and at every pre-activation, and tanh' uses the rounded
+    activation (the oracle's reading of a bf16 backward pass)."""
     P = torch.tensor(params, dtype=torch.float64, requires_grad=True)
     rnd = bf16_ste if pol.bf16 else (lambda t: t)
+    rb = pol.bf16 and backward_rounding
+    act = TanhRoundedBackward.apply if rb else torch.tanh
+    outg = RoundGradient.apply if rb else (lambda t: t)
 
     def net(p, out, x, width):
         parts, used = split_params(p, width, pol.hidden, out, pol.hidden_layers)
         h = torch.tensor(x, dtype=torch.float64)
         for l in range(pol.hidden_layers):
-            h = torch.tanh(rnd(h) @ rnd(parts[2 * l]) + parts[2 * l + 1])
-        return rnd(h) @ rnd(parts[-2]) + parts[-1], used
+            h = act(rnd(h) @ rnd(parts[2 * l]) + parts[2 * l + 1])
+        return outg(rnd(h) @ rnd(parts[-2]) + parts[-1]), used
 
     obs = np.asarray(obs, dtype=np.float64)
     y, used = net(P, pol.out_dim, obs, pol.in_dim)
@@ -103,6 +140,35 @@ def test_loss_and_gradient_against_autograd(dist, bf16):
     np.testing.assert_allclose(loss, t_loss, rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(stats[2], t_ent, rtol=1e-11)
     np.testing.assert_allclose(grad, t_grad, rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("dist", [ref.CATEGORICAL, ref.DIAG_GAUSSIAN])
+@pytest.mark.parametrize("layers", [2, 4])
+def test_bf16_backward_roundings_are_small_and_where_stated(dist, layers):
+    # The bf16 backward pass rounds dL/dy and every dL/d(pre-activation) to bfloat16 and takes tanh' at
+    # the rounded activation.  (a) That gradient stays within the bf16 tolerance (2e-2) of the one without those
+    # roundings (per network, in the Euclidean norm); (b) it is not the same gradient (the
+    # roundings are really there); (c) with operands that bf16 holds exactly the two coincide.
+    pol, params, obs, actions, logp_old, adv, ret = make_case(dist, True, 60 + dist + layers, R=64, layers=layers)
+    cfg = ref.ppo_cfg(clip=0.2, vf_coef=0.7, ent_coef=0.03)
+    _, grad, _ = ref.ppo_loss(pol, cfg, params, obs, actions, logp_old, adv, ret)
+    _, g_plain, _ = torch_objective(pol, cfg, params, obs, actions, logp_old, adv, ret, backward_rounding=False)
+    n_pi = pol.policy_param_count
+    for sl in (slice(0, n_pi), slice(n_pi, None)):       # per network, in the Euclidean norm
+        assert np.linalg.norm(grad[sl] - g_plain[sl]) <= 2e-2 * np.linalg.norm(g_plain[sl])
+    assert np.abs(grad - g_plain).max() > 0
+    # every rounding point of the backward pass is exact: no hidden layer (tanh never runs), and
+    # dL/dy a dyadic number -- one row, value net only: dv = c_v 2 (b - ret) with all weights zero
+    lin = ref.Policy(4, 8, 5, bf16=True, hidden_layers=1)
+    p0 = np.zeros(lin.param_count)
+    p0[-1] = 0.75
+    x = np.array([[0.5, -0.25, 1.0, 2.0]])
+    _, g1, _ = ref.ppo_loss(lin, ref.ppo_cfg(vf_coef=0.5, ent_coef=0.0), p0, x, np.array([1], np.int32),
+                            np.array([-np.log(5.0)]), np.zeros(1), np.array([0.25]))
+    assert g1[-1] == 0.5 * 2 * 0.5            # output bias of the value net: dv = 0.5, representable
+    _, g2, _ = torch_objective(lin, ref.ppo_cfg(vf_coef=0.5, ent_coef=0.0), p0, x, np.array([1], np.int32),
+                               np.array([-np.log(5.0)]), np.zeros(1), np.array([0.25]), backward_rounding=False)
+    np.testing.assert_allclose(g1[lin.policy_param_count:], g2[lin.policy_param_count:], rtol=1e-15, atol=0)
 
 
 @pytest.mark.parametrize("dist,bf16,group", [(ref.CATEGORICAL, False, 3), (ref.CATEGORICAL, True, 4),
