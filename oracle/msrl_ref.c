@@ -151,7 +151,7 @@ static void dense(const double* W, const double* b, int in, int out, const doubl
 }
 
 /* in - H - ... - H - out network with L >= 1 tanh hidden layers of H units (the paper's
- * evaluation uses a deeper policy than its listings: section 6, "seven-layer DNN"; the depth is a
+ * evaluation uses a deeper policy than its listings: section 7.1, "seven-layer DNN"; the depth is a
  * parameter here); params = W1 b1, then W b per further hidden layer, then the output layer's
  * W b, every W stored [inputs, outputs].  bf16 = 1 rounds every layer input and every weight to
  * bfloat16; sums, bias add and tanh are not rounded. */
@@ -352,7 +352,7 @@ void ref_particle_move(const ref_env_cfg* c, double* s, const int32_t* actions, 
 
 /* ---------------------------------------------------------------- pursuit ("tag") env
  *
- * The workload of the paper's GPU-only experiment (section 7.4, Fig. 10) is a pursuit task of the
+ * The workload of the paper's GPU-only experiment (section 7.3, Fig. 10) is a pursuit task of the
  * multi-agent particle family: heterogeneous agents (chasers and runners) with a policy per role,
  * rewards per role, and bodies that push each other apart.  The paper gives no formulas; this is a
  * synthetic stand-in defined here:

@@ -1,7 +1,7 @@
 """Pins of the oracle's pursuit ("tag") env: CPU only.
 
 The env is a synthetic stand-in defined in oracle/msrl_ref.c (the paper names the task of its
-GPU-only experiment, section 7.4, and gives no formulas).  It is pinned to things other than itself:
+GPU-only experiment, section 7.3, Fig. 10, and gives no formulas).  It is pinned to things other than itself:
 the particle env's move (already pinned) when bodies never touch, conservation of momentum by the
 contact forces, a two-body case worked out by hand, the speed limit, rewards and observations
 rebuilt with array operations, and the routing of the per-role parameter sets in the rollout loop.
@@ -164,3 +164,33 @@ def test_rollout_uses_one_parameter_set_per_role():
         np.testing.assert_array_equal(tr["rewards"][0, e * N:(e + 1) * N], r)
         np.testing.assert_array_equal(tr["obs"][1, e * N:(e + 1) * N], ref.env_obs(env, s1))
     assert (tr["dones"].sum(0) == 0).all() and (g == 5).all()
+
+
+def test_rollout_with_a_centralised_critic_per_role():
+    # value_in_dim = N * D with the pursuit env: every role has its own critic on the env's joint
+    # observation, and a role's parameter set is counted with the critic at that width.  A runner's value
+    # must come from the second set's critic (on the joint observation), a chaser's from the first set's.
+    rng = np.random.default_rng(6)
+    env = make_env()
+    pol = ref.Policy(D, 16, 5, value_in_dim=N * D)
+    n = pol.param_count
+    assert n == ref.net_param_count(D, 16, 5) + ref.net_param_count(N * D, 16, 1)
+    params = rng.normal(0, 0.5, 2 * n)
+    state, g = ref.init(env, 78, 0, 2)
+    tr = ref.rollout(env, pol, 78, 0, state, g, params, 2)
+    n_pi = pol.policy_param_count
+    for t in range(3):
+        for e in range(2):
+            joint = tr["obs"][t, e * N:(e + 1) * N]
+            v_role = [ref.central_value(pol, params[:n], joint), ref.central_value(pol, params[n:], joint)]
+            # the critic of a set is the plain network of its parameters on the concatenated rows
+            for k, role in enumerate((params[:n], params[n:])):
+                np.testing.assert_allclose(v_role[k], ref.mlp(N * D, 16, 1, role[n_pi:], joint.ravel())[0], rtol=1e-14)
+            assert abs(v_role[0] - v_role[1]) > 1e-3
+            for i in range(N):
+                m = e * N + i
+                k = 0 if i < NC else 1
+                assert tr["values"][t, m] == v_role[k]
+                if t < 2:
+                    role = params[:n] if k == 0 else params[n:]
+                    np.testing.assert_array_equal(tr["logits"][t, m], ref.mlp(D, 16, 5, role[:n_pi], tr["obs"][t, m]))
