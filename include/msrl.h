@@ -81,7 +81,7 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   obs_dim floats; s' = A s + B a + noise_std * N(0,I); reward
  *   -(s.s + act_cost * a.a) on the state before the step.  Reset: s ~ N(0,I).
  * MSRL_ENV_TAG: pursuit variant of the particle env (a stand-in for the task of
- *   the GPU-only experiment, section 7.4): the first num_chasers agents chase
+ *   the GPU-only experiment, section 7.3, Fig. 10): the first num_chasers agents chase
  *   the others ("runners"), with one parameter set per role (see
  *   msrl_policy_cfg.roles).  State and reset as MSRL_ENV_PARTICLE.  Observation
  *   of agent i, obs_dim = 4 + 2*num_landmarks + 4*(num_agents-1):
@@ -95,8 +95,9 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   -10 per chaser in contact with it, -10 * (max(0,|px|-1) + max(0,|py|-1)).
  *   Supported by msrl_rollout_step / msrl_rollout_gae (and the snapshot calls).
  *   The kernel has two workgroup shapes with identical results (one or four
- *   tiles of 32 envs); msrl_rollout_init picks by num_envs, the environment
- *   variable MSRL_TAG_TILES=1|4, read there, overrides the choice.
+ *   tiles of 32 envs); tag_tiles = 0 lets msrl_rollout_init pick by num_envs,
+ *   1 or 4 fixes the shape (EINVAL for any other value, and for a non-zero
+ *   value with another env kind).
  *
  * An episode ends (done = 1, then reset) on every step whose counter g
  * satisfies (g+1) % episode_len == 0; g counts the env's steps since init.
@@ -120,6 +121,7 @@ typedef struct {
   float vmax_c, vmax_r;      /* speed limits */
   float radius_c, radius_r;  /* body radii */
   float contact_force, contact_margin;
+  int32_t tag_tiles;      /* 0: chosen by the library; 1 or 4: 32-env tiles per workgroup */
 } msrl_env_cfg;
 
 /*
@@ -136,7 +138,7 @@ typedef struct {
  * with W row-major [in, out], so that y = x W + b.
  *
  * hidden_layers (0 means 2; 2..8): number of tanh layers of `hidden` units in
- * front of the output layer (the evaluation of the paper, section 6, uses a
+ * front of the output layer (the evaluation of the paper, section 7.1, uses a
  * seven-layer network).  Each layer beyond two adds one W[hidden, hidden]
  * b[hidden] pair in front of W3.  More than two layers are supported by
  * msrl_rollout_step / msrl_rollout_gae, by msrl_observe / msrl_env_step (which
@@ -319,9 +321,14 @@ typedef struct {
 /* Allocates the workspaces.  EINVAL unless hidden is a multiple of 32 and out_dim <= 32.
  * bfloat16 networks with two hidden layers of 64, 128 or 256 units, a categorical policy of at most
  * 16 actions and at most 62 inputs take the path that keeps the activations on chip (with a
- * centralised critic: the policy network only); everything else, and every learner created while the environment variable
- * MSRL_LEARNER_UNFUSED is set, the path through device memory.  Both compute the same gradient. */
+ * centralised critic: the policy network only); everything else the path through device memory.
+ * Both compute the same gradient (the same rounding points in bfloat16 mode). */
 int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_learner** out);
+/* The same with the choice of path made by the caller (tests and measurements: it keeps the
+ * device-memory kernels covered for configurations that would take the on-chip path).
+ * MSRL_LEARNER_PATH_AUTO is msrl_learner_init; EINVAL for an unknown path. */
+typedef enum { MSRL_LEARNER_PATH_AUTO = 0, MSRL_LEARNER_PATH_DEVICE_MEMORY = 1 } msrl_learner_path;
+int msrl_learner_init_path(const msrl_policy_cfg* policy, int64_t max_rows, int32_t path, msrl_learner** out);
 void msrl_learner_destroy(msrl_learner* learner);
 
 /*

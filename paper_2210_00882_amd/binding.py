@@ -22,7 +22,7 @@ MSRL_PHASE_ENV, MSRL_PHASE_MLP, MSRL_PHASE_CLOCKS = 1, 2, 3
 EXPORTS = (
     "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",
     "msrl_rollout_gae", "msrl_measure_phase", "msrl_observe", "msrl_act", "msrl_env_step",
-    "msrl_learner_init", "msrl_learner_destroy", "msrl_ppo_grad", "msrl_adam_step", "msrl_ppo_update", "msrl_params_cast", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
+    "msrl_learner_init", "msrl_learner_init_path", "msrl_learner_destroy", "msrl_ppo_grad", "msrl_adam_step", "msrl_ppo_update", "msrl_params_cast", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
 )
 
 
@@ -37,6 +37,7 @@ class msrl_env_cfg(C.Structure):
         ("num_chasers", C.c_int32), ("accel_c", C.c_float), ("accel_r", C.c_float),
         ("vmax_c", C.c_float), ("vmax_r", C.c_float), ("radius_c", C.c_float), ("radius_r", C.c_float),
         ("contact_force", C.c_float), ("contact_margin", C.c_float),
+        ("tag_tiles", C.c_int32),
     ]
 
 
@@ -97,6 +98,8 @@ def load():
     lib.msrl_env_step.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.msrl_learner_init.restype = C.c_int
     lib.msrl_learner_init.argtypes = [C.POINTER(msrl_policy_cfg), i64, C.POINTER(vp)]
+    lib.msrl_learner_init_path.restype = C.c_int
+    lib.msrl_learner_init_path.argtypes = [C.POINTER(msrl_policy_cfg), i64, i32, C.POINTER(vp)]
     lib.msrl_learner_destroy.restype = None
     lib.msrl_learner_destroy.argtypes = [vp]
     lib.msrl_ppo_grad.restype = C.c_int
@@ -143,7 +146,7 @@ def _stream(stream):
     return C.c_void_p(s.cuda_stream)
 
 
-def make_env_cfg(cfg, A=None, B=None):
+def make_env_cfg(cfg, A=None, B=None, tag_tiles=0):
     """msrl_env_cfg from a synth.Config; A, B float32 host arrays for lingauss.
     Returns (struct, keepalive)."""
     keep = []
@@ -156,7 +159,7 @@ def make_env_cfg(cfg, A=None, B=None):
     e = msrl_env_cfg(cfg.kind, cfg.num_envs, cfg.num_agents, cfg.num_landmarks, cfg.obs_dim, cfg.act_dim,
                      cfg.episode_len, cfg.dt, cfg.damping, cfg.force, cfg.radius, pa, pb,
                      cfg.noise_std, cfg.act_cost, cfg.num_chasers, cfg.accel_c, cfg.accel_r, cfg.vmax_c, cfg.vmax_r,
-                     cfg.radius_c, cfg.radius_r, cfg.contact_force, cfg.contact_margin)
+                     cfg.radius_c, cfg.radius_r, cfg.contact_force, cfg.contact_margin, tag_tiles)
     return e, keep
 
 
@@ -234,9 +237,18 @@ def make_ppo_cfg(clip=0.2, vf_coef=0.5, ent_coef=0.01, lr=3e-4, beta1=0.9, beta2
     return msrl_ppo_cfg(clip, vf_coef, ent_coef, lr, beta1, beta2, adam_eps)
 
 
+MSRL_LEARNER_PATH_AUTO, MSRL_LEARNER_PATH_DEVICE_MEMORY = 0, 1
+
+
 def msrl_learner_init(policy_cfg: msrl_policy_cfg, max_rows: int) -> C.c_void_p:
     L = C.c_void_p()
     _check(load().msrl_learner_init(C.byref(policy_cfg), C.c_int64(max_rows), C.byref(L)))
+    return L
+
+
+def msrl_learner_init_path(policy_cfg: msrl_policy_cfg, max_rows: int, path: int) -> C.c_void_p:
+    L = C.c_void_p()
+    _check(load().msrl_learner_init_path(C.byref(policy_cfg), C.c_int64(max_rows), C.c_int32(path), C.byref(L)))
     return L
 
 

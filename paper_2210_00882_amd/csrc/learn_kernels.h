@@ -72,6 +72,9 @@ __device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_elem(__bf16* p, float v) { *p = (__bf16)v; }
 __device__ __forceinline__ float load_elem(const float* p) { return *p; }
 __device__ __forceinline__ float load_elem(const __bf16* p) { return (float)*p; }
+// the value a store of element type S would hold (bf16: rounded to nearest even)
+__device__ __forceinline__ float as_stored(float v, const float*) { return v; }
+__device__ __forceinline__ float as_stored(float v, const __bf16*) { return (float)(__bf16)v; }
 
 // 8 consecutive elements as 16-byte pieces (the address must be 16-byte aligned: ld and column
 // offsets are multiples of 8 elements)
@@ -326,8 +329,10 @@ __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = 0.0f;
           }
+          // final values for the column pass, as the stores hold them: the column sums (a bias gradient)
+          // add up the same rounded values the weight-gradient contraction reads
 #pragma unroll
-          for (int e = 0; e < 8; ++e) t[rl * TW + c8 + e] = v[e];  // final values for the column pass
+          for (int e = 0; e < 8; ++e) t[rl * TW + c8 + e] = as_stored(v[e], (const SC*)nullptr);
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

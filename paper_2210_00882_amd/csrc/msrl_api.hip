@@ -70,8 +70,9 @@ namespace {
                   #expr, hipGetErrorString(e_));                                            \
   } while (0)
 
-std::vector<KernelEntry> all_kernels() {
-  return {entry_p1_h64_f32(),  entry_p2_h64_f32(),    entry_p3_h64_f32(), entry_p3_h64_bf16(),
+// the compiled rollout kernels (built once; find_kernel sits behind the per-step calls too)
+const std::vector<KernelEntry>& all_kernels() {
+  static const std::vector<KernelEntry> table = {entry_p1_h64_f32(),  entry_p2_h64_f32(),    entry_p3_h64_f32(), entry_p3_h64_bf16(),
           entry_p6_h128_f32(), entry_p10_h256_bf16(), entry_l17_6_h256(),
           entry_p10_h256_bf16_env(), entry_p10_h256_bf16_mlp(), entry_p10_h256_bf16_clocks(),
           entry_p3_h64_f32_env(),
@@ -85,6 +86,7 @@ std::vector<KernelEntry> all_kernels() {
           entry_p3_h64_f32_deep(), entry_p3_h64_bf16_deep(), entry_p10_h256_bf16_deep(),
           entry_l17_6_h256_deep(),
           entry_p3_h64_bf16_central(), entry_p10_h256_bf16_central()};
+  return table;
 }
 
 bool valid_policy(const msrl_policy_cfg* p) {
@@ -114,6 +116,14 @@ bool valid_env_shape(const msrl_env_cfg* e) {
     return e->num_landmarks >= 0 && e->num_chasers >= 1 && e->num_chasers < e->num_agents &&
            e->obs_dim == 4 + 2 * e->num_landmarks + 4 * (e->num_agents - 1) && e->contact_margin > 0.0f;
   return false;
+}
+
+// Pursuit env: 32-env tiles per workgroup.  Four tiles (16 waves behind one copy of the weights in LDS,
+// four waves per SIMD) once that still gives most compute units a workgroup, one tile (more, smaller
+// workgroups, two per compute unit) below.
+bool tag_tiles_compiled(int tiles) { return tiles == 1 || tiles == 4; }
+int choose_tag_tiles(int num_envs, int cus) {
+  return (int64_t)(num_envs / 128) * 8 >= (int64_t)cus * 5 ? 4 : 1;
 }
 
 size_t net_params(int in, int h, int out, int layers) {
@@ -365,6 +375,91 @@ int enqueue_tag(msrl_state* st, const void* params, int32_t T, msrl_traj* out, h
   return MSRL_OK;
 }
 
+// Host-side set-up of a state for (env, policy): argument checks, kernel selection, launch shape and
+// the layout of the packed parameters.  Touches no device memory: every device pointer of *st is
+// left null and *packed_bytes says how large the packed image is.  `who` names the caller in messages.
+int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, const msrl_policy_cfg* policy,
+                    uint64_t seed, size_t* packed_bytes) {
+  if (!valid_env_shape(env))
+    return fail(MSRL_EINVAL, "%s: inconsistent environment configuration "
+                             "(kind %d, envs %d, agents %d, landmarks %d, obs_dim %d, episode_len %d)",
+                who, env->kind, env->num_envs, env->num_agents, env->num_landmarks, env->obs_dim, env->episode_len);
+  if (!valid_policy(policy)) return fail(MSRL_EINVAL, "%s: invalid policy configuration", who);
+  if (policy->in_dim != env->obs_dim)
+    return fail(MSRL_EINVAL, "%s: policy in_dim %d != obs_dim %d", who, policy->in_dim, env->obs_dim);
+  if (roles_of(*policy) != (env->kind == MSRL_ENV_TAG ? 2 : 1))
+    return fail(MSRL_EINVAL, "%s: the pursuit env takes two parameter sets (roles = 2), the others one", who);
+  if (env->kind == MSRL_ENV_PARTICLE || env->kind == MSRL_ENV_TAG) {
+    if (policy->dist != MSRL_CATEGORICAL || policy->out_dim != 5)
+      return fail(MSRL_EINVAL, "%s: the particle envs need a categorical policy with out_dim 5", who);
+  } else {
+    if (policy->dist != MSRL_DIAG_GAUSSIAN || policy->out_dim != 2 * env->act_dim)
+      return fail(MSRL_EINVAL, "%s: the lingauss env needs a Gaussian policy with out_dim 2*act_dim", who);
+  }
+  if (central_of(*policy) &&
+      (env->kind != MSRL_ENV_PARTICLE || policy->value_in_dim != env->num_agents * policy->in_dim ||
+       policy->dtype != MSRL_BF16 || layers_of(*policy) != 2))
+    return fail(MSRL_EINVAL, "%s: value_in_dim %d: a centralised critic takes num_agents * in_dim = %d "
+                             "inputs (particle env, bfloat16 networks, two hidden layers)",
+                who, policy->value_in_dim, env->num_agents * policy->in_dim);
+  if (env->tag_tiles != 0 && (env->kind != MSRL_ENV_TAG || !tag_tiles_compiled(env->tag_tiles)))
+    return fail(MSRL_EINVAL, "%s: tag_tiles %d (0 lets the library choose; 1 or 4, pursuit env only)", who,
+                env->tag_tiles);
+  // kernel selection
+  KernelEntry found;
+  memset(&found, 0, sizeof(found));
+  found.envs_per_wave = 32;
+  found.waves = 1;
+  const bool ok = env->kind == MSRL_ENV_TAG
+                      ? policy->dtype == MSRL_BF16 && layers_of(*policy) == 2 &&
+                            tag_rollout_compiled(env->num_chasers, env->num_agents - env->num_chasers,
+                                                 env->num_landmarks, policy->hidden)
+                      : find_kernel(*env, *policy, PHASE_ALL, &found);
+  if (!ok)
+    return fail(MSRL_EUNSUPPORTED,
+                "%s: no kernel compiled for kind %d, agents %d, landmarks %d, obs_dim %d, "
+                "act_dim %d, hidden %d, dtype %d",
+                who, env->kind, env->num_agents, env->num_landmarks, env->obs_dim, env->act_dim, policy->hidden,
+                policy->dtype);
+
+  memset(st, 0, sizeof(*st));
+  st->env = *env;
+  st->env.A = nullptr;
+  st->env.B = nullptr;
+  st->pol = *policy;
+  st->seed = seed;
+  st->kernel = found;
+  int cus = 256;
+  if (hipGetDevice(&st->device) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, st->device) != hipSuccess || cus < 1)
+    return fail(MSRL_EDEVICE, "%s: cannot query the current device", who);
+  {
+    // Every workgroup runs all T steps, so the launch takes ceil(blocks / CUs) rounds.  Shrink the
+    // block to the smallest size that needs no more rounds than the largest one: equal work per
+    // workgroup instead of a short last round.  (Rounds are counted per CU even where several
+    // workgroups fit one: they would share its SIMDs, and a wave with fewer rows costs the same.)
+    const int64_t max_epb = (int64_t)found.envs_per_wave * found.waves;
+    const int64_t blocks_max = (env->num_envs + max_epb - 1) / max_epb;
+    const int64_t rounds = (blocks_max + cus - 1) / cus;
+    int64_t epb = (env->num_envs + rounds * cus - 1) / (rounds * cus);
+    if (epb < 1) epb = 1;
+    if (epb > max_epb) epb = max_epb;
+    st->envs_per_block = (int)epb;
+  }
+  // Pursuit env: tiles of 32 envs per workgroup (msrl_env_cfg.tag_tiles, 0 = chosen here).
+  st->tag_tiles = env->tag_tiles != 0 ? env->tag_tiles : choose_tag_tiles(env->num_envs, cus);
+  st->state_size = (int)msrl_env_state_size(env);
+  // The particle observation ends in 2 (N - 1) slots that are always zero: layer 1 skips them.
+  st->in_used = env->kind == MSRL_ENV_PARTICLE ? 4 * env->num_agents + 2 : policy->in_dim;
+  const int n_nets = 2 * roles_of(*policy);
+  st->layout = net_layout(st->in_used, policy->hidden, policy->dtype == MSRL_BF16, layers_of(*policy));
+  st->central = central_of(*policy);
+  // (joint observation: num_agents blocks of whole layer-1 tiles, see pack_params)
+  st->critic_layout = net_layout(env->num_agents * tiles_for_inputs(st->in_used + 1, true) * 16 - 1, policy->hidden, true);
+  *packed_bytes = st->central ? st->layout.bytes + st->critic_layout.bytes : n_nets * st->layout.bytes;
+  return MSRL_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -388,96 +483,18 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
                       msrl_state** out) {
   if (!env || !policy || !out) return fail(MSRL_EINVAL, "msrl_rollout_init: NULL argument");
   *out = nullptr;
-  if (!valid_env_shape(env))
-    return fail(MSRL_EINVAL, "msrl_rollout_init: inconsistent environment configuration "
-                             "(kind %d, envs %d, agents %d, landmarks %d, obs_dim %d, episode_len %d)",
-                env->kind, env->num_envs, env->num_agents, env->num_landmarks, env->obs_dim, env->episode_len);
-  if (!valid_policy(policy)) return fail(MSRL_EINVAL, "msrl_rollout_init: invalid policy configuration");
-  if (policy->in_dim != env->obs_dim)
-    return fail(MSRL_EINVAL, "msrl_rollout_init: policy in_dim %d != obs_dim %d", policy->in_dim, env->obs_dim);
-  if (roles_of(*policy) != (env->kind == MSRL_ENV_TAG ? 2 : 1))
-    return fail(MSRL_EINVAL, "msrl_rollout_init: the pursuit env takes two parameter sets (roles = 2), the others one");
-  if (env->kind == MSRL_ENV_PARTICLE || env->kind == MSRL_ENV_TAG) {
-    if (policy->dist != MSRL_CATEGORICAL || policy->out_dim != 5)
-      return fail(MSRL_EINVAL, "msrl_rollout_init: the particle envs need a categorical policy with out_dim 5");
-  } else {
-    if (policy->dist != MSRL_DIAG_GAUSSIAN || policy->out_dim != 2 * env->act_dim)
-      return fail(MSRL_EINVAL, "msrl_rollout_init: the lingauss env needs a Gaussian policy with out_dim 2*act_dim");
-    if (!env->A || !env->B) return fail(MSRL_EINVAL, "msrl_rollout_init: lingauss needs A and B");
-  }
-  if (central_of(*policy) &&
-      (env->kind != MSRL_ENV_PARTICLE || policy->value_in_dim != env->num_agents * policy->in_dim ||
-       policy->dtype != MSRL_BF16 || layers_of(*policy) != 2))
-    return fail(MSRL_EINVAL, "msrl_rollout_init: value_in_dim %d: a centralised critic takes num_agents * in_dim = %d "
-                             "inputs (particle env, bfloat16 networks, two hidden layers)",
-                policy->value_in_dim, env->num_agents * policy->in_dim);
-  // kernel selection
-  KernelEntry found;
-  memset(&found, 0, sizeof(found));
-  found.envs_per_wave = 32;
-  found.waves = 1;
-  const bool ok = env->kind == MSRL_ENV_TAG
-                      ? policy->dtype == MSRL_BF16 && layers_of(*policy) == 2 &&
-                            tag_rollout_compiled(env->num_chasers, env->num_agents - env->num_chasers,
-                                                 env->num_landmarks, policy->hidden)
-                      : find_kernel(*env, *policy, PHASE_ALL, &found);
-  if (!ok)
-    return fail(MSRL_EUNSUPPORTED,
-                "msrl_rollout_init: no kernel compiled for kind %d, agents %d, landmarks %d, obs_dim %d, "
-                "act_dim %d, hidden %d, dtype %d",
-                env->kind, env->num_agents, env->num_landmarks, env->obs_dim, env->act_dim, policy->hidden,
-                policy->dtype);
-
   msrl_state* st = new (std::nothrow) msrl_state;
   if (!st) return fail(MSRL_ENOMEM, "msrl_rollout_init: host allocation failed");
-  memset(st, 0, sizeof(*st));
-  st->env = *env;
-  st->env.A = nullptr;
-  st->env.B = nullptr;
-  st->pol = *policy;
-  st->seed = seed;
-  st->kernel = found;
-  {
-    // Every workgroup runs all T steps, so the launch takes ceil(blocks / CUs) rounds.  Shrink the
-    // block to the smallest size that needs no more rounds than the largest one: equal work per
-    // workgroup instead of a short last round.  (Rounds are counted per CU even where several
-    // workgroups fit one: they would share its SIMDs, and a wave with fewer rows costs the same.)
-    hipDeviceProp_t prop;
-    int dev = 0;
-    int cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      cus = prop.multiProcessorCount;
-    const int64_t max_epb = (int64_t)found.envs_per_wave * found.waves;
-    const int64_t blocks_max = (env->num_envs + max_epb - 1) / max_epb;
-    const int64_t rounds = (blocks_max + cus - 1) / cus;
-    int64_t epb = (env->num_envs + rounds * cus - 1) / (rounds * cus);
-    if (epb < 1) epb = 1;
-    if (epb > max_epb) epb = max_epb;
-    st->envs_per_block = (int)epb;
+  size_t packed_bytes = 0;
+  int rc = configure_state(st, "msrl_rollout_init", env, policy, seed, &packed_bytes);
+  if (rc != MSRL_OK) {
+    delete st;
+    return rc;
   }
-  {
-    // Pursuit env: four tiles per workgroup (16 waves behind one copy of the weights in LDS) once that
-    // still gives most compute units a workgroup, one tile (more, smaller workgroups) below.  The
-    // environment variable MSRL_TAG_TILES (1 or 4) overrides the choice.
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-      cus = 256;
-    st->tag_tiles = (int64_t)(env->num_envs / 128) * 8 >= (int64_t)cus * 5 ? 4 : 1;
-    const char* force = getenv("MSRL_TAG_TILES");
-    if (force && (force[0] == '1' || force[0] == '4') && force[1] == 0) st->tag_tiles = force[0] - '0';
+  if (env->kind == MSRL_ENV_LINGAUSS && (!env->A || !env->B)) {
+    delete st;
+    return fail(MSRL_EINVAL, "msrl_rollout_init: lingauss needs A and B");
   }
-  st->state_size = (int)msrl_env_state_size(env);
-  // The particle observation ends in 2 (N - 1) slots that are always zero: layer 1 skips them.
-  st->in_used = env->kind == MSRL_ENV_PARTICLE ? 4 * env->num_agents + 2 : policy->in_dim;
-  const int n_nets = 2 * roles_of(*policy);
-  st->layout = net_layout(st->in_used, policy->hidden, policy->dtype == MSRL_BF16, layers_of(*policy));
-  st->central = central_of(*policy);
-  // (joint observation: num_agents blocks of whole layer-1 tiles, see pack_params)
-  st->critic_layout = net_layout(env->num_agents * tiles_for_inputs(st->in_used + 1, true) * 16 - 1, policy->hidden, true);
-  const size_t packed_bytes = st->central ? st->layout.bytes + st->critic_layout.bytes : n_nets * st->layout.bytes;
-
-  int rc = MSRL_OK;
   auto cleanup = [&](int code) {
     msrl_rollout_destroy(st);
     return code;
@@ -492,7 +509,6 @@ int msrl_rollout_init(const msrl_env_cfg* env, const msrl_policy_cfg* policy, ui
     }                                                                                          \
   } while (0)
 
-  INIT_TRY(hipGetDevice(&st->device));
   const size_t E = (size_t)env->num_envs;
   INIT_TRY(hipMalloc((void**)&st->env_state, E * st->state_size * sizeof(float)));
   INIT_TRY(hipMalloc((void**)&st->g, E * sizeof(int64_t)));

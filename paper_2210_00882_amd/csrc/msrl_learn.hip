@@ -442,7 +442,13 @@ int check_learner_args(const char* who, msrl_learner* L, const void* params, int
 extern "C" {
 
 int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_learner** out) {
+  return msrl_learner_init_path(policy, max_rows, MSRL_LEARNER_PATH_AUTO, out);
+}
+
+int msrl_learner_init_path(const msrl_policy_cfg* policy, int64_t max_rows, int32_t path, msrl_learner** out) {
   if (!policy || !out) return fail(MSRL_EINVAL, "msrl_learner_init: NULL argument");
+  if (path != MSRL_LEARNER_PATH_AUTO && path != MSRL_LEARNER_PATH_DEVICE_MEMORY)
+    return fail(MSRL_EINVAL, "msrl_learner_init_path: unknown path %d", path);
   *out = nullptr;
   if (policy->in_dim < 1 || policy->hidden < 32 || policy->hidden % 32 != 0 || policy->out_dim < 1 ||
       policy->out_dim > 32 || (policy->dtype != MSRL_F32 && policy->dtype != MSRL_BF16) ||
@@ -476,7 +482,7 @@ int msrl_learner_init(const msrl_policy_cfg* policy, int64_t max_rows, msrl_lear
   L->kt1 = policy->in_dim + 2 <= 32 ? 2 : 4;
   L->fused_policy = L->bf16 && policy->dist == MSRL_CATEGORICAL && policy->out_dim <= 16 && policy->in_dim + 2 <= 64 &&
                     (policy->hidden == 64 || policy->hidden == 128 || policy->hidden == 256) && L->layers == 2 &&
-                    !getenv("MSRL_LEARNER_UNFUSED");
+                    path != MSRL_LEARNER_PATH_DEVICE_MEMORY;
   L->fused = L->fused_policy && L->G == 1;
   L->fly = net_layout(16 * L->kt1 - 1, policy->hidden, true);
   int rc = MSRL_OK;

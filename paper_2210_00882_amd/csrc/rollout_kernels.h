@@ -732,6 +732,10 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           if (net == 1) {
             ws.wait_oldest();
             if (FULL && t > 0) flush(t - 1, 0x1f);
+            // The flush reads s_out / s_done of step t-1; the next writes to them are this step's values,
+            // behind the value network.  A network of several stages has a stage barrier in between; one
+            // that fits a single stage has none, so the order is made explicit here.
+            if constexpr (Stream::STAGES_PER_NET == 1) __syncthreads();
           }
           Net::layer1(&s_l1[net][0] + lane, x, h1);
           stamp(net == 0 ? CLK_P_L1 : CLK_V_L1);

@@ -1,6 +1,6 @@
 // Fused actor + environment rollout for the pursuit ("tag") env: heterogeneous agents with one
 // parameter set per role (interface header, MSRL_ENV_TAG; the task of the paper's GPU-only
-// experiment, section 7.4, as a synthetic stand-in).
+// experiment, section 7.3, Fig. 10, as a synthetic stand-in).
 //
 // Layout: a workgroup owns TILES tiles of 32 envs and has one wave per tile and agent slot; lane n of
 // a wave is env n of its tile, so the 32 rows of a wave's MFMA tile all have the same role and use

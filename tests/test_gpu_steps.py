@@ -117,3 +117,113 @@ def test_observe_and_act_leave_the_state_alone_and_argument_errors():
         with pytest.raises(B.MsrlError) as e:
             B.msrl_env_step(gpu.state, a, None, None, obs)
         assert e.value.code == B.MSRL_EINVAL
+
+
+ACT_CASES = {
+    "n3_f32_ragged": lambda: synth.CONFIGS[1].with_(num_envs=53, episode_len=4),
+    "n1_f32": lambda: synth.particle("p1", 70, 1, 64, 6, 3, synth.F32, 11),
+    "n2_f32": lambda: synth.particle("p2", 37, 2, 64, 6, 3, synth.F32, 13),
+    "n6_f32": lambda: synth.CONFIGS[3].with_(num_envs=77, episode_len=5),
+    "n3_bf16": lambda: synth.particle("p3b", 45, 3, 64, 6, 3, synth.BF16, 12),
+    "n10_bf16": lambda: synth.CONFIGS[5].with_(num_envs=100, episode_len=3),
+    "lingauss": lambda: synth.CONFIGS[4].with_(num_envs=150, episode_len=3),
+}
+
+
+def _caller_rows(cfg, rng, kind):
+    """Observation rows [M, D] that no state of the library produced."""
+    M, D, N = cfg.M, cfg.obs_dim, cfg.num_agents
+    if kind == "random":
+        rows = rng.standard_normal((M, D)).astype(np.float32) * np.float32(0.7)
+    else:                                          # large and tiny magnitudes: tanh saturation, bf16 rounding
+        rows = (rng.standard_normal((M, D)) * rng.choice([1e-3, 0.3, 4.0], size=(M, 1))).astype(np.float32)
+    if cfg.kind == synth.PARTICLE and N > 1:       # the trailing 2 (N - 1) slots of the layout are zero
+        rows[:, D - 2 * (N - 1):] = 0.0
+    return rows
+
+
+@pytest.mark.parametrize("which", sorted(ACT_CASES))
+def test_act_on_caller_chosen_rows_against_the_oracle(which):
+    """The actor fragment of DP-A / DP-B (section 6, Table 2) acts on observations that come from outside the
+    device fragment: rows the test draws itself, and rows of a different env batch.  Networks against
+    the oracle row by row; the sampler against the oracle's, fed the GPU's logits and the Philox
+    counters (env, agent, step counter of the state)."""
+    import torch
+    cfg = ACT_CASES[which]()
+    env, pol, params, dyn = oracle_setup(cfg)
+    bf16 = cfg.dtype == synth.BF16
+    net_tol = 2e-2 if bf16 else TOL_F32
+    N, M, D = cfg.num_agents, cfg.M, cfg.obs_dim
+    rng = np.random.default_rng(17)
+    seed = 901
+    # rows of another env batch (other seed, a few steps in)
+    with GpuRollout(cfg, params.astype(np.float32), 555, dyn=dyn) as other:
+        other.run(3, gae=False, logits=False)
+        foreign = torch.empty((M, D), dtype=torch.float32, device="cuda")
+        other.B.msrl_observe(other.state, foreign)
+        torch.cuda.synchronize()
+        foreign = foreign.cpu().numpy()
+    with GpuRollout(cfg, params.astype(np.float32), seed, dyn=dyn) as gpu:
+        B = gpu.B
+        # distinct, non-zero step counters: the noise must be the one of (env, agent, g[env])
+        g = (rng.integers(1, 1000, size=cfg.num_envs)).astype(np.int64)
+        gpu.set_state(None, g)
+        for label, rows in (("random", _caller_rows(cfg, rng, "random")),
+                            ("scaled", _caller_rows(cfg, rng, "scaled")),
+                            ("foreign", foreign)):
+            obs = torch.from_numpy(rows).cuda()
+            a = torch.full((M,) if cfg.dist == synth.CATEGORICAL else (M, cfg.act_dim), -7,
+                           dtype=torch.int32 if cfg.dist == synth.CATEGORICAL else torch.float32, device="cuda")
+            lp = torch.full((M,), -77.0, device="cuda")
+            v = torch.full((M,), -77.0, device="cuda")
+            lg = torch.full((M, cfg.out_dim), -77.0, device="cuda")
+            B.msrl_act(gpu.state, gpu.params, obs, a, lp, v, lg)
+            torch.cuda.synchronize()
+            a, lp, v, lg = a.cpu().numpy(), lp.cpu().numpy(), v.cpu().numpy(), lg.cpu().numpy()
+            edges = 0
+            for m in range(M):
+                e, i = divmod(m, N)
+                lg_o, v_o = ref.policy_value(pol, params, rows[m])
+                assert_close(lg[m], lg_o, net_tol, f"{label}: logits row {m}")
+                assert_close(v[m], v_o, net_tol, f"{label}: value row {m}")
+                a_o, lp_o, mg = ref.sample(pol, seed, e, i, int(g[e]), lg[m])
+                if cfg.dist == synth.CATEGORICAL:
+                    if int(a[m]) != a_o:
+                        assert mg < 1e-5, f"{label}: action row {m}: gpu {a[m]} oracle {a_o} margin {mg}"
+                        edges += 1
+                        z = lg[m].astype(np.float64) - lg[m].max()
+                        lp_o = float(z[int(a[m])] - np.log(np.exp(z).sum()))
+                else:
+                    assert_close(a[m], a_o, TOL_F32, f"{label}: action row {m}")
+                assert_close(lp[m], lp_o, TOL_F32, f"{label}: logp row {m}")
+            assert edges <= 2
+        es1, g1 = gpu.get_state()
+        np.testing.assert_array_equal(g1, g)      # acting does not advance the state
+
+
+@pytest.mark.parametrize("which", sorted(ACT_CASES))
+def test_observe_against_the_oracle(which):
+    """msrl_observe == the oracle's observation of the state msrl_state_get returns, at the initial
+    state, after a rollout (mid-episode, moving agents) and for a state the test injects."""
+    import torch
+    cfg = ACT_CASES[which]()
+    env, _, params, dyn = oracle_setup(cfg)
+    N, M, D = cfg.num_agents, cfg.M, cfg.obs_dim
+    rng = np.random.default_rng(23)
+    with GpuRollout(cfg, params.astype(np.float32), 77, dyn=dyn) as gpu:
+        obs = torch.empty((M, D), dtype=torch.float32, device="cuda")
+
+        def check(label):
+            obs.fill_(-77.0)
+            gpu.B.msrl_observe(gpu.state, obs)
+            torch.cuda.synchronize()
+            o = obs.cpu().numpy()
+            es, _ = gpu.get_state()
+            for e in range(cfg.num_envs):
+                assert_close(o[e * N:(e + 1) * N], ref.env_obs(env, es[e].astype(np.float64)), TOL_F32,
+                             f"{label}: env {e}")
+        check("initial")
+        gpu.run(5, gae=False, logits=False)
+        check("after 5 steps")
+        gpu.set_state(rng.standard_normal((cfg.num_envs, cfg.env_state_size)).astype(np.float32), None)
+        check("injected")

@@ -81,17 +81,16 @@ def check(cfg, tr, env, pol, params, env_ids, g0, T):
 
 @pytest.mark.parametrize("tiles,E", [(1, 70), (4, 70), (4, 300)])
 @pytest.mark.parametrize("nc,nr,L", [(3, 1, 2), (2, 2, 1)])
-def test_tag_rollout_every_env_and_step(nc, nr, L, tiles, E, monkeypatch):
-    # both workgroup shapes (one or four 32-env tiles, MSRL_TAG_TILES is read by msrl_rollout_init): E = 70 is
+def test_tag_rollout_every_env_and_step(nc, nr, L, tiles, E):
+    # both workgroup shapes (one or four 32-env tiles, msrl_env_cfg.tag_tiles): E = 70 is
     # one ragged workgroup of four tiles with an empty tile, E = 300 three workgroups with a ragged last tile
-    monkeypatch.setenv("MSRL_TAG_TILES", str(tiles))
     # big bodies, so that contact forces and contact rewards occur in most steps
     cfg = synth.tag("tag", E, nc, nr, L, 64, 20 if E < 100 else 8, 7, idx=50 + nc).with_(radius_c=0.3, radius_r=0.25)
     env = tag_env(cfg)
     pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
     params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
     assert params.size == 2 * pol.param_count
-    with GpuRollout(cfg, params.astype(np.float32), SEED) as gpu:
+    with GpuRollout(cfg, params.astype(np.float32), SEED, tag_tiles=tiles) as gpu:
         es0, g0 = gpu.get_state()
         np.testing.assert_array_equal(es0[3], ref.env_reset(env, SEED, 3, 0).astype(np.float32))
         shift = (np.arange(cfg.num_envs) * 3 + 1).astype(np.int64)     # a different episode phase per env
