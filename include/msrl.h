@@ -234,6 +234,32 @@ int msrl_rollout_gae(msrl_state* st, const void* params, int32_t T,
                      float gamma, float lambda, msrl_traj* out, void* hip_stream);
 
 /*
+ * msrl_rollout_gae for callers that cannot allocate device memory and cannot let the library do it
+ * either: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It
+ * takes no msrl_state and calls no hipMalloc / hipFree or any other allocating routine.
+ *   - The env batch is the caller's: env_state DEVICE [num_envs, msrl_env_state_size] floats and
+ *     step_counters DEVICE [num_envs] int64, in the layout of msrl_state_get / msrl_state_set; both
+ *     are read at the start and advanced in place, so consecutive calls continue the trajectory as
+ *     consecutive msrl_rollout_gae calls do.  (An initial state can come from msrl_state_get of a
+ *     state made at set-up time, or from the caller's own draws.)
+ *   - The re-ordered parameter image, which msrl_rollout_init would allocate, lives in a static
+ *     device array of the library of MSRL_STATIC_SCRATCH_BYTES per GPU (held until the process
+ *     ends).  A configuration whose image is larger (e.g. 256-unit networks with more than three
+ *     hidden layers) is refused with MSRL_EUNSUPPORTED, as is MSRL_ENV_LINGAUSS (its dynamics
+ *     matrices are HOST pointers and would need a device copy).
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress); make that
+ *     call outside a graph capture.
+ *   - Every call on a GPU uses that GPU's one array: two such calls that overlap in time on one
+ *     GPU (different streams or threads) race; calls on one stream are ordered and safe.
+ * Same arguments, results and errors as msrl_rollout_init(env, policy, seed) followed by
+ * msrl_rollout_gae otherwise (env->A and env->B are ignored).
+ */
+#define MSRL_STATIC_SCRATCH_BYTES (1u << 20)
+int msrl_rollout_gae_static(const msrl_env_cfg* env, const msrl_policy_cfg* policy, uint64_t seed,
+                            float* env_state, int64_t* step_counters, const void* params, int32_t T,
+                            float gamma, float lambda, msrl_traj* out, void* hip_stream);
+
+/*
  * Measurement only (phase rooflines of the rollout kernel; not part of the
  * method).  Same arguments as msrl_rollout_step.
  *   MSRL_PHASE_ENV: the rollout with both networks skipped.  Logits and values

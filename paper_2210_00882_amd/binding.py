@@ -21,7 +21,7 @@ MSRL_PHASE_ENV, MSRL_PHASE_MLP, MSRL_PHASE_CLOCKS = 1, 2, 3
 
 EXPORTS = (
     "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",
-    "msrl_rollout_gae", "msrl_measure_phase", "msrl_observe", "msrl_act", "msrl_env_step",
+    "msrl_rollout_gae", "msrl_rollout_gae_static", "msrl_measure_phase", "msrl_observe", "msrl_act", "msrl_env_step",
     "msrl_learner_init", "msrl_learner_init_path", "msrl_learner_destroy", "msrl_ppo_grad", "msrl_adam_step", "msrl_ppo_update", "msrl_params_cast", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
 )
 
@@ -88,6 +88,9 @@ def load():
     lib.msrl_gae.argtypes = [vp, vp, vp, i32, i64, f32, f32, vp, vp, vp]
     lib.msrl_rollout_gae.restype = C.c_int
     lib.msrl_rollout_gae.argtypes = [vp, vp, i32, f32, f32, C.POINTER(msrl_traj), vp]
+    lib.msrl_rollout_gae_static.restype = C.c_int
+    lib.msrl_rollout_gae_static.argtypes = [C.POINTER(msrl_env_cfg), C.POINTER(msrl_policy_cfg), u64, vp, vp, vp, i32,
+                                            f32, f32, C.POINTER(msrl_traj), vp]
     lib.msrl_measure_phase.restype = C.c_int
     lib.msrl_measure_phase.argtypes = [vp, vp, i32, C.POINTER(msrl_traj), i32, vp]
     lib.msrl_observe.restype = C.c_int
@@ -211,6 +214,18 @@ def msrl_rollout_gae(state, params, T: int, gamma: float, lam: float, out: dict,
     tr = _traj(out)
     _check(load().msrl_rollout_gae(state, _ptr(params), C.c_int32(T), C.c_float(gamma), C.c_float(lam),
                                    C.byref(tr), _stream(stream)))
+
+
+MSRL_STATIC_SCRATCH_BYTES = 1 << 20
+
+
+def msrl_rollout_gae_static(env_cfg: msrl_env_cfg, policy_cfg: msrl_policy_cfg, seed: int, env_state, step_counters,
+                            params, T: int, gamma: float, lam: float, out: dict, stream=None) -> None:
+    """env_state float32 [E, S] and step_counters int64 [E]: device tensors, advanced in place."""
+    tr = _traj(out)
+    _check(load().msrl_rollout_gae_static(C.byref(env_cfg), C.byref(policy_cfg), C.c_uint64(seed), _ptr(env_state),
+                                          _ptr(step_counters), _ptr(params), C.c_int32(T), C.c_float(gamma),
+                                          C.c_float(lam), C.byref(tr), _stream(stream)))
 
 
 def msrl_measure_phase(state, params, T: int, out: dict, phase: int, stream=None) -> None:

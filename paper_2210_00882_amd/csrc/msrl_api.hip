@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -462,6 +463,44 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
 
 }  // namespace
 
+// ------------------------------------------------------------------ the entry point that allocates nothing
+// msrl_rollout_gae_static keeps the packed parameter image (the buffer msrl_rollout_init would
+// allocate) in this array.  Every GPU holds its own copy at its own address; in host code the name
+// below is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) uint8_t scratch[MSRL_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+uint8_t* g_scratch_ptr[MAX_DEVICES];  // device address of `scratch` on device d, looked up on first use
+
+// address of the scratch array on the current device (looked up once per device, with it current)
+int scratch_of_current_device(uint8_t** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES)
+    return fail(MSRL_EUNSUPPORTED, "msrl_rollout_gae_static: device index %d is beyond the %d devices it keeps track of",
+                dev, MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(MSRL_EDEVICE, "msrl_rollout_gae_static: the scratch array has no address on device %d", dev);
+    g_scratch_ptr[dev] = (uint8_t*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MSRL_OK;
+}
+
+// p[0 .. n) <- 0 in 16-byte pieces (a kernel rather than a memset node: the call may be captured into a graph)
+__global__ void zero16_kernel(uint4* p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* msrl_last_error(void) { return g_err; }
@@ -586,6 +625,45 @@ int msrl_rollout_gae(msrl_state* st, const void* params, int32_t T, float gamma,
   const int64_t M = (int64_t)st->env.num_envs * st->env.num_agents;
   HIP_TRY(launch_gae(out->rewards, out->values, out->dones, T, M, gamma, lambda, out->adv, out->ret,
                      (hipStream_t)hip_stream));
+  return MSRL_OK;
+}
+
+int msrl_rollout_gae_static(const msrl_env_cfg* env, const msrl_policy_cfg* policy, uint64_t seed,
+                            float* env_state, int64_t* step_counters, const void* params, int32_t T,
+                            float gamma, float lambda, msrl_traj* out, void* hip_stream) {
+  if (!env || !policy || !env_state || !step_counters || !params)
+    return fail(MSRL_EINVAL, "msrl_rollout_gae_static: NULL argument");
+  if (T <= 0) return fail(MSRL_EINVAL, "msrl_rollout_gae_static: T must be positive (got %d)", T);
+  if (env->kind == MSRL_ENV_LINGAUSS)
+    return fail(MSRL_EUNSUPPORTED, "msrl_rollout_gae_static: the lingauss env is not supported (its dynamics "
+                                   "matrices need a device copy, which msrl_rollout_init makes)");
+  msrl_state st;  // lives for this call only; every device pointer in it is the caller's or the scratch array
+  size_t packed_bytes = 0;
+  int rc = configure_state(&st, "msrl_rollout_gae_static", env, policy, seed, &packed_bytes);
+  if (rc != MSRL_OK) return rc;
+  if (packed_bytes > (size_t)MSRL_STATIC_SCRATCH_BYTES)
+    return fail(MSRL_EUNSUPPORTED, "msrl_rollout_gae_static: the packed parameters of this configuration take %zu "
+                                   "bytes, the static scratch array holds %zu; use msrl_rollout_init + msrl_rollout_gae",
+                packed_bytes, (size_t)MSRL_STATIC_SCRATCH_BYTES);
+  rc = check_traj(&st, out, true);
+  if (rc != MSRL_OK) return rc;
+  uint8_t* sp = nullptr;
+  rc = scratch_of_current_device(&sp);
+  if (rc != MSRL_OK) return rc;
+  st.env_state = env_state;
+  st.g = step_counters;
+  st.packed = sp;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  // The array keeps the image of the last call, whatever its configuration was: clear the part this
+  // call uses (the packing kernel writes the weights and leaves the padding tiles alone).
+  const size_t pieces = (packed_bytes + 15) / 16;
+  hipLaunchKernelGGL(zero16_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, stream, (uint4*)sp, pieces);
+  HIP_TRY(hipGetLastError());
+  rc = env->kind == MSRL_ENV_TAG ? enqueue_tag(&st, params, T, out, stream)
+                                 : enqueue_rollout(&st, st.kernel, params, T, out, stream);
+  if (rc != MSRL_OK) return rc;
+  const int64_t M = (int64_t)env->num_envs * env->num_agents;
+  HIP_TRY(launch_gae(out->rewards, out->values, out->dones, T, M, gamma, lambda, out->adv, out->ret, stream));
   return MSRL_OK;
 }
 
