@@ -114,6 +114,45 @@ __device__ __forceinline__ void tanh_range(const f32x16& acc, float (&t)[16], in
     if (r >= r0 && r < r1 && pinned) pin(t[r]);
 }
 
+// tanh of accumulator registers [r0, r1) in three stages, each closed by pins, so that a caller can put
+// an MFMA between the stages: the independent chains of a stage follow one another (no dependent
+// instruction directly behind a transcendental one, so no wait states), and the matrix pipe gets its
+// next instruction while the chains are half way.
+//   stage 1: w = 2^(c x) + 1     stage 2: w = 1 / w     stage 3: t = 1 - 2 w
+__device__ __forceinline__ void tanh_stage1(const f32x16& acc, float (&w)[16], int r0, int r1) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) {
+      w[r] = acc[r];
+      pin(w[r]);
+    }
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) w[r] = __builtin_amdgcn_exp2f(w[r] * 2.8853900817779268f);
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) w[r] = w[r] + 1.0f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) pin(w[r]);
+}
+__device__ __forceinline__ void tanh_stage2(float (&w)[16], int r0, int r1) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) w[r] = __builtin_amdgcn_rcpf(w[r]);
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) pin(w[r]);
+}
+__device__ __forceinline__ void tanh_stage3(const float (&w)[16], float (&t)[16], int r0, int r1) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) t[r] = 1.0f - 2.0f * w[r];
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+    if (r >= r0 && r < r1) pin(t[r]);
+}
+
 // the 16 activated values of a chunk as the next layer's B operands
 template <bool BF16>
 __device__ __forceinline__ void to_operands(const float (&t)[16], typename Operand<BF16>::T* out) {
@@ -147,6 +186,9 @@ struct Mlp {
                                                          // tile, layer-3 tiles of chunk c-1, of chunk c
   static constexpr int L3_PREV = KT2 + 1, L3_OWN = KT2 + 1 + TPC;
   static constexpr int G = 4;  // LDS reads run G tiles ahead of the MFMAs that consume them
+  // bf16: one MFMA per tile and (with 256 units) one activation per tile, so the tanh chains are taken two
+  // tiles at a time (see tanh_stage1); fp32 tiles are four MFMAs long and hide a chain each as they are
+  static constexpr bool PAIRED = BF16 && KT2 % 2 == 0;
 
   // tanh of the previous chunk, spread over the NT tiles of the current one
   template <int NT>
@@ -209,6 +251,34 @@ struct Mlp {
       prev[q] = acc[q];
       acc[q] = zero16();
     }
+    if constexpr (PIPE && PAIRED) {
+      // two tiles per round: the tanh chains of both tiles' share of the chunk before run side by side,
+      // the second tile's MFMAs sit between their first and second stage
+      float w[NB][16];
+#pragma unroll
+      for (int kt = 0; kt < KT2; kt += 2) {
+        const int r0 = kt * 16 / KT2, r1 = (kt + 2) * 16 / KT2;
+        u32x4 raw = ring[kt % G];
+        if (kt + G < L3_PREV + TPC) ring[kt % G] = tiles[(kt + G) * 64];
+        pin(raw);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) tanh_stage1(prev[q], w[q], r0, r1);
+        u32x4 raw2 = ring[(kt + 1) % G];
+        if (kt + 1 + G < L3_PREV + TPC) ring[(kt + 1) % G] = tiles[(kt + 1 + G) * 64];
+        pin(raw2);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw2, &h1[q][(kt + 1) * PT], acc[q]);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+          tanh_stage2(w[q], r0, r1);
+          tanh_stage3(w[q], t[q], r0, r1);
+        }
+        tick(kt);
+        tick(kt + 1);
+      }
+    } else {
 #pragma unroll
     for (int kt = 0; kt < KT2; ++kt) {
       u32x4 raw = ring[kt % G];
@@ -218,6 +288,7 @@ struct Mlp {
       for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
       if (PIPE) tanh_slice<KT2>(prev, t, kt);
       tick(kt);
+    }
     }
     {
       const Op one = Operand<BF16>::one(h);
@@ -235,6 +306,99 @@ struct Mlp {
         const u32x4 raw = ring[(L3_PREV + i) % G];
 #pragma unroll
         for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h2[q][i * PT], out[q]);
+      }
+    }
+  }
+
+  // The CPS chunk blocks of one stage (consecutive in the LDS buffer) as one stream of tiles: the ring of
+  // LDS reads runs on across the chunk boundaries, so the latency of the first reads is paid once per
+  // stage (behind its barrier) and not once per chunk.  Chunk 0 is piped (its predecessor's tanh and
+  // layer-3 share run beside it) iff PIPE0; the later chunks always are.  tick(c, kt) once per layer-2 tile.
+  template <bool PIPE0, int CPS, class Tick>
+  __device__ static __forceinline__ void layer2_chunks(const u32x4* tiles, const Op (&h1)[NB][KT2 * PT],
+                                                       f32x16 (&acc)[NB], f32x16 (&out)[NB], int h,
+                                                       Tick&& tick) {
+    // tiles a chunk consumes, in order: its KT2 layer-2 tiles, its bias tile and, if piped, the TPC
+    // layer-3 tiles fed by the chunk before it; they are consecutive inside the chunk block
+    constexpr int PER0 = KT2 + 1 + (PIPE0 ? TPC : 0), PERN = KT2 + 1 + TPC;
+    constexpr int TOTAL = PER0 + (CPS - 1) * PERN;
+    auto tile_at = [](int p) -> int {  // position in the stream -> tile index in the buffer
+      if (p < PER0) return p;
+      const int q = p - PER0;
+      return (1 + q / PERN) * CHUNK_TILES + q % PERN;
+    };
+    u32x4 ring[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) ring[i] = tiles[tile_at(i) * 64];
+    // next tile of the stream; the slot it leaves is refilled G positions ahead
+    auto pop = [&](int p) -> u32x4 {
+      const u32x4 raw = ring[p % G];
+      if (p + G < TOTAL) ring[p % G] = tiles[tile_at(p + G) * 64];
+      return raw;
+    };
+#pragma unroll
+    for (int c = 0; c < CPS; ++c) {
+      const bool pipe = PIPE0 || c > 0;
+      const int p0 = c == 0 ? 0 : PER0 + (c - 1) * PERN;  // position of the chunk's first tile
+      f32x16 prev[NB];
+      float t[NB][16];
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        prev[q] = acc[q];
+        acc[q] = zero16();
+      }
+      if (pipe && PAIRED) {
+        // two tiles per round: the tanh chains of both tiles' share of the chunk before run side by
+        // side, the second tile's MFMAs sit between their first and second stage
+        float w[NB][16];
+#pragma unroll
+        for (int kt = 0; kt < KT2; kt += 2) {
+          const int r0 = kt * 16 / KT2, r1 = (kt + 2) * 16 / KT2;
+          u32x4 raw = pop(p0 + kt);
+          pin(raw);
+#pragma unroll
+          for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
+#pragma unroll
+          for (int q = 0; q < NB; ++q) tanh_stage1(prev[q], w[q], r0, r1);
+          u32x4 raw2 = pop(p0 + kt + 1);
+          pin(raw2);
+#pragma unroll
+          for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw2, &h1[q][(kt + 1) * PT], acc[q]);
+#pragma unroll
+          for (int q = 0; q < NB; ++q) {
+            tanh_stage2(w[q], r0, r1);
+            tanh_stage3(w[q], t[q], r0, r1);
+          }
+          tick(c, kt);
+          tick(c, kt + 1);
+        }
+      } else {
+#pragma unroll
+        for (int kt = 0; kt < KT2; ++kt) {
+          u32x4 raw = pop(p0 + kt);
+          if (pipe) pin(raw);
+#pragma unroll
+          for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
+          if (pipe) tanh_slice<KT2>(prev, t, kt);
+          tick(c, kt);
+        }
+      }
+      {
+        const Op one = Operand<BF16>::one(h);
+        const u32x4 raw = pop(p0 + KT2);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) mma_bias_tile<BF16>(raw, one, acc[q]);
+      }
+      if (pipe) {
+        Op h2[NB][PC];
+#pragma unroll
+        for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], h2[q]);
+#pragma unroll
+        for (int i = 0; i < TPC; ++i) {
+          const u32x4 raw = pop(p0 + KT2 + 1 + i);
+#pragma unroll
+          for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h2[q][i * PT], out[q]);
+        }
       }
     }
   }

@@ -751,20 +751,18 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             int next = net * Stream::STAGES_PER_NET + sc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
             if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
             const int nbuf = (gs + Stream::AHEAD) % NBUF;
-  #pragma unroll
-            for (int c = 0; c < CPS; ++c) {
-              const u32x4* tiles = ws.tiles(gs % NBUF, c);
+            {
               // the copies of the stage AHEAD stages later, spread over this stage's tile loops
-              auto tick = [&](int kt) {
+              auto tick = [&](int c, int kt) {
   #pragma unroll
                 for (int i = 0; i < Stream::PER_WAVE; ++i)
                   if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
               };
-              if (c == 0 && sc == 0)
-                Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
+              if (sc == 0)
+                Net::template layer2_chunks<false, CPS>(ws.tiles(gs % NBUF, 0), h1, acc, out, h, tick);
               else
-                Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
-              if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
+                Net::template layer2_chunks<true, CPS>(ws.tiles(gs % NBUF, 0), h1, acc, out, h, tick);
+              if (sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(ws.tiles(gs % NBUF, CPS - 1), acc, out);
             }
             ++gs;
             if (sc < 5) stamp((net == 0 ? CLK_P_STAGE : CLK_V_STAGE) + sc);
