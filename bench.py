@@ -93,6 +93,46 @@ def cpu_baseline(cfg, seed, seconds_target=15.0):
     }
 
 
+def other_config(B, synth, torch, idx, steps, with_cpu):
+    """One of the smaller configurations in the same way as the headline one: the whole call, the rollout
+    kernel alone (HIP events), its fraction of the MFMA peak of its dtype, and the oracle on a bounded sample."""
+    cfg = synth.CONFIGS[idx]
+    dyn = synth.make_dynamics(cfg) if cfg.kind == synth.LINGAUSS else (None, None)
+    env_cfg, keep = B.make_env_cfg(cfg, *dyn)
+    state = B.msrl_rollout_init(env_cfg, B.make_policy_cfg(cfg), cfg.env_seed)
+    dparams = B.upload_params(cfg, synth.make_params(cfg))
+    out = B.alloc_traj(cfg, cfg.T, logits=False, gae=True)
+    T, steps_per_call = cfg.T, cfg.T * cfg.M
+    for _ in range(2):
+        B.msrl_rollout_gae(state, dparams, T, cfg.gamma, cfg.lam, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.msrl_rollout_gae(state, dparams, T, cfg.gamma, cfg.lam, out)
+    torch.cuda.synchronize()
+    ms_call = (time.perf_counter() - t0) / steps * 1e3
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    for k in range(steps):
+        ev[k][0].record()
+        B.msrl_rollout_step(state, dparams, T, out)
+        ev[k][1].record()
+    torch.cuda.synchronize()
+    roll_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    B.msrl_rollout_destroy(state)
+    dt_name = "bf16" if cfg.dtype == synth.BF16 else "f32"
+    tf = mlp_flops_per_agent_step(cfg) * steps_per_call / (roll_ms * 1e-3) / 1e12
+    res = {"workload": cfg.name, "dtype": dt_name, "rows_M": cfg.M, "T": T, "agent_steps_per_call": steps_per_call,
+           "ms_per_call": ms_call, "agent_steps_per_s": steps_per_call / (ms_call * 1e-3),
+           "rollout_ms_per_launch": roll_ms,
+           "roofline": {"kernel": "rollout", "bound": "mfma", "achieved": tf, "peak": PEAK_TFLOPS[dt_name],
+                        "unit": "TFLOP/s", "frac": tf / PEAK_TFLOPS[dt_name]},
+           "hbm_GBps": (rollout_bytes_per_agent_step(cfg) + GAE_BYTES_PER_AGENT_STEP) * steps_per_call / (ms_call * 1e-3) / 1e9}
+    if with_cpu:
+        res["cpu_baseline"] = cpu_baseline(cfg, cfg.env_seed, seconds_target=3.0)
+    del out
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,6 +141,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="synthetic configuration 1..5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-phases", action="store_true", help="skip the env-only / MLP-only phase timings")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the figures of the smaller configurations")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this size (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -361,7 +402,7 @@ def main():
 
         # one training iteration of Listing 1 at that scale: a 25-step episode of 100,000 agents (rollout + GAE),
         # then the learner's update of both roles on the 2.5 M rows it produced (one pass, four minibatches per
-        # role; the rows of a role are gathered with torch.index_select) -- the kind of figure the paper's
+        # role; a role's rows are named by an msrl_row_select, nothing is copied) -- the kind of figure the paper's
         # "time per episode" (Fig. 10b) is, on a different task definition
         try:
             ecfg = synth.tag("tag_100k_agents_episode", 25000, 3, 1, 2, 64, 25, 25)
@@ -374,10 +415,11 @@ def main():
             m1, v1 = torch.zeros_like(master), torch.zeros_like(master)
             acting = torch.empty(master.numel(), dtype=torch.bfloat16, device="cuda")
             eout = B.alloc_traj(ecfg, ecfg.T, logits=False, gae=True)
-            agent = torch.arange(ecfg.T * ecfg.M, device="cuda") % ecfg.num_agents
-            sets = [torch.nonzero(agent < ecfg.num_chasers).flatten(), torch.nonzero(agent >= ecfg.num_chasers).flatten()]
+            N_, NC_ = ecfg.num_agents, ecfg.num_chasers
+            sets = [B.msrl_row_select(N_, 0, NC_), B.msrl_row_select(N_, NC_, N_ - NC_)]   # the rows of each role
+            counts = [ecfg.T * ecfg.num_envs * r.count for r in sets]
             mbs = 4
-            learners = [B.msrl_learner_init(one_role, -(-int(r.numel()) // mbs) + mbs) for r in sets]
+            learners = [B.msrl_learner_init(one_role, -(-c // mbs) + mbs) for c in counts]
             pc = B.make_ppo_cfg(lr=3e-4)
             flat = lambda t: t.reshape(-1, *t.shape[2:])
             evs = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -390,9 +432,9 @@ def main():
                 batch = [flat(eout["obs"][:ecfg.T]), flat(eout["actions"]), flat(eout["logp"]), flat(eout["adv"]),
                          flat(eout["ret"])]
                 for r in range(2):
-                    sel = [t.index_select(0, sets[r]) for t in batch]
                     sl = slice(r * n_role, (r + 1) * n_role)
-                    ksteps[r] = B.msrl_ppo_update(learners[r], master[sl], m1[sl], v1[sl], ksteps[r], 1, mbs, *sel, pc)
+                    ksteps[r] = B.msrl_ppo_update(learners[r], master[sl], m1[sl], v1[sl], ksteps[r], 1, mbs, *batch, pc,
+                                                  rows=sets[r])
                 evs[2].record()
                 torch.cuda.synchronize()
                 if k > 0:
@@ -443,6 +485,15 @@ def main():
     del out
     torch.cuda.empty_cache()
 
+    # the smaller configurations (the parity-test cases) in the same JSON line, for the record
+    others = None
+    if not args.no_other_configs:
+        others = {}
+        for idx in sorted(synth.CONFIGS):
+            if idx != args.config:
+                others[f"cfg{idx}"] = other_config(B, synth, torch, idx, max(3, args.steps), not args.no_cpu_baseline)
+        torch.cuda.empty_cache()
+
     result = {
         "metric": "agent-steps/sec of fused rollout+GAE at 1 GPU",
         "value": agent_steps / (ms_per_step * 1e-3),
@@ -456,6 +507,7 @@ def main():
         "roofline": roofline,
         "roofline_gae": roofline_gae,
         "phases": phases,
+        "other_configs": others,
         "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(cfg, seed),
     }
     print(json.dumps(result))

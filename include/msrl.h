@@ -337,7 +337,17 @@ int msrl_env_step(msrl_state* st, const void* actions, float* rewards, uint8_t* 
  *   L = mean_rows( policy term - ent_coef H ) + vf_coef mean_groups (V_theta(group) - ret)^2.
  * R must then be a multiple of G (EINVAL otherwise), and msrl_ppo_update cuts
  * its blocks at group boundaries.
+ *
+ * Rows of one role.  Listing 1 runs one learner per agent role, each on the rows of its own agents;
+ * in a stored trajectory those rows are interleaved with the other roles' (row = (t, env, agent)).
+ * msrl_row_select names them without a copy: selected row r (0 <= r < R) is row
+ *   (r / count) * group + first + r % count
+ * of obs, actions, logp_old, adv and ret, i.e. with group = num_agents the agents first ..
+ * first + count - 1 of every env at every step.  NULL selects every row (row r is row r).  EINVAL
+ * unless group >= 1, first >= 0, count >= 1, first + count <= group, and for a selection together
+ * with a centralised critic (which reads whole groups of rows).
  */
+typedef struct { int32_t group, first, count; } msrl_row_select;
 typedef struct msrl_learner msrl_learner; /* opaque: workspaces for up to max_rows rows per call */
 typedef struct {
   float clip, vf_coef, ent_coef;
@@ -367,7 +377,8 @@ void msrl_learner_destroy(msrl_learner* learner);
  */
 int msrl_ppo_grad(msrl_learner* learner, const float* params, int64_t R, const float* obs,
                   const void* actions, const float* logp_old, const float* adv, const float* ret,
-                  const msrl_ppo_cfg* cfg, float* grad, float* stats, void* hip_stream);
+                  const msrl_row_select* rows, const msrl_ppo_cfg* cfg, float* grad, float* stats,
+                  void* hip_stream);
 
 /* One Adam step on n parameters, in place; k >= 1 is the number of this step. */
 int msrl_adam_step(float* params, float* m, float* v, const float* grad, int64_t n, int64_t k,
@@ -387,7 +398,11 @@ int msrl_params_cast(const float* master, void* out, int64_t n, int32_t dtype, v
 int msrl_ppo_update(msrl_learner* learner, float* params, float* m, float* v, int64_t* step_counter,
                     int64_t R, int32_t iters, int32_t minibatches, const float* obs,
                     const void* actions, const float* logp_old, const float* adv, const float* ret,
-                    const msrl_ppo_cfg* cfg, void* hip_stream);
+                    const msrl_row_select* rows, const msrl_ppo_cfg* cfg, void* hip_stream);
+
+/* out[0] (DEVICE) <- mean of x over the R selected rows (x: DEVICE, one float per row; rows as above,
+ * NULL = rows 0 .. R-1): e.g. the mean reward of one role's agents over a stored trajectory. */
+int msrl_rows_mean(const float* x, int64_t R, const msrl_row_select* rows, float* out, void* hip_stream);
 
 /*
  * Snapshot / restore of the env batch.  env_state: HOST

@@ -22,7 +22,7 @@ MSRL_PHASE_ENV, MSRL_PHASE_MLP, MSRL_PHASE_CLOCKS = 1, 2, 3
 EXPORTS = (
     "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",
     "msrl_rollout_gae", "msrl_rollout_gae_static", "msrl_measure_phase", "msrl_observe", "msrl_act", "msrl_env_step",
-    "msrl_learner_init", "msrl_learner_init_path", "msrl_learner_destroy", "msrl_ppo_grad", "msrl_adam_step", "msrl_ppo_update", "msrl_params_cast", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
+    "msrl_learner_init", "msrl_learner_init_path", "msrl_learner_destroy", "msrl_ppo_grad", "msrl_rows_mean", "msrl_adam_step", "msrl_ppo_update", "msrl_params_cast", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
 )
 
 
@@ -50,6 +50,10 @@ class msrl_policy_cfg(C.Structure):
 class msrl_traj(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
                 ("obs", "actions", "logp", "rewards", "dones", "values", "logits", "adv", "ret")]
+
+
+class msrl_row_select(C.Structure):
+    _fields_ = [("group", C.c_int32), ("first", C.c_int32), ("count", C.c_int32)]
 
 
 class msrl_ppo_cfg(C.Structure):
@@ -106,14 +110,17 @@ def load():
     lib.msrl_learner_destroy.restype = None
     lib.msrl_learner_destroy.argtypes = [vp]
     lib.msrl_ppo_grad.restype = C.c_int
-    lib.msrl_ppo_grad.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, C.POINTER(msrl_ppo_cfg), vp, vp, vp]
+    lib.msrl_ppo_grad.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, C.POINTER(msrl_row_select),
+                                  C.POINTER(msrl_ppo_cfg), vp, vp, vp]
+    lib.msrl_rows_mean.restype = C.c_int
+    lib.msrl_rows_mean.argtypes = [vp, i64, C.POINTER(msrl_row_select), vp, vp]
     lib.msrl_adam_step.restype = C.c_int
     lib.msrl_adam_step.argtypes = [vp, vp, vp, vp, i64, i64, C.POINTER(msrl_ppo_cfg), vp]
     lib.msrl_params_cast.restype = C.c_int
     lib.msrl_params_cast.argtypes = [vp, vp, i64, i32, vp]
     lib.msrl_ppo_update.restype = C.c_int
     lib.msrl_ppo_update.argtypes = [vp, vp, vp, vp, C.POINTER(i64), i64, i32, i32, vp, vp, vp, vp, vp,
-                                    C.POINTER(msrl_ppo_cfg), vp]
+                                    C.POINTER(msrl_row_select), C.POINTER(msrl_ppo_cfg), vp]
     lib.msrl_state_get.restype = C.c_int
     lib.msrl_state_get.argtypes = [vp, vp, vp]
     lib.msrl_state_set.restype = C.c_int
@@ -271,12 +278,29 @@ def msrl_learner_destroy(learner) -> None:
     load().msrl_learner_destroy(learner)
 
 
+def _selected(n_rows: int, rows):
+    """(number of selected rows, pointer argument) for a row selection over arrays of n_rows rows."""
+    if rows is None:
+        return n_rows, None
+    if rows.group < 1:      # (the library rejects it)
+        return n_rows, C.byref(rows)
+    return n_rows // rows.group * rows.count, C.byref(rows)
+
+
 def msrl_ppo_grad(learner, params, obs, actions, logp_old, adv, ret, cfg: msrl_ppo_cfg, grad, stats=None,
-                  stream=None) -> None:
-    """All tensors on the device; params / grad float32 [param_count]; rows = logp_old.numel()."""
-    _check(load().msrl_ppo_grad(learner, _ptr(params), C.c_int64(logp_old.numel()), _ptr(obs), _ptr(actions),
-                                _ptr(logp_old), _ptr(adv), _ptr(ret), C.byref(cfg), _ptr(grad), _ptr(stats),
+                  stream=None, rows: msrl_row_select | None = None) -> None:
+    """All tensors on the device; params / grad float32 [param_count].  rows: optional msrl_row_select over the
+    rows of the given arrays (one role's rows of a stored trajectory); default every row."""
+    R, sel = _selected(logp_old.numel(), rows)
+    _check(load().msrl_ppo_grad(learner, _ptr(params), C.c_int64(R), _ptr(obs), _ptr(actions),
+                                _ptr(logp_old), _ptr(adv), _ptr(ret), sel, C.byref(cfg), _ptr(grad), _ptr(stats),
                                 _stream(stream)))
+
+
+def msrl_rows_mean(x, out, rows: msrl_row_select | None = None, stream=None) -> None:
+    """out[0] (device float32) <- mean of x (one float per row) over the selected rows."""
+    R, sel = _selected(x.numel(), rows)
+    _check(load().msrl_rows_mean(_ptr(x), C.c_int64(R), sel, _ptr(out), _stream(stream)))
 
 
 def msrl_adam_step(params, m, v, grad, k: int, cfg: msrl_ppo_cfg, stream=None) -> None:
@@ -290,12 +314,13 @@ def msrl_params_cast(master, out, dtype: int, stream=None) -> None:
 
 
 def msrl_ppo_update(learner, params, m, v, step: int, iters: int, minibatches: int, obs, actions, logp_old, adv,
-                    ret, cfg: msrl_ppo_cfg, stream=None) -> int:
+                    ret, cfg: msrl_ppo_cfg, stream=None, rows: msrl_row_select | None = None) -> int:
     """-> the new step counter; params, m, v (float32, device) are updated in place."""
     k = C.c_int64(step)
+    R, sel = _selected(logp_old.numel(), rows)
     _check(load().msrl_ppo_update(learner, _ptr(params), _ptr(m), _ptr(v), C.byref(k),
-                                  C.c_int64(logp_old.numel()), C.c_int32(iters), C.c_int32(minibatches),
-                                  _ptr(obs), _ptr(actions), _ptr(logp_old), _ptr(adv), _ptr(ret), C.byref(cfg),
+                                  C.c_int64(R), C.c_int32(iters), C.c_int32(minibatches),
+                                  _ptr(obs), _ptr(actions), _ptr(logp_old), _ptr(adv), _ptr(ret), sel, C.byref(cfg),
                                   _stream(stream)))
     return int(k.value)
 

@@ -18,6 +18,7 @@
 // surrogate objective stated with msrl_ppo_grad in the interface header).
 #pragma once
 #include "mlp.h"
+#include "row_sel.h"
 
 namespace msrl {
 
@@ -38,6 +39,7 @@ struct RowsArgs {
   // tiled unit-major outputs (bf16): xt has 16 KT1 units, h1t .. dz1t have H, dyt has 16
   __bf16 *xt, *h1t, *h2t, *dz2t, *dz1t, *dyt;
   float* stats;  // bins as in LossArgs
+  RowSel sel;    // where row r of this call lies in obs, actions, logp_old, adv, ret
 };
 
 __device__ __forceinline__ uint32_t quad_swap1(uint32_t x) {  // value of lane ^ 1
@@ -288,17 +290,18 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     const bool live = tile < a.n_tiles;  // uniform over the wave
     const int64_t row = tile * 32 + n;
     const bool valid = live && row < a.R;
+    const int64_t prow = valid ? a.sel.at(row) : 0;  // the row inside the caller's arrays
     ws.wait_oldest();  // forward stage 0 is in; every wave has left the previous tile
     // per-row inputs of the loss, fetched early
     int act = 0;
     float lpo = 0.0f, adv = 0.0f, ret = 0.0f;
     if (valid) {
       if constexpr (NET == 0) {
-        act = ((const int32_t*)a.actions)[row];
-        lpo = a.logp_old[row];
-        adv = a.adv[row];
+        act = ((const int32_t*)a.actions)[prow];
+        lpo = a.logp_old[prow];
+        adv = a.adv[prow];
       } else {
-        ret = a.ret[row];
+        ret = a.ret[prow];
       }
     }
 
@@ -309,11 +312,11 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
       f32x8 f;
       const int i0 = 16 * kt + 8 * h;
       if (valid && a.obs_vec4 && i0 + 8 <= a.D) {
-        const f32x4 u = *(const f32x4*)(a.obs + row * a.D + i0), w = *(const f32x4*)(a.obs + row * a.D + i0 + 4);
+        const f32x4 u = *(const f32x4*)(a.obs + prow * a.D + i0), w = *(const f32x4*)(a.obs + prow * a.D + i0 + 4);
         f = f32x8{u[0], u[1], u[2], u[3], w[0], w[1], w[2], w[3]};
       } else {
 #pragma unroll
-        for (int s = 0; s < 8; ++s) f[s] = (valid && i0 + s < a.D) ? a.obs[row * a.D + i0 + s] : 0.0f;
+        for (int s = 0; s < 8; ++s) f[s] = (valid && i0 + s < a.D) ? a.obs[prow * a.D + i0 + s] : 0.0f;
       }
 #pragma unroll
       for (int s = 0; s < 8; ++s)

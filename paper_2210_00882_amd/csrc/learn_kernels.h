@@ -13,6 +13,7 @@
 // is bounds-checked against the extents passed in.
 #pragma once
 #include "dev_common.h"
+#include "row_sel.h"
 
 namespace msrl {
 
@@ -473,6 +474,16 @@ __global__ void convert_pad_kernel(const S* src, int64_t rows, int64_t cols, int
   store_elem(dst + idx, (r < rows && c < cols) ? load_elem(src + r * lds_ + c) : 0.0f);
 }
 
+// dst[r][c] = src[sel.at(r)][c] converted, zero for c in [cols, ldd) and for r in [rows, rows_pad)
+template <typename D>
+__global__ void gather_pad_kernel(const float* src, RowSel sel, int64_t rows, int64_t cols, int64_t lds_, D* dst,
+                                  int64_t ldd, int64_t rows_pad) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= rows_pad * ldd) return;
+  const int64_t r = idx / ldd, c = idx % ldd;
+  store_elem(dst + idx, (r < rows && c < cols) ? src[sel.at(r) * lds_ + c] : 0.0f);
+}
+
 __global__ void fill_kernel(float* p, int64_t n, float v) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < n) p[idx] = v;
@@ -521,6 +532,7 @@ struct LossArgs {
   int64_t Rv, Rv_pad;
   float inv_Rv;
   int policy, value;  // which of the two parts this launch computes (the other one's buffers are not touched)
+  RowSel sel;         // where row n of this call lies in actions, logp_old, adv, ret
 };
 
 // One row per lane.  Every loop runs over the 32 padded columns with a predicate, so that the
@@ -536,6 +548,7 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
     float dv = 0.0f;
     if (n < a.R && a.policy) {
       const int O = a.out_dim;
+      const int64_t pn = a.sel.at(n);
       float y[32];
 #pragma unroll
       for (int k = 0; k < 32; k += 4) {
@@ -555,7 +568,7 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
 #pragma unroll
         for (int k = 0; k < 32; ++k) z += k < O ? expf(y[k] - mx) : 0.0f;
         const float lse = mx + logf(z);
-        const int act = ((const int32_t*)a.actions)[n];
+        const int act = ((const int32_t*)a.actions)[pn];
 #pragma unroll
         for (int k = 0; k < 32; ++k) {
           const float lp = y[k] - lse;
@@ -577,7 +590,7 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
 #pragma unroll
             for (int k = 0; k < 32; ++k) ls = k == K + d ? y[k] : ls;
             const float mu = y[d], sg = expf(ls);
-            const float e = (((const float*)a.actions)[n * K + d] - mu) / sg;
+            const float e = (((const float*)a.actions)[pn * K + d] - mu) / sg;
             logp += -0.5f * e * e - ls - 0.9189385332046727f;
             ent += ls + 1.4189385332046727f;
             dlp[d] = e / sg;
@@ -589,7 +602,7 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
           }
         }
       }
-      const float rho = expf(logp - a.logp_old[n]), A = a.adv[n];
+      const float rho = expf(logp - a.logp_old[pn]), A = a.adv[pn];
       const float rc = fminf(fmaxf(rho, 1.0f - a.clip), 1.0f + a.clip);
       const float un = rho * A, cl = rc * A;
       const bool clipped = cl < un;
@@ -599,10 +612,10 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
       s_pi = -(clipped ? cl : un);
       s_h = ent;
       s_c = clipped ? 1.0f : 0.0f;
-      s_kl = a.logp_old[n] - logp;
+      s_kl = a.logp_old[pn] - logp;
     }
     if (n < a.Rv && a.value) {  // thread n also takes group n of the value network
-      const float err = a.v[n * 32] - a.ret[n * a.G];
+      const float err = a.v[n * 32] - a.ret[a.sel.at(n * a.G)];
       dv = a.vf_coef * 2.0f * err * a.inv_Rv;
       s_v = err * err;
     }
@@ -645,6 +658,19 @@ __global__ __launch_bounds__(64) void stats_reduce_kernel(float* stats) {
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
     if (threadIdx.x == 0) stats[q] = s;
   }
+}
+
+// out[0] += scale * sum of x[sel.at(r)], r < rows (one float atomic per workgroup; out cleared by the caller)
+__global__ __launch_bounds__(256) void rows_sum_kernel(const float* x, RowSel sel, int64_t rows, float scale, float* out) {
+  __shared__ float part[4];
+  float s = 0.0f;
+  for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += (int64_t)gridDim.x * blockDim.x)
+    s += x[sel.at(r)];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicAdd(out, scale * (part[0] + part[1] + part[2] + part[3]));
 }
 
 // ---------------------------------------------------------------- Adam

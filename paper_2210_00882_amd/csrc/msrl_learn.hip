@@ -164,9 +164,17 @@ hipError_t convert_pad(hipStream_t s, const S* src, int64_t rows, int64_t cols, 
   return hipGetLastError();
 }
 
+template <typename D>
+hipError_t gather_pad(hipStream_t s, const float* src, const RowSel& sel, int64_t rows, int64_t cols, int64_t ld_src,
+                      D* dst, int64_t ldd, int64_t rows_pad) {
+  hipLaunchKernelGGL((gather_pad_kernel<D>), grid1(rows_pad * ldd), dim3(256), 0, s, src, sel, rows, cols, ld_src, dst,
+                     ldd, rows_pad);
+  return hipGetLastError();
+}
+
 // gradient of one minibatch; grad (device, n_params floats) is overwritten; stats[0..4] are sums
 template <bool BF16>
-int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs, const void* actions,
+int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel, const float* obs, const void* actions,
               const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* c, float* grad,
               hipStream_t s, int nets = 3, bool finish = true) {
   // nets: bit n set = network n (0 policy, 1 value) is handled here; with bit 0 clear, grad and the
@@ -190,7 +198,10 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
   // observations in compute type, padded; and unit-major
   for (int n = 0; n < (G > 1 ? 2 : 1); ++n) {
     if (!((nets >> n) & 1) && G > 1) continue;
-    LTRY(convert_pad(s, obs, Rn[n], Dn[n], Dn[n], (E*)xcn[n], Dpn[n], Rkn[n]));
+    // (the value network of a centralised critic reads whole groups: the same rows as [R / G, G * in_dim];
+    // a selection of rows is refused for it, so only a row offset at a group boundary remains)
+    const RowSel rs = n == 0 ? sel : RowSel{sel.row0 / G, 0, 0, 0};
+    LTRY(gather_pad(s, obs, rs, Rn[n], Dn[n], Dn[n], (E*)xcn[n], Dpn[n], Rkn[n]));
     LTRY(transpose(s, (const E*)xcn[n], Rn[n], Dpn[n], Dpn[n], (E*)xtn[n], Rp, Rkn[n], Dpn[n]));
   }
   const int NL = L->layers;
@@ -243,6 +254,7 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs,
     a.clip = c->clip; a.vf_coef = c->vf_coef; a.ent_coef = c->ent_coef; a.inv_R = 1.0f / (float)R;
     a.G = G; a.Rv = Rn[1]; a.Rv_pad = Rkn[1]; a.inv_Rv = 1.0f / (float)Rn[1];
     a.policy = nets & 1; a.value = (nets >> 1) & 1;
+    a.sel = sel;
     hipLaunchKernelGGL((loss_kernel<E>), grid1(Rkn[0]), dim3(256), 0, s, a);
     if (finish) hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
     LTRY(hipGetLastError());
@@ -303,9 +315,10 @@ static_assert(ROWS_STAT_BINS == STAT_BINS, "the row kernel and the loss kernel s
 // The same gradient with the activations kept on chip: weights packed into MFMA tiles, one row
 // kernel launch per network (forward, loss, backward through the activations; writes the tiled
 // unit-major operands), then the weight and bias gradients from those.
-int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float* obs, const void* actions,
-                    const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* c, float* grad,
-                    hipStream_t s, int nets = 3, bool clear = true, bool finish = true) {
+int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel, const float* obs,
+                    const void* actions, const float* logp_old, const float* adv, const float* ret,
+                    const msrl_ppo_cfg* c, float* grad, hipStream_t s, int nets = 3, bool clear = true,
+                    bool finish = true) {
   // nets: bit n set = network n is handled here (1: the policy network only; the value network's pass
   // through device memory adds to the same grad and statistics bins).  clear / finish: zero grad and the
   // bins first / add the bins up at the end (the caller does both around two concurrent passes)
@@ -371,6 +384,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
     a.obs = obs; a.actions = actions; a.logp_old = logp_old; a.adv = adv; a.ret = ret;
     a.R = R; a.n_tiles = n_tiles; a.D = D; a.out_dim = L->pol.out_dim;
     a.obs_vec4 = (D % 4 == 0 && ((uintptr_t)obs & 15) == 0) ? 1 : 0;
+    a.sel = sel;
     a.clip = c->clip; a.vf_coef = c->vf_coef; a.ent_coef = c->ent_coef; a.inv_R = 1.0f / (float)R;
     a.xt = (__bf16*)L->xt; a.h1t = (__bf16*)b.ht[0]; a.h2t = (__bf16*)b.ht[1]; a.dz2t = (__bf16*)b.dzt[1];
     a.dz1t = (__bf16*)b.dzt[0]; a.dyt = (__bf16*)b.dyt;
@@ -424,7 +438,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const float
 
 int check_learner_args(const char* who, msrl_learner* L, const void* params, int64_t R, const void* obs,
                        const void* actions, const void* logp_old, const void* adv, const void* ret,
-                       const msrl_ppo_cfg* c) {
+                       const msrl_row_select* rows, const msrl_ppo_cfg* c) {
   if (!L || !params || !obs || !actions || !logp_old || !adv || !ret || !c)
     return fail(MSRL_EINVAL, "%s: NULL argument", who);
   if (R < 1 || R > L->max_rows)
@@ -434,7 +448,37 @@ int check_learner_args(const char* who, msrl_learner* L, const void* params, int
   if (R % L->G != 0)
     return fail(MSRL_EINVAL, "%s: %lld rows are no whole groups of %d (the agents of an env, centralised critic)", who,
                 (long long)R, L->G);
+  if (rows) {
+    if (rows->group < 1 || rows->first < 0 || rows->count < 1 || rows->first + rows->count > rows->group)
+      return fail(MSRL_EINVAL, "%s: row selection (group %d, first %d, count %d) must satisfy 0 <= first, 1 <= count, "
+                               "first + count <= group", who, rows->group, rows->first, rows->count);
+    if (L->G > 1)
+      return fail(MSRL_EINVAL, "%s: a centralised critic reads whole groups of rows; a row selection is not supported", who);
+  }
   return MSRL_OK;
+}
+
+RowSel selection(const msrl_row_select* rows, int64_t row0) {
+  return rows ? RowSel{row0, rows->group, rows->first, rows->count} : RowSel{row0, 0, 0, 0};
+}
+
+// the gradient of logical rows [row0, row0 + R) of the selection, into grad
+int grad_rows(msrl_learner* L, const float* params, int64_t R, int64_t row0, const msrl_row_select* rows,
+              const float* obs, const void* actions, const float* logp_old, const float* adv, const float* ret,
+              const msrl_ppo_cfg* cfg, float* grad, hipStream_t s) {
+  const RowSel sel = selection(rows, row0);
+  if (L->fused) return fused_grad_pass(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s);
+  if (L->fused_policy) {
+    // Centralised critic: the policy network on chip, then the value network (one row per group, a wide
+    // first layer) through device memory; it adds its part of grad and of the statistics.  (Running the
+    // second pass on a stream of its own beside the first was measured: no gain, the row kernel's
+    // workgroups leave no LDS for the value network's kernels to start beside them.)
+    int rc = fused_grad_pass(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s, 1, true, false);
+    if (rc == MSRL_OK) rc = grad_pass<true>(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s, 2, true);
+    return rc;
+  }
+  return L->bf16 ? grad_pass<true>(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s)
+                 : grad_pass<false>(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s);
 }
 
 }  // namespace
@@ -549,27 +593,29 @@ void msrl_learner_destroy(msrl_learner* L) {
 }
 
 int msrl_ppo_grad(msrl_learner* L, const float* params, int64_t R, const float* obs, const void* actions,
-                  const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* cfg,
-                  float* grad, float* stats, void* hip_stream) {
-  int rc = check_learner_args("msrl_ppo_grad", L, params, R, obs, actions, logp_old, adv, ret, cfg);
+                  const float* logp_old, const float* adv, const float* ret, const msrl_row_select* rows,
+                  const msrl_ppo_cfg* cfg, float* grad, float* stats, void* hip_stream) {
+  int rc = check_learner_args("msrl_ppo_grad", L, params, R, obs, actions, logp_old, adv, ret, rows, cfg);
   if (rc != MSRL_OK) return rc;
   if (!grad) return fail(MSRL_EINVAL, "msrl_ppo_grad: grad is NULL");
   hipStream_t s = (hipStream_t)hip_stream;
-  if (L->fused) {
-    rc = fused_grad_pass(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s);
-  } else if (L->fused_policy) {
-    // Centralised critic: the policy network on chip, then the value network (one row per group, a wide
-    // first layer) through device memory; it adds its part of grad and of the statistics.  (Running the
-    // second pass on a stream of its own beside the first was measured: no gain, the row kernel's
-    // workgroups leave no LDS for the value network's kernels to start beside them.)
-    rc = fused_grad_pass(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s, 1, true, false);
-    if (rc == MSRL_OK) rc = grad_pass<true>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s, 2, true);
-  } else {
-    rc = L->bf16 ? grad_pass<true>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s)
-                 : grad_pass<false>(L, params, R, obs, actions, logp_old, adv, ret, cfg, grad, s);
-  }
+  rc = grad_rows(L, params, R, 0, rows, obs, actions, logp_old, adv, ret, cfg, grad, s);
   if (rc != MSRL_OK) return rc;
   if (stats) LTRY(hipMemcpyAsync(stats, L->stats, 5 * sizeof(float), hipMemcpyDeviceToDevice, s));
+  return MSRL_OK;
+}
+
+int msrl_rows_mean(const float* x, int64_t R, const msrl_row_select* rows, float* out, void* hip_stream) {
+  if (!x || !out) return fail(MSRL_EINVAL, "msrl_rows_mean: NULL argument");
+  if (R < 1) return fail(MSRL_EINVAL, "msrl_rows_mean: R must be positive");
+  if (rows && (rows->group < 1 || rows->first < 0 || rows->count < 1 || rows->first + rows->count > rows->group))
+    return fail(MSRL_EINVAL, "msrl_rows_mean: bad row selection");
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(fill_kernel, dim3(1), dim3(64), 0, s, out, (int64_t)1, 0.0f);
+  const int64_t blocks = (R + 256 * 16 - 1) / (256 * 16);
+  hipLaunchKernelGGL(rows_sum_kernel, dim3((unsigned)(blocks < 1024 ? blocks : 1024)), dim3(256), 0, s, x,
+                     selection(rows, 0), R, 1.0f / (float)R, out);
+  LTRY(hipGetLastError());
   return MSRL_OK;
 }
 
@@ -600,8 +646,8 @@ int msrl_params_cast(const float* master, void* out, int64_t n, int32_t dtype, v
 
 int msrl_ppo_update(msrl_learner* L, float* params, float* m, float* v, int64_t* step_counter, int64_t R,
                     int32_t iters, int32_t minibatches, const float* obs, const void* actions,
-                    const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* cfg,
-                    void* hip_stream) {
+                    const float* logp_old, const float* adv, const float* ret, const msrl_row_select* rows,
+                    const msrl_ppo_cfg* cfg, void* hip_stream) {
   if (!L || !params || !m || !v || !step_counter || !obs || !actions || !logp_old || !adv || !ret || !cfg)
     return fail(MSRL_EINVAL, "msrl_ppo_update: NULL argument");
   if (iters < 1 || minibatches < 1 || R < minibatches)
@@ -614,13 +660,13 @@ int msrl_ppo_update(msrl_learner* L, float* params, float* m, float* v, int64_t*
   if (largest > L->max_rows)
     return fail(MSRL_EINVAL, "msrl_ppo_update: a minibatch of %lld rows exceeds the learner's %lld",
                 (long long)largest, (long long)L->max_rows);
-  const int D = L->pol.in_dim;
-  const size_t act_stride = L->pol.dist == MSRL_CATEGORICAL ? sizeof(int32_t) : sizeof(float) * (L->pol.out_dim / 2);
+  int rc = check_learner_args("msrl_ppo_update", L, params, largest, obs, actions, logp_old, adv, ret, rows, cfg);
+  if (rc != MSRL_OK) return rc;
   for (int it = 0; it < iters; ++it)
     for (int b = 0; b < minibatches; ++b) {
       const int64_t r0 = (int64_t)b * block, r1 = b == minibatches - 1 ? R : r0 + block;
-      int rc = msrl_ppo_grad(L, params, r1 - r0, obs + (size_t)r0 * D, (const uint8_t*)actions + (size_t)r0 * act_stride,
-                             logp_old + r0, adv + r0, ret + r0, cfg, L->grad, nullptr, hip_stream);
+      rc = grad_rows(L, params, r1 - r0, r0, rows, obs, actions, logp_old, adv, ret, cfg, L->grad,
+                     (hipStream_t)hip_stream);
       if (rc != MSRL_OK) return rc;
       *step_counter += 1;
       rc = msrl_adam_step(params, m, v, L->grad, (int64_t)L->n_params, *step_counter, cfg, hip_stream);

@@ -26,12 +26,12 @@ def ppo_train(cfg: synth.Config, params_f32: np.ndarray, iterations: int, seed: 
     one_role = B.make_policy_cfg(cfg)
     one_role.roles = 1
     n_role = B.msrl_param_count(one_role)
-    agent = torch.arange(T * M, device="cuda") % N
+    # (Listing 1: one learner per role; a role's rows are named by a row selection, nothing is copied)
     if roles == 1:
         row_sets = [None]
     else:
-        row_sets = [torch.nonzero(agent < cfg.num_chasers).flatten(), torch.nonzero(agent >= cfg.num_chasers).flatten()]
-    counts = [T * M if r is None else int(r.numel()) for r in row_sets]
+        row_sets = [B.msrl_row_select(N, 0, cfg.num_chasers), B.msrl_row_select(N, cfg.num_chasers, N - cfg.num_chasers)]
+    counts = [T * M if r is None else T * cfg.num_envs * r.count for r in row_sets]
     # (the last block takes the remainder; with a centralised critic the blocks hold whole groups of N rows)
     learners = [B.msrl_learner_init(one_role, -(-c // minibatches) + minibatches * N) for c in counts]
     try:
@@ -42,23 +42,21 @@ def ppo_train(cfg: synth.Config, params_f32: np.ndarray, iterations: int, seed: 
         out = B.alloc_traj(cfg, T, logits=False, gae=True)
         pc = B.make_ppo_cfg(clip=clip, vf_coef=vf_coef, ent_coef=ent_coef, lr=lr)
         rows = lambda t: t.reshape(-1, *t.shape[2:])
-        steps, history = [0] * roles, []
-        for _ in range(iterations):
+        steps = [0] * roles
+        mean_rew = torch.empty((iterations, roles), dtype=torch.float32, device="cuda")   # written by msrl_rows_mean
+        for it in range(iterations):
             if acting is not master:
                 B.msrl_params_cast(master, acting, B.MSRL_BF16)
             B.msrl_rollout_gae(state, acting, T, gamma, lam, out)
             batch = [rows(out["obs"][:T]), rows(out["actions"]), rows(out["logp"]), rows(out["adv"]), rows(out["ret"])]
             for r in range(roles):
-                sel = batch if row_sets[r] is None else [t.index_select(0, row_sets[r]) for t in batch]
                 sl = slice(r * n_role, (r + 1) * n_role)
                 steps[r] = B.msrl_ppo_update(learners[r], master[sl], m[sl], v[sl], steps[r], iters, minibatches,
-                                             *sel, pc)
-            rew = out["rewards"]
-            if roles == 1:
-                history.append(float(rew.mean()))   # syncs
-            else:
-                per_agent = rew.reshape(T, cfg.num_envs, N).mean(dim=(0, 1)).cpu().numpy()
-                history.append((float(per_agent[:cfg.num_chasers].mean()), float(per_agent[cfg.num_chasers:].mean())))
+                                             *batch, pc, rows=row_sets[r])
+            for r in range(roles):
+                B.msrl_rows_mean(out["rewards"], mean_rew[it, r:r + 1], rows=row_sets[r])
+        hist = mean_rew.cpu().numpy()            # read back once, after the loop
+        history = [float(h[0]) for h in hist] if roles == 1 else [(float(h[0]), float(h[1])) for h in hist]
         return master.cpu().numpy(), history
     finally:
         for L in learners:
