@@ -93,7 +93,9 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   Rewards on the new positions ("contact": d < radius_c + radius_r between a
  *   chaser and a runner): every chaser +10 per contact of any chaser; a runner
  *   -10 per chaser in contact with it, -10 * (max(0,|px|-1) + max(0,|py|-1)).
- *   Supported by msrl_rollout_step / msrl_rollout_gae (and the snapshot calls).
+ *   Supported by msrl_rollout_step / msrl_rollout_gae, the step-granular calls
+ *   (msrl_observe / msrl_act / msrl_env_step) and the snapshot calls; not by
+ *   msrl_measure_phase.
  *   The kernel has two workgroup shapes with identical results (one or four
  *   tiles of 32 envs); tag_tiles = 0 lets msrl_rollout_init pick by num_envs,
  *   1 or 4 fixes the shape (EINVAL for any other value, and for a non-zero
@@ -141,9 +143,8 @@ typedef struct {
  * front of the output layer (the evaluation of the paper, section 7.1, uses a
  * seven-layer network).  Each layer beyond two adds one W[hidden, hidden]
  * b[hidden] pair in front of W3.  More than two layers are supported by
- * msrl_rollout_step / msrl_rollout_gae, by msrl_observe / msrl_env_step (which
- * run no network) and by the learner; msrl_act and msrl_measure_phase return
- * MSRL_EUNSUPPORTED for them.
+ * msrl_rollout_step / msrl_rollout_gae, by the step-granular calls and by the
+ * learner; msrl_measure_phase returns MSRL_EUNSUPPORTED for them.
  *
  * roles (0 means 1; 2 for MSRL_ENV_TAG): number of parameter sets.  The
  * parameter buffer holds them one after the other (policy then value each);
@@ -155,9 +156,11 @@ typedef struct {
  * env, the rows of its agents one after the other, and gives one value per env;
  * values[t, m] then holds that value on every row of the env.  W1 of the value
  * network is [value_in_dim, hidden].  Supported by msrl_rollout_step /
- * msrl_rollout_gae on the particle env with bfloat16 networks, and by the
- * learner (any multiple G of in_dim: the value network then reads groups of G
- * consecutive rows, see msrl_ppo_grad).
+ * msrl_rollout_gae and the step-granular calls on the particle env with
+ * bfloat16 networks (msrl_act then takes the joint observation of an env from
+ * the rows the caller gives for its agents), and by the learner (any multiple
+ * G of in_dim: the value network then reads groups of G consecutive rows, see
+ * msrl_ppo_grad).
  */
 typedef struct {
   int32_t in_dim, hidden, out_dim;

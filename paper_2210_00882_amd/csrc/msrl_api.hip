@@ -86,7 +86,10 @@ const std::vector<KernelEntry>& all_kernels() {
           entry_p10_h256_bf16_act(), entry_p10_h256_bf16_step(),
           entry_p3_h64_f32_deep(), entry_p3_h64_bf16_deep(), entry_p10_h256_bf16_deep(),
           entry_l17_6_h256_deep(),
-          entry_p3_h64_bf16_central(), entry_p10_h256_bf16_central()};
+          entry_p3_h64_bf16_central(), entry_p10_h256_bf16_central(),
+          entry_p3_h64_f32_act_deep(), entry_p3_h64_bf16_act_deep(), entry_p10_h256_bf16_act_deep(),
+          entry_l17_6_h256_act_deep(),
+          entry_p3_h64_bf16_act_central(), entry_p10_h256_bf16_act_central()};
   return table;
 }
 
@@ -272,16 +275,17 @@ int check_traj(const msrl_state* st, const msrl_traj* out, bool need_gae) {
 // the compiled kernel for this state's configuration and the given phase variant, or null
 bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase, KernelEntry* out) {
   const bool bf16 = pol.dtype == MSRL_BF16;
-  // networks with more than two hidden layers have a full-rollout kernel of their own and no
-  // measurement or actor-only variants; the environment-only variant runs no network
+  // networks with more than two hidden layers, and a centralised critic, have kernels of their own for the
+  // full rollout and for the actor fragment, and no measurement variants; the environment-only variant
+  // runs no network
   if (layers_of(pol) > 2) {
+    if (central_of(pol)) return false;
     if (phase == PHASE_ALL) phase = PHASE_DEEP;
+    else if (phase == PHASE_ACT) phase = PHASE_ACT_DEEP;
     else if (phase != PHASE_STEP) return false;
-  }
-  // likewise a centralised critic
-  if (central_of(pol)) {
-    if (layers_of(pol) > 2) return false;
+  } else if (central_of(pol)) {
     if (phase == PHASE_ALL) phase = PHASE_CENTRAL;
+    else if (phase == PHASE_ACT) phase = PHASE_ACT_CENTRAL;
     else if (phase != PHASE_STEP) return false;
   }
   for (const KernelEntry& k : all_kernels()) {
@@ -342,9 +346,12 @@ int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* param
 }
 
 // the pursuit env has a kernel family of its own (tag_kernels.h)
-int enqueue_tag(msrl_state* st, const void* params, int32_t T, msrl_traj* out, hipStream_t stream) {
-  int rc = pack_params(st, params, stream);
-  if (rc != MSRL_OK) return rc;
+int enqueue_tag(msrl_state* st, const void* params, int32_t T, msrl_traj* out, hipStream_t stream,
+                int phase = TAG_ALL, const float* obs_in = nullptr, const void* actions_in = nullptr) {
+  if (params) {  // (the environment-only variant runs no network)
+    int rc = pack_params(st, params, stream);
+    if (rc != MSRL_OK) return rc;
+  }
   const msrl_env_cfg& e = st->env;
   TagArgs a;
   memset(&a, 0, sizeof(a));
@@ -371,8 +378,10 @@ int enqueue_tag(msrl_state* st, const void* params, int32_t T, msrl_traj* out, h
   a.values = out->values;
   a.logits = out->logits;
   a.M = (int64_t)e.num_envs * e.num_agents;
-  HIP_TRY(launch_tag_rollout(e.num_chasers, e.num_agents - e.num_chasers, e.num_landmarks, st->pol.hidden, st->tag_tiles, a,
-                             stream));
+  a.obs_in = obs_in;
+  a.actions_in = (const int32_t*)actions_in;
+  HIP_TRY(launch_tag_rollout(e.num_chasers, e.num_agents - e.num_chasers, e.num_landmarks, st->pol.hidden, st->tag_tiles,
+                             phase, a, stream));
   return MSRL_OK;
 }
 
@@ -685,6 +694,12 @@ int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj*
 
 int msrl_observe(msrl_state* st, float* obs, void* hip_stream) {
   if (!st || !obs) return fail(MSRL_EINVAL, "msrl_observe: NULL argument");
+  if (st->env.kind == MSRL_ENV_TAG) {
+    msrl_traj out;
+    memset(&out, 0, sizeof(out));
+    out.obs = obs;
+    return enqueue_tag(st, nullptr, 0, &out, (hipStream_t)hip_stream, TAG_STEP);
+  }
   KernelEntry k;
   if (!find_kernel(st->env, st->pol, PHASE_STEP, &k))
     return fail(MSRL_EUNSUPPORTED, "msrl_observe: not compiled for this configuration");
@@ -698,6 +713,15 @@ int msrl_act(msrl_state* st, const void* params, const float* obs, void* actions
              float* logits, void* hip_stream) {
   if (!st || !params || !obs || !actions || !logp || !values)
     return fail(MSRL_EINVAL, "msrl_act: NULL argument");
+  if (st->env.kind == MSRL_ENV_TAG) {
+    msrl_traj out;
+    memset(&out, 0, sizeof(out));
+    out.actions = actions;
+    out.logp = logp;
+    out.values = values;
+    out.logits = logits;
+    return enqueue_tag(st, params, 0, &out, (hipStream_t)hip_stream, TAG_ACT, obs, nullptr);
+  }
   KernelEntry k;
   if (!find_kernel(st->env, st->pol, PHASE_ACT, &k))
     return fail(MSRL_EUNSUPPORTED, "msrl_act: not compiled for this configuration");
@@ -714,6 +738,14 @@ int msrl_env_step(msrl_state* st, const void* actions, float* rewards, uint8_t* 
                   void* hip_stream) {
   if (!st || !actions || !rewards || !dones || !next_obs)
     return fail(MSRL_EINVAL, "msrl_env_step: NULL argument");
+  if (st->env.kind == MSRL_ENV_TAG) {
+    msrl_traj out;
+    memset(&out, 0, sizeof(out));
+    out.obs = next_obs;
+    out.rewards = rewards;
+    out.dones = dones;
+    return enqueue_tag(st, nullptr, 1, &out, (hipStream_t)hip_stream, TAG_STEP, nullptr, actions);
+  }
   KernelEntry k;
   if (!find_kernel(st->env, st->pol, PHASE_STEP, &k))
     return fail(MSRL_EUNSUPPORTED, "msrl_env_step: not compiled for this configuration");

@@ -73,4 +73,12 @@ KernelEntry entry_l17_6_h256_deep();
 KernelEntry entry_p3_h64_bf16_central();
 KernelEntry entry_p10_h256_bf16_central();
 
+// the actor fragment for those
+KernelEntry entry_p3_h64_f32_act_deep();
+KernelEntry entry_p3_h64_bf16_act_deep();
+KernelEntry entry_p10_h256_bf16_act_deep();
+KernelEntry entry_l17_6_h256_act_deep();
+KernelEntry entry_p3_h64_bf16_act_central();
+KernelEntry entry_p10_h256_bf16_act_central();
+
 }  // namespace msrl

@@ -120,8 +120,10 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 //              holds its tiles) and is evaluated once per env by the workgroup as a whole: the
 //              joint observations of its envs are the columns of one MFMA tile, and wave w computes
 //              the 32-unit chunk w of each layer, the layers meeting in LDS.
+//   PHASE_ACT_DEEP, PHASE_ACT_CENTRAL  PHASE_ACT for networks with more than two hidden layers / with a
+//              centralised critic (the joint observation is then built from the caller's rows).
 enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHASE_ACT = 4, PHASE_STEP = 5,
-             PHASE_DEEP = 6, PHASE_CENTRAL = 7 };
+             PHASE_DEEP = 6, PHASE_CENTRAL = 7, PHASE_ACT_DEEP = 8, PHASE_ACT_CENTRAL = 9 };
 // stamps: start of the step, observation rows built and stored, policy layer 1 done (after the
 // stage barrier that precedes it), policy stage s done (s < 5), same for the value network,
 // logits and values ready, sampling and move done, end of the step
@@ -143,15 +145,16 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int NZ = 4 * N + 2;
   constexpr int KT1 = BF16 ? (NZ + 1 + 15) / 16 : (NZ + 1 + 7) / 8;
   constexpr int NBUF = 2;             // LDS window: the stage in use and the one being copied
-  constexpr bool CENTRAL = PHASE == PHASE_CENTRAL;
+  constexpr bool ACT = PHASE == PHASE_ACT || PHASE == PHASE_ACT_DEEP || PHASE == PHASE_ACT_CENTRAL;
+  constexpr bool CENTRAL = PHASE == PHASE_CENTRAL || PHASE == PHASE_ACT_CENTRAL;
   // chunk blocks per stage (fewer barriers when they fit; the centralised critic needs the LDS)
   constexpr int CPS = BF16 && H >= 64 && !CENTRAL ? 2 : 1;
   typedef Mlp<H, BF16, NB, KT1> Net;
   typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   typedef typename Net::Op Op;
   static_assert(EPW >= 1, "a wave must hold at least one env");
-  constexpr bool DEEP = PHASE == PHASE_DEEP;
-  constexpr bool FULL = PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS || DEEP || CENTRAL;
+  constexpr bool DEEP = PHASE == PHASE_DEEP || PHASE == PHASE_ACT_DEEP;
+  constexpr bool FULL = (PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS || DEEP || CENTRAL) && !ACT;
   static_assert(!CENTRAL || (BF16 && WAVES == Net::NUC), "centralised critic: bf16, one wave per 32-unit chunk");
   // The joint observation is laid out as one block of KT1 tiles per agent, the agent's row exactly as the
   // policy's layer 1 takes it (its constant 1 at input NZ included: agent 0's carries the critic's bias).
@@ -159,7 +162,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int JCOLS = WAVES * EPW;            // envs of a workgroup = columns of the critic's tile
   static_assert(!CENTRAL || JCOLS <= 32, "the envs of a workgroup are the columns of one tile");
   constexpr bool HAS_NETS = PHASE != PHASE_ENV && PHASE != PHASE_STEP;     // the variant runs the networks
-  constexpr bool STORES_OBS = PHASE != PHASE_MLP && PHASE != PHASE_ACT;    // ... stores observation rows
+  constexpr bool STORES_OBS = PHASE != PHASE_MLP && !ACT;                  // ... stores observation rows
   static_assert(NB == 1, "the observation staging below assumes one 32-row block per wave");
 
   // Observation rows leave through a per-wave LDS staging area: the lanes write their features
@@ -465,7 +468,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       float2 pr[NP];
       // PHASE_ACT takes the pair from the caller's row instead (zero beyond the row and for idle rows)
       auto pair_in = [&](int gp) -> float2 {
-        if constexpr (PHASE == PHASE_ACT) {
+        if constexpr (ACT) {
           if (!valid[q] || 2 * gp + 2 > D) return make_float2(0.0f, 0.0f);
           return *(const float2*)(a.obs_in + (size_t)(m0 + row[q]) * D + 2 * gp);
         } else {
@@ -782,7 +785,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       for (int q = 0; q < NB; ++q)
         if (h == 0 && valid[q]) s_out[0][wrow0 + row[q]] = out_v[q][0];
     }
-    if (PHASE != PHASE_ACT && t == a.T) break;
+    if (!ACT && t == a.T) break;
 
     // ---------------- sampling, physics
     float rew_term[NB];
@@ -821,7 +824,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     }
     wave_lds_sync();
     stamp(CLK_SAMPLE);
-    if constexpr (PHASE == PHASE_ACT) break;  // one evaluation, no move
+    if constexpr (ACT) break;  // one evaluation, no move
 
     // ---------------- shared reward: lane h = 0 takes landmark ag (distance of the nearest agent),
     // lane h = 1 agent ag (collisions with the agents after it): one distance per lane and agent
@@ -875,7 +878,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 
   if constexpr (HAS_NETS) ws.wait_all();  // copies issued ahead for stages that will not run
   if constexpr (!HAS_NETS) __syncthreads();
-  if constexpr (PHASE == PHASE_ACT) {
+  if constexpr (ACT && !CENTRAL) {
     flush(0, 0x07);  // values, actions, logp of the one evaluation
     return;          // the env state did not move
   }
@@ -894,6 +897,10 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     __syncthreads();
     collect_values();
     __syncthreads();
+    if constexpr (ACT) {
+      flush(0, 0x07);  // values (just collected), actions, logp of the one evaluation
+      return;          // the env state did not move
+    }
   }
   if constexpr (PHASE != PHASE_MLP && PHASE != PHASE_STEP)
     flush(a.T, 0x01);  // values[T]; every earlier step went out inside the loop
@@ -929,10 +936,12 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 // actions_in is float [M, K]).
 template <int D, int K, int H, int WAVES, int PHASE = PHASE_ALL>
 __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArgs a) {
-  static_assert(PHASE == PHASE_ALL || PHASE == PHASE_ACT || PHASE == PHASE_STEP || PHASE == PHASE_DEEP,
+  static_assert(PHASE == PHASE_ALL || PHASE == PHASE_ACT || PHASE == PHASE_STEP || PHASE == PHASE_DEEP ||
+                    PHASE == PHASE_ACT_DEEP,
                 "no measurement variants here");
   constexpr bool HAS_NETS = PHASE != PHASE_STEP;
-  constexpr bool DEEP = PHASE == PHASE_DEEP;
+  constexpr bool DEEP = PHASE == PHASE_DEEP || PHASE == PHASE_ACT_DEEP;
+  constexpr bool ACT = PHASE == PHASE_ACT || PHASE == PHASE_ACT_DEEP;
   constexpr int KT1 = (D + 1 + 7) / 8;  // + the constant-1 input that carries the bias
   constexpr int NR = 4 * KT1;           // state registers per lane
   constexpr int NBUF = 2, CPS = 1;
@@ -981,7 +990,7 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
     const int u = 8 * (r >> 2) + 4 * h + (r & 3);
-    const float* src = PHASE == PHASE_ACT ? a.obs_in : a.env_state;  // PHASE_ACT works on the caller's rows
+    const float* src = ACT ? a.obs_in : a.env_state;  // PHASE_ACT works on the caller's rows
     s[0][r] = u < D ? src[(size_t)env * D + u] : 0.0f;
   }
   const int64_t g64 = a.g[env];
@@ -992,7 +1001,7 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   for (int t = 0; t <= a.T; ++t) {
     const size_t o = (size_t)t * a.M + env;
     // PHASE_STEP writes one observation, that of the last state, to row block 0
-    if (valid && PHASE != PHASE_ACT && (PHASE != PHASE_STEP || t == a.T)) {
+    if (valid && !ACT && (PHASE != PHASE_STEP || t == a.T)) {
       const size_t oo = PHASE == PHASE_STEP ? (size_t)env : o;
 #pragma unroll
       for (int r = 0; r < NR; ++r) {
@@ -1087,7 +1096,7 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
       }
     }
     if (valid && h == 0 && PHASE != PHASE_STEP) a.values[o] = out_v[0][0];
-    if (PHASE != PHASE_ACT && t == a.T) break;
+    if (!ACT && t == a.T) break;
 
     // action dims 4h + c: mean in register c, log-std in register 4 + c
     float eps[4], act[4], lp = 0.0f, cost = 0.0f;
@@ -1120,12 +1129,12 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
     const bool done = tau + 1 == a.ep;
     if (valid && h == 0) {
       if (PHASE != PHASE_STEP) a.logp[o] = lp;
-      if (PHASE != PHASE_ACT) {
+      if (!ACT) {
         a.rewards[o] = -rew;
         a.dones[o] = done ? 1 : 0;
       }
     }
-    if constexpr (PHASE == PHASE_ACT) break;  // one evaluation, no move
+    if constexpr (ACT) break;  // one evaluation, no move
 
     // s' = A s + B a + noise_std * eps
     f32x16 acc;
@@ -1152,7 +1161,7 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   }
 
   if constexpr (HAS_NETS) ws.wait_all();  // copies issued ahead for stages that will not run
-  if constexpr (PHASE == PHASE_ACT) return;  // the env state did not move
+  if constexpr (ACT) return;  // the env state did not move
 
   if (valid) {
 #pragma unroll

@@ -36,11 +36,23 @@ struct TagArgs {
   float* values;
   float* logits;  // may be null
   int64_t M;
+  const float* obs_in;        // TAG_ACT: observation rows [M, D] to act on
+  const int32_t* actions_in;  // TAG_STEP: actions [M] to apply
 };
 
-template <int NC, int NR, int L, int H, int TILES = 1>
+// Variants (the step-granular calls of the library, as for the other envs):
+//   TAG_ACT   both networks of the row's role and the sampling on observation rows given by the caller, with the
+//             noise the fused kernel would draw at the state's step counters; writes values, actions, logp
+//             (and logits) of one evaluation; the state is not changed;
+//   TAG_STEP  applies the caller's actions for T = 1 (move, contact forces, rewards, done, reset, counters + 1;
+//             writes rewards[0], dones[0]) and writes the observation of the resulting state to obs[0]; with
+//             T = 0 it only writes the observation of the current state.  No network runs.
+enum : int { TAG_ALL = 0, TAG_ACT = 1, TAG_STEP = 2 };
+
+template <int NC, int NR, int L, int H, int TILES = 1, int PHASE = TAG_ALL>
 __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(TagArgs a) {
   constexpr int N = NC + NR;
+  constexpr bool ACT = PHASE == TAG_ACT, STEP = PHASE == TAG_STEP;
   static_assert(64 * N * TILES <= 1024, "one wave per tile and agent slot");
   constexpr int D = 4 + 2 * L + 4 * (N - 1);
   constexpr int S = 4 * N + 2 * L;
@@ -77,7 +89,7 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
   float(&s_cnt)[32][N] = t_cnt[tile];
   const int role = j < NC ? 0 : 1;
   const NetLayout ly = net_layout(D, H, true);
-  for (int net = 0; net < 4; ++net) {
+  for (int net = 0; net < (STEP ? 0 : 4); ++net) {
     const u32x4* src = (const u32x4*)(a.packed + (size_t)net * ly.bytes + ly.w1);
     for (int i = threadIdx.x; i < NET_TILES * 64; i += blockDim.x) {
       const int tile = i >> 6;
@@ -126,6 +138,8 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
         return 0.0f;
       } else if constexpr (idx == D) {
         return 1.0f;  // input D carries the bias
+      } else if constexpr (ACT) {
+        return valid ? a.obs_in[((size_t)env * N + j) * D + idx] : 0.0f;  // the caller's row
       } else if constexpr (idx < 4) {
         return idx == 0 ? v.x : idx == 1 ? v.y : idx == 2 ? p.x : p.y;
       } else if constexpr ((idx - 4) / 2 < L) {
@@ -141,9 +155,12 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
       }
     };
     Op x[1][KT1];
-    float* const orow = a.obs + ((size_t)t * a.M + (size_t)env * N + j) * D;
+    // (TAG_STEP stores one observation, that of the last state, to step slot 0, and runs no network)
+    float* const orow = a.obs + ((size_t)(STEP ? 0 : t) * a.M + (size_t)env * N + j) * D;
+    const bool observe = !STEP || t == a.T;
 #pragma unroll
     for (int kt = 0; kt < KT1; ++kt) {
+      if (!observe) break;
       f32x8 f;
       auto fill = [&](auto KT, auto S8) {
         constexpr int k = decltype(KT)::value, s = decltype(S8)::value;
@@ -162,7 +179,7 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
       if (kt == 1) fill_all(std::integral_constant<int, 1>{});
       if (kt == 2) fill_all(std::integral_constant<int, 2>{});
       if (kt == 3) fill_all(std::integral_constant<int, 3>{});
-      if (valid) {
+      if (valid && !ACT) {
         float* dst = orow + 16 * kt + 8 * h;
         const int i0 = 16 * kt + 8 * h;
         // rows are D floats apart: 16-byte pieces when D % 4 == 0, 8-byte pieces otherwise (D is even)
@@ -182,8 +199,9 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
 
     // ---------------- networks of this wave's role, from the resident images
     f32x16 out_p[1], out_v[1];
+    out_p[0] = out_v[0] = zero16();
 #pragma unroll
-    for (int net = 0; net < 2; ++net) {
+    for (int net = 0; net < (STEP ? 0 : 2); ++net) {
       f32x16(&out)[1] = net == 0 ? out_p : out_v;
       const u32x4* base = &s_net[2 * role + net][0] + lane;
       Op h1[1][Net::KT2];
@@ -219,8 +237,8 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
       }
     }
     const size_t o = (size_t)t * a.M + (size_t)env * N + j;
-    if (valid && h == 0) a.values[o] = out_v[0][0];
-    if (t == a.T) break;
+    if (valid && h == 0 && !STEP) a.values[o] = out_v[0][0];
+    if (!ACT && t == a.T) break;
 
     // ---------------- sampling
     float l[5];
@@ -234,7 +252,8 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
     int act;
     sample_categorical5(l, u01(w.w[0]), act, lp);
     act = __shfl(act, n);  // the h = 0 lane of the row decides
-    if (valid && h == 0) {
+    if constexpr (STEP) act = valid ? a.actions_in[(size_t)env * N + j] : 0;
+    if (valid && h == 0 && !STEP) {
       a.actions[o] = act;
       a.logp[o] = lp;
       if (a.logits) {
@@ -242,6 +261,8 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
         for (int k = 0; k < 5; ++k) a.logits[o * 5 + k] = l[k];
       }
     }
+
+    if constexpr (ACT) break;  // one evaluation, no move
 
     // ---------------- move: action force and contact forces, from the positions before the move
     float fx = a.accel[role] * ((act == 1 ? 1.0f : 0.0f) - (act == 2 ? 1.0f : 0.0f));
@@ -321,6 +342,8 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
     }
   }
 
+  if constexpr (ACT) return;  // the env state did not move
+
   // ---------------- write the env state back
   if (valid && h == 0) {
     float* eo = a.env_state + (size_t)env * S;
@@ -337,8 +360,9 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
 }
 
 // launcher of the compiled instances; returns hipErrorInvalidValue when no instance matches.
-// tiles: env tiles per workgroup, 1 or 4.
-hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, int tiles, const TagArgs& a, hipStream_t stream);
+// tiles: env tiles per workgroup, 1 or 4 (the step-granular variants always take 1); phase: TAG_*.
+hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, int tiles, int phase, const TagArgs& a,
+                              hipStream_t stream);
 bool tag_rollout_compiled(int nc, int nr, int landmarks, int hidden);
 
 }  // namespace msrl

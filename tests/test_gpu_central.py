@@ -90,11 +90,15 @@ def test_central_critic_error_paths():
     try:
         params = B.upload_params(cfg, synth.make_params(cfg))
         obs = torch.zeros((cfg.M, cfg.obs_dim), device="cuda")
-        B.msrl_observe(st, obs)                      # no network involved: allowed
+        B.msrl_observe(st, obs)
         a = torch.zeros(cfg.M, dtype=torch.int32, device="cuda")
         lp = torch.zeros(cfg.M, device="cuda")
-        with pytest.raises(B.MsrlError):
-            B.msrl_act(st, params, obs, a, lp, lp.clone())
+        B.msrl_act(st, params, obs, a, lp, lp.clone())        # (checked against the oracle in test_gpu_steps.py)
+        out = B.alloc_traj(cfg, 2, logits=False, gae=False)
+        with pytest.raises(B.MsrlError) as e:                 # no measurement variants with a centralised critic
+            B.msrl_measure_phase(st, params, 2, out, B.MSRL_PHASE_MLP)
+        assert e.value.code == B.MSRL_EUNSUPPORTED
+        torch.cuda.synchronize()
     finally:
         B.msrl_rollout_destroy(st)
 

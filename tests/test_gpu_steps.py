@@ -14,6 +14,37 @@ from paper_2210_00882_amd import synth
 pytestmark = pytest.mark.gpu
 
 
+def setup_any(cfg):
+    """oracle_setup for every env kind (the pursuit env has no entry there)."""
+    if cfg.kind == synth.TAG:
+        from test_gpu_tag import tag_env
+        pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
+        return tag_env(cfg), pol, synth.make_params(cfg, bias_std=0.1).astype(np.float64), None
+    return oracle_setup(cfg)
+
+
+def expected_outputs(cfg, pol, params, rows_env):
+    """Oracle networks on the N rows of one env -> (logits [N, out], values [N]); handles the role routing of
+    the pursuit env and the centralised critic."""
+    N = cfg.num_agents
+    lg, v = [], []
+    central = getattr(cfg, "central_critic", False)
+    for i in range(N):
+        prm = params
+        if cfg.kind == synth.TAG:
+            n = pol.param_count
+            prm = params[:n] if i < cfg.num_chasers else params[n:]
+        if central:
+            lg.append(ref.mlp(pol.in_dim, pol.hidden, pol.out_dim, prm[:pol.policy_param_count], rows_env[i],
+                              bf16=cfg.dtype == synth.BF16))
+            v.append(ref.central_value(pol, prm, rows_env))
+        else:
+            a, b = ref.policy_value(pol, prm, rows_env[i])
+            lg.append(a)
+            v.append(b)
+    return np.array(lg), np.array(v)
+
+
 def split_rollout(gpu, T, logits=True):
     """T x { observe / act / env_step } -> the arrays msrl_rollout_step would fill."""
     import torch
@@ -36,18 +67,33 @@ def split_rollout(gpu, T, logits=True):
     return {k: (None if v is None else v.cpu().numpy()) for k, v in tr.items()}
 
 
-@pytest.mark.parametrize("which", ["n3_f32_ragged", "n1_f32", "n6_f32", "n3_bf16", "n10_bf16", "lingauss"])
+ACT_CASES = {
+    "n3_f32_ragged": lambda: synth.CONFIGS[1].with_(num_envs=53, episode_len=4),
+    "n1_f32": lambda: synth.particle("p1", 70, 1, 64, 6, 3, synth.F32, 11),
+    "n2_f32": lambda: synth.particle("p2", 37, 2, 64, 6, 3, synth.F32, 13),
+    "n6_f32": lambda: synth.CONFIGS[3].with_(num_envs=77, episode_len=5),
+    "n3_bf16": lambda: synth.particle("p3b", 45, 3, 64, 6, 3, synth.BF16, 12),
+    "n10_bf16": lambda: synth.CONFIGS[5].with_(num_envs=100, episode_len=3),
+    "lingauss": lambda: synth.CONFIGS[4].with_(num_envs=150, episode_len=3),
+    # networks with more than two hidden layers (the evaluated networks of section 7.1 have seven layers)
+    "n3_f32_4_layers": lambda: synth.particle("p3d", 45, 3, 64, 6, 3, synth.F32, 14).with_(hidden_layers=4),
+    "n3_bf16_3_layers": lambda: synth.particle("p3d", 45, 3, 64, 6, 3, synth.BF16, 15).with_(hidden_layers=3),
+    "n10_bf16_6_layers": lambda: synth.CONFIGS[5].with_(num_envs=50, episode_len=3, hidden_layers=6),
+    "lingauss_3_layers": lambda: synth.CONFIGS[4].with_(num_envs=70, episode_len=3, hidden_layers=3),
+    # centralised critic (section 2.1): the value network on the joint observation of the env's agents
+    "n3_bf16_central": lambda: synth.particle("p3c", 45, 3, 64, 6, 3, synth.BF16, 16).with_(central_critic=True),
+    "n10_bf16_central": lambda: synth.CONFIGS[5].with_(num_envs=50, episode_len=3, central_critic=True),
+    # pursuit env (the task of the GPU-only experiment, section 7.3): one parameter set per role
+    "tag_3_1": lambda: synth.tag("tag", 70, 3, 1, 2, 64, 6, 3, idx=50).with_(radius_c=0.3, radius_r=0.25),
+    "tag_2_2": lambda: synth.tag("tag", 41, 2, 2, 1, 64, 6, 3, idx=51).with_(radius_c=0.3, radius_r=0.25),
+}
+
+
+@pytest.mark.parametrize("which", sorted(ACT_CASES))
 def test_split_calls_reproduce_the_fused_rollout(which):
-    cfg = {
-        "n3_f32_ragged": synth.CONFIGS[1].with_(num_envs=53, episode_len=4),
-        "n1_f32": synth.particle("p1", 70, 1, 64, 6, 3, synth.F32, 11),
-        "n6_f32": synth.CONFIGS[3].with_(num_envs=77, episode_len=5),
-        "n3_bf16": synth.particle("p3b", 45, 3, 64, 6, 3, synth.BF16, 12),
-        "n10_bf16": synth.CONFIGS[5].with_(num_envs=100, episode_len=3),
-        "lingauss": synth.CONFIGS[4].with_(num_envs=150, episode_len=3),
-    }[which]
+    cfg = ACT_CASES[which]()
     T = 7
-    _, _, params, dyn = oracle_setup(cfg)
+    _, _, params, dyn = setup_any(cfg)
     with GpuRollout(cfg, params.astype(np.float32), 31, dyn=dyn) as gpu:
         fused = gpu.run(T, gae=False, logits=True)
         es_f, g_f = gpu.get_state()
@@ -61,19 +107,21 @@ def test_split_calls_reproduce_the_fused_rollout(which):
     assert (g_s == T).all()
 
 
-def test_env_step_against_the_oracle_for_chosen_actions():
+@pytest.mark.parametrize("which", ["n3_f32", "tag_3_1", "tag_2_2"])
+def test_env_step_against_the_oracle_for_chosen_actions(which):
     import torch
-    cfg = synth.CONFIGS[1].with_(num_envs=41, episode_len=3)
-    env, _, params, _ = oracle_setup(cfg)
+    cfg = synth.CONFIGS[1].with_(num_envs=41, episode_len=3) if which == "n3_f32" else ACT_CASES[which]()
+    env, _, params, _ = setup_any(cfg)
     N, M, D = cfg.num_agents, cfg.M, cfg.obs_dim
     rng = np.random.default_rng(5)
     seed = 77
+    contacts = 0
     with GpuRollout(cfg, params.astype(np.float32), seed) as gpu:
         B = gpu.B
         obs = torch.empty((M, D), dtype=torch.float32, device="cuda")
         rew = torch.empty(M, dtype=torch.float32, device="cuda")
         done = torch.empty(M, dtype=torch.uint8, device="cuda")
-        for step in range(4):                       # crosses an episode end (reset draws)
+        for step in range(7):                       # crosses episode ends (reset draws)
             es, g = gpu.get_state()
             acts = rng.integers(0, 5, size=M).astype(np.int32)
             B.msrl_env_step(gpu.state, torch.from_numpy(acts).cuda(), rew, done, obs)
@@ -84,12 +132,15 @@ def test_env_step_against_the_oracle_for_chosen_actions():
             for e in range(cfg.num_envs):
                 s = es[e].astype(np.float64)
                 s2, r, d, margin = ref.env_step(env, seed, e, int(g[e]), s, acts[e * N:(e + 1) * N])
-                if margin > 1e-5:   # no pair distance within 1e-5 of the collision threshold
-                    assert_close(r_gpu[e * N:(e + 1) * N], np.full(N, r), TOL_F32, f"reward env {e} step {step}")
+                if margin > 1e-5:   # no pair distance within 1e-5 of the collision / contact threshold
+                    assert_close(r_gpu[e * N:(e + 1) * N], np.broadcast_to(r, (N,)), TOL_F32, f"reward env {e} step {step}")
+                contacts += int(np.any(np.asarray(r) > 0))
                 assert (d_gpu[e * N:(e + 1) * N] == d).all()
                 assert_close(es1[e], s2, TOL_F32, f"state env {e} step {step}")
                 assert_close(o_gpu[e * N:(e + 1) * N], ref.env_obs(env, es1[e].astype(np.float64)), TOL_F32,
                              f"next obs env {e} step {step}")
+    if cfg.kind == synth.TAG:
+        assert contacts > 10       # contact forces and contact rewards were exercised
 
 
 def test_observe_and_act_leave_the_state_alone_and_argument_errors():
@@ -119,16 +170,6 @@ def test_observe_and_act_leave_the_state_alone_and_argument_errors():
         assert e.value.code == B.MSRL_EINVAL
 
 
-ACT_CASES = {
-    "n3_f32_ragged": lambda: synth.CONFIGS[1].with_(num_envs=53, episode_len=4),
-    "n1_f32": lambda: synth.particle("p1", 70, 1, 64, 6, 3, synth.F32, 11),
-    "n2_f32": lambda: synth.particle("p2", 37, 2, 64, 6, 3, synth.F32, 13),
-    "n6_f32": lambda: synth.CONFIGS[3].with_(num_envs=77, episode_len=5),
-    "n3_bf16": lambda: synth.particle("p3b", 45, 3, 64, 6, 3, synth.BF16, 12),
-    "n10_bf16": lambda: synth.CONFIGS[5].with_(num_envs=100, episode_len=3),
-    "lingauss": lambda: synth.CONFIGS[4].with_(num_envs=150, episode_len=3),
-}
-
 
 def _caller_rows(cfg, rng, kind):
     """Observation rows [M, D] that no state of the library produced."""
@@ -137,7 +178,7 @@ def _caller_rows(cfg, rng, kind):
         rows = rng.standard_normal((M, D)).astype(np.float32) * np.float32(0.7)
     else:                                          # large and tiny magnitudes: tanh saturation, bf16 rounding
         rows = (rng.standard_normal((M, D)) * rng.choice([1e-3, 0.3, 4.0], size=(M, 1))).astype(np.float32)
-    if cfg.kind == synth.PARTICLE and N > 1:       # the trailing 2 (N - 1) slots of the layout are zero
+    if cfg.kind == synth.PARTICLE and N > 1:       # the trailing 2 (N - 1) slots of the particle layout are zero
         rows[:, D - 2 * (N - 1):] = 0.0
     return rows
 
@@ -150,7 +191,7 @@ def test_act_on_caller_chosen_rows_against_the_oracle(which):
     counters (env, agent, step counter of the state)."""
     import torch
     cfg = ACT_CASES[which]()
-    env, pol, params, dyn = oracle_setup(cfg)
+    env, pol, params, dyn = setup_any(cfg)
     bf16 = cfg.dtype == synth.BF16
     net_tol = 2e-2 if bf16 else TOL_F32
     N, M, D = cfg.num_agents, cfg.M, cfg.obs_dim
@@ -181,21 +222,22 @@ def test_act_on_caller_chosen_rows_against_the_oracle(which):
             torch.cuda.synchronize()
             a, lp, v, lg = a.cpu().numpy(), lp.cpu().numpy(), v.cpu().numpy(), lg.cpu().numpy()
             edges = 0
-            for m in range(M):
-                e, i = divmod(m, N)
-                lg_o, v_o = ref.policy_value(pol, params, rows[m])
-                assert_close(lg[m], lg_o, net_tol, f"{label}: logits row {m}")
-                assert_close(v[m], v_o, net_tol, f"{label}: value row {m}")
-                a_o, lp_o, mg = ref.sample(pol, seed, e, i, int(g[e]), lg[m])
-                if cfg.dist == synth.CATEGORICAL:
-                    if int(a[m]) != a_o:
-                        assert mg < 1e-5, f"{label}: action row {m}: gpu {a[m]} oracle {a_o} margin {mg}"
-                        edges += 1
-                        z = lg[m].astype(np.float64) - lg[m].max()
-                        lp_o = float(z[int(a[m])] - np.log(np.exp(z).sum()))
-                else:
-                    assert_close(a[m], a_o, TOL_F32, f"{label}: action row {m}")
-                assert_close(lp[m], lp_o, TOL_F32, f"{label}: logp row {m}")
+            for e in range(cfg.num_envs):
+                lg_o, v_o = expected_outputs(cfg, pol, params, rows[e * N:(e + 1) * N])
+                for i in range(N):
+                    m = e * N + i
+                    assert_close(lg[m], lg_o[i], net_tol, f"{label}: logits row {m}")
+                    assert_close(v[m], v_o[i], net_tol, f"{label}: value row {m}")
+                    a_o, lp_o, mg = ref.sample(pol, seed, e, i, int(g[e]), lg[m])
+                    if cfg.dist == synth.CATEGORICAL:
+                        if int(a[m]) != a_o:
+                            assert mg < 1e-5, f"{label}: action row {m}: gpu {a[m]} oracle {a_o} margin {mg}"
+                            edges += 1
+                            z = lg[m].astype(np.float64) - lg[m].max()
+                            lp_o = float(z[int(a[m])] - np.log(np.exp(z).sum()))
+                    else:
+                        assert_close(a[m], a_o, TOL_F32, f"{label}: action row {m}")
+                    assert_close(lp[m], lp_o, TOL_F32, f"{label}: logp row {m}")
             assert edges <= 2
         es1, g1 = gpu.get_state()
         np.testing.assert_array_equal(g1, g)      # acting does not advance the state
@@ -207,7 +249,7 @@ def test_observe_against_the_oracle(which):
     state, after a rollout (mid-episode, moving agents) and for a state the test injects."""
     import torch
     cfg = ACT_CASES[which]()
-    env, _, params, dyn = oracle_setup(cfg)
+    env, _, params, dyn = setup_any(cfg)
     N, M, D = cfg.num_agents, cfg.M, cfg.obs_dim
     rng = np.random.default_rng(23)
     with GpuRollout(cfg, params.astype(np.float32), 77, dyn=dyn) as gpu:

@@ -146,10 +146,9 @@ def test_tag_default_bodies_and_errors():
     with GpuRollout(cfg, params.astype(np.float32), SEED) as gpu:
         tr = gpu.run(cfg.T)
         check(cfg, tr, env, pol, params, list(range(cfg.num_envs)), np.zeros(cfg.num_envs, dtype=np.int64), cfg.T)
-        import torch
-        obs = torch.zeros((cfg.M, cfg.obs_dim), device="cuda")
-        with pytest.raises(B.MsrlError):        # the step-granular calls have no pursuit variant
-            B.msrl_observe(gpu.state, obs)
+        with pytest.raises(B.MsrlError) as e:   # the measurement variants have no pursuit kernel
+            B.msrl_measure_phase(gpu.state, gpu.params, 2, gpu.dev, B.MSRL_PHASE_ENV)
+        assert e.value.code == B.MSRL_EUNSUPPORTED
     assert B.msrl_param_count(B.make_policy_cfg(cfg)) == cfg.param_count == 2 * pol.param_count
     env_cfg, keep = B.make_env_cfg(cfg, None, None)
     one_role = B.make_policy_cfg(cfg)
