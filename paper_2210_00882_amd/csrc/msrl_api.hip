@@ -45,6 +45,7 @@ struct msrl_state {
   int envs_per_block;    // envs owned by one workgroup
   int in_used;           // leading observation features that can be non-zero (inputs of layer 1)
   int tag_tiles;         // pursuit env: 32-env tiles per workgroup (1 or 4)
+  bool packed_valid;     // `packed` holds the image of the parameters of an earlier call
 };
 
 namespace {
@@ -308,6 +309,7 @@ int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* param
   if (params) {
     int rc = pack_params(st, params, stream);
     if (rc != MSRL_OK) return rc;
+    st->packed_valid = true;
   }
   RolloutArgs a;
   memset(&a, 0, sizeof(a));
@@ -351,6 +353,7 @@ int enqueue_tag(msrl_state* st, const void* params, int32_t T, msrl_traj* out, h
   if (params) {  // (the environment-only variant runs no network)
     int rc = pack_params(st, params, stream);
     if (rc != MSRL_OK) return rc;
+    st->packed_valid = true;
   }
   const msrl_env_cfg& e = st->env;
   TagArgs a;
@@ -711,8 +714,9 @@ int msrl_observe(msrl_state* st, float* obs, void* hip_stream) {
 
 int msrl_act(msrl_state* st, const void* params, const float* obs, void* actions, float* logp, float* values,
              float* logits, void* hip_stream) {
-  if (!st || !params || !obs || !actions || !logp || !values)
-    return fail(MSRL_EINVAL, "msrl_act: NULL argument");
+  if (!st || !obs || !actions || !logp || !values) return fail(MSRL_EINVAL, "msrl_act: NULL argument");
+  if (!params && !st->packed_valid)
+    return fail(MSRL_EINVAL, "msrl_act: params is NULL and no earlier call on this state passed parameters");
   if (st->env.kind == MSRL_ENV_TAG) {
     msrl_traj out;
     memset(&out, 0, sizeof(out));

@@ -156,9 +156,16 @@ def test_observe_and_act_leave_the_state_alone_and_argument_errors():
         lp = torch.empty(M, dtype=torch.float32, device="cuda")
         v = torch.empty(M, dtype=torch.float32, device="cuda")
         B.msrl_observe(gpu.state, obs)
+        with pytest.raises(B.MsrlError) as e:      # no parameters have been passed to this state yet
+            B.msrl_act(gpu.state, None, obs, a, lp, v)
+        assert e.value.code == B.MSRL_EINVAL
         B.msrl_act(gpu.state, gpu.params, obs, a, lp, v)
         B.msrl_act(gpu.state, gpu.params, obs, a, lp, v)
+        # params = NULL: the image of the last parameters is used again
+        a2, lp2, v2 = torch.full_like(a, -1), torch.full_like(lp, -1.0), torch.full_like(v, -1.0)
+        B.msrl_act(gpu.state, None, obs, a2, lp2, v2)
         torch.cuda.synchronize()
+        assert torch.equal(a, a2) and torch.equal(lp, lp2) and torch.equal(v, v2)
         es1, g1 = gpu.get_state()
         np.testing.assert_array_equal(es0, es1)
         np.testing.assert_array_equal(g0, g1)
