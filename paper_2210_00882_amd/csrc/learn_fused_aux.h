@@ -65,9 +65,10 @@ struct WgradTArgs {
   int m_out;        // rows m < m_out of C are written
   int64_t n_tiles;
   int tiles_per_slice;  // row tiles per workgroup, even
-  float* C;         // [m_out, ldc] += A^T-contraction (fp32 atomics)
+  float* C;         // [slice][m_out, ldc] = the slice's A^T-contraction; the copies are slice_stride floats apart
   int64_t ldc;
-  float* bias;      // [N] += sums of B over the rows, or null
+  float* bias;      // [slice][N] = the slice's sums of B over the rows, or null
+  int64_t slice_stride;
 };
 
 // Output-stationary like wgrad_kernel (learn_kernels.h): workgroup z takes the row tiles
@@ -78,9 +79,11 @@ struct WgradTArgs {
 // memory latency (NTW = 1, the output layer, has the registers for a deeper queue).
 // The bias gradient is one more contraction with a left operand of ones: wave w adds it up for
 // column tile w.
+// Every slice stores its own copy of the result; reduce_partials_kernel (learn_kernels.h) adds the
+// copies up in slice order, so the gradient does not depend on the order the workgroups finish in.
 // Several such contractions in one launch (blockIdx.y picks the job): the launches of one gradient
-// pass are short and end in float atomics, so their tails and their memory latencies overlap when
-// the workgroups of all of them are resident together.
+// pass are short, so their tails and their memory latencies overlap when the workgroups of all of
+// them are resident together.
 struct WgradTJobs {
   int n;
   WgradTArgs job[4];
@@ -167,7 +170,7 @@ __global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTJobs jobs) {
   }
   if (b_live && h == 0) {
     const int nn = 32 * wave + i;  // every row of the ones-contraction is the column sum: take row 0
-    if (nn < g.N) atomicAdd(g.bias + nn, accb[0]);
+    if (nn < g.N) g.bias[(int64_t)blockIdx.x * g.slice_stride + nn] = accb[0];
   }
   if (!m_live) return;
 #pragma unroll
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTJobs jobs) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int m = m0 + 8 * (r / 4) + 4 * h + r % 4;
-      if (m < g.m_out && m < g.M) atomicAdd(g.C + (int64_t)m * g.ldc + nn, acc[j][r]);
+      if (m < g.m_out && m < g.M) g.C[(int64_t)blockIdx.x * g.slice_stride + (int64_t)m * g.ldc + nn] = acc[j][r];
     }
   }
 }

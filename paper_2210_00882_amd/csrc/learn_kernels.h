@@ -104,7 +104,9 @@ enum : int {
   EPI_BIAS_TANH = 0,  // C = tanh(acc + bias[n])
   EPI_BIAS = 1,       // C = acc + bias[n]
   EPI_DTANH = 2,      // C = acc * (1 - Hm[m][n]^2)
-  EPI_ATOMIC = 3      // C += acc (fp32 atomics; the k range is split over blockIdx.z)
+  EPI_PARTIAL = 3     // C[slice] = acc: the k range is split over blockIdx.z and every slice writes its own
+                      // copy of C, slice_stride floats apart; reduce_partials_kernel adds the copies up in a
+                      // fixed order (no float atomics: the gradient is the same bits on every run)
 };
 
 struct GemmArgs {
@@ -117,7 +119,8 @@ struct GemmArgs {
   int64_t M_alloc, N_alloc;  // rows of A / B that may be read (rows beyond read as zero)
   int64_t K;       // contraction length, a multiple of the k tile; both operands hold it
   int64_t lda, ldb, ldc, ldh;
-  int64_t k_per_slice;  // EPI_ATOMIC: k values per blockIdx.z, a multiple of the k tile
+  int64_t k_per_slice;  // EPI_PARTIAL: k values per blockIdx.z, a multiple of the k tile
+  int64_t slice_stride; // EPI_PARTIAL: floats between the copies of C of consecutive slices
 };
 
 // 4 waves per workgroup; a wave owns 32 rows of C and NT = 4 column tiles of 32.
@@ -125,14 +128,14 @@ template <bool BF16, typename SA, typename SB, typename SC, int EPI>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   typedef typename Frag<BF16>::T F;
   constexpr int KT = Frag<BF16>::KT, NT = 4;
-  __shared__ float s_c[EPI == EPI_ATOMIC ? 1 : 4][EPI == EPI_ATOMIC ? 1 : 32 * (32 * NT + 4)];
+  __shared__ float s_c[EPI == EPI_PARTIAL ? 1 : 4][EPI == EPI_PARTIAL ? 1 : 32 * (32 * NT + 4)];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int i = lane & 31, h = lane >> 5;
   const int64_t m0 = ((int64_t)blockIdx.x * 4 + wave) * 32;
   const int64_t n0 = (int64_t)blockIdx.y * (32 * NT);
   if (m0 >= g.M) return;
   int64_t k_begin = 0, k_end = g.K;
-  if (EPI == EPI_ATOMIC) {
+  if (EPI == EPI_PARTIAL) {
     k_begin = (int64_t)blockIdx.z * g.k_per_slice;
     k_end = min(g.K, k_begin + g.k_per_slice);
     if (k_begin >= k_end) return;
@@ -162,7 +165,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     }
   }
   // accumulator: lane (n = i, h), register r <-> row 8 (r / 4) + 4 h + r % 4 of the tile
-  if constexpr (EPI == EPI_ATOMIC) {
+  if constexpr (EPI == EPI_PARTIAL) {
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       const int64_t n = n0 + 32 * j + i;
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t m = m0 + 8 * (r / 4) + 4 * h + r % 4;
-        if (m < g.M) atomicAdd((float*)g.C + m * g.ldc + n, acc[j][r]);
+        if (m < g.M) ((float*)g.C)[(int64_t)blockIdx.z * g.slice_stride + m * g.ldc + n] = acc[j][r];
       }
     }
   } else {
@@ -241,7 +244,9 @@ struct RowGemmArgs {
   int64_t ldt;
   int64_t M_pad;   // rows covered (>= M, a multiple of 16); tiles beyond are not visited
   int64_t tiles;   // 256-row tiles
-  float* colsum;   // with Ct: colsum[n] += sum_m C[m][n] (the bias gradient of the layer), or null
+  float* colsum;   // with Ct: colsum[workgroup blockIdx.x][n] = that workgroup's share of sum_m C[m][n] (the bias
+                   // gradient of the layer; the shares are colsum_stride floats apart), or null
+  int64_t colsum_stride;
 };
 
 template <bool BF16, typename SC, int EPI, int NT>
@@ -358,21 +363,33 @@ __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
     }
   }
   if (ra.Ct && ra.colsum) {
+    // the eight waves' sums are added in wave order, then one plain store per column: no float atomics
+    float* red = &s_c[0][0];
+    __syncthreads();  // every wave is past its last tile
 #pragma unroll
-    for (int c = 0; c < NT / 2; ++c) {
-      const int64_t n = n0 + 64 * c + lane;
-      if (n < g.N) atomicAdd(ra.colsum + n, csum[c]);
+    for (int c = 0; c < NT / 2; ++c) red[(wave * (NT / 2) + c) * 64 + lane] = csum[c];
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int c = 0; c < NT / 2; ++c) {
+        const int64_t n = n0 + 64 * c + lane;
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) s += red[(w * (NT / 2) + c) * 64 + lane];
+        if (n < g.N) ra.colsum[(int64_t)blockIdx.x * ra.colsum_stride + n] = s;
+      }
     }
   }
 }
 
 // ---------------------------------------------------------------- weight-gradient contraction
-// C[m][n] += sum_k A[m][k] B[n][k] with few m, n (<= 256 each: the units of two layers) and a
+// C[slice][m][n] = sum_{k in slice} A[m][k] B[n][k] with few m, n (<= 256 each: the units of two layers) and a
 // very long k (the rows of the minibatch).  Output-stationary: workgroup z takes the k range
 // [z k_per_slice, (z+1) k_per_slice), wave w of its 8 waves the 32 rows m = 32 w .. 32 w + 31 of C
 // and all columns (up to 128 accumulator registers); the B fragments of a chunk of 4 k tiles are
 // shared through LDS (loaded once per workgroup, by all threads, one chunk ahead in registers), the
-// A fragments are the wave's own and come straight from global memory.  fp32 atomics at the end.
+// A fragments are the wave's own and come straight from global memory.  Every slice writes its own
+// copy of C (slice_stride floats apart); reduce_partials_kernel adds the copies in slice order.
 template <bool BF16, typename S>
 __global__ __launch_bounds__(512) void wgrad_kernel(GemmArgs g) {
   typedef typename Frag<BF16>::T F;
@@ -437,7 +454,7 @@ __global__ __launch_bounds__(512) void wgrad_kernel(GemmArgs g) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int64_t m = m0 + 8 * (r / 4) + 4 * h + r % 4;
-      if (m < g.M) atomicAdd((float*)g.C + m * g.ldc + n, acc[j][r]);
+      if (m < g.M) ((float*)g.C)[(int64_t)blockIdx.x * g.slice_stride + m * g.ldc + n] = acc[j][r];
     }
   }
 }
@@ -489,11 +506,11 @@ __global__ void fill_kernel(float* p, int64_t n, float v) {
   if (idx < n) p[idx] = v;
 }
 
-// out[u] += sum_r src[u][r], r < rows (src unit-major).  blockIdx.x = unit, blockIdx.y = slice of
-// `per_slice` rows; one float atomic per workgroup.
+// out[slice][u] = sum_{r in slice} src[u][r], r < rows (src unit-major).  blockIdx.x = unit, blockIdx.y =
+// slice of `per_slice` rows, whose sums lie slice_stride floats apart.
 template <typename S>
 __global__ __launch_bounds__(256) void rowsum_kernel(const S* src, int64_t units, int64_t rows, int64_t lds_,
-                                                     int64_t per_slice, float* out) {
+                                                     int64_t per_slice, float* out, int64_t slice_stride) {
   __shared__ float part[4];
   const int64_t u = blockIdx.x;
   const int64_t r_begin = (int64_t)blockIdx.y * per_slice, r_end = min(rows, r_begin + per_slice);
@@ -504,7 +521,41 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const S* src, int64_t units
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
   __syncthreads();
-  if (threadIdx.x == 0 && u < units) atomicAdd(out + u, part[0] + part[1] + part[2] + part[3]);
+  if (threadIdx.x == 0 && u < units)
+    out[(int64_t)blockIdx.y * slice_stride + u] = part[0] + part[1] + part[2] + part[3];
+}
+
+// ---------------------------------------------------------------- sum of the slices' gradients
+// grad[j.offset + i] = sum_{s < j.slices} part[s * slice_stride + j.offset + i], s ascending, for every
+// job j (one per parameter tensor: the kernels above split a tensor's contraction over a number of
+// slices of its own).  The order of the additions is fixed, so a gradient is the same bits every time.
+constexpr int REDUCE_MAX_JOBS = 40;
+struct ReduceJobs {
+  int32_t offset[REDUCE_MAX_JOBS];  // first float of the tensor in the parameter vector
+  int32_t count[REDUCE_MAX_JOBS];
+  int32_t slices[REDUCE_MAX_JOBS];
+  int32_t first_block[REDUCE_MAX_JOBS + 1];  // prefix sums of ceil(count / 256): block -> job
+  int32_t jobs;
+};
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* part, int64_t slice_stride, ReduceJobs j,
+                                                              float* grad) {
+  int q = 0;
+  while (q + 1 < j.jobs && (int)blockIdx.x >= j.first_block[q + 1]) ++q;
+  const int i = ((int)blockIdx.x - j.first_block[q]) * 256 + (int)threadIdx.x;
+  if (i >= j.count[q]) return;
+  const float* p = part + j.offset[q] + i;
+  // four chains keep several loads in flight; they are joined in a fixed order
+  float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+  const int n = j.slices[q];
+  int s = 0;
+  for (; s + 4 <= n; s += 4) {
+    s0 += p[(int64_t)(s + 0) * slice_stride];
+    s1 += p[(int64_t)(s + 1) * slice_stride];
+    s2 += p[(int64_t)(s + 2) * slice_stride];
+    s3 += p[(int64_t)(s + 3) * slice_stride];
+  }
+  for (; s < n; ++s) s0 += p[(int64_t)s * slice_stride];
+  grad[j.offset[q] + i] = (s0 + s1) + (s2 + s3);
 }
 
 // ---------------------------------------------------------------- per-row loss

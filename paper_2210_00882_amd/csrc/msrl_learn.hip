@@ -54,6 +54,9 @@ struct msrl_learner {
   void* xtv;             // [Dvp, Rp]
   NetBufs net[2];
   float* grad;           // scratch gradient of msrl_ppo_update
+  float* part;           // [part_slices][part_stride]: the slices' shares of a gradient, added up in slice order
+  int part_slices;       // most slices any contraction may be split into
+  int64_t part_stride;   // n_params rounded up to 64 floats
   float* stats;          // [8 + 5 * STAT_BINS]: results, then the bins the loss kernel adds into
   size_t n_params;
   // on-chip gradient pass (learn_fused.h): bf16 networks with a categorical policy of at most 16 actions
@@ -95,7 +98,8 @@ template <> struct CT<false> { typedef float T; };
 template <bool BF16, typename SC, int EPI>
 hipError_t gemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, const void* B, int64_t N_alloc,
                 int64_t ldb, void* C, int64_t M, int64_t N, int64_t ldc, int64_t K, const float* bias,
-                const void* Hm, int64_t ldh, int slices = 1) {
+                const void* Hm, int64_t ldh, int slices = 1, int64_t slice_stride = 0, int* used = nullptr) {
+  // EPI_PARTIAL: C is the first of `*used` copies, slice_stride floats apart, one per slice of K
   typedef typename CT<BF16>::T E;
   GemmArgs g;
   memset(&g, 0, sizeof(g));
@@ -104,6 +108,9 @@ hipError_t gemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, cons
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ldh = ldh;
   const int64_t kt = Frag<BF16>::KT;
   g.k_per_slice = round_up((K + slices - 1) / slices, kt);
+  g.slice_stride = slice_stride;
+  slices = (int)((K + g.k_per_slice - 1) / g.k_per_slice);  // no empty slice: every copy of C is written
+  if (used) *used = slices;
   dim3 grid((unsigned)((M + 127) / 128), (unsigned)((N + 127) / 128), (unsigned)slices);
   hipLaunchKernelGGL((gemm_kernel<BF16, E, E, SC, EPI>), grid, dim3(256), 0, s, g);
   return hipGetLastError();
@@ -113,7 +120,9 @@ hipError_t gemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, cons
 template <bool BF16, typename SC, int EPI>
 hipError_t rowgemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, const void* B, int64_t N_alloc,
                    int64_t ldb, void* C, int64_t M, int64_t N, int64_t ldc, int64_t K, const float* bias,
-                   const void* Hm, int64_t ldh, void* Ct, int64_t ldt, int64_t M_pad, float* colsum = nullptr) {
+                   const void* Hm, int64_t ldh, void* Ct, int64_t ldt, int64_t M_pad, float* colsum = nullptr,
+                   int64_t colsum_stride = 0, int* colsum_slices = nullptr) {
+  // colsum: the first of `*colsum_slices` copies (one per workgroup along x), colsum_stride floats apart
   constexpr int NT = BF16 ? 4 : 2;
   RowGemmArgs ra;
   memset(&ra, 0, sizeof(ra));
@@ -121,18 +130,21 @@ hipError_t rowgemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, c
   g.A = A; g.B = B; g.C = C; g.bias = bias; g.Hm = Hm;
   g.M = M; g.N = N; g.M_alloc = M_alloc; g.N_alloc = N_alloc; g.K = K;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ldh = ldh;
-  ra.Ct = Ct; ra.ldt = ldt; ra.M_pad = Ct ? M_pad : M; ra.colsum = colsum;
+  ra.Ct = Ct; ra.ldt = ldt; ra.M_pad = Ct ? M_pad : M; ra.colsum = colsum; ra.colsum_stride = colsum_stride;
   ra.tiles = (ra.M_pad + 255) / 256;
+  if (colsum_slices) *colsum_slices = (int)(ra.tiles < 256 ? ra.tiles : 256);
   if (K > 256 || N % 8 != 0) return hipErrorInvalidValue;  // shapes the learner never produces
   dim3 grid((unsigned)(ra.tiles < 256 ? ra.tiles : 256), (unsigned)((N + 32 * NT - 1) / (32 * NT)));
   hipLaunchKernelGGL((rowgemm_kernel<BF16, SC, EPI, NT>), grid, dim3(512), 0, s, ra);
   return hipGetLastError();
 }
 
-// weight-gradient contraction: C[M <= 256, N <= 256] += A B^T over K = rows, split into `slices`
+// weight-gradient contraction: C[slice][M <= 256, N <= 256] = A B^T over the slice's part of K = rows; K is split
+// into at most `slices` parts, `*used` of them in the end, whose copies of C lie slice_stride floats apart
 template <bool BF16>
 hipError_t wgrad(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, const void* B, int64_t N_alloc,
-                 int64_t ldb, float* C, int64_t M, int64_t N, int64_t ldc, int64_t K, int slices) {
+                 int64_t ldb, float* C, int64_t M, int64_t N, int64_t ldc, int64_t K, int slices, int64_t slice_stride,
+                 int* used_out) {
   typedef typename CT<BF16>::T E;
   if (M > 256 || N > 256) return hipErrorInvalidValue;
   GemmArgs g;
@@ -142,7 +154,9 @@ hipError_t wgrad(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, con
   g.lda = lda; g.ldb = ldb; g.ldc = ldc;
   const int64_t kc = 4 * Frag<BF16>::KT;
   g.k_per_slice = round_up((K + slices - 1) / slices, kc);
+  g.slice_stride = slice_stride;
   const int64_t used = (K + g.k_per_slice - 1) / g.k_per_slice;
+  *used_out = (int)used;
   hipLaunchKernelGGL((wgrad_kernel<BF16, E>), dim3((unsigned)used), dim3(512), 0, s, g);
   return hipGetLastError();
 }
@@ -172,13 +186,37 @@ hipError_t gather_pad(hipStream_t s, const float* src, const RowSel& sel, int64_
   return hipGetLastError();
 }
 
-// gradient of one minibatch; grad (device, n_params floats) is overwritten; stats[0..4] are sums
+// The parameter tensors of a gradient pass, each with the number of slices its contraction was split
+// into; launch() adds the slices' copies (in L->part) up into grad, in slice order.
+struct Reducer {
+  ReduceJobs j;
+  int blocks;
+  Reducer() : blocks(0) { memset(&j, 0, sizeof(j)); }
+  void add(size_t offset, size_t count, int slices) {
+    j.offset[j.jobs] = (int32_t)offset;
+    j.count[j.jobs] = (int32_t)count;
+    j.slices[j.jobs] = slices;
+    j.first_block[j.jobs] = blocks;
+    blocks += (int)((count + 255) / 256);
+    j.first_block[++j.jobs] = blocks;
+  }
+  hipError_t launch(const msrl_learner* L, float* grad, hipStream_t s) {
+    if (j.jobs == 0) return hipSuccess;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)L->part,
+                       L->part_stride, j, grad);
+    return hipGetLastError();
+  }
+};
+static_assert(REDUCE_MAX_JOBS >= 2 * 2 * (MAX_LAYERS + 1), "a weight and a bias tensor per layer and network");
+
+// gradient of one minibatch; the handled networks' part of grad (device, n_params floats) is overwritten;
+// stats[0..4] are sums
 template <bool BF16>
 int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel, const float* obs, const void* actions,
               const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* c, float* grad,
               hipStream_t s, int nets = 3, bool finish = true) {
-  // nets: bit n set = network n (0 policy, 1 value) is handled here; with bit 0 clear, grad and the
-  // statistics bins have been cleared by the caller and the on-chip pass adds the policy network's part.
+  // nets: bit n set = network n (0 policy, 1 value) is handled here; with bit 0 clear, the statistics bins
+  // have been cleared by the caller and the on-chip pass adds the policy network's part.
   // finish: add the statistics bins up at the end (not while another pass still adds to them)
   typedef typename CT<BF16>::T E;
   const int H = L->pol.hidden;
@@ -191,10 +229,8 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
   const int64_t Rn[2] = {R, R / G}, Rkn[2] = {round_up(R, 16), round_up(R / G, 16)};
   void* xcn[2] = {L->xc, G > 1 ? L->xcv : L->xc};
   void* xtn[2] = {L->xt, G > 1 ? L->xtv : L->xt};
-  if (nets & 1) {
-    hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
+  if (nets & 1)
     hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
-  }
   // observations in compute type, padded; and unit-major
   for (int n = 0; n < (G > 1 ? 2 : 1); ++n) {
     if (!((nets >> n) & 1) && G > 1) continue;
@@ -260,6 +296,8 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
     LTRY(hipGetLastError());
   }
   size_t off = 0;
+  Reducer red;
+  const int64_t ps = L->part_stride;
   for (int n = 0; n < 2; ++n) {
     NetBufs& b = L->net[n];
     const int O = n == 0 ? L->pol.out_dim : 1;
@@ -270,43 +308,59 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
       off += net_count(D, H, O, NL);
       continue;
     }
-    float* Gr = grad + off;
-    float* gW3 = Gr + first + (size_t)(NL - 1) * mid;
-    float* gb3 = gW3 + (size_t)H * O;
-    auto gW = [&](int l) { return l == 0 ? Gr : Gr + first + (size_t)(l - 1) * mid; };        // weights of hidden layer l
-    auto gb = [&](int l) { return l == 0 ? Gr + (size_t)D * H : gW(l) + (size_t)H * H; };     // ... its bias
+    // offsets into the parameter vector; the kernels write the slices' copies at L->part + offset
+    const size_t oW3 = off + first + (size_t)(NL - 1) * mid, ob3 = oW3 + (size_t)H * O;
+    auto oW = [&](int l) { return l == 0 ? off : off + first + (size_t)(l - 1) * mid; };          // weights of hidden layer l
+    auto ob = [&](int l) { return l == 0 ? off + (size_t)D * H : oW(l) + (size_t)H * H; };       // ... its bias
+    float* const part = L->part;
+    int used = 0;
     // backward through the activations: dZ of every hidden layer leaves unit-major, its column sums
     // are the bias gradient; the first layer's is not needed row-major
     LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dy, Rp, 32, b.wn3, H, 32, NL > 1 ? b.dz[NL - 1] : nullptr, R, H, H, 32, nullptr,
-                                      b.h[NL - 1], H, b.dzt[NL - 1], Rp, Rk, gb(NL - 1))));
-    for (int l = NL - 2; l >= 0; --l)
+                                      b.h[NL - 1], H, b.dzt[NL - 1], Rp, Rk, part + ob(NL - 1), ps, &used)));
+    red.add(ob(NL - 1), H, used);
+    for (int l = NL - 2; l >= 0; --l) {
       LTRY((rowgemm<BF16, E, EPI_DTANH>(s, b.dz[l + 1], Rp, H, b.wn[l + 1], H, H, l > 0 ? b.dz[l] : nullptr, R, H, H, H,
-                                        nullptr, b.h[l], H, b.dzt[l], Rp, Rk, gb(l))));
-    // weight gradients: contraction over the rows, split over workgroups, fp32 atomics
-    const int slices = (int)fmax(1.0, fmin(512.0, (double)(Rk / 1024)));
+                                        nullptr, b.h[l], H, b.dzt[l], Rp, Rk, part + ob(l), ps, &used)));
+      red.add(ob(l), H, used);
+    }
+    // weight gradients: contraction over the rows, split over workgroups; every slice writes a copy of its own
+    int slices = (int)fmax(1.0, fmin(256.0, (double)(Rk / 1024)));
+    if (slices > L->part_slices) slices = L->part_slices;
     if (H <= 256) {
-      LTRY((wgrad<BF16>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, slices)));
-      for (int l = NL - 1; l >= 1; --l)
-        LTRY((wgrad<BF16>(s, b.ht[l - 1], H, Rp, b.dzt[l], H, Rp, gW(l), H, H, H, Rk, slices)));
+      LTRY((wgrad<BF16>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, part + oW3, H, O, O, Rk, slices, ps, &used)));
+      red.add(oW3, (size_t)H * O, used);
+      for (int l = NL - 1; l >= 1; --l) {
+        LTRY((wgrad<BF16>(s, b.ht[l - 1], H, Rp, b.dzt[l], H, Rp, part + oW(l), H, H, H, Rk, slices, ps, &used)));
+        red.add(oW(l), (size_t)H * H, used);
+      }
       if (D <= 256)
-        LTRY((wgrad<BF16>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, slices)));
+        LTRY((wgrad<BF16>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, part + oW(0), D, H, H, Rk, slices, ps, &used)));
       else  // more input units than the kernel's panel holds (the joint observation)
-        LTRY((gemm<BF16, float, EPI_ATOMIC>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, nullptr, nullptr, 0, slices)));
+        LTRY((gemm<BF16, float, EPI_PARTIAL>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, part + oW(0), D, H, H, Rk, nullptr, nullptr, 0, slices, ps, &used)));
+      red.add(oW(0), (size_t)D * H, used);
     } else {
-      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, gW3, H, O, O, Rk, nullptr, nullptr, 0, slices)));
-      for (int l = NL - 1; l >= 1; --l)
-        LTRY((gemm<BF16, float, EPI_ATOMIC>(s, b.ht[l - 1], H, Rp, b.dzt[l], H, Rp, gW(l), H, H, H, Rk, nullptr, nullptr, 0, slices)));
-      LTRY((gemm<BF16, float, EPI_ATOMIC>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, gW(0), D, H, H, Rk, nullptr, nullptr, 0, slices)));
+      LTRY((gemm<BF16, float, EPI_PARTIAL>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, part + oW3, H, O, O, Rk, nullptr, nullptr, 0, slices, ps, &used)));
+      red.add(oW3, (size_t)H * O, used);
+      for (int l = NL - 1; l >= 1; --l) {
+        LTRY((gemm<BF16, float, EPI_PARTIAL>(s, b.ht[l - 1], H, Rp, b.dzt[l], H, Rp, part + oW(l), H, H, H, Rk, nullptr, nullptr, 0, slices, ps, &used)));
+        red.add(oW(l), (size_t)H * H, used);
+      }
+      LTRY((gemm<BF16, float, EPI_PARTIAL>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, part + oW(0), D, H, H, Rk, nullptr, nullptr, 0, slices, ps, &used)));
+      red.add(oW(0), (size_t)D * H, used);
     }
     {
-      const int64_t per_slice = 16384;
+      int64_t per_slice = 16384;
+      if ((R + per_slice - 1) / per_slice > L->part_slices) per_slice = (R + L->part_slices - 1) / L->part_slices;
       const unsigned ns = (unsigned)((R + per_slice - 1) / per_slice);
       hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)O, ns), dim3(256), 0, s, (const E*)b.dyt, (int64_t)O, R, Rp,
-                         per_slice, gb3);
+                         per_slice, part + ob3, ps);
+      red.add(ob3, O, (int)ns);
     }
     LTRY(hipGetLastError());
     off += net_count(D, H, O, NL);
   }
+  LTRY(red.launch(L, grad, s));
   return MSRL_OK;
 }
 
@@ -320,14 +374,12 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
                     const msrl_ppo_cfg* c, float* grad, hipStream_t s, int nets = 3, bool clear = true,
                     bool finish = true) {
   // nets: bit n set = network n is handled here (1: the policy network only; the value network's pass
-  // through device memory adds to the same grad and statistics bins).  clear / finish: zero grad and the
-  // bins first / add the bins up at the end (the caller does both around two concurrent passes)
+  // through device memory writes its own part of grad and adds to the same statistics bins).  clear /
+  // finish: zero the bins first / add the bins up at the end
   const int D = L->pol.in_dim, H = L->pol.hidden, kt1 = L->kt1;
   const NetLayout& ly = L->fly;
-  if (clear) {
-    hipLaunchKernelGGL(fill_kernel, grid1((int64_t)L->n_params), dim3(256), 0, s, grad, (int64_t)L->n_params, 0.0f);
+  if (clear)
     hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
-  }
   const float* b3p[2];
   {
     LearnPackJobs jobs;
@@ -398,41 +450,41 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
   LTRY(hipGetLastError());
   size_t off = 0;
   // Slices of row tiles: two compute units' share each, i.e. half as many workgroups per contraction as
-  // compute units.  Every slice ends in float atomics on the same addresses (4096 for a 64 x 64 result);
-  // measured against one share per slice: 3.64 -> 3.17 ms for the update of 2.5 M rows with 64-unit
-  // networks, 1.53 -> 1.42 ms per 524,288 rows with 256-unit ones; four shares are no better (the six
-  // contractions of a pass run two launches deep, so the chip stays busy).
+  // compute units (the six contractions of a pass run two launches deep, so the chip stays busy).  Every
+  // slice stores a copy of its result; the copies are added up in slice order afterwards.
   int tps = (int)((n_tiles + L->cus - 1) / L->cus);
   tps = (tps + 1) / 2 * 2 * 2;
+  while ((n_tiles + tps - 1) / tps > L->part_slices) tps *= 2;
   const unsigned slices = (unsigned)((n_tiles + tps - 1) / tps);
   // the contractions of both networks in two launches: the four with a hidden layer's width of columns,
   // and the two of the output layers
   WgradTJobs wide, narrow;
   wide.n = narrow.n = 0;
+  Reducer red;
   for (int n = 0; n < 2; ++n) {
     if (!((nets >> n) & 1)) continue;  // (the value network, behind the policy network's gradient)
     NetBufs& b = L->net[n];
     const int O = n == 0 ? L->pol.out_dim : 1;
-    float* gW1 = grad + off;
-    float* gb1 = gW1 + (size_t)D * H;
-    float* gW2 = gb1 + H;
-    float* gb2 = gW2 + (size_t)H * H;
-    float* gW3 = gb2 + H;
-    float* gb3 = gW3 + (size_t)H * O;
-    auto wg = [&](const void* A, int UA, int M, const void* B, int UB, int N, float* C, int64_t ldc, float* bias) {
+    const size_t oW1 = off, ob1 = oW1 + (size_t)D * H, oW2 = ob1 + H, ob2 = oW2 + (size_t)H * H, oW3 = ob2 + H,
+                 ob3 = oW3 + (size_t)H * O;
+    auto wg = [&](const void* A, int UA, int M, const void* B, int UB, int N, size_t oC, int64_t ldc, size_t obias) {
       WgradTArgs& g = N <= 32 ? narrow.job[narrow.n++] : wide.job[wide.n++];
       memset(&g, 0, sizeof(g));
       g.A = (const __bf16*)A; g.B = (const __bf16*)B; g.UA = UA; g.UB = UB; g.M = M; g.N = N; g.m_out = M;
-      g.n_tiles = n_tiles; g.tiles_per_slice = tps; g.C = C; g.ldc = ldc; g.bias = bias;
+      g.n_tiles = n_tiles; g.tiles_per_slice = tps; g.C = L->part + oC; g.ldc = ldc; g.bias = L->part + obias;
+      g.slice_stride = L->part_stride;
+      red.add(oC, (size_t)M * ldc, (int)slices);
+      red.add(obias, (size_t)N, (int)slices);
     };
-    wg(b.ht[1], H, H, b.dyt, 16, O, gW3, O, gb3);
-    wg(b.ht[0], H, H, b.dzt[1], H, H, gW2, H, gb2);
-    wg(L->xt, 16 * kt1, D, b.dzt[0], H, H, gW1, H, gb1);
+    wg(b.ht[1], H, H, b.dyt, 16, O, oW3, O, ob3);
+    wg(b.ht[0], H, H, b.dzt[1], H, H, oW2, H, ob2);
+    wg(L->xt, 16 * kt1, D, b.dzt[0], H, H, oW1, H, ob1);
     off += net_count(D, H, O);
   }
   if (wide.n) hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices, (unsigned)wide.n), dim3(512), 0, s, wide);
   if (narrow.n) hipLaunchKernelGGL((wgrad_tiled_kernel<1, 4>), dim3(slices, (unsigned)narrow.n), dim3(512), 0, s, narrow);
   LTRY(hipGetLastError());
+  LTRY(red.launch(L, grad, s));
   return MSRL_OK;
 }
 
@@ -564,6 +616,10 @@ int msrl_learner_init_path(const msrl_policy_cfg* policy, int64_t max_rows, int3
     A(&b.dyt, 32 * Rp * e);
   }
   A((void**)&L->grad, L->n_params * sizeof(float));
+  // a contraction over the rows is split into at most this many slices (never more than one per 128 rows)
+  L->part_slices = (int)(L->Rp / 128 + 1 < 256 ? L->Rp / 128 + 1 : 256);
+  L->part_stride = round_up((int64_t)L->n_params, 64);
+  A((void**)&L->part, (size_t)L->part_slices * (size_t)L->part_stride * sizeof(float));
   A((void**)&L->stats, (8 + 5 * STAT_BINS) * sizeof(float));
   if (rc != MSRL_OK) {
     msrl_learner_destroy(L);
@@ -575,7 +631,7 @@ int msrl_learner_init_path(const msrl_policy_cfg* policy, int64_t max_rows, int3
 
 void msrl_learner_destroy(msrl_learner* L) {
   if (!L) return;
-  void* ptrs[] = {L->xc, L->xt, L->xcv, L->xtv, L->grad, L->stats, L->fpacked};
+  void* ptrs[] = {L->xc, L->xt, L->xcv, L->xtv, L->grad, L->part, L->stats, L->fpacked};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (int n = 0; n < 2; ++n) {
