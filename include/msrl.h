@@ -76,7 +76,11 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   store them but leave the matching rows of W1 out of the contraction, so a
  *   non-finite weight in those rows does not reach the outputs.
  *   Reset draws every agent and landmark position uniform in [-1,1)^2, v = 0.
- *   act_dim is ignored.  The compiled kernels need num_landmarks == num_agents.
+ *   act_dim is ignored.  Kernels are compiled for num_landmarks == num_agents =
+ *   1 .. 10 with 64, 128 or 256 hidden units, fp32 and bf16 networks, two to
+ *   eight hidden layers (fp32 networks of 256 units: at most 7 agents, the
+ *   design keeps the first layer of both networks in LDS); anything else is
+ *   MSRL_EUNSUPPORTED.
  * MSRL_ENV_LINGAUSS: num_agents = 1, num_landmarks = 0, state = observation of
  *   obs_dim floats; s' = A s + B a + noise_std * N(0,I); reward
  *   -(s.s + act_cost * a.a) on the state before the step.  Reset: s ~ N(0,I).

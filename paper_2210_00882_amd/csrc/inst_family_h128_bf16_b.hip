@@ -1,0 +1,6 @@
+// Particle-env rollout kernels for 6 .. 10 agents per env, 128 hidden units, bf16 networks
+// (see MSRL_PARTICLE_FAMILIES in registry.h).
+#include "registry.h"
+namespace msrl {
+MSRL_FAMILY_BODY(h128_bf16_b, 6, 10, 128, true)
+}  // namespace msrl

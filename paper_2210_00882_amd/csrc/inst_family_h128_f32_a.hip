@@ -1,0 +1,6 @@
+// Particle-env rollout kernels for 1 .. 5 agents per env, 128 hidden units, fp32 networks
+// (see MSRL_PARTICLE_FAMILIES in registry.h).
+#include "registry.h"
+namespace msrl {
+MSRL_FAMILY_BODY(h128_f32_a, 1, 5, 128, false)
+}  // namespace msrl

@@ -74,23 +74,20 @@ namespace {
 
 // the compiled rollout kernels (built once; find_kernel sits behind the per-step calls too)
 const std::vector<KernelEntry>& all_kernels() {
-  static const std::vector<KernelEntry> table = {entry_p1_h64_f32(),  entry_p2_h64_f32(),    entry_p3_h64_f32(), entry_p3_h64_bf16(),
-          entry_p6_h128_f32(), entry_p10_h256_bf16(), entry_l17_6_h256(),
-          entry_p10_h256_bf16_env(), entry_p10_h256_bf16_mlp(), entry_p10_h256_bf16_clocks(),
-          entry_p3_h64_f32_env(),
-          entry_l17_6_h256_act(), entry_l17_6_h256_step(),
-          entry_p1_h64_f32_act(), entry_p1_h64_f32_step(),
-          entry_p2_h64_f32_act(), entry_p2_h64_f32_step(),
-          entry_p3_h64_f32_act(), entry_p3_h64_f32_step(),
-          entry_p3_h64_bf16_act(), entry_p3_h64_bf16_step(),
-          entry_p6_h128_f32_act(), entry_p6_h128_f32_step(),
-          entry_p10_h256_bf16_act(), entry_p10_h256_bf16_step(),
-          entry_p3_h64_f32_deep(), entry_p3_h64_bf16_deep(), entry_p10_h256_bf16_deep(),
-          entry_l17_6_h256_deep(),
-          entry_p3_h64_bf16_central(), entry_p10_h256_bf16_central(),
-          entry_p3_h64_f32_act_deep(), entry_p3_h64_bf16_act_deep(), entry_p10_h256_bf16_act_deep(),
-          entry_l17_6_h256_act_deep(),
-          entry_p3_h64_bf16_act_central(), entry_p10_h256_bf16_act_central()};
+  static const std::vector<KernelEntry> table = [] {
+    std::vector<KernelEntry> t;
+#define MSRL_CALL_FAMILY(NAME, N0, N1, H, BF16) particle_family_##NAME(t);
+    MSRL_PARTICLE_FAMILIES(MSRL_CALL_FAMILY)
+#undef MSRL_CALL_FAMILY
+    const KernelEntry more[] = {entry_l17_6_h256(), entry_l17_6_h256_act(), entry_l17_6_h256_step(),
+                                entry_l17_6_h256_deep(), entry_l17_6_h256_act_deep(),
+                                entry_p10_h256_bf16_env(), entry_p10_h256_bf16_mlp(), entry_p10_h256_bf16_clocks(),
+                                entry_p3_h64_f32_env(),
+                                entry_p3_h64_bf16_central(), entry_p10_h256_bf16_central(),
+                                entry_p3_h64_bf16_act_central(), entry_p10_h256_bf16_act_central()};
+    t.insert(t.end(), more, more + sizeof(more) / sizeof(more[0]));
+    return t;
+  }();
   return table;
 }
 

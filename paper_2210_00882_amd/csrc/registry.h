@@ -1,6 +1,8 @@
 // Table of the compiled rollout kernels.  Each instantiation lives in its own
 // translation unit (inst_*.hip) so that they compile in parallel.
 #pragma once
+#include <vector>
+
 #include "rollout_kernels.h"
 
 namespace msrl {
@@ -34,12 +36,57 @@ struct KernelEntry {
   }
 #define MSRL_LINGAUSS_ENTRY(NAME, D, K, H, WAVES) MSRL_LINGAUSS_ENTRY_PHASE(NAME, D, K, H, WAVES, PHASE_ALL)
 
-KernelEntry entry_p1_h64_f32();
-KernelEntry entry_p2_h64_f32();
-KernelEntry entry_p3_h64_f32();
-KernelEntry entry_p3_h64_bf16();
-KernelEntry entry_p6_h128_f32();
-KernelEntry entry_p10_h256_bf16();
+// ---- the particle env's kernel for every shape the design holds, by construction
+// Agents per env N = 1 .. 10, hidden width 64 / 128 / 256, fp32 and bf16 networks; per shape the full
+// rollout, the actor fragment, the env step, and the first two for networks with more than two hidden
+// layers.  Waves per workgroup (they share one LDS copy of the weights): two for 64 units; eight above,
+// but four where eight would not fit - fp32 networks of 256 units (their resident layer-1 tiles fill the
+// LDS) and the deep fp32 kernels of 128 units (eight waves leave each 256 registers, which the deep
+// kernel's state in fp32 exceeds; four waves run one per SIMD with twice that).
+constexpr int particle_waves(int H, bool bf16, int phase) {
+  const bool deep = phase == PHASE_DEEP || phase == PHASE_ACT_DEEP;
+  return H == 64 ? 2 : (!bf16 && (H >= 256 || deep)) ? 4 : 8;
+}
+// fp32 networks of 256 units: the layer-1 tiles of both networks (ceil((4 N + 3) / 8) tiles of 8 inputs x
+// 256 units x 4 bytes each) stay in LDS beside the two-stage window; beyond 7 agents they exceed 160 KB
+constexpr bool particle_fits(int N, int H, bool bf16) { return bf16 || H < 256 || N <= 7; }
+
+template <int N, int H, bool BF16, int PHASE>
+KernelEntry particle_entry() {
+  constexpr int W = particle_waves(H, BF16, PHASE);
+  return KernelEntry{0, N, 0, H, BF16 ? 1 : 0, (const void*)&particle_rollout_kernel<N, H, BF16, 1, W, PHASE>,
+                     32 / N, W, PHASE};
+}
+
+template <int N0, int N1, int H, bool BF16>
+void add_particle_family(std::vector<KernelEntry>& out) {
+  if constexpr (N0 <= N1) {
+    if constexpr (particle_fits(N0, H, BF16)) {
+      out.push_back(particle_entry<N0, H, BF16, PHASE_ALL>());
+      out.push_back(particle_entry<N0, H, BF16, PHASE_ACT>());
+      out.push_back(particle_entry<N0, H, BF16, PHASE_STEP>());
+      out.push_back(particle_entry<N0, H, BF16, PHASE_DEEP>());
+      out.push_back(particle_entry<N0, H, BF16, PHASE_ACT_DEEP>());
+    }
+    add_particle_family<N0 + 1, N1, H, BF16>(out);
+  }
+}
+
+// one translation unit per entry of this list (inst_family_*.hip): X(name, first N, last N, H, bf16)
+#define MSRL_PARTICLE_FAMILIES(X)                                                   \
+  X(h64_f32_a, 1, 5, 64, false)    X(h64_f32_b, 6, 10, 64, false)                   \
+  X(h64_bf16_a, 1, 5, 64, true)    X(h64_bf16_b, 6, 10, 64, true)                   \
+  X(h128_f32_a, 1, 5, 128, false)  X(h128_f32_b, 6, 10, 128, false)                 \
+  X(h128_bf16_a, 1, 5, 128, true)  X(h128_bf16_b, 6, 10, 128, true)                 \
+  X(h256_f32_a, 1, 4, 256, false)  X(h256_f32_b, 5, 7, 256, false)                  \
+  X(h256_bf16_a, 1, 5, 256, true)  X(h256_bf16_b, 6, 10, 256, true)
+#define MSRL_DECLARE_FAMILY(NAME, N0, N1, H, BF16) void particle_family_##NAME(std::vector<KernelEntry>& out);
+MSRL_PARTICLE_FAMILIES(MSRL_DECLARE_FAMILY)
+#undef MSRL_DECLARE_FAMILY
+// in its translation unit: MSRL_DEFINE_FAMILY(name) with the list's numbers
+#define MSRL_FAMILY_BODY(NAME, N0, N1, H, BF16) \
+  void particle_family_##NAME(std::vector<KernelEntry>& out) { add_particle_family<N0, N1, H, BF16>(out); }
+
 KernelEntry entry_l17_6_h256();
 // measurement variants (phase rooflines)
 KernelEntry entry_p10_h256_bf16_env();
@@ -50,34 +97,14 @@ KernelEntry entry_p3_h64_f32_env();
 // step-granular variants (actor only, environment only)
 KernelEntry entry_l17_6_h256_act();
 KernelEntry entry_l17_6_h256_step();
-KernelEntry entry_p1_h64_f32_act();
-KernelEntry entry_p1_h64_f32_step();
-KernelEntry entry_p2_h64_f32_act();
-KernelEntry entry_p2_h64_f32_step();
-KernelEntry entry_p3_h64_f32_act();
-KernelEntry entry_p3_h64_f32_step();
-KernelEntry entry_p3_h64_bf16_act();
-KernelEntry entry_p3_h64_bf16_step();
-KernelEntry entry_p6_h128_f32_act();
-KernelEntry entry_p6_h128_f32_step();
-KernelEntry entry_p10_h256_bf16_act();
-KernelEntry entry_p10_h256_bf16_step();
 
 // more than two hidden layers
-KernelEntry entry_p3_h64_f32_deep();
-KernelEntry entry_p3_h64_bf16_deep();
-KernelEntry entry_p10_h256_bf16_deep();
 KernelEntry entry_l17_6_h256_deep();
+KernelEntry entry_l17_6_h256_act_deep();
 
-// centralised critic (value network on the joint observation of an env)
+// centralised critic (value network on the joint observation of an env), and the actor fragment for it
 KernelEntry entry_p3_h64_bf16_central();
 KernelEntry entry_p10_h256_bf16_central();
-
-// the actor fragment for those
-KernelEntry entry_p3_h64_f32_act_deep();
-KernelEntry entry_p3_h64_bf16_act_deep();
-KernelEntry entry_p10_h256_bf16_act_deep();
-KernelEntry entry_l17_6_h256_act_deep();
 KernelEntry entry_p3_h64_bf16_act_central();
 KernelEntry entry_p10_h256_bf16_act_central();
 

@@ -168,8 +168,12 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   // Observation rows leave through a per-wave LDS staging area: the lanes write their features
   // in row layout, then the wave stores the same bytes as consecutive 16-byte (8-byte when D is
   // not a multiple of 4) pieces, so that one store instruction covers whole cache lines instead
-  // of 64 separate rows.  SE envs (SR rows) are staged per pass.
-  constexpr int SE = EPW * N * D * 4 <= 4608 ? EPW : (3072 / (N * D * 4) >= 1 ? 3072 / (N * D * 4) : 1);
+  // of 64 separate rows.  SE envs (SR rows) are staged per pass: all of the wave's when they take at most
+  // STG_ALL bytes, else as many as fit STG_SOME (networks of 256 units fill the LDS with their resident
+  // layer-1 tiles and the window, fp32 ones the more, so their staging areas are smaller).
+  constexpr int STG_ALL = !BF16 && H >= 256 ? 2048 : 4608;
+  constexpr int STG_SOME = H >= 256 ? (BF16 ? 2560 : 2048) : 3072;
+  constexpr int SE = EPW * N * D * 4 <= STG_ALL ? EPW : (STG_SOME / (N * D * 4) >= 1 ? STG_SOME / (N * D * 4) : 1);
   constexpr int SR = SE * N;
   constexpr int PASSES = (EPW + SE - 1) / SE;
   constexpr int PW = D % 4 == 0 ? 4 : 2;  // floats per piece

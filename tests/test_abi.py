@@ -42,7 +42,10 @@ def test_param_count_and_state_size():
     (dict(obs_dim=17), B.MSRL_EINVAL),            # particle obs_dim must be 4 + 2L + 4(N-1)
     (dict(out_dim=4), B.MSRL_EINVAL),             # categorical particle policy has 5 outputs
     (dict(hidden=96), B.MSRL_EUNSUPPORTED),       # valid but not compiled
-    (dict(dtype=synth.BF16, hidden=128, num_agents=6, num_landmarks=6, obs_dim=36), B.MSRL_EUNSUPPORTED),
+    # fp32 networks of 256 units: at most 7 agents per env (the layer-1 tiles of both networks stay in LDS)
+    (dict(hidden=256, num_agents=8, num_landmarks=8, obs_dim=48), B.MSRL_EUNSUPPORTED),
+    (dict(num_agents=11, num_landmarks=11, obs_dim=66), B.MSRL_EUNSUPPORTED),   # more than 10 agents per env
+    (dict(num_agents=3, num_landmarks=2, obs_dim=16), B.MSRL_EUNSUPPORTED),     # landmarks != agents
 ])
 def test_init_rejects_bad_configurations_before_touching_the_device(mutate, code):
     cfg = synth.CONFIGS[1].with_(**mutate)

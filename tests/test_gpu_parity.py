@@ -106,6 +106,37 @@ def test_particle_small_agent_counts(N):
     run_and_check(cfg, 12)
 
 
+SWEEP_FAMILIES = [(64, synth.F32), (64, synth.BF16), (128, synth.F32), (128, synth.BF16), (256, synth.F32),
+                  (256, synth.BF16)]
+
+
+@pytest.mark.parametrize("N", range(1, 11))
+@pytest.mark.parametrize("H,dtype", SWEEP_FAMILIES)
+def test_particle_agent_count_sweep(N, H, dtype):
+    # the agent sweep of section 7.4 at the oracle's size: 50 envs, every env and step, for every
+    # network width and type.  fp32 networks of 256 units hold at most 7 agents per env (their
+    # layer-1 tiles must fit the LDS): the library says so instead of running.
+    from paper_2210_00882_amd import binding as B
+    cfg = synth.particle(f"sweep{N}", 50, N, H, 8, 5, dtype=dtype, idx=100 + N)
+    if dtype == synth.F32 and H == 256 and N > 7:
+        e, _ = B.make_env_cfg(cfg)
+        with pytest.raises(B.MsrlError) as ei:
+            B.msrl_rollout_init(e, B.make_policy_cfg(cfg), 1)
+        assert ei.value.code == B.MSRL_EUNSUPPORTED
+        return
+    tr, stats = run_and_check(cfg, 8)
+    assert stats["rows"] == 8 * cfg.M
+
+
+@pytest.mark.parametrize("N", [2, 5, 7, 10])
+@pytest.mark.parametrize("H,dtype", SWEEP_FAMILIES)
+def test_particle_agent_count_sweep_three_hidden_layers(N, H, dtype):
+    if dtype == synth.F32 and H == 256 and N > 7:
+        pytest.skip("no kernel: see test_particle_agent_count_sweep")
+    cfg = synth.particle(f"sweepdeep{N}", 50, N, H, 7, 4, dtype=dtype, idx=120 + N).with_(hidden_layers=3)
+    run_and_check(cfg, 7)
+
+
 def test_particle_bf16_small():
     cfg = synth.particle("p3bf16", 50, 3, 64, 20, 6, dtype=synth.BF16, idx=20)
     run_and_check(cfg, 20)

@@ -75,6 +75,11 @@ ACT_CASES = {
     "n3_bf16": lambda: synth.particle("p3b", 45, 3, 64, 6, 3, synth.BF16, 12),
     "n10_bf16": lambda: synth.CONFIGS[5].with_(num_envs=100, episode_len=3),
     "lingauss": lambda: synth.CONFIGS[4].with_(num_envs=150, episode_len=3),
+    # shapes off the benchmark table (every agent count 1 .. 10 is compiled for every width and type)
+    "n4_h128_bf16": lambda: synth.particle("p4", 45, 4, 128, 6, 3, synth.BF16, 17),
+    "n7_h256_f32": lambda: synth.particle("p7", 33, 7, 256, 6, 3, synth.F32, 18),
+    "n8_h128_f32_3_layers": lambda: synth.particle("p8", 29, 8, 128, 6, 3, synth.F32, 19).with_(hidden_layers=3),
+    "n9_h64_bf16": lambda: synth.particle("p9", 31, 9, 64, 6, 3, synth.BF16, 20),
     # networks with more than two hidden layers (the evaluated networks of section 7.1 have seven layers)
     "n3_f32_4_layers": lambda: synth.particle("p3d", 45, 3, 64, 6, 3, synth.F32, 14).with_(hidden_layers=4),
     "n3_bf16_3_layers": lambda: synth.particle("p3d", 45, 3, 64, 6, 3, synth.BF16, 15).with_(hidden_layers=3),
