@@ -100,9 +100,14 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   Supported by msrl_rollout_step / msrl_rollout_gae, the step-granular calls
  *   (msrl_observe / msrl_act / msrl_env_step) and the snapshot calls; not by
  *   msrl_measure_phase.
+ *   Kernels are compiled for every (num_chasers, runners) with at most 8
+ *   agents per env, 0 .. 4 landmarks (never more than agents), bf16 networks
+ *   of 64 hidden units and two hidden layers (the four networks stay in LDS);
+ *   anything else is MSRL_EUNSUPPORTED.
  *   The kernel has two workgroup shapes with identical results (one or four
- *   tiles of 32 envs); tag_tiles = 0 lets msrl_rollout_init pick by num_envs,
- *   1 or 4 fixes the shape (EINVAL for any other value, and for a non-zero
+ *   tiles of 32 envs; four only with at most 4 agents per env); tag_tiles = 0
+ *   lets msrl_rollout_init pick by num_envs, 1 or 4 fixes the shape (EINVAL
+ *   for any other value, for 4 with more than 4 agents, and for a non-zero
  *   value with another env kind).
  *
  * An episode ends (done = 1, then reset) on every step whose counter g

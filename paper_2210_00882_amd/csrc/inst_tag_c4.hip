@@ -1,0 +1,5 @@
+// Pursuit-env rollout kernels with 4 chasers (see MSRL_TAG_FAMILIES in tag_kernels.h).
+#include "tag_kernels.h"
+namespace msrl {
+MSRL_TAG_FAMILY_BODY(4)
+}  // namespace msrl

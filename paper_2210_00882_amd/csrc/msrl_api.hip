@@ -123,9 +123,9 @@ bool valid_env_shape(const msrl_env_cfg* e) {
 // Pursuit env: 32-env tiles per workgroup.  Four tiles (16 waves behind one copy of the weights in LDS,
 // four waves per SIMD) once that still gives most compute units a workgroup, one tile (more, smaller
 // workgroups, two per compute unit) below.
-bool tag_tiles_compiled(int tiles) { return tiles == 1 || tiles == 4; }
-int choose_tag_tiles(int num_envs, int cus) {
-  return (int64_t)(num_envs / 128) * 8 >= (int64_t)cus * 5 ? 4 : 1;
+// (four tiles x agents must fit the 16 waves of a workgroup: at most 4 agents per env.)
+int choose_tag_tiles(int num_envs, int num_agents, int cus) {
+  return num_agents * 4 <= 16 && (int64_t)(num_envs / 128) * 8 >= (int64_t)cus * 5 ? 4 : 1;
 }
 
 size_t net_params(int in, int h, int out, int layers) {
@@ -412,9 +412,10 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
     return fail(MSRL_EINVAL, "%s: value_in_dim %d: a centralised critic takes num_agents * in_dim = %d "
                              "inputs (particle env, bfloat16 networks, two hidden layers)",
                 who, policy->value_in_dim, env->num_agents * policy->in_dim);
-  if (env->tag_tiles != 0 && (env->kind != MSRL_ENV_TAG || !tag_tiles_compiled(env->tag_tiles)))
-    return fail(MSRL_EINVAL, "%s: tag_tiles %d (0 lets the library choose; 1 or 4, pursuit env only)", who,
-                env->tag_tiles);
+  if (env->tag_tiles != 0 && (env->kind != MSRL_ENV_TAG || (env->tag_tiles != 1 && env->tag_tiles != 4) ||
+                              (env->tag_tiles == 4 && env->num_agents > 4)))
+    return fail(MSRL_EINVAL, "%s: tag_tiles %d (0 lets the library choose; 1, or 4 with at most 4 agents per env; "
+                             "pursuit env only)", who, env->tag_tiles);
   // kernel selection
   KernelEntry found;
   memset(&found, 0, sizeof(found));
@@ -457,7 +458,7 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
     st->envs_per_block = (int)epb;
   }
   // Pursuit env: tiles of 32 envs per workgroup (msrl_env_cfg.tag_tiles, 0 = chosen here).
-  st->tag_tiles = env->tag_tiles != 0 ? env->tag_tiles : choose_tag_tiles(env->num_envs, cus);
+  st->tag_tiles = env->tag_tiles != 0 ? env->tag_tiles : choose_tag_tiles(env->num_envs, env->num_agents, cus);
   st->state_size = (int)msrl_env_state_size(env);
   // The particle observation ends in 2 (N - 1) slots that are always zero: layer 1 skips them.
   st->in_used = env->kind == MSRL_ENV_PARTICLE ? 4 * env->num_agents + 2 : policy->in_dim;

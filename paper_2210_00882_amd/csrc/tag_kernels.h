@@ -14,6 +14,7 @@
 // The MLP itself is the chained MFMA form of mlp.h, reading its tiles from the resident images.
 #pragma once
 #include <type_traits>
+#include <vector>
 
 #include "rollout_kernels.h"
 
@@ -359,10 +360,50 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
   }
 }
 
+// ---- the compiled instances, by construction: every (chasers, runners) with at most 8 agents in all and
+// up to 4 landmarks (never more than agents), 64 hidden units; per shape the full rollout with one env tile
+// per workgroup and, while 4 tiles x agents fit the 16 waves of a workgroup, with four; the actor fragment;
+// the env step.
+struct TagEntry {
+  int nc, nr, landmarks, hidden, tiles, phase;
+  const void* fn;  // __global__ void (*)(TagArgs)
+};
+constexpr int TAG_MAX_AGENTS = 8, TAG_MAX_LANDMARKS = 4;
+
+template <int NC, int NR, int L>
+void add_tag_shape(std::vector<TagEntry>& out) {
+  out.push_back(TagEntry{NC, NR, L, 64, 1, TAG_ALL, (const void*)&tag_rollout_kernel<NC, NR, L, 64, 1, TAG_ALL>});
+  out.push_back(TagEntry{NC, NR, L, 64, 1, TAG_ACT, (const void*)&tag_rollout_kernel<NC, NR, L, 64, 1, TAG_ACT>});
+  out.push_back(TagEntry{NC, NR, L, 64, 1, TAG_STEP, (const void*)&tag_rollout_kernel<NC, NR, L, 64, 1, TAG_STEP>});
+  if constexpr (4 * (NC + NR) <= 16)
+    out.push_back(TagEntry{NC, NR, L, 64, 4, TAG_ALL, (const void*)&tag_rollout_kernel<NC, NR, L, 64, 4, TAG_ALL>});
+}
+template <int NC, int NR, int L = 0>
+void add_tag_landmarks(std::vector<TagEntry>& out) {
+  if constexpr (L <= TAG_MAX_LANDMARKS && L <= NC + NR) {
+    add_tag_shape<NC, NR, L>(out);
+    add_tag_landmarks<NC, NR, L + 1>(out);
+  }
+}
+// all shapes with NC chasers (one translation unit per NC: inst_tag_c*.hip)
+template <int NC, int NR = 1>
+void add_tag_chasers(std::vector<TagEntry>& out) {
+  if constexpr (NC + NR <= TAG_MAX_AGENTS) {
+    add_tag_landmarks<NC, NR>(out);
+    add_tag_chasers<NC, NR + 1>(out);
+  }
+}
+#define MSRL_TAG_FAMILIES(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7)
+#define MSRL_DECLARE_TAG_FAMILY(NC) void tag_family_c##NC(std::vector<TagEntry>& out);
+MSRL_TAG_FAMILIES(MSRL_DECLARE_TAG_FAMILY)
+#undef MSRL_DECLARE_TAG_FAMILY
+#define MSRL_TAG_FAMILY_BODY(NC) \
+  void tag_family_c##NC(std::vector<TagEntry>& out) { add_tag_chasers<NC>(out); }
+
 // launcher of the compiled instances; returns hipErrorInvalidValue when no instance matches.
 // tiles: env tiles per workgroup, 1 or 4 (the step-granular variants always take 1); phase: TAG_*.
 hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, int tiles, int phase, const TagArgs& a,
                               hipStream_t stream);
-bool tag_rollout_compiled(int nc, int nr, int landmarks, int hidden);
+bool tag_rollout_compiled(int nc, int nr, int landmarks, int hidden, int tiles = 1);
 
 }  // namespace msrl

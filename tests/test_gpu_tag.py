@@ -84,8 +84,20 @@ def check(cfg, tr, env, pol, params, env_ids, g0, T):
 def test_tag_rollout_every_env_and_step(nc, nr, L, tiles, E):
     # both workgroup shapes (one or four 32-env tiles, msrl_env_cfg.tag_tiles): E = 70 is
     # one ragged workgroup of four tiles with an empty tile, E = 300 three workgroups with a ragged last tile
+    tag_parity(nc, nr, L, tiles, E, 20 if E < 100 else 8, 100)
+
+
+@pytest.mark.parametrize("nc,nr,L,tiles", [(1, 1, 0, 0), (1, 1, 2, 4), (1, 3, 4, 4), (3, 1, 0, 1), (4, 4, 4, 0),
+                                           (7, 1, 3, 0), (1, 7, 0, 0), (5, 2, 1, 0), (2, 6, 4, 0), (3, 3, 3, 0),
+                                           (4, 1, 4, 0), (6, 1, 2, 0)])
+def test_tag_shapes_off_the_benchmark(nc, nr, L, tiles):
+    # every (chasers, runners) up to 8 agents with up to 4 landmarks is compiled: a sample of the corners
+    tag_parity(nc, nr, L, tiles, 45, 8, 10)
+
+
+def tag_parity(nc, nr, L, tiles, E, T, min_contacts):
     # big bodies, so that contact forces and contact rewards occur in most steps
-    cfg = synth.tag("tag", E, nc, nr, L, 64, 20 if E < 100 else 8, 7, idx=50 + nc).with_(radius_c=0.3, radius_r=0.25)
+    cfg = synth.tag("tag", E, nc, nr, L, 64, T, 7, idx=50 + nc).with_(radius_c=0.3, radius_r=0.25)
     env = tag_env(cfg)
     pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
     params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
@@ -111,7 +123,7 @@ def test_tag_rollout_every_env_and_step(nc, nr, L, tiles, E):
             for k, v in st.items():
                 total[k] = total.get(k, 0) + v
     assert total["rows"] == 2 * cfg.T * cfg.M
-    assert total["contacts"] > 100          # the contact path was exercised
+    assert total["contacts"] > min_contacts  # the contact path was exercised
     # chasers share their reward, runners do not see it
     r = tr["rewards"].reshape(cfg.T, cfg.num_envs, cfg.num_agents)
     assert (r[:, :, :nc] == r[:, :, :1]).all() and (r[:, :, :nc] >= 0).all() and (r[:, :, nc:] <= 0).all()
@@ -155,9 +167,18 @@ def test_tag_default_bodies_and_errors():
     one_role.roles = 1
     with pytest.raises(B.MsrlError):
         B.msrl_rollout_init(env_cfg, one_role, 1)
-    with pytest.raises(B.MsrlError):            # no instance for five agents
-        c5 = synth.tag("tag5", 8, 4, 1, 2, 64, 4, 4)
-        B.msrl_rollout_init(B.make_env_cfg(c5, None, None)[0], B.make_policy_cfg(c5), 1)
+    for bad in (synth.tag("tag9", 8, 5, 4, 2, 64, 4, 4),       # more than 8 agents per env
+                synth.tag("tagl5", 8, 3, 3, 5, 64, 4, 4),      # more than 4 landmarks
+                synth.tag("tagl3", 8, 1, 1, 3, 64, 4, 4),      # more landmarks than agents
+                synth.tag("tagh", 8, 3, 1, 2, 128, 4, 4)):     # networks that do not fit the LDS four at a time
+        with pytest.raises(B.MsrlError) as e:
+            B.msrl_rollout_init(B.make_env_cfg(bad, None, None)[0], B.make_policy_cfg(bad), 1)
+        assert e.value.code == B.MSRL_EUNSUPPORTED, bad.name
+    c5 = synth.tag("tag5", 8, 4, 1, 2, 64, 4, 4)               # four tiles x five agents exceed a workgroup
+    e5 = B.make_env_cfg(c5, None, None, tag_tiles=4)[0]
+    with pytest.raises(B.MsrlError) as e:
+        B.msrl_rollout_init(e5, B.make_policy_cfg(c5), 1)
+    assert e.value.code == B.MSRL_EINVAL
     with pytest.raises(B.MsrlError):            # a learner holds one parameter set
         B.msrl_learner_init(B.make_policy_cfg(cfg), 64)
 
