@@ -82,9 +82,7 @@ const std::vector<KernelEntry>& all_kernels() {
     const KernelEntry more[] = {entry_l17_6_h256(), entry_l17_6_h256_act(), entry_l17_6_h256_step(),
                                 entry_l17_6_h256_deep(), entry_l17_6_h256_act_deep(),
                                 entry_p10_h256_bf16_env(), entry_p10_h256_bf16_mlp(), entry_p10_h256_bf16_clocks(),
-                                entry_p3_h64_f32_env(),
-                                entry_p3_h64_bf16_central(), entry_p10_h256_bf16_central(),
-                                entry_p3_h64_bf16_act_central(), entry_p10_h256_bf16_act_central()};
+                                entry_p3_h64_f32_env()};
     t.insert(t.end(), more, more + sizeof(more) / sizeof(more[0]));
     return t;
   }();
@@ -467,7 +465,9 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
   st->central = central_of(*policy);
   // (joint observation: num_agents blocks of whole layer-1 tiles, see pack_params)
   st->critic_layout = net_layout(env->num_agents * tiles_for_inputs(st->in_used + 1, true) * 16 - 1, policy->hidden, true);
-  *packed_bytes = st->central ? st->layout.bytes + st->critic_layout.bytes : n_nets * st->layout.bytes;
+  // (behind a centralised critic's image: the memory its kernel's tile fetches may read past the end)
+  *packed_bytes = st->central ? st->layout.bytes + st->critic_layout.bytes + (size_t)CRITIC_FETCH_PAD_TILES * 1024
+                              : n_nets * st->layout.bytes;
   return MSRL_OK;
 }
 

@@ -51,9 +51,14 @@ constexpr int particle_waves(int H, bool bf16, int phase) {
 // 256 units x 4 bytes each) stay in LDS beside the two-stage window; beyond 7 agents they exceed 160 KB
 constexpr bool particle_fits(int N, int H, bool bf16) { return bf16 || H < 256 || N <= 7; }
 
+// Centralised critic (bf16 networks): one wave per 32-unit chunk of the hidden layers, and the envs of a
+// workgroup (waves x floor(32 / N)) are the at most 32 columns of the critic's tile: 64 units from 2
+// agents per env, 128 from 4, 256 from 7.
+constexpr bool particle_central_fits(int N, int H, bool bf16) { return bf16 && N >= 2 && (H / 32) * (32 / N) <= 32; }
+
 template <int N, int H, bool BF16, int PHASE>
 KernelEntry particle_entry() {
-  constexpr int W = particle_waves(H, BF16, PHASE);
+  constexpr int W = PHASE == PHASE_CENTRAL || PHASE == PHASE_ACT_CENTRAL ? H / 32 : particle_waves(H, BF16, PHASE);
   return KernelEntry{0, N, 0, H, BF16 ? 1 : 0, (const void*)&particle_rollout_kernel<N, H, BF16, 1, W, PHASE>,
                      32 / N, W, PHASE};
 }
@@ -67,6 +72,10 @@ void add_particle_family(std::vector<KernelEntry>& out) {
       out.push_back(particle_entry<N0, H, BF16, PHASE_STEP>());
       out.push_back(particle_entry<N0, H, BF16, PHASE_DEEP>());
       out.push_back(particle_entry<N0, H, BF16, PHASE_ACT_DEEP>());
+    }
+    if constexpr (particle_central_fits(N0, H, BF16)) {
+      out.push_back(particle_entry<N0, H, BF16, PHASE_CENTRAL>());
+      out.push_back(particle_entry<N0, H, BF16, PHASE_ACT_CENTRAL>());
     }
     add_particle_family<N0 + 1, N1, H, BF16>(out);
   }
@@ -102,10 +111,5 @@ KernelEntry entry_l17_6_h256_step();
 KernelEntry entry_l17_6_h256_deep();
 KernelEntry entry_l17_6_h256_act_deep();
 
-// centralised critic (value network on the joint observation of an env), and the actor fragment for it
-KernelEntry entry_p3_h64_bf16_central();
-KernelEntry entry_p10_h256_bf16_central();
-KernelEntry entry_p3_h64_bf16_act_central();
-KernelEntry entry_p10_h256_bf16_act_central();
 
 }  // namespace msrl

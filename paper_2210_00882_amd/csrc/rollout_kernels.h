@@ -122,6 +122,9 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 //              the 32-unit chunk w of each layer, the layers meeting in LDS.
 //   PHASE_ACT_DEEP, PHASE_ACT_CENTRAL  PHASE_ACT for networks with more than two hidden layers / with a
 //              centralised critic (the joint observation is then built from the caller's rows).
+// tiles of 1 KiB a fetch of the centralised critic's weights may read past the end of its image
+constexpr int CRITIC_FETCH_PAD_TILES = 32;
+
 enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHASE_ACT = 4, PHASE_STEP = 5,
              PHASE_DEEP = 6, PHASE_CENTRAL = 7, PHASE_ACT_DEEP = 8, PHASE_ACT_CENTRAL = 9 };
 // stamps: start of the step, observation rows built and stored, policy layer 1 done (after the
@@ -348,10 +351,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int S1 = SPN - S2;
   constexpr int RING = !CENTRAL ? 1 : ((L2T + S2 - 1) / S2 > (KT1C + S1 - 1) / S1 ? (L2T + S2 - 1) / S2 : (KT1C + S1 - 1) / S1);
   // uniform base addresses (scalar registers) of the chunk's layer-1 tiles and of its chunk block; the
-  // lanes add 16 lane.  A fetch of RING tiles may reach past the tiles of its layer: it stays inside
-  // the image (chunk blocks follow the layer-1 tiles, a block is longer than its layer-2 tiles), and
-  // the surplus is not used.
-  static_assert(!CENTRAL || (S2 * RING <= Net::CHUNK_TILES && S1 * RING - KT1C <= Net::CHUNK_TILES), "fetch range");
+  // lanes add 16 lane.  A fetch of RING tiles may reach past the tiles of its layer, by fewer than
+  // CRITIC_FETCH_PAD_TILES tiles: the surplus is not used, and the host keeps that much memory behind
+  // the critic's image so that the last wave's fetches stay inside the allocation.
+  static_assert(!CENTRAL || (S2 * RING - L2T <= CRITIC_FETCH_PAD_TILES && S1 * RING - KT1C <= CRITIC_FETCH_PAD_TILES),
+                "fetch range");
   const uint8_t* t1 = a.critic + (size_t)wave * KT1C * 1024;
   const uint8_t* t2 = a.critic + lyc.chunks + (size_t)wave * Net::CHUNK_TILES * 1024;
   const uint32_t lane16 = (uint32_t)lane * 16u;

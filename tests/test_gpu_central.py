@@ -28,6 +28,26 @@ def test_p3_central_critic_every_env_and_step(E, T, ep):
     _values_shared_per_env(cfg, tr)
 
 
+@pytest.mark.parametrize("N,H", [(2, 64), (4, 64), (5, 64), (7, 64), (10, 64), (4, 128), (6, 128), (7, 128), (9, 128),
+                                 (10, 128), (7, 256), (8, 256), (9, 256)])
+def test_central_critic_shapes_off_the_benchmark(N, H):
+    # one wave per 32-unit chunk, the envs of a workgroup as the columns of the critic's tile: compiled for
+    # 64 units from 2 agents per env, 128 from 4, 256 from 7 (up to 10 each)
+    cfg = synth.particle(f"central{N}_{H}", 50, N, H, 9, 4, dtype=synth.BF16, idx=70 + N).with_(central_critic=True)
+    tr, stats = run_and_check(cfg, 9, calls=2)
+    assert stats["mlp_rows"] == 2 * 10 * cfg.M
+    _values_shared_per_env(cfg, tr)
+
+
+def test_central_critic_shapes_that_do_not_fit():
+    from paper_2210_00882_amd import binding as B
+    for N, H in [(3, 128), (6, 256), (2, 256)]:   # more envs per workgroup than the 32 columns of the critic's tile
+        cfg = synth.particle("c", 8, N, H, 4, 4, dtype=synth.BF16, idx=1).with_(central_critic=True)
+        with pytest.raises(B.MsrlError) as e:
+            B.msrl_rollout_init(B.make_env_cfg(cfg, None, None)[0], B.make_policy_cfg(cfg), 1)
+        assert e.value.code == B.MSRL_EUNSUPPORTED
+
+
 @pytest.mark.parametrize("T", [1, 2, 3])
 def test_central_critic_shortest_rollouts(T):
     # the value leaves the kernel two steps behind the step it belongs to: the shortest rollouts are all tail
