@@ -234,8 +234,13 @@ __device__ __forceinline__ void bwd_chunk(const u32x4* tiles, const bf16x8 (&dz2
 constexpr int ROWS_WAVES = 8;  // waves per workgroup of the row kernel = row tiles per group
 constexpr int ROWS_STAT_BINS = 64;  // bins per statistic in RowsArgs::stats (after 8 result slots)
 
+// workgroups of the row kernel that share a compute unit: two for 64-unit networks (their registers are
+// held to 128 per lane for that, and 60 KiB of LDS each leave the room), one above
+constexpr int rows_workgroups_per_cu(int H) { return H <= 64 ? 2 : 1; }
+
 template <int H, int KT1, int NET, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVES / 4 * rows_workgroups_per_cu(H))))
+void ppo_rows_kernel(RowsArgs a) {
   constexpr int NBUF = 2;
   typedef Mlp<H, true, 1, KT1> Net;
   constexpr int NUC = Net::NUC, KT2 = Net::KT2, TPC = Net::TPC, G = Net::G;
@@ -244,10 +249,16 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
   constexpr int SPN = Stream::STAGES_PER_NET;
   typedef bf16x8 Op;
   static_assert(KT2 >= G && TPC <= 2, "ring prefetch depth; layer-3 tiles per chunk");
+  // Up to 128 units all 2 SPN stages of a tile (forward, then backward chunk blocks) fit the LDS at once:
+  // they are copied there once, and the tile loop has no waits for copies and no barriers, so the waves of
+  // a workgroup drift apart and cover each other's memory latencies.  (The wait for a streamed stage,
+  // s_waitcnt vmcnt, also waits for every store the wave has in flight - two KiB per row here.)
+  constexpr bool RESIDENT = H <= 128;
+  constexpr int WBUFS = RESIDENT ? 2 * SPN : NBUF;
 
   __shared__ __attribute__((aligned(16))) u32x4 s_l1[Net::L1_TILES * 64];
   __shared__ __attribute__((aligned(16))) u32x4 s_w3t[NUC * 64];
-  __shared__ __attribute__((aligned(16))) u32x4 s_w[NBUF * Stream::BUF_SLOTS];
+  __shared__ __attribute__((aligned(16))) u32x4 s_w[WBUFS * Stream::BUF_SLOTS];
   __shared__ __attribute__((aligned(16))) float s_b3[32];
   __shared__ __attribute__((aligned(16))) uint32_t s_stg[WAVES][Stager::WORDS];
 
@@ -265,7 +276,12 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
   ws.chunk_bytes = ly.chunk_bytes;
   ws.wave = wave;
   ws.lane = lane;
-  ws.issue(0, 0);
+  if constexpr (RESIDENT) {
+#pragma unroll
+    for (int sgi = 0; sgi < 2 * SPN; ++sgi) ws.issue(sgi, sgi);
+  } else {
+    ws.issue(0, 0);
+  }
   {
     const u32x4* src = (const u32x4*)(a.packed + ly.w1);
     for (int i = threadIdx.x; i < Net::L1_TILES * 64; i += blockDim.x) s_l1[i] = src[i];
@@ -273,13 +289,14 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     for (int i = threadIdx.x; i < NUC * 64; i += blockDim.x) s_w3t[i] = src3[i];
     if (threadIdx.x < 32) s_b3[threadIdx.x] = (int)threadIdx.x < O ? a.b3[threadIdx.x] : 0.0f;
   }
-  __syncthreads();
+  if constexpr (RESIDENT) ws.wait_all(); else __syncthreads();
 
   float st[5] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f};  // per-lane sums: policy term, value term, entropy, clipped, kl
-  int gs = 0;  // stages consumed so far: stage gs sits in buffer gs % NBUF
+  int gs = 0;  // stages consumed so far: stage gs sits in buffer gs % WBUFS
   const int64_t groups = (a.n_tiles + WAVES - 1) / WAVES;
   // copies of stage `next` into buffer `nbuf`, spread over the tile loops of the current stage
   auto spread = [&](int next, int nbuf, int c, int kt) {
+    if constexpr (RESIDENT) return;
 #pragma unroll
     for (int i = 0; i < Stream::PER_WAVE; ++i)
       if (i * (CPS * KT2) / Stream::PER_WAVE == c * KT2 + kt) ws.issue_part(next, nbuf, i);
@@ -291,7 +308,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
     const int64_t row = tile * 32 + n;
     const bool valid = live && row < a.R;
     const int64_t prow = valid ? a.sel.at(row) : 0;  // the row inside the caller's arrays
-    ws.wait_oldest();  // forward stage 0 is in; every wave has left the previous tile
+    if constexpr (!RESIDENT) ws.wait_oldest();  // forward stage 0 is in; every wave has left the previous tile
     // per-row inputs of the loss, fetched early
     int act = 0;
     float lpo = 0.0f, adv = 0.0f, ret = 0.0f;
@@ -349,12 +366,14 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
       f32x16 acc = zero16();
 #pragma unroll 1
       for (int sc = 0; sc < SPN; ++sc) {
-        if (sc != 0) ws.wait_oldest();
+        if constexpr (!RESIDENT) {
+          if (sc != 0) ws.wait_oldest();
+        }
         const int next = sc + 1;  // the first backward stage follows the last forward stage
         const int nbuf = (gs + 1) % NBUF;
 #pragma unroll
         for (int c = 0; c < CPS; ++c) {
-          const u32x4* tiles = ws.tiles(gs % NBUF, c);
+          const u32x4* tiles = ws.tiles(gs % WBUFS, c);
           auto tick = [&](int kt) { spread(next, nbuf, c, kt); };
           Op hn[2];
           if (c == 0 && sc == 0) {  // the first chunk of a tile has no chunk before it
@@ -368,7 +387,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
       }
       // last chunk: its tanh and layer-3 contribution (tiles of the last stage, still resident)
       {
-        const u32x4* tiles = ws.tiles((gs - 1) % NBUF, CPS - 1);
+        const u32x4* tiles = ws.tiles((gs - 1) % WBUFS, CPS - 1);
         float t[16];
         Op hl[2];
         tanh_range(acc, t, 0, 16, false);
@@ -466,13 +485,13 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
       Op hp[2] = {Op{0, 0, 0, 0, 0, 0, 0, 0}, Op{0, 0, 0, 0, 0, 0, 0, 0}};  // layer-1 activations of the chunk before
 #pragma unroll 1
       for (int sc = 0; sc < SPN; ++sc) {
-        ws.wait_oldest();
+        if constexpr (!RESIDENT) ws.wait_oldest();
         int next = SPN + sc + 1;  // the next tile's first forward stage follows the last backward stage
         if (next >= 2 * SPN) next -= 2 * SPN;
         const int nbuf = (gs + 1) % NBUF;
 #pragma unroll
         for (int c = 0; c < CPS; ++c) {
-          const u32x4* tiles = ws.tiles(gs % NBUF, c);
+          const u32x4* tiles = ws.tiles(gs % WBUFS, c);
           auto tick = [&](int kt) { spread(next, nbuf, c, kt); };
           const int chunk = sc * CPS + c;
           Op dz[2];
@@ -502,7 +521,7 @@ __global__ __launch_bounds__(64 * WAVES) void ppo_rows_kernel(RowsArgs a) {
       }
     }
   }
-  ws.wait_all();  // the copy issued ahead for a tile that does not exist
+  if constexpr (!RESIDENT) ws.wait_all();  // the copy issued ahead for a tile that does not exist
 
   // sums of the wave -> one atomic per statistic and wave, spread over the bins
 #pragma unroll

@@ -525,10 +525,43 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const S* src, int64_t units
     out[(int64_t)blockIdx.y * slice_stride + u] = part[0] + part[1] + part[2] + part[3];
 }
 
+// ---------------------------------------------------------------- Adam
+// One step on element idx (c1 = 1 - beta1^k, c2 = 1 - beta2^k for step k).  The kernel below and the
+// reduction of the slices' gradients (which can apply the step to what it has just summed) share it.
+struct AdamArgs {
+  float *p, *m, *v;  // p null: no step
+  float lr, b1, b2, eps, c1, c2;
+};
+__device__ __forceinline__ void adam_update(const AdamArgs& a, int64_t idx, float gi) {
+  const float mi = a.b1 * a.m[idx] + (1.0f - a.b1) * gi;
+  const float vi = a.b2 * a.v[idx] + (1.0f - a.b2) * gi * gi;
+  a.m[idx] = mi;
+  a.v[idx] = vi;
+  a.p[idx] -= a.lr * (mi / a.c1) / (sqrtf(vi / a.c2) + a.eps);
+}
+__global__ void adam_kernel(AdamArgs a, const float* g, int64_t n) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < n) adam_update(a, idx, g[idx]);
+}
+
+// stats[q] = sum of the bins of statistic q (the first wave of a workgroup)
+constexpr int STAT_BINS = 64;
+__device__ __forceinline__ void stats_reduce(float* stats) {
+  if (threadIdx.x >= 64) return;
+  for (int q = 0; q < 5; ++q) {
+    float s = stats[8 + q * STAT_BINS + threadIdx.x];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (threadIdx.x == 0) stats[q] = s;
+  }
+}
+
 // ---------------------------------------------------------------- sum of the slices' gradients
 // grad[j.offset + i] = sum_{s < j.slices} part[s * slice_stride + j.offset + i], s ascending, for every
 // job j (one per parameter tensor: the kernels above split a tensor's contraction over a number of
 // slices of its own).  The order of the additions is fixed, so a gradient is the same bits every time.
+// With `adam.p` set the Adam step of each element follows at once; with `stats` set one more workgroup
+// (the last) adds up the bins of the loss statistics.
 constexpr int REDUCE_MAX_JOBS = 40;
 struct ReduceJobs {
   int32_t offset[REDUCE_MAX_JOBS];  // first float of the tensor in the parameter vector
@@ -538,7 +571,11 @@ struct ReduceJobs {
   int32_t jobs;
 };
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* part, int64_t slice_stride, ReduceJobs j,
-                                                              float* grad) {
+                                                              float* grad, AdamArgs adam, float* stats) {
+  if ((int)blockIdx.x >= j.first_block[j.jobs]) {
+    if (stats) stats_reduce(stats);
+    return;
+  }
   int q = 0;
   while (q + 1 < j.jobs && (int)blockIdx.x >= j.first_block[q + 1]) ++q;
   const int i = ((int)blockIdx.x - j.first_block[q]) * 256 + (int)threadIdx.x;
@@ -555,11 +592,12 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* part,
     s3 += p[(int64_t)(s + 3) * slice_stride];
   }
   for (; s < n; ++s) s0 += p[(int64_t)s * slice_stride];
-  grad[j.offset[q] + i] = (s0 + s1) + (s2 + s3);
+  const float gi = (s0 + s1) + (s2 + s3);
+  grad[j.offset[q] + i] = gi;
+  if (adam.p) adam_update(adam, j.offset[q] + i, gi);
 }
 
 // ---------------------------------------------------------------- per-row loss
-constexpr int STAT_BINS = 64;
 struct LossArgs {
   const float* y;       // [R, 32] policy outputs (columns >= out_dim unused)
   const float* v;       // [R, 32] value output in column 0
@@ -701,15 +739,7 @@ __global__ __launch_bounds__(256) void loss_kernel(LossArgs a) {
               part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x]);
 }
 
-// stats[q] = sum of the bins of statistic q (one wave)
-__global__ __launch_bounds__(64) void stats_reduce_kernel(float* stats) {
-  for (int q = 0; q < 5; ++q) {
-    float s = stats[8 + q * STAT_BINS + threadIdx.x];
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-    if (threadIdx.x == 0) stats[q] = s;
-  }
-}
+__global__ __launch_bounds__(64) void stats_reduce_kernel(float* stats) { stats_reduce(stats); }
 
 // out[0] += scale * sum of x[sel.at(r)], r < rows (one float atomic per workgroup; out cleared by the caller)
 __global__ __launch_bounds__(256) void rows_sum_kernel(const float* x, RowSel sel, int64_t rows, float scale, float* out) {
@@ -722,19 +752,6 @@ __global__ __launch_bounds__(256) void rows_sum_kernel(const float* x, RowSel se
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
   __syncthreads();
   if (threadIdx.x == 0) atomicAdd(out, scale * (part[0] + part[1] + part[2] + part[3]));
-}
-
-// ---------------------------------------------------------------- Adam
-__global__ void adam_kernel(float* p, float* m, float* v, const float* g, int64_t n, float lr, float b1, float b2,
-                            float eps, float c1, float c2) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= n) return;
-  const float gi = g[idx];
-  const float mi = b1 * m[idx] + (1.0f - b1) * gi;
-  const float vi = b2 * v[idx] + (1.0f - b2) * gi * gi;
-  m[idx] = mi;
-  v[idx] = vi;
-  p[idx] -= lr * (mi / c1) / (sqrtf(vi / c2) + eps);
 }
 
 }  // namespace msrl

@@ -200,10 +200,13 @@ struct Reducer {
     blocks += (int)((count + 255) / 256);
     j.first_block[++j.jobs] = blocks;
   }
-  hipError_t launch(const msrl_learner* L, float* grad, hipStream_t s) {
+  // adam: the step to apply to what is summed, or null; stats: bins to add up on the way, or null
+  hipError_t launch(const msrl_learner* L, float* grad, const AdamArgs* adam, float* stats, hipStream_t s) {
     if (j.jobs == 0) return hipSuccess;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)L->part,
-                       L->part_stride, j, grad);
+    AdamArgs none;
+    memset(&none, 0, sizeof(none));
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)blocks + (stats ? 1u : 0u)), dim3(256), 0, s,
+                       (const float*)L->part, L->part_stride, j, grad, adam ? *adam : none, stats);
     return hipGetLastError();
   }
 };
@@ -214,7 +217,7 @@ static_assert(REDUCE_MAX_JOBS >= 2 * 2 * (MAX_LAYERS + 1), "a weight and a bias 
 template <bool BF16>
 int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel, const float* obs, const void* actions,
               const float* logp_old, const float* adv, const float* ret, const msrl_ppo_cfg* c, float* grad,
-              hipStream_t s, int nets = 3, bool finish = true) {
+              hipStream_t s, const AdamArgs* adam, int nets = 3, bool finish = true) {
   // nets: bit n set = network n (0 policy, 1 value) is handled here; with bit 0 clear, the statistics bins
   // have been cleared by the caller and the on-chip pass adds the policy network's part.
   // finish: add the statistics bins up at the end (not while another pass still adds to them)
@@ -360,7 +363,7 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
     LTRY(hipGetLastError());
     off += net_count(D, H, O, NL);
   }
-  LTRY(red.launch(L, grad, s));
+  LTRY(red.launch(L, grad, adam, nullptr, s));
   return MSRL_OK;
 }
 
@@ -371,19 +374,21 @@ static_assert(ROWS_STAT_BINS == STAT_BINS, "the row kernel and the loss kernel s
 // unit-major operands), then the weight and bias gradients from those.
 int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel, const float* obs,
                     const void* actions, const float* logp_old, const float* adv, const float* ret,
-                    const msrl_ppo_cfg* c, float* grad, hipStream_t s, int nets = 3, bool clear = true,
-                    bool finish = true) {
+                    const msrl_ppo_cfg* c, float* grad, hipStream_t s, const AdamArgs* adam, int nets = 3,
+                    bool clear = true, bool finish = true) {
   // nets: bit n set = network n is handled here (1: the policy network only; the value network's pass
   // through device memory writes its own part of grad and adds to the same statistics bins).  clear /
   // finish: zero the bins first / add the bins up at the end
   const int D = L->pol.in_dim, H = L->pol.hidden, kt1 = L->kt1;
   const NetLayout& ly = L->fly;
-  if (clear)
-    hipLaunchKernelGGL(fill_kernel, grid1(8 + 5 * STAT_BINS), dim3(256), 0, s, L->stats, (int64_t)(8 + 5 * STAT_BINS), 0.0f);
   const float* b3p[2];
   {
     LearnPackJobs jobs;
     memset(&jobs, 0, sizeof(jobs));
+    if (clear) {  // the statistics bins are zeroed on the way
+      jobs.clear = L->stats;
+      jobs.n_clear = 8 + 5 * STAT_BINS;
+    }
     const float* P = params;
     int max_items = 0;
     for (int n = 0; n < 2; ++n) {
@@ -425,7 +430,8 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
   }
   const int64_t n_tiles = (R + 31) / 32;
   const int64_t groups = (n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
-  const unsigned grid = (unsigned)(groups < L->cus ? groups : L->cus);
+  const int64_t resident = (int64_t)L->cus * rows_workgroups_per_cu(H);
+  const unsigned grid = (unsigned)(groups < resident ? groups : resident);
   for (int n = 0; n < 2; ++n) {
     if (!((nets >> n) & 1)) continue;
     NetBufs& b = L->net[n];
@@ -446,18 +452,27 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
                             : launch_ppo_rows_h256(kt1, n, a, grid, s);
     LTRY(e);
   }
-  if (finish) hipLaunchKernelGGL(stats_reduce_kernel, dim3(1), dim3(64), 0, s, L->stats);
   LTRY(hipGetLastError());
   size_t off = 0;
-  // Slices of row tiles: two compute units' share each, i.e. half as many workgroups per contraction as
-  // compute units (the six contractions of a pass run two launches deep, so the chip stays busy).  Every
-  // slice stores a copy of its result; the copies are added up in slice order afterwards.
-  int tps = (int)((n_tiles + L->cus - 1) / L->cus);
-  tps = (tps + 1) / 2 * 2 * 2;
+  // Slices of row tiles.  Networks of 64 units: the waves of a workgroup split a slice's tiles and every
+  // wave holds a whole result (wgrad_wave_kernel), all six contractions in one launch, about half as many
+  // slices as compute units (x 6 jobs: three workgroups of four waves per compute unit).  Wider ones: two
+  // compute units' share per slice, i.e. half as many workgroups per contraction as compute units (the six
+  // contractions of a pass run two launches deep, so the chip stays busy).  Every slice stores a copy of
+  // its result; the copies are added up in slice order afterwards.
+  const bool small = H <= 64;
+  int tps;
+  if (small) {
+    const int target = L->cus / 2 < 1 ? 1 : L->cus / 2;
+    tps = (int)((n_tiles + target - 1) / target);
+  } else {
+    tps = (int)((n_tiles + L->cus - 1) / L->cus);
+    tps = (tps + 1) / 2 * 2 * 2;
+  }
   while ((n_tiles + tps - 1) / tps > L->part_slices) tps *= 2;
   const unsigned slices = (unsigned)((n_tiles + tps - 1) / tps);
   // the contractions of both networks in two launches: the four with a hidden layer's width of columns,
-  // and the two of the output layers
+  // and the two of the output layers (64 units: all in the first)
   WgradTJobs wide, narrow;
   wide.n = narrow.n = 0;
   Reducer red;
@@ -468,7 +483,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
     const size_t oW1 = off, ob1 = oW1 + (size_t)D * H, oW2 = ob1 + H, ob2 = oW2 + (size_t)H * H, oW3 = ob2 + H,
                  ob3 = oW3 + (size_t)H * O;
     auto wg = [&](const void* A, int UA, int M, const void* B, int UB, int N, size_t oC, int64_t ldc, size_t obias) {
-      WgradTArgs& g = N <= 32 ? narrow.job[narrow.n++] : wide.job[wide.n++];
+      WgradTArgs& g = N <= 32 && !small ? narrow.job[narrow.n++] : wide.job[wide.n++];
       memset(&g, 0, sizeof(g));
       g.A = (const __bf16*)A; g.B = (const __bf16*)B; g.UA = UA; g.UB = UB; g.M = M; g.N = N; g.m_out = M;
       g.n_tiles = n_tiles; g.tiles_per_slice = tps; g.C = L->part + oC; g.ldc = ldc; g.bias = L->part + obias;
@@ -481,10 +496,13 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
     wg(L->xt, 16 * kt1, D, b.dzt[0], H, H, oW1, H, ob1);
     off += net_count(D, H, O);
   }
-  if (wide.n) hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices, (unsigned)wide.n), dim3(512), 0, s, wide);
+  if (small)
+    hipLaunchKernelGGL((wgrad_wave_kernel<2, 2, 4, 2>), dim3(slices, (unsigned)wide.n), dim3(256), 0, s, wide);
+  else if (wide.n)
+    hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices, (unsigned)wide.n), dim3(512), 0, s, wide);
   if (narrow.n) hipLaunchKernelGGL((wgrad_tiled_kernel<1, 4>), dim3(slices, (unsigned)narrow.n), dim3(512), 0, s, narrow);
   LTRY(hipGetLastError());
-  LTRY(red.launch(L, grad, s));
+  LTRY(red.launch(L, grad, adam, finish ? L->stats : nullptr, s));  // (the bins are complete: the row kernels ran)
   return MSRL_OK;
 }
 
@@ -510,27 +528,39 @@ int check_learner_args(const char* who, msrl_learner* L, const void* params, int
   return MSRL_OK;
 }
 
+AdamArgs adam_args(float* params, float* m, float* v, int64_t k, const msrl_ppo_cfg* cfg) {
+  AdamArgs a;
+  a.p = params; a.m = m; a.v = v;
+  a.lr = cfg->lr; a.b1 = cfg->beta1; a.b2 = cfg->beta2; a.eps = cfg->adam_eps;
+  a.c1 = (float)(1.0 - pow((double)cfg->beta1, (double)k));
+  a.c2 = (float)(1.0 - pow((double)cfg->beta2, (double)k));
+  return a;
+}
+
 RowSel selection(const msrl_row_select* rows, int64_t row0) {
   return rows ? RowSel{row0, rows->group, rows->first, rows->count} : RowSel{row0, 0, 0, 0};
 }
 
-// the gradient of logical rows [row0, row0 + R) of the selection, into grad
+// the gradient of logical rows [row0, row0 + R) of the selection, into grad; with `adam`, the Adam step on
+// every element follows inside the kernel that finishes the gradient
 int grad_rows(msrl_learner* L, const float* params, int64_t R, int64_t row0, const msrl_row_select* rows,
               const float* obs, const void* actions, const float* logp_old, const float* adv, const float* ret,
-              const msrl_ppo_cfg* cfg, float* grad, hipStream_t s) {
+              const msrl_ppo_cfg* cfg, float* grad, hipStream_t s, const AdamArgs* adam = nullptr) {
   const RowSel sel = selection(rows, row0);
-  if (L->fused) return fused_grad_pass(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s);
+  if (L->fused) return fused_grad_pass(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s, adam);
   if (L->fused_policy) {
     // Centralised critic: the policy network on chip, then the value network (one row per group, a wide
     // first layer) through device memory; it adds its part of grad and of the statistics.  (Running the
     // second pass on a stream of its own beside the first was measured: no gain, the row kernel's
     // workgroups leave no LDS for the value network's kernels to start beside them.)
-    int rc = fused_grad_pass(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s, 1, true, false);
-    if (rc == MSRL_OK) rc = grad_pass<true>(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s, 2, true);
+    // (With an Adam step folded in, each pass steps its own network's parameters: the value network's pass reads
+    // none of the policy network's.)
+    int rc = fused_grad_pass(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s, adam, 1, true, false);
+    if (rc == MSRL_OK) rc = grad_pass<true>(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s, adam, 2, true);
     return rc;
   }
-  return L->bf16 ? grad_pass<true>(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s)
-                 : grad_pass<false>(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s);
+  return L->bf16 ? grad_pass<true>(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s, adam)
+                 : grad_pass<false>(L, params, R, sel, obs, actions, logp_old, adv, ret, cfg, grad, s, adam);
 }
 
 }  // namespace
@@ -680,10 +710,8 @@ int msrl_adam_step(float* params, float* m, float* v, const float* grad, int64_t
   if (!params || !m || !v || !grad || !cfg) return fail(MSRL_EINVAL, "msrl_adam_step: NULL argument");
   if (n < 0 || k < 1) return fail(MSRL_EINVAL, "msrl_adam_step: n must be >= 0 and the step counter >= 1");
   if (n == 0) return MSRL_OK;
-  const float c1 = (float)(1.0 - pow((double)cfg->beta1, (double)k));
-  const float c2 = (float)(1.0 - pow((double)cfg->beta2, (double)k));
-  hipLaunchKernelGGL(adam_kernel, grid1(n), dim3(256), 0, (hipStream_t)hip_stream, params, m, v, grad, n, cfg->lr,
-                     cfg->beta1, cfg->beta2, cfg->adam_eps, c1, c2);
+  const AdamArgs a = adam_args(params, m, v, k, cfg);
+  hipLaunchKernelGGL(adam_kernel, grid1(n), dim3(256), 0, (hipStream_t)hip_stream, a, grad, n);
   LTRY(hipGetLastError());
   return MSRL_OK;
 }
@@ -721,12 +749,15 @@ int msrl_ppo_update(msrl_learner* L, float* params, float* m, float* v, int64_t*
   for (int it = 0; it < iters; ++it)
     for (int b = 0; b < minibatches; ++b) {
       const int64_t r0 = (int64_t)b * block, r1 = b == minibatches - 1 ? R : r0 + block;
-      rc = grad_rows(L, params, r1 - r0, r0, rows, obs, actions, logp_old, adv, ret, cfg, L->grad,
-                     (hipStream_t)hip_stream);
-      if (rc != MSRL_OK) return rc;
+      // the Adam step rides on the kernel that adds up the slices of the gradient
       *step_counter += 1;
-      rc = msrl_adam_step(params, m, v, L->grad, (int64_t)L->n_params, *step_counter, cfg, hip_stream);
-      if (rc != MSRL_OK) return rc;
+      const AdamArgs adam = adam_args(params, m, v, *step_counter, cfg);
+      rc = grad_rows(L, params, r1 - r0, r0, rows, obs, actions, logp_old, adv, ret, cfg, L->grad,
+                     (hipStream_t)hip_stream, &adam);
+      if (rc != MSRL_OK) {
+        *step_counter -= 1;  // nothing was enqueued for this step
+        return rc;
+      }
     }
   return MSRL_OK;
 }
