@@ -328,7 +328,8 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
       red.add(ob(l), H, used);
     }
     // weight gradients: contraction over the rows, split over workgroups; every slice writes a copy of its own
-    int slices = (int)fmax(1.0, fmin(256.0, (double)(Rk / 1024)));
+    // (at least 256 rows per slice, and no more slices than fill the chip about once)
+    int slices = (int)fmax(1.0, fmin(256.0, (double)(Rk / 256)));
     if (slices > L->part_slices) slices = L->part_slices;
     if (H <= 256) {
       LTRY((wgrad<BF16>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, part + oW3, H, O, O, Rk, slices, ps, &used)));
@@ -353,7 +354,7 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
       red.add(oW(0), (size_t)D * H, used);
     }
     {
-      int64_t per_slice = 16384;
+      int64_t per_slice = 2048;
       if ((R + per_slice - 1) / per_slice > L->part_slices) per_slice = (R + L->part_slices - 1) / L->part_slices;
       const unsigned ns = (unsigned)((R + per_slice - 1) / per_slice);
       hipLaunchKernelGGL((rowsum_kernel<E>), dim3((unsigned)O, ns), dim3(256), 0, s, (const E*)b.dyt, (int64_t)O, R, Rp,
