@@ -40,6 +40,12 @@ struct RowsArgs {
   __bf16 *xt, *h1t, *h2t, *dz2t, *dz1t, *dyt;
   float* stats;  // bins as in LossArgs
   RowSel sel;    // where row r of this call lies in obs, actions, logp_old, adv, ret
+  // 64-unit networks: the weight gradients are formed inside the row kernel (no tiled tensors are written);
+  // workgroup b stores its share as copy b (copies part_stride floats apart) of the gradient vector in `part`,
+  // the six tensors of this network at the offsets o*
+  float* part;
+  int64_t part_stride;
+  int32_t oW1, ob1, oW2, ob2, oW3, ob3;
 };
 
 __device__ __forceinline__ uint32_t quad_swap1(uint32_t x) {  // value of lane ^ 1
@@ -89,8 +95,8 @@ struct Stager {
     for (int k = 0; k < K; ++k) ((u32x4*)tile)[at[k]] = v[k];
     wave_lds_sync();
   }
-  // one 32-unit chunk in operand form -> units unit0 .. unit0 + 31 of a tile
-  __device__ __forceinline__ void chunk(__bf16* tile, int U, int unit0, const bf16x8 (&op)[2]) const {
+  // one 32-unit chunk in operand form into the staging area (units 0 .. 31)
+  __device__ __forceinline__ void stage_chunk(const bf16x8 (&op)[2]) const {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const u32x4 w = __builtin_bit_cast(u32x4, op[j]);
@@ -100,21 +106,53 @@ struct Stager {
         stg[(8 * (r / 4) + r % 4) * 4 + w_chain] = trade(w[d]);
       }
     }
+  }
+  // the first 16 units of a chunk (operand 0) into the staging area (units 0 .. 15)
+  __device__ __forceinline__ void stage_half(const bf16x8& op) const {
+    const u32x4 w = __builtin_bit_cast(u32x4, op);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) stg[(8 * (d / 2) + 2 * (d % 2)) * 4 + w_chain] = trade(w[d]);
+  }
+  // 16 observation inputs (one layer-1 operand) into the staging area, units slot0 .. slot0 + 15 (slot0 = 0 or 16)
+  __device__ __forceinline__ void stage_inputs16(const bf16x8& op, int slot0) const {
+    const u32x4 w = __builtin_bit_cast(u32x4, op);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) stg[(2 * d + slot0) * 4 + w_lin] = trade(w[d]);
+  }
+  // one 32-unit chunk in operand form -> units unit0 .. unit0 + 31 of a tile
+  __device__ __forceinline__ void chunk(__bf16* tile, int U, int unit0, const bf16x8 (&op)[2]) const {
+    stage_chunk(op);
     flush<32>(tile, U, unit0);
   }
   // the first 16 units of a chunk (operand 0) -> units 0 .. 15 of a tile with 16 units
   __device__ __forceinline__ void half_chunk(__bf16* tile, const bf16x8& op) const {
-    const u32x4 w = __builtin_bit_cast(u32x4, op);
-#pragma unroll
-    for (int d = 0; d < 4; ++d) stg[(8 * (d / 2) + 2 * (d % 2)) * 4 + w_chain] = trade(w[d]);
+    stage_half(op);
     flush<16>(tile, 16, 0);
   }
   // 16 observation inputs (one layer-1 operand) -> units unit0 .. unit0 + 15 of a tile
   __device__ __forceinline__ void inputs16(__bf16* tile, int U, int unit0, const bf16x8& op) const {
-    const u32x4 w = __builtin_bit_cast(u32x4, op);
-#pragma unroll
-    for (int d = 0; d < 4; ++d) stg[(2 * d) * 4 + w_lin] = trade(w[d]);
+    stage_inputs16(op, 0);
     flush<16>(tile, U, unit0);
+  }
+  // The staged values as operands of a contraction over the rows (the weight gradients): for MFMA step k
+  // (rows 16 k .. 16 k + 15 of the tile) lane (i, h) takes rows 8 (2 k + h) .. + 7 of unit i -- the same 16
+  // bytes a lane of the weight-gradient kernels fetches from a tile in memory.
+  __device__ __forceinline__ void frags32(bf16x8 (&f)[2]) const {
+    wave_lds_sync();
+#pragma unroll
+    for (int k = 0; k < 2; ++k) f[k] = __builtin_bit_cast(bf16x8, *(const u32x4*)(stg + (2 * k + (lane >> 5)) * GS + (lane & 31) * 4));
+    wave_lds_sync();
+  }
+  // ... when only units 0 .. 15 are staged: the lanes of units 16 .. 31 get zero
+  __device__ __forceinline__ void frags16(bf16x8 (&f)[2]) const {
+    wave_lds_sync();
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      u32x4 v = {0, 0, 0, 0};
+      if ((lane & 31) < 16) v = *(const u32x4*)(stg + (2 * k + (lane >> 5)) * GS + (lane & 31) * 4);
+      f[k] = __builtin_bit_cast(bf16x8, v);
+    }
+    wave_lds_sync();
   }
   // The way back, for a chunk the wave wrote earlier: its 2 KiB into registers as they lie in
   // memory (fetch; issued early), then through the staging area into operand form (unstage).
@@ -231,12 +269,14 @@ __device__ __forceinline__ void bwd_chunk(const u32x4* tiles, const bf16x8 (&dz2
   if (PIPE) to_operands<true>(t, dprev);
 }
 
-constexpr int ROWS_WAVES = 8;  // waves per workgroup of the row kernel = row tiles per group
+// waves per workgroup of the row kernel = row tiles per group: eight, two per SIMD; four (one per SIMD, with
+// the whole register file) for 64-unit networks, which keep their weight-gradient tiles in registers
+constexpr int rows_waves(int H) { return H <= 64 ? 4 : 8; }
 constexpr int ROWS_STAT_BINS = 64;  // bins per statistic in RowsArgs::stats (after 8 result slots)
 
 // workgroups of the row kernel that share a compute unit: two for 64-unit networks (their registers are
 // held to 128 per lane for that, and 60 KiB of LDS each leave the room), one above
-constexpr int rows_workgroups_per_cu(int H) { return H <= 64 ? 2 : 1; }
+constexpr int rows_workgroups_per_cu(int H) { return 1; }
 
 template <int H, int KT1, int NET, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVES / 4 * rows_workgroups_per_cu(H))))
@@ -255,12 +295,23 @@ void ppo_rows_kernel(RowsArgs a) {
   // s_waitcnt vmcnt, also waits for every store the wave has in flight - two KiB per row here.)
   constexpr bool RESIDENT = H <= 128;
   constexpr int WBUFS = RESIDENT ? 2 * SPN : NBUF;
+  // 64-unit networks: the weight gradients are formed here too.  What the other widths write as tiles is, on
+  // its way through the staging area, already in the operand form of a contraction over the tile's 32 rows; a
+  // wave keeps those operands (x, h1, h2; then dy, dz2, dz1 as they appear) and adds the products to gradient
+  // tiles it holds for the whole launch: XT x 2 (W1; its rows in_dim, in_dim + 1 meet the constant-1 inputs
+  // and so are the bias gradient), 2 x 2 (W2), 2 (W3), and a ones-row product each for the biases of layers
+  // 2 and 3 -- 11 or 13 tiles of 16 registers, which is why these kernels run one wave per SIMD.  At the end
+  // the waves of a workgroup add their tiles up in wave order and store one copy per workgroup.
+  constexpr bool ONCHIP = H <= 64;
+  constexpr int XT = ONCHIP ? KT1 / 2 : 1;  // 32-unit tiles of the observation operand
+  static_assert(!ONCHIP || (KT1 % 2 == 0 && NUC == 2 && WAVES >= 2), "two layer-1 operands per 32-unit tile; 64 hidden units");
 
   __shared__ __attribute__((aligned(16))) u32x4 s_l1[Net::L1_TILES * 64];
   __shared__ __attribute__((aligned(16))) u32x4 s_w3t[NUC * 64];
   __shared__ __attribute__((aligned(16))) u32x4 s_w[WBUFS * Stream::BUF_SLOTS];
   __shared__ __attribute__((aligned(16))) float s_b3[32];
   __shared__ __attribute__((aligned(16))) uint32_t s_stg[WAVES][Stager::WORDS];
+  __shared__ float s_red[ONCHIP ? (WAVES - 1) * 16 * 64 : 1];  // the other waves' copy of one gradient tile
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -292,6 +343,25 @@ void ppo_rows_kernel(RowsArgs a) {
   if constexpr (RESIDENT) ws.wait_all(); else __syncthreads();
 
   float st[5] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f};  // per-lane sums: policy term, value term, entropy, clipped, kl
+  // ONCHIP: gradient tiles (C[m][n]: register r of lane (i, h) <-> m = 8 (r / 4) + 4 h + r % 4, n = i) ...
+  f32x16 gW1[XT][2], gW2[2][2], gW3[2], gB2[2], gB3;
+  // ... and the operands kept from the forward pass
+  bf16x8 fx[XT][2], fh1[2][2], fh2[2][2];
+  Op h2keep[ONCHIP ? KT2 : 1];  // layer-2 activations in chained operand form (the other widths read them back)
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+  if constexpr (ONCHIP) {
+    gB3 = zero16();
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      gW3[c] = gB2[c] = zero16();
+#pragma unroll
+      for (int m = 0; m < 2; ++m) gW2[m][c] = zero16();
+#pragma unroll
+      for (int m = 0; m < XT; ++m) gW1[m][c] = zero16();
+    }
+  }
   int gs = 0;  // stages consumed so far: stage gs sits in buffer gs % WBUFS
   const int64_t groups = (a.n_tiles + WAVES - 1) / WAVES;
   // copies of stage `next` into buffer `nbuf`, spread over the tile loops of the current stage
@@ -301,46 +371,97 @@ void ppo_rows_kernel(RowsArgs a) {
     for (int i = 0; i < Stream::PER_WAVE; ++i)
       if (i * (CPS * KT2) / Stream::PER_WAVE == c * KT2 + kt) ws.issue_part(next, nbuf, i);
   };
+  // ONCHIP: chunk c of dL/dz1 (operand form) times the observation operands -> W1's gradient tiles
+  auto dz1_product = [&](int c, const Op (&dz)[2]) {
+    bf16x8 fdz[2];
+    sg.stage_chunk(dz);
+    sg.frags32(fdz);
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+      for (int m = 0; m < XT; ++m) {
+        if (c == 0) gW1[m][0] = mma(fx[m][k], fdz[k], gW1[m][0]);
+        else gW1[m][1] = mma(fx[m][k], fdz[k], gW1[m][1]);
+      }
+  };
+  // What a tile reads per row: this lane's 8 observation inputs of every layer-1 operand and the inputs of
+  // the loss; zeros for rows beyond the end.  ONCHIP kernels (one wave per SIMD, nothing to cover a load's
+  // latency with) fetch them one tile ahead where the registers allow (two layer-1 operands).
+  constexpr bool AHEAD = ONCHIP && KT1 <= 2;
+  struct RowInputs {
+    f32x8 f[KT1];
+    int act;
+    float lpo, adv, ret;
+  };
+  auto load_rows = [&](int64_t grp) -> RowInputs {
+    RowInputs in;
+    const int64_t row = (grp * WAVES + wave) * 32 + n;
+    const bool valid = grp < groups && row < a.R;
+    const int64_t prow = valid ? a.sel.at(row) : 0;  // the row inside the caller's arrays
+    in.act = 0;
+    in.lpo = in.adv = in.ret = 0.0f;
+    if (valid) {
+      if constexpr (NET == 0) {
+        in.act = ((const int32_t*)a.actions)[prow];
+        in.lpo = a.logp_old[prow];
+        in.adv = a.adv[prow];
+      } else {
+        in.ret = a.ret[prow];
+      }
+    }
+#pragma unroll
+    for (int kt = 0; kt < KT1; ++kt) {
+      const int i0 = 16 * kt + 8 * h;
+      if (valid && a.obs_vec4 && i0 + 8 <= a.D) {
+        const f32x4 u = *(const f32x4*)(a.obs + prow * a.D + i0), w = *(const f32x4*)(a.obs + prow * a.D + i0 + 4);
+        in.f[kt] = f32x8{u[0], u[1], u[2], u[3], w[0], w[1], w[2], w[3]};
+      } else {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) in.f[kt][s] = (valid && i0 + s < a.D) ? a.obs[prow * a.D + i0 + s] : 0.0f;
+      }
+    }
+    return in;
+  };
+  RowInputs ahead;
+  if constexpr (AHEAD) ahead = load_rows(blockIdx.x);
 #pragma unroll 1
   for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
     const int64_t tile = grp * WAVES + wave;
     const bool live = tile < a.n_tiles;  // uniform over the wave
     const int64_t row = tile * 32 + n;
     const bool valid = live && row < a.R;
-    const int64_t prow = valid ? a.sel.at(row) : 0;  // the row inside the caller's arrays
     if constexpr (!RESIDENT) ws.wait_oldest();  // forward stage 0 is in; every wave has left the previous tile
-    // per-row inputs of the loss, fetched early
-    int act = 0;
-    float lpo = 0.0f, adv = 0.0f, ret = 0.0f;
-    if (valid) {
-      if constexpr (NET == 0) {
-        act = ((const int32_t*)a.actions)[prow];
-        lpo = a.logp_old[prow];
-        adv = a.adv[prow];
-      } else {
-        ret = a.ret[prow];
-      }
+    RowInputs in;
+    if constexpr (AHEAD) {
+      in = ahead;
+      ahead = load_rows(grp + gridDim.x);
+    } else {
+      in = load_rows(grp);
     }
+    const int act = in.act;
+    const float lpo = in.lpo, adv = in.adv, ret = in.ret;
 
     // ---------------- observation row -> layer-1 operands (inputs D and D + 1 carry the two bias parts)
     Op x[1][KT1];
 #pragma unroll
     for (int kt = 0; kt < KT1; ++kt) {
-      f32x8 f;
+      f32x8 f = in.f[kt];
       const int i0 = 16 * kt + 8 * h;
-      if (valid && a.obs_vec4 && i0 + 8 <= a.D) {
-        const f32x4 u = *(const f32x4*)(a.obs + prow * a.D + i0), w = *(const f32x4*)(a.obs + prow * a.D + i0 + 4);
-        f = f32x8{u[0], u[1], u[2], u[3], w[0], w[1], w[2], w[3]};
-      } else {
-#pragma unroll
-        for (int s = 0; s < 8; ++s) f[s] = (valid && i0 + s < a.D) ? a.obs[prow * a.D + i0 + s] : 0.0f;
-      }
 #pragma unroll
       for (int s = 0; s < 8; ++s)
         if (i0 + s == a.D || i0 + s == a.D + 1) f[s] = 1.0f;
       x[0][kt] = __builtin_convertvector(f, bf16x8);
     }
-    if (NET == 0 && live) {
+    if constexpr (ONCHIP) {
+      if (live) {
+#pragma unroll
+        for (int m = 0; m < XT; ++m) {
+          sg.stage_inputs16(x[0][2 * m], 0);
+          sg.stage_inputs16(x[0][2 * m + 1], 16);
+          sg.frags32(fx[m]);
+        }
+      }
+    } else if (NET == 0 && live) {
       __bf16* xt = a.xt + (size_t)tile * (16 * KT1) * 32;
 #pragma unroll
       for (int kt = 0; kt < KT1; ++kt) sg.inputs16(xt, 16 * KT1, 16 * kt, x[0][kt]);
@@ -360,7 +481,12 @@ void ppo_rows_kernel(RowsArgs a) {
 #pragma unroll
         for (int c = 0; c < NUC; ++c) {
           const Op pr[2] = {h1[0][2 * c], h1[0][2 * c + 1]};
-          sg.chunk(t1, H, 32 * c, pr);
+          if constexpr (ONCHIP) {
+            sg.stage_chunk(pr);
+            sg.frags32(fh1[c]);
+          } else {
+            sg.chunk(t1, H, 32 * c, pr);
+          }
         }
       }
       f32x16 acc = zero16();
@@ -380,7 +506,17 @@ void ppo_rows_kernel(RowsArgs a) {
             fwd_chunk<Net, false>(tiles, h1, acc, out, h, hn, tick);
           } else {
             fwd_chunk<Net, true>(tiles, h1, acc, out, h, hn, tick);
-            if (live) sg.chunk(t2, H, 32 * (sc * CPS + c - 1), hn);
+            if constexpr (ONCHIP) {
+              // (64 units: one stage of two chunks, so this is chunk 0, finished while chunk 1 was summed)
+              h2keep[0] = hn[0];
+              h2keep[1] = hn[1];
+              if (live) {
+                sg.stage_chunk(hn);
+                sg.frags32(fh2[0]);
+              }
+            } else {
+              if (live) sg.chunk(t2, H, 32 * (sc * CPS + c - 1), hn);
+            }
           }
         }
         ++gs;
@@ -395,7 +531,16 @@ void ppo_rows_kernel(RowsArgs a) {
 #pragma unroll
         for (int i = 0; i < TPC; ++i)
           out = mma(__builtin_bit_cast(bf16x8, tiles[(Net::L3_OWN + i) * 64]), hl[i], out);
-        if (live) sg.chunk(t2, H, 32 * (NUC - 1), hl);
+        if constexpr (ONCHIP) {
+          h2keep[2] = hl[0];
+          h2keep[3] = hl[1];
+          if (live) {
+            sg.stage_chunk(hl);
+            sg.frags32(fh2[1]);
+          }
+        } else {
+          if (live) sg.chunk(t2, H, 32 * (NUC - 1), hl);
+        }
       }
     }
 
@@ -454,19 +599,40 @@ void ppo_rows_kernel(RowsArgs a) {
     }
     Op dyo[2];
     to_operands<true>(dyr, dyo);
-    if (live) sg.half_chunk(a.dyt + (size_t)tile * 16 * 32, dyo[0]);
+    if constexpr (ONCHIP) {
+      if (live) {
+        bf16x8 fdy[2];
+        sg.stage_half(dyo[0]);
+        sg.frags16(fdy);
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+#pragma unroll
+          for (int m = 0; m < 2; ++m) gW3[m] = mma(fh2[m][k], fdy[k], gW3[m]);
+          gB3 = mma(ones, fdy[k], gB3);
+        }
+      }
+    } else {
+      if (live) sg.half_chunk(a.dyt + (size_t)tile * 16 * 32, dyo[0]);
+    }
 
     // ---------------- dL/dz2 = (W3 dy) * (1 - h2^2), chunk by chunk
     Op dz2[KT2];
     {
       __bf16* tz2 = a.dz2t + (size_t)tile * H * 32;
       u32x4 raw[2] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
-      if (live) sg.fetch(t2, H, 0, raw);
+      if constexpr (!ONCHIP) {
+        if (live) sg.fetch(t2, H, 0, raw);
+      }
 #pragma unroll
       for (int c = 0; c < NUC; ++c) {
         Op hp[2];
-        sg.unstage(raw, hp);
-        if (live && c + 1 < NUC) sg.fetch(t2, H, 32 * (c + 1), raw);
+        if constexpr (ONCHIP) {
+          hp[0] = h2keep[2 * c];
+          hp[1] = h2keep[2 * c + 1];
+        } else {
+          sg.unstage(raw, hp);
+          if (live && c + 1 < NUC) sg.fetch(t2, H, 32 * (c + 1), raw);
+        }
         const f32x16 g = mma(__builtin_bit_cast(bf16x8, s_w3t[c * 64 + lane]), dyo[0], zero16());
         float t[16];
         dtanh_range(g, hp, t, 0, 16, false);
@@ -474,7 +640,21 @@ void ppo_rows_kernel(RowsArgs a) {
         to_operands<true>(t, dz);
         dz2[2 * c] = dz[0];
         dz2[2 * c + 1] = dz[1];
-        if (live) sg.chunk(tz2, H, 32 * c, dz);
+        if constexpr (ONCHIP) {
+          if (live) {
+            bf16x8 fdz[2];
+            sg.stage_chunk(dz);
+            sg.frags32(fdz);
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+#pragma unroll
+              for (int m = 0; m < 2; ++m) gW2[m][c] = mma(fh1[m][k], fdz[k], gW2[m][c]);
+              gB2[c] = mma(ones, fdz[k], gB2[c]);
+            }
+          }
+        } else {
+          if (live) sg.chunk(tz2, H, 32 * c, dz);
+        }
       }
     }
 
@@ -499,7 +679,11 @@ void ppo_rows_kernel(RowsArgs a) {
             bwd_chunk<Net, false>(tiles, dz2, acc, hp, dz, tick);
           } else {
             bwd_chunk<Net, true>(tiles, dz2, acc, hp, dz, tick);
-            if (live) sg.chunk(tz1, H, 32 * (chunk - 1), dz);
+            if constexpr (ONCHIP) {
+              if (live) dz1_product(0, dz);  // (one stage of two chunks: this is chunk 0)
+            } else {
+              if (live) sg.chunk(tz1, H, 32 * (chunk - 1), dz);
+            }
           }
           // activations of this chunk, for the epilogue that runs during the next one (register indices
           // are compile-time constants inside each branch)
@@ -517,9 +701,70 @@ void ppo_rows_kernel(RowsArgs a) {
         dtanh_range(acc, hp, t, 0, 16, false);
         Op dz[2];
         to_operands<true>(t, dz);
-        if (live) sg.chunk(tz1, H, 32 * (NUC - 1), dz);
+        if constexpr (ONCHIP) {
+          if (live) dz1_product(NUC - 1, dz);
+        } else {
+          if (live) sg.chunk(tz1, H, 32 * (NUC - 1), dz);
+        }
       }
     }
+  }
+  if constexpr (ONCHIP) {
+    // The waves' tiles are added in wave order (through LDS, a tile at a time) and wave 0 stores the sum as
+    // this workgroup's copy: tile (mt, nt) of a tensor holds C[32 mt + m][32 nt + i], m as above.
+    const int64_t copy = (int64_t)blockIdx.x * a.part_stride;
+    auto reduce_tile = [&](f32x16& g) {
+      __syncthreads();  // the tile before has been read
+      if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_red[((wave - 1) * 16 + r) * 64 + lane] = g[r];
+      }
+      __syncthreads();
+      if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < WAVES - 1; ++w)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) g[r] += s_red[(w * 16 + r) * 64 + lane];
+      }
+    };
+    // rows m < M of C into a row-major tensor at offset oC with `ldc` columns, of which N are in use
+    auto store_tile = [&](const f32x16& g, int mt, int nt, int M, int N, int32_t oC, int ldc) {
+      const int nn = 32 * nt + n;
+      if (wave != 0 || nn >= N) return;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = 32 * mt + 8 * (r / 4) + 4 * h + r % 4;
+        if (m < M) a.part[copy + oC + (int64_t)m * ldc + nn] = g[r];
+      }
+    };
+    // row `row` of C (a bias gradient) into a vector at offset ob
+    auto store_row = [&](const f32x16& g, int mt, int nt, int row, int N, int32_t ob) {
+      const int nn = 32 * nt + n;
+      if (wave != 0 || nn >= N) return;
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (32 * mt + 8 * (r / 4) + 4 * h + r % 4 == row) a.part[copy + ob + nn] = g[r];
+    };
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+#pragma unroll
+      for (int m = 0; m < XT; ++m) {
+        reduce_tile(gW1[m][c]);
+        store_tile(gW1[m][c], m, c, a.D, H, a.oW1, H);
+        store_row(gW1[m][c], m, c, a.D, H, a.ob1);  // the constant-1 input at index D: the sum over the rows
+      }
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {
+        reduce_tile(gW2[m][c]);
+        store_tile(gW2[m][c], m, c, H, H, a.oW2, H);
+      }
+      reduce_tile(gB2[c]);
+      store_row(gB2[c], 0, c, 0, H, a.ob2);  // every row of a ones-product is the sum over the rows
+      reduce_tile(gW3[c]);
+      store_tile(gW3[c], c, 0, H, O, a.oW3, O);
+    }
+    reduce_tile(gB3);
+    store_row(gB3, 0, 0, 0, O, a.ob3);
   }
   if constexpr (!RESIDENT) ws.wait_all();  // the copy issued ahead for a tile that does not exist
 
@@ -541,10 +786,10 @@ hipError_t launch_ppo_rows_h256(int kt1, int net, const RowsArgs& a, unsigned gr
 
 #define MSRL_ROWS_LAUNCHER(HID)                                                                             \
   hipError_t launch_ppo_rows_h##HID(int kt1, int net, const RowsArgs& a, unsigned grid, hipStream_t s) {    \
-    if (kt1 == 2 && net == 0) hipLaunchKernelGGL((ppo_rows_kernel<HID, 2, 0, ROWS_WAVES>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, a);      \
-    else if (kt1 == 2) hipLaunchKernelGGL((ppo_rows_kernel<HID, 2, 1, ROWS_WAVES>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, a);    \
-    else if (kt1 == 4 && net == 0) hipLaunchKernelGGL((ppo_rows_kernel<HID, 4, 0, ROWS_WAVES>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, a); \
-    else if (kt1 == 4) hipLaunchKernelGGL((ppo_rows_kernel<HID, 4, 1, ROWS_WAVES>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, a);    \
+    if (kt1 == 2 && net == 0) hipLaunchKernelGGL((ppo_rows_kernel<HID, 2, 0, rows_waves(HID)>), dim3(grid), dim3(64 * rows_waves(HID)), 0, s, a);      \
+    else if (kt1 == 2) hipLaunchKernelGGL((ppo_rows_kernel<HID, 2, 1, rows_waves(HID)>), dim3(grid), dim3(64 * rows_waves(HID)), 0, s, a);    \
+    else if (kt1 == 4 && net == 0) hipLaunchKernelGGL((ppo_rows_kernel<HID, 4, 0, rows_waves(HID)>), dim3(grid), dim3(64 * rows_waves(HID)), 0, s, a); \
+    else if (kt1 == 4) hipLaunchKernelGGL((ppo_rows_kernel<HID, 4, 1, rows_waves(HID)>), dim3(grid), dim3(64 * rows_waves(HID)), 0, s, a);    \
     else return hipErrorInvalidValue;                                                                       \
     return hipGetLastError();                                                                               \
   }

@@ -557,42 +557,52 @@ __device__ __forceinline__ void stats_reduce(float* stats) {
 }
 
 // ---------------------------------------------------------------- sum of the slices' gradients
-// grad[j.offset + i] = sum_{s < j.slices} part[s * slice_stride + j.offset + i], s ascending, for every
-// job j (one per parameter tensor: the kernels above split a tensor's contraction over a number of
-// slices of its own).  The order of the additions is fixed, so a gradient is the same bits every time.
-// With `adam.p` set the Adam step of each element follows at once; with `stats` set one more workgroup
-// (the last) adds up the bins of the loss statistics.
-constexpr int REDUCE_MAX_JOBS = 40;
+// grad[j.offset + i] = sum_{s < j.slices} part[s * slice_stride + j.offset + i] for every job j (one per
+// parameter tensor: the kernels above split a tensor's contraction over a number of slices of its own).
+// A workgroup takes REDUCE_ELEMS consecutive elements of a job, one per lane; wave w of its four adds the
+// slices [w n / 4, (w + 1) n / 4) in ascending order (four chains, so that several loads are in flight),
+// and the waves' sums are joined in wave order.  The order of the additions is fixed, so a gradient is the
+// same bits every time.  With `adam.p` set the Adam step of each element follows at once; with `stats` set
+// one more workgroup (the last) adds up the bins of the loss statistics.
+constexpr int REDUCE_MAX_JOBS = 40, REDUCE_ELEMS = 64;
 struct ReduceJobs {
   int32_t offset[REDUCE_MAX_JOBS];  // first float of the tensor in the parameter vector
   int32_t count[REDUCE_MAX_JOBS];
   int32_t slices[REDUCE_MAX_JOBS];
-  int32_t first_block[REDUCE_MAX_JOBS + 1];  // prefix sums of ceil(count / 256): block -> job
+  int32_t first_block[REDUCE_MAX_JOBS + 1];  // prefix sums of ceil(count / REDUCE_ELEMS): block -> job
   int32_t jobs;
 };
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* part, int64_t slice_stride, ReduceJobs j,
                                                               float* grad, AdamArgs adam, float* stats) {
+  __shared__ float s_sum[3][REDUCE_ELEMS];
   if ((int)blockIdx.x >= j.first_block[j.jobs]) {
     if (stats) stats_reduce(stats);
     return;
   }
   int q = 0;
   while (q + 1 < j.jobs && (int)blockIdx.x >= j.first_block[q + 1]) ++q;
-  const int i = ((int)blockIdx.x - j.first_block[q]) * 256 + (int)threadIdx.x;
-  if (i >= j.count[q]) return;
-  const float* p = part + j.offset[q] + i;
-  // four chains keep several loads in flight; they are joined in a fixed order
-  float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i = ((int)blockIdx.x - j.first_block[q]) * REDUCE_ELEMS + lane;
+  const bool live = i < j.count[q];
   const int n = j.slices[q];
-  int s = 0;
-  for (; s + 4 <= n; s += 4) {
-    s0 += p[(int64_t)(s + 0) * slice_stride];
-    s1 += p[(int64_t)(s + 1) * slice_stride];
-    s2 += p[(int64_t)(s + 2) * slice_stride];
-    s3 += p[(int64_t)(s + 3) * slice_stride];
+  const int s_begin = wave * n / 4, s_end = (wave + 1) * n / 4;
+  float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+  if (live) {
+    const float* p = part + j.offset[q] + i;
+    int s = s_begin;
+    for (; s + 4 <= s_end; s += 4) {
+      s0 += p[(int64_t)(s + 0) * slice_stride];
+      s1 += p[(int64_t)(s + 1) * slice_stride];
+      s2 += p[(int64_t)(s + 2) * slice_stride];
+      s3 += p[(int64_t)(s + 3) * slice_stride];
+    }
+    for (; s < s_end; ++s) s0 += p[(int64_t)s * slice_stride];
   }
-  for (; s < n; ++s) s0 += p[(int64_t)s * slice_stride];
-  const float gi = (s0 + s1) + (s2 + s3);
+  const float mine = (s0 + s1) + (s2 + s3);
+  if (wave > 0) s_sum[wave - 1][lane] = mine;
+  __syncthreads();
+  if (wave != 0 || !live) return;
+  const float gi = ((mine + s_sum[0][lane]) + s_sum[1][lane]) + s_sum[2][lane];
   grad[j.offset[q] + i] = gi;
   if (adam.p) adam_update(adam, j.offset[q] + i, gi);
 }

@@ -197,7 +197,7 @@ struct Reducer {
     j.count[j.jobs] = (int32_t)count;
     j.slices[j.jobs] = slices;
     j.first_block[j.jobs] = blocks;
-    blocks += (int)((count + 255) / 256);
+    blocks += (int)((count + REDUCE_ELEMS - 1) / REDUCE_ELEMS);
     j.first_block[++j.jobs] = blocks;
   }
   // adam: the step to apply to what is summed, or null; stats: bins to add up on the way, or null
@@ -430,14 +430,30 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
     LTRY(hipGetLastError());
   }
   const int64_t n_tiles = (R + 31) / 32;
-  const int64_t groups = (n_tiles + ROWS_WAVES - 1) / ROWS_WAVES;
+  const int64_t groups = (n_tiles + rows_waves(H) - 1) / rows_waves(H);
   const int64_t resident = (int64_t)L->cus * rows_workgroups_per_cu(H);
   const unsigned grid = (unsigned)(groups < resident ? groups : resident);
+  // 64-unit networks: the row kernel forms the weight gradients itself, one copy per workgroup
+  const bool small = H <= 64;
+  Reducer red;
+  size_t off = 0;
   for (int n = 0; n < 2; ++n) {
+    const int O = n == 0 ? L->pol.out_dim : 1;
+    const size_t oW1 = off, ob1 = oW1 + (size_t)D * H, oW2 = ob1 + H, ob2 = oW2 + (size_t)H * H, oW3 = ob2 + H,
+                 ob3 = oW3 + (size_t)H * O;
+    off += net_count(D, H, O);
     if (!((nets >> n) & 1)) continue;
     NetBufs& b = L->net[n];
     RowsArgs a;
     memset(&a, 0, sizeof(a));
+    if (small) {
+      a.part = L->part; a.part_stride = L->part_stride;
+      a.oW1 = (int32_t)oW1; a.ob1 = (int32_t)ob1; a.oW2 = (int32_t)oW2; a.ob2 = (int32_t)ob2; a.oW3 = (int32_t)oW3;
+      a.ob3 = (int32_t)ob3;
+      const size_t offs[6] = {oW1, ob1, oW2, ob2, oW3, ob3};
+      const size_t counts[6] = {(size_t)D * H, (size_t)H, (size_t)H * H, (size_t)H, (size_t)H * O, (size_t)O};
+      for (int q = 0; q < 6; ++q) red.add(offs[q], counts[q], (int)grid);
+    }
     a.packed = L->fpacked + (size_t)n * 2 * ly.bytes;
     a.b3 = b3p[n];
     a.obs = obs; a.actions = actions; a.logp_old = logp_old; a.adv = adv; a.ret = ret;
@@ -454,29 +470,22 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
     LTRY(e);
   }
   LTRY(hipGetLastError());
-  size_t off = 0;
-  // Slices of row tiles.  Networks of 64 units: the waves of a workgroup split a slice's tiles and every
-  // wave holds a whole result (wgrad_wave_kernel), all six contractions in one launch, about half as many
-  // slices as compute units (x 6 jobs: three workgroups of four waves per compute unit).  Wider ones: two
-  // compute units' share per slice, i.e. half as many workgroups per contraction as compute units (the six
-  // contractions of a pass run two launches deep, so the chip stays busy).  Every slice stores a copy of
-  // its result; the copies are added up in slice order afterwards.
-  const bool small = H <= 64;
-  int tps;
   if (small) {
-    const int target = L->cus / 2 < 1 ? 1 : L->cus / 2;
-    tps = (int)((n_tiles + target - 1) / target);
-  } else {
-    tps = (int)((n_tiles + L->cus - 1) / L->cus);
-    tps = (tps + 1) / 2 * 2 * 2;
+    LTRY(red.launch(L, grad, adam, finish ? L->stats : nullptr, s));
+    return MSRL_OK;
   }
+  off = 0;
+  // Slices of row tiles: two compute units' share per slice, i.e. half as many workgroups per contraction as
+  // compute units (the six contractions of a pass run two launches deep, so the chip stays busy).  Every
+  // slice stores a copy of its result; the copies are added up in slice order afterwards.
+  int tps = (int)((n_tiles + L->cus - 1) / L->cus);
+  tps = (tps + 1) / 2 * 2 * 2;
   while ((n_tiles + tps - 1) / tps > L->part_slices) tps *= 2;
   const unsigned slices = (unsigned)((n_tiles + tps - 1) / tps);
   // the contractions of both networks in two launches: the four with a hidden layer's width of columns,
-  // and the two of the output layers (64 units: all in the first)
+  // and the two of the output layers
   WgradTJobs wide, narrow;
   wide.n = narrow.n = 0;
-  Reducer red;
   for (int n = 0; n < 2; ++n) {
     if (!((nets >> n) & 1)) continue;  // (the value network, behind the policy network's gradient)
     NetBufs& b = L->net[n];
@@ -484,7 +493,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
     const size_t oW1 = off, ob1 = oW1 + (size_t)D * H, oW2 = ob1 + H, ob2 = oW2 + (size_t)H * H, oW3 = ob2 + H,
                  ob3 = oW3 + (size_t)H * O;
     auto wg = [&](const void* A, int UA, int M, const void* B, int UB, int N, size_t oC, int64_t ldc, size_t obias) {
-      WgradTArgs& g = N <= 32 && !small ? narrow.job[narrow.n++] : wide.job[wide.n++];
+      WgradTArgs& g = N <= 32 ? narrow.job[narrow.n++] : wide.job[wide.n++];
       memset(&g, 0, sizeof(g));
       g.A = (const __bf16*)A; g.B = (const __bf16*)B; g.UA = UA; g.UB = UB; g.M = M; g.N = N; g.m_out = M;
       g.n_tiles = n_tiles; g.tiles_per_slice = tps; g.C = L->part + oC; g.ldc = ldc; g.bias = L->part + obias;
@@ -497,9 +506,7 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
     wg(L->xt, 16 * kt1, D, b.dzt[0], H, H, oW1, H, ob1);
     off += net_count(D, H, O);
   }
-  if (small)
-    hipLaunchKernelGGL((wgrad_wave_kernel<2, 2, 4, 2>), dim3(slices, (unsigned)wide.n), dim3(256), 0, s, wide);
-  else if (wide.n)
+  if (wide.n)
     hipLaunchKernelGGL((wgrad_tiled_kernel<8, 2>), dim3(slices, (unsigned)wide.n), dim3(512), 0, s, wide);
   if (narrow.n) hipLaunchKernelGGL((wgrad_tiled_kernel<1, 4>), dim3(slices, (unsigned)narrow.n), dim3(512), 0, s, narrow);
   LTRY(hipGetLastError());
