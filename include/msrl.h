@@ -101,11 +101,13 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   (msrl_observe / msrl_act / msrl_env_step) and the snapshot calls; not by
  *   msrl_measure_phase.
  *   Kernels are compiled for every (num_chasers, runners) with at most 8
- *   agents per env, 0 .. 4 landmarks (never more than agents), bf16 networks
- *   of 64 hidden units and two hidden layers (the four networks stay in LDS);
+ *   agents per env, 0 .. 4 landmarks (never more than agents), networks of 64
+ *   hidden units and two hidden layers, bf16 or - except for the largest
+ *   shapes - fp32 (the four networks stay in LDS: 160 KiB must hold them);
  *   anything else is MSRL_EUNSUPPORTED.
  *   The kernel has two workgroup shapes with identical results (one or four
- *   tiles of 32 envs; four only with at most 4 agents per env); tag_tiles = 0
+ *   tiles of 32 envs; four only with at most 4 agents per env and bf16
+ *   networks); tag_tiles = 0
  *   lets msrl_rollout_init pick by num_envs, 1 or 4 fixes the shape (EINVAL
  *   for any other value, for 4 with more than 4 agents, and for a non-zero
  *   value with another env kind).

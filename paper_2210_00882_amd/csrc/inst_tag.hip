@@ -15,23 +15,23 @@ const std::vector<TagEntry>& tag_kernels() {
   return table;
 }
 
-const TagEntry* find_tag(int nc, int nr, int landmarks, int hidden, int tiles, int phase) {
+const TagEntry* find_tag(int nc, int nr, int landmarks, int hidden, bool bf16, int tiles, int phase) {
   for (const TagEntry& k : tag_kernels())
-    if (k.nc == nc && k.nr == nr && k.landmarks == landmarks && k.hidden == hidden && k.tiles == tiles &&
-        k.phase == phase)
+    if (k.nc == nc && k.nr == nr && k.landmarks == landmarks && k.hidden == hidden && (k.bf16 != 0) == bf16 &&
+        k.tiles == tiles && k.phase == phase)
       return &k;
   return nullptr;
 }
 }  // namespace
 
-bool tag_rollout_compiled(int nc, int nr, int landmarks, int hidden, int tiles) {
-  return find_tag(nc, nr, landmarks, hidden, tiles, TAG_ALL) != nullptr;
+bool tag_rollout_compiled(int nc, int nr, int landmarks, int hidden, bool bf16, int tiles) {
+  return find_tag(nc, nr, landmarks, hidden, bf16, tiles, TAG_ALL) != nullptr;
 }
 
-hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, int tiles, int phase, const TagArgs& a,
-                              hipStream_t stream) {
+hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, bool bf16, int tiles, int phase,
+                              const TagArgs& a, hipStream_t stream) {
   if (phase == TAG_ACT || phase == TAG_STEP) tiles = 1;
-  const TagEntry* k = find_tag(nc, nr, landmarks, hidden, tiles, phase);
+  const TagEntry* k = find_tag(nc, nr, landmarks, hidden, bf16, tiles, phase);
   if (!k) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)((a.E + 32 * tiles - 1) / (32 * tiles));
   TagArgs args = a;

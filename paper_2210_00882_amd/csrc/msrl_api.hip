@@ -378,8 +378,8 @@ int enqueue_tag(msrl_state* st, const void* params, int32_t T, msrl_traj* out, h
   a.M = (int64_t)e.num_envs * e.num_agents;
   a.obs_in = obs_in;
   a.actions_in = (const int32_t*)actions_in;
-  HIP_TRY(launch_tag_rollout(e.num_chasers, e.num_agents - e.num_chasers, e.num_landmarks, st->pol.hidden, st->tag_tiles,
-                             phase, a, stream));
+  HIP_TRY(launch_tag_rollout(e.num_chasers, e.num_agents - e.num_chasers, e.num_landmarks, st->pol.hidden,
+                             st->pol.dtype == MSRL_BF16, st->tag_tiles, phase, a, stream));
   return MSRL_OK;
 }
 
@@ -420,9 +420,10 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
   found.envs_per_wave = 32;
   found.waves = 1;
   const bool ok = env->kind == MSRL_ENV_TAG
-                      ? policy->dtype == MSRL_BF16 && layers_of(*policy) == 2 &&
+                      ? layers_of(*policy) == 2 &&
                             tag_rollout_compiled(env->num_chasers, env->num_agents - env->num_chasers,
-                                                 env->num_landmarks, policy->hidden)
+                                                 env->num_landmarks, policy->hidden, policy->dtype == MSRL_BF16,
+                                                 env->tag_tiles == 4 ? 4 : 1)
                       : find_kernel(*env, *policy, PHASE_ALL, &found);
   if (!ok)
     return fail(MSRL_EUNSUPPORTED,
@@ -457,6 +458,10 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
   }
   // Pursuit env: tiles of 32 envs per workgroup (msrl_env_cfg.tag_tiles, 0 = chosen here).
   st->tag_tiles = env->tag_tiles != 0 ? env->tag_tiles : choose_tag_tiles(env->num_envs, env->num_agents, cus);
+  if (env->kind == MSRL_ENV_TAG && st->tag_tiles == 4 &&
+      !tag_rollout_compiled(env->num_chasers, env->num_agents - env->num_chasers, env->num_landmarks, policy->hidden,
+                            policy->dtype == MSRL_BF16, 4))
+    st->tag_tiles = 1;  // (fp32 networks: one tile per workgroup only)
   st->state_size = (int)msrl_env_state_size(env);
   // The particle observation ends in 2 (N - 1) slots that are always zero: layer 1 skips them.
   st->in_used = env->kind == MSRL_ENV_PARTICLE ? 4 * env->num_agents + 2 : policy->in_dim;

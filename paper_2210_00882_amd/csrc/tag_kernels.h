@@ -50,16 +50,27 @@ struct TagArgs {
 //             T = 0 it only writes the observation of the current state.  No network runs.
 enum : int { TAG_ALL = 0, TAG_ACT = 1, TAG_STEP = 2 };
 
-template <int NC, int NR, int L, int H, int TILES = 1, int PHASE = TAG_ALL>
+// layer-1 tiles of an observation of D features (+ the constant-1 input that carries the bias): 16 inputs
+// per bf16 tile, 8 per fp32 tile
+constexpr int tag_kt1(int D, bool bf16) { return bf16 ? (D + 1 + 15) / 16 : (D + 1 + 7) / 8; }
+// LDS of a workgroup: the four resident networks, their output biases, the state tables of its tiles
+constexpr int tag_lds_bytes(int N, int L, int H, bool bf16, int tiles) {
+  const int kt1 = tag_kt1(4 + 2 * L + 4 * (N - 1), bf16), nuc = H / 32, kt2 = bf16 ? H / 16 : H / 8;
+  const int net_tiles = nuc * kt1 + nuc * (kt2 + 1 + kt2 / nuc);
+  return 4 * net_tiles * 1024 + 4 * 32 * 4 + tiles * (2 * 2 * 32 * N * 8 + 2 * 32 * (L > 0 ? L : 1) * 8 + 32 * N * 8 + 32 * N * 4);
+}
+
+template <int NC, int NR, int L, int H, bool BF16 = true, int TILES = 1, int PHASE = TAG_ALL>
 __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(TagArgs a) {
   constexpr int N = NC + NR;
   constexpr bool ACT = PHASE == TAG_ACT, STEP = PHASE == TAG_STEP;
   static_assert(64 * N * TILES <= 1024, "one wave per tile and agent slot");
   constexpr int D = 4 + 2 * L + 4 * (N - 1);
   constexpr int S = 4 * N + 2 * L;
-  constexpr int KT1 = (D + 1 + 15) / 16;  // + the constant-1 input that carries the bias
-  typedef Mlp<H, true, 1, KT1> Net;
+  constexpr int KT1 = tag_kt1(D, BF16);
+  typedef Mlp<H, BF16, 1, KT1> Net;
   typedef typename Net::Op Op;
+  constexpr int PT = Net::PT;
   // Resident image of a network: its layer-1 tiles, then per 32-unit chunk the layer-2 tiles, the
   // bias tile and the layer-3 tiles the chunk feeds (the second copy of the layer-3 tiles that the
   // streaming kernels keep in the following block is left out: 72 KiB for the four networks, so
@@ -89,7 +100,7 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
   float2(&s_pm)[32][N] = t_pm[tile];
   float(&s_cnt)[32][N] = t_cnt[tile];
   const int role = j < NC ? 0 : 1;
-  const NetLayout ly = net_layout(D, H, true);
+  const NetLayout ly = net_layout(D, H, BF16);
   for (int net = 0; net < (STEP ? 0 : 4); ++net) {
     const u32x4* src = (const u32x4*)(a.packed + (size_t)net * ly.bytes + ly.w1);
     for (int i = threadIdx.x; i < NET_TILES * 64; i += blockDim.x) {
@@ -155,12 +166,39 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
         return vel ? (idx % 2 ? w.y : w.x) : (idx % 2 ? w.y - p.y : w.x - p.x);
       }
     };
-    Op x[1][KT1];
+    Op x[1][KT1 * PT];
     // (TAG_STEP stores one observation, that of the last state, to step slot 0, and runs no network)
     float* const orow = a.obs + ((size_t)(STEP ? 0 : t) * a.M + (size_t)env * N + j) * D;
     const bool observe = !STEP || t == a.T;
+    if constexpr (!BF16) {
+      // fp32 operands: operand mm of the layer-1 contraction is feature 2 mm + h (one k step of two inputs per
+      // MFMA); the lane with h = mm % 2 stores the pair (2 mm, 2 mm + 1) of the observation row
+      auto pair_at = [&](auto MM) {
+        constexpr int mm = decltype(MM)::value;
+        if constexpr (mm < KT1 * 4) {
+          const float lo = feature(std::integral_constant<int, 2 * mm>{});
+          const float hi = feature(std::integral_constant<int, 2 * mm + 1>{});
+          x[0][mm] = h ? hi : lo;
+          if (valid && !ACT && 2 * mm + 2 <= D && h == (mm & 1)) *(f32x2*)(orow + 2 * mm) = f32x2{lo, hi};
+        }
+      };
+      auto pairs8 = [&](auto B) {
+        constexpr int b = decltype(B)::value;
+        pair_at(std::integral_constant<int, b>{}); pair_at(std::integral_constant<int, b + 1>{});
+        pair_at(std::integral_constant<int, b + 2>{}); pair_at(std::integral_constant<int, b + 3>{});
+        pair_at(std::integral_constant<int, b + 4>{}); pair_at(std::integral_constant<int, b + 5>{});
+        pair_at(std::integral_constant<int, b + 6>{}); pair_at(std::integral_constant<int, b + 7>{});
+      };
+      static_assert(KT1 * 4 <= 32, "layer-1 operands of the observation");
+      if (observe) {
+        pairs8(std::integral_constant<int, 0>{});
+        pairs8(std::integral_constant<int, 8>{});
+        pairs8(std::integral_constant<int, 16>{});
+        pairs8(std::integral_constant<int, 24>{});
+      }
+    }
 #pragma unroll
-    for (int kt = 0; kt < KT1; ++kt) {
+    for (int kt = 0; kt < (BF16 ? KT1 : 0); ++kt) {
       if (!observe) break;
       f32x8 f;
       auto fill = [&](auto KT, auto S8) {
@@ -175,7 +213,7 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
         fill(KT, std::integral_constant<int, 4>{}); fill(KT, std::integral_constant<int, 5>{});
         fill(KT, std::integral_constant<int, 6>{}); fill(KT, std::integral_constant<int, 7>{});
       };
-      static_assert(KT1 <= 4, "layer-1 tiles of the observation");
+      static_assert(!BF16 || KT1 <= 4, "layer-1 tiles of the observation");
       if (kt == 0) fill_all(std::integral_constant<int, 0>{});
       if (kt == 1) fill_all(std::integral_constant<int, 1>{});
       if (kt == 2) fill_all(std::integral_constant<int, 2>{});
@@ -195,7 +233,7 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
           }
         }
       }
-      x[0][kt] = __builtin_convertvector(f, bf16x8);
+      if constexpr (BF16) x[0][kt] = __builtin_convertvector(f, bf16x8);
     }
 
     // ---------------- networks of this wave's role, from the resident images
@@ -205,7 +243,7 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
     for (int net = 0; net < (STEP ? 0 : 2); ++net) {
       f32x16(&out)[1] = net == 0 ? out_p : out_v;
       const u32x4* base = &s_net[2 * role + net][0] + lane;
-      Op h1[1][Net::KT2];
+      Op h1[1][Net::KT2 * PT];
       Net::layer1(base, x, h1);
       out[0] = bias_init(s_b3[2 * role + net], h);
       // layer 2 chunk by chunk; the tanh of chunk c-1 and its layer-3 MFMAs run among those of chunk c
@@ -220,19 +258,19 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
           for (int kt = 0; kt < Net::KT2; ++kt) {
             u32x4 raw = blk[kt * 64];
             if (c > 0) pin(raw);
-            acc = mma(__builtin_bit_cast(bf16x8, raw), h1[0][kt], acc);
+            mma_tile<BF16>(raw, &h1[0][kt * PT], acc);
             if (c > 0) tanh_range(prev, tt, kt * 16 / Net::KT2, (kt + 1) * 16 / Net::KT2, true);
           }
-          acc = mma(__builtin_bit_cast(bf16x8, blk[Net::KT2 * 64]), Operand<true>::one(h), acc);
+          mma_bias_tile<BF16>(blk[Net::KT2 * 64], Operand<BF16>::one(h), acc);
         } else {
           tanh_range(prev, tt, 0, 16, false);
         }
         if (c > 0) {
-          Op h2[2];
-          to_operands<true>(tt, h2);
+          Op h2[Net::PC];
+          to_operands<BF16>(tt, h2);
           const u32x4* l3 = base + (Net::L1_TILES + (c - 1) * BLOCK + Net::KT2 + 1) * 64;
 #pragma unroll
-          for (int i = 0; i < Net::TPC; ++i) out[0] = mma(__builtin_bit_cast(bf16x8, l3[i * 64]), h2[i], out[0]);
+          for (int i = 0; i < Net::TPC; ++i) mma_tile<BF16>(l3[i * 64], &h2[i * PT], out[0]);
         }
         prev = acc;
       }
@@ -361,22 +399,32 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
 }
 
 // ---- the compiled instances, by construction: every (chasers, runners) with at most 8 agents in all and
-// up to 4 landmarks (never more than agents), 64 hidden units; per shape the full rollout with one env tile
-// per workgroup and, while 4 tiles x agents fit the 16 waves of a workgroup, with four; the actor fragment;
-// the env step.
+// up to 4 landmarks (never more than agents), 64 hidden units, bf16 networks and - where the four networks
+// still fit the LDS at twice the size - fp32 ones; per shape the full rollout with one env tile per workgroup
+// and (bf16), while 4 tiles x agents fit the 16 waves of a workgroup, with four; the actor fragment; the env
+// step.
 struct TagEntry {
-  int nc, nr, landmarks, hidden, tiles, phase;
+  int nc, nr, landmarks, hidden, bf16, tiles, phase;
   const void* fn;  // __global__ void (*)(TagArgs)
 };
 constexpr int TAG_MAX_AGENTS = 8, TAG_MAX_LANDMARKS = 4;
 
+template <int NC, int NR, int L, bool BF16>
+void add_tag_shape_typed(std::vector<TagEntry>& out) {
+  // (fp32 networks are twice the size: the four of them must still fit the 160 KiB of LDS)
+  if constexpr (tag_lds_bytes(NC + NR, L, 64, BF16, 1) <= 160 * 1024) {
+    const int b = BF16 ? 1 : 0;
+    out.push_back(TagEntry{NC, NR, L, 64, b, 1, TAG_ALL, (const void*)&tag_rollout_kernel<NC, NR, L, 64, BF16, 1, TAG_ALL>});
+    out.push_back(TagEntry{NC, NR, L, 64, b, 1, TAG_ACT, (const void*)&tag_rollout_kernel<NC, NR, L, 64, BF16, 1, TAG_ACT>});
+    out.push_back(TagEntry{NC, NR, L, 64, b, 1, TAG_STEP, (const void*)&tag_rollout_kernel<NC, NR, L, 64, BF16, 1, TAG_STEP>});
+    if constexpr (BF16 && 4 * (NC + NR) <= 16)
+      out.push_back(TagEntry{NC, NR, L, 64, b, 4, TAG_ALL, (const void*)&tag_rollout_kernel<NC, NR, L, 64, BF16, 4, TAG_ALL>});
+  }
+}
 template <int NC, int NR, int L>
 void add_tag_shape(std::vector<TagEntry>& out) {
-  out.push_back(TagEntry{NC, NR, L, 64, 1, TAG_ALL, (const void*)&tag_rollout_kernel<NC, NR, L, 64, 1, TAG_ALL>});
-  out.push_back(TagEntry{NC, NR, L, 64, 1, TAG_ACT, (const void*)&tag_rollout_kernel<NC, NR, L, 64, 1, TAG_ACT>});
-  out.push_back(TagEntry{NC, NR, L, 64, 1, TAG_STEP, (const void*)&tag_rollout_kernel<NC, NR, L, 64, 1, TAG_STEP>});
-  if constexpr (4 * (NC + NR) <= 16)
-    out.push_back(TagEntry{NC, NR, L, 64, 4, TAG_ALL, (const void*)&tag_rollout_kernel<NC, NR, L, 64, 4, TAG_ALL>});
+  add_tag_shape_typed<NC, NR, L, true>(out);
+  add_tag_shape_typed<NC, NR, L, false>(out);
 }
 template <int NC, int NR, int L = 0>
 void add_tag_landmarks(std::vector<TagEntry>& out) {
@@ -402,8 +450,8 @@ MSRL_TAG_FAMILIES(MSRL_DECLARE_TAG_FAMILY)
 
 // launcher of the compiled instances; returns hipErrorInvalidValue when no instance matches.
 // tiles: env tiles per workgroup, 1 or 4 (the step-granular variants always take 1); phase: TAG_*.
-hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, int tiles, int phase, const TagArgs& a,
-                              hipStream_t stream);
-bool tag_rollout_compiled(int nc, int nr, int landmarks, int hidden, int tiles = 1);
+hipError_t launch_tag_rollout(int nc, int nr, int landmarks, int hidden, bool bf16, int tiles, int phase,
+                              const TagArgs& a, hipStream_t stream);
+bool tag_rollout_compiled(int nc, int nr, int landmarks, int hidden, bool bf16, int tiles = 1);
 
 }  // namespace msrl

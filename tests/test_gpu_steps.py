@@ -18,7 +18,7 @@ def setup_any(cfg):
     """oracle_setup for every env kind (the pursuit env has no entry there)."""
     if cfg.kind == synth.TAG:
         from test_gpu_tag import tag_env
-        pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
+        pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=cfg.dtype == synth.BF16)
         return tag_env(cfg), pol, synth.make_params(cfg, bias_std=0.1).astype(np.float64), None
     return oracle_setup(cfg)
 
@@ -91,6 +91,7 @@ ACT_CASES = {
     # pursuit env (the task of the GPU-only experiment, section 7.3): one parameter set per role
     "tag_3_1": lambda: synth.tag("tag", 70, 3, 1, 2, 64, 6, 3, idx=50).with_(radius_c=0.3, radius_r=0.25),
     "tag_2_2": lambda: synth.tag("tag", 41, 2, 2, 1, 64, 6, 3, idx=51).with_(radius_c=0.3, radius_r=0.25),
+    "tag_2_3_f32": lambda: synth.tag("tag", 37, 2, 3, 2, 64, 6, 3, dtype=synth.F32, idx=52).with_(radius_c=0.3, radius_r=0.25),
 }
 
 

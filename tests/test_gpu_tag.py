@@ -39,6 +39,7 @@ def state_from_obs(cfg, rows):
 def check(cfg, tr, env, pol, params, env_ids, g0, T):
     N = cfg.num_agents
     n_role = pol.param_count
+    TOL_NET = TOL_BF16 if cfg.dtype == synth.BF16 else TOL_F32
     stats = {"rows": 0, "action_edge": 0, "contact_edge": 0, "contacts": 0}
     for k, e in enumerate(env_ids):
         rows = slice(e * N, (e + 1) * N)
@@ -51,9 +52,9 @@ def check(cfg, tr, env, pol, params, env_ids, g0, T):
                 m = e * N + i
                 prm = params[:n_role] if i < cfg.num_chasers else params[n_role:]
                 lg, v = ref.policy_value(pol, prm, o_gpu[i])
-                assert_close(tr["values"][t, m], v, TOL_BF16, f"value env {e} agent {i} t {t}")
+                assert_close(tr["values"][t, m], v, TOL_NET, f"value env {e} agent {i} t {t}")
                 if t < T:
-                    assert_close(tr["logits"][t, m], lg, TOL_BF16, f"logits env {e} agent {i} t {t}")
+                    assert_close(tr["logits"][t, m], lg, TOL_NET, f"logits env {e} agent {i} t {t}")
             if t == T:
                 break
             acts = []
@@ -95,11 +96,30 @@ def test_tag_shapes_off_the_benchmark(nc, nr, L, tiles):
     tag_parity(nc, nr, L, tiles, 45, 8, 10)
 
 
-def tag_parity(nc, nr, L, tiles, E, T, min_contacts):
+@pytest.mark.parametrize("nc,nr,L", [(3, 1, 2), (1, 1, 0), (2, 2, 1), (4, 3, 4), (1, 6, 2), (5, 1, 0)])
+def test_tag_with_fp32_networks(nc, nr, L):
+    # fp32 networks (twice the LDS: compiled where the four of them still fit, i.e. all but the largest shapes),
+    # to the fp32 tolerance
+    tag_parity(nc, nr, L, 0, 45, 8, 10, dtype=synth.F32)
+
+
+def test_tag_fp32_shapes_that_do_not_fit():
+    from paper_2210_00882_amd import binding as B
+    big = synth.tag("tagbig", 8, 4, 4, 4, 64, 4, 4, dtype=synth.F32)     # four fp32 networks of 41 inputs: 169 KB
+    with pytest.raises(B.MsrlError) as e:
+        B.msrl_rollout_init(B.make_env_cfg(big, None, None)[0], B.make_policy_cfg(big), 1)
+    assert e.value.code == B.MSRL_EUNSUPPORTED
+    four = synth.tag("tag4", 8, 3, 1, 2, 64, 4, 4, dtype=synth.F32)      # four tiles per workgroup: bf16 only
+    with pytest.raises(B.MsrlError) as e:
+        B.msrl_rollout_init(B.make_env_cfg(four, None, None, tag_tiles=4)[0], B.make_policy_cfg(four), 1)
+    assert e.value.code == B.MSRL_EUNSUPPORTED
+
+
+def tag_parity(nc, nr, L, tiles, E, T, min_contacts, dtype=synth.BF16):
     # big bodies, so that contact forces and contact rewards occur in most steps
-    cfg = synth.tag("tag", E, nc, nr, L, 64, T, 7, idx=50 + nc).with_(radius_c=0.3, radius_r=0.25)
+    cfg = synth.tag("tag", E, nc, nr, L, 64, T, 7, dtype=dtype, idx=50 + nc).with_(radius_c=0.3, radius_r=0.25)
     env = tag_env(cfg)
-    pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=True)
+    pol = ref.Policy(cfg.obs_dim, cfg.hidden, 5, bf16=dtype == synth.BF16)
     params = synth.make_params(cfg, bias_std=0.1).astype(np.float64)
     assert params.size == 2 * pol.param_count
     with GpuRollout(cfg, params.astype(np.float32), SEED, tag_tiles=tiles) as gpu:
