@@ -168,12 +168,13 @@ typedef struct {
  * values[t, m] then holds that value on every row of the env.  W1 of the value
  * network is [value_in_dim, hidden].  Supported by msrl_rollout_step /
  * msrl_rollout_gae and the step-granular calls on the particle env with
- * bfloat16 networks of two hidden layers (msrl_act then takes the joint
- * observation of an env from the rows the caller gives for its agents);
- * kernels are compiled for 64 hidden units with 2 .. 10 agents per env, 128
+ * networks of two hidden layers (msrl_act then takes the joint observation of
+ * an env from the rows the caller gives for its agents); kernels are compiled
+ * for bfloat16 networks of 64 hidden units with 2 .. 10 agents per env, 128
  * with 4 .. 10 and 256 with 7 .. 10 (the envs of a workgroup must fit the 32
- * columns of the critic's tile), anything else is MSRL_EUNSUPPORTED; and by
- * the learner (any multiple
+ * columns of the critic's tile), and for fp32 networks of 64 units with
+ * 2 .. 8 and 128 with 4 .. 8 agents; anything else is MSRL_EUNSUPPORTED; and
+ * by the learner (any multiple
  * G of in_dim: the value network then reads groups of G consecutive rows, see
  * msrl_ppo_grad).
  */

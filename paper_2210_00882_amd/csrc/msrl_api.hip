@@ -406,9 +406,9 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
   }
   if (central_of(*policy) &&
       (env->kind != MSRL_ENV_PARTICLE || policy->value_in_dim != env->num_agents * policy->in_dim ||
-       policy->dtype != MSRL_BF16 || layers_of(*policy) != 2))
+       layers_of(*policy) != 2))
     return fail(MSRL_EINVAL, "%s: value_in_dim %d: a centralised critic takes num_agents * in_dim = %d "
-                             "inputs (particle env, bfloat16 networks, two hidden layers)",
+                             "inputs (particle env, two hidden layers)",
                 who, policy->value_in_dim, env->num_agents * policy->in_dim);
   if (env->tag_tiles != 0 && (env->kind != MSRL_ENV_TAG || (env->tag_tiles != 1 && env->tag_tiles != 4) ||
                               (env->tag_tiles == 4 && env->num_agents > 4)))
@@ -469,7 +469,11 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
   st->layout = net_layout(st->in_used, policy->hidden, policy->dtype == MSRL_BF16, layers_of(*policy));
   st->central = central_of(*policy);
   // (joint observation: num_agents blocks of whole layer-1 tiles, see pack_params)
-  st->critic_layout = net_layout(env->num_agents * tiles_for_inputs(st->in_used + 1, true) * 16 - 1, policy->hidden, true);
+  {
+    const bool bf16 = policy->dtype == MSRL_BF16;
+    st->critic_layout = net_layout(env->num_agents * tiles_for_inputs(st->in_used + 1, bf16) * (bf16 ? 16 : 8) - 1,
+                                   policy->hidden, bf16);
+  }
   // (behind a centralised critic's image: the memory its kernel's tile fetches may read past the end)
   *packed_bytes = st->central ? st->layout.bytes + st->critic_layout.bytes + (size_t)CRITIC_FETCH_PAD_TILES * 1024
                               : n_nets * st->layout.bytes;

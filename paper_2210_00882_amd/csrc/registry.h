@@ -51,10 +51,14 @@ constexpr int particle_waves(int H, bool bf16, int phase) {
 // 256 units x 4 bytes each) stay in LDS beside the two-stage window; beyond 7 agents they exceed 160 KB
 constexpr bool particle_fits(int N, int H, bool bf16) { return bf16 || H < 256 || N <= 7; }
 
-// Centralised critic (bf16 networks): one wave per 32-unit chunk of the hidden layers, and the envs of a
-// workgroup (waves x floor(32 / N)) are the at most 32 columns of the critic's tile: 64 units from 2
-// agents per env, 128 from 4, 256 from 7.
-constexpr bool particle_central_fits(int N, int H, bool bf16) { return bf16 && N >= 2 && (H / 32) * (32 / N) <= 32; }
+// Centralised critic: one wave per 32-unit chunk of the hidden layers, and the envs of a workgroup
+// (waves x floor(32 / N)) are the at most 32 columns of the critic's tile: 64 units from 2 agents per env,
+// 128 from 4, 256 from 7.  fp32 networks: 64 and 128 units with at most 8 agents per env (the joint
+// observation, twice as many tiles, and the fp32 window must fit the LDS; the critic's ring of tile registers
+// grows with the agents).
+constexpr bool particle_central_fits(int N, int H, bool bf16) {
+  return N >= 2 && (H / 32) * (32 / N) <= 32 && (bf16 || (H <= 128 && N <= 8));
+}
 
 template <int N, int H, bool BF16, int PHASE>
 KernelEntry particle_entry() {

@@ -158,7 +158,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   static_assert(EPW >= 1, "a wave must hold at least one env");
   constexpr bool DEEP = PHASE == PHASE_DEEP || PHASE == PHASE_ACT_DEEP;
   constexpr bool FULL = (PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS || DEEP || CENTRAL) && !ACT;
-  static_assert(!CENTRAL || (BF16 && WAVES == Net::NUC), "centralised critic: bf16, one wave per 32-unit chunk");
+  static_assert(!CENTRAL || WAVES == Net::NUC, "centralised critic: one wave per 32-unit chunk");
   // The joint observation is laid out as one block of KT1 tiles per agent, the agent's row exactly as the
   // policy's layer 1 takes it (its constant 1 at input NZ included: agent 0's carries the critic's bias).
   constexpr int KT1C = N * KT1;
@@ -220,7 +220,8 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   ws.wave = wave;
   ws.lane = lane;
   if constexpr (DEEP) ws.stages_per_net = (layers - 1) * Stream::STAGES_PER_NET;
-  const NetLayout lyc = net_layout(KT1C * 16 - 1, H, true);  // the critic's image (PHASE_CENTRAL): KT1C layer-1 tiles
+  // the critic's image (PHASE_CENTRAL): KT1C layer-1 tiles of 16 (bf16) or 8 (fp32) inputs
+  const NetLayout lyc = net_layout(KT1C * (BF16 ? 16 : 8) - 1, H, BF16);
   if constexpr (HAS_NETS) {
 #pragma unroll
     for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
@@ -382,30 +383,52 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   f32x16 cacc = zero16();
   u32x4 cring[RING];
   // layer-2 tile kt of the chunk times the layer-1 outputs in s_hc (the bias tile times the constant 1)
+  // (a tile of B operands in LDS is 16 bytes per lane for both types: one bf16 operand or the four fp32 ones)
+  auto lds_operands = [&](const u32x4& raw, Op (&b)[Net::PT]) {
+    if constexpr (BF16) {
+      b[0] = __builtin_bit_cast(bf16x8, raw);
+    } else {
+      const f32x4 f = __builtin_bit_cast(f32x4, raw);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) b[i] = f[i];
+    }
+  };
   auto critic_l2_tile = [&](const u32x4& w, int kt, f32x16& c) {
-    const bf16x8 b = kt < Net::KT2 ? __builtin_bit_cast(bf16x8, s_hc[kt * 64 + lane]) : Operand<true>::one(h);
-    c = mma(__builtin_bit_cast(bf16x8, w), b, c);
+    if (kt < Net::KT2) {
+      Op b[Net::PT];
+      lds_operands(s_hc[kt * 64 + lane], b);
+      mma_tile<BF16>(w, b, c);
+    } else {
+      mma_bias_tile<BF16>(w, Operand<BF16>::one(h), c);
+    }
   };
   // tanh of the chunk's layer-2 sums and the output layer: the chunk's share of the value of column lane % 32
   auto critic_l3 = [&](const f32x16& c) {
     float tt[16];
-    bf16x8 h2c[2];
+    Op h2c[Net::PC];
     tanh_range(c, tt, 0, 16, false);
-    to_operands<true>(tt, h2c);
+    to_operands<BF16>(tt, h2c);
     f32x16 ov = zero16();
 #pragma unroll
-    for (int i = 0; i < Net::TPC; ++i)
-      ov = mma(__builtin_bit_cast(bf16x8, s_w3c[(wave * Net::TPC + i) * 64 + lane]), h2c[i], ov);
+    for (int i = 0; i < Net::TPC; ++i) mma_tile<BF16>(s_w3c[(wave * Net::TPC + i) * 64 + lane], &h2c[i * Net::PT], ov);
     if (h == 0) s_vpart[wave][n] = ov[0];  // output 0: register 0 of the h = 0 lanes
   };
   // tanh of the chunk's layer-1 sums; outputs (as the next layer's operand tiles) to s_hc
   auto critic_l1_publish = [&](const f32x16& c) {
     float tt[16];
-    bf16x8 hc[2];
+    Op hc[Net::PC];
     tanh_range(c, tt, 0, 16, false);
-    to_operands<true>(tt, hc);
-    s_hc[(2 * wave) * 64 + lane] = __builtin_bit_cast(u32x4, hc[0]);
-    s_hc[(2 * wave + 1) * 64 + lane] = __builtin_bit_cast(u32x4, hc[1]);
+    to_operands<BF16>(tt, hc);
+    // the chunk's 32 units are TPC tiles of the next layer's contraction
+#pragma unroll
+    for (int i = 0; i < Net::TPC; ++i) {
+      u32x4 raw;
+      if constexpr (BF16)
+        raw = __builtin_bit_cast(u32x4, hc[i]);
+      else
+        raw = __builtin_bit_cast(u32x4, f32x4{hc[4 * i], hc[4 * i + 1], hc[4 * i + 2], hc[4 * i + 3]});
+      s_hc[(Net::TPC * wave + i) * 64 + lane] = raw;
+    }
   };
   // value of the rows' envs from the shares in s_vpart
   auto collect_values = [&]() {
@@ -500,6 +523,15 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           if ((mm & 1) == 1 && h == 1) pr[mm / 2] = o;
           x[q][mm] = h ? o.y : o.x;
           if (2 * mm == NZ) x[q][mm] = h ? 0.0f : 1.0f;  // input NZ carries the bias
+        }
+        if constexpr (CENTRAL) {
+          // the same operands, four to a tile, are the agent's block of column (env) `col` of the joint observation
+          if (valid[q]) {
+            u32x4* dst = s_j + (ag[q] * KT1) * 64 + h * 32 + wave * EPW + base[q] / N;
+#pragma unroll
+            for (int kt = 0; kt < KT1; ++kt)
+              dst[kt * 64] = __builtin_bit_cast(u32x4, f32x4{x[q][4 * kt], x[q][4 * kt + 1], x[q][4 * kt + 2], x[q][4 * kt + 3]});
+          }
         }
       }
       // feature index of pr[i]
@@ -702,8 +734,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 #pragma unroll
             for (int i = 0; i < RING; ++i) {
               const int kt = (sc - S2) * RING + i;
-              if (kt < KT1C)
-                cacc = mma(__builtin_bit_cast(bf16x8, cring[i]), __builtin_bit_cast(bf16x8, s_j[kt * 64 + lane]), cacc);
+              if (kt < KT1C) {
+                Op b[Net::PT];
+                lds_operands(s_j[kt * 64 + lane], b);
+                mma_tile<BF16>(cring[i], b, cacc);
+              }
             }
           }
           {

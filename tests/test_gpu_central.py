@@ -39,10 +39,21 @@ def test_central_critic_shapes_off_the_benchmark(N, H):
     _values_shared_per_env(cfg, tr)
 
 
+@pytest.mark.parametrize("N,H", [(2, 64), (3, 64), (5, 64), (8, 64), (4, 128), (6, 128), (8, 128)])
+def test_central_critic_with_fp32_networks(N, H):
+    # fp32 networks: 64 and 128 units, up to 8 agents per env; to the fp32 tolerance
+    cfg = synth.particle(f"central{N}_{H}f", 50, N, H, 9, 4, dtype=synth.F32, idx=90 + N).with_(central_critic=True)
+    tr, stats = run_and_check(cfg, 9, calls=2)
+    assert stats["mlp_rows"] == 2 * 10 * cfg.M
+    _values_shared_per_env(cfg, tr)
+
+
 def test_central_critic_shapes_that_do_not_fit():
     from paper_2210_00882_amd import binding as B
-    for N, H in [(3, 128), (6, 256), (2, 256)]:   # more envs per workgroup than the 32 columns of the critic's tile
-        cfg = synth.particle("c", 8, N, H, 4, 4, dtype=synth.BF16, idx=1).with_(central_critic=True)
+    shapes = [(3, 128, synth.BF16), (6, 256, synth.BF16), (2, 256, synth.BF16),   # more envs per workgroup than the 32 columns of the critic's tile
+              (9, 64, synth.F32), (9, 128, synth.F32), (7, 256, synth.F32)]       # fp32: the LDS, the ring of tile registers
+    for N, H, dt in shapes:
+        cfg = synth.particle("c", 8, N, H, 4, 4, dtype=dt, idx=1).with_(central_critic=True)
         with pytest.raises(B.MsrlError) as e:
             B.msrl_rollout_init(B.make_env_cfg(cfg, None, None)[0], B.make_policy_cfg(cfg), 1)
         assert e.value.code == B.MSRL_EUNSUPPORTED
@@ -94,8 +105,8 @@ def test_central_critic_error_paths():
     pc = B.make_policy_cfg(cfg)
     assert B.msrl_param_count(pc) == cfg.param_count
     env_cfg, keep = B.make_env_cfg(cfg, None, None)
-    # fp32 networks, a width that is not N * in_dim, more than two hidden layers: refused
-    for bad in (cfg.with_(dtype=synth.F32), cfg.with_(hidden_layers=3)):
+    # more than two hidden layers: refused
+    for bad in (cfg.with_(hidden_layers=3),):
         with pytest.raises(B.MsrlError):
             B.msrl_rollout_init(env_cfg, B.make_policy_cfg(bad), 1)
     pc_bad = B.make_policy_cfg(cfg)

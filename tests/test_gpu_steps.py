@@ -88,6 +88,7 @@ ACT_CASES = {
     # centralised critic (section 2.1): the value network on the joint observation of the env's agents
     "n3_bf16_central": lambda: synth.particle("p3c", 45, 3, 64, 6, 3, synth.BF16, 16).with_(central_critic=True),
     "n10_bf16_central": lambda: synth.CONFIGS[5].with_(num_envs=50, episode_len=3, central_critic=True),
+    "n3_f32_central": lambda: synth.CONFIGS[1].with_(num_envs=45, episode_len=3, central_critic=True),
     # pursuit env (the task of the GPU-only experiment, section 7.3): one parameter set per role
     "tag_3_1": lambda: synth.tag("tag", 70, 3, 1, 2, 64, 6, 3, idx=50).with_(radius_c=0.3, radius_r=0.25),
     "tag_2_2": lambda: synth.tag("tag", 41, 2, 2, 1, 64, 6, 3, idx=51).with_(radius_c=0.3, radius_r=0.25),
