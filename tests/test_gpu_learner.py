@@ -69,6 +69,9 @@ CASES = {
     "cfg5_bf16_7_layers": (synth.CONFIGS[5].with_(hidden_layers=7), 131),
     "cfg5_bf16_many_tiles": (synth.CONFIGS[5], 32 * 4 * 5 + 17),
     "p6_bf16_h128": (synth.particle("p6b", 8, 6, 128, 4, 4, synth.BF16, 12), 150),
+    # 64 units with more than 30 inputs: the on-chip weight gradients with two tiles of observation inputs
+    "p6_bf16_h64": (synth.particle("p6c", 8, 6, 64, 4, 4, synth.BF16, 14), 32 * 9 + 5),
+    "p10_bf16_h64": (synth.particle("p10c", 8, 10, 64, 4, 4, synth.BF16, 15), 217),
     # the same bf16 networks through the kernels that keep the activations in device memory
     "p3_bf16_unfused": (synth.particle("p3b", 8, 3, 64, 4, 4, synth.BF16, 12), 300),
     "cfg5_bf16_unfused": (synth.CONFIGS[5], 259),
