@@ -289,6 +289,17 @@ def main():
             phases["learner_grad"] = {"bound": "mfma", "ms_per_call": ms, "rows": rows, "achieved": tf,
                                       "peak": PEAK_TFLOPS[dt_name], "unit": "TFLOP/s", "frac": tf / PEAK_TFLOPS[dt_name],
                                       "rows_per_s": rows / (ms * 1e-3)}
+            if cfg.dtype == synth.BF16 and cfg.hidden > 64 and cfg.dist == synth.CATEGORICAL:
+                # What the on-chip path moves through HBM per row by design (bf16 tiles, both networks): x once,
+                # h1, h2, dz2, dz1, dy per network, each written by the row kernel and read by the weight
+                # gradients, h2 read once more by the row kernel; the observation row and the loss inputs per network.
+                H, D = cfg.hidden, cfg.obs_dim
+                kt1 = 2 if D + 2 <= 32 else 4
+                tiles_b = 2 * (4 * H * 2 + 32) + 16 * kt1 * 2
+                per_row = 2 * tiles_b + 2 * H * 2 + 2 * (4 * D + 12)
+                gbs = per_row * rows / (ms * 1e-3) / 1e9
+                phases["learner_grad"]["hbm"] = {"bytes_per_call": per_row * rows, "achieved": gbs, "peak": PEAK_HBM_GBS,
+                                                 "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
             del master, grad
         except B.MsrlError:
             pass
