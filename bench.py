@@ -479,7 +479,10 @@ def main():
                 split[names[i]] = float(mean[i] - prev)
                 prev = float(mean[i])
             phases["clocks"] = {"unit": "shader-clock cycles, mean over the 8 waves of workgroup 0, step T/2",
-                                "step_total": prev, "split": split}
+                                "step_total": prev, "split": split,
+                                # of which: in the waits at the ten stage barriers of the step (copies landed + barrier)
+                                "stage_barrier_waits": float(mean[20]),
+                                "stage_barrier_waits_per_wave": [float(x) for x in c[:, 20]]}
         except B.MsrlError:
             pass  # variant not compiled for this configuration
 

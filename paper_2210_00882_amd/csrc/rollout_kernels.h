@@ -131,7 +131,8 @@ enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHAS
 // stage barrier that precedes it), policy stage s done (s < 5), same for the value network,
 // logits and values ready, sampling and move done, end of the step
 enum : int { CLK_START = 0, CLK_OBS = 1, CLK_P_L1 = 2, CLK_P_STAGE = 3, CLK_V_L1 = 8, CLK_V_STAGE = 9,
-             CLK_NETS = 14, CLK_SAMPLE = 15, CLK_END = 16, CLK_COUNT = 17 };
+             CLK_NETS = 14, CLK_SAMPLE = 15, CLK_END = 16, CLK_COUNT = 17,
+             CLK_WAIT = 20 };  // slot 20: cycles of the step spent in the waits at the stage barriers
 
 // ------------------------------------------------------------------ particle env
 template <int N, int H, bool BF16, int NB, int WAVES, int PHASE = PHASE_ALL>
@@ -455,6 +456,17 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       }
     };
     stamp(CLK_START);
+    // PHASE_CLOCKS: the wait for a stage (copies landed + workgroup barrier), timed
+    long long clk_wait = 0;
+    auto stage_wait = [&]() {
+      if constexpr (PHASE == PHASE_CLOCKS) {
+        const long long w0 = clock64();
+        ws.wait_oldest();
+        clk_wait += clock64() - w0;
+      } else {
+        ws.wait_oldest();
+      }
+    };
     if constexpr (CENTRAL || DEEP) {
       // The compiler moves every address and constant that does not change over the steps in front of
       // the loop; with the registers of these variants on top they no longer fit and would be reloaded from
@@ -471,7 +483,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       // The barrier of the policy network's first stage comes first in the step: its copies went out
       // during the last stage of the step before, and the wait for them also waits for every store
       // the wave still has in flight, so it must not sit behind the observation stores below.
-      ws.wait_oldest();
+      stage_wait();
       if constexpr (CENTRAL) {
         if (t > 1) collect_values();  // of step t - 2
       }
@@ -776,7 +788,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           // (the observation stores went out at the start of the step): the collected per-row
           // outputs of the previous step go out here.
           if (net == 1) {
-            ws.wait_oldest();
+            stage_wait();
             if (FULL && t > 0) flush(t - 1, 0x1f);
             // The flush reads s_out / s_done of step t-1; the next writes to them are this step's values,
             // behind the value network.  A network of several stages has a stage barrier in between; one
@@ -793,7 +805,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           }
   #pragma unroll 1
           for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
-            if (sc != 0) ws.wait_oldest();
+            if (sc != 0) stage_wait();
             int next = net * Stream::STAGES_PER_NET + sc + Stream::AHEAD;  // AHEAD stages ahead, cyclic over the step
             if (next >= Stream::STAGES_PER_STEP) next -= Stream::STAGES_PER_STEP;
             const int nbuf = (gs + Stream::AHEAD) % NBUF;
@@ -917,6 +929,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     }
     wave_lds_sync();
     stamp(CLK_END);
+    if constexpr (PHASE == PHASE_CLOCKS) {
+      if (blockIdx.x == 0 && t == a.T / 2 && lane == 0) a.logits[32 * wave + CLK_WAIT] = (float)clk_wait;
+    }
   }
 
   if constexpr (HAS_NETS) ws.wait_all();  // copies issued ahead for stages that will not run
