@@ -1,4 +1,6 @@
 // Table and launcher of the compiled instances of the pursuit-env rollout kernel (tag_kernels.h).
+#include <unordered_map>
+
 #include "tag_kernels.h"
 
 namespace msrl {
@@ -15,12 +17,24 @@ const std::vector<TagEntry>& tag_kernels() {
   return table;
 }
 
+// (the table has about a thousand entries and the step-granular calls look one up per call: an index by
+// shape, built once)
+uint32_t tag_key(int nc, int nr, int landmarks, int hidden, bool bf16, int tiles, int phase) {
+  return (uint32_t)nc | (uint32_t)nr << 4 | (uint32_t)landmarks << 8 | (uint32_t)(bf16 ? 1 : 0) << 12 |
+         (uint32_t)tiles << 13 | (uint32_t)phase << 16 | (uint32_t)hidden << 20;
+}
 const TagEntry* find_tag(int nc, int nr, int landmarks, int hidden, bool bf16, int tiles, int phase) {
-  for (const TagEntry& k : tag_kernels())
-    if (k.nc == nc && k.nr == nr && k.landmarks == landmarks && k.hidden == hidden && (k.bf16 != 0) == bf16 &&
-        k.tiles == tiles && k.phase == phase)
-      return &k;
-  return nullptr;
+  static const std::unordered_map<uint32_t, const TagEntry*> index = [] {
+    std::unordered_map<uint32_t, const TagEntry*> m;
+    for (const TagEntry& k : tag_kernels())
+      m.emplace(tag_key(k.nc, k.nr, k.landmarks, k.hidden, k.bf16 != 0, k.tiles, k.phase), &k);
+    return m;
+  }();
+  if (nc < 0 || nc > 15 || nr < 0 || nr > 15 || landmarks < 0 || landmarks > 15 || tiles < 0 || tiles > 7 ||
+      phase < 0 || phase > 15 || hidden < 0 || hidden > 4095)
+    return nullptr;
+  const auto it = index.find(tag_key(nc, nr, landmarks, hidden, bf16, tiles, phase));
+  return it == index.end() ? nullptr : it->second;
 }
 }  // namespace
 

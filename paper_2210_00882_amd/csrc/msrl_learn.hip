@@ -432,7 +432,8 @@ int fused_grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSe
   const int64_t n_tiles = (R + 31) / 32;
   const int64_t groups = (n_tiles + rows_waves(H) - 1) / rows_waves(H);
   const int64_t resident = (int64_t)L->cus * rows_workgroups_per_cu(H);
-  const unsigned grid = (unsigned)(groups < resident ? groups : resident);
+  unsigned grid = (unsigned)(groups < resident ? groups : resident);
+  if (H <= 64 && grid > (unsigned)L->part_slices) grid = (unsigned)L->part_slices;  // one copy of the gradient per workgroup
   // 64-unit networks: the row kernel forms the weight gradients itself, one copy per workgroup
   const bool small = H <= 64;
   Reducer red;
