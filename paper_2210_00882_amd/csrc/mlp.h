@@ -472,6 +472,16 @@ struct Mlp {
   }
 };
 
+// Of the two waves that share a SIMD the older one wins the issue arbitration, runs ahead and then waits at
+// the stage barrier while the other finishes alone.  Handing the higher priority to the other half of the
+// workgroup stage by stage keeps the pair closer together.
+__device__ __forceinline__ void stage_priority(int stage, int wave, int waves) {
+  if ((stage & 1) == (wave >= waves / 2 ? 1 : 0))
+    __builtin_amdgcn_s_setprio(1);
+  else
+    __builtin_amdgcn_s_setprio(0);
+}
+
 // Weight stream of a workgroup: stage g of the endless sequence (groups of CPS
 // policy chunk blocks, then of value chunk blocks, then policy again, ...) lives
 // in LDS buffer g % NBUF and is copied there NBUF - 1 stages ahead by direct global->LDS loads

@@ -815,15 +815,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   #pragma unroll
                 for (int i = 0; i < Stream::PER_WAVE; ++i)
                   if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
-                // Of the two waves that share a SIMD the older one wins the issue arbitration, runs ahead and
-                // then waits at the stage barrier while the other finishes alone.  Handing the higher priority
-                // to the other half of the workgroup stage by stage keeps the pair closer together (1 % of the
-                // call at the benchmark's shape; per chunk the same, per tile the instruction costs more than
-                // it gains).
-                if (kt == 0 && c == 0) {
-                  if ((sc & 1) == (wave >= WAVES / 2 ? 1 : 0)) __builtin_amdgcn_s_setprio(1);
-                  else __builtin_amdgcn_s_setprio(0);
-                }
+                if (kt == 0 && c == 0) stage_priority(sc, wave, WAVES);  // (1 % of the call at the benchmark's shape)
               };
               if (sc == 0)
                 Net::template layer2_chunks<false, CPS>(ws.tiles(gs % NBUF, 0), h1, acc, out, h, tick);
