@@ -112,6 +112,16 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   for any other value, for 4 with more than 4 agents, and for a non-zero
  *   value with another env kind).
  *
+ * MSRL_ENV_PARTICLE with 64-unit networks of two hidden layers and a per-agent
+ *   critic has two kernel shapes with identical results: a wave evaluates the
+ *   policy and then the value network of its 32 rows, or two waves share the
+ *   rows, one network each (every weight resident on chip; the shape for
+ *   step is then half as long a chain of instructions and has no stage
+ *   barriers).  wave_roles = 0 lets msrl_rollout_init pick (two waves wherever
+ *   compiled, with two or four row blocks per workgroup by num_envs), 1 or 2
+ *   fixes the shape (EINVAL for any other value or another env kind,
+ *   EUNSUPPORTED for 2 where it is not compiled).
+ *
  * An episode ends (done = 1, then reset) on every step whose counter g
  * satisfies (g+1) % episode_len == 0; g counts the env's steps since init.
  */
@@ -135,6 +145,8 @@ typedef struct {
   float radius_c, radius_r;  /* body radii */
   float contact_force, contact_margin;
   int32_t tag_tiles;      /* 0: chosen by the library; 1 or 4: 32-env tiles per workgroup */
+  int32_t wave_roles;     /* particle env: 0 chosen by the library; 1: a wave evaluates both networks of its
+                             rows; 2: two waves per row block, one per network (see above) */
 } msrl_env_cfg;
 
 /*
@@ -301,6 +313,16 @@ int msrl_rollout_gae_static(const msrl_env_cfg* env, const msrl_policy_cfg* poli
 typedef enum { MSRL_PHASE_ENV = 1, MSRL_PHASE_MLP = 2, MSRL_PHASE_CLOCKS = 3 } msrl_phase;
 int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj* out,
                        int32_t phase, void* hip_stream);
+
+/*
+ * The launch shape msrl_rollout_init chose for the fused rollout of this state
+ * (host call, no device work): workgroups per launch, waves per workgroup, and
+ * how many of those waves own a block of 32 rows (all of them, or half with
+ * msrl_env_cfg.wave_roles = 2).  Any of the three pointers may be NULL.  Nothing
+ * in the results depends on the shape; the call is there so that tests and
+ * benchmarks can tell which kernel shape they ran.  EINVAL for a NULL state.
+ */
+int msrl_rollout_shape(const msrl_state* st, int32_t* workgroups, int32_t* waves, int32_t* row_waves);
 
 /*
  * Step-granular calls: the two halves of Actor.act (Listing 1) as calls of their

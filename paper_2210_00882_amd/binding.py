@@ -21,7 +21,7 @@ MSRL_PHASE_ENV, MSRL_PHASE_MLP, MSRL_PHASE_CLOCKS = 1, 2, 3
 
 EXPORTS = (
     "msrl_param_count", "msrl_env_state_size", "msrl_rollout_init", "msrl_rollout_step", "msrl_gae",
-    "msrl_rollout_gae", "msrl_rollout_gae_static", "msrl_measure_phase", "msrl_observe", "msrl_act", "msrl_env_step",
+    "msrl_rollout_gae", "msrl_rollout_gae_static", "msrl_measure_phase", "msrl_rollout_shape", "msrl_observe", "msrl_act", "msrl_env_step",
     "msrl_learner_init", "msrl_learner_init_path", "msrl_learner_destroy", "msrl_ppo_grad", "msrl_rows_mean", "msrl_adam_step", "msrl_ppo_update", "msrl_params_cast", "msrl_state_get", "msrl_state_set", "msrl_rollout_destroy", "msrl_last_error",
 )
 
@@ -38,6 +38,7 @@ class msrl_env_cfg(C.Structure):
         ("vmax_c", C.c_float), ("vmax_r", C.c_float), ("radius_c", C.c_float), ("radius_r", C.c_float),
         ("contact_force", C.c_float), ("contact_margin", C.c_float),
         ("tag_tiles", C.c_int32),
+        ("wave_roles", C.c_int32),
     ]
 
 
@@ -96,6 +97,8 @@ def load():
     lib.msrl_rollout_gae_static.argtypes = [C.POINTER(msrl_env_cfg), C.POINTER(msrl_policy_cfg), u64, vp, vp, vp, i32,
                                             f32, f32, C.POINTER(msrl_traj), vp]
     lib.msrl_measure_phase.restype = C.c_int
+    lib.msrl_rollout_shape.restype = C.c_int
+    lib.msrl_rollout_shape.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
     lib.msrl_measure_phase.argtypes = [vp, vp, i32, C.POINTER(msrl_traj), i32, vp]
     lib.msrl_observe.restype = C.c_int
     lib.msrl_observe.argtypes = [vp, vp, vp]
@@ -156,7 +159,7 @@ def _stream(stream):
     return C.c_void_p(s.cuda_stream)
 
 
-def make_env_cfg(cfg, A=None, B=None, tag_tiles=0):
+def make_env_cfg(cfg, A=None, B=None, tag_tiles=0, wave_roles=0):
     """msrl_env_cfg from a synth.Config; A, B float32 host arrays for lingauss.
     Returns (struct, keepalive)."""
     keep = []
@@ -169,7 +172,7 @@ def make_env_cfg(cfg, A=None, B=None, tag_tiles=0):
     e = msrl_env_cfg(cfg.kind, cfg.num_envs, cfg.num_agents, cfg.num_landmarks, cfg.obs_dim, cfg.act_dim,
                      cfg.episode_len, cfg.dt, cfg.damping, cfg.force, cfg.radius, pa, pb,
                      cfg.noise_std, cfg.act_cost, cfg.num_chasers, cfg.accel_c, cfg.accel_r, cfg.vmax_c, cfg.vmax_r,
-                     cfg.radius_c, cfg.radius_r, cfg.contact_force, cfg.contact_margin, tag_tiles)
+                     cfg.radius_c, cfg.radius_r, cfg.contact_force, cfg.contact_margin, tag_tiles, wave_roles)
     return e, keep
 
 
@@ -239,6 +242,13 @@ def msrl_measure_phase(state, params, T: int, out: dict, phase: int, stream=None
     tr = _traj(out)
     _check(load().msrl_measure_phase(state, _ptr(params), C.c_int32(T), C.byref(tr), C.c_int32(phase),
                                      _stream(stream)))
+
+
+def msrl_rollout_shape(state) -> tuple:
+    """-> (workgroups, waves per workgroup, waves that own a row block)"""
+    wg, w, rw = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(load().msrl_rollout_shape(state, C.byref(wg), C.byref(w), C.byref(rw)))
+    return wg.value, w.value, rw.value
 
 
 def msrl_observe(state, obs, stream=None) -> None:

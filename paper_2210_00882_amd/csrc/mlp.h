@@ -506,7 +506,7 @@ struct WeightStream {
   static constexpr int PER_WAVE = (STAGE_TILES + WAVES - 1) / WAVES;  // copies per wave and stage
   static constexpr int BUF_SLOTS = STAGE_TILES * 64;                   // u32x4 slots per buffer
   static constexpr int AHEAD = NBUF - 1;
-  static_assert(NBUF >= 2 && (NBUF - 2) * PER_WAVE <= 15, "the hand-written wait encodes the count in 4 bits");
+  static_assert(NBUF >= 2, "a stage in use and one in flight");
   u32x4* lds;  // NBUF * BUF_SLOTS slots
   const uint8_t* packed;
   size_t net_bytes, chunks_off, chunk_bytes;
@@ -545,6 +545,7 @@ struct WeightStream {
   }
   // wait until the oldest stage in flight has landed, then for every wave of the workgroup
   __device__ __forceinline__ void wait_oldest() const {
+    static_assert((NBUF - 2) * PER_WAVE <= 15, "the hand-written wait encodes the count in 4 bits");
     // s_waitcnt vmcnt(n): simm16 = vmcnt[3:0] | expcnt(7) << 4 | lgkmcnt(15) << 8
     __builtin_amdgcn_s_waitcnt(0x0F70 | ((NBUF - 2) * PER_WAVE));
     __syncthreads();

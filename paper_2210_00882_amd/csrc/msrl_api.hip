@@ -42,7 +42,7 @@ struct msrl_state {
   NetLayout critic_layout;  // centralised critic: its image follows the policy network's in `packed`
   bool central;
   KernelEntry kernel;
-  int envs_per_block;    // envs owned by one workgroup
+  int cus;               // compute units of the device
   int in_used;           // leading observation features that can be non-zero (inputs of layer 1)
   int tag_tiles;         // pursuit env: 32-env tiles per workgroup (1 or 4)
   bool packed_valid;     // `packed` holds the image of the parameters of an earlier call
@@ -269,7 +269,8 @@ int check_traj(const msrl_state* st, const msrl_traj* out, bool need_gae) {
 }
 
 // the compiled kernel for this state's configuration and the given phase variant, or null
-bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase, KernelEntry* out) {
+// (row_waves != 0: only a kernel with that many row blocks per workgroup)
+bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase, KernelEntry* out, int row_waves = 0) {
   const bool bf16 = pol.dtype == MSRL_BF16;
   // networks with more than two hidden layers, and a centralised critic, have kernels of their own for the
   // full rollout and for the actor fragment, and no measurement variants; the environment-only variant
@@ -286,6 +287,7 @@ bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase,
   }
   for (const KernelEntry& k : all_kernels()) {
     if (k.phase != phase || k.kind != env.kind || k.hidden != pol.hidden || (k.bf16 != 0) != bf16) continue;
+    if (row_waves != 0 && k.row_waves != row_waves) continue;
     if (env.kind == MSRL_ENV_PARTICLE) {
       if (k.n != env.num_agents || env.num_landmarks != env.num_agents) continue;
     } else {
@@ -295,6 +297,22 @@ bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase,
     return true;
   }
   return false;
+}
+
+// Envs per workgroup of a launch of `kernel`.  Every workgroup runs all T steps, so the launch takes
+// ceil(blocks / CUs) rounds.  The block is shrunk to the smallest size that needs no more rounds than
+// the largest one: equal work per workgroup instead of a short last round.  (Rounds are counted per CU
+// even where several workgroups fit one: they would share its SIMDs, and a wave with fewer rows costs
+// the same.)  Computed per launch: the kernels of a state (full rollout, actor fragment, env step,
+// measurement variants) differ in the row blocks a workgroup holds.
+int envs_per_block(const KernelEntry& kernel, int64_t num_envs, int cus) {
+  const int64_t max_epb = (int64_t)kernel.envs_per_wave * (kernel.row_waves ? kernel.row_waves : kernel.waves);
+  const int64_t blocks_max = (num_envs + max_epb - 1) / max_epb;
+  const int64_t rounds = (blocks_max + cus - 1) / cus;
+  int64_t epb = (num_envs + rounds * cus - 1) / (rounds * cus);
+  if (epb < 1) epb = 1;
+  if (epb > max_epb) epb = max_epb;
+  return (int)epb;
 }
 
 // params may be null for the variants that run no network; obs_in / actions_in feed the
@@ -333,7 +351,7 @@ int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* param
   a.M = (int64_t)st->env.num_envs * st->env.num_agents;
   a.obs_in = obs_in;
   a.actions_in = actions_in;
-  a.envs_per_block = st->envs_per_block;
+  a.envs_per_block = envs_per_block(kernel, st->env.num_envs, st->cus);
   a.layers = layers_of(st->pol);
   a.critic = st->central ? st->packed + st->layout.bytes : nullptr;
   const int64_t blocks = ((int64_t)a.E + a.envs_per_block - 1) / a.envs_per_block;
@@ -414,6 +432,9 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
                               (env->tag_tiles == 4 && env->num_agents > 4)))
     return fail(MSRL_EINVAL, "%s: tag_tiles %d (0 lets the library choose; 1, or 4 with at most 4 agents per env; "
                              "pursuit env only)", who, env->tag_tiles);
+  if (env->wave_roles != 0 && (env->kind != MSRL_ENV_PARTICLE || env->wave_roles < 0 || env->wave_roles > 2))
+    return fail(MSRL_EINVAL, "%s: wave_roles %d (0 lets the library choose, 1 or 2 waves per row block; "
+                             "particle env only)", who, env->wave_roles);
   // kernel selection
   KernelEntry found;
   memset(&found, 0, sizeof(found));
@@ -432,6 +453,31 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
                 who, env->kind, env->num_agents, env->num_landmarks, env->obs_dim, env->act_dim, policy->hidden,
                 policy->dtype);
 
+  int cus = 256;
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1)
+    return fail(MSRL_EDEVICE, "%s: cannot query the current device", who);
+  if (env->kind == MSRL_ENV_PARTICLE) {
+    // Two waves per row block, one per network, wherever that shape is compiled (64-unit networks): the two
+    // networks of a step do not depend on each other, a step is then half as long a chain of instructions, and
+    // with every weight tile resident it has no stage barriers (measured faster at every env count, 1.1x to
+    // 1.9x).  Two row blocks per workgroup - one wave per SIMD - as long as that gives every SIMD at most one
+    // wave anyway, else four where compiled (fp32: 1.2x at 16k envs and more; bf16: no gain).
+    const int plain_rw = found.waves;
+    const int64_t row_blocks = ((int64_t)env->num_envs + found.envs_per_wave - 1) / found.envs_per_wave;
+    KernelEntry split;
+    bool have = find_kernel(*env, *policy, PHASE_SPLIT, &split, plain_rw);
+    if (have && row_blocks > 2 * (int64_t)cus) {
+      KernelEntry wide;
+      if (find_kernel(*env, *policy, PHASE_SPLIT, &wide, 2 * plain_rw)) split = wide;
+    }
+    if (env->wave_roles == 2 && !have)
+      return fail(MSRL_EUNSUPPORTED, "%s: wave_roles 2 is compiled for 64-unit networks of two hidden layers "
+                                     "with a per-agent critic", who);
+    if (have && env->wave_roles != 1) found = split;
+  }
+
   memset(st, 0, sizeof(*st));
   st->env = *env;
   st->env.A = nullptr;
@@ -439,23 +485,8 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
   st->pol = *policy;
   st->seed = seed;
   st->kernel = found;
-  int cus = 256;
-  if (hipGetDevice(&st->device) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, st->device) != hipSuccess || cus < 1)
-    return fail(MSRL_EDEVICE, "%s: cannot query the current device", who);
-  {
-    // Every workgroup runs all T steps, so the launch takes ceil(blocks / CUs) rounds.  Shrink the
-    // block to the smallest size that needs no more rounds than the largest one: equal work per
-    // workgroup instead of a short last round.  (Rounds are counted per CU even where several
-    // workgroups fit one: they would share its SIMDs, and a wave with fewer rows costs the same.)
-    const int64_t max_epb = (int64_t)found.envs_per_wave * found.waves;
-    const int64_t blocks_max = (env->num_envs + max_epb - 1) / max_epb;
-    const int64_t rounds = (blocks_max + cus - 1) / cus;
-    int64_t epb = (env->num_envs + rounds * cus - 1) / (rounds * cus);
-    if (epb < 1) epb = 1;
-    if (epb > max_epb) epb = max_epb;
-    st->envs_per_block = (int)epb;
-  }
+  st->device = device;
+  st->cus = cus;
   // Pursuit env: tiles of 32 envs per workgroup (msrl_env_cfg.tag_tiles, 0 = chosen here).
   st->tag_tiles = env->tag_tiles != 0 ? env->tag_tiles : choose_tag_tiles(env->num_envs, env->num_agents, cus);
   if (env->kind == MSRL_ENV_TAG && st->tag_tiles == 4 &&
@@ -700,6 +731,25 @@ int msrl_measure_phase(msrl_state* st, const void* params, int32_t T, msrl_traj*
   if (!find_kernel(st->env, st->pol, phase, &k))
     return fail(MSRL_EUNSUPPORTED, "msrl_measure_phase: phase %d is not compiled for this configuration", phase);
   return enqueue_rollout(st, k, params, T, out, (hipStream_t)hip_stream);
+}
+
+int msrl_rollout_shape(const msrl_state* st, int32_t* workgroups, int32_t* waves, int32_t* row_waves) {
+  if (!st) return fail(MSRL_EINVAL, "msrl_rollout_shape: NULL state");
+  int64_t wg;
+  int w, rw;
+  if (st->env.kind == MSRL_ENV_TAG) {
+    wg = ((int64_t)st->env.num_envs + 32 * st->tag_tiles - 1) / (32 * st->tag_tiles);
+    w = rw = st->env.num_agents * st->tag_tiles;
+  } else {
+    const int epb = envs_per_block(st->kernel, st->env.num_envs, st->cus);
+    wg = ((int64_t)st->env.num_envs + epb - 1) / epb;
+    w = st->kernel.waves;
+    rw = st->kernel.row_waves ? st->kernel.row_waves : st->kernel.waves;
+  }
+  if (workgroups) *workgroups = (int32_t)wg;
+  if (waves) *waves = w;
+  if (row_waves) *row_waves = rw;
+  return MSRL_OK;
 }
 
 int msrl_observe(msrl_state* st, float* obs, void* hip_stream) {

@@ -17,6 +17,7 @@ struct KernelEntry {
   int envs_per_wave;
   int waves;          // waves per workgroup
   int phase;          // PHASE_ALL, or a measurement variant
+  int row_waves;      // waves of a workgroup that own rows (PHASE_SPLIT: half of them; 0 stands for all)
 };
 
 // NB: 32-row blocks per wave; WAVES: waves per workgroup (they share the LDS weight window)
@@ -60,11 +61,20 @@ constexpr bool particle_central_fits(int N, int H, bool bf16) {
   return N >= 2 && (H / 32) * (32 / N) <= 32 && (bf16 || (H <= 128 && N <= 8));
 }
 
-template <int N, int H, bool BF16, int PHASE>
+// Two waves per row block (PHASE_SPLIT: one evaluates the policy network, the other the value network, and
+// every weight tile of both stays in LDS), for 64-unit networks: two row blocks per workgroup (one wave per
+// SIMD), and for fp32 networks also four (two waves per SIMD: faster once every SIMD has a wave anyway).
+constexpr bool particle_split_compiled(int H) { return H == 64; }
+constexpr bool particle_split_wide_compiled(int H, bool bf16) { return H == 64 && !bf16; }
+
+// WIDE: PHASE_SPLIT with twice the row blocks per workgroup
+template <int N, int H, bool BF16, int PHASE, int WIDE = 1>
 KernelEntry particle_entry() {
-  constexpr int W = PHASE == PHASE_CENTRAL || PHASE == PHASE_ACT_CENTRAL ? H / 32 : particle_waves(H, BF16, PHASE);
+  constexpr int RW =
+      (PHASE == PHASE_CENTRAL || PHASE == PHASE_ACT_CENTRAL ? H / 32 : particle_waves(H, BF16, PHASE)) * WIDE;
+  constexpr int W = PHASE == PHASE_SPLIT ? 2 * RW : RW;
   return KernelEntry{0, N, 0, H, BF16 ? 1 : 0, (const void*)&particle_rollout_kernel<N, H, BF16, 1, W, PHASE>,
-                     32 / N, W, PHASE};
+                     32 / N, W, PHASE, RW};
 }
 
 template <int N0, int N1, int H, bool BF16>
@@ -76,6 +86,8 @@ void add_particle_family(std::vector<KernelEntry>& out) {
       out.push_back(particle_entry<N0, H, BF16, PHASE_STEP>());
       out.push_back(particle_entry<N0, H, BF16, PHASE_DEEP>());
       out.push_back(particle_entry<N0, H, BF16, PHASE_ACT_DEEP>());
+      if constexpr (particle_split_compiled(H)) out.push_back(particle_entry<N0, H, BF16, PHASE_SPLIT>());
+      if constexpr (particle_split_wide_compiled(H, BF16)) out.push_back(particle_entry<N0, H, BF16, PHASE_SPLIT, 2>());
     }
     if constexpr (particle_central_fits(N0, H, BF16)) {
       out.push_back(particle_entry<N0, H, BF16, PHASE_CENTRAL>());

@@ -126,7 +126,7 @@ __device__ __forceinline__ void sample_categorical5(const float (&l)[5], float u
 constexpr int CRITIC_FETCH_PAD_TILES = 32;
 
 enum : int { PHASE_ALL = 0, PHASE_ENV = 1, PHASE_MLP = 2, PHASE_CLOCKS = 3, PHASE_ACT = 4, PHASE_STEP = 5,
-             PHASE_DEEP = 6, PHASE_CENTRAL = 7, PHASE_ACT_DEEP = 8, PHASE_ACT_CENTRAL = 9 };
+             PHASE_DEEP = 6, PHASE_CENTRAL = 7, PHASE_ACT_DEEP = 8, PHASE_ACT_CENTRAL = 9, PHASE_SPLIT = 10 };
 // stamps: start of the step, observation rows built and stored, policy layer 1 done (after the
 // stage barrier that precedes it), policy stage s done (s < 5), same for the value network,
 // logits and values ready, sampling and move done, end of the step
@@ -148,17 +148,23 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   // the bias, which sits at input index NZ.
   constexpr int NZ = 4 * N + 2;
   constexpr int KT1 = BF16 ? (NZ + 1 + 15) / 16 : (NZ + 1 + 7) / 8;
-  constexpr int NBUF = 2;             // LDS window: the stage in use and the one being copied
   constexpr bool ACT = PHASE == PHASE_ACT || PHASE == PHASE_ACT_DEEP || PHASE == PHASE_ACT_CENTRAL;
   constexpr bool CENTRAL = PHASE == PHASE_CENTRAL || PHASE == PHASE_ACT_CENTRAL;
   // chunk blocks per stage (fewer barriers when they fit; the centralised critic needs the LDS)
   constexpr int CPS = BF16 && H >= 64 && !CENTRAL ? 2 : 1;
   typedef Mlp<H, BF16, NB, KT1> Net;
+  // PHASE_SPLIT: waves [0, RW) evaluate the policy network of row blocks 0 .. RW-1, waves [RW, 2 RW) the value
+  // network of the same row blocks (role 1); every stage of both networks is resident in LDS
+  constexpr bool SPLIT = PHASE == PHASE_SPLIT;
+  static_assert(!SPLIT || WAVES % 2 == 0, "two waves per row block");
+  constexpr int RW = SPLIT ? WAVES / 2 : WAVES;  // row blocks of a workgroup
+  // LDS window: the stage in use and the one being copied; PHASE_SPLIT: all stages of a step
+  constexpr int NBUF = SPLIT ? 2 * Net::NUC / CPS : 2;
   typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   typedef typename Net::Op Op;
   static_assert(EPW >= 1, "a wave must hold at least one env");
   constexpr bool DEEP = PHASE == PHASE_DEEP || PHASE == PHASE_ACT_DEEP;
-  constexpr bool FULL = (PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS || DEEP || CENTRAL) && !ACT;
+  constexpr bool FULL = (PHASE == PHASE_ALL || PHASE == PHASE_CLOCKS || DEEP || CENTRAL || SPLIT) && !ACT;
   static_assert(!CENTRAL || WAVES == Net::NUC, "centralised critic: one wave per 32-unit chunk");
   // The joint observation is laid out as one block of KT1 tiles per agent, the agent's row exactly as the
   // policy's layer 1 takes it (its constant 1 at input NZ included: agent 0's carries the critic's bias).
@@ -200,15 +206,28 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   // Per-row outputs of a step (value, action, logp, reward, done) are collected for the whole
   // workgroup and written one array per wave after the next barrier: WAVES * VR consecutive rows
   // per store instead of VR, so that all but the edge cache lines are written whole.
-  constexpr int WGR = PHASE == PHASE_MLP ? 1 : WAVES * VR;
+  constexpr int WGR = PHASE == PHASE_MLP ? 1 : RW * VR;
   constexpr int PF = D < (BF16 ? 16 : 8) * KT1 ? D : (BF16 ? 16 : 8) * KT1;  // features every write fills
   constexpr bool PART_IN_STG = PF >= 32 && SR >= 2 && STORES_OBS && H >= 256;
   __shared__ float s_part[WAVES][PART_IN_STG ? 1 : 2 * ROWS];
-  __shared__ float s_out[4][WGR];
-  __shared__ __attribute__((aligned(4))) uint8_t s_done[WGR];
+  // (PHASE_SPLIT: two copies, used in turn by the steps, since the step has no barrier between the
+  // store of the collected outputs and the first write of the next ones)
+  constexpr int PAR = SPLIT ? 2 : 1;
+  __shared__ float s_out[PAR][4][WGR];
+  __shared__ __attribute__((aligned(4))) uint8_t s_done[PAR][WGR];
+  __shared__ int s_act[SPLIT ? RW : 1][32];  // PHASE_SPLIT: the sampled actions, policy wave -> value wave
 
   int lane = threadIdx.x & 63;  // (not const: the centralised-critic variant hides it from the optimiser once per step)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: lives in a scalar register
+  const int role = SPLIT ? wave / RW : 0;     // which network this wave evaluates (PHASE_SPLIT)
+  const int rset = SPLIT ? wave % RW : wave;  // its row block within the workgroup
+  // Both waves of a row block step their own copy of its envs (the same arithmetic on the same actions);
+  // the policy wave samples and stores actions, log-probabilities and the final state, the value wave
+  // stores the observation rows and computes the reward (2 % faster than everything on the policy wave,
+  // whose chain of instructions is the step's critical path).
+  const bool writer = role == 0;
+  const bool obs_writer = !SPLIT || role == 1;
+  const bool rew_writer = !SPLIT || role == 1;
   const int n = lane & 31, h = lane >> 5;
   const int layers = DEEP ? a.layers : 2;
   const NetLayout ly = net_layout(NZ, H, BF16, layers);
@@ -226,6 +245,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   if constexpr (HAS_NETS) {
 #pragma unroll
     for (int s = 0; s < Stream::AHEAD; ++s) ws.issue(s, s);
+    if constexpr (SPLIT) ws.issue(NBUF - 1, NBUF - 1);  // all of them: nothing is copied inside the step loop
     if constexpr (CENTRAL) {
       const u32x4* src = (const u32x4*)(a.packed + ly.w1);
       for (int i = threadIdx.x; i < Net::L1_TILES * 64; i += blockDim.x) s_l1[0][i] = src[i];
@@ -245,11 +265,14 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   }
   // features the lanes never write (>= the layer-1 tile range) stay zero for the whole kernel
   for (int i = threadIdx.x; i < WAVES * STG; i += blockDim.x) (&s_stg[0][0])[i] = 0.0f;
-  __syncthreads();
+  if constexpr (SPLIT)
+    ws.wait_all();
+  else
+    __syncthreads();
   // envs of this workgroup: [blk0, blk0 + envs_per_block); of this wave: EPW of them
   const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
   const int64_t blk_end = min(blk0 + (int64_t)a.envs_per_block, (int64_t)a.E);
-  const int64_t env0 = blk0 + (int64_t)wave * EPW;
+  const int64_t env0 = blk0 + (int64_t)rset * EPW;
   float2* tab = s_tab[wave];
   float* stg = s_stg[wave];
   // Reward partials (2 x 32 floats, used only between the env move and the end of the step): when the
@@ -297,20 +320,21 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   wave_lds_sync();
 
   const int64_t m0 = env0 * N;  // first trajectory row of this wave
-  const int wrow0 = wave * VR;  // ... and its first row within the workgroup
+  const int wrow0 = rset * VR;  // ... and its first row within the workgroup
   // stores the collected per-row outputs of step ts; bit k of `arrays` selects array k (value,
   // action, logp, reward, done), which goes out through wave k % WAVES, 64 consecutive rows per
   // store instruction
   auto flush = [&](int ts, int arrays) {
     const int wg_rows = __builtin_amdgcn_readfirstlane((int)(blk_end - blk0)) * N;
     const size_t o0 = (size_t)ts * a.M + (size_t)blk0 * N;
+    const int fp = SPLIT ? (ts & 1) : 0;
     constexpr int J = (WGR + 63) / 64;
     for (int arr = wave; arr < 5; arr += WAVES) {
       if (!((arrays >> arr) & 1)) continue;
       if (arr < 4) {
         float vv[J];
 #pragma unroll
-        for (int j = 0; j < J; ++j) vv[j] = s_out[arr][min(lane + 64 * j, WGR - 1)];
+        for (int j = 0; j < J; ++j) vv[j] = s_out[fp][arr][min(lane + 64 * j, WGR - 1)];
         float* dst = arr == 0 ? a.values : arr == 1 ? (float*)a.actions : arr == 2 ? a.logp : a.rewards;
 #pragma unroll
         for (int j = 0; j < J; ++j)
@@ -318,7 +342,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       } else {
         uint8_t vv[J];
 #pragma unroll
-        for (int j = 0; j < J; ++j) vv[j] = s_done[min(lane + 64 * j, WGR - 1)];
+        for (int j = 0; j < J; ++j) vv[j] = s_done[fp][min(lane + 64 * j, WGR - 1)];
 #pragma unroll
         for (int j = 0; j < J; ++j)
           if (lane + 64 * j < wg_rows) a.dones[o0 + lane + 64 * j] = vv[j];
@@ -439,13 +463,14 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       float vsum = s_b3[1][0];
 #pragma unroll
       for (int w = 0; w < WAVES; ++w) vsum += s_vpart[w][col];
-      if (h == 0 && valid[q]) s_out[0][wrow0 + row[q]] = vsum;
+      if (h == 0 && valid[q]) s_out[0][0][wrow0 + row[q]] = vsum;
     }
   };
   float checksum[NB] = {};      // PHASE_MLP only
 
   long long clk0 = 0;
   for (int t = 0; t <= a.T; ++t) {
+    const int par = SPLIT ? (t & 1) : 0;
     auto stamp = [&](int i) {
       if constexpr (PHASE == PHASE_CLOCKS) {
         if (blockIdx.x == 0 && t == a.T / 2 && lane == 0) {
@@ -479,6 +504,10 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       __syncthreads();
       if (t > 0) flush(t - 1, PHASE == PHASE_STEP ? 0x18 : 0x1f);
       __syncthreads();
+    } else if constexpr (SPLIT) {
+      // every wave has finished step t-1: its collected outputs (in the other copy of s_out) go out
+      __syncthreads();
+      if (t > 0) flush(t - 1, 0x1f);
     } else {
       // The barrier of the policy network's first stage comes first in the step: its copies went out
       // during the last stage of the step before, and the wait for them also waits for every store
@@ -567,7 +596,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             }
           }
           wave_lds_sync();
-          const int pieces = min(SR, live_rows - r0) * (D / PW);
+          const int pieces = obs_writer ? min(SR, live_rows - r0) * (D / PW) : 0;
           float* gdst = a.obs + ((size_t)(PHASE == PHASE_STEP ? 0 : t) * a.M + m0 + r0) * D;
 #pragma unroll
           for (int j = 0; j * 64 < SR * (D / PW); ++j) {
@@ -713,6 +742,27 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
             ++sn;
           }
         }
+      } else if constexpr (SPLIT) {
+        // ---------------- this wave's network; all its stages are resident: no copies, waits or barriers
+        f32x16 out[NB], acc[NB];
+        Net::layer1(&s_l1[role][0] + lane, x, h1);
+        {
+          const f32x16 b = bias_init(s_b3[role], h);
+#pragma unroll
+          for (int q = 0; q < NB; ++q) out[q] = b;
+        }
+        auto tick = [&](int, int) {};
+#pragma unroll
+        for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
+          const int buf = role * Stream::STAGES_PER_NET + sc;
+          if (sc == 0)
+            Net::template layer2_chunks<false, CPS>(ws.tiles(buf, 0), h1, acc, out, h, tick);
+          else
+            Net::template layer2_chunks<true, CPS>(ws.tiles(buf, 0), h1, acc, out, h, tick);
+          if (sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(ws.tiles(buf, CPS - 1), acc, out);
+        }
+#pragma unroll
+        for (int q = 0; q < NB; ++q) out_p[q] = out_v[q] = out[q];
       } else if constexpr (CENTRAL) {
         // ---------------- policy network through the window, the critic riding on its stages
         Net::layer1(&s_l1[0][0] + lane, x, h1);
@@ -839,7 +889,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     if constexpr (!CENTRAL) {
 #pragma unroll
       for (int q = 0; q < NB; ++q)
-        if (h == 0 && valid[q]) s_out[0][wrow0 + row[q]] = out_v[q][0];
+        if (h == 0 && valid[q] && (!SPLIT || role == 1)) s_out[par][0][wrow0 + row[q]] = out_v[q][0];
     }
     if (!ACT && t == a.T) break;
 
@@ -854,17 +904,25 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
       l[2] = out_p[q][2];
       l[3] = out_p[q][3];
       l[4] = __shfl_xor(out_p[q][0], 32);  // logit 4 sits in register 0 of the partner lane
-      const Words4 w = draw(a.seed_lo, a.seed_hi, env[q], (uint32_t)ag[q], g32[q], 0, 0);
-      float lp;
-      int act;
-      sample_categorical5(l, u01(w.w[0]), act, lp);
-      act = __shfl(act, n);  // the h = 0 lane of the row decides
+      float lp = 0.0f;
+      int act = 0;
+      if (writer) {  // (uniform)
+        const Words4 w = draw(a.seed_lo, a.seed_hi, env[q], (uint32_t)ag[q], g32[q], 0, 0);
+        sample_categorical5(l, u01(w.w[0]), act, lp);
+        act = __shfl(act, n);  // the h = 0 lane of the row decides
+      }
+      if constexpr (SPLIT) {
+        // the value wave of the row block moves its copy of the envs with the policy wave's actions
+        if (writer && h == 0) s_act[rset][n] = act;
+        __syncthreads();
+        if (!writer) act = s_act[rset][n];
+      }
       if constexpr (PHASE == PHASE_STEP) act = valid[q] ? ((const int32_t*)a.actions_in)[m0 + row[q]] : 0;
       action[q] = act;
       const size_t o = (size_t)t * a.M + m0 + row[q];
-      if (h == 0 && valid[q]) {
-        s_out[1][wrow0 + row[q]] = __int_as_float(act);
-        s_out[2][wrow0 + row[q]] = lp;
+      if (h == 0 && valid[q] && writer) {
+        s_out[par][1][wrow0 + row[q]] = __int_as_float(act);
+        s_out[par][2][wrow0 + row[q]] = lp;
         if (PHASE != PHASE_CLOCKS && a.logits) {
 #pragma unroll
           for (int k = 0; k < 5; ++k) a.logits[o * 5 + k] = l[k];
@@ -886,6 +944,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     // lane h = 1 agent ag (collisions with the agents after it): one distance per lane and agent
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
+      if (!rew_writer) break;  // (uniform)
       const float2 lm = tab[base[q] + ag[q]];
       const float2 ref = h ? p[q] : lm;
       float mn = 3.0e38f, cnt = 0.0f;
@@ -905,14 +964,16 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     for (int q = 0; q < NB; ++q) {
       // each half-wave sums its own kind of term over the env's agents; the halves are then added
       float r = 0.0f;
-      const float* mine = h ? part1 : part0;
+      if (rew_writer) {  // (uniform)
+        const float* mine = h ? part1 : part0;
 #pragma unroll
-      for (int j = 0; j < N; ++j) r += mine[base[q] + j];
-      r += __shfl_xor(r, 32);
+        for (int j = 0; j < N; ++j) r += mine[base[q] + j];
+        r += __shfl_xor(r, 32);
+      }
       const bool done = tau[q] + 1 == a.ep;
-      if (h == 0 && valid[q]) {
-        s_out[3][wrow0 + row[q]] = r;
-        s_done[wrow0 + row[q]] = done ? 1 : 0;
+      if (h == 0 && valid[q] && rew_writer) {
+        s_out[par][3][wrow0 + row[q]] = r;
+        s_done[par][wrow0 + row[q]] = done ? 1 : 0;
       }
       g32[q] += 1;
       tau[q] = done ? 0 : tau[q] + 1;
@@ -973,7 +1034,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   // ---------------- write the env state back
 #pragma unroll
   for (int q = 0; q < NB; ++q) {
-    if (h == 0 && valid[q]) {
+    if (h == 0 && valid[q] && writer) {
       float* es = a.env_state + (size_t)env[q] * S;
       es[4 * ag[q]] = p[q].x;
       es[4 * ag[q] + 1] = p[q].y;

@@ -58,12 +58,12 @@ def oracle_setup(cfg: synth.Config, bias_std=0.1, params=None):
 class GpuRollout:
     """One env batch on cuda:0 driven through the C ABI binding."""
 
-    def __init__(self, cfg: synth.Config, params_f32, seed, dyn=None, tag_tiles=0):
+    def __init__(self, cfg: synth.Config, params_f32, seed, dyn=None, tag_tiles=0, wave_roles=0):
         import torch
         from paper_2210_00882_amd import binding as B
         self.B, self.cfg, self.torch = B, cfg, torch
         A, Bm = dyn if dyn is not None else (None, None)
-        self.env_cfg, self._keep = B.make_env_cfg(cfg, A, Bm, tag_tiles=tag_tiles)
+        self.env_cfg, self._keep = B.make_env_cfg(cfg, A, Bm, tag_tiles=tag_tiles, wave_roles=wave_roles)
         self.pol_cfg = B.make_policy_cfg(cfg)
         self.state = B.msrl_rollout_init(self.env_cfg, self.pol_cfg, seed)
         self.params = B.upload_params(cfg, params_f32)

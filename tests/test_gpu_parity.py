@@ -16,9 +16,9 @@ pytestmark = pytest.mark.gpu
 SEED = 0xC0FFEE1234
 
 
-def run_and_check(cfg, T, env_ids=None, g_shift=None, mlp_rows_cap=None, bias_std=0.1, calls=1):
+def run_and_check(cfg, T, env_ids=None, g_shift=None, mlp_rows_cap=None, bias_std=0.1, calls=1, wave_roles=0):
     env, pol, params, dyn = oracle_setup(cfg, bias_std=bias_std)
-    with GpuRollout(cfg, params.astype(np.float32), SEED, dyn) as gpu:
+    with GpuRollout(cfg, params.astype(np.float32), SEED, dyn, wave_roles=wave_roles) as gpu:
         es0, g0 = gpu.get_state()
         # the initial state is episode 0 of the reset stream
         for e in ([0, cfg.num_envs - 1] if env_ids is None else env_ids[:4]):
@@ -126,6 +126,70 @@ def test_particle_agent_count_sweep(N, H, dtype):
         return
     tr, stats = run_and_check(cfg, 8)
     assert stats["rows"] == 8 * cfg.M
+
+
+@pytest.mark.parametrize("N", range(1, 11))
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_particle_one_and_two_waves_per_row_block(N, dtype):
+    # 64-unit networks have two kernel shapes (msrl_env_cfg.wave_roles): a wave runs both networks of its rows,
+    # or the policy and the value network of a row block run on two waves.  The library picks the second one
+    # wherever it is compiled, so the sweep above covers it; here each shape is fixed in turn, checked against
+    # the oracle (every env and step, two calls), and the two must agree bit for bit.
+    from paper_2210_00882_amd import binding as B
+    cfg = synth.particle(f"roles{N}", 53, N, 64, 9, 4, dtype=dtype, idx=140 + N)
+    for roles, want in ((0, (4, 2)), (1, (2, 2)), (2, (4, 2))):
+        st = B.msrl_rollout_init(B.make_env_cfg(cfg, wave_roles=roles)[0], B.make_policy_cfg(cfg), 1)
+        wg, waves, row_waves = B.msrl_rollout_shape(st)
+        B.msrl_rollout_destroy(st)
+        assert (waves, row_waves) == want and wg * row_waves * (32 // N) >= cfg.num_envs
+    one, stats = run_and_check(cfg, 9, calls=2, wave_roles=1)
+    assert stats["rows"] == 2 * 9 * cfg.M
+    two, stats = run_and_check(cfg, 9, calls=2, wave_roles=2)
+    assert stats["rows"] == 2 * 9 * cfg.M
+    for k in one:
+        np.testing.assert_array_equal(one[k], two[k], err_msg=k)
+
+
+@pytest.mark.parametrize("N", [1, 3, 10])
+def test_particle_two_waves_per_row_block_at_scale(N):
+    # enough envs that one wave per SIMD no longer holds them: fp32 networks then run four row blocks (eight
+    # waves) per workgroup.  Sampled envs against the oracle, and every output bit-equal to the one-wave shape.
+    from paper_2210_00882_amd import binding as B
+    E = (2 * 256 + 37) * (32 // N) + 1
+    cfg = synth.particle(f"roles_wide{N}", E, N, 64, 5, 3, dtype=synth.F32, idx=160 + N)
+    st = B.msrl_rollout_init(B.make_env_cfg(cfg)[0], B.make_policy_cfg(cfg), 1)
+    wg, waves, row_waves = B.msrl_rollout_shape(st)
+    B.msrl_rollout_destroy(st)
+    assert (waves, row_waves) == (8, 4) and wg * 4 * (32 // N) >= E
+    rng = np.random.default_rng(N)
+    ids = [0, 1, E - 1] + sorted(rng.choice(E, 6, replace=False).tolist())
+    two, _ = run_and_check(cfg, 5, env_ids=ids)
+    one, _ = run_and_check(cfg, 5, env_ids=ids, wave_roles=1)
+    for k in one:
+        np.testing.assert_array_equal(one[k], two[k], err_msg=k)
+
+
+def test_wave_roles_error_paths():
+    from paper_2210_00882_amd import binding as B
+    wide = synth.particle("roles_wide", 8, 3, 128, 4, 4, idx=150)
+    with pytest.raises(B.MsrlError) as ei:  # compiled for 64 units only
+        B.msrl_rollout_init(B.make_env_cfg(wide, wave_roles=2)[0], B.make_policy_cfg(wide), 1)
+    assert ei.value.code == B.MSRL_EUNSUPPORTED
+    deep = synth.particle("roles_deep", 8, 3, 64, 4, 4, idx=151).with_(hidden_layers=3)
+    with pytest.raises(B.MsrlError) as ei:
+        B.msrl_rollout_init(B.make_env_cfg(deep, wave_roles=2)[0], B.make_policy_cfg(deep), 1)
+    assert ei.value.code == B.MSRL_EUNSUPPORTED
+    small = synth.particle("roles_small", 8, 3, 64, 4, 4, idx=152)
+    for bad in (-1, 3):
+        with pytest.raises(B.MsrlError) as ei:
+            B.msrl_rollout_init(B.make_env_cfg(small, wave_roles=bad)[0], B.make_policy_cfg(small), 1)
+        assert ei.value.code == B.MSRL_EINVAL
+    lg = synth.CONFIGS[4].with_(num_envs=8)
+    _, _, _, dyn = oracle_setup(lg)
+    e, keep = B.make_env_cfg(lg, dyn[0], dyn[1], wave_roles=1)
+    with pytest.raises(B.MsrlError) as ei:  # particle env only
+        B.msrl_rollout_init(e, B.make_policy_cfg(lg), 1)
+    assert ei.value.code == B.MSRL_EINVAL
 
 
 @pytest.mark.parametrize("N", [2, 5, 7, 10])
