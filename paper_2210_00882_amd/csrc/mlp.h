@@ -189,6 +189,73 @@ struct Mlp {
   // bf16: one MFMA per tile and (with 256 units) one activation per tile, so the tanh chains are taken two
   // tiles at a time (see tanh_stage1); fp32 tiles are four MFMAs long and hide a chain each as they are
   static constexpr bool PAIRED = BF16 && KT2 % 2 == 0;
+  // fp32 networks: the output layer runs on the VALU.  Its few outputs (5 logits, 1 value, 2 K Gaussian
+  // parameters) would fill 32 rows of an MFMA that takes 64 cycles per 2 inputs - a sixth of the matrix
+  // work of a 128-unit network - while the VALU of these kernels is mostly idle.  Each lane multiplies the
+  // activations it holds (16 per chunk) with their weights as the tanh slices complete, between the MFMAs of
+  // the next chunk; `out` then holds the lane's partial sum of output o in register o, and out_finish adds the
+  // two lanes of a row and the bias and puts the result where the MFMA would have (the accumulator layout).
+  // bf16 networks keep the MFMA (2 instructions of 32 cycles per chunk; their VALU is the busy unit), and so do
+  // 256-unit fp32 networks (their kernels have no register to spare: even the one sum of a value network
+  // pushes scalar spills into scratch memory) and output layers with more than 6 outputs.
+  // OUTS: bit o set <-> output o exists.
+  template <uint32_t OUTS>
+  static constexpr bool l3v() { return !BF16 && H <= 128 && __builtin_popcount(OUTS) <= 6; }
+  // layer-3 tiles of a chunk that pass through the ring of LDS reads
+  template <uint32_t OUTS>
+  static constexpr int l3s() { return l3v<OUTS>() ? 0 : TPC; }
+
+  __device__ static __forceinline__ int lane_id() {
+    return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  }
+  // start value of the output accumulators: the bias (MFMA path), or zero (the bias comes in out_finish)
+  template <uint32_t OUTS>
+  __device__ static __forceinline__ f32x16 out_init(const float* lds_bias, int h) {
+    if constexpr (l3v<OUTS>()) return zero16();
+    else return bias_init(lds_bias, h);
+  }
+  // out[o] += sum over registers r in [r0, r1) of t[r] * W3[unit of (r, h)][o] for the outputs o whose bit is set
+  // in OUTS and that are below nout (a network with fewer outputs than the kernel's mask: a constant where the
+  // caller's loop over the networks is unrolled).  w3h: the layer-3 tiles
+  // of the chunk as floats, at the slot of lane 32 h: register r = 4 i + j meets component j of slot o + 32 h of
+  // tile i (the A operand of the MFMA that would multiply it), the same address for every lane of a half-wave.
+  template <uint32_t OUTS>
+  __device__ static __forceinline__ void l3_slice(const float* w3h, const float (&t)[16], f32x16& out, int r0, int r1,
+                                                  int nout) {
+    static_assert(OUTS != 0 && OUTS < 65536u, "one register per output");
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (r >= r0 && r < r1) {
+#pragma unroll
+        for (int o = 0; o < 16; ++o)
+          if (((OUTS >> o) & 1u) && o < nout)
+            out[o] = __builtin_fmaf(t[r], w3h[((r / 4) * 64 + o) * 4 + r % 4], out[o]);
+      }
+  }
+  // this half-wave's view of layer-3 tile `first` of the chunk block whose lane slots start at `tiles`
+  __device__ static __forceinline__ const float* l3_weights(const u32x4* tiles, int first, int h) {
+    return (const float*)(tiles + first * 64 - lane_id() + 32 * h);
+  }
+  // after the last chunk: (VALU path) partial sums of the two lanes of a row + bias, into the accumulator layout
+  template <uint32_t OUTS>
+  __device__ static __forceinline__ void out_finish(f32x16 (&out)[NB], const float* lds_bias, int h) {
+    if constexpr (l3v<OUTS>()) {
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        float tot[16];
+#pragma unroll
+        for (int o = 0; o < 16; ++o)
+          tot[o] = (OUTS >> o) & 1u ? out[q][o] + __shfl_xor(out[q][o], 32) + lds_bias[o] : 0.0f;
+        f32x16 res;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int u0 = 8 * (r / 4) + r % 4, u1 = u0 + 4;  // the register's output on the lanes h = 0 / h = 1
+          res[r] = h ? (u1 < 16 ? tot[u1 < 16 ? u1 : 0] : 0.0f) : (u0 < 16 ? tot[u0 < 16 ? u0 : 0] : 0.0f);
+        }
+        out[q] = res;
+      }
+    }
+  }
 
   // tanh of the previous chunk, spread over the NT tiles of the current one
   template <int NT>
@@ -237,10 +304,13 @@ struct Mlp {
   // chunk uc-1 on entry, which get tanh and feed layer 3 meanwhile.
   // tick(kt) is called once per layer-2 tile: the caller spreads the copies of a later stage over
   // the loop, so that they queue behind the MFMAs instead of stalling every wave at the stage start.
-  template <bool PIPE, class Tick>
+  template <bool PIPE, uint32_t OUTS, class Tick>
   __device__ static __forceinline__ void layer2_chunk(const u32x4* tiles, const Op (&h1)[NB][KT2 * PT],
-                                                      f32x16 (&acc)[NB], f32x16 (&out)[NB], int h,
+                                                      f32x16 (&acc)[NB], f32x16 (&out)[NB], int h, int nout,
                                                       Tick&& tick) {
+    constexpr bool L3V = l3v<OUTS>();
+    constexpr int L3S = l3s<OUTS>();
+    const float* w3h = L3V ? l3_weights(tiles, L3_PREV, h) : nullptr;
     u32x4 ring[G];
 #pragma unroll
     for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
@@ -259,14 +329,14 @@ struct Mlp {
       for (int kt = 0; kt < KT2; kt += 2) {
         const int r0 = kt * 16 / KT2, r1 = (kt + 2) * 16 / KT2;
         u32x4 raw = ring[kt % G];
-        if (kt + G < L3_PREV + TPC) ring[kt % G] = tiles[(kt + G) * 64];
+        if (kt + G < L3_PREV + L3S) ring[kt % G] = tiles[(kt + G) * 64];
         pin(raw);
 #pragma unroll
         for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
 #pragma unroll
         for (int q = 0; q < NB; ++q) tanh_stage1(prev[q], w[q], r0, r1);
         u32x4 raw2 = ring[(kt + 1) % G];
-        if (kt + 1 + G < L3_PREV + TPC) ring[(kt + 1) % G] = tiles[(kt + 1 + G) * 64];
+        if (kt + 1 + G < L3_PREV + L3S) ring[(kt + 1) % G] = tiles[(kt + 1 + G) * 64];
         pin(raw2);
 #pragma unroll
         for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw2, &h1[q][(kt + 1) * PT], acc[q]);
@@ -282,22 +352,28 @@ struct Mlp {
 #pragma unroll
     for (int kt = 0; kt < KT2; ++kt) {
       u32x4 raw = ring[kt % G];
-      if (kt + G < L3_PREV + TPC) ring[kt % G] = tiles[(kt + G) * 64];
+      if (kt + G < L3_PREV + L3S) ring[kt % G] = tiles[(kt + G) * 64];
       if (PIPE) pin(raw);
 #pragma unroll
       for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
-      if (PIPE) tanh_slice<KT2>(prev, t, kt);
+      if (PIPE) {
+        tanh_slice<KT2>(prev, t, kt);
+        if constexpr (l3v<OUTS>()) {
+#pragma unroll
+          for (int q = 0; q < NB; ++q) l3_slice<OUTS>(w3h, t[q], out[q], kt * 16 / KT2, (kt + 1) * 16 / KT2, nout);
+        }
+      }
       tick(kt);
     }
     }
     {
       const Op one = Operand<BF16>::one(h);
       const u32x4 raw = ring[KT2 % G];
-      if (KT2 + G < L3_PREV + TPC) ring[KT2 % G] = tiles[(KT2 + G) * 64];
+      if (KT2 + G < L3_PREV + L3S) ring[KT2 % G] = tiles[(KT2 + G) * 64];
 #pragma unroll
       for (int q = 0; q < NB; ++q) mma_bias_tile<BF16>(raw, one, acc[q]);
     }
-    if (PIPE) {
+    if (PIPE && !L3V) {
       Op h2[NB][PC];
 #pragma unroll
       for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], h2[q]);
@@ -314,13 +390,16 @@ struct Mlp {
   // LDS reads runs on across the chunk boundaries, so the latency of the first reads is paid once per
   // stage (behind its barrier) and not once per chunk.  Chunk 0 is piped (its predecessor's tanh and
   // layer-3 share run beside it) iff PIPE0; the later chunks always are.  tick(c, kt) once per layer-2 tile.
-  template <bool PIPE0, int CPS, class Tick>
+  template <bool PIPE0, int CPS, uint32_t OUTS, class Tick>
   __device__ static __forceinline__ void layer2_chunks(const u32x4* tiles, const Op (&h1)[NB][KT2 * PT],
-                                                       f32x16 (&acc)[NB], f32x16 (&out)[NB], int h,
+                                                       f32x16 (&acc)[NB], f32x16 (&out)[NB], int h, int nout,
                                                        Tick&& tick) {
     // tiles a chunk consumes, in order: its KT2 layer-2 tiles, its bias tile and, if piped, the TPC
     // layer-3 tiles fed by the chunk before it; they are consecutive inside the chunk block
-    constexpr int PER0 = KT2 + 1 + (PIPE0 ? TPC : 0), PERN = KT2 + 1 + TPC;
+    // (the layer-3 tiles only where the MFMA multiplies them)
+    constexpr bool L3V = l3v<OUTS>();
+    constexpr int L3S = l3s<OUTS>();
+    constexpr int PER0 = KT2 + 1 + (PIPE0 ? L3S : 0), PERN = KT2 + 1 + L3S;
     constexpr int TOTAL = PER0 + (CPS - 1) * PERN;
     auto tile_at = [](int p) -> int {  // position in the stream -> tile index in the buffer
       if (p < PER0) return p;
@@ -340,6 +419,7 @@ struct Mlp {
     for (int c = 0; c < CPS; ++c) {
       const bool pipe = PIPE0 || c > 0;
       const int p0 = c == 0 ? 0 : PER0 + (c - 1) * PERN;  // position of the chunk's first tile
+      const float* w3h = L3V ? l3_weights(tiles, c * CHUNK_TILES + L3_PREV, h) : nullptr;
       f32x16 prev[NB];
       float t[NB][16];
 #pragma unroll
@@ -379,7 +459,13 @@ struct Mlp {
           if (pipe) pin(raw);
 #pragma unroll
           for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &h1[q][kt * PT], acc[q]);
-          if (pipe) tanh_slice<KT2>(prev, t, kt);
+          if (pipe) {
+            tanh_slice<KT2>(prev, t, kt);
+            if constexpr (l3v<OUTS>()) {
+#pragma unroll
+              for (int q = 0; q < NB; ++q) l3_slice<OUTS>(w3h, t[q], out[q], kt * 16 / KT2, (kt + 1) * 16 / KT2, nout);
+            }
+          }
           tick(c, kt);
         }
       }
@@ -389,7 +475,7 @@ struct Mlp {
 #pragma unroll
         for (int q = 0; q < NB; ++q) mma_bias_tile<BF16>(raw, one, acc[q]);
       }
-      if (pipe) {
+      if (pipe && !L3V) {
         Op h2[NB][PC];
 #pragma unroll
         for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], h2[q]);
@@ -452,8 +538,19 @@ struct Mlp {
   }
 
   // after the last chunk stage: its tanh and layer-3 contribution (tiles of the same stage)
+  template <uint32_t OUTS>
   __device__ static __forceinline__ void layer2_drain(const u32x4* tiles, const f32x16 (&acc)[NB],
-                                                      f32x16 (&out)[NB]) {
+                                                      f32x16 (&out)[NB], int h, int nout) {
+    if constexpr (l3v<OUTS>()) {
+      const float* w3h = l3_weights(tiles, L3_OWN, h);
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        float t[16];
+        tanh_range(acc[q], t, 0, 16, false);
+        l3_slice<OUTS>(w3h, t, out[q], 0, 16, nout);
+      }
+      return;
+    }
     u32x4 w3[TPC];
 #pragma unroll
     for (int i = 0; i < TPC; ++i) w3[i] = tiles[(L3_OWN + i) * 64];

@@ -352,6 +352,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
 
 
   int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % NBUF
+  // Outputs of a network as a bit mask (5 logits; the value network uses the first).  Only the fp32 output
+  // layer's code depends on it: few outputs run on the VALU (Mlp::l3v).  All 16 bits keep the output layer on
+  // the MFMA: bf16 kernels, and the variants with more hidden layers or a centralised critic (their fp32
+  // kernels have no registers left for it).
+  constexpr uint32_t OUTS = BF16 || DEEP || CENTRAL ? 0xFFFFu : 0x1Fu;
 
   // Centralised critic (PHASE_CENTRAL).  The joint observations of the workgroup's envs are the
   // columns of one tile, and this wave computes the 32-unit chunk `wave` of each hidden layer.  Those
@@ -715,7 +720,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           }
           // last hidden layer and output layer
           {
-            const f32x16 b = bias_init(s_b3[net], h);
+            const f32x16 b = Net::template out_init<OUTS>(s_b3[net], h);
 #pragma unroll
             for (int q = 0; q < NB; ++q) out[q] = b;
           }
@@ -733,10 +738,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
                   if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
               };
               if (c == 0 && sc == 0)
-                Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
+                Net::template layer2_chunk<false, OUTS>(tiles, h1, acc, out, h, 16, tick);
               else
-                Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
-              if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
+                Net::template layer2_chunk<true, OUTS>(tiles, h1, acc, out, h, 16, tick);
+              if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1)
+                Net::template layer2_drain<OUTS>(tiles, acc, out, h, 16);
             }
             ++gs;
             ++sn;
@@ -746,21 +752,24 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         // ---------------- this wave's network; all its stages are resident: no copies, waits or barriers
         f32x16 out[NB], acc[NB];
         Net::layer1(&s_l1[role][0] + lane, x, h1);
+        auto tick = [&](int, int) {};
         {
-          const f32x16 b = bias_init(s_b3[role], h);
+          const f32x16 b = Net::template out_init<OUTS>(s_b3[role], h);
 #pragma unroll
           for (int q = 0; q < NB; ++q) out[q] = b;
         }
-        auto tick = [&](int, int) {};
+        // (the value wave computes all five sums too: its output-layer rows beyond the first are zero)
 #pragma unroll
         for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
           const int buf = role * Stream::STAGES_PER_NET + sc;
           if (sc == 0)
-            Net::template layer2_chunks<false, CPS>(ws.tiles(buf, 0), h1, acc, out, h, tick);
+            Net::template layer2_chunks<false, CPS, OUTS>(ws.tiles(buf, 0), h1, acc, out, h, 16, tick);
           else
-            Net::template layer2_chunks<true, CPS>(ws.tiles(buf, 0), h1, acc, out, h, tick);
-          if (sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(ws.tiles(buf, CPS - 1), acc, out);
+            Net::template layer2_chunks<true, CPS, OUTS>(ws.tiles(buf, 0), h1, acc, out, h, 16, tick);
+          if (sc == Stream::STAGES_PER_NET - 1)
+            Net::template layer2_drain<OUTS>(ws.tiles(buf, CPS - 1), acc, out, h, 16);
         }
+        Net::template out_finish<OUTS>(out, s_b3[role], h);
 #pragma unroll
         for (int q = 0; q < NB; ++q) out_p[q] = out_v[q] = out[q];
       } else if constexpr (CENTRAL) {
@@ -768,7 +777,7 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
         Net::layer1(&s_l1[0][0] + lane, x, h1);
         f32x16 acc[NB];
         {
-          const f32x16 b = bias_init(s_b3[0], h);
+          const f32x16 b = Net::template out_init<OUTS>(s_b3[0], h);
 #pragma unroll
           for (int q = 0; q < NB; ++q) out_p[q] = b;
         }
@@ -819,12 +828,13 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
               if (i * Net::KT2 / Stream::PER_WAVE == kt) ws.issue_part(next, nbuf, i);
           };
           if (sc == 0)
-            Net::template layer2_chunk<false>(tiles, h1, acc, out_p, h, tick);
+            Net::template layer2_chunk<false, OUTS>(tiles, h1, acc, out_p, h, 16, tick);
           else
-            Net::template layer2_chunk<true>(tiles, h1, acc, out_p, h, tick);
-          if (sc == SPN - 1) Net::layer2_drain(tiles, acc, out_p);
+            Net::template layer2_chunk<true, OUTS>(tiles, h1, acc, out_p, h, 16, tick);
+          if (sc == SPN - 1) Net::template layer2_drain<OUTS>(tiles, acc, out_p, h, 16);
           ++gs;
         }
+
         critic_l1_publish(cacc);
         cacc = zero16();  // layer 2 starts from zero in stage 0 of the next step
 #pragma unroll
@@ -848,8 +858,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
           Net::layer1(&s_l1[net][0] + lane, x, h1);
           stamp(net == 0 ? CLK_P_L1 : CLK_V_L1);
           f32x16 acc[NB];
+          const int nout = net == 0 ? 5 : 1;  // (a constant once the loop over the networks is unrolled)
           {
-            const f32x16 b = bias_init(s_b3[net], h);
+            const f32x16 b = Net::template out_init<OUTS>(s_b3[net], h);
   #pragma unroll
             for (int q = 0; q < NB; ++q) out[q] = b;
           }
@@ -868,14 +879,16 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
                 if (kt == 0 && c == 0) stage_priority(sc, wave, WAVES);  // (1 % of the call at the benchmark's shape)
               };
               if (sc == 0)
-                Net::template layer2_chunks<false, CPS>(ws.tiles(gs % NBUF, 0), h1, acc, out, h, tick);
+                Net::template layer2_chunks<false, CPS, OUTS>(ws.tiles(gs % NBUF, 0), h1, acc, out, h, nout, tick);
               else
-                Net::template layer2_chunks<true, CPS>(ws.tiles(gs % NBUF, 0), h1, acc, out, h, tick);
-              if (sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(ws.tiles(gs % NBUF, CPS - 1), acc, out);
+                Net::template layer2_chunks<true, CPS, OUTS>(ws.tiles(gs % NBUF, 0), h1, acc, out, h, nout, tick);
+              if (sc == Stream::STAGES_PER_NET - 1)
+                Net::template layer2_drain<OUTS>(ws.tiles(gs % NBUF, CPS - 1), acc, out, h, nout);
             }
             ++gs;
             if (sc < 5) stamp((net == 0 ? CLK_P_STAGE : CLK_V_STAGE) + sc);
           }
+          Net::template out_finish<OUTS>(out, s_b3[net], h);
         }
       }
     }
@@ -1188,7 +1201,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
             for (int j = 0; j < Net::KT2 * Net::PT; ++j) h1[0][j] = hb[0][j];
           }
         }
-        out[0] = bias_init(s_b3[net], h);
+        constexpr uint32_t OUTS = 0xFFFFu;  // (output layer on the MFMA: 2 K outputs)
+        out[0] = Net::template out_init<OUTS>(s_b3[net], h);
 #pragma unroll 1
         for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
           ws.wait_oldest();
@@ -1206,10 +1220,10 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
                 if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
             };
             if (c == 0 && sc == 0)
-              Net::template layer2_chunk<false>(tiles, h1, acc, out, h, tick);
+              Net::template layer2_chunk<false, OUTS>(tiles, h1, acc, out, h, 16, tick);
             else
-              Net::template layer2_chunk<true>(tiles, h1, acc, out, h, tick);
-            if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::layer2_drain(tiles, acc, out);
+              Net::template layer2_chunk<true, OUTS>(tiles, h1, acc, out, h, 16, tick);
+            if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::template layer2_drain<OUTS>(tiles, acc, out, h, 16);
           }
           ++gs;
         }
