@@ -221,15 +221,21 @@ struct Mlp {
   // tile i (the A operand of the MFMA that would multiply it), the same address for every lane of a half-wave.
   template <uint32_t OUTS>
   __device__ static __forceinline__ void l3_slice(const float* w3h, const float (&t)[16], f32x16& out, int r0, int r1,
-                                                  int nout) {
+                                                  int nout, f32x4 (&wg)[16]) {
     static_assert(OUTS != 0 && OUTS < 65536u, "one register per output");
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       if (r >= r0 && r < r1) {
+        if (r % 4 == 0) {
+          // the weights of registers r .. r+3, 16 bytes per output, fetched as the group starts (as single
+          // words the compiler fetches them far ahead and the 128-unit kernel spills 29 registers)
+#pragma unroll
+          for (int o = 0; o < 16; ++o)
+            if (((OUTS >> o) & 1u) && o < nout) wg[o] = *(const f32x4*)(w3h + ((r / 4) * 64 + o) * 4);
+        }
 #pragma unroll
         for (int o = 0; o < 16; ++o)
-          if (((OUTS >> o) & 1u) && o < nout)
-            out[o] = __builtin_fmaf(t[r], w3h[((r / 4) * 64 + o) * 4 + r % 4], out[o]);
+          if (((OUTS >> o) & 1u) && o < nout) out[o] = __builtin_fmaf(t[r], wg[o][r % 4], out[o]);
       }
   }
   // this half-wave's view of layer-3 tile `first` of the chunk block whose lane slots start at `tiles`
@@ -311,6 +317,7 @@ struct Mlp {
     constexpr bool L3V = l3v<OUTS>();
     constexpr int L3S = l3s<OUTS>();
     const float* w3h = L3V ? l3_weights(tiles, L3_PREV, h) : nullptr;
+    f32x4 wg[16];
     u32x4 ring[G];
 #pragma unroll
     for (int i = 0; i < G; ++i) ring[i] = tiles[i * 64];
@@ -360,7 +367,7 @@ struct Mlp {
         tanh_slice<KT2>(prev, t, kt);
         if constexpr (l3v<OUTS>()) {
 #pragma unroll
-          for (int q = 0; q < NB; ++q) l3_slice<OUTS>(w3h, t[q], out[q], kt * 16 / KT2, (kt + 1) * 16 / KT2, nout);
+          for (int q = 0; q < NB; ++q) l3_slice<OUTS>(w3h, t[q], out[q], kt * 16 / KT2, (kt + 1) * 16 / KT2, nout, wg);
         }
       }
       tick(kt);
@@ -420,6 +427,7 @@ struct Mlp {
       const bool pipe = PIPE0 || c > 0;
       const int p0 = c == 0 ? 0 : PER0 + (c - 1) * PERN;  // position of the chunk's first tile
       const float* w3h = L3V ? l3_weights(tiles, c * CHUNK_TILES + L3_PREV, h) : nullptr;
+      f32x4 wg[16];
       f32x16 prev[NB];
       float t[NB][16];
 #pragma unroll
@@ -463,7 +471,7 @@ struct Mlp {
             tanh_slice<KT2>(prev, t, kt);
             if constexpr (l3v<OUTS>()) {
 #pragma unroll
-              for (int q = 0; q < NB; ++q) l3_slice<OUTS>(w3h, t[q], out[q], kt * 16 / KT2, (kt + 1) * 16 / KT2, nout);
+              for (int q = 0; q < NB; ++q) l3_slice<OUTS>(w3h, t[q], out[q], kt * 16 / KT2, (kt + 1) * 16 / KT2, nout, wg);
             }
           }
           tick(c, kt);
@@ -543,11 +551,12 @@ struct Mlp {
                                                       f32x16 (&out)[NB], int h, int nout) {
     if constexpr (l3v<OUTS>()) {
       const float* w3h = l3_weights(tiles, L3_OWN, h);
+      f32x4 wg[16];
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
         float t[16];
         tanh_range(acc[q], t, 0, 16, false);
-        l3_slice<OUTS>(w3h, t, out[q], 0, 16, nout);
+        l3_slice<OUTS>(w3h, t, out[q], 0, 16, nout, wg);
       }
       return;
     }
