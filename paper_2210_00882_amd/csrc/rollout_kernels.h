@@ -1201,7 +1201,9 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
             for (int j = 0; j < Net::KT2 * Net::PT; ++j) h1[0][j] = hb[0][j];
           }
         }
-        constexpr uint32_t OUTS = 0xFFFFu;  // (output layer on the MFMA: 2 K outputs)
+        // (all 16 bits: the output layer stays on the MFMA.  The policy has 2 K outputs; the one sum of the value
+        // network on the VALU was tried: the 256-unit kernel then keeps its layer-1 outputs in scratch memory)
+        constexpr uint32_t OUTS = 0xFFFFu;
         out[0] = Net::template out_init<OUTS>(s_b3[net], h);
 #pragma unroll 1
         for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
