@@ -118,12 +118,14 @@ def other_config(B, synth, torch, idx, steps, with_cpu):
         ev[k][1].record()
     torch.cuda.synchronize()
     roll_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    shape = B.msrl_rollout_shape(state)
     B.msrl_rollout_destroy(state)
     dt_name = "bf16" if cfg.dtype == synth.BF16 else "f32"
     tf = mlp_flops_per_agent_step(cfg) * steps_per_call / (roll_ms * 1e-3) / 1e12
     res = {"workload": cfg.name, "dtype": dt_name, "rows_M": cfg.M, "T": T, "agent_steps_per_call": steps_per_call,
            "ms_per_call": ms_call, "agent_steps_per_s": steps_per_call / (ms_call * 1e-3),
            "rollout_ms_per_launch": roll_ms,
+           "launch": {"workgroups": shape[0], "waves_per_workgroup": shape[1], "row_blocks_per_workgroup": shape[2]},
            "roofline": {"kernel": "rollout", "bound": "mfma", "achieved": tf, "peak": PEAK_TFLOPS[dt_name],
                         "unit": "TFLOP/s", "frac": tf / PEAK_TFLOPS[dt_name]},
            "hbm_GBps": (rollout_bytes_per_agent_step(cfg) + GAE_BYTES_PER_AGENT_STEP) * steps_per_call / (ms_call * 1e-3) / 1e9}
@@ -158,6 +160,7 @@ def main():
     env_cfg, keep = B.make_env_cfg(cfg, *dyn)
     state = B.msrl_rollout_init(env_cfg, B.make_policy_cfg(cfg), seed)
     dparams = B.upload_params(cfg, params)
+    launch_shape = B.msrl_rollout_shape(state)
     out = B.alloc_traj(cfg, cfg.T, logits=False, gae=True)
     T, M = cfg.T, cfg.M
     agent_steps = T * M
@@ -517,7 +520,9 @@ def main():
         "dtype": dt_name, "data": "synthetic",
         "config": {"workload": cfg.name, "num_envs": cfg.num_envs, "num_agents": cfg.num_agents,
                    "rows_M": M, "T": T, "obs_dim": cfg.obs_dim, "hidden": cfg.hidden,
-                   "agent_steps_per_step": agent_steps},
+                   "agent_steps_per_step": agent_steps,
+                   "launch": {"workgroups": launch_shape[0], "waves_per_workgroup": launch_shape[1],
+                              "row_blocks_per_workgroup": launch_shape[2]}},
         "roofline": roofline,
         "roofline_gae": roofline_gae,
         "phases": phases,

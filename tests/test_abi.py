@@ -65,4 +65,5 @@ def test_null_and_size_checks():
     assert lib.msrl_gae(None, None, None, 4, 4, 0.99, 0.95, None, None, None) == B.MSRL_EINVAL
     assert lib.msrl_gae(None, None, None, 0, 4, 0.99, 0.95, None, None, None) == B.MSRL_OK
     assert lib.msrl_state_get(None, None, None) == B.MSRL_EINVAL
+    assert lib.msrl_rollout_shape(None, None, None, None) == B.MSRL_EINVAL
     lib.msrl_rollout_destroy(None)
