@@ -112,8 +112,9 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *   for any other value, for 4 with more than 4 agents, and for a non-zero
  *   value with another env kind).
  *
- * MSRL_ENV_PARTICLE with 64-unit networks of two hidden layers and a per-agent
- *   critic has two kernel shapes with identical results: a wave evaluates the
+ * MSRL_ENV_PARTICLE with 64-unit networks (or 128-unit bf16 networks) of two
+ *   hidden layers and a per-agent critic has two kernel shapes with identical
+ *   results: a wave evaluates the
  *   policy and then the value network of its 32 rows, or two waves share the
  *   rows, one network each (every weight resident on chip; the shape for
  *   step is then half as long a chain of instructions and has no stage

@@ -269,8 +269,9 @@ int check_traj(const msrl_state* st, const msrl_traj* out, bool need_gae) {
 }
 
 // the compiled kernel for this state's configuration and the given phase variant, or null
-// (row_waves != 0: only a kernel with that many row blocks per workgroup)
-bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase, KernelEntry* out, int row_waves = 0) {
+// (several instances of a phase differ in the row blocks per workgroup: pick < 0 takes the one with the fewest,
+// pick > 0 the one with the most, 0 the first)
+bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase, KernelEntry* out, int pick = 0) {
   const bool bf16 = pol.dtype == MSRL_BF16;
   // networks with more than two hidden layers, and a centralised critic, have kernels of their own for the
   // full rollout and for the actor fragment, and no measurement variants; the environment-only variant
@@ -285,18 +286,20 @@ bool find_kernel(const msrl_env_cfg& env, const msrl_policy_cfg& pol, int phase,
     else if (phase == PHASE_ACT) phase = PHASE_ACT_CENTRAL;
     else if (phase != PHASE_STEP) return false;
   }
+  bool found = false;
   for (const KernelEntry& k : all_kernels()) {
     if (k.phase != phase || k.kind != env.kind || k.hidden != pol.hidden || (k.bf16 != 0) != bf16) continue;
-    if (row_waves != 0 && k.row_waves != row_waves) continue;
+
     if (env.kind == MSRL_ENV_PARTICLE) {
       if (k.n != env.num_agents || env.num_landmarks != env.num_agents) continue;
     } else {
       if (k.n != env.obs_dim || k.k != env.act_dim) continue;
     }
-    *out = k;
-    return true;
+    if (!found || (pick < 0 && k.row_waves < out->row_waves) || (pick > 0 && k.row_waves > out->row_waves)) *out = k;
+    found = true;
+    if (pick == 0) break;
   }
-  return false;
+  return found;
 }
 
 // Envs per workgroup of a launch of `kernel`.  Every workgroup runs all T steps, so the launch takes
@@ -459,23 +462,20 @@ int configure_state(msrl_state* st, const char* who, const msrl_env_cfg* env, co
       hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1)
     return fail(MSRL_EDEVICE, "%s: cannot query the current device", who);
   if (env->kind == MSRL_ENV_PARTICLE) {
-    // Two waves per row block, one per network, wherever that shape is compiled (64-unit networks): the two
-    // networks of a step do not depend on each other, a step is then half as long a chain of instructions, and
-    // with every weight tile resident it has no stage barriers (measured faster at every env count, 1.1x to
-    // 1.9x).  Two row blocks per workgroup - one wave per SIMD - as long as that gives every SIMD at most one
-    // wave anyway, else four where compiled (fp32: 1.2x at 16k envs and more; bf16: no gain).
-    const int plain_rw = found.waves;
+    // Two waves per row block, one per network, where that shape is compiled: the two networks of a step do
+    // not depend on each other, a step is then half as long a chain of instructions, and with every weight
+    // tile resident it has no stage barriers.  64-unit networks: measured faster at every env count (1.1x to
+    // 1.9x); two row blocks per workgroup - one wave per SIMD - as long as that gives every SIMD at most one
+    // wave anyway, else four where compiled (fp32: 1.2x at 16k envs and more; bf16: no gain).  128-unit bf16
+    // networks: 1.8x as long as its workgroups run in one round, the same or a little slower beyond.
     const int64_t row_blocks = ((int64_t)env->num_envs + found.envs_per_wave - 1) / found.envs_per_wave;
     KernelEntry split;
-    bool have = find_kernel(*env, *policy, PHASE_SPLIT, &split, plain_rw);
-    if (have && row_blocks > 2 * (int64_t)cus) {
-      KernelEntry wide;
-      if (find_kernel(*env, *policy, PHASE_SPLIT, &wide, 2 * plain_rw)) split = wide;
-    }
+    const bool have = find_kernel(*env, *policy, PHASE_SPLIT, &split, row_blocks > 2 * (int64_t)cus ? 1 : -1);
     if (env->wave_roles == 2 && !have)
-      return fail(MSRL_EUNSUPPORTED, "%s: wave_roles 2 is compiled for 64-unit networks of two hidden layers "
-                                     "with a per-agent critic", who);
-    if (have && env->wave_roles != 1) found = split;
+      return fail(MSRL_EUNSUPPORTED, "%s: wave_roles 2 is compiled for 64-unit networks and 128-unit bf16 networks "
+                                     "of two hidden layers with a per-agent critic", who);
+    const bool pays = policy->hidden == 64 || row_blocks <= (int64_t)split.row_waves * cus;
+    if (have && (env->wave_roles == 2 || (env->wave_roles == 0 && pays))) found = split;
   }
 
   memset(st, 0, sizeof(*st));

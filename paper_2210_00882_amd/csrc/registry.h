@@ -62,16 +62,19 @@ constexpr bool particle_central_fits(int N, int H, bool bf16) {
 }
 
 // Two waves per row block (PHASE_SPLIT: one evaluates the policy network, the other the value network, and
-// every weight tile of both stays in LDS), for 64-unit networks: two row blocks per workgroup (one wave per
-// SIMD), and for fp32 networks also four (two waves per SIMD: faster once every SIMD has a wave anyway).
-constexpr bool particle_split_compiled(int H) { return H == 64; }
-constexpr bool particle_split_wide_compiled(int H, bool bf16) { return H == 64 && !bf16; }
+// every weight tile of both stays in LDS).  Row blocks per workgroup of the narrow (which = 0) and the wide
+// (which = 1) instance, 0 = not compiled: 64-unit networks two (one wave per SIMD), fp32 ones also four (two
+// waves per SIMD: faster once every SIMD has a wave anyway); 128-unit bf16 networks four (88 KB of weights;
+// fp32 ones would need 168 KB).
+constexpr int particle_split_rows(int H, bool bf16, int which) {
+  return H == 64 ? (which == 0 ? 2 : (bf16 ? 0 : 4)) : (H == 128 && bf16 && which == 0 ? 4 : 0);
+}
 
-// WIDE: PHASE_SPLIT with twice the row blocks per workgroup
-template <int N, int H, bool BF16, int PHASE, int WIDE = 1>
+// RWS: row blocks per workgroup of a PHASE_SPLIT instance
+template <int N, int H, bool BF16, int PHASE, int RWS = 0>
 KernelEntry particle_entry() {
-  constexpr int RW =
-      (PHASE == PHASE_CENTRAL || PHASE == PHASE_ACT_CENTRAL ? H / 32 : particle_waves(H, BF16, PHASE)) * WIDE;
+  constexpr int RW = PHASE == PHASE_SPLIT ? RWS
+                     : PHASE == PHASE_CENTRAL || PHASE == PHASE_ACT_CENTRAL ? H / 32 : particle_waves(H, BF16, PHASE);
   constexpr int W = PHASE == PHASE_SPLIT ? 2 * RW : RW;
   return KernelEntry{0, N, 0, H, BF16 ? 1 : 0, (const void*)&particle_rollout_kernel<N, H, BF16, 1, W, PHASE>,
                      32 / N, W, PHASE, RW};
@@ -86,8 +89,10 @@ void add_particle_family(std::vector<KernelEntry>& out) {
       out.push_back(particle_entry<N0, H, BF16, PHASE_STEP>());
       out.push_back(particle_entry<N0, H, BF16, PHASE_DEEP>());
       out.push_back(particle_entry<N0, H, BF16, PHASE_ACT_DEEP>());
-      if constexpr (particle_split_compiled(H)) out.push_back(particle_entry<N0, H, BF16, PHASE_SPLIT>());
-      if constexpr (particle_split_wide_compiled(H, BF16)) out.push_back(particle_entry<N0, H, BF16, PHASE_SPLIT, 2>());
+      if constexpr (particle_split_rows(H, BF16, 0) != 0)
+        out.push_back(particle_entry<N0, H, BF16, PHASE_SPLIT, particle_split_rows(H, BF16, 0)>());
+      if constexpr (particle_split_rows(H, BF16, 1) != 0)
+        out.push_back(particle_entry<N0, H, BF16, PHASE_SPLIT, particle_split_rows(H, BF16, 1)>());
     }
     if constexpr (particle_central_fits(N0, H, BF16)) {
       out.push_back(particle_entry<N0, H, BF16, PHASE_CENTRAL>());

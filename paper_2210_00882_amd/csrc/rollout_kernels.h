@@ -181,8 +181,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   // of 64 separate rows.  SE envs (SR rows) are staged per pass: all of the wave's when they take at most
   // STG_ALL bytes, else as many as fit STG_SOME (networks of 256 units fill the LDS with their resident
   // layer-1 tiles and the window, fp32 ones the more, so their staging areas are smaller).
-  constexpr int STG_ALL = !BF16 && H >= 256 ? 2048 : 4608;
-  constexpr int STG_SOME = H >= 256 ? (BF16 ? 2560 : 2048) : 3072;
+  constexpr bool TIGHT = SPLIT && H >= 128;  // (all weights resident: little LDS left)
+  constexpr int STG_ALL = (!BF16 && H >= 256) || TIGHT ? 2048 : 4608;
+  constexpr int STG_SOME = H >= 256 ? (BF16 ? 2560 : 2048) : (TIGHT ? 2048 : 3072);
   constexpr int SE = EPW * N * D * 4 <= STG_ALL ? EPW : (STG_SOME / (N * D * 4) >= 1 ? STG_SOME / (N * D * 4) : 1);
   constexpr int SR = SE * N;
   constexpr int PASSES = (EPW + SE - 1) / SE;

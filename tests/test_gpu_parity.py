@@ -129,15 +129,16 @@ def test_particle_agent_count_sweep(N, H, dtype):
 
 
 @pytest.mark.parametrize("N", range(1, 11))
-@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
-def test_particle_one_and_two_waves_per_row_block(N, dtype):
-    # 64-unit networks have two kernel shapes (msrl_env_cfg.wave_roles): a wave runs both networks of its rows,
+@pytest.mark.parametrize("H,dtype", [(64, synth.F32), (64, synth.BF16), (128, synth.BF16)])
+def test_particle_one_and_two_waves_per_row_block(N, H, dtype):
+    # 64-unit networks (and 128-unit bf16 ones) have two kernel shapes (msrl_env_cfg.wave_roles): a wave runs both networks of its rows,
     # or the policy and the value network of a row block run on two waves.  The library picks the second one
     # wherever it is compiled, so the sweep above covers it; here each shape is fixed in turn, checked against
     # the oracle (every env and step, two calls), and the two must agree bit for bit.
     from paper_2210_00882_amd import binding as B
-    cfg = synth.particle(f"roles{N}", 53, N, 64, 9, 4, dtype=dtype, idx=140 + N)
-    for roles, want in ((0, (4, 2)), (1, (2, 2)), (2, (4, 2))):
+    cfg = synth.particle(f"roles{N}", 53, N, H, 9, 4, dtype=dtype, idx=140 + N)
+    plain, split = ((2, 2), (4, 2)) if H == 64 else ((8, 8), (8, 4))
+    for roles, want in ((0, split), (1, plain), (2, split)):
         st = B.msrl_rollout_init(B.make_env_cfg(cfg, wave_roles=roles)[0], B.make_policy_cfg(cfg), 1)
         wg, waves, row_waves = B.msrl_rollout_shape(st)
         B.msrl_rollout_destroy(st)
@@ -169,10 +170,31 @@ def test_particle_two_waves_per_row_block_at_scale(N):
         np.testing.assert_array_equal(one[k], two[k], err_msg=k)
 
 
+def test_wave_roles_choice_by_size():
+    # what msrl_rollout_init picks when left to choose: 64-unit networks always run two waves per row block (two
+    # row blocks per workgroup while that leaves a SIMD one wave at most; fp32 then four); 128-unit bf16 networks
+    # only while the workgroups of that shape run in one round
+    from paper_2210_00882_amd import binding as B
+
+    def shape(E, H, dtype):
+        cfg = synth.particle("choice", E, 3, H, 4, 4, dtype=dtype, idx=170)
+        st = B.msrl_rollout_init(B.make_env_cfg(cfg)[0], B.make_policy_cfg(cfg), 1)
+        sh = B.msrl_rollout_shape(st)
+        B.msrl_rollout_destroy(st)
+        return sh[1:]
+
+    cus = 256
+    small, mid, large = 10 * 2 * cus, 10 * 4 * cus, 10 * 4 * cus + 1
+    assert shape(small, 64, synth.F32) == (4, 2) and shape(small + 1, 64, synth.F32) == (8, 4)
+    assert shape(small, 64, synth.BF16) == (4, 2) and shape(large, 64, synth.BF16) == (4, 2)
+    assert shape(mid, 128, synth.BF16) == (8, 4) and shape(large, 128, synth.BF16) == (8, 8)
+    assert shape(small, 128, synth.F32) == (8, 8)
+
+
 def test_wave_roles_error_paths():
     from paper_2210_00882_amd import binding as B
     wide = synth.particle("roles_wide", 8, 3, 128, 4, 4, idx=150)
-    with pytest.raises(B.MsrlError) as ei:  # compiled for 64 units only
+    with pytest.raises(B.MsrlError) as ei:  # 128 units: bf16 only (the fp32 weights do not fit the LDS)
         B.msrl_rollout_init(B.make_env_cfg(wide, wave_roles=2)[0], B.make_policy_cfg(wide), 1)
     assert ei.value.code == B.MSRL_EUNSUPPORTED
     deep = synth.particle("roles_deep", 8, 3, 64, 4, 4, idx=151).with_(hidden_layers=3)
