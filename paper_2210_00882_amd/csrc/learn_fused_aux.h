@@ -189,127 +189,4 @@ __global__ __launch_bounds__(512) void wgrad_tiled_kernel(WgradTJobs jobs) {
   }
 }
 
-// The same contractions for layers of at most 32 MT x 32 NT units (64-unit networks: MT = NT = 2).  With so
-// few units the kernel above would leave most of its waves without rows of C, so here the waves of a
-// workgroup split the slice's row tiles instead (wave w takes tiles w, w + WAVES, ...): every wave holds the
-// whole result, fetches both operands of its tiles straight from global memory DEPTH tiles ahead, and at the
-// end the waves' results are added through LDS in a fixed order (pairwise: the upper half onto the lower
-// half, until wave 0 holds the sum), then stored as the slice's copy.
-template <int MT, int NT, int WAVES, int DEPTH>
-__global__ __launch_bounds__(64 * WAVES) void wgrad_wave_kernel(WgradTJobs jobs) {
-  const WgradTArgs& g = jobs.job[blockIdx.y];
-  static_assert(WAVES >= 2 && (WAVES & (WAVES - 1)) == 0, "the pairwise sum halves the waves");
-  constexpr int VALS = MT * NT * 16 + NT;  // floats per lane: the accumulators, then the bias sums
-  __shared__ float s_red[(WAVES / 2) * VALS * 64];
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int i = lane & 31, h = lane >> 5;
-  const int64_t t_begin = (int64_t)blockIdx.x * g.tiles_per_slice;
-  const int64_t t_end = min(g.n_tiles, t_begin + g.tiles_per_slice);
-  if (t_begin >= t_end) return;  // whole workgroup
-  const int mtiles = min(MT, (g.M + 31) / 32), ntiles = min(NT, (g.N + 31) / 32);
-  const bool bias = g.bias != nullptr;
-  const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-  auto a_frag = [&](int mt, int kk, int64_t T) -> bf16x8 {
-    const int unit = 32 * mt + i;
-    if (mt < mtiles && unit < g.M && T < t_end) return ((const bf16x8*)g.A)[((size_t)T * 4 + 2 * kk + h) * g.UA + unit];
-    return zero;
-  };
-  auto b_frag = [&](int nt, int kk, int64_t T) -> bf16x8 {
-    const int unit = 32 * nt + i;
-    if (nt < ntiles && unit < g.N && T < t_end) return ((const bf16x8*)g.B)[((size_t)T * 4 + 2 * kk + h) * g.UB + unit];
-    return zero;
-  };
-  f32x16 acc[MT][NT], accb[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    accb[nt] = zero16();
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = zero16();
-  }
-  bf16x8 ones;
-#pragma unroll
-  for (int s = 0; s < 8; ++s) ones[s] = (__bf16)1.0f;
-  // queue of DEPTH tiles: slot d holds tile t_begin + wave + (d + DEPTH k) WAVES for k = 0, 1, ...
-  bf16x8 qa[DEPTH][2][MT], qb[DEPTH][2][NT];
-  auto fill = [&](int d, int64_t T) {
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) qa[d][kk][mt] = a_frag(mt, kk, T);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) qb[d][kk][nt] = b_frag(nt, kk, T);
-    }
-  };
-#pragma unroll
-  for (int d = 0; d < DEPTH; ++d) fill(d, t_begin + wave + (int64_t)d * WAVES);
-  for (int64_t T0 = t_begin + wave; T0 < t_end; T0 += DEPTH * WAVES) {
-#pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
-      const int64_t T = T0 + (int64_t)d * WAVES;
-      if (T >= t_end) break;  // uniform over the wave
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          if (nt >= ntiles) continue;  // uniform
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            if (mt >= mtiles) continue;  // uniform
-            acc[mt][nt] = mma(qa[d][kk][mt], qb[d][kk][nt], acc[mt][nt]);
-          }
-          if (bias) accb[nt] = mma(ones, qb[d][kk][nt], accb[nt]);
-        }
-      }
-      fill(d, T + (int64_t)DEPTH * WAVES);
-    }
-  }
-  // pairwise sum over the waves, the same order every time
-#pragma unroll
-  for (int stride = WAVES / 2; stride >= 1; stride /= 2) {
-    if (wave >= stride && wave < 2 * stride) {
-      float* dst = s_red + (size_t)(wave - stride) * VALS * 64 + lane;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) dst[((mt * NT + nt) * 16 + r) * 64] = acc[mt][nt][r];
-        dst[(MT * NT * 16 + nt) * 64] = accb[nt][0];
-      }
-    }
-    __syncthreads();
-    if (wave < stride) {
-      const float* src = s_red + (size_t)wave * VALS * 64 + lane;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[mt][nt][r] += src[((mt * NT + nt) * 16 + r) * 64];
-        accb[nt][0] += src[(MT * NT * 16 + nt) * 64];
-      }
-    }
-    __syncthreads();
-  }
-  if (wave != 0) return;
-  const int64_t copy = (int64_t)blockIdx.x * g.slice_stride;
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int nn = 32 * nt + i;
-    if (nt >= ntiles || nn >= g.N) continue;
-    // every row of the ones-contraction is the column sum: row 0 is register 0 of the h = 0 lanes
-    if (bias && h == 0) g.bias[copy + nn] = accb[nt][0];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      if (mt >= mtiles) continue;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = 32 * mt + 8 * (r / 4) + 4 * h + r % 4;
-        if (m < g.m_out && m < g.M) g.C[copy + (int64_t)m * g.ldc + nn] = acc[mt][nt][r];
-      }
-    }
-  }
-}
-
 }  // namespace msrl

@@ -338,10 +338,13 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
         LTRY((wgrad<BF16>(s, b.ht[l - 1], H, Rp, b.dzt[l], H, Rp, part + oW(l), H, H, H, Rk, slices, ps, &used)));
         red.add(oW(l), (size_t)H * H, used);
       }
-      if (D <= 256)
-        LTRY((wgrad<BF16>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, part + oW(0), D, H, H, Rk, slices, ps, &used)));
-      else  // more input units than the kernel's panel holds (the joint observation)
-        LTRY((gemm<BF16, float, EPI_PARTIAL>(s, xtn[n], Dp, Rp, b.dzt[0], H, Rp, part + oW(0), D, H, H, Rk, nullptr, nullptr, 0, slices, ps, &used)));
+      // (more input units than the kernel's panel holds - the joint observation - go in panels of 256: the same
+      // slices of the rows for each, so one reduce job covers the whole tensor)
+      for (int d0 = 0; d0 < D; d0 += 256) {
+        const int dm = D - d0 < 256 ? D - d0 : 256;
+        LTRY((wgrad<BF16>(s, (const E*)xtn[n] + (size_t)d0 * Rp, Dp - d0, Rp, b.dzt[0], H, Rp,
+                          part + oW(0) + (size_t)d0 * H, dm, H, H, Rk, slices, ps, &used)));
+      }
       red.add(oW(0), (size_t)D * H, used);
     } else {
       LTRY((gemm<BF16, float, EPI_PARTIAL>(s, b.ht[NL - 1], H, Rp, b.dyt, 32, Rp, part + oW3, H, O, O, Rk, nullptr, nullptr, 0, slices, ps, &used)));
