@@ -237,7 +237,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 // tanh derivative), then, if Ct is given, column-wise for the unit-major copy Ct[n][m] that the
 // weight-gradient contraction reads (rows m in [M, M_pad) of it are written as zero); the column
 // pass can also add up the columns (the bias gradient).  C itself may be null when only the
-// unit-major copy is wanted.  Needs K <= 256 and N a multiple of 8.
+// unit-major copy is wanted.  Needs K <= KMAX (256; 704 with half as many columns per workgroup, for
+// the joint observation in bf16) and N a multiple of 8.
 struct RowGemmArgs {
   GemmArgs g;
   void* Ct;        // [N, ldt] or null
@@ -249,10 +250,10 @@ struct RowGemmArgs {
   int64_t colsum_stride;
 };
 
-template <bool BF16, typename SC, int EPI, int NT>
+template <bool BF16, typename SC, int EPI, int NT, int KMAX = 256>
 __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
   typedef typename Frag<BF16>::T F;
-  constexpr int KT = Frag<BF16>::KT, KK_MAX = 256 / KT, TW = 64 + 4;
+  constexpr int KT = Frag<BF16>::KT, KK_MAX = KMAX / KT, TW = 64 + 4;
   static_assert(NT % 2 == 0, "the epilogue works on pairs of 32-column tiles");
   __shared__ __attribute__((aligned(16))) u32x4 s_b[NT * KK_MAX * 64];
   __shared__ float s_c[8][32 * TW];

@@ -117,13 +117,16 @@ hipError_t gemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, cons
 }
 
 // row-parallel contraction (weights in LDS, optional unit-major copy Ct of the result)
-template <bool BF16, typename SC, int EPI>
+template <bool BF16, typename SC, int EPI, bool WIDE = false>
 hipError_t rowgemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, const void* B, int64_t N_alloc,
                    int64_t ldb, void* C, int64_t M, int64_t N, int64_t ldc, int64_t K, const float* bias,
                    const void* Hm, int64_t ldh, void* Ct, int64_t ldt, int64_t M_pad, float* colsum = nullptr,
                    int64_t colsum_stride = 0, int* colsum_slices = nullptr) {
   // colsum: the first of `*colsum_slices` copies (one per workgroup along x), colsum_stride floats apart
-  constexpr int NT = BF16 ? 4 : 2;
+  // wide: K in (256, 704], bf16 only (the panel of 64 columns x 704 inputs is 88 KB of LDS)
+  constexpr int NT = BF16 && !WIDE ? 4 : 2;
+  constexpr int KMAX = WIDE ? 704 : 256;
+  static_assert(!WIDE || BF16, "the wide panel exists in bf16 only");
   RowGemmArgs ra;
   memset(&ra, 0, sizeof(ra));
   GemmArgs& g = ra.g;
@@ -133,9 +136,9 @@ hipError_t rowgemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, c
   ra.Ct = Ct; ra.ldt = ldt; ra.M_pad = Ct ? M_pad : M; ra.colsum = colsum; ra.colsum_stride = colsum_stride;
   ra.tiles = (ra.M_pad + 255) / 256;
   if (colsum_slices) *colsum_slices = (int)(ra.tiles < 256 ? ra.tiles : 256);
-  if (K > 256 || N % 8 != 0) return hipErrorInvalidValue;  // shapes the learner never produces
+  if (K > KMAX || N % 8 != 0) return hipErrorInvalidValue;  // shapes the learner never produces
   dim3 grid((unsigned)(ra.tiles < 256 ? ra.tiles : 256), (unsigned)((N + 32 * NT - 1) / (32 * NT)));
-  hipLaunchKernelGGL((rowgemm_kernel<BF16, SC, EPI, NT>), grid, dim3(512), 0, s, ra);
+  hipLaunchKernelGGL((rowgemm_kernel<BF16, SC, EPI, NT, KMAX>), grid, dim3(512), 0, s, ra);
   return hipGetLastError();
 }
 
@@ -271,8 +274,12 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
     // forward (the activations also leave unit-major, for the weight gradients)
     if (Dp <= 256) {
       LTRY((rowgemm<BF16, E, EPI_BIAS_TANH>(s, xcn[n], Rp, Dp, b.wt[0], H, Dp, b.h[0], R, H, H, Dp, P + (size_t)D * H, nullptr, 0, b.ht[0], Rp, Rk)));
+    } else if (BF16 && Dp <= 704) {
+      // the joint observation: the row kernel with a panel of fewer columns and more inputs
+      if constexpr (BF16)
+        LTRY((rowgemm<BF16, E, EPI_BIAS_TANH, true>(s, xcn[n], Rp, Dp, b.wt[0], H, Dp, b.h[0], R, H, H, Dp, P + (size_t)D * H, nullptr, 0, b.ht[0], Rp, Rk)));
     } else {
-      // wider than the row kernel's weight panel (the joint observation): the general kernel, then the unit-major copy
+      // wider than the row kernel's weight panels: the general kernel, then the unit-major copy
       LTRY((gemm<BF16, E, EPI_BIAS_TANH>(s, xcn[n], Rk, Dp, b.wt[0], H, Dp, b.h[0], R, H, H, Dp, P + (size_t)D * H, nullptr, 0)));
       LTRY(transpose(s, (const E*)b.h[0], R, H, H, (E*)b.ht[0], Rp, Rk, H));
     }
