@@ -357,7 +357,9 @@ int enqueue_rollout(msrl_state* st, const KernelEntry& kernel, const void* param
   a.envs_per_block = envs_per_block(kernel, st->env.num_envs, st->cus);
   a.layers = layers_of(st->pol);
   a.critic = st->central ? st->packed + st->layout.bytes : nullptr;
-  const int64_t blocks = ((int64_t)a.E + a.envs_per_block - 1) / a.envs_per_block;
+  int64_t blocks = ((int64_t)a.E + a.envs_per_block - 1) / a.envs_per_block;
+  // (the actor fragment's kernel walks over the row blocks itself: one workgroup per compute unit at most)
+  if (kernel.kind == MSRL_ENV_PARTICLE && kernel.phase == PHASE_ACT && blocks > st->cus) blocks = st->cus;
   void* args[] = {&a};
   HIP_TRY(hipLaunchKernel(kernel.fn, dim3((unsigned)blocks), dim3(64 * kernel.waves), args, 0, stream));
   return MSRL_OK;

@@ -270,8 +270,17 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     ws.wait_all();
   else
     __syncthreads();
+  int gs = 0;  // stages consumed so far: stage gs sits in buffer gs % NBUF
+  // PHASE_ACT is persistent: the launch has at most one workgroup per compute unit, and a workgroup walks over
+  // the row blocks vb = blockIdx.x, blockIdx.x + gridDim.x, ... with one copy of the resident weights and one
+  // running weight stream (the set-up above is a tenth of a one-block pass).  Every other variant runs all its
+  // steps on one block (the grid covers the blocks).  The walk is a jump back to this label: what is declared
+  // below is set up again for the next block.
+  constexpr bool PERSIST = PHASE == PHASE_ACT;
+  int64_t vb = blockIdx.x;
+next_row_block:
   // envs of this workgroup: [blk0, blk0 + envs_per_block); of this wave: EPW of them
-  const int64_t blk0 = (int64_t)blockIdx.x * a.envs_per_block;
+  const int64_t blk0 = vb * a.envs_per_block;
   const int64_t blk_end = min(blk0 + (int64_t)a.envs_per_block, (int64_t)a.E);
   const int64_t env0 = blk0 + (int64_t)rset * EPW;
   float2* tab = s_tab[wave];
@@ -352,7 +361,6 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   };
 
 
-  int gs = 0;                   // stages consumed so far: stage gs sits in buffer gs % NBUF
   // Outputs of a network as a bit mask (5 logits; the value network uses the first).  Only the fp32 output
   // layer's code depends on it: few outputs run on the VALU (Mlp::l3v).  All 16 bits keep the output layer on
   // the MFMA: bf16 kernels, and the variants with more hidden layers or a centralised critic (their fp32
@@ -1010,6 +1018,14 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
     }
   }
 
+  if constexpr (PERSIST) {
+    __syncthreads();  // every wave's outputs of this row block are in s_out
+    flush(0, 0x07);   // values, actions, logp (the next block writes s_out behind several stage barriers)
+    vb += gridDim.x;
+    if (vb * a.envs_per_block < a.E) goto next_row_block;
+    ws.wait_all();  // copies issued ahead for a block that will not come
+    return;
+  }
   if constexpr (HAS_NETS) ws.wait_all();  // copies issued ahead for stages that will not run
   if constexpr (!HAS_NETS) __syncthreads();
   if constexpr (ACT && !CENTRAL) {
