@@ -114,6 +114,27 @@ def test_split_calls_reproduce_the_fused_rollout(which):
     assert (g_s == T).all()
 
 
+@pytest.mark.parametrize("which", ["n1_h64_f32", "n10_h256_bf16"])
+def test_actor_fragment_over_more_row_blocks_than_compute_units(which):
+    # the plain actor kernel is persistent: with more row blocks than the device has compute units a workgroup
+    # walks over several of them (a ragged last one included).  T x {act, env_step} must still be the fused
+    # rollout bit for bit, for every row.
+    cfg = (synth.particle("walk1", 40001, 1, 64, 2, 3, synth.F32, 21) if which == "n1_h64_f32"
+           else synth.CONFIGS[5].with_(num_envs=7001, episode_len=3))
+    T = 2
+    _, _, params, dyn = setup_any(cfg)
+    with GpuRollout(cfg, params.astype(np.float32), 33, dyn=dyn) as gpu:
+        fused = gpu.run(T, gae=False, logits=True)
+        es_f, g_f = gpu.get_state()
+    with GpuRollout(cfg, params.astype(np.float32), 33, dyn=dyn) as gpu:
+        split = split_rollout(gpu, T)
+        es_s, g_s = gpu.get_state()
+    for k in ("obs", "actions", "logp", "rewards", "dones", "values", "logits"):
+        np.testing.assert_array_equal(fused[k], split[k], err_msg=k)
+    np.testing.assert_array_equal(es_f, es_s)
+    np.testing.assert_array_equal(g_f, g_s)
+
+
 @pytest.mark.parametrize("which", ["n3_f32", "tag_3_1", "tag_2_2"])
 def test_env_step_against_the_oracle_for_chosen_actions(which):
     import torch
