@@ -57,6 +57,19 @@ __device__ __forceinline__ void mma_tile(const u32x4& raw, const typename Operan
   }
 }
 
+// the same for the first NM of the tile's MFMAs (fp32 tiles are four MFMAs of two inputs each: a layer-1 tile
+// whose last inputs do not exist needs fewer; the products left out are zero weight times zero input)
+template <bool BF16, int NM>
+__device__ __forceinline__ void mma_tile_first(const u32x4& raw, const typename Operand<BF16>::T* b, f32x16& acc) {
+  if constexpr (BF16) {
+    mma_tile<BF16>(raw, b, acc);
+  } else {
+    const f32x4 a = __builtin_bit_cast(f32x4, raw);
+#pragma unroll
+    for (int j = 0; j < NM; ++j) acc = mma(a[j], b[j], acc);
+  }
+}
+
 // acc += bias tile * 1: only input slot (h = 0, first k) of the tile is populated
 template <bool BF16>
 __device__ __forceinline__ void mma_bias_tile(const u32x4& raw, const typename Operand<BF16>::T& one,
@@ -173,7 +186,9 @@ __device__ __forceinline__ void to_operands(const float (&t)[16], typename Opera
 // Software pipeline inside a wave: while the MFMAs of chunk c run, the VALU applies tanh to the
 // accumulators of chunk c-1, so both pipes are busy from one instruction stream.  In a layer-2
 // stage the layer-3 MFMAs of chunk c-1 follow.
-template <int H, bool BF16, int NB, int KT1>
+// L1_LAST: fp32 only, the MFMAs of the last layer-1 tile that meet an existing input (0: all four); which inputs
+// an MFMA of a tile multiplies depends on the operand layout of the kernel's observation
+template <int H, bool BF16, int NB, int KT1, int L1_LAST = 0>
 struct Mlp {
   typedef typename Operand<BF16>::T Op;
   static constexpr int PT = Operand<BF16>::PER_TILE;
@@ -292,8 +307,15 @@ struct Mlp {
           u32x4 raw = ring[idx % G];
           if (idx + G < L1_TILES) ring[idx % G] = tiles[(idx + G) * 64];
           if (uc > 0) pin(raw);
+          constexpr int LAST = BF16 || L1_LAST == 0 ? PT : L1_LAST;
+          static_assert(LAST >= 1 && LAST <= PT, "one to four MFMAs");
 #pragma unroll
-          for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
+          for (int q = 0; q < NB; ++q) {
+            if (kt == KT1 - 1)
+              mma_tile_first<BF16, LAST>(raw, &x[q][kt * PT], acc[q]);
+            else
+              mma_tile<BF16>(raw, &x[q][kt * PT], acc[q]);
+          }
         }
         if (uc > 0) tanh_slice<KT1>(prev, t, kt);
       }

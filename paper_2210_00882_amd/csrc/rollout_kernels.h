@@ -152,7 +152,9 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr bool CENTRAL = PHASE == PHASE_CENTRAL || PHASE == PHASE_ACT_CENTRAL;
   // chunk blocks per stage (fewer barriers when they fit; the centralised critic needs the LDS)
   constexpr int CPS = BF16 && H >= 64 && !CENTRAL ? 2 : 1;
-  typedef Mlp<H, BF16, NB, KT1> Net;
+  // (fp32 operand mm of layer 1 is the input pair 2 mm + h: the NZ + 1 inputs end in MFMA L1_LAST of the last tile)
+  constexpr int L1_LAST = BF16 ? 0 : (NZ + 1 - 8 * (KT1 - 1) + 1) / 2;
+  typedef Mlp<H, BF16, NB, KT1, L1_LAST> Net;
   // PHASE_SPLIT: waves [0, RW) evaluate the policy network of row blocks 0 .. RW-1, waves [RW, 2 RW) the value
   // network of the same row blocks (role 1); every stage of both networks is resident in LDS
   constexpr bool SPLIT = PHASE == PHASE_SPLIT;
@@ -1095,7 +1097,10 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   constexpr int KT1 = (D + 1 + 7) / 8;  // + the constant-1 input that carries the bias
   constexpr int NR = 4 * KT1;           // state registers per lane
   constexpr int NBUF = 2, CPS = 1;
-  typedef Mlp<H, false, 1, KT1> Net;
+  // (the state sits in accumulator layout: MFMA j of a layer-1 tile multiplies inputs 8 kt + j and 8 kt + 4 + j,
+  // so the D + 1 inputs, the constant 1 included, reach MFMA min(4, inputs in the last tile) of the last tile)
+  constexpr int L1_REST = D + 1 - 8 * (KT1 - 1);
+  typedef Mlp<H, false, 1, KT1, L1_REST < 4 ? L1_REST : 4> Net;
   typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   static_assert(D <= 31 && K <= 8, "one MFMA chunk of state (plus the constant input), one tile of action");
 
