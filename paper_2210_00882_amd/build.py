@@ -21,9 +21,19 @@ FLAGS = [
 ] + os.environ.get("MSRL_EXTRA_FLAGS", "").split()
 
 
+# Flags for single translation units (by file-name prefix).  The lin-Gauss kernel's tile loops (32 tiles of a
+# 256-unit fp32 layer with the output layer's arithmetic between them) are longer than the compiler's limit for
+# loops it unrolls on request; not unrolled, the register arrays they index end up in scratch memory.
+PER_FILE = {
+    "inst_l17_": ["-mllvm", "-pragma-unroll-threshold=200000"],
+}
+
+
 def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    subprocess.check_call([HIPCC, *FLAGS, "-c", src, "-o", obj], stderr=subprocess.STDOUT)
+    name = os.path.basename(src)
+    obj = os.path.join(OBJ, name + ".o")
+    extra = [f for prefix, fl in PER_FILE.items() if name.startswith(prefix) for f in fl]
+    subprocess.check_call([HIPCC, *FLAGS, *extra, "-c", src, "-o", obj], stderr=subprocess.STDOUT)
     return obj
 
 

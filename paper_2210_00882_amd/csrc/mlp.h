@@ -188,7 +188,9 @@ __device__ __forceinline__ void to_operands(const float (&t)[16], typename Opera
 // stage the layer-3 MFMAs of chunk c-1 follow.
 // L1_LAST: fp32 only, the MFMAs of the last layer-1 tile that meet an existing input (0: all four); which inputs
 // an MFMA of a tile multiplies depends on the operand layout of the kernel's observation
-template <int H, bool BF16, int NB, int KT1, int L1_LAST = 0>
+// H1_ACC: fp32 only, the layer-1 outputs are parked in accumulation registers (a kernel with one wave per SIMD
+// has 256 of them beside its 256 vector registers, and an MFMA takes its B operand from either file)
+template <int H, bool BF16, int NB, int KT1, int L1_LAST = 0, bool H1_ACC = false>
 struct Mlp {
   typedef typename Operand<BF16>::T Op;
   static constexpr int PT = Operand<BF16>::PER_TILE;
@@ -211,11 +213,12 @@ struct Mlp {
   // the next chunk; `out` then holds the lane's partial sum of output o in register o, and out_finish adds the
   // two lanes of a row and the bias and puts the result where the MFMA would have (the accumulator layout).
   // bf16 networks keep the MFMA (2 instructions of 32 cycles per chunk; their VALU is the busy unit), and so do
-  // 256-unit fp32 networks (their kernels have no register to spare: even the one sum of a value network
-  // pushes scalar spills into scratch memory) and output layers with more than 6 outputs.
-  // OUTS: bit o set <-> output o exists.
+  // output layers with more than 6 outputs, or more than one for 256-unit networks (their kernels have few
+  // registers to spare).  OUTS: bit o set <-> output o exists.
   template <uint32_t OUTS>
-  static constexpr bool l3v() { return !BF16 && H <= 128 && __builtin_popcount(OUTS) <= 6; }
+  static constexpr bool l3v() {
+    return !BF16 && __builtin_popcount(OUTS) <= (H <= 128 ? 6 : 1);
+  }
   // layer-3 tiles of a chunk that pass through the ring of LDS reads
   template <uint32_t OUTS>
   static constexpr int l3s() { return l3v<OUTS>() ? 0 : TPC; }
@@ -321,7 +324,15 @@ struct Mlp {
       }
       if (uc > 0) {
 #pragma unroll
-        for (int q = 0; q < NB; ++q) to_operands<BF16>(t[q], &h1[q][(uc - 1) * PC]);
+        for (int q = 0; q < NB; ++q) {
+          if constexpr (H1_ACC && !BF16) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(h1[q][(uc - 1) * PC + r]) : "v"(t[q][r]));
+          } else {
+            to_operands<BF16>(t[q], &h1[q][(uc - 1) * PC]);
+          }
+        }
       }
 #pragma unroll
       for (int q = 0; q < NB; ++q) prev[q] = acc[q];

@@ -1100,7 +1100,8 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
   // (the state sits in accumulator layout: MFMA j of a layer-1 tile multiplies inputs 8 kt + j and 8 kt + 4 + j,
   // so the D + 1 inputs, the constant 1 included, reach MFMA min(4, inputs in the last tile) of the last tile)
   constexpr int L1_REST = D + 1 - 8 * (KT1 - 1);
-  typedef Mlp<H, false, 1, KT1, L1_REST < 4 ? L1_REST : 4> Net;
+  // (one wave per SIMD: the layer-1 outputs live in accumulation registers, 151 vector registers instead of 256)
+  typedef Mlp<H, false, 1, KT1, L1_REST < 4 ? L1_REST : 4, true> Net;
   typedef WeightStream<Net, WAVES, NBUF, CPS> Stream;
   static_assert(D <= 31 && K <= 8, "one MFMA chunk of state (plus the constant input), one tile of action");
 
@@ -1223,10 +1224,11 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
             for (int j = 0; j < Net::KT2 * Net::PT; ++j) h1[0][j] = hb[0][j];
           }
         }
-        // (all 16 bits: the output layer stays on the MFMA.  The policy has 2 K outputs; the one sum of the value
-        // network on the VALU was tried: the 256-unit kernel then keeps its layer-1 outputs in scratch memory)
-        constexpr uint32_t OUTS = 0xFFFFu;
-        out[0] = Net::template out_init<OUTS>(s_b3[net], h);
+        // Output layer: the policy's 2 K outputs on the MFMA (all 16 bits), the one value on the VALU (`net` is a
+        // constant once the loop over the networks is unrolled).  Measured at the benchmark's shape: both on the
+        // MFMA 21.64 ms, the value on the VALU 21.27, both on the VALU 21.62 (12 sums per activation are too many).
+        constexpr uint32_t OUTS_P = 0xFFFFu, OUTS_V = 0x1u;
+        out[0] = net == 0 ? Net::template out_init<OUTS_P>(s_b3[net], h) : Net::template out_init<OUTS_V>(s_b3[net], h);
 #pragma unroll 1
         for (int sc = 0; sc < Stream::STAGES_PER_NET; ++sc) {
           ws.wait_oldest();
@@ -1243,14 +1245,27 @@ __global__ __launch_bounds__(64 * WAVES) void lingauss_rollout_kernel(RolloutArg
               for (int i = 0; i < Stream::PER_WAVE; ++i)
                 if (i * (CPS * Net::KT2) / Stream::PER_WAVE == c * Net::KT2 + kt) ws.issue_part(next, nbuf, i);
             };
-            if (c == 0 && sc == 0)
-              Net::template layer2_chunk<false, OUTS>(tiles, h1, acc, out, h, 16, tick);
-            else
-              Net::template layer2_chunk<true, OUTS>(tiles, h1, acc, out, h, 16, tick);
-            if (c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1) Net::template layer2_drain<OUTS>(tiles, acc, out, h, 16);
+            const bool first = c == 0 && sc == 0, last = c == CPS - 1 && sc == Stream::STAGES_PER_NET - 1;
+            if (net == 0) {
+              if (first)
+                Net::template layer2_chunk<false, OUTS_P>(tiles, h1, acc, out, h, 16, tick);
+              else
+                Net::template layer2_chunk<true, OUTS_P>(tiles, h1, acc, out, h, 16, tick);
+              if (last) Net::template layer2_drain<OUTS_P>(tiles, acc, out, h, 16);
+            } else {
+              if (first)
+                Net::template layer2_chunk<false, OUTS_V>(tiles, h1, acc, out, h, 16, tick);
+              else
+                Net::template layer2_chunk<true, OUTS_V>(tiles, h1, acc, out, h, 16, tick);
+              if (last) Net::template layer2_drain<OUTS_V>(tiles, acc, out, h, 16);
+            }
           }
           ++gs;
         }
+        if (net == 0)
+          Net::template out_finish<OUTS_P>(out, s_b3[net], h);
+        else
+          Net::template out_finish<OUTS_V>(out, s_b3[net], h);
       }
     }
     if (valid && h == 0 && PHASE != PHASE_STEP) a.values[o] = out_v[0][0];
