@@ -241,7 +241,7 @@ def main():
             B.msrl_observe(state, obs1)
             a1, lp1, v1 = out["actions"][0], out["logp"][0], out["values"][0]
             r1, d1 = out["rewards"][0], out["dones"][0]
-            reps = 10
+            reps = 30
             for name in ("act", "env_step"):
                 ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 for k in range(reps + 1):
