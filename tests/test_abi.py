@@ -56,6 +56,22 @@ def test_init_rejects_bad_configurations_before_touching_the_device(mutate, code
     assert ei.value.code == code and len(B.msrl_last_error()) > 10
 
 
+@pytest.mark.parametrize("roles", [-1, 3, 7])
+def test_init_rejects_bad_wave_roles_before_touching_the_device(roles):
+    cfg = synth.CONFIGS[1]
+    e, _ = B.make_env_cfg(cfg, wave_roles=roles)
+    with pytest.raises(B.MsrlError) as ei:
+        B.msrl_rollout_init(e, B.make_policy_cfg(cfg), 1)
+    assert ei.value.code == B.MSRL_EINVAL and "wave_roles" in B.msrl_last_error()
+    # the field belongs to the particle env
+    lg = synth.CONFIGS[4].with_(num_envs=8)
+    A, Bm = synth.make_dynamics(lg)
+    e, keep = B.make_env_cfg(lg, A, Bm, wave_roles=2)
+    with pytest.raises(B.MsrlError) as ei:
+        B.msrl_rollout_init(e, B.make_policy_cfg(lg), 1)
+    assert ei.value.code == B.MSRL_EINVAL
+
+
 def test_null_and_size_checks():
     lib = B.load()
     assert lib.msrl_rollout_init(None, None, 0, None) == B.MSRL_EINVAL
