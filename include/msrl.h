@@ -114,14 +114,14 @@ typedef enum { MSRL_CATEGORICAL = 0, MSRL_DIAG_GAUSSIAN = 1 } msrl_dist;
  *
  * MSRL_ENV_PARTICLE with 64-unit networks (or 128-unit bf16 networks) of two
  *   hidden layers and a per-agent critic has two kernel shapes with identical
- *   results: a wave evaluates the
- *   policy and then the value network of its 32 rows, or two waves share the
- *   rows, one network each (every weight resident on chip; the shape for
- *   step is then half as long a chain of instructions and has no stage
- *   barriers).  wave_roles = 0 lets msrl_rollout_init pick (two waves wherever
- *   compiled, with two or four row blocks per workgroup by num_envs), 1 or 2
- *   fixes the shape (EINVAL for any other value or another env kind,
- *   EUNSUPPORTED for 2 where it is not compiled).
+ *   results: a wave evaluates the policy and then the value network of its 32
+ *   rows, or two waves share the rows, one network each, with every weight
+ *   resident on chip (a step is then half as long a chain of instructions and
+ *   has no stage barriers).  wave_roles = 0 lets msrl_rollout_init pick (64
+ *   units: always two waves, with two or four row blocks per workgroup by
+ *   num_envs; 128 units: two waves while the workgroups of that shape run in
+ *   one round), 1 or 2 fixes the shape (EINVAL for any other value or another
+ *   env kind, EUNSUPPORTED for 2 where it is not compiled).
  *
  * An episode ends (done = 1, then reset) on every step whose counter g
  * satisfies (g+1) % episode_len == 0; g counts the env's steps since init.
