@@ -26,6 +26,7 @@ FLAGS = [
 # loops it unrolls on request; not unrolled, the register arrays they index end up in scratch memory.
 PER_FILE = {
     "inst_l17_": ["-mllvm", "-pragma-unroll-threshold=200000"],
+    "inst_family_h256_f32_": ["-mllvm", "-pragma-unroll-threshold=200000"],
 }
 
 

@@ -217,7 +217,7 @@ struct Mlp {
   // registers to spare).  OUTS: bit o set <-> output o exists.
   template <uint32_t OUTS>
   static constexpr bool l3v() {
-    return !BF16 && __builtin_popcount(OUTS) <= (H <= 128 ? 6 : 1);
+    return !BF16 && __builtin_popcount(OUTS) <= (H <= 128 || H1_ACC ? 6 : 1);
   }
   // layer-3 tiles of a chunk that pass through the ring of LDS reads
   template <uint32_t OUTS>

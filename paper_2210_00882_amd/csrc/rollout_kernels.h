@@ -154,7 +154,11 @@ __global__ __launch_bounds__(64 * WAVES) void particle_rollout_kernel(RolloutArg
   constexpr int CPS = BF16 && H >= 64 && !CENTRAL ? 2 : 1;
   // (fp32 operand mm of layer 1 is the input pair 2 mm + h: the NZ + 1 inputs end in MFMA L1_LAST of the last tile)
   constexpr int L1_LAST = BF16 ? 0 : (NZ + 1 - 8 * (KT1 - 1) + 1) / 2;
-  typedef Mlp<H, BF16, NB, KT1, L1_LAST> Net;
+  // fp32 networks of 256 units run one wave per SIMD (four per workgroup): their layer-1 outputs live in the
+  // accumulation registers that would otherwise lie idle, which leaves room for the output layer on the VALU
+  // (the full rollout and the actor fragment alike: they must agree bit for bit)
+  constexpr bool H1_ACC = !BF16 && H >= 256 && WAVES == 4 && (PHASE == PHASE_ALL || PHASE == PHASE_ACT);
+  typedef Mlp<H, BF16, NB, KT1, L1_LAST, H1_ACC> Net;
   // PHASE_SPLIT: waves [0, RW) evaluate the policy network of row blocks 0 .. RW-1, waves [RW, 2 RW) the value
   // network of the same row blocks (role 1); every stage of both networks is resident in LDS
   constexpr bool SPLIT = PHASE == PHASE_SPLIT;
