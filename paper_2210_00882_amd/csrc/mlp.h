@@ -213,8 +213,9 @@ struct Mlp {
   // the next chunk; `out` then holds the lane's partial sum of output o in register o, and out_finish adds the
   // two lanes of a row and the bias and puts the result where the MFMA would have (the accumulator layout).
   // bf16 networks keep the MFMA (2 instructions of 32 cycles per chunk; their VALU is the busy unit), and so do
-  // output layers with more than 6 outputs, or more than one for 256-unit networks (their kernels have few
-  // registers to spare).  OUTS: bit o set <-> output o exists.
+  // output layers with more than 6 outputs - more than one for 256-unit networks whose layer-1 outputs are not
+  // parked in accumulation registers (H1_ACC): those kernels have few registers to spare.
+  // OUTS: bit o set <-> output o exists.
   template <uint32_t OUTS>
   static constexpr bool l3v() {
     return !BF16 && __builtin_popcount(OUTS) <= (H <= 128 || H1_ACC ? 6 : 1);
