@@ -492,14 +492,29 @@ __global__ void convert_pad_kernel(const S* src, int64_t rows, int64_t cols, int
   store_elem(dst + idx, (r < rows && c < cols) ? load_elem(src + r * lds_ + c) : 0.0f);
 }
 
-// dst[r][c] = src[sel.at(r)][c] converted, zero for c in [cols, ldd) and for r in [rows, rows_pad)
+// Both copies of the observations in one pass over the source: dst[r][c] = src[sel.at(r)][c] converted (zero for
+// c in [cols, ldd) and for r in [rows, rows_pad)) and dstT[c][r] = the same values unit-major (rows of ldt elements; columns in [rows, rows_pad) zero), 32 x 32 tiles
+// through LDS.  Grid: (ceil(rows_pad / 32), ceil(ldd / 32)).
 template <typename D>
-__global__ void gather_pad_kernel(const float* src, RowSel sel, int64_t rows, int64_t cols, int64_t lds_, D* dst,
-                                  int64_t ldd, int64_t rows_pad) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= rows_pad * ldd) return;
-  const int64_t r = idx / ldd, c = idx % ldd;
-  store_elem(dst + idx, (r < rows && c < cols) ? src[sel.at(r) * lds_ + c] : 0.0f);
+__global__ __launch_bounds__(256) void gather_pad_transpose_kernel(const float* src, RowSel sel, int64_t rows,
+                                                                    int64_t cols, int64_t lds_, D* dst, int64_t ldd,
+                                                                    D* dstT, int64_t ldt, int64_t rows_pad) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  const int64_t r0 = (int64_t)blockIdx.x * 32, c0 = (int64_t)blockIdx.y * 32;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int64_t r = r0 + ty + 8 * s, c = c0 + tx;
+    const float v = (r < rows && c < cols) ? src[sel.at(r) * lds_ + c] : 0.0f;
+    tile[ty + 8 * s][tx] = v;
+    if (r < rows_pad && c < ldd) store_elem(dst + r * ldd + c, v);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int64_t c = c0 + ty + 8 * s, r = r0 + tx;
+    if (c < ldd && r < rows_pad) store_elem(dstT + c * ldt + r, tile[tx][ty + 8 * s]);
+  }
 }
 
 __global__ void fill_kernel(float* p, int64_t n, float v) {

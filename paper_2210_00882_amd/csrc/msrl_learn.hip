@@ -181,14 +181,6 @@ hipError_t convert_pad(hipStream_t s, const S* src, int64_t rows, int64_t cols, 
   return hipGetLastError();
 }
 
-template <typename D>
-hipError_t gather_pad(hipStream_t s, const float* src, const RowSel& sel, int64_t rows, int64_t cols, int64_t ld_src,
-                      D* dst, int64_t ldd, int64_t rows_pad) {
-  hipLaunchKernelGGL((gather_pad_kernel<D>), grid1(rows_pad * ldd), dim3(256), 0, s, src, sel, rows, cols, ld_src, dst,
-                     ldd, rows_pad);
-  return hipGetLastError();
-}
-
 // The parameter tensors of a gradient pass, each with the number of slices its contraction was split
 // into; launch() adds the slices' copies (in L->part) up into grad, in slice order.
 struct Reducer {
@@ -243,8 +235,12 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
     // (the value network of a centralised critic reads whole groups: the same rows as [R / G, G * in_dim];
     // a selection of rows is refused for it, so only a row offset at a group boundary remains)
     const RowSel rs = n == 0 ? sel : RowSel{sel.row0 / G, 0, 0, 0};
-    LTRY(gather_pad(s, obs, rs, Rn[n], Dn[n], Dn[n], (E*)xcn[n], Dpn[n], Rkn[n]));
-    LTRY(transpose(s, (const E*)xcn[n], Rn[n], Dpn[n], Dpn[n], (E*)xtn[n], Rp, Rkn[n], Dpn[n]));
+    {
+      dim3 grid((unsigned)((Rkn[n] + 31) / 32), (unsigned)((Dpn[n] + 31) / 32));
+      hipLaunchKernelGGL((gather_pad_transpose_kernel<E>), grid, dim3(256), 0, s, obs, rs, Rn[n], (int64_t)Dn[n],
+                         (int64_t)Dn[n], (E*)xcn[n], (int64_t)Dpn[n], (E*)xtn[n], Rp, Rkn[n]);
+      LTRY(hipGetLastError());
+    }
   }
   const int NL = L->layers;
   const size_t mid = (size_t)H * H + H;
