@@ -241,11 +241,12 @@ def main():
             B.msrl_observe(state, obs1)
             a1, lp1, v1 = out["actions"][0], out["logp"][0], out["values"][0]
             r1, d1 = out["rewards"][0], out["dones"][0]
-            reps = 30
+            # (short calls: enough untimed ones first that the timed ones run at the clock of a busy device)
+            reps, warm = 30, 30
             for name in ("act", "env_step"):
                 ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                for k in range(reps + 1):
-                    if k == 1:
+                for k in range(reps + warm):
+                    if k == warm:
                         ev0.record()
                     if name == "act":   # (parameters passed once; later calls reuse their re-ordered image)
                         B.msrl_act(state, dparams if k == 0 else None, obs1, a1, lp1, v1)
@@ -276,10 +277,10 @@ def main():
             flat = lambda t: t.reshape(-1, *t.shape[2:])[:rows]
             batch = (flat(out["obs"][:T]), flat(out["actions"]), flat(out["logp"]), flat(out["adv"]), flat(out["ret"]))
             pc = B.make_ppo_cfg()
-            reps = 3
+            reps, warm = 10, 5
             ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            for k in range(reps + 1):
-                if k == 1:
+            for k in range(reps + warm):
+                if k == warm:
                     ev0.record()
                 B.msrl_ppo_grad(learner, master, *batch, pc, grad)
             ev1.record()
@@ -366,10 +367,10 @@ def main():
             flat = lambda t: t.reshape(-1, *t.shape[2:])[:rows]
             batch = (flat(out["obs"][:T]), flat(out["actions"]), flat(out["logp"]), flat(out["adv"]), flat(out["ret"]))
             pc = B.make_ppo_cfg()
-            reps = 3
+            reps, warm = 10, 5
             ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            for k in range(reps + 1):
-                if k == 1:
+            for k in range(reps + warm):
+                if k == warm:
                     ev0.record()
                 B.msrl_ppo_grad(learner, master, *batch, pc, grad)
             ev1.record()
@@ -395,9 +396,9 @@ def main():
             tparams = B.upload_params(tcfg, synth.make_params(tcfg))
             tout = B.alloc_traj(tcfg, tcfg.T, logits=False, gae=True)
             ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            reps = 5
-            for k in range(reps + 1):
-                if k == 1:
+            reps, warm = 10, 5
+            for k in range(reps + warm):
+                if k == warm:
                     ev0.record()
                 B.msrl_rollout_gae(tstate, tparams, tcfg.T, tcfg.gamma, tcfg.lam, tout)
             ev1.record()
@@ -437,8 +438,8 @@ def main():
             pc = B.make_ppo_cfg(lr=3e-4)
             flat = lambda t: t.reshape(-1, *t.shape[2:])
             evs = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-            reps, t_roll, ksteps = 3, 0.0, [0, 0]
-            for k in range(reps + 1):
+            reps, warm, t_roll, ms_it, ksteps = 6, 3, 0.0, 0.0, [0, 0]
+            for k in range(reps + warm):
                 evs[0].record()
                 B.msrl_params_cast(master, acting, B.MSRL_BF16)
                 B.msrl_rollout_gae(estate, acting, ecfg.T, ecfg.gamma, ecfg.lam, eout)
@@ -451,9 +452,9 @@ def main():
                                                   rows=sets[r])
                 evs[2].record()
                 torch.cuda.synchronize()
-                if k > 0:
+                if k >= warm:
                     t_roll += evs[0].elapsed_time(evs[1])
-                    ms_it = (ms_it if k > 1 else 0.0) + evs[0].elapsed_time(evs[2])
+                    ms_it += evs[0].elapsed_time(evs[2])
             for Lr in learners:
                 B.msrl_learner_destroy(Lr)
             B.msrl_rollout_destroy(estate)
