@@ -369,9 +369,8 @@ next_row_block:
 
   // Outputs of a network as a bit mask (5 logits; the value network uses the first).  Only the fp32 output
   // layer's code depends on it: few outputs run on the VALU (Mlp::l3v).  All 16 bits keep the output layer on
-  // the MFMA: bf16 kernels, and the variants with more hidden layers or a centralised critic (their fp32
-  // kernels have no registers left for it).
-  constexpr uint32_t OUTS = BF16 || DEEP || CENTRAL ? 0xFFFFu : 0x1Fu;
+  // the MFMA (bf16 kernels).
+  constexpr uint32_t OUTS = BF16 ? 0xFFFFu : 0x1Fu;
 
   // Centralised critic (PHASE_CENTRAL).  The joint observations of the workgroup's envs are the
   // columns of one tile, and this wave computes the 32-unit chunk `wave` of each hidden layer.  Those
@@ -762,6 +761,7 @@ next_row_block:
             ++gs;
             ++sn;
           }
+          Net::template out_finish<OUTS>(out, s_b3[net], h);
         }
       } else if constexpr (SPLIT) {
         // ---------------- this wave's network; all its stages are resident: no copies, waits or barriers
@@ -849,6 +849,7 @@ next_row_block:
           if (sc == SPN - 1) Net::template layer2_drain<OUTS>(tiles, acc, out_p, h, 16);
           ++gs;
         }
+        Net::template out_finish<OUTS>(out_p, s_b3[0], h);
 
         critic_l1_publish(cacc);
         cacc = zero16();  // layer 2 starts from zero in stage 0 of the next step
