@@ -72,6 +72,14 @@ __device__ __forceinline__ float fast_tanh(float x) {
   return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
 }
 
+// The same for an argument that already carries the factor 2 log2(e): the packed fp32 images hold their hidden
+// layers' weights and biases times that factor (packed.h), so the fp32 kernels' pre-activations arrive scaled
+// and the chain is one multiply shorter.
+constexpr float TANH_PRESCALE = 2.8853900817779268f;
+__device__ __forceinline__ float fast_tanh_prescaled(float x) {
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(x) + 1.0f);
+}
+
 // Keeps the compiler from moving LDS traffic of one wave across this point.
 // A wave's own LDS operations complete in issue order, so data written by one
 // lane is visible to the other lanes of the same wave afterwards.

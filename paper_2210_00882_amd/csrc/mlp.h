@@ -111,6 +111,8 @@ __device__ __forceinline__ void pin(u32x4& v) { asm volatile("" : "+v"(v)); }
 
 // tanh of accumulator registers [r0, r1) of a 32-unit chunk into a scratch array.  When pinned,
 // the whole group is computed between two pins, so it stays between the neighbouring MFMAs.
+// PRESCALED: the accumulators hold 2 log2(e) times the pre-activation (fp32 networks, see fast_tanh_prescaled).
+template <bool PRESCALED = false>
 __device__ __forceinline__ void tanh_range(const f32x16& acc, float (&t)[16], int r0, int r1, bool pinned) {
   float v[16];
 #pragma unroll
@@ -121,7 +123,7 @@ __device__ __forceinline__ void tanh_range(const f32x16& acc, float (&t)[16], in
     }
 #pragma unroll
   for (int r = 0; r < 16; ++r)
-    if (r >= r0 && r < r1) t[r] = fast_tanh(v[r]);
+    if (r >= r0 && r < r1) t[r] = PRESCALED ? fast_tanh_prescaled(v[r]) : fast_tanh(v[r]);
 #pragma unroll
   for (int r = 0; r < 16; ++r)
     if (r >= r0 && r < r1 && pinned) pin(t[r]);
@@ -287,7 +289,7 @@ struct Mlp {
   __device__ static __forceinline__ void tanh_slice(const f32x16 (&prev)[NB], float (&t)[NB][16], int kt) {
     const int r0 = kt * 16 / NT, r1 = (kt + 1) * 16 / NT;
 #pragma unroll
-    for (int q = 0; q < NB; ++q) tanh_range(prev[q], t[q], r0, r1, true);
+    for (int q = 0; q < NB; ++q) tanh_range<!BF16>(prev[q], t[q], r0, r1, true);
   }
 
   // Layer 1.  tiles: this lane's slot of tile 0 in LDS (tile t is at tiles[64 t]); x holds the
@@ -574,7 +576,7 @@ struct Mlp {
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
       float t[16];
-      tanh_range(acc[q], t, 0, 16, false);
+      tanh_range<!BF16>(acc[q], t, 0, 16, false);
       to_operands<BF16>(t, hlast[q]);
     }
   }
@@ -589,7 +591,7 @@ struct Mlp {
 #pragma unroll
       for (int q = 0; q < NB; ++q) {
         float t[16];
-        tanh_range(acc[q], t, 0, 16, false);
+        tanh_range<!BF16>(acc[q], t, 0, 16, false);
         l3_slice<OUTS>(w3h, t, out[q], 0, 16, nout, wg);
       }
       return;
@@ -601,7 +603,7 @@ struct Mlp {
     Op h2[NB][PC];
 #pragma unroll
     for (int q = 0; q < NB; ++q) {
-      tanh_range(acc[q], t[q], 0, 16, false);
+      tanh_range<!BF16>(acc[q], t[q], 0, 16, false);
       to_operands<BF16>(t[q], h2[q]);
     }
 #pragma unroll

@@ -171,6 +171,7 @@ PackJob weight_job(const void* src, void* dst, bool bf16, int n_in, int n_out, i
   j.n_in = n_in; j.n_out = n_out; j.src_out_major = 0;
   j.nuc = nuc; j.kt = kt; j.in_map = in_map; j.out_map = out_map; j.gauss_k = gauss_k;
   j.group = kt; j.chunk_stride = kt; j.slot_base = 0;  // plain (uc major, kt minor) order
+  j.scale = 1.0f;
   return j;
 }
 
@@ -214,6 +215,9 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     const uint8_t* b3 = W3 + (size_t)p.hidden * out * esz;
     // only the inputs that can be non-zero are packed (a prefix of the rows of W1)
     PackJob j1 = weight_job(W1, dst + L.w1, bf16, in_used, p.hidden, L.nuc, L.kt1, in_map1, OUT_NATURAL, 0);
+    // fp32 hidden layers are stored times 2 log2(e): the kernels' tanh then starts at the exp2 (dev_common.h)
+    const float hidden_scale = bf16 ? 1.0f : TANH_PRESCALE;
+    j1.scale = hidden_scale;
     j1.bias = b1;  // the bias is the input after them; the kernels feed 1 there
     j1.bias_index = joint ? st->in_used : in_used;  // (joint: in the padding of the first agent's block)
     if (joint) {
@@ -227,6 +231,7 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
       const uint8_t* Wl = Wmid + (size_t)l * (hh + hb);
       PackJob jm = weight_job(Wl, dst + L.chunks + (size_t)l * L.nuc * L.chunk_bytes, bf16, p.hidden, p.hidden, L.nuc,
                               L.kt2 + 1, IN_CHAIN, OUT_NATURAL, 0);
+      jm.scale = hidden_scale;
       jm.bias = Wl + hh;
       jm.bias_index = p.hidden;
       jm.chunk_stride = L.chunk_tiles;
@@ -236,6 +241,7 @@ int pack_params(msrl_state* st, const void* params, hipStream_t stream) {
     // tiles fed by chunk uc-1, the tpc layer-3 tiles fed by chunk uc
     uint8_t* last = dst + L.chunks + (size_t)(layers - 2) * L.nuc * L.chunk_bytes;
     PackJob j2 = weight_job(W2, last, bf16, p.hidden, p.hidden, L.nuc, L.kt2 + 1, IN_CHAIN, OUT_NATURAL, 0);
+    j2.scale = hidden_scale;
     j2.bias = b2;
     j2.bias_index = p.hidden;
     j2.chunk_stride = L.chunk_tiles;

@@ -75,7 +75,7 @@ __global__ void pack_kernel(PackJobs jobs) {
       w[p] = (__float_as_uint(v[2 * p]) >> 16) | (__float_as_uint(v[2 * p + 1]) & 0xFFFF0000u);
     ((uint4*)j.dst)[dst_slot] = make_uint4(w[0], w[1], w[2], w[3]);
   } else {
-    ((float4*)j.dst)[dst_slot] = make_float4(v[0], v[1], v[2], v[3]);
+    ((float4*)j.dst)[dst_slot] = make_float4(v[0] * j.scale, v[1] * j.scale, v[2] * j.scale, v[3] * j.scale);
   }
 }
 

@@ -106,6 +106,9 @@ struct PackJob {
   // (the joint observation of a centralised critic: per agent, the non-zero prefix of its row padded to
   // whole tiles; the bias sits in the padding of the first block, at bias_index)
   int in_block, in_block_used, in_block_stride;
+  // fp32 images: factor on the weights and on the bias riding with them (1, or TANH_PRESCALE for the layers
+  // that end in tanh); bf16 images are not scaled (the product would not be a bfloat16 value)
+  float scale;
 };
 
 struct PackJobs {

@@ -450,7 +450,7 @@ next_row_block:
   auto critic_l3 = [&](const f32x16& c) {
     float tt[16];
     Op h2c[Net::PC];
-    tanh_range(c, tt, 0, 16, false);
+    tanh_range<!BF16>(c, tt, 0, 16, false);
     to_operands<BF16>(tt, h2c);
     f32x16 ov = zero16();
 #pragma unroll
@@ -461,7 +461,7 @@ next_row_block:
   auto critic_l1_publish = [&](const f32x16& c) {
     float tt[16];
     Op hc[Net::PC];
-    tanh_range(c, tt, 0, 16, false);
+    tanh_range<!BF16>(c, tt, 0, 16, false);
     to_operands<BF16>(tt, hc);
     // the chunk's 32 units are TPC tiles of the next layer's contraction
 #pragma unroll

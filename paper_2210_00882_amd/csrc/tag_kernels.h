@@ -259,11 +259,11 @@ __global__ __launch_bounds__(64 * (NC + NR) * TILES) void tag_rollout_kernel(Tag
             u32x4 raw = blk[kt * 64];
             if (c > 0) pin(raw);
             mma_tile<BF16>(raw, &h1[0][kt * PT], acc);
-            if (c > 0) tanh_range(prev, tt, kt * 16 / Net::KT2, (kt + 1) * 16 / Net::KT2, true);
+            if (c > 0) tanh_range<!BF16>(prev, tt, kt * 16 / Net::KT2, (kt + 1) * 16 / Net::KT2, true);
           }
           mma_bias_tile<BF16>(blk[Net::KT2 * 64], Operand<BF16>::one(h), acc);
         } else {
-          tanh_range(prev, tt, 0, 16, false);
+          tanh_range<!BF16>(prev, tt, 0, 16, false);
         }
         if (c > 0) {
           Op h2[Net::PC];
