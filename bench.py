@@ -54,6 +54,16 @@ def read_traffic(name: str):
     return float(m.group(1)) if m else None
 
 
+def read_mfma_issued(name: str, flops_per_mfma: float):
+    """Flops of the MFMA instructions one launch issues (padding of inputs, outputs and rows included), from the
+    committed counter summary (SQ_INSTS_MFMA per launch), if there is one."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^\|\s*SQ_INSTS_MFMA\s*\|\s*([0-9.eE+]+)\s*\|", open(path).read(), flags=re.M)
+    return float(m.group(1)) * flops_per_mfma if m else None
+
+
 def cpu_baseline(cfg, seed, seconds_target=15.0):
     """The oracle as it stands on the host cores, on the first envs of the same
     workload over the full T (envs are independent and keyed by global env id)."""
@@ -201,6 +211,12 @@ def main():
         "ms_per_launch": roll_ms,
         "hbm_GBps": rollout_bytes_per_agent_step(cfg) * agent_steps / (roll_ms * 1e-3) / 1e9,
     }
+    # the same on issued work: what the matrix pipe executes, padding included (32x32x16 bf16: 32768 flops per
+    # instruction; 32x32x2 fp32: 4096)
+    issued = read_mfma_issued(f"rollout_cfg{args.config}_units.md", 32768.0 if cfg.dtype == synth.BF16 else 4096.0)
+    if issued:
+        roofline["mfma_issued"] = {"flops_per_launch": issued, "over_algorithmic": issued / flops,
+                                   "frac": issued / (roll_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dt_name]}
     gae_achieved = GAE_BYTES_PER_AGENT_STEP * agent_steps / (gae_ms * 1e-3) / 1e9
     roofline_gae = {
         "kernel": "gae", "bound": "hbm", "achieved": gae_achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
