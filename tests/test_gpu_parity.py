@@ -87,7 +87,7 @@ def test_cfg1_free_running_matches_oracle_until_a_bin_edge():
     assert same_envs >= cfg.num_envs - 3
 
 
-@pytest.mark.parametrize("E,T,ep", [(1, 3, 2), (7, 9, 4), (45, 30, 7), (10, 1, 25), (11, 26, 25)])
+@pytest.mark.parametrize("E,T,ep", [(1, 3, 2), (7, 9, 4), (45, 30, 7), (10, 1, 25), (11, 26, 25), (5, 6, 1)])
 def test_particle_ragged_env_counts(E, T, ep):
     cfg = synth.CONFIGS[1].with_(num_envs=E, episode_len=ep)
     run_and_check(cfg, T)
