@@ -550,15 +550,43 @@ struct Mlp {
       prev[q] = acc[q];
       acc[q] = zero16();
     }
+    if constexpr (PIPE && PAIRED) {
+      // two tiles per round, the tanh chains of both side by side (as in layer2_chunk)
+      float w[NB][16];
 #pragma unroll
-    for (int kt = 0; kt < KT2; ++kt) {
-      u32x4 raw = ring[kt % G];
-      if (kt + G < KT2 + 1) ring[kt % G] = tiles[(kt + G) * 64];
-      if (PIPE) pin(raw);
+      for (int kt = 0; kt < KT2; kt += 2) {
+        const int r0 = kt * 16 / KT2, r1 = (kt + 2) * 16 / KT2;
+        u32x4 raw = ring[kt % G];
+        if (kt + G < KT2 + 1) ring[kt % G] = tiles[(kt + G) * 64];
+        pin(raw);
 #pragma unroll
-      for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &hin[q][kt * PT], acc[q]);
-      if (PIPE) tanh_slice<KT2>(prev, t, kt);
-      tick(kt);
+        for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &hin[q][kt * PT], acc[q]);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) tanh_stage1(prev[q], w[q], r0, r1);
+        u32x4 raw2 = ring[(kt + 1) % G];
+        if (kt + 1 + G < KT2 + 1) ring[(kt + 1) % G] = tiles[(kt + 1 + G) * 64];
+        pin(raw2);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw2, &hin[q][(kt + 1) * PT], acc[q]);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+          tanh_stage2(w[q], r0, r1);
+          tanh_stage3(w[q], t[q], r0, r1);
+        }
+        tick(kt);
+        tick(kt + 1);
+      }
+    } else {
+#pragma unroll
+      for (int kt = 0; kt < KT2; ++kt) {
+        u32x4 raw = ring[kt % G];
+        if (kt + G < KT2 + 1) ring[kt % G] = tiles[(kt + G) * 64];
+        if (PIPE) pin(raw);
+#pragma unroll
+        for (int q = 0; q < NB; ++q) mma_tile<BF16>(raw, &hin[q][kt * PT], acc[q]);
+        if (PIPE) tanh_slice<KT2>(prev, t, kt);
+        tick(kt);
+      }
     }
     {
       const Op one = Operand<BF16>::one(h);
