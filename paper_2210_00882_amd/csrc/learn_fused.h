@@ -219,14 +219,36 @@ __device__ __forceinline__ void fwd_chunk(const u32x4* tiles, const bf16x8 (&h1)
   const f32x16 prev = acc;
   float t[16];
   acc = zero16();
+  if constexpr (PIPE && KT2 % 2 == 0) {
+    // two tiles per round, the tanh chains of both side by side in three pinned groups (as in Mlp::layer2_chunk)
+    float w[16];
 #pragma unroll
-  for (int kt = 0; kt < KT2; ++kt) {
-    u32x4 raw = ring[kt % G];
-    if (kt + G < LAST) ring[kt % G] = tiles[(kt + G) * 64];
-    if (PIPE) pin(raw);
-    acc = mma(__builtin_bit_cast(bf16x8, raw), h1[0][kt], acc);
-    if (PIPE) tanh_range(prev, t, kt * 16 / KT2, (kt + 1) * 16 / KT2, true);
-    tick(kt);
+    for (int kt = 0; kt < KT2; kt += 2) {
+      const int r0 = kt * 16 / KT2, r1 = (kt + 2) * 16 / KT2;
+      u32x4 raw = ring[kt % G];
+      if (kt + G < LAST) ring[kt % G] = tiles[(kt + G) * 64];
+      pin(raw);
+      acc = mma(__builtin_bit_cast(bf16x8, raw), h1[0][kt], acc);
+      tanh_stage1(prev, w, r0, r1);
+      u32x4 raw2 = ring[(kt + 1) % G];
+      if (kt + 1 + G < LAST) ring[(kt + 1) % G] = tiles[(kt + 1 + G) * 64];
+      pin(raw2);
+      acc = mma(__builtin_bit_cast(bf16x8, raw2), h1[0][kt + 1], acc);
+      tanh_stage2(w, r0, r1);
+      tanh_stage3(w, t, r0, r1);
+      tick(kt);
+      tick(kt + 1);
+    }
+  } else {
+#pragma unroll
+    for (int kt = 0; kt < KT2; ++kt) {
+      u32x4 raw = ring[kt % G];
+      if (kt + G < LAST) ring[kt % G] = tiles[(kt + G) * 64];
+      if (PIPE) pin(raw);
+      acc = mma(__builtin_bit_cast(bf16x8, raw), h1[0][kt], acc);
+      if (PIPE) tanh_range(prev, t, kt * 16 / KT2, (kt + 1) * 16 / KT2, true);
+      tick(kt);
+    }
   }
   {
     bf16x8 one = {0, 0, 0, 0, 0, 0, 0, 0};  // the two parts of the bias sit at k slots 0 and 1 of h = 0
