@@ -245,7 +245,7 @@ struct RowGemmArgs {
   int64_t ldt;
   int64_t M_pad;   // rows covered (>= M, a multiple of 16); tiles beyond are not visited
   int64_t tiles;   // 256-row tiles
-  float* colsum;   // with Ct: colsum[workgroup blockIdx.x][n] = that workgroup's share of sum_m C[m][n] (the bias
+  float* colsum;   // with Ct: colsum[workgroup blockIdx.y][n] = that workgroup's share of sum_m C[m][n] (the bias
                    // gradient of the layer; the shares are colsum_stride floats apart), or null
   int64_t colsum_stride;
 };
@@ -261,7 +261,9 @@ __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int i = lane & 31, h = lane >> 5;
-  const int64_t n0 = (int64_t)blockIdx.y * (32 * NT);
+  // (the column group is the fast grid index: the workgroups that read the same rows of A run at the same
+  // time, so only the first of them fetches those rows from HBM)
+  const int64_t n0 = (int64_t)blockIdx.x * (32 * NT);
   const int KK = (int)(g.K / KT);
   for (int idx = threadIdx.x; idx < NT * KK * 64; idx += 512) {
     const int j = idx / (KK * 64), rem = idx % (KK * 64), kk = rem / 64, l = rem % 64;
@@ -275,7 +277,7 @@ __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
   float csum[NT / 2];  // column sums of this lane's column of each 64-column chunk
 #pragma unroll
   for (int c = 0; c < NT / 2; ++c) csum[c] = 0.0f;
-  for (int64_t tile = blockIdx.x; tile < ra.tiles; tile += gridDim.x) {
+  for (int64_t tile = blockIdx.y; tile < ra.tiles; tile += gridDim.y) {
     const int64_t m0 = (tile * 8 + wave) * 32;
     if (m0 >= ra.M_pad) continue;  // wave-uniform
     const SC* arow = (const SC*)g.A + (m0 + i) * g.lda;
@@ -377,7 +379,7 @@ __global__ __launch_bounds__(512) void rowgemm_kernel(RowGemmArgs ra) {
         float s = 0.0f;
 #pragma unroll
         for (int w = 0; w < 8; ++w) s += red[(w * (NT / 2) + c) * 64 + lane];
-        if (n < g.N) ra.colsum[(int64_t)blockIdx.x * ra.colsum_stride + n] = s;
+        if (n < g.N) ra.colsum[(int64_t)blockIdx.y * ra.colsum_stride + n] = s;
       }
     }
   }

@@ -137,7 +137,7 @@ hipError_t rowgemm(hipStream_t s, const void* A, int64_t M_alloc, int64_t lda, c
   ra.tiles = (ra.M_pad + 255) / 256;
   if (colsum_slices) *colsum_slices = (int)(ra.tiles < 256 ? ra.tiles : 256);
   if (K > KMAX || N % 8 != 0) return hipErrorInvalidValue;  // shapes the learner never produces
-  dim3 grid((unsigned)(ra.tiles < 256 ? ra.tiles : 256), (unsigned)((N + 32 * NT - 1) / (32 * NT)));
+  dim3 grid((unsigned)((N + 32 * NT - 1) / (32 * NT)), (unsigned)(ra.tiles < 256 ? ra.tiles : 256));
   hipLaunchKernelGGL((rowgemm_kernel<BF16, SC, EPI, NT, KMAX>), grid, dim3(512), 0, s, ra);
   return hipGetLastError();
 }
