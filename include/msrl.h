@@ -421,8 +421,9 @@ void msrl_learner_destroy(msrl_learner* learner);
  * max_rows); stats (optional, 5 floats) <- sums over the rows of: the policy
  * term, (V - ret)^2 (with a centralised critic: the sum over the R / G groups),
  * the entropy, 1 where the clipped branch of the min is active, logp_old - logp.
- * The weight gradients are accumulated with float
- * atomics, so their last bits depend on the order of the additions.
+ * grad is summed in a fixed order: the same inputs give the same bits on every
+ * call.  The five statistics (and msrl_rows_mean's result) are added up with
+ * float atomics over a few bins, so their last bits can differ between calls.
  */
 int msrl_ppo_grad(msrl_learner* learner, const float* params, int64_t R, const float* obs,
                   const void* actions, const float* logp_old, const float* adv, const float* ret,
