@@ -495,27 +495,42 @@ __global__ void convert_pad_kernel(const S* src, int64_t rows, int64_t cols, int
 }
 
 // Both copies of the observations in one pass over the source: dst[r][c] = src[sel.at(r)][c] converted (zero for
-// c in [cols, ldd) and for r in [rows, rows_pad)) and dstT[c][r] = the same values unit-major (rows of ldt elements; columns in [rows, rows_pad) zero), 32 x 32 tiles
-// through LDS.  Grid: (ceil(rows_pad / 32), ceil(ldd / 32)).
+// c in [cols, ldd) and for r in [rows, rows_pad)) and dstT[c][r] = the same values unit-major (rows of ldt
+// elements; columns in [rows, rows_pad) zero), 64 x 64 tiles through LDS, a lane stores two neighbouring
+// elements at once.  ldd, ldt and rows_pad are even.  Grid: (ceil(rows_pad / 64), ceil(ldd / 64)).
+__device__ __forceinline__ void store_pair(float* p, float a, float b) { *(float2*)p = make_float2(a, b); }
+__device__ __forceinline__ void store_pair(__bf16* p, float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v;
+  v[0] = (__bf16)a;
+  v[1] = (__bf16)b;
+  *(bf16x2*)p = v;
+}
 template <typename D>
 __global__ __launch_bounds__(256) void gather_pad_transpose_kernel(const float* src, RowSel sel, int64_t rows,
                                                                     int64_t cols, int64_t lds_, D* dst, int64_t ldd,
                                                                     D* dstT, int64_t ldt, int64_t rows_pad) {
-  __shared__ float tile[32][33];
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-  const int64_t r0 = (int64_t)blockIdx.x * 32, c0 = (int64_t)blockIdx.y * 32;
+  __shared__ float tile[64][65];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 pairs x 8
+  const int64_t r0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    const int64_t r = r0 + ty + 8 * s, c = c0 + tx;
-    const float v = (r < rows && c < cols) ? src[sel.at(r) * lds_ + c] : 0.0f;
-    tile[ty + 8 * s][tx] = v;
-    if (r < rows_pad && c < ldd) store_elem(dst + r * ldd + c, v);
+  for (int s = 0; s < 8; ++s) {
+    const int64_t r = r0 + ty + 8 * s, c = c0 + 2 * tx;
+    float v0 = 0.0f, v1 = 0.0f;
+    if (r < rows) {
+      const float* row = src + sel.at(r) * lds_;
+      if (c < cols) v0 = row[c];
+      if (c + 1 < cols) v1 = row[c + 1];
+    }
+    tile[ty + 8 * s][2 * tx] = v0;
+    tile[ty + 8 * s][2 * tx + 1] = v1;
+    if (r < rows_pad && c < ldd) store_pair(dst + r * ldd + c, v0, v1);
   }
   __syncthreads();
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    const int64_t c = c0 + ty + 8 * s, r = r0 + tx;
-    if (c < ldd && r < rows_pad) store_elem(dstT + c * ldt + r, tile[tx][ty + 8 * s]);
+  for (int s = 0; s < 8; ++s) {
+    const int64_t c = c0 + ty + 8 * s, r = r0 + 2 * tx;
+    if (c < ldd && r < rows_pad) store_pair(dstT + c * ldt + r, tile[2 * tx][ty + 8 * s], tile[2 * tx + 1][ty + 8 * s]);
   }
 }
 

@@ -236,7 +236,7 @@ int grad_pass(msrl_learner* L, const float* params, int64_t R, const RowSel& sel
     // a selection of rows is refused for it, so only a row offset at a group boundary remains)
     const RowSel rs = n == 0 ? sel : RowSel{sel.row0 / G, 0, 0, 0};
     {
-      dim3 grid((unsigned)((Rkn[n] + 31) / 32), (unsigned)((Dpn[n] + 31) / 32));
+      dim3 grid((unsigned)((Rkn[n] + 63) / 64), (unsigned)((Dpn[n] + 63) / 64));  // (padded sizes: all even)
       hipLaunchKernelGGL((gather_pad_transpose_kernel<E>), grid, dim3(256), 0, s, obs, rs, Rn[n], (int64_t)Dn[n],
                          (int64_t)Dn[n], (E*)xcn[n], (int64_t)Dpn[n], (E*)xtn[n], Rp, Rkn[n]);
       LTRY(hipGetLastError());
